@@ -1,0 +1,250 @@
+"""ctypes front-end of the C oracle (oracle/gnnd_oracle.c) plus the evaluation
+formulas of the paper (Recall@k, Sec. 6.1; phi(G), Sec. 4.3) in numpy.
+
+TEST INFRASTRUCTURE: see the header of gnnd_oracle.c.  Argument marshalling
+only; the algorithm is in the C file.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+L2SQ_F32, ANGULAR_F32, L2SQ_U8 = 0, 1, 2
+TAG_INIT, TAG_REV_NEW, TAG_REV_OLD, TAG_MERGE = 1, 2, 3, 4
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "gnnd_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle_gnnd.so")
+_lib = None
+
+
+def build_oracle(force=False):
+    """Compile the oracle with gcc (plain C, -O2, contraction off so that only
+    the explicit fmaf calls fuse)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-std=gnu11", "-O2", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared",
+               "-Wall", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    build_oracle()
+    lib = C.CDLL(_LIB)
+    i32p, f64p, u8p = (np.ctypeslib.ndpointer(dtype=t, flags="C_CONTIGUOUS")
+                       for t in (np.int32, np.float64, np.uint8))
+    vp = C.c_void_p
+    lib.og_mix64.restype = C.c_uint64
+    lib.og_mix64.argtypes = [C.c_uint64]
+    lib.og_hash.restype = C.c_uint64
+    lib.og_hash.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32]
+    lib.og_bounded.restype = C.c_uint32
+    lib.og_bounded.argtypes = [C.c_uint64, C.c_uint32]
+    lib.og_distance.restype = C.c_double
+    lib.og_distance.argtypes = [C.c_int, C.c_int, vp, C.c_int64, C.c_int64]
+    lib.og_bruteforce.restype = None
+    lib.og_bruteforce.argtypes = [vp, C.c_int64, C.c_int, C.c_int, i32p, C.c_int64, C.c_int,
+                                  i32p, f64p]
+    lib.og_init_random.restype = None
+    lib.og_init_random.argtypes = [vp, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_uint64, i32p,
+                                   f64p, u8p]
+    lib.og_sample.restype = None
+    lib.og_sample.argtypes = [C.c_int64, C.c_int, C.c_int, C.c_uint64, C.c_uint32, i32p, u8p,
+                              i32p, i32p, i32p, i32p]
+    lib.og_pair_of.restype = None
+    lib.og_pair_of.argtypes = [C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+    lib.og_join.restype = C.c_uint64
+    lib.og_join.argtypes = [vp, C.c_int64, C.c_int, C.c_int, C.c_int, i32p, i32p, i32p, i32p,
+                            C.c_int64, i32p, i32p, f64p, i32p]
+    lib.og_insert_one.restype = C.c_int
+    lib.og_insert_one.argtypes = [C.c_int, i32p, f64p, u8p, C.c_int32, C.c_double]
+    lib.og_update.restype = C.c_uint64
+    lib.og_update.argtypes = [C.c_int64, C.c_int, C.c_int, i32p, f64p, u8p, i32p, i32p, f64p,
+                              i32p]
+    lib.og_merge_init.restype = None
+    lib.og_merge_init.argtypes = [vp, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int,
+                                  C.c_uint64, i32p, f64p, i32p, f64p, i32p, f64p, u8p, i32p,
+                                  f64p]
+    lib.og_merge_final.restype = None
+    lib.og_merge_final.argtypes = [C.c_int64, C.c_int, i32p, f64p, i32p, f64p]
+    _lib = lib
+    return lib
+
+
+def _vec(vectors, metric):
+    want = np.uint8 if metric == L2SQ_U8 else np.float32
+    v = np.ascontiguousarray(vectors)
+    if v.dtype != want:
+        raise TypeError(f"metric {metric} needs {want} vectors, got {v.dtype}")
+    return v
+
+
+def set_threads(t):
+    """Number of OpenMP threads of the join / brute-force loops (results do not
+    depend on it: every node writes its own output rows)."""
+    C.CDLL("libgomp.so.1").omp_set_num_threads(int(t))
+
+
+def mix64(z):
+    return int(_load().og_mix64(C.c_uint64(z)))
+
+
+def hash5(seed, tag, a, b, c):
+    return int(_load().og_hash(seed, tag, a, b, c))
+
+
+def bounded(h, n):
+    return int(_load().og_bounded(h, n))
+
+
+def distance(vectors, metric, i, j):
+    v = _vec(vectors, metric)
+    return float(_load().og_distance(metric, v.shape[1], v.ctypes.data, i, j))
+
+
+def pair_of(t):
+    u, v = C.c_int32(), C.c_int32()
+    _load().og_pair_of(t, C.byref(u), C.byref(v))
+    return u.value, v.value
+
+
+def bruteforce(vectors, metric, queries, K):
+    v = _vec(vectors, metric)
+    q = np.ascontiguousarray(queries, dtype=np.int32)
+    ids = np.empty((len(q), K), np.int32)
+    dist = np.empty((len(q), K), np.float64)
+    _load().og_bruteforce(v.ctypes.data, v.shape[0], v.shape[1], metric, q, len(q), K, ids, dist)
+    return ids, dist
+
+
+class Graph:
+    """k-NN graph state: ids, dist (float64 holding the metric's own float32 or
+    int32 values exactly) and the NEW flags, n rows of k."""
+
+    def __init__(self, ids, dist, isnew):
+        self.ids, self.dist, self.isnew = ids, dist, isnew
+
+    def copy(self):
+        return Graph(self.ids.copy(), self.dist.copy(), self.isnew.copy())
+
+
+def init_random(vectors, k, metric, seed):
+    v = _vec(vectors, metric)
+    n, d = v.shape
+    g = Graph(np.empty((n, k), np.int32), np.empty((n, k), np.float64), np.empty((n, k), np.uint8))
+    _load().og_init_random(v.ctypes.data, n, d, k, metric, seed, g.ids, g.dist, g.isnew)
+    return g
+
+
+def sample(g, p, seed, it):
+    """Returns (snew, cnew, sold, cold); clears the flags of the sampled NEW
+    entries of g in place."""
+    n, k = g.ids.shape
+    snew = np.empty((n, 2 * p), np.int32)
+    sold = np.empty((n, 2 * p), np.int32)
+    cnew = np.empty(n, np.int32)
+    cold = np.empty(n, np.int32)
+    _load().og_sample(n, k, p, seed, it, g.ids, g.isnew, snew, cnew, sold, cold)
+    return snew, cnew, sold, cold
+
+
+def join(vectors, metric, p, snew, cnew, sold, cold, split=-1):
+    """Returns (pu, pv, pd, pcnt, dist_evals): proposals 'insert pv with distance
+    pd into the list of pu', up to 6p per joined node."""
+    v = _vec(vectors, metric)
+    n, d = v.shape
+    pu = np.full((n, 6 * p), -1, np.int32)
+    pv = np.full((n, 6 * p), -1, np.int32)
+    pd = np.full((n, 6 * p), np.inf, np.float64)
+    pcnt = np.zeros(n, np.int32)
+    ev = _load().og_join(v.ctypes.data, n, d, p, metric, snew, cnew, sold, cold, split, pu, pv,
+                         pd, pcnt)
+    return pu, pv, pd, pcnt, int(ev)
+
+
+def insert_one(ids_row, dist_row, isnew_row, v, d):
+    return int(_load().og_insert_one(len(ids_row), ids_row, dist_row, isnew_row, v, d))
+
+
+def update(g, p, pu, pv, pd, pcnt):
+    n, k = g.ids.shape
+    return int(_load().og_update(n, k, p, g.ids, g.dist, g.isnew, pu, pv, pd, pcnt))
+
+
+def iterate(vectors, metric, g, p, seed, it, split=-1):
+    """One GNND iteration (Alg. 1 loop body) in place; `it` counts from 1.
+    Returns a dict of statistics and the intermediate sample lists/proposals."""
+    snew, cnew, sold, cold = sample(g, p, seed, it)
+    pu, pv, pd, pcnt, ev = join(vectors, metric, p, snew, cnew, sold, cold, split)
+    ins = update(g, p, pu, pv, pd, pcnt)
+    return dict(iter=it, inserts=ins, dist_evals=ev, sum_new=int(cnew.sum()),
+                sum_old=int(cold.sum()), proposals=int(pcnt.sum()),
+                snew=snew, cnew=cnew, sold=sold, cold=cold)
+
+
+def build(vectors, k, p, metric, seed, iters):
+    """Alg. 1 as a whole: random initial graph, then `iters` iterations."""
+    g = init_random(vectors, k, metric, seed)
+    stats = []
+    for it in range(1, iters + 1):
+        st = iterate(vectors, metric, g, p, seed, it)
+        stats.append({key: st[key] for key in ("iter", "inserts", "dist_evals", "sum_new",
+                                               "sum_old", "proposals")})
+    return g, stats
+
+
+def merge_init(vectors, n1, k, metric, seed, g1, g2):
+    v = _vec(vectors, metric)
+    n, d = v.shape
+    n2 = n - n1
+    fill = k // 2
+    g = Graph(np.empty((n, k), np.int32), np.empty((n, k), np.float64), np.empty((n, k), np.uint8))
+    aside_ids = np.empty((n, fill), np.int32)
+    aside_dist = np.empty((n, fill), np.float64)
+    _load().og_merge_init(v.ctypes.data, n1, n2, d, k, metric, seed, g1.ids, g1.dist, g2.ids,
+                          g2.dist, g.ids, g.dist, g.isnew, aside_ids, aside_dist)
+    return g, aside_ids, aside_dist
+
+
+def merge_final(g, aside_ids, aside_dist):
+    n, k = g.ids.shape
+    _load().og_merge_final(n, k, g.ids, g.dist, aside_ids, aside_dist)
+
+
+def merge(vectors, n1, k, p, metric, seed, g1, g2, iters):
+    """Alg. 3 as a whole.  vectors = S1 rows then S2 rows; g2 holds ids local to
+    S2.  Returns the merged graph (global ids) and per-iteration statistics."""
+    g, aside_ids, aside_dist = merge_init(vectors, n1, k, metric, seed, g1, g2)
+    stats = []
+    for it in range(1, iters + 1):
+        st = iterate(vectors, metric, g, p, seed, it, split=n1)
+        stats.append({key: st[key] for key in ("iter", "inserts", "dist_evals", "sum_new",
+                                               "sum_old", "proposals")})
+    merge_final(g, aside_ids, aside_dist)
+    return g, stats
+
+
+# --- evaluation formulas ----------------------------------------------------
+def recall_at(graph_ids, graph_dist, truth_ids, truth_dist, K=10):
+    """Recall@K (Sec. 6.1 equation) over the evaluated rows.  Returns
+    (tie_tolerant, strict): the first counts a listed neighbour among the first
+    K as a true positive when its distance does not exceed the exact K-th
+    distance of that node (equal distances are interchangeable neighbours); the
+    second counts id matches with the exact (distance, id)-ordered list."""
+    gi = np.asarray(graph_ids)[:, :K]
+    gd = np.asarray(graph_dist)[:, :K]
+    kth = np.asarray(truth_dist)[:, K - 1:K]
+    tol = float(((gd <= kth) & (gi >= 0)).sum()) / gi.size
+    strict = sum(len(np.intersect1d(gi[r], truth_ids[r, :K])) for r in range(len(gi))) / gi.size
+    return tol, float(strict)
+
+
+def phi(graph_dist):
+    """phi(G): sum of all listed distances (Sec. 4.3 equation)."""
+    return float(np.asarray(graph_dist, dtype=np.float64).sum())

@@ -1,0 +1,547 @@
+"""Pins of the CPU oracle against things other than itself: published mixer
+outputs, exactly rounded arithmetic done with rationals, numpy float64 brute
+force, closed special cases, set identities and monotonicity invariants.
+CPU only."""
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle as og
+import workloads as W
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ---------------------------------------------------------------- RNG -------
+def test_mixer_matches_published_splitmix64_outputs():
+    want = [int(l, 16) for l in open(os.path.join(GOLDEN, "splitmix64_seed0.txt"))
+            if l.strip() and not l.startswith("#")]
+    state = 0
+    for w in want:
+        state = (state + 0x9E3779B97F4A7C15) % (1 << 64)
+        assert og.mix64(state) == w
+
+
+def test_hash_counters_all_matter_and_bounded_is_uniform():
+    base = og.hash5(42, 1, 5, 6, 7)
+    assert base == og.hash5(42, 1, 5, 6, 7)
+    others = {og.hash5(43, 1, 5, 6, 7), og.hash5(42, 2, 5, 6, 7), og.hash5(42, 1, 6, 5, 7),
+              og.hash5(42, 1, 5, 7, 6), og.hash5(42, 1, 5, 6, 8), og.hash5(42, 1, 6, 6, 7)}
+    assert base not in others and len(others) == 6
+    n = 10
+    counts = np.zeros(n)
+    draws = 20000
+    for i in range(draws):
+        r = og.bounded(og.hash5(7, 1, i, 0, 0), n)
+        assert 0 <= r < n
+        counts[r] += 1
+    chi2 = ((counts - draws / n) ** 2 / (draws / n)).sum()
+    assert chi2 < 40.0  # 9 degrees of freedom; far tail
+    assert og.bounded((1 << 64) - 1, 1000) == 999 and og.bounded(0, 1000) == 0
+    # avalanche: flipping one counter bit flips about half of the output bits
+    flips = [bin(og.hash5(1, 2, i, 9, 3) ^ og.hash5(1, 2, i ^ 1, 9, 3)).count("1")
+             for i in range(0, 400, 2)]
+    assert 28 < np.mean(flips) < 36
+
+
+# ---------------------------------------------------------- distances -------
+def _round_f32(x: Fraction) -> Fraction:
+    """Exactly round a rational to the nearest float32 (ties to even), normal range."""
+    if x == 0:
+        return Fraction(0)
+    sign = -1 if x < 0 else 1
+    x = abs(x)
+    e = 0
+    while x >= 2:
+        x /= 2
+        e += 1
+    while x < 1:
+        x *= 2
+        e -= 1
+    scaled = x * (1 << 23)
+    fl = scaled.numerator // scaled.denominator
+    rem = scaled - fl
+    if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and fl % 2 == 1):
+        fl += 1
+    return sign * Fraction(fl, 1 << 23) * (Fraction(2) ** e)
+
+
+def _fr(v):
+    return Fraction(float(v))
+
+
+def test_l2_is_float32_fused_in_dimension_order():
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal((6, 11)).astype(np.float32)
+    differs_from_unfused = 0
+    for i in range(6):
+        for j in range(6):
+            acc = Fraction(0)
+            unf = np.float32(0)
+            for q in range(x.shape[1]):
+                diff = _round_f32(_fr(x[i, q]) - _fr(x[j, q]))
+                acc = _round_f32(diff * diff + acc)
+                dq = np.float32(x[i, q] - x[j, q])
+                unf = np.float32(np.float32(dq * dq) + unf)
+            got = og.distance(x, og.L2SQ_F32, i, j)
+            assert Fraction(got) == acc
+            differs_from_unfused += float(unf) != got
+            assert got == og.distance(x, og.L2SQ_F32, j, i)
+    assert differs_from_unfused > 0  # the test can tell fused from unfused
+
+
+def test_angular_is_one_minus_float32_fused_dot():
+    rng = np.random.default_rng(4)
+    x = rng.standard_normal((5, 9)).astype(np.float32)
+    x /= np.linalg.norm(x, axis=1, keepdims=True)
+    for i in range(5):
+        for j in range(5):
+            acc = Fraction(0)
+            for q in range(x.shape[1]):
+                acc = _round_f32(_fr(x[i, q]) * _fr(x[j, q]) + acc)
+            want = _round_f32(Fraction(1) - acc)
+            assert Fraction(og.distance(x, og.ANGULAR_F32, i, j)) == want
+
+
+def test_u8_distance_is_exact_integer():
+    rng = np.random.default_rng(5)
+    x = rng.integers(0, 256, size=(8, 37)).astype(np.uint8)
+    for i in range(8):
+        for j in range(8):
+            want = int(((x[i].astype(np.int64) - x[j].astype(np.int64)) ** 2).sum())
+            assert og.distance(x, og.L2SQ_U8, i, j) == want
+
+
+# -------------------------------------------------------- brute force -------
+def _numpy_knn(x, metric, K):
+    xd = x.astype(np.float64)
+    if metric == og.ANGULAR_F32:
+        D = 1.0 - xd @ xd.T
+    else:
+        D = ((xd[:, None, :] - xd[None, :, :]) ** 2).sum(-1)
+    n = len(x)
+    ids = np.empty((n, K), np.int64)
+    for i in range(n):
+        order = sorted((D[i, j], j) for j in range(n) if j != i)
+        ids[i] = [j for _, j in order[:K]]
+    return ids, D
+
+
+@pytest.mark.parametrize("metric", [og.L2SQ_F32, og.L2SQ_U8])
+def test_bruteforce_equals_numpy_full_sort_on_exact_data(metric):
+    x = W.small_integer_f32(300, 6, seed=11)  # exact distances, many ties
+    if metric == og.L2SQ_U8:
+        x = x.astype(np.uint8)
+    ids, dist = og.bruteforce(x, metric, np.arange(300), 12)
+    want, D = _numpy_knn(x, metric, 12)
+    assert (ids == want).all()
+    assert (dist == np.take_along_axis(D, want, 1)).all()
+
+
+def test_bruteforce_angular_close_to_float64():
+    x = W.deep_like_f32(200, 24, seed=12, n_comp=8)
+    ids, dist = og.bruteforce(x, og.ANGULAR_F32, np.arange(200), 10)
+    want, D = _numpy_knn(x, og.ANGULAR_F32, 10)
+    ref = np.take_along_axis(D, ids.astype(np.int64), 1)
+    assert np.abs(dist - ref).max() < 1e-6
+    assert (ids == want).mean() > 0.99  # only float32 near-ties may differ
+
+
+def test_bruteforce_points_on_a_line():
+    # 1-d points at distinct integer positions: the K nearest are the K closest
+    # positions in sorted order.
+    rng = np.random.default_rng(13)
+    pos = rng.permutation(500)[:64].astype(np.float32)
+    x = pos[:, None].copy()
+    ids, dist = og.bruteforce(x, og.L2SQ_F32, np.arange(64), 4)
+    for i in range(64):
+        want = sorted(((pos[j] - pos[i]) ** 2, j) for j in range(64) if j != i)[:4]
+        assert [j for _, j in want] == list(ids[i])
+
+
+# ------------------------------------------------------------ init ----------
+def _check_lists(g, x, metric, expect_all_new=None):
+    n, k = g.ids.shape
+    for s in range(n):
+        row = g.ids[s]
+        assert len(set(row.tolist())) == k and s not in row and row.min() >= 0 and row.max() < n
+        keys = list(zip(g.dist[s].tolist(), row.tolist()))
+        assert keys == sorted(keys)
+    if expect_all_new is not None:
+        assert (g.isnew == expect_all_new).all()
+
+
+def test_init_invariants_and_stored_distances():
+    x = W.uniform_f32(200, 8, seed=21)
+    g = og.init_random(x, 12, og.L2SQ_F32, 5)
+    _check_lists(g, x, og.L2SQ_F32, expect_all_new=1)
+    for s in range(0, 200, 17):
+        for j in range(12):
+            assert g.dist[s, j] == og.distance(x, og.L2SQ_F32, s, int(g.ids[s, j]))
+    g2 = og.init_random(x, 12, og.L2SQ_F32, 6)
+    assert (g2.ids != g.ids).mean() > 0.5  # the seed matters
+    # ids look uniformly drawn: mean in-degree equals k, no node dominates
+    indeg = np.bincount(g.ids.ravel(), minlength=200)
+    assert indeg.sum() == 200 * 12 and indeg.max() < 40
+
+
+@pytest.mark.parametrize("metric", [og.L2SQ_F32, og.ANGULAR_F32, og.L2SQ_U8])
+def test_init_with_k_equal_n_minus_1_is_the_exact_graph(metric):
+    n = 24
+    if metric == og.L2SQ_U8:
+        x = W.sift_like_u8(n, 10, seed=22, n_comp=3)
+    elif metric == og.ANGULAR_F32:
+        x = W.deep_like_f32(n, 10, seed=22, n_comp=3)
+    else:
+        x = W.uniform_f32(n, 10, seed=22)
+    g = og.init_random(x, n - 1, metric, 9)
+    ids, dist = og.bruteforce(x, metric, np.arange(n), n - 1)
+    assert (g.ids == ids).all() and (g.dist == dist).all()
+
+
+# ------------------------------------------------------- Eq. 1-2 map --------
+def test_pair_map_enumerates_the_strict_lower_triangle_once():
+    seen = {}
+    for t in range(64 * 63 // 2):
+        u, v = og.pair_of(t)
+        assert 0 <= v < u <= 63 and u * (u - 1) // 2 + v == t
+        seen[(u, v)] = t
+    assert len(seen) == 2016
+    assert og.pair_of(0) == (1, 0) and og.pair_of(1) == (2, 0) and og.pair_of(2) == (2, 1)
+
+
+# ---------------------------------------------------------- sampling --------
+def _forward(ids_row, flags_row, p):
+    new = [int(v) for v, f in zip(ids_row, flags_row) if f][:p]
+    old = [int(v) for v, f in zip(ids_row, flags_row) if not f][:p]
+    return new, old
+
+
+def _check_sampling(g_before, g_after, p, seed, it, snew, cnew, sold, cold):
+    n, k = g_before.ids.shape
+    fwd_new, fwd_old = [], []
+    for s in range(n):
+        a, b = _forward(g_before.ids[s], g_before.isnew[s], p)
+        fwd_new.append(a)
+        fwd_old.append(b)
+        # flags: exactly the sampled NEW entries were cleared
+        for j in range(k):
+            was = g_before.isnew[s, j]
+            now = g_after.isnew[s, j]
+            sampled = was and int(g_before.ids[s, j]) in a
+            assert now == (1 if (was and not sampled) else 0)
+    for kind, fwd, lists, cnts, tag in (("new", fwd_new, snew, cnew, og.TAG_REV_NEW),
+                                        ("old", fwd_old, sold, cold, og.TAG_REV_OLD)):
+        cands = [[] for _ in range(n)]
+        for s in range(n):
+            for v in fwd[s]:
+                cands[v].append(s)
+        for v in range(n):
+            got = lists[v, :cnts[v]].tolist()
+            assert got == sorted(set(got)) and len(got) <= 2 * p and v not in got
+            assert (lists[v, cnts[v]:] == -1).all()
+            room = 2 * p - len(fwd[v])
+            ranked = sorted(cands[v], key=lambda s: (og.hash5(seed, tag, v, s, it) >> 32, s))
+            want = sorted(set(fwd[v]) | set(ranked[:room]))
+            assert got == want, (kind, v)
+            if len(cands[v]) <= room:  # everything fits: the full reverse list is present
+                assert set(cands[v]) <= set(got)
+
+
+def test_sampling_definition_first_and_later_iterations():
+    x = W.uniform_f32(300, 6, seed=31)
+    k, p, seed = 10, 4, 77
+    g = og.init_random(x, k, og.L2SQ_F32, seed)
+    for it in range(1, 4):
+        before = g.copy()
+        snew, cnew, sold, cold = og.sample(g, p, seed, it)
+        if it == 1:
+            assert cold.sum() == 0  # first iteration: every entry is NEW
+        _check_sampling(before, g, p, seed, it, snew, cnew, sold, cold)
+        pu, pv, pd, pcnt, _ = og.join(x, og.L2SQ_F32, p, snew, cnew, sold, cold)
+        og.update(g, p, pu, pv, pd, pcnt)
+    assert (cnew == 2 * p).any()  # the cap was active somewhere
+
+
+def test_sampling_without_cap_gives_full_reverse_lists():
+    # 2p - k >= n - 1: nothing can overflow, so each list is forward + all reverse.
+    x = W.uniform_f32(20, 4, seed=32)
+    k, p = 4, 12
+    g = og.init_random(x, k, og.L2SQ_F32, 1)
+    before = g.copy()
+    snew, cnew, sold, cold = og.sample(g, p, 1, 1)
+    for v in range(20):
+        want = set(before.ids[v].tolist()) | {s for s in range(20) if v in before.ids[s]}
+        assert set(snew[v, :cnew[v]].tolist()) == want
+    assert (g.isnew == 0).all()
+
+
+# -------------------------------------------------------------- join --------
+def _python_join(x64, dist_fn, N, O, split):
+    """Proposals of one node from the definition, distances via dist_fn."""
+    props = []
+    for u in N:
+        if split < 0:
+            c = sorted((dist_fn(u, v), v) for v in N if v != u)
+            if c:
+                props.append((u, c[0][1], c[0][0]))
+        c = sorted((dist_fn(u, v), v) for v in O
+                   if v != u and (split < 0 or (u < split) != (v < split)))
+        if c:
+            props.append((u, c[0][1], c[0][0]))
+    for u in O:
+        c = sorted((dist_fn(u, v), v) for v in N
+                   if v != u and (split < 0 or (u < split) != (v < split)))
+        if c:
+            props.append((u, c[0][1], c[0][0]))
+    return props
+
+
+@pytest.mark.parametrize("split", [-1, 60])
+def test_join_against_python_brute_force(split):
+    x = W.small_integer_f32(120, 5, seed=41, hi=8)  # exact arithmetic, many ties
+    x64 = x.astype(np.float64)
+    k, p, seed = 8, 4, 3
+    g = og.init_random(x, k, og.L2SQ_F32, seed)
+    dist_fn = lambda a, b: float(((x64[a] - x64[b]) ** 2).sum())
+    for it in range(1, 4):
+        snew, cnew, sold, cold = og.sample(g, p, seed, it)
+        pu, pv, pd, pcnt, evals = og.join(x, og.L2SQ_F32, p, snew, cnew, sold, cold, split)
+        want_evals = 0
+        for s in range(120):
+            N = snew[s, :cnew[s]].tolist()
+            O = sold[s, :cold[s]].tolist()
+            want = _python_join(x64, dist_fn, N, O, split)
+            got = list(zip(pu[s, :pcnt[s]].tolist(), pv[s, :pcnt[s]].tolist(),
+                           pd[s, :pcnt[s]].tolist()))
+            assert sorted(got) == sorted(want), (it, s)
+            assert len(got) <= 6 * p
+            if split < 0:
+                want_evals += len(N) * (len(N) - 1) // 2
+                want_evals += sum(1 for a in N for b in O if a != b)
+            else:
+                want_evals += sum(1 for a in N for b in O
+                                  if a != b and (a < split) != (b < split))
+        assert evals == want_evals
+        og.update(g, p, pu, pv, pd, pcnt)
+
+
+def test_join_skips_an_object_sampled_as_both_new_and_old():
+    x = W.small_integer_f32(6, 3, seed=42)
+    p = 2
+    snew = np.full((6, 4), -1, np.int32)
+    sold = np.full((6, 4), -1, np.int32)
+    cnew = np.zeros(6, np.int32)
+    cold = np.zeros(6, np.int32)
+    snew[0, :2] = [1, 2]
+    sold[0, :2] = [2, 3]
+    cnew[0], cold[0] = 2, 2
+    pu, pv, pd, pcnt, evals = og.join(x, og.L2SQ_F32, p, snew, cnew, sold, cold)
+    assert evals == 1 + 3  # (1,2) and (1,2),(1,3),(2,3); the pair (2,2) is skipped
+    props = set(zip(pu[0, :pcnt[0]].tolist(), pv[0, :pcnt[0]].tolist()))
+    assert all(u != v for u, v in props)
+
+
+# ------------------------------------------------------------ update --------
+def test_update_is_order_independent_and_equals_sorted_union():
+    x = W.small_integer_f32(150, 4, seed=51, hi=6)
+    k, p, seed = 6, 3, 8
+    g = og.init_random(x, k, og.L2SQ_F32, seed)
+    rng = np.random.default_rng(0)
+    for it in range(1, 4):
+        snew, cnew, sold, cold = og.sample(g, p, seed, it)
+        pu, pv, pd, pcnt, _ = og.join(x, og.L2SQ_F32, p, snew, cnew, sold, cold)
+        before = g.copy()
+        props = [(int(pu[s, j]), int(pv[s, j]), float(pd[s, j]))
+                 for s in range(150) for j in range(pcnt[s])]
+        inserts = og.update(g, p, pu, pv, pd, pcnt)
+        # (a) definition: sort the union, one entry per id, truncate
+        total_new = 0
+        for u in range(150):
+            pool = {int(i): (float(d), int(f)) for i, d, f in
+                    zip(before.ids[u], before.dist[u], before.isnew[u])}
+            for (uu, v, d) in props:
+                if uu == u and v not in pool:
+                    pool[v] = (d, 1)
+            top = sorted((d, v, f) for v, (d, f) in pool.items())[:k]
+            assert [v for _, v, _ in top] == g.ids[u].tolist()
+            assert [d for d, _, _ in top] == g.dist[u].tolist()
+            assert [f for _, _, f in top] == g.isnew[u].tolist()
+            total_new += len(set(g.ids[u].tolist()) - set(before.ids[u].tolist()))
+        assert inserts == total_new
+        # (b) one-at-a-time insertion in random orders gives the same lists
+        for _ in range(3):
+            h = before.copy()
+            for idx in rng.permutation(len(props)):
+                u, v, d = props[idx]
+                og.insert_one(h.ids[u], h.dist[u], h.isnew[u], v, d)
+            assert (h.ids == g.ids).all() and (h.dist == g.dist).all()
+            assert (h.isnew == g.isnew).all()
+
+
+# ---------------------------------------------------- whole iterations ------
+@pytest.mark.parametrize("metric", [og.L2SQ_F32, og.ANGULAR_F32, og.L2SQ_U8])
+def test_iterations_improve_monotonically_and_keep_invariants(metric):
+    n, k, p, seed = 500, 10, 6, 42
+    if metric == og.L2SQ_U8:
+        x = W.sift_like_u8(n, 16, seed=61, n_comp=8)
+    elif metric == og.ANGULAR_F32:
+        x = W.deep_like_f32(n, 16, seed=61, n_comp=8)
+    else:
+        x = W.uniform_f32(n, 16, seed=61)
+    g = og.init_random(x, k, metric, seed)
+    phi = og.phi(g.dist)
+    for it in range(1, 7):
+        before = g.copy()
+        st = og.iterate(x, metric, g, p, seed, it)
+        _check_lists(g, x, metric)
+        assert (g.dist <= before.dist).all()  # every rank of every list
+        new_phi = og.phi(g.dist)
+        assert new_phi <= phi
+        phi = new_phi
+        # flag bookkeeping: NEW entries = unsampled NEW left over + admitted entries
+        left = 0
+        for s in range(n):
+            left += max(0, int(before.isnew[s].sum()) - p)
+        assert int(g.isnew.sum()) <= left + st["inserts"]
+        if p >= k:
+            assert int(g.isnew.sum()) <= st["inserts"]
+        for s in range(0, n, 37):
+            for j in range(k):
+                assert g.dist[s, j] == og.distance(x, metric, s, int(g.ids[s, j]))
+    assert st["inserts"] < n  # it converges
+
+
+def test_tiny_build_reaches_the_exact_graph():
+    x = W.uniform_f32(256, 8, seed=62)
+    g, stats = og.build(x, 32, 32, og.L2SQ_F32, 42, 12)
+    ids, dist = og.bruteforce(x, og.L2SQ_F32, np.arange(256), 10)
+    tol, strict = og.recall_at(g.ids, g.dist, ids, dist, 10)
+    assert tol == 1.0 and strict == 1.0
+
+
+def test_recall_formula_on_a_hand_made_case():
+    # two nodes, K = 2: node 0 lists both true neighbours, node 1 lists one.
+    truth_ids = np.array([[1, 2], [0, 2]])
+    truth_dist = np.array([[1.0, 2.0], [1.0, 3.0]])
+    g_ids = np.array([[2, 1], [0, 3]])
+    g_dist = np.array([[2.0, 1.0], [1.0, 4.0]])
+    tol, strict = og.recall_at(g_ids, g_dist, truth_ids, truth_dist, 2)
+    assert tol == 0.75 and strict == 0.75
+    # a different id at the same distance as the K-th counts for the tolerant form only
+    g_ids2 = np.array([[1, 5], [0, 2]])
+    g_dist2 = np.array([[1.0, 2.0], [1.0, 3.0]])
+    tol, strict = og.recall_at(g_ids2, g_dist2, truth_ids, truth_dist, 2)
+    assert tol == 1.0 and strict == 0.75
+    assert og.phi(g_dist) == 8.0
+
+
+# ------------------------------------------------------------- merge --------
+def _exact_graph(x, metric, k):
+    ids, dist = og.bruteforce(x, metric, np.arange(len(x)), k)
+    return og.Graph(ids, dist, np.zeros_like(ids, dtype=np.uint8))
+
+
+def test_merge_final_is_top_k_of_union_with_the_set_aside_half():
+    k, n1, n2 = 9, 40, 30
+    x = W.uniform_f32(n1 + n2, 6, seed=72)
+    g1 = _exact_graph(x[:n1], og.L2SQ_F32, k)
+    g2 = _exact_graph(x[n1:], og.L2SQ_F32, k)
+    g, aside_ids, aside_dist = og.merge_init(x, n1, k, og.L2SQ_F32, 4, g1, g2)
+    og.iterate(x, og.L2SQ_F32, g, k, 4, 1, split=n1)
+    before = g.copy()
+    og.merge_final(g, aside_ids, aside_dist)
+    for s in range(n1 + n2):
+        pool = dict(zip(before.ids[s].tolist(), before.dist[s].tolist()))
+        for v, d in zip(aside_ids[s].tolist(), aside_dist[s].tolist()):
+            pool.setdefault(v, d)
+        top = sorted((d, v) for v, d in pool.items())[:k]
+        assert [v for _, v in top] == g.ids[s].tolist()
+        assert [d for d, _ in top] == g.dist[s].tolist()
+
+
+def test_merge_with_no_iterations_keeps_each_input_list():
+    # Zero refinement rounds: top-k of (kept half + random fill + set-aside
+    # half) can only be as good as or better than the input list, rank by rank,
+    # and it contains the whole input list unless a fill object displaced a tail.
+    k, n1, n2 = 8, 30, 25
+    x = W.uniform_f32(n1 + n2, 5, seed=76)
+    g1 = _exact_graph(x[:n1], og.L2SQ_F32, k)
+    g2 = _exact_graph(x[n1:], og.L2SQ_F32, k)
+    g, _ = og.merge(x, n1, k, k, og.L2SQ_F32, 5, g1, g2, 0)
+    assert (g.dist[:n1] <= g1.dist).all() and (g.dist[n1:] <= g2.dist).all()
+    for s in range(n1):
+        own = [v for v in g.ids[s].tolist() if v < n1]
+        assert own == g1.ids[s, :len(own)].tolist()
+
+
+def test_merge_init_structure():
+    k, n1, n2, seed = 9, 40, 30, 4
+    x = W.uniform_f32(n1 + n2, 6, seed=73)
+    g1 = _exact_graph(x[:n1], og.L2SQ_F32, k)
+    g2 = _exact_graph(x[n1:], og.L2SQ_F32, k)
+    g, aside_ids, aside_dist = og.merge_init(x, n1, k, og.L2SQ_F32, seed, g1, g2)
+    keep, fill = 5, 4
+    for s in range(n1 + n2):
+        first = s < n1
+        src = g1 if first else g2
+        loc = s if first else s - n1
+        shift = 0 if first else n1
+        kept = (src.ids[loc, :keep] + shift).tolist()
+        aside = (src.ids[loc, keep:] + shift).tolist()
+        assert aside_ids[s].tolist() == aside and (aside_dist[s] == src.dist[loc, keep:]).all()
+        row = g.ids[s].tolist()
+        assert len(set(row)) == k
+        old = [v for v, f in zip(row, g.isnew[s]) if not f]
+        new = [v for v, f in zip(row, g.isnew[s]) if f]
+        assert sorted(old) == sorted(kept) and len(new) == fill
+        for v in new:  # random objects of the other subset
+            assert (v >= n1) if first else (v < n1)
+        keys = list(zip(g.dist[s].tolist(), row))
+        assert keys == sorted(keys)
+        for j in range(k):
+            assert g.dist[s, j] == og.distance(x, og.L2SQ_F32, s, row[j])
+    # fills differ between nodes (they are random) and with the seed
+    g_b, _, _ = og.merge_init(x, n1, k, og.L2SQ_F32, seed + 1, g1, g2)
+    assert (g_b.ids != g.ids).any()
+
+
+def test_merge_of_exact_subgraphs_recovers_the_exact_graph_and_never_worsens():
+    k, p, n1, n2 = 10, 10, 150, 130
+    x = W.uniform_f32(n1 + n2, 6, seed=74)
+    g1 = _exact_graph(x[:n1], og.L2SQ_F32, k)
+    g2 = _exact_graph(x[n1:], og.L2SQ_F32, k)
+    g, stats = og.merge(x, n1, k, p, og.L2SQ_F32, 11, g1, g2, 6)
+    n = n1 + n2
+    _check_lists(g, x, og.L2SQ_F32)
+    # per rank never worse than the input list of the node
+    assert (g.dist[:n1] <= g1.dist).all() and (g.dist[n1:] <= g2.dist).all()
+    ids, dist = og.bruteforce(x, og.L2SQ_F32, np.arange(n), k)
+    tol, strict = og.recall_at(g.ids, g.dist, ids, dist, k)
+    g0, _ = og.merge(x, n1, k, p, og.L2SQ_F32, 11, g1, g2, 0)
+    tol0, _ = og.recall_at(g0.ids, g0.dist, ids, dist, k)
+    assert tol > 0.95 and tol > tol0 + 0.2  # the refinement rounds do the work
+    # only cross-subset pairs were evaluated: far fewer than a raw build needs
+    _, raw_stats = og.build(x, k, p, og.L2SQ_F32, 11, 6)
+    assert sum(s["dist_evals"] for s in stats) < sum(s["dist_evals"] for s in raw_stats)
+
+
+def test_merge_join_only_proposes_cross_subset_pairs():
+    k, p, n1, n2 = 8, 8, 50, 40
+    x = W.uniform_f32(n1 + n2, 5, seed=75)
+    g1 = _exact_graph(x[:n1], og.L2SQ_F32, k)
+    g2 = _exact_graph(x[n1:], og.L2SQ_F32, k)
+    g, aside_ids, aside_dist = og.merge_init(x, n1, k, og.L2SQ_F32, 3, g1, g2)
+    for it in range(1, 4):
+        snew, cnew, sold, cold = og.sample(g, p, 3, it)
+        # NEW entries of a node always lie in the other subset
+        for s in range(n1 + n2):
+            for v in snew[s, :cnew[s]]:
+                assert (v < n1) != (s < n1)
+        pu, pv, pd, pcnt, _ = og.join(x, og.L2SQ_F32, p, snew, cnew, sold, cold, split=n1)
+        for s in range(n1 + n2):
+            for j in range(pcnt[s]):
+                assert (pu[s, j] < n1) != (pv[s, j] < n1)
+        og.update(g, p, pu, pv, pd, pcnt)
