@@ -1,0 +1,175 @@
+/*
+ * gnnd.h - C ABI of the MI355X (gfx950) implementation of GPU NN-Descent (GNND)
+ * and the GPU graph merge (GGM) of "Large-Scale Approximate k-NN Graph
+ * Construction on GPU" (arxiv 2103.15386).
+ *
+ * Problem statement (Alg. 1 inputs/outputs): a reference set S of n vectors of
+ * dimension d, the list length k, the sample number p and an iteration count;
+ * the result is the k-NN graph G: for every object its k nearest neighbours
+ * found so far, as ids with distances, ascending by (distance, id).
+ *
+ * Conventions for every entry point
+ *  - "dev" pointers are device (HBM) pointers on the GPU that owns `stream`;
+ *    "host" pointers are ordinary host memory.  The library never allocates or
+ *    frees device memory: vectors, workspace and outputs belong to the caller
+ *    and must outlive the context that uses them.
+ *  - Work is enqueued on `stream` (a hipStream_t passed as void*).  Calls that
+ *    hand scalars back to the host (statistics) synchronise the stream first;
+ *    the others return after enqueueing.
+ *  - Every function returns GNND_OK or a negative error code and never aborts;
+ *    gnnd_last_error() gives the text.  Arguments are validated before anything
+ *    is launched.
+ *  - Ids are int32, 0-based row numbers of the vector array.  Distances are
+ *    float32 for the two float metrics and int32 for GNND_L2SQ_U8.
+ *  - All random draws come from a counter-based hash of (seed, purpose, node,
+ *    slot, attempt/iteration): results do not depend on thread timing, and two
+ *    runs with the same seed produce the same bytes.
+ */
+#ifndef GNND_H_
+#define GNND_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct gnnd_ctx gnnd_ctx; /* opaque, host-side, owned by the library */
+
+/* Distance (Sec. 4.2: "the specified distance metric"). */
+enum {
+  GNND_L2SQ_F32 = 0,    /* squared L2, float32 vectors, float32 result            */
+  GNND_ANGULAR_F32 = 1, /* 1 - dot product, float32 (unit) vectors, float32 result */
+  GNND_L2SQ_U8 = 2      /* squared L2, uint8 vectors, exact int32 result           */
+};
+
+enum {
+  GNND_OK = 0,
+  GNND_EINVAL = -1, /* bad argument                                   */
+  GNND_ENOSPC = -2, /* workspace too small                            */
+  GNND_ESTATE = -3, /* call out of order (e.g. iterate before a graph) */
+  GNND_EHIP = -4    /* a HIP runtime call or kernel launch failed      */
+};
+
+/* How the cross-matching distances (Sec. 4.2) are evaluated. */
+enum {
+  GNND_JOIN_AUTO = 0, /* library picks                                               */
+  GNND_JOIN_VALU = 1, /* per-pair float32 fused accumulation in dimension order      */
+  GNND_JOIN_MFMA = 2  /* Gram-block form on the matrix cores (exact for uint8 data)  */
+};
+
+typedef struct gnnd_params {
+  int64_t n;      /* number of vectors, k < n <= 2^30                               */
+  int32_t d;      /* dimension, >= 1 (float metrics: multiple of 4 reads fastest)   */
+  int32_t k;      /* list length, 2 <= k <= 64                                      */
+  int32_t p;      /* sample number of Sec. 4.1, 1 <= p <= min(k, 32)                */
+  int32_t metric; /* GNND_L2SQ_F32 / GNND_ANGULAR_F32 / GNND_L2SQ_U8               */
+  uint64_t seed;  /* seed of all random draws                                       */
+  void* stream;   /* hipStream_t; NULL = the default stream                         */
+  void* workspace_dev;    /* device scratch, 256-byte aligned, caller-owned         */
+  size_t workspace_bytes; /* its size, >= gnnd_workspace_bytes()                    */
+  int32_t join_path;      /* GNND_JOIN_*                                            */
+  int32_t reserved;       /* must be 0                                              */
+} gnnd_params;
+
+/* Counters of one iteration.  ms_* are stream times from HIP events. */
+typedef struct gnnd_iter_stats {
+  int32_t iter;        /* 1-based number of the iteration just finished            */
+  int32_t reserved;
+  uint64_t inserts;    /* list entries present now that were absent before it      */
+  uint64_t dist_evals; /* distances evaluated by the cross-matching                */
+  uint64_t sum_new;    /* total size of all NEW sample lists                       */
+  uint64_t sum_old;    /* total size of all OLD sample lists                       */
+  uint64_t proposals;  /* nearest-object results handed to the list update         */
+  float ms_sample, ms_join, ms_update;
+  float reserved2;
+} gnnd_iter_stats;
+
+/* Device scratch needed for these parameters (pure host arithmetic; n, d, k, p,
+ * metric are read).  Returns 0 when the parameters are invalid. */
+size_t gnnd_workspace_bytes(const gnnd_params* prm);
+
+/* Create a context over `vectors_dev`: n*d elements, row-major, float32 or
+ * uint8 according to the metric, 16-byte aligned.  Validates everything, lays
+ * the workspace out and clears its counters (enqueued on the stream). */
+int gnnd_create(gnnd_ctx** out, const gnnd_params* prm, const void* vectors_dev);
+void gnnd_destroy(gnnd_ctx* ctx);
+
+/* Text of the last error of this context (or of the last failed gnnd_create /
+ * context-free call when ctx is NULL).  Never NULL. */
+const char* gnnd_last_error(const gnnd_ctx* ctx);
+
+/* Alg. 1, first loop: every list gets k distinct random objects other than the
+ * node itself, with their distances, ascending by (distance, id), all flagged
+ * NEW.  Resets the iteration counter to 0. */
+int gnnd_init_random(gnnd_ctx* ctx);
+
+/* One pass of the Alg. 1 loop body: ParallelSample (Sec. 4.1), cross-matching
+ * (Sec. 4.2), selective update and list insertion (Sec. 4.3).  `stats_host`
+ * may be NULL (then nothing is copied back and the call does not synchronise). */
+int gnnd_iterate(gnnd_ctx* ctx, gnnd_iter_stats* stats_host);
+
+/* The three stages of gnnd_iterate one at a time, in this order, for step-wise
+ * checks: sampling; cross-matching + nearest-object selection; list update
+ * (which ends the iteration and may return its statistics). */
+int gnnd_step_sample(gnnd_ctx* ctx);
+int gnnd_step_join(gnnd_ctx* ctx);
+int gnnd_step_update(gnnd_ctx* ctx, gnnd_iter_stats* stats_host);
+
+/* Alg. 1 as a whole: gnnd_init_random, then up to max_iters iterations.
+ * delta > 0 additionally stops after an iteration with fewer than
+ * delta * n * k inserts (not in the paper; 0 = fixed iteration count).
+ * `last_host` (may be NULL) receives the statistics of the last iteration run. */
+int gnnd_build(gnnd_ctx* ctx, int32_t max_iters, float delta, gnnd_iter_stats* last_host);
+
+/* Copy the graph out: n*k ids, n*k distances (float32 or int32 by metric) and
+ * n*k NEW flags (0/1), row per node, ascending by (distance, id).  Any of the
+ * three device pointers may be NULL. */
+int gnnd_get_graph(gnnd_ctx* ctx, int32_t* ids_dev, void* dist_dev, uint8_t* isnew_dev);
+
+/* Load a graph (same layout; rows must be sorted by (distance, id) and hold k
+ * distinct ids) and set the iteration counter: continuing from a saved graph
+ * gives the same bytes as an uninterrupted run. */
+int gnnd_set_graph(gnnd_ctx* ctx, const int32_t* ids_dev, const void* dist_dev,
+                   const uint8_t* isnew_dev, int32_t iter);
+
+/* Sample lists of the last gnnd_step_sample / gnnd_iterate (Sec. 4.1): n rows of
+ * 2p ids ascending, unused tail -1, and the n list sizes, per kind. */
+int gnnd_get_samples(gnnd_ctx* ctx, int32_t* new_dev, int32_t* cnt_new_dev, int32_t* old_dev,
+                     int32_t* cnt_old_dev);
+
+/* Nearest-object results of the last gnnd_step_join (Alg. 2 outputs), dense:
+ * n rows of 6p slots = [NEW u: nearest other NEW | NEW u: nearest OLD |
+ * OLD u: nearest NEW], 2p slots each, slot i belonging to the i-th sample.
+ * u_dev = list to insert into (-1 = no result, or dropped because it cannot
+ * beat the list's last entry), v_dev = object to insert, dist_dev = distance
+ * (float32 / int32 by metric). */
+int gnnd_get_proposals(gnnd_ctx* ctx, int32_t* u_dev, int32_t* v_dev, void* dist_dev);
+
+/* GGM (Sec. 5.1, Alg. 3): merge the k-NN graph G1 of S1 (n1 vectors at
+ * vec1_dev) and G2 of S2 (n2 vectors at vec2_dev) into the graph of S1 u S2,
+ * prm->n = n1 + n2, rows 0..n1-1 = S1 then S2; input ids are local to their
+ * set, output ids are rows of the union.  Each list keeps its first ceil(k/2)
+ * entries, the rest is set aside and replaced by floor(k/2) random objects of
+ * the other set flagged NEW; `iters` GNND iterations then evaluate only pairs
+ * from different sets (and no NEW x NEW pairs); finally each list is the best k
+ * of the refined list and its set-aside half.  Needs min(n1, n2) >= floor(k/2).
+ * Synchronises when stats_host (array of `iters` entries, may be NULL) is given. */
+int gnnd_merge(const gnnd_params* prm, const void* vec1_dev, int64_t n1, const void* vec2_dev,
+               int64_t n2, const int32_t* ids1_dev, const void* dist1_dev,
+               const int32_t* ids2_dev, const void* dist2_dev, int32_t iters,
+               int32_t* ids_out_dev, void* dist_out_dev, gnnd_iter_stats* stats_host);
+
+/* Exact K nearest neighbours by exhaustive search (the ground truth of
+ * Recall@K, Sec. 6.1) of nq query nodes (ids in queries_dev) against all n
+ * vectors, the node itself excluded: nq*K ids and distances ascending by
+ * (distance, id).  K <= 64.  Needs no context and no workspace. */
+int gnnd_exact_knn(const void* vectors_dev, int64_t n, int32_t d, int32_t metric,
+                   const int32_t* queries_dev, int64_t nq, int32_t K, int32_t* ids_out_dev,
+                   void* dist_out_dev, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GNND_H_ */

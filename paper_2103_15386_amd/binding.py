@@ -1,0 +1,305 @@
+"""ctypes binding of the C ABI in include/gnnd.h.  Marshalling only."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+L2SQ_F32, ANGULAR_F32, L2SQ_U8 = 0, 1, 2
+JOIN_AUTO, JOIN_VALU, JOIN_MFMA = 0, 1, 2
+OK, EINVAL, ENOSPC, ESTATE, EHIP = 0, -1, -2, -3, -4
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libgnnd_hip.so")
+_lib = None
+
+EXPORTS = [
+    "gnnd_workspace_bytes", "gnnd_create", "gnnd_destroy", "gnnd_last_error", "gnnd_init_random",
+    "gnnd_iterate", "gnnd_step_sample", "gnnd_step_join", "gnnd_step_update", "gnnd_build",
+    "gnnd_get_graph", "gnnd_set_graph", "gnnd_get_samples", "gnnd_get_proposals", "gnnd_merge",
+    "gnnd_exact_knn",
+]
+
+
+class GnndError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"gnnd error {code}: {msg}")
+        self.code = code
+
+
+class Params(C.Structure):
+    _fields_ = [("n", C.c_int64), ("d", C.c_int32), ("k", C.c_int32), ("p", C.c_int32),
+                ("metric", C.c_int32), ("seed", C.c_uint64), ("stream", C.c_void_p),
+                ("workspace_dev", C.c_void_p), ("workspace_bytes", C.c_size_t),
+                ("join_path", C.c_int32), ("reserved", C.c_int32)]
+
+
+class IterStats(C.Structure):
+    _fields_ = [("iter", C.c_int32), ("reserved", C.c_int32), ("inserts", C.c_uint64),
+                ("dist_evals", C.c_uint64), ("sum_new", C.c_uint64), ("sum_old", C.c_uint64),
+                ("proposals", C.c_uint64), ("ms_sample", C.c_float), ("ms_join", C.c_float),
+                ("ms_update", C.c_float), ("reserved2", C.c_float)]
+
+    def as_dict(self):
+        return {f: getattr(self, f) for f, _ in self._fields_ if not f.startswith("reserved")}
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libgnnd_hip.so (built in-tree by paper_2103_15386_amd.build).  Raises
+    if it has not been built: there is no other implementation to fall back to."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise GnndError(EHIP, f"{_LIB_PATH} is missing: run `python -m paper_2103_15386_amd.build`")
+    lib = C.CDLL(_LIB_PATH)
+    vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    PP = C.POINTER(Params)
+    SP = C.POINTER(IterStats)
+    lib.gnnd_workspace_bytes.restype = C.c_size_t
+    lib.gnnd_workspace_bytes.argtypes = [PP]
+    lib.gnnd_create.restype = C.c_int
+    lib.gnnd_create.argtypes = [C.POINTER(vp), PP, vp]
+    lib.gnnd_destroy.restype = None
+    lib.gnnd_destroy.argtypes = [vp]
+    lib.gnnd_last_error.restype = C.c_char_p
+    lib.gnnd_last_error.argtypes = [vp]
+    for name in ("gnnd_init_random", "gnnd_step_sample", "gnnd_step_join"):
+        getattr(lib, name).restype = C.c_int
+        getattr(lib, name).argtypes = [vp]
+    lib.gnnd_iterate.restype = C.c_int
+    lib.gnnd_iterate.argtypes = [vp, SP]
+    lib.gnnd_step_update.restype = C.c_int
+    lib.gnnd_step_update.argtypes = [vp, SP]
+    lib.gnnd_build.restype = C.c_int
+    lib.gnnd_build.argtypes = [vp, i32, C.c_float, SP]
+    lib.gnnd_get_graph.restype = C.c_int
+    lib.gnnd_get_graph.argtypes = [vp, vp, vp, vp]
+    lib.gnnd_set_graph.restype = C.c_int
+    lib.gnnd_set_graph.argtypes = [vp, vp, vp, vp, i32]
+    lib.gnnd_get_samples.restype = C.c_int
+    lib.gnnd_get_samples.argtypes = [vp, vp, vp, vp, vp]
+    lib.gnnd_get_proposals.restype = C.c_int
+    lib.gnnd_get_proposals.argtypes = [vp, vp, vp, vp]
+    lib.gnnd_merge.restype = C.c_int
+    lib.gnnd_merge.argtypes = [PP, vp, i64, vp, i64, vp, vp, vp, vp, i32, vp, vp, SP]
+    lib.gnnd_exact_knn.restype = C.c_int
+    lib.gnnd_exact_knn.argtypes = [vp, i64, i32, i32, vp, i64, i32, vp, vp, vp]
+    _lib = lib
+    return lib
+
+
+def _err(ctx=None):
+    return load_library().gnnd_last_error(ctx).decode()
+
+
+def _check(rc, ctx=None):
+    if rc != OK:
+        raise GnndError(rc, _err(ctx))
+
+
+def _elem_dtype(metric):
+    return torch.uint8 if metric == L2SQ_U8 else torch.float32
+
+
+def _dist_dtype(metric):
+    return torch.int32 if metric == L2SQ_U8 else torch.float32
+
+
+def _require_device(t, dtype, what):
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise GnndError(EINVAL, f"{what} must be a GPU tensor (no CPU path exists)")
+    if t.dtype != dtype or not t.is_contiguous():
+        raise GnndError(EINVAL, f"{what} must be contiguous {dtype}")
+    return t
+
+
+def _stream_ptr(device):
+    return torch.cuda.current_stream(device).cuda_stream
+
+
+def make_params(n, d, k, p, metric, seed=42, join_path=JOIN_AUTO, stream=0, workspace=None):
+    prm = Params()
+    prm.n, prm.d, prm.k, prm.p, prm.metric = n, d, k, p, metric
+    prm.seed = seed
+    prm.stream = stream
+    prm.join_path = join_path
+    prm.reserved = 0
+    if workspace is not None:
+        prm.workspace_dev = workspace.data_ptr()
+        prm.workspace_bytes = workspace.numel() * workspace.element_size()
+    return prm
+
+
+def workspace_bytes(n, d, k, p, metric):
+    """Bytes of device scratch a context with these parameters needs (0 = invalid)."""
+    prm = make_params(n, d, k, p, metric)
+    return int(load_library().gnnd_workspace_bytes(C.byref(prm)))
+
+
+class Gnnd:
+    """One GNND context over a resident vector tensor (n x d, float32 or uint8)."""
+
+    def __init__(self, vectors, k, p, metric=L2SQ_F32, seed=42, join_path=JOIN_AUTO):
+        lib = load_library()
+        self.vectors = _require_device(vectors, _elem_dtype(metric), "vectors")
+        self.n, self.d = vectors.shape
+        self.k, self.p, self.metric, self.seed = k, p, metric, seed
+        need = workspace_bytes(self.n, self.d, k, p, metric)
+        if need == 0:
+            prm = make_params(self.n, self.d, k, p, metric, seed, join_path)
+            ctx = C.c_void_p()
+            rc = lib.gnnd_create(C.byref(ctx), C.byref(prm), vectors.data_ptr())
+            raise GnndError(rc, _err())
+        self.workspace = torch.empty(need, dtype=torch.uint8, device=vectors.device)
+        self.prm = make_params(self.n, self.d, k, p, metric, seed, join_path,
+                               _stream_ptr(vectors.device), self.workspace)
+        self._ctx = C.c_void_p()
+        _check(lib.gnnd_create(C.byref(self._ctx), C.byref(self.prm), vectors.data_ptr()))
+        self._lib = lib
+
+    def close(self):
+        if getattr(self, "_ctx", None):
+            self._lib.gnnd_destroy(self._ctx)
+            self._ctx = None
+
+    __del__ = close
+
+    def init_random(self):
+        _check(self._lib.gnnd_init_random(self._ctx), self._ctx)
+
+    def iterate(self, want_stats=True):
+        st = IterStats()
+        _check(self._lib.gnnd_iterate(self._ctx, C.byref(st) if want_stats else None), self._ctx)
+        return st.as_dict() if want_stats else None
+
+    def step_sample(self):
+        _check(self._lib.gnnd_step_sample(self._ctx), self._ctx)
+
+    def step_join(self):
+        _check(self._lib.gnnd_step_join(self._ctx), self._ctx)
+
+    def step_update(self, want_stats=True):
+        st = IterStats()
+        _check(self._lib.gnnd_step_update(self._ctx, C.byref(st) if want_stats else None),
+               self._ctx)
+        return st.as_dict() if want_stats else None
+
+    def build(self, max_iters, delta=0.0, want_stats=True):
+        st = IterStats()
+        _check(self._lib.gnnd_build(self._ctx, max_iters, delta,
+                                    C.byref(st) if want_stats else None), self._ctx)
+        return st.as_dict() if want_stats else None
+
+    def graph(self, with_flags=False):
+        dev = self.vectors.device
+        ids = torch.empty((self.n, self.k), dtype=torch.int32, device=dev)
+        dist = torch.empty((self.n, self.k), dtype=_dist_dtype(self.metric), device=dev)
+        flags = torch.empty((self.n, self.k), dtype=torch.uint8, device=dev) if with_flags else None
+        _check(self._lib.gnnd_get_graph(self._ctx, ids.data_ptr(), dist.data_ptr(),
+                                        flags.data_ptr() if with_flags else None), self._ctx)
+        return (ids, dist, flags) if with_flags else (ids, dist)
+
+    def set_graph(self, ids, dist, flags, it):
+        _require_device(ids, torch.int32, "ids")
+        _require_device(dist, _dist_dtype(self.metric), "dist")
+        _require_device(flags, torch.uint8, "flags")
+        _check(self._lib.gnnd_set_graph(self._ctx, ids.data_ptr(), dist.data_ptr(),
+                                        flags.data_ptr(), it), self._ctx)
+
+    def samples(self):
+        dev = self.vectors.device
+        L = 2 * self.p
+        snew = torch.empty((self.n, L), dtype=torch.int32, device=dev)
+        sold = torch.empty((self.n, L), dtype=torch.int32, device=dev)
+        cnew = torch.empty(self.n, dtype=torch.int32, device=dev)
+        cold = torch.empty(self.n, dtype=torch.int32, device=dev)
+        _check(self._lib.gnnd_get_samples(self._ctx, snew.data_ptr(), cnew.data_ptr(),
+                                          sold.data_ptr(), cold.data_ptr()), self._ctx)
+        return snew, cnew, sold, cold
+
+    def proposals(self):
+        dev = self.vectors.device
+        shape = (self.n, 6 * self.p)
+        u = torch.empty(shape, dtype=torch.int32, device=dev)
+        v = torch.empty(shape, dtype=torch.int32, device=dev)
+        dist = torch.empty(shape, dtype=_dist_dtype(self.metric), device=dev)
+        _check(self._lib.gnnd_get_proposals(self._ctx, u.data_ptr(), v.data_ptr(),
+                                            dist.data_ptr()), self._ctx)
+        return u, v, dist
+
+
+# ---- free functions with the names of the C entry points --------------------
+def gnnd_init_random(ctx: Gnnd):
+    ctx.init_random()
+
+
+def gnnd_iterate(ctx: Gnnd, want_stats=True):
+    return ctx.iterate(want_stats)
+
+
+def gnnd_build(vectors, k, p, metric=L2SQ_F32, seed=42, iters=12, join_path=JOIN_AUTO):
+    """Build a graph from scratch; returns (ids, dist, context)."""
+    ctx = Gnnd(vectors, k, p, metric, seed, join_path)
+    ctx.build(iters, want_stats=False)
+    ids, dist = ctx.graph()
+    return ids, dist, ctx
+
+
+def gnnd_merge(vec1, vec2, ids1, dist1, ids2, dist2, k, p, metric=L2SQ_F32, seed=42, iters=6,
+               join_path=JOIN_AUTO, want_stats=False):
+    """GGM of two graphs; returns (ids, dist[, stats]) over the union, S1 rows first."""
+    lib = load_library()
+    et, dt = _elem_dtype(metric), _dist_dtype(metric)
+    _require_device(vec1, et, "vec1")
+    _require_device(vec2, et, "vec2")
+    for t, ty, nm in ((ids1, torch.int32, "ids1"), (ids2, torch.int32, "ids2"),
+                      (dist1, dt, "dist1"), (dist2, dt, "dist2")):
+        _require_device(t, ty, nm)
+    n1, d = vec1.shape
+    n2 = vec2.shape[0]
+    n = n1 + n2
+    need = workspace_bytes(n, d, k, p, metric)
+    dev = vec1.device
+    ws = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    prm = make_params(n, d, k, p, metric, seed, join_path, _stream_ptr(dev), ws)
+    ids = torch.empty((n, k), dtype=torch.int32, device=dev)
+    dist = torch.empty((n, k), dtype=dt, device=dev)
+    stats = (IterStats * max(iters, 1))()
+    rc = lib.gnnd_merge(C.byref(prm), vec1.data_ptr(), n1, vec2.data_ptr(), n2, ids1.data_ptr(),
+                        dist1.data_ptr(), ids2.data_ptr(), dist2.data_ptr(), iters,
+                        ids.data_ptr(), dist.data_ptr(), stats if want_stats else None)
+    _check(rc)
+    torch.cuda.current_stream(dev).synchronize()  # the workspace dies with this frame
+    if want_stats:
+        return ids, dist, [stats[i].as_dict() for i in range(iters)]
+    return ids, dist
+
+
+def exact_knn(vectors, queries, K, metric=L2SQ_F32):
+    """Exhaustive exact K-NN of the query nodes (evaluation ground truth)."""
+    lib = load_library()
+    _require_device(vectors, _elem_dtype(metric), "vectors")
+    _require_device(queries, torch.int32, "queries")
+    n, d = vectors.shape
+    nq = queries.numel()
+    ids = torch.empty((nq, K), dtype=torch.int32, device=vectors.device)
+    dist = torch.empty((nq, K), dtype=_dist_dtype(metric), device=vectors.device)
+    _check(lib.gnnd_exact_knn(vectors.data_ptr(), n, d, metric, queries.data_ptr(), nq, K,
+                              ids.data_ptr(), dist.data_ptr(), _stream_ptr(vectors.device)))
+    return ids, dist
+
+
+def recall_at(graph_dist, truth_dist, K=10):
+    """Recall@K (Sec. 6.1) of graph rows against exact rows of the same nodes: a
+    listed neighbour among the first K is a true positive when its distance does
+    not exceed the exact K-th distance (equal distances are interchangeable)."""
+    gd = graph_dist[:, :K]
+    kth = truth_dist[:, K - 1:K]
+    return float((gd <= kth).sum().item()) / gd.numel()

@@ -1,0 +1,51 @@
+"""Build step of the HIP library (hipcc cross-compiles for gfx950; no GPU needed)."""
+from __future__ import annotations
+
+import os
+import subprocess
+from concurrent.futures import ThreadPoolExecutor
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "libgnnd_hip.so")
+SOURCES = ["graph_kernels.hip", "join_valu.hip", "gnnd_api.hip"]
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-result",
+         # packed FP32 instructions are kept off on purpose
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+
+
+def _headers():
+    inc = os.path.join(os.path.dirname(HERE), "include", "gnnd.h")
+    return [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hpp")] + [inc]
+
+
+def build_library(force=False, verbose=False):
+    """Compile every HIP source for gfx950 and link libgnnd_hip.so in-tree."""
+    srcs = [os.path.join(CSRC, s) for s in SOURCES]
+    objs = [s[:-4] + ".o" for s in srcs]
+    newest_hdr = max(os.path.getmtime(h) for h in _headers())
+
+    def compile_one(pair):
+        src, obj = pair
+        if (not force and os.path.exists(obj)
+                and os.path.getmtime(obj) >= max(os.path.getmtime(src), newest_hdr)):
+            return False
+        cmd = [HIPCC, *FLAGS, "-c", src, "-o", obj]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True)
+        return True
+
+    with ThreadPoolExecutor(max_workers=4) as ex:
+        rebuilt = list(ex.map(compile_one, zip(srcs, objs)))
+    if force or any(rebuilt) or not os.path.exists(LIB):
+        cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build_library(force=True, verbose=True))

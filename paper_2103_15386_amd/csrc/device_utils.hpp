@@ -1,0 +1,258 @@
+// Device-side building blocks shared by the GNND kernels: the counter-based
+// hash, the order-preserving distance encoding, packed list entries and the
+// 64-lane sorting / merging networks that act on one value per lane.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace gnnd {
+
+constexpr int kWave = 64;
+constexpr uint64_t kKeyMax = ~0ull;
+constexpr uint32_t kIdMax = 0x7fffffffu;
+
+enum : int { kL2F32 = 0, kAngularF32 = 1, kL2U8 = 2 };
+enum : uint32_t { kTagInit = 1, kTagRevNew = 2, kTagRevOld = 3, kTagMerge = 4 };
+constexpr uint32_t kHashAttempts = 256;
+
+// ---- counter-based random numbers ---------------------------------------
+// hash(seed, tag, a, b, c): three rounds of the splitmix64 output mixer over
+// (seed, tag), the packed pair (a, b), and c.  Any thread can draw any number.
+__host__ __device__ inline uint64_t mix64(uint64_t z) {
+  z ^= z >> 30;
+  z *= 0xbf58476d1ce4e5b9ull;
+  z ^= z >> 27;
+  z *= 0x94d049bb133111ebull;
+  z ^= z >> 31;
+  return z;
+}
+// The (seed, tag) round depends on nothing per thread: computed once on the host.
+__host__ __device__ inline uint64_t hash_base(uint64_t seed, uint32_t tag) {
+  return mix64(seed + 0x9e3779b97f4a7c15ull * ((uint64_t)tag + 1));
+}
+__device__ inline uint64_t hash3(uint64_t base, uint32_t a, uint32_t b, uint32_t c) {
+  uint64_t h = mix64(base ^ (((uint64_t)a << 32) | (uint64_t)b));
+  return mix64(h + (uint64_t)c);
+}
+// upper 32 hash bits mapped onto [0, n) by multiply-high
+__device__ inline uint32_t bounded(uint64_t h, uint32_t n) {
+  return __umulhi((uint32_t)(h >> 32), n);
+}
+
+// ---- distances as order-preserving 32-bit codes -------------------------
+// A float (possibly negative: 1 - dot can round below zero) or an int32 maps to
+// an unsigned code with the same order, so (code << 32 | id) compares like
+// (distance, id).
+__device__ inline uint32_t ord_f32(float x) {
+  uint32_t b = __float_as_uint(x);
+  return b ^ ((b >> 31) ? 0xffffffffu : 0x80000000u);
+}
+__device__ inline float unord_f32(uint32_t o) {
+  return __uint_as_float((o & 0x80000000u) ? (o ^ 0x80000000u) : ~o);
+}
+__device__ inline uint32_t ord_i32(int32_t x) { return (uint32_t)x ^ 0x80000000u; }
+__device__ inline int32_t unord_i32(uint32_t o) { return (int32_t)(o ^ 0x80000000u); }
+
+// ---- packed list entry ---------------------------------------------------
+// 64 bits: [63:32] distance code, [31:2] neighbour id, bit 1 "admitted by the
+// update in progress", bit 0 NEW flag.  Unsigned comparison of two entries
+// with different ids orders them by (distance, id).
+__device__ inline uint64_t make_entry(uint32_t code, uint32_t id, uint32_t flags) {
+  return ((uint64_t)code << 32) | ((uint64_t)id << 2) | flags;
+}
+__device__ inline uint32_t entry_id(uint64_t e) { return ((uint32_t)e) >> 2; }
+__device__ inline uint32_t entry_code(uint64_t e) { return (uint32_t)(e >> 32); }
+__device__ inline uint64_t entry_key(uint64_t e) { return e >> 2; }  // (distance, id) only
+
+// ---- wavefront helpers (one value per lane, 64 lanes) --------------------
+__device__ inline int lane_id() { return (int)(threadIdx.x & (kWave - 1)); }
+__device__ inline uint64_t lanes_below(int lane) { return (1ull << lane) - 1ull; }
+
+__device__ inline uint64_t readlane64(uint64_t x, int l) {
+  uint32_t lo = __builtin_amdgcn_readlane((uint32_t)x, l);
+  uint32_t hi = __builtin_amdgcn_readlane((uint32_t)(x >> 32), l);
+  return ((uint64_t)hi << 32) | lo;
+}
+
+template <typename T>
+__device__ inline T vmin(T a, T b) { return a < b ? a : b; }
+template <typename T>
+__device__ inline T vmax(T a, T b) { return a < b ? b : a; }
+
+// Full ascending sort of 64 lane values (bitonic network, 21 exchange stages).
+template <typename T>
+__device__ inline T wave_sort(T v, int lane) {
+#pragma unroll
+  for (int k = 2; k <= kWave; k <<= 1) {
+#pragma unroll
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      T o = __shfl_xor(v, j, kWave);
+      bool keep_min = (((lane & j) == 0) == ((lane & k) == 0));
+      v = keep_min ? vmin(v, o) : vmax(v, o);
+    }
+  }
+  return v;
+}
+
+// Lanes hold a bitonic sequence (ascending then descending, or an element-wise
+// min of an ascending and a reversed ascending one): 6 stages sort it ascending.
+template <typename T>
+__device__ inline T wave_bitonic_merge(T v, int lane) {
+#pragma unroll
+  for (int j = kWave >> 1; j > 0; j >>= 1) {
+    T o = __shfl_xor(v, j, kWave);
+    v = ((lane & j) == 0) ? vmin(v, o) : vmax(v, o);
+  }
+  return v;
+}
+
+// The 64 smallest of two ascending 64-lane sequences, ascending.
+template <typename T>
+__device__ inline T wave_merge_smallest(T a_sorted, T b_sorted, int lane) {
+  T br = __shfl(b_sorted, kWave - 1 - lane, kWave);
+  return wave_bitonic_merge(vmin(a_sorted, br), lane);
+}
+
+// Stable compaction of the lanes with keep == true to the front; the other
+// lanes end up behind them holding `fill`.
+__device__ inline uint64_t wave_compact(uint64_t v, bool keep, uint64_t fill, int lane) {
+  uint64_t mask = __ballot(keep);
+  int nkeep = __popcll(mask);
+  int before = __popcll(mask & lanes_below(lane));
+  int dst = keep ? before : nkeep + (lane - before);
+  uint64_t x = keep ? v : fill;
+  uint32_t lo = __builtin_amdgcn_ds_permute(dst << 2, (int)(uint32_t)x);
+  uint32_t hi = __builtin_amdgcn_ds_permute(dst << 2, (int)(uint32_t)(x >> 32));
+  return ((uint64_t)hi << 32) | lo;
+}
+
+// ---- canonical distances --------------------------------------------------
+// Float metrics accumulate one fused multiply-add per dimension, in dimension
+// order, in float32; bytes accumulate exact int32 squares.  The result is the
+// order-preserving code of the distance.
+template <int METRIC>
+struct DistOf;
+
+template <>
+struct DistOf<kL2F32> {
+  using elem = float;
+  __device__ static uint32_t eval(const float* a, const float* b, int d) {
+    float acc = 0.f;
+    int j = 0;
+    if ((d & 3) == 0) {
+      const float4* a4 = reinterpret_cast<const float4*>(a);
+      const float4* b4 = reinterpret_cast<const float4*>(b);
+      for (; j < (d >> 2); ++j) {
+        float4 x = a4[j], y = b4[j];
+        float t;
+        t = x.x - y.x; acc = __fmaf_rn(t, t, acc);
+        t = x.y - y.y; acc = __fmaf_rn(t, t, acc);
+        t = x.z - y.z; acc = __fmaf_rn(t, t, acc);
+        t = x.w - y.w; acc = __fmaf_rn(t, t, acc);
+      }
+    } else {
+      for (; j < d; ++j) {
+        float t = a[j] - b[j];
+        acc = __fmaf_rn(t, t, acc);
+      }
+    }
+    return ord_f32(acc);
+  }
+};
+
+template <>
+struct DistOf<kAngularF32> {
+  using elem = float;
+  __device__ static uint32_t eval(const float* a, const float* b, int d) {
+    float acc = 0.f;
+    int j = 0;
+    if ((d & 3) == 0) {
+      const float4* a4 = reinterpret_cast<const float4*>(a);
+      const float4* b4 = reinterpret_cast<const float4*>(b);
+      for (; j < (d >> 2); ++j) {
+        float4 x = a4[j], y = b4[j];
+        acc = __fmaf_rn(x.x, y.x, acc);
+        acc = __fmaf_rn(x.y, y.y, acc);
+        acc = __fmaf_rn(x.z, y.z, acc);
+        acc = __fmaf_rn(x.w, y.w, acc);
+      }
+    } else {
+      for (; j < d; ++j) acc = __fmaf_rn(a[j], b[j], acc);
+    }
+    return ord_f32(1.0f - acc);
+  }
+};
+
+template <>
+struct DistOf<kL2U8> {
+  using elem = uint8_t;
+  __device__ static uint32_t eval(const uint8_t* a, const uint8_t* b, int d) {
+    int32_t acc = 0;
+    int j = 0;
+    if ((d & 3) == 0) {
+      const uint32_t* a4 = reinterpret_cast<const uint32_t*>(a);
+      const uint32_t* b4 = reinterpret_cast<const uint32_t*>(b);
+      for (; j < (d >> 2); ++j) {
+        uint32_t x = a4[j], y = b4[j];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          int32_t t = (int32_t)((x >> (8 * q)) & 0xff) - (int32_t)((y >> (8 * q)) & 0xff);
+          acc += t * t;
+        }
+      }
+    } else {
+      for (; j < d; ++j) {
+        int32_t t = (int32_t)a[j] - (int32_t)b[j];
+        acc += t * t;
+      }
+    }
+    return ord_i32(acc);
+  }
+};
+
+// Vectors may live in two arrays (the two sets of a merge): rows below `split`
+// come from the first, the others from the second.
+struct VecSrc {
+  const void* a;
+  const void* b;
+  int64_t split;
+  int32_t d;
+  template <typename T>
+  __device__ const T* row(uint32_t id) const {
+    return ((int64_t)id < split) ? reinterpret_cast<const T*>(a) + (int64_t)id * d
+                                 : reinterpret_cast<const T*>(b) + ((int64_t)id - split) * d;
+  }
+};
+
+// Draw `count` (<= 64) distinct ids out of [0, range) + base for node s, one per
+// lane: slot j takes hash(base_hash, s, j, attempt) mapped onto the range for
+// attempt = 0, 1, ... until the id differs from `forbid` and from the ids of
+// the slots before it; after kHashAttempts failures it walks to the next free
+// id cyclically.  Wave-uniform loop; returns the id of slot `lane` (lanes >=
+// count: undefined).
+__device__ inline uint32_t draw_distinct(uint64_t base_hash, uint32_t s, int count,
+                                         uint32_t range, uint32_t base, uint32_t forbid,
+                                         int lane) {
+  uint32_t mine = 0xffffffffu;
+  for (int j = 0; j < count; ++j) {
+    uint32_t cand = 0;
+    bool ok = false;
+    for (uint32_t attempt = 0; attempt < kHashAttempts && !ok; ++attempt) {
+      cand = bounded(hash3(base_hash, s, (uint32_t)j, attempt), range) + base;
+      bool clash = (lane < j) && (mine == cand);
+      ok = (cand != forbid) && (__ballot(clash) == 0ull);
+    }
+    // at most `range` steps: the host has checked that enough ids are free
+    for (uint32_t step = 0; step < range && !ok; ++step) {
+      uint32_t local = cand - base;
+      local = (local + 1 == range) ? 0 : local + 1;
+      cand = local + base;
+      bool clash = (lane < j) && (mine == cand);
+      ok = (cand != forbid) && (__ballot(clash) == 0ull);
+    }
+    if (lane == j) mine = cand;
+  }
+  return mine;
+}
+
+}  // namespace gnnd

@@ -1,0 +1,415 @@
+// Host side of the C ABI declared in include/gnnd.h: argument validation,
+// workspace layout, stage sequencing, statistics.  No device memory is
+// allocated here; every array is carved out of the caller's workspace.
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "../../include/gnnd.h"
+#include "kernels.hpp"
+
+using namespace gnnd;
+
+namespace {
+
+thread_local std::string g_last_error = "";
+
+struct Layout {
+  size_t off_G, off_kth, off_snew, off_sold, off_cnew, off_cold, off_rcn, off_rco, off_ron,
+      off_roo, off_csn, off_cso, off_pcnt, off_poff, off_pdest, off_pkey, off_bins, off_scan,
+      off_cnt, off_snap, off_aside, total;
+};
+
+inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
+const char* check_params(const gnnd_params* q) {
+  if (!q) return "params is NULL";
+  if (q->metric < GNND_L2SQ_F32 || q->metric > GNND_L2SQ_U8) return "unknown metric";
+  if (q->k < 2 || q->k > 64) return "k must be in [2, 64]";
+  if (q->p < 1 || q->p > 32 || q->p > q->k) return "p must be in [1, min(k, 32)]";
+  if (q->d < 1) return "d must be >= 1";
+  if (q->metric == GNND_L2SQ_U8 && q->d > 32768) return "d must be <= 32768 for uint8 vectors";
+  if (q->n <= q->k) return "n must exceed k";
+  if (q->n > ((int64_t)1 << 30)) return "n must be <= 2^30";
+  if (q->n * (int64_t)q->p >= ((int64_t)1 << 32)) return "n * p must be below 2^32";
+  if (q->join_path < GNND_JOIN_AUTO || q->join_path > GNND_JOIN_MFMA) return "unknown join_path";
+  if (q->reserved != 0) return "reserved must be 0";
+  return nullptr;
+}
+
+Layout make_layout(const gnnd_params* q, bool with_aside) {
+  Layout L;
+  const size_t n = (size_t)q->n, k = (size_t)q->k, p = (size_t)q->p;
+  size_t o = 0;
+  auto take = [&](size_t bytes) {
+    size_t at = o;
+    o = align_up(o + bytes);
+    return at;
+  };
+  L.off_G = take(n * k * 8);
+  L.off_kth = take(n * 4);
+  L.off_snew = take(n * 2 * p * 4);
+  L.off_sold = take(n * 2 * p * 4);
+  L.off_cnew = take(n * 4);
+  L.off_cold = take(n * 4);
+  L.off_rcn = take(n * 4);
+  L.off_rco = take(n * 4);
+  L.off_ron = take((n + 1) * 8);
+  L.off_roo = take((n + 1) * 8);
+  L.off_csn = take(n * p * 4);
+  L.off_cso = take(n * p * 4);
+  L.off_pcnt = take(n * 4);
+  L.off_poff = take((n + 1) * 8);
+  L.off_pdest = take(n * 6 * p * 4);
+  L.off_pkey = take(n * 6 * p * 8);
+  L.off_bins = take(n * 6 * p * 8);
+  L.off_scan = take(scan_tmp_elems((int64_t)n) * 8);
+  L.off_cnt = take((size_t)kStripes * C_SLOTS * 8);
+  L.off_snap = take((size_t)kStripes * C_SLOTS * 8);
+  L.off_aside = take(with_aside ? n * (k / 2) * 8 : 0);
+  L.total = o;
+  return L;
+}
+
+}  // namespace
+
+struct gnnd_ctx {
+  gnnd_params prm;
+  Shape sh;
+  DevState ds;
+  hipStream_t stream;
+  int32_t iter;       // iterations completed
+  int stage;          // 0 = ready for sample, 1 = sampled, 2 = joined
+  bool has_graph;
+  bool merge_mode;
+  hipEvent_t ev[4];
+  bool have_events;
+  uint64_t* snap;  // device copy of the counters taken when the iteration began
+  std::string err;
+};
+
+namespace {
+
+int fail(gnnd_ctx* c, int code, const std::string& msg) {
+  if (c) c->err = msg;
+  g_last_error = msg;
+  return code;
+}
+int hip_fail(gnnd_ctx* c, hipError_t e, const char* what) {
+  return fail(c, GNND_EHIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+void bind(gnnd_ctx* c, const Layout& L) {
+  char* w = (char*)c->prm.workspace_dev;
+  DevState& d = c->ds;
+  d.G = (uint64_t*)(w + L.off_G);
+  d.kth = (uint32_t*)(w + L.off_kth);
+  d.snew = (int32_t*)(w + L.off_snew);
+  d.sold = (int32_t*)(w + L.off_sold);
+  d.cnew = (int32_t*)(w + L.off_cnew);
+  d.cold = (int32_t*)(w + L.off_cold);
+  d.rcnt_new = (uint32_t*)(w + L.off_rcn);
+  d.rcnt_old = (uint32_t*)(w + L.off_rco);
+  d.roff_new = (uint64_t*)(w + L.off_ron);
+  d.roff_old = (uint64_t*)(w + L.off_roo);
+  d.csr_new = (int32_t*)(w + L.off_csn);
+  d.csr_old = (int32_t*)(w + L.off_cso);
+  d.pcnt = (uint32_t*)(w + L.off_pcnt);
+  d.poff = (uint64_t*)(w + L.off_poff);
+  d.prop_dest = (int32_t*)(w + L.off_pdest);
+  d.prop_key = (uint64_t*)(w + L.off_pkey);
+  d.bins = (uint64_t*)(w + L.off_bins);
+  d.scan_tmp = (uint64_t*)(w + L.off_scan);
+  d.counters = (uint64_t*)(w + L.off_cnt);
+  d.aside = (uint64_t*)(w + L.off_aside);
+  c->snap = (uint64_t*)(w + L.off_snap);
+}
+
+// Shared by gnnd_create and gnnd_merge.
+int create_impl(gnnd_ctx** out, const gnnd_params* prm, const void* vec_a, const void* vec_b,
+                int64_t split, bool merge_mode) {
+  if (!out) return fail(nullptr, GNND_EINVAL, "out is NULL");
+  *out = nullptr;
+  if (const char* m = check_params(prm)) return fail(nullptr, GNND_EINVAL, m);
+  if (!vec_a) return fail(nullptr, GNND_EINVAL, "vectors pointer is NULL");
+  if (((uintptr_t)vec_a & 15) || ((uintptr_t)vec_b & 15))
+    return fail(nullptr, GNND_EINVAL, "vectors must be 16-byte aligned");
+  if (!prm->workspace_dev) return fail(nullptr, GNND_EINVAL, "workspace is NULL");
+  if ((uintptr_t)prm->workspace_dev & 255)
+    return fail(nullptr, GNND_EINVAL, "workspace must be 256-byte aligned");
+  Layout L = make_layout(prm, merge_mode);
+  if (prm->workspace_bytes < L.total) {
+    char buf[128];
+    snprintf(buf, sizeof buf, "workspace too small: %zu bytes given, %zu needed",
+             prm->workspace_bytes, L.total);
+    return fail(nullptr, GNND_ENOSPC, buf);
+  }
+  gnnd_ctx* c = new (std::nothrow) gnnd_ctx();
+  if (!c) return fail(nullptr, GNND_EINVAL, "out of host memory");
+  c->prm = *prm;
+  c->stream = (hipStream_t)prm->stream;
+  c->sh = Shape{prm->n, prm->d, prm->k, prm->p, prm->metric, split, vec_a, vec_b};
+  c->iter = 0;
+  c->stage = 0;
+  c->has_graph = false;
+  c->merge_mode = merge_mode;
+  c->have_events = false;
+  bind(c, L);
+  // counters that must start at zero (they return to zero after every iteration)
+  hipError_t e = launch_zero_u32(c->ds.rcnt_new, (size_t)prm->n, c->stream);
+  if (e == hipSuccess) e = launch_zero_u32(c->ds.rcnt_old, (size_t)prm->n, c->stream);
+  if (e == hipSuccess) e = launch_zero_u32(c->ds.pcnt, (size_t)prm->n, c->stream);
+  if (e == hipSuccess)
+    e = launch_zero_u32((uint32_t*)c->ds.counters, (size_t)kStripes * C_SLOTS * 2, c->stream);
+  if (e != hipSuccess) {
+    int rc = hip_fail(nullptr, e, "clearing workspace counters");
+    delete c;
+    return rc;
+  }
+  *out = c;
+  return GNND_OK;
+}
+
+int ensure_events(gnnd_ctx* c) {
+  if (c->have_events) return GNND_OK;
+  for (int i = 0; i < 4; ++i) {
+    hipError_t e = hipEventCreate(&c->ev[i]);
+    if (e != hipSuccess) return hip_fail(c, e, "hipEventCreate");
+  }
+  c->have_events = true;
+  return GNND_OK;
+}
+
+int read_stats(gnnd_ctx* c, gnnd_iter_stats* out) {
+  constexpr int N = kStripes * C_SLOTS;
+  uint64_t host[2 * N];
+  hipError_t e = hipMemcpyAsync(host, c->ds.counters, N * 8, hipMemcpyDeviceToHost, c->stream);
+  if (e == hipSuccess)
+    e = hipMemcpyAsync(host + N, c->snap, N * 8, hipMemcpyDeviceToHost, c->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+  if (e != hipSuccess) return hip_fail(c, e, "reading counters");
+  uint64_t tot[C_SLOTS] = {0};
+  for (int s = 0; s < kStripes; ++s)
+    for (int j = 0; j < C_SLOTS; ++j) tot[j] += host[s * C_SLOTS + j] - host[N + s * C_SLOTS + j];
+  memset(out, 0, sizeof *out);
+  out->iter = c->iter;
+  out->inserts = tot[C_INSERTS];
+  out->dist_evals = tot[C_EVALS];
+  out->sum_new = tot[C_SUMNEW];
+  out->sum_old = tot[C_SUMOLD];
+  out->proposals = tot[C_PROPS];
+  return GNND_OK;
+}
+
+int step_sample(gnnd_ctx* c) {
+  if (!c->has_graph) return fail(c, GNND_ESTATE, "no graph: call gnnd_init_random or gnnd_set_graph first");
+  if (c->stage != 0) return fail(c, GNND_ESTATE, "stage order is sample, join, update");
+  // the counters only grow: keep their values from before this iteration
+  hipError_t e = hipMemcpyAsync(c->snap, c->ds.counters, (size_t)kStripes * C_SLOTS * 8,
+                                hipMemcpyDeviceToDevice, c->stream);
+  if (e != hipSuccess) return hip_fail(c, e, "counter snapshot");
+  e = launch_sample(c->sh, c->ds, c->prm.seed, (uint32_t)(c->iter + 1), c->stream);
+  if (e != hipSuccess) return hip_fail(c, e, "sampling kernels");
+  c->stage = 1;
+  return GNND_OK;
+}
+int step_join(gnnd_ctx* c) {
+  if (c->stage != 1) return fail(c, GNND_ESTATE, "stage order is sample, join, update");
+  hipError_t e = launch_join(c->sh, c->ds, c->prm.join_path, c->merge_mode, c->stream);
+  if (e != hipSuccess) return hip_fail(c, e, "join kernel");
+  c->stage = 2;
+  return GNND_OK;
+}
+int step_update(gnnd_ctx* c) {
+  if (c->stage != 2) return fail(c, GNND_ESTATE, "stage order is sample, join, update");
+  hipError_t e = launch_update(c->sh, c->ds, c->stream);
+  if (e != hipSuccess) return hip_fail(c, e, "update kernels");
+  c->stage = 0;
+  c->iter += 1;
+  return GNND_OK;
+}
+
+int iterate_impl(gnnd_ctx* c, gnnd_iter_stats* out) {
+  int rc;
+  if (out) {
+    if ((rc = ensure_events(c)) != GNND_OK) return rc;
+    (void)hipEventRecord(c->ev[0], c->stream);
+  }
+  if ((rc = step_sample(c)) != GNND_OK) return rc;
+  if (out) (void)hipEventRecord(c->ev[1], c->stream);
+  if ((rc = step_join(c)) != GNND_OK) return rc;
+  if (out) (void)hipEventRecord(c->ev[2], c->stream);
+  if ((rc = step_update(c)) != GNND_OK) return rc;
+  if (out) {
+    (void)hipEventRecord(c->ev[3], c->stream);
+    if ((rc = read_stats(c, out)) != GNND_OK) return rc;
+    (void)hipEventElapsedTime(&out->ms_sample, c->ev[0], c->ev[1]);
+    (void)hipEventElapsedTime(&out->ms_join, c->ev[1], c->ev[2]);
+    (void)hipEventElapsedTime(&out->ms_update, c->ev[2], c->ev[3]);
+  }
+  return GNND_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t gnnd_workspace_bytes(const gnnd_params* prm) {
+  if (check_params(prm)) return 0;
+  return make_layout(prm, true).total;
+}
+
+int gnnd_create(gnnd_ctx** out, const gnnd_params* prm, const void* vectors_dev) {
+  return create_impl(out, prm, vectors_dev, nullptr, prm ? prm->n : 0, false);
+}
+
+void gnnd_destroy(gnnd_ctx* c) {
+  if (!c) return;
+  if (c->have_events)
+    for (int i = 0; i < 4; ++i) (void)hipEventDestroy(c->ev[i]);
+  delete c;
+}
+
+const char* gnnd_last_error(const gnnd_ctx* c) { return c ? c->err.c_str() : g_last_error.c_str(); }
+
+int gnnd_init_random(gnnd_ctx* c) {
+  if (!c) return fail(nullptr, GNND_EINVAL, "ctx is NULL");
+  if (c->merge_mode) return fail(c, GNND_ESTATE, "context belongs to a merge");
+  hipError_t e = launch_init_random(c->sh, c->ds, c->prm.seed, c->stream);
+  if (e != hipSuccess) return hip_fail(c, e, "init kernel");
+  c->has_graph = true;
+  c->iter = 0;
+  c->stage = 0;
+  return GNND_OK;
+}
+
+int gnnd_iterate(gnnd_ctx* c, gnnd_iter_stats* out) {
+  if (!c) return fail(nullptr, GNND_EINVAL, "ctx is NULL");
+  return iterate_impl(c, out);
+}
+
+int gnnd_step_sample(gnnd_ctx* c) {
+  if (!c) return fail(nullptr, GNND_EINVAL, "ctx is NULL");
+  return step_sample(c);
+}
+int gnnd_step_join(gnnd_ctx* c) {
+  if (!c) return fail(nullptr, GNND_EINVAL, "ctx is NULL");
+  return step_join(c);
+}
+int gnnd_step_update(gnnd_ctx* c, gnnd_iter_stats* out) {
+  if (!c) return fail(nullptr, GNND_EINVAL, "ctx is NULL");
+  int rc = step_update(c);
+  if (rc != GNND_OK) return rc;
+  return out ? read_stats(c, out) : GNND_OK;
+}
+
+int gnnd_build(gnnd_ctx* c, int32_t max_iters, float delta, gnnd_iter_stats* last) {
+  if (!c) return fail(nullptr, GNND_EINVAL, "ctx is NULL");
+  if (max_iters < 0) return fail(c, GNND_EINVAL, "max_iters must be >= 0");
+  if (!(delta >= 0.f)) return fail(c, GNND_EINVAL, "delta must be >= 0");
+  int rc = gnnd_init_random(c);
+  if (rc != GNND_OK) return rc;
+  gnnd_iter_stats st;
+  memset(&st, 0, sizeof st);
+  for (int32_t t = 0; t < max_iters; ++t) {
+    const bool want = delta > 0.f || (last && t == max_iters - 1);
+    rc = iterate_impl(c, want ? &st : nullptr);
+    if (rc != GNND_OK) return rc;
+    if (delta > 0.f && (double)st.inserts < (double)delta * (double)c->prm.n * c->prm.k) break;
+  }
+  if (last) *last = st;
+  return GNND_OK;
+}
+
+int gnnd_get_graph(gnnd_ctx* c, int32_t* ids, void* dist, uint8_t* isnew) {
+  if (!c) return fail(nullptr, GNND_EINVAL, "ctx is NULL");
+  if (!c->has_graph) return fail(c, GNND_ESTATE, "no graph yet");
+  hipError_t e = launch_get_graph(c->sh, c->ds, ids, dist, isnew, c->stream);
+  return e == hipSuccess ? GNND_OK : hip_fail(c, e, "get_graph kernel");
+}
+
+int gnnd_set_graph(gnnd_ctx* c, const int32_t* ids, const void* dist, const uint8_t* isnew,
+                   int32_t iter) {
+  if (!c) return fail(nullptr, GNND_EINVAL, "ctx is NULL");
+  if (!ids || !dist) return fail(c, GNND_EINVAL, "ids and dist are required");
+  if (iter < 0) return fail(c, GNND_EINVAL, "iter must be >= 0");
+  hipError_t e = launch_set_graph(c->sh, c->ds, ids, dist, isnew, c->stream);
+  if (e != hipSuccess) return hip_fail(c, e, "set_graph kernel");
+  c->has_graph = true;
+  c->iter = iter;
+  c->stage = 0;
+  return GNND_OK;
+}
+
+int gnnd_get_samples(gnnd_ctx* c, int32_t* snew, int32_t* cnew, int32_t* sold, int32_t* cold) {
+  if (!c) return fail(nullptr, GNND_EINVAL, "ctx is NULL");
+  if (c->stage == 0 && c->iter == 0) return fail(c, GNND_ESTATE, "nothing sampled yet");
+  const size_t n = (size_t)c->prm.n, L = 2 * (size_t)c->prm.p;
+  hipError_t e = hipSuccess;
+  if (snew) e = hipMemcpyAsync(snew, c->ds.snew, n * L * 4, hipMemcpyDeviceToDevice, c->stream);
+  if (e == hipSuccess && sold)
+    e = hipMemcpyAsync(sold, c->ds.sold, n * L * 4, hipMemcpyDeviceToDevice, c->stream);
+  if (e == hipSuccess && cnew)
+    e = hipMemcpyAsync(cnew, c->ds.cnew, n * 4, hipMemcpyDeviceToDevice, c->stream);
+  if (e == hipSuccess && cold)
+    e = hipMemcpyAsync(cold, c->ds.cold, n * 4, hipMemcpyDeviceToDevice, c->stream);
+  return e == hipSuccess ? GNND_OK : hip_fail(c, e, "copying sample lists");
+}
+
+int gnnd_get_proposals(gnnd_ctx* c, int32_t* u, int32_t* v, void* dist) {
+  if (!c) return fail(nullptr, GNND_EINVAL, "ctx is NULL");
+  if (!u || !v || !dist) return fail(c, GNND_EINVAL, "u, v and dist are required");
+  if (c->stage != 2) return fail(c, GNND_ESTATE, "proposals exist between join and update only");
+  hipError_t e = launch_get_proposals(c->sh, c->ds, u, v, dist, c->stream);
+  return e == hipSuccess ? GNND_OK : hip_fail(c, e, "get_proposals kernel");
+}
+
+int gnnd_merge(const gnnd_params* prm, const void* vec1, int64_t n1, const void* vec2, int64_t n2,
+               const int32_t* ids1, const void* dist1, const int32_t* ids2, const void* dist2,
+               int32_t iters, int32_t* ids_out, void* dist_out, gnnd_iter_stats* stats) {
+  if (const char* m = check_params(prm)) return fail(nullptr, GNND_EINVAL, m);
+  if (n1 <= 0 || n2 <= 0 || n1 + n2 != prm->n)
+    return fail(nullptr, GNND_EINVAL, "n1 + n2 must equal params.n, both positive");
+  if (n1 <= prm->k || n2 <= prm->k)
+    return fail(nullptr, GNND_EINVAL, "each input graph needs more than k nodes");
+  if (iters < 0) return fail(nullptr, GNND_EINVAL, "iters must be >= 0");
+  if (!vec2 || !ids1 || !dist1 || !ids2 || !dist2 || !ids_out || !dist_out)
+    return fail(nullptr, GNND_EINVAL, "NULL pointer argument");
+  gnnd_ctx* c = nullptr;
+  int rc = create_impl(&c, prm, vec1, vec2, n1, true);
+  if (rc != GNND_OK) return rc;
+  hipError_t e = launch_merge_init(c->sh, c->ds, prm->seed, n1, ids1, dist1, ids2, dist2, c->stream);
+  if (e != hipSuccess) {
+    rc = hip_fail(nullptr, e, "merge init kernel");
+  } else {
+    c->has_graph = true;
+    for (int32_t t = 0; t < iters && rc == GNND_OK; ++t)
+      rc = iterate_impl(c, stats ? stats + t : nullptr);
+    if (rc == GNND_OK) {
+      e = launch_merge_final(c->sh, c->ds, ids_out, dist_out, c->stream);
+      if (e != hipSuccess) rc = hip_fail(nullptr, e, "merge final kernel");
+    } else {
+      g_last_error = c->err;
+    }
+  }
+  gnnd_destroy(c);
+  return rc;
+}
+
+int gnnd_exact_knn(const void* vec, int64_t n, int32_t d, int32_t metric, const int32_t* queries,
+                   int64_t nq, int32_t K, int32_t* ids_out, void* dist_out, void* stream) {
+  if (!vec || !queries || !ids_out || !dist_out)
+    return fail(nullptr, GNND_EINVAL, "NULL pointer argument");
+  if (metric < GNND_L2SQ_F32 || metric > GNND_L2SQ_U8) return fail(nullptr, GNND_EINVAL, "unknown metric");
+  if (n < 2 || n > ((int64_t)1 << 30) || d < 1 || nq < 0 || K < 1 || K > 64)
+    return fail(nullptr, GNND_EINVAL, "need 2 <= n <= 2^30, d >= 1, nq >= 0, 1 <= K <= 64");
+  if ((uintptr_t)vec & 15) return fail(nullptr, GNND_EINVAL, "vectors must be 16-byte aligned");
+  hipError_t e = launch_exact_knn(vec, n, d, metric, queries, nq, K, ids_out, dist_out,
+                                  (hipStream_t)stream);
+  return e == hipSuccess ? GNND_OK : hip_fail(nullptr, e, "exact_knn kernel");
+}
+
+}  // extern "C"

@@ -1,0 +1,628 @@
+// Graph-side kernels of GNND for gfx950: random initial lists, sampling with
+// reverse neighbours, the list update, and the copy-in / copy-out helpers.
+// One 64-lane wavefront owns one list: a list entry, a sample or a proposal
+// lives in one lane, and sorting / merging / compaction are lane networks.
+#include "device_utils.hpp"
+#include "kernels.hpp"
+
+namespace gnnd {
+
+constexpr int kBlock = 256;
+constexpr int kWavesPerBlock = kBlock / kWave;
+
+__device__ inline int64_t wave_global_index() {
+  return (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+}
+static inline unsigned blocks_for_waves(int64_t waves) {
+  return (unsigned)((waves + kWavesPerBlock - 1) / kWavesPerBlock);
+}
+
+__device__ inline void counter_add(uint64_t* counters, int which, int64_t stripe_hint,
+                                   uint64_t v) {
+  atomicAdd(reinterpret_cast<unsigned long long*>(
+                counters + (stripe_hint & (kStripes - 1)) * C_SLOTS + which),
+            (unsigned long long)v);
+}
+
+// ---------------------------------------------------------------------------
+// Alg. 1, first loop: k distinct random neighbours per node, distances, sorted
+// ascending by (distance, id), flagged NEW.
+template <int METRIC>
+__global__ __launch_bounds__(kBlock) void k_init_random(VecSrc vs, int64_t n, int k,
+                                                        uint64_t base_hash, uint64_t* G,
+                                                        uint32_t* kth) {
+  using D = DistOf<METRIC>;
+  using T = typename D::elem;
+  const int64_t s = wave_global_index();
+  if (s >= n) return;
+  const int lane = lane_id();
+  uint32_t id = draw_distinct(base_hash, (uint32_t)s, k, (uint32_t)n, 0u, (uint32_t)s, lane);
+  uint64_t e = kKeyMax;
+  if (lane < k) {
+    uint32_t code = D::eval(vs.row<T>((uint32_t)s), vs.row<T>(id), vs.d);
+    e = make_entry(code, id, 1u);
+  }
+  e = wave_sort(e, lane);
+  if (lane < k) G[s * k + lane] = e;
+  if (lane == k - 1) kth[s] = entry_code(e);
+}
+
+// ---------------------------------------------------------------------------
+// Sec. 4.1, forward part: the first p NEW and the first p OLD entries of each
+// list go to the front of the node's sample rows; the sampled NEW entries are
+// flagged OLD; every sampled v counts one reverse candidate for v.
+__global__ __launch_bounds__(kBlock) void k_sample_fwd(int64_t n, int k, int p, uint64_t* G,
+                                                       int32_t* snew, int32_t* sold,
+                                                       int32_t* cnew, int32_t* cold,
+                                                       uint32_t* rcnt_new, uint32_t* rcnt_old) {
+  const int64_t s = wave_global_index();
+  if (s >= n) return;
+  const int lane = lane_id();
+  const bool valid = lane < k;
+  uint64_t e = valid ? G[s * k + lane] : 0ull;
+  const bool isnew = valid && (e & 1ull);
+  const bool isold = valid && !(e & 1ull);
+  const uint64_t mn = __ballot(isnew), mo = __ballot(isold);
+  const int rn = __popcll(mn & lanes_below(lane)), ro = __popcll(mo & lanes_below(lane));
+  const uint32_t id = entry_id(e);
+  const int L = 2 * p;
+  if (isnew && rn < p) {
+    snew[s * L + rn] = (int32_t)id;
+    G[s * k + lane] = e & ~1ull;
+    atomicAdd(&rcnt_new[id], 1u);
+  }
+  if (isold && ro < p) {
+    sold[s * L + ro] = (int32_t)id;
+    atomicAdd(&rcnt_old[id], 1u);
+  }
+  if (lane == 0) {
+    int cn = __popcll(mn), co = __popcll(mo);
+    cnew[s] = cn < p ? cn : p;
+    cold[s] = co < p ? co : p;
+  }
+}
+
+// Reverse candidates grouped by target: s goes into the segment of every
+// forward sample v of s.  Counting down the candidate counters hands out the
+// slots and leaves the counters at zero for the next iteration.
+__global__ __launch_bounds__(kBlock) void k_rev_fill(int64_t n, int p, const int32_t* snew,
+                                                     const int32_t* sold, const int32_t* cnew,
+                                                     const int32_t* cold, uint32_t* rcnt_new,
+                                                     uint32_t* rcnt_old,
+                                                     const uint64_t* roff_new,
+                                                     const uint64_t* roff_old, int32_t* csr_new,
+                                                     int32_t* csr_old) {
+  const int64_t s = wave_global_index();
+  if (s >= n) return;
+  const int lane = lane_id();
+  const int L = 2 * p;
+  if (lane < cnew[s]) {
+    int32_t v = snew[s * L + lane];
+    uint32_t pos = atomicSub(&rcnt_new[v], 1u) - 1u;
+    csr_new[roff_new[v] + pos] = (int32_t)s;
+  }
+  if (lane < cold[s]) {
+    int32_t v = sold[s * L + lane];
+    uint32_t pos = atomicSub(&rcnt_old[v], 1u) - 1u;
+    csr_old[roff_old[v] + pos] = (int32_t)s;
+  }
+}
+
+// Sec. 4.1, reverse part and duplicate removal.  The list of v holds its
+// forward samples; of its reverse candidates the 2p - |forward| with the
+// smallest hash(seed, kind, v, s, iter) (ties by s) are appended - the paper's
+// "append until the list is full" with the winners chosen by a hash instead of
+// by thread timing.  The list is then sorted by id and duplicates dropped.
+__global__ __launch_bounds__(kBlock) void k_rev_select(int64_t n, int p, uint64_t base_new,
+                                                       uint64_t base_old, uint32_t iter,
+                                                       int32_t* snew, int32_t* sold,
+                                                       int32_t* cnew, int32_t* cold,
+                                                       const uint64_t* roff_new,
+                                                       const uint64_t* roff_old,
+                                                       const int32_t* csr_new,
+                                                       const int32_t* csr_old,
+                                                       uint64_t* counters) {
+  const int64_t v = wave_global_index();
+  if (v >= n) return;
+  const int lane = lane_id();
+  const int kind = blockIdx.y;
+  int32_t* list = (kind ? sold : snew) + v * 2 * p;
+  int32_t* cnt = kind ? cold : cnew;
+  const uint64_t* roff = kind ? roff_old : roff_new;
+  const int32_t* csr = kind ? csr_old : csr_new;
+  const uint64_t base = kind ? base_old : base_new;
+
+  const int nf = cnt[v];
+  const uint32_t fwd = lane < nf ? (uint32_t)list[lane] : kIdMax;
+  const uint64_t beg = roff[v];
+  const uint64_t deg = roff[v + 1] - beg;
+  const int room = 2 * p - nf;
+  uint32_t rev = kIdMax;
+  int m;
+  if (deg <= (uint64_t)room) {
+    m = (int)deg;
+    if (lane < m) rev = (uint32_t)csr[beg + lane];
+  } else {
+    m = room;
+    uint64_t best = kKeyMax;
+    for (uint64_t c = 0; c < deg; c += kWave) {
+      uint64_t key = kKeyMax;
+      if (c + lane < deg) {
+        uint32_t s = (uint32_t)csr[beg + c + lane];
+        key = ((hash3(base, (uint32_t)v, s, iter) >> 32) << 32) | (uint64_t)s;
+      }
+      key = wave_sort(key, lane);
+      best = wave_merge_smallest(best, key, lane);
+    }
+    if (lane < room) rev = (uint32_t)best;
+  }
+  const int src = lane - nf;
+  const uint32_t r = __shfl(rev, src < 0 ? 0 : src, kWave);
+  uint32_t val = lane < nf ? fwd : (src < m ? r : kIdMax);
+  val = wave_sort(val, lane);
+  const uint32_t prev = __shfl_up(val, 1, kWave);
+  const bool keep = val != kIdMax && (lane == 0 || val != prev);
+  const uint64_t mask = __ballot(keep);
+  const int count = __popcll(mask);
+  if (keep) list[__popcll(mask & lanes_below(lane))] = (int32_t)val;
+  if (lane >= count && lane < 2 * p) list[lane] = -1;
+  if (lane == 0) {
+    cnt[v] = count;
+    counter_add(counters, kind ? C_SUMOLD : C_SUMNEW, v, (uint64_t)count);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Proposals grouped by destination list (same count-down slot scheme).
+__global__ __launch_bounds__(kBlock) void k_prop_fill(int64_t slots, const int32_t* prop_dest,
+                                                      const uint64_t* prop_key, uint32_t* pcnt,
+                                                      const uint64_t* poff, uint64_t* bins) {
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i >= slots) return;
+  const int32_t u = prop_dest[i];
+  if (u < 0) return;
+  uint32_t pos = atomicSub(&pcnt[u], 1u) - 1u;
+  bins[poff[u] + pos] = prop_key[i];
+}
+
+// Drop from `pk` (one candidate per lane, kKeyMax = none) what cannot enter the
+// ascending list `row` of k entries: not closer than its last entry, already
+// in it, or a repeat of another candidate.  Returns the survivors ascending.
+__device__ inline uint64_t filter_candidates(uint64_t pk, uint64_t row, int k, int lane,
+                                             bool& any) {
+  const uint64_t last = readlane64(row, k - 1);
+  if (pk != kKeyMax && entry_key(pk) >= entry_key(last)) pk = kKeyMax;
+  any = __ballot(pk != kKeyMax) != 0ull;
+  if (!any) return pk;
+  bool dup = false;
+  for (int i = 0; i < k; ++i) dup |= (entry_key(pk) == entry_key(readlane64(row, i)));
+  if (dup) pk = kKeyMax;
+  any = __ballot(pk != kKeyMax) != 0ull;
+  if (!any) return pk;
+  pk = wave_sort(pk, lane);
+  const uint64_t prev = __shfl_up(pk, 1, kWave);
+  const bool rep = lane > 0 && pk != kKeyMax && entry_key(pk) == entry_key(prev);
+  if (__ballot(rep) != 0ull) pk = wave_compact(pk, !rep, kKeyMax, lane);
+  return pk;
+}
+
+// Sec. 4.3 list insertion for all proposals of one destination at once: the
+// list becomes the best k, by (distance, id), of its entries and the proposed
+// objects, one entry per id - what inserting them one by one under a lock
+// gives in any order.  Admitted entries are flagged NEW.
+__global__ __launch_bounds__(kBlock) void k_update(int64_t n, int k, uint64_t* G, uint32_t* kth,
+                                                   const uint64_t* poff, const uint64_t* bins,
+                                                   uint64_t* counters) {
+  const int64_t u = wave_global_index();
+  if (u >= n) return;
+  const uint64_t beg = poff[u];
+  const uint64_t cnt = poff[u + 1] - beg;
+  if (cnt == 0) return;
+  const int lane = lane_id();
+  uint64_t row = lane < k ? G[u * k + lane] : kKeyMax;
+  bool changed = false;
+  for (uint64_t c = 0; c < cnt; c += kWave) {
+    uint64_t pk = (c + lane < cnt) ? bins[beg + c + lane] : kKeyMax;
+    bool any;
+    pk = filter_candidates(pk, row, k, lane, any);
+    if (!any) continue;
+    row = wave_merge_smallest(row, pk, lane);
+    if (lane >= k) row = kKeyMax;
+    changed = true;
+  }
+  if (!changed) return;
+  const uint64_t admitted = __ballot(lane < k && (row & 2ull));
+  if (lane < k) G[u * k + lane] = row & ~2ull;
+  if (lane == k - 1) kth[u] = entry_code(row);
+  if (lane == 0) counter_add(counters, C_INSERTS, u, (uint64_t)__popcll(admitted));
+}
+
+// ---------------------------------------------------------------------------
+template <bool FLOAT>
+__global__ __launch_bounds__(kBlock) void k_get_graph(int64_t total, const uint64_t* G,
+                                                      int32_t* ids, void* dist,
+                                                      uint8_t* isnew) {
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i >= total) return;
+  const uint64_t e = G[i];
+  if (ids) ids[i] = (int32_t)entry_id(e);
+  if (isnew) isnew[i] = (uint8_t)(e & 1ull);
+  if (dist) {
+    if (FLOAT) reinterpret_cast<float*>(dist)[i] = unord_f32(entry_code(e));
+    else reinterpret_cast<int32_t*>(dist)[i] = unord_i32(entry_code(e));
+  }
+}
+
+template <bool FLOAT>
+__global__ __launch_bounds__(kBlock) void k_set_graph(int64_t total, int k, uint64_t* G,
+                                                      uint32_t* kth, const int32_t* ids,
+                                                      const void* dist, const uint8_t* isnew) {
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i >= total) return;
+  uint32_t code = FLOAT ? ord_f32(reinterpret_cast<const float*>(dist)[i])
+                        : ord_i32(reinterpret_cast<const int32_t*>(dist)[i]);
+  G[i] = make_entry(code, (uint32_t)ids[i], isnew ? (uint32_t)(isnew[i] & 1) : 0u);
+  if ((i % k) == k - 1) kth[i / k] = code;
+}
+
+template <bool FLOAT>
+__global__ __launch_bounds__(kBlock) void k_get_proposals(int64_t slots,
+                                                          const int32_t* prop_dest,
+                                                          const uint64_t* prop_key, int32_t* u,
+                                                          int32_t* v, void* dist) {
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i >= slots) return;
+  const int32_t dest = prop_dest[i];
+  const uint64_t e = prop_key[i];
+  u[i] = dest;
+  v[i] = dest < 0 ? -1 : (int32_t)entry_id(e);
+  if (FLOAT) reinterpret_cast<float*>(dist)[i] = dest < 0 ? 0.f : unord_f32(entry_code(e));
+  else reinterpret_cast<int32_t*>(dist)[i] = dest < 0 ? 0 : unord_i32(entry_code(e));
+}
+
+__global__ __launch_bounds__(kBlock) void k_zero_u32(uint32_t* p, size_t count) {
+  const size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i < count) p[i] = 0u;
+}
+
+// ---------------------------------------------------------------------------
+// GGM, Alg. 3 "Divide" + "Append": keep the first ceil(k/2) entries (OLD), set
+// the rest aside, refill with floor(k/2) random objects of the other set (NEW)
+// and restore the (distance, id) order.
+template <int METRIC>
+__global__ __launch_bounds__(kBlock) void k_merge_init(VecSrc vs, int64_t n, int64_t n1, int k,
+                                                       uint64_t base_hash, const int32_t* ids1,
+                                                       const void* dist1, const int32_t* ids2,
+                                                       const void* dist2, uint64_t* G,
+                                                       uint32_t* kth, uint64_t* aside) {
+  using D = DistOf<METRIC>;
+  using T = typename D::elem;
+  const int64_t s = wave_global_index();
+  if (s >= n) return;
+  const int lane = lane_id();
+  const bool first = s < n1;
+  const int64_t loc = first ? s : s - n1;
+  const int32_t* sid = (first ? ids1 : ids2) + loc * k;
+  const void* sdist = first ? dist1 : dist2;
+  const uint32_t shift = first ? 0u : (uint32_t)n1;
+  const int keep = (k + 1) / 2, fill = k / 2;
+  uint32_t id_in = 0, code_in = 0;
+  if (lane < k) {
+    id_in = (uint32_t)sid[lane] + shift;
+    code_in = METRIC == kL2U8
+                  ? ord_i32(reinterpret_cast<const int32_t*>(sdist)[loc * k + lane])
+                  : ord_f32(reinterpret_cast<const float*>(sdist)[loc * k + lane]);
+  }
+  if (lane >= keep && lane < k) aside[s * fill + (lane - keep)] = make_entry(code_in, id_in, 0u);
+  const uint32_t draw = draw_distinct(base_hash, (uint32_t)s, fill,
+                                      (uint32_t)(first ? n - n1 : n1), first ? (uint32_t)n1 : 0u,
+                                      0xffffffffu, lane);
+  const int src = lane - keep;
+  const uint32_t did = __shfl(draw, src < 0 ? 0 : src, kWave);
+  uint64_t e = kKeyMax;
+  if (lane < keep) {
+    e = make_entry(code_in, id_in, 0u);
+  } else if (lane < k) {
+    uint32_t code = D::eval(vs.row<T>((uint32_t)s), vs.row<T>(did), vs.d);
+    e = make_entry(code, did, 1u);
+  }
+  e = wave_sort(e, lane);
+  if (lane < k) G[s * k + lane] = e;
+  if (lane == k - 1) kth[s] = entry_code(e);
+}
+
+// GGM, Alg. 3 "Merge and Sort": best k of the refined list and the set-aside half.
+template <bool FLOAT>
+__global__ __launch_bounds__(kBlock) void k_merge_final(int64_t n, int k, const uint64_t* G,
+                                                        const uint64_t* aside, int32_t* ids_out,
+                                                        void* dist_out) {
+  const int64_t s = wave_global_index();
+  if (s >= n) return;
+  const int lane = lane_id();
+  const int fill = k / 2;
+  uint64_t row = lane < k ? G[s * k + lane] : kKeyMax;
+  uint64_t pk = lane < fill ? aside[s * fill + lane] : kKeyMax;
+  // the set-aside entries may tie with the list's last entry: compare on the
+  // full (distance, id) key, which filter_candidates does
+  bool any;
+  pk = filter_candidates(pk, row, k, lane, any);
+  if (any) {
+    row = wave_merge_smallest(row, pk, lane);
+  }
+  if (lane < k) {
+    ids_out[s * k + lane] = (int32_t)entry_id(row);
+    if (FLOAT) reinterpret_cast<float*>(dist_out)[s * k + lane] = unord_f32(entry_code(row));
+    else reinterpret_cast<int32_t*>(dist_out)[s * k + lane] = unord_i32(entry_code(row));
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Exhaustive exact K-NN of a query node (ground truth for Recall@K): each wave
+// scans a quarter of the data set, one candidate per lane, and keeps the best
+// 64 in its lanes; the four lists are merged at the end.
+template <int METRIC>
+__global__ __launch_bounds__(kBlock) void k_exact_knn(const void* vec, int64_t n, int d,
+                                                      const int32_t* queries, int K,
+                                                      int32_t* ids_out, void* dist_out) {
+  using D = DistOf<METRIC>;
+  using T = typename D::elem;
+  __shared__ uint64_t part[kWavesPerBlock][kWave];
+  const int lane = lane_id();
+  const int wave = threadIdx.x >> 6;
+  const int64_t q = blockIdx.x;
+  const uint32_t s = (uint32_t)queries[q];
+  const T* base = reinterpret_cast<const T*>(vec);
+  const T* qrow = base + (int64_t)s * d;
+  uint64_t best = kKeyMax;  // ascending in lanes; lanes >= K stay unused
+  for (int64_t c0 = (int64_t)wave * kWave; c0 < n; c0 += kBlock) {
+    const int64_t c = c0 + lane;
+    uint64_t key = kKeyMax;
+    if (c < n && c != (int64_t)s) {
+      uint32_t code = D::eval(qrow, base + c * d, d);
+      key = ((uint64_t)code << 32) | (uint64_t)c;
+    }
+    const uint64_t last = readlane64(best, K - 1);
+    if (key >= last) key = kKeyMax;
+    if (__ballot(key != kKeyMax) == 0ull) continue;
+    key = wave_sort(key, lane);
+    best = wave_merge_smallest(best, key, lane);
+    if (lane >= K) best = kKeyMax;
+  }
+  part[wave][lane] = best;
+  __syncthreads();
+  if (wave == 0) {
+    for (int w = 1; w < kWavesPerBlock; ++w) {
+      best = wave_merge_smallest(best, part[w][lane], lane);
+      if (lane >= K) best = kKeyMax;
+    }
+    if (lane < K) {
+      const bool have = best != kKeyMax;
+      ids_out[q * K + lane] = have ? (int32_t)(uint32_t)best : -1;
+      uint32_t code = (uint32_t)(best >> 32);
+      if (METRIC == kL2U8)
+        reinterpret_cast<int32_t*>(dist_out)[q * K + lane] = have ? unord_i32(code) : 0x7fffffff;
+      else
+        reinterpret_cast<float*>(dist_out)[q * K + lane] =
+            have ? unord_f32(code) : __uint_as_float(0x7f800000u);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Exclusive scan, three passes: per-block scan of 1024 elements, scan of the
+// block sums by one block, add-back.
+constexpr int kScanPerThread = 4;
+constexpr int kScanPerBlock = kBlock * kScanPerThread;
+
+__device__ inline uint64_t block_exclusive_scan(uint64_t v, uint64_t* total) {
+  __shared__ uint64_t wsum[kWavesPerBlock];
+  const int lane = lane_id();
+  const int wave = threadIdx.x >> 6;
+  uint64_t inc = v;
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {
+    uint64_t o = __shfl_up(inc, off, kWave);
+    if (lane >= off) inc += o;
+  }
+  if (lane == kWave - 1) wsum[wave] = inc;
+  __syncthreads();
+  uint64_t before = 0, all = 0;
+  for (int w = 0; w < kWavesPerBlock; ++w) {
+    if (w < wave) before += wsum[w];
+    all += wsum[w];
+  }
+  __syncthreads();
+  *total = all;
+  return before + inc - v;
+}
+
+__global__ __launch_bounds__(kBlock) void k_scan_local(const uint32_t* in, uint64_t* out,
+                                                       uint64_t* bsum, int64_t count) {
+  const int64_t i0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * kScanPerThread;
+  uint32_t v[kScanPerThread];
+  uint64_t sum = 0;
+#pragma unroll
+  for (int j = 0; j < kScanPerThread; ++j) {
+    v[j] = (i0 + j < count) ? in[i0 + j] : 0u;
+    sum += v[j];
+  }
+  uint64_t total;
+  uint64_t run = block_exclusive_scan(sum, &total);
+#pragma unroll
+  for (int j = 0; j < kScanPerThread; ++j) {
+    if (i0 + j <= count) out[i0 + j] = run;
+    run += v[j];
+  }
+  if (threadIdx.x == 0) bsum[blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(kBlock) void k_scan_bsum(uint64_t* bsum, int64_t nb) {
+  uint64_t carry = 0;
+  for (int64_t c = 0; c < nb; c += kBlock) {
+    const int64_t i = c + threadIdx.x;
+    uint64_t v = i < nb ? bsum[i] : 0;
+    uint64_t total;
+    uint64_t ex = block_exclusive_scan(v, &total);
+    if (i < nb) bsum[i] = carry + ex;
+    carry += total;
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void k_scan_add(uint64_t* out, const uint64_t* bsum,
+                                                     int64_t count) {
+  const int64_t i0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * kScanPerThread;
+  const uint64_t add = bsum[blockIdx.x];
+#pragma unroll
+  for (int j = 0; j < kScanPerThread; ++j)
+    if (i0 + j <= count) out[i0 + j] += add;
+}
+
+size_t scan_tmp_elems(int64_t count) { return (size_t)((count + 1 + kScanPerBlock - 1) / kScanPerBlock); }
+
+hipError_t launch_scan(const uint32_t* in, uint64_t* out, uint64_t* tmp, int64_t count,
+                       hipStream_t st) {
+  const int64_t nb = (count + 1 + kScanPerBlock - 1) / kScanPerBlock;
+  k_scan_local<<<(unsigned)nb, kBlock, 0, st>>>(in, out, tmp, count);
+  k_scan_bsum<<<1, kBlock, 0, st>>>(tmp, nb);
+  k_scan_add<<<(unsigned)nb, kBlock, 0, st>>>(out, tmp, count);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+static VecSrc vec_src(const Shape& sh) { return VecSrc{sh.vec_a, sh.vec_b, sh.split, sh.d}; }
+
+hipError_t launch_zero_u32(uint32_t* p, size_t count, hipStream_t st) {
+  if (count == 0) return hipSuccess;
+  k_zero_u32<<<(unsigned)((count + kBlock - 1) / kBlock), kBlock, 0, st>>>(p, count);
+  return hipGetLastError();
+}
+
+hipError_t launch_init_random(const Shape& sh, const DevState& ds, uint64_t seed,
+                              hipStream_t st) {
+  const unsigned grid = blocks_for_waves(sh.n);
+  const uint64_t base = hash_base(seed, kTagInit);
+  switch (sh.metric) {
+    case kL2F32:
+      k_init_random<kL2F32><<<grid, kBlock, 0, st>>>(vec_src(sh), sh.n, sh.k, base, ds.G, ds.kth);
+      break;
+    case kAngularF32:
+      k_init_random<kAngularF32><<<grid, kBlock, 0, st>>>(vec_src(sh), sh.n, sh.k, base, ds.G,
+                                                          ds.kth);
+      break;
+    default:
+      k_init_random<kL2U8><<<grid, kBlock, 0, st>>>(vec_src(sh), sh.n, sh.k, base, ds.G, ds.kth);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_sample(const Shape& sh, const DevState& ds, uint64_t seed, uint32_t iter,
+                         hipStream_t st) {
+  const unsigned grid = blocks_for_waves(sh.n);
+  k_sample_fwd<<<grid, kBlock, 0, st>>>(sh.n, sh.k, sh.p, ds.G, ds.snew, ds.sold, ds.cnew,
+                                        ds.cold, ds.rcnt_new, ds.rcnt_old);
+  hipError_t e = launch_scan(ds.rcnt_new, ds.roff_new, ds.scan_tmp, sh.n, st);
+  if (e != hipSuccess) return e;
+  e = launch_scan(ds.rcnt_old, ds.roff_old, ds.scan_tmp, sh.n, st);
+  if (e != hipSuccess) return e;
+  k_rev_fill<<<grid, kBlock, 0, st>>>(sh.n, sh.p, ds.snew, ds.sold, ds.cnew, ds.cold,
+                                      ds.rcnt_new, ds.rcnt_old, ds.roff_new, ds.roff_old,
+                                      ds.csr_new, ds.csr_old);
+  k_rev_select<<<dim3(grid, 2), kBlock, 0, st>>>(
+      sh.n, sh.p, hash_base(seed, kTagRevNew), hash_base(seed, kTagRevOld), iter, ds.snew,
+      ds.sold, ds.cnew, ds.cold, ds.roff_new, ds.roff_old, ds.csr_new, ds.csr_old, ds.counters);
+  return hipGetLastError();
+}
+
+hipError_t launch_update(const Shape& sh, const DevState& ds, hipStream_t st) {
+  hipError_t e = launch_scan(ds.pcnt, ds.poff, ds.scan_tmp, sh.n, st);
+  if (e != hipSuccess) return e;
+  const int64_t slots = sh.n * 6 * sh.p;
+  k_prop_fill<<<(unsigned)((slots + kBlock - 1) / kBlock), kBlock, 0, st>>>(
+      slots, ds.prop_dest, ds.prop_key, ds.pcnt, ds.poff, ds.bins);
+  k_update<<<blocks_for_waves(sh.n), kBlock, 0, st>>>(sh.n, sh.k, ds.G, ds.kth, ds.poff, ds.bins,
+                                                      ds.counters);
+  return hipGetLastError();
+}
+
+hipError_t launch_get_graph(const Shape& sh, const DevState& ds, int32_t* ids, void* dist,
+                            uint8_t* isnew, hipStream_t st) {
+  const int64_t total = sh.n * sh.k;
+  const unsigned grid = (unsigned)((total + kBlock - 1) / kBlock);
+  if (sh.metric == kL2U8) k_get_graph<false><<<grid, kBlock, 0, st>>>(total, ds.G, ids, dist, isnew);
+  else k_get_graph<true><<<grid, kBlock, 0, st>>>(total, ds.G, ids, dist, isnew);
+  return hipGetLastError();
+}
+
+hipError_t launch_set_graph(const Shape& sh, const DevState& ds, const int32_t* ids,
+                            const void* dist, const uint8_t* isnew, hipStream_t st) {
+  const int64_t total = sh.n * sh.k;
+  const unsigned grid = (unsigned)((total + kBlock - 1) / kBlock);
+  if (sh.metric == kL2U8)
+    k_set_graph<false><<<grid, kBlock, 0, st>>>(total, sh.k, ds.G, ds.kth, ids, dist, isnew);
+  else
+    k_set_graph<true><<<grid, kBlock, 0, st>>>(total, sh.k, ds.G, ds.kth, ids, dist, isnew);
+  return hipGetLastError();
+}
+
+hipError_t launch_get_proposals(const Shape& sh, const DevState& ds, int32_t* u, int32_t* v,
+                                void* dist, hipStream_t st) {
+  const int64_t slots = sh.n * 6 * sh.p;
+  const unsigned grid = (unsigned)((slots + kBlock - 1) / kBlock);
+  if (sh.metric == kL2U8)
+    k_get_proposals<false><<<grid, kBlock, 0, st>>>(slots, ds.prop_dest, ds.prop_key, u, v, dist);
+  else
+    k_get_proposals<true><<<grid, kBlock, 0, st>>>(slots, ds.prop_dest, ds.prop_key, u, v, dist);
+  return hipGetLastError();
+}
+
+hipError_t launch_merge_init(const Shape& sh, const DevState& ds, uint64_t seed, int64_t n1,
+                             const int32_t* ids1, const void* dist1, const int32_t* ids2,
+                             const void* dist2, hipStream_t st) {
+  const unsigned grid = blocks_for_waves(sh.n);
+  const uint64_t base = hash_base(seed, kTagMerge);
+  switch (sh.metric) {
+    case kL2F32:
+      k_merge_init<kL2F32><<<grid, kBlock, 0, st>>>(vec_src(sh), sh.n, n1, sh.k, base, ids1, dist1,
+                                                    ids2, dist2, ds.G, ds.kth, ds.aside);
+      break;
+    case kAngularF32:
+      k_merge_init<kAngularF32><<<grid, kBlock, 0, st>>>(vec_src(sh), sh.n, n1, sh.k, base, ids1,
+                                                         dist1, ids2, dist2, ds.G, ds.kth,
+                                                         ds.aside);
+      break;
+    default:
+      k_merge_init<kL2U8><<<grid, kBlock, 0, st>>>(vec_src(sh), sh.n, n1, sh.k, base, ids1, dist1,
+                                                   ids2, dist2, ds.G, ds.kth, ds.aside);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_merge_final(const Shape& sh, const DevState& ds, int32_t* ids_out,
+                              void* dist_out, hipStream_t st) {
+  const unsigned grid = blocks_for_waves(sh.n);
+  if (sh.metric == kL2U8)
+    k_merge_final<false><<<grid, kBlock, 0, st>>>(sh.n, sh.k, ds.G, ds.aside, ids_out, dist_out);
+  else
+    k_merge_final<true><<<grid, kBlock, 0, st>>>(sh.n, sh.k, ds.G, ds.aside, ids_out, dist_out);
+  return hipGetLastError();
+}
+
+hipError_t launch_exact_knn(const void* vec, int64_t n, int32_t d, int32_t metric,
+                            const int32_t* queries, int64_t nq, int32_t K, int32_t* ids_out,
+                            void* dist_out, hipStream_t st) {
+  if (nq == 0) return hipSuccess;
+  const unsigned grid = (unsigned)nq;
+  switch (metric) {
+    case kL2F32:
+      k_exact_knn<kL2F32><<<grid, kBlock, 0, st>>>(vec, n, d, queries, K, ids_out, dist_out);
+      break;
+    case kAngularF32:
+      k_exact_knn<kAngularF32><<<grid, kBlock, 0, st>>>(vec, n, d, queries, K, ids_out, dist_out);
+      break;
+    default:
+      k_exact_knn<kL2U8><<<grid, kBlock, 0, st>>>(vec, n, d, queries, K, ids_out, dist_out);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace gnnd

@@ -1,0 +1,309 @@
+// Cross-matching (Sec. 4.2) and selective nearest-object search (Sec. 4.3,
+// Alg. 2) for one node per workgroup, canonical arithmetic: every distance is
+// accumulated per pair, one fused multiply-add per dimension in dimension
+// order (exact int32 for bytes), so results are bit-identical to a sequential
+// evaluation.
+//
+// Layout: the node's <= 64 NEW and <= 64 OLD sample vectors are staged through
+// LDS in chunks of 64 dimensions (coalesced row reads from HBM); the 64 x 128
+// block of distances [NEW x (NEW | OLD)] is register-tiled 4 x 8 per thread
+// over a 16 x 16 thread grid with the rows/columns of a thread 16 apart, so
+// partially filled lists switch whole 16 x 16 sub-blocks off uniformly.  Only
+// the lower block triangle of NEW x NEW is evaluated.  The distances then go
+// to LDS and three wavefronts pick, per sample, the nearest other NEW sample,
+// the nearest OLD sample, and per OLD sample the nearest NEW sample.
+#include "device_utils.hpp"
+#include "kernels.hpp"
+
+namespace gnnd {
+
+constexpr int kJB = 256;      // threads per workgroup
+constexpr int kDC = 64;       // dimensions per staged chunk
+constexpr int kLD = kDC + 4;  // LDS row stride (elements), keeps 16-byte alignment
+constexpr int kDLD = 129;     // row stride of the distance matrix in LDS
+
+template <int METRIC>
+struct JoinTraits;
+template <>
+struct JoinTraits<kL2F32> {
+  using elem = float;
+  using acc = float;
+  __device__ static void step(float a, float b, float& s) {
+    float t = a - b;
+    s = __fmaf_rn(t, t, s);
+  }
+  __device__ static uint32_t code(float s) { return ord_f32(s); }
+};
+template <>
+struct JoinTraits<kAngularF32> {
+  using elem = float;
+  using acc = float;
+  __device__ static void step(float a, float b, float& s) { s = __fmaf_rn(a, b, s); }
+  __device__ static uint32_t code(float s) { return ord_f32(1.0f - s); }
+};
+template <>
+struct JoinTraits<kL2U8> {
+  using elem = uint8_t;
+  using acc = int32_t;
+  __device__ static void step(int32_t a, int32_t b, int32_t& s) {
+    int32_t t = a - b;
+    s += __mul24(t, t);
+  }
+  __device__ static uint32_t code(int32_t s) { return ord_i32(s); }
+};
+
+// Stage dimensions [d0, d0 + kDC) of one vector into an LDS row (as the
+// accumulation type), zero beyond the vector's end.  16 threads per row.
+template <typename ACC>
+__device__ inline void stage_row(ACC* dst, const float* src, int d, int d0, int part,
+                                 bool aligned) {
+  const int j = d0 + part * 4;
+  float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (src != nullptr) {
+    if (aligned && j + 3 < d) {
+      v = *reinterpret_cast<const float4*>(src + j);
+    } else {
+      if (j + 0 < d) v.x = src[j + 0];
+      if (j + 1 < d) v.y = src[j + 1];
+      if (j + 2 < d) v.z = src[j + 2];
+      if (j + 3 < d) v.w = src[j + 3];
+    }
+  }
+  *reinterpret_cast<float4*>(dst + part * 4) = v;
+}
+template <typename ACC>
+__device__ inline void stage_row(ACC* dst, const uint8_t* src, int d, int d0, int part,
+                                 bool aligned) {
+  const int j = d0 + part * 4;
+  int4 v = make_int4(0, 0, 0, 0);
+  if (src != nullptr) {
+    if (aligned && j + 3 < d) {
+      uint32_t w = *reinterpret_cast<const uint32_t*>(src + j);
+      v = make_int4((int)(w & 0xff), (int)((w >> 8) & 0xff), (int)((w >> 16) & 0xff),
+                    (int)(w >> 24));
+    } else {
+      if (j + 0 < d) v.x = src[j + 0];
+      if (j + 1 < d) v.y = src[j + 1];
+      if (j + 2 < d) v.z = src[j + 2];
+      if (j + 3 < d) v.w = src[j + 3];
+    }
+  }
+  *reinterpret_cast<int4*>(dst + part * 4) = v;
+}
+
+template <int METRIC>
+__global__ __launch_bounds__(kJB) void k_join_valu(
+    VecSrc vs, int64_t n, int p, int merge_mode, const int32_t* __restrict__ snew,
+    const int32_t* __restrict__ sold, const int32_t* __restrict__ cnew,
+    const int32_t* __restrict__ cold, const uint32_t* __restrict__ kth, uint32_t* pcnt,
+    int32_t* __restrict__ prop_dest, uint64_t* __restrict__ prop_key, uint64_t* counters) {
+  using TR = JoinTraits<METRIC>;
+  using T = typename TR::elem;
+  using ACC = typename TR::acc;
+  __shared__ __attribute__((aligned(16))) ACC tile[128 * kLD];
+  __shared__ int32_t ids[128];
+  static_assert(128 * kLD >= 64 * kDLD, "distance matrix must fit in the staging tile");
+
+  const int64_t s = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int L = 2 * p;
+  const int nn = cnew[s], no = cold[s];
+  int32_t* out_dest = prop_dest + s * 3 * L;
+  uint64_t* out_key = prop_key + s * 3 * L;
+
+  if (tid < 128) {
+    int32_t id = -1;
+    if (tid < 64) {
+      if (tid < nn) id = snew[s * L + tid];
+    } else if (tid - 64 < no) {
+      id = sold[s * L + tid - 64];
+    }
+    ids[tid] = id;
+  }
+  const bool do_nn = !merge_mode && nn > 1;
+  if (nn == 0 || (!do_nn && no == 0)) {  // nothing to evaluate: all slots empty
+    for (int i = tid; i < 3 * L; i += kJB) out_dest[i] = -1;
+    return;
+  }
+  __syncthreads();
+
+  const int tx = tid & 15, ty = tid >> 4;
+  const int RB = (nn + 15) >> 4;  // active 16-row blocks (NEW)
+  const int CO = (no + 15) >> 4;  // active 16-column blocks (OLD)
+  const int d = vs.d;
+  const bool aligned = (d & 3) == 0;
+
+  ACC acc[4][8];
+#pragma unroll
+  for (int r = 0; r < 4; ++r)
+#pragma unroll
+    for (int c = 0; c < 8; ++c) acc[r][c] = 0;
+
+  for (int d0 = 0; d0 < d; d0 += kDC) {
+    // stage: 16 threads per row, 16 rows per pass
+    const int part = tid & 15;
+#pragma unroll
+    for (int pass = 0; pass < 8; ++pass) {
+      const int row = pass * 16 + (tid >> 4);
+      const bool wanted = row < 64 ? (row < RB * 16) : (row - 64 < CO * 16);
+      if (wanted) {
+        const int32_t id = ids[row];
+        const T* src = id >= 0 ? vs.row<T>((uint32_t)id) : nullptr;
+        stage_row<ACC>(tile + row * kLD, src, d, d0, part, aligned);
+      }
+    }
+    __syncthreads();
+    const int width = (d - d0) < kDC ? (d - d0) : kDC;
+    const int nsub = (width + 15) >> 4;
+    for (int sub = 0; sub < nsub; ++sub) {
+      ACC a[4][16];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        if (r < RB) {
+          const ACC* src = tile + (ty + 16 * r) * kLD + sub * 16;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int4 w = *reinterpret_cast<const int4*>(src + q * 4);
+            a[r][q * 4 + 0] = __builtin_bit_cast(ACC, w.x);
+            a[r][q * 4 + 1] = __builtin_bit_cast(ACC, w.y);
+            a[r][q * 4 + 2] = __builtin_bit_cast(ACC, w.z);
+            a[r][q * 4 + 3] = __builtin_bit_cast(ACC, w.w);
+          }
+        }
+      }
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        const bool col_on = c < 4 ? (do_nn && c < RB) : (c - 4 < CO);
+        if (col_on) {
+          const int crow = c < 4 ? (tx + 16 * c) : (64 + tx + 16 * (c - 4));
+          const ACC* src = tile + crow * kLD + sub * 16;
+          ACC b[16];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int4 w = *reinterpret_cast<const int4*>(src + q * 4);
+            b[q * 4 + 0] = __builtin_bit_cast(ACC, w.x);
+            b[q * 4 + 1] = __builtin_bit_cast(ACC, w.y);
+            b[q * 4 + 2] = __builtin_bit_cast(ACC, w.z);
+            b[q * 4 + 3] = __builtin_bit_cast(ACC, w.w);
+          }
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            if (r < RB && (c >= 4 || c <= r)) {
+#pragma unroll
+              for (int j = 0; j < 16; ++j) TR::step(a[r][j], b[j], acc[r][c]);
+            }
+          }
+        }
+      }
+    }
+    __syncthreads();
+  }
+
+  // distances (as order-preserving codes) to LDS: Dm[row][col], col < 64 NEW, >= 64 OLD
+  uint32_t* Dm = reinterpret_cast<uint32_t*>(tile);
+#pragma unroll
+  for (int r = 0; r < 4; ++r)
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      const bool on = r < RB && (c < 4 ? (do_nn && c <= r) : (c - 4 < CO));
+      if (on) {
+        const int col = c < 4 ? (tx + 16 * c) : (64 + tx + 16 * (c - 4));
+        Dm[(ty + 16 * r) * kDLD + col] = TR::code(acc[r][c]);
+      }
+    }
+  __syncthreads();
+
+  // nearest-object search: wave 0 NEW->NEW, wave 1 NEW->OLD, wave 2 OLD->NEW
+  const int wave = tid >> 6, lane = tid & 63;
+  if (wave > 2) return;
+  const int64_t split = vs.split;
+  uint64_t best = kKeyMax;
+  int32_t self = -1;
+  uint32_t evaluated = 0;
+  if (wave == 0) {
+    if (do_nn && lane < nn) {
+      self = ids[lane];
+      for (int v = 0; v < nn; ++v) {
+        if (v == lane) continue;
+        const uint32_t code = ((v >> 4) <= (lane >> 4)) ? Dm[lane * kDLD + v] : Dm[v * kDLD + lane];
+        const uint64_t key = ((uint64_t)code << 32) | (uint32_t)ids[v];
+        best = key < best ? key : best;
+      }
+    }
+  } else if (wave == 1) {
+    if (lane < nn) {
+      self = ids[lane];
+      for (int o = 0; o < no; ++o) {
+        const int32_t other = ids[64 + o];
+        bool ok = other != self;
+        if (merge_mode) ok = ok && (((int64_t)self < split) != ((int64_t)other < split));
+        if (!ok) continue;
+        ++evaluated;
+        const uint64_t key = ((uint64_t)Dm[lane * kDLD + 64 + o] << 32) | (uint32_t)other;
+        best = key < best ? key : best;
+      }
+    }
+  } else {
+    if (lane < no) {
+      self = ids[64 + lane];
+      for (int u = 0; u < nn; ++u) {
+        const int32_t other = ids[u];
+        bool ok = other != self;
+        if (merge_mode) ok = ok && (((int64_t)self < split) != ((int64_t)other < split));
+        if (!ok) continue;
+        const uint64_t key = ((uint64_t)Dm[u * kDLD + 64 + lane] << 32) | (uint32_t)other;
+        best = key < best ? key : best;
+      }
+    }
+  }
+  const bool found = best != kKeyMax;
+  // a result that cannot beat the last entry of the destination list is dropped here
+  const bool pass = found && (uint32_t)(best >> 32) <= kth[self < 0 ? 0 : self];
+  if (lane < L) {
+    out_dest[wave * L + lane] = pass ? self : -1;
+    out_key[wave * L + lane] = make_entry((uint32_t)(best >> 32), (uint32_t)best, 3u);
+  }
+  if (pass) atomicAdd(&pcnt[self], 1u);
+  const uint64_t nfound = __popcll(__ballot(found));
+  if (wave == 1) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) evaluated += __shfl_xor(evaluated, off, kWave);
+  }
+  if (lane == 0) {
+    if (nfound) atomicAdd(reinterpret_cast<unsigned long long*>(
+                              counters + (s & (kStripes - 1)) * C_SLOTS + C_PROPS),
+                          (unsigned long long)nfound);
+    if (wave == 1) {
+      uint64_t ev = (uint64_t)evaluated + (do_nn ? (uint64_t)nn * (nn - 1) / 2 : 0);
+      if (ev) atomicAdd(reinterpret_cast<unsigned long long*>(
+                            counters + (s & (kStripes - 1)) * C_SLOTS + C_EVALS),
+                        (unsigned long long)ev);
+    }
+  }
+}
+
+hipError_t launch_join(const Shape& sh, const DevState& ds, int path, bool merge_mode,
+                       hipStream_t st) {
+  (void)path;
+  VecSrc vs{sh.vec_a, sh.vec_b, sh.split, sh.d};
+  const unsigned grid = (unsigned)sh.n;
+  switch (sh.metric) {
+    case kL2F32:
+      k_join_valu<kL2F32><<<grid, kJB, 0, st>>>(vs, sh.n, sh.p, merge_mode ? 1 : 0, ds.snew,
+                                                ds.sold, ds.cnew, ds.cold, ds.kth, ds.pcnt,
+                                                ds.prop_dest, ds.prop_key, ds.counters);
+      break;
+    case kAngularF32:
+      k_join_valu<kAngularF32><<<grid, kJB, 0, st>>>(vs, sh.n, sh.p, merge_mode ? 1 : 0, ds.snew,
+                                                     ds.sold, ds.cnew, ds.cold, ds.kth, ds.pcnt,
+                                                     ds.prop_dest, ds.prop_key, ds.counters);
+      break;
+    default:
+      k_join_valu<kL2U8><<<grid, kJB, 0, st>>>(vs, sh.n, sh.p, merge_mode ? 1 : 0, ds.snew,
+                                               ds.sold, ds.cnew, ds.cold, ds.kth, ds.pcnt,
+                                               ds.prop_dest, ds.prop_key, ds.counters);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace gnnd

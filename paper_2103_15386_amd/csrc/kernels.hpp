@@ -1,0 +1,72 @@
+// Host-callable launchers of the GNND kernels (one per pipeline stage) and the
+// device-pointer bundle they work on.  Every launcher enqueues on `st` and
+// returns the hipGetLastError() of its launches.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace gnnd {
+
+enum : int { C_INSERTS = 0, C_EVALS = 1, C_SUMNEW = 2, C_SUMOLD = 3, C_PROPS = 4, C_SLOTS = 8 };
+constexpr int kStripes = 64;  // counters are striped to spread same-address atomics
+
+// Everything lives in the caller's workspace; sizes in elements.
+struct DevState {
+  uint64_t* G;         // n*k packed entries, row per node, ascending
+  uint32_t* kth;       // n: distance code of the last entry of each list
+  int32_t* snew;       // n*2p NEW sample lists
+  int32_t* sold;       // n*2p OLD sample lists
+  int32_t* cnew;       // n list sizes
+  int32_t* cold;       // n
+  uint32_t* rcnt_new;  // n reverse-candidate counts (zero between iterations)
+  uint32_t* rcnt_old;  // n
+  uint64_t* roff_new;  // n+1 offsets into csr_new
+  uint64_t* roff_old;  // n+1
+  int32_t* csr_new;    // n*p reverse candidates grouped by target
+  int32_t* csr_old;    // n*p
+  uint32_t* pcnt;      // n proposals per destination (zero between iterations)
+  uint64_t* poff;      // n+1 offsets into bins
+  int32_t* prop_dest;  // n*6p dense proposal slots: destination list or -1
+  uint64_t* prop_key;  // n*6p: packed (distance, object, flags) of the slot
+  uint64_t* bins;      // n*6p proposals grouped by destination
+  uint64_t* scan_tmp;  // block sums of the scans
+  uint64_t* counters;  // kStripes * C_SLOTS
+  uint64_t* aside;     // merge only: n * floor(k/2) set-aside entries
+};
+
+struct Shape {
+  int64_t n;
+  int32_t d, k, p, metric;
+  int64_t split;  // merge: first id of the second set; otherwise n
+  const void* vec_a;
+  const void* vec_b;
+};
+
+hipError_t launch_init_random(const Shape& sh, const DevState& ds, uint64_t seed, hipStream_t st);
+hipError_t launch_sample(const Shape& sh, const DevState& ds, uint64_t seed, uint32_t iter,
+                         hipStream_t st);
+hipError_t launch_join(const Shape& sh, const DevState& ds, int path, bool merge_mode,
+                       hipStream_t st);
+hipError_t launch_update(const Shape& sh, const DevState& ds, hipStream_t st);
+hipError_t launch_get_graph(const Shape& sh, const DevState& ds, int32_t* ids, void* dist,
+                            uint8_t* isnew, hipStream_t st);
+hipError_t launch_set_graph(const Shape& sh, const DevState& ds, const int32_t* ids,
+                            const void* dist, const uint8_t* isnew, hipStream_t st);
+hipError_t launch_get_proposals(const Shape& sh, const DevState& ds, int32_t* u, int32_t* v,
+                                void* dist, hipStream_t st);
+hipError_t launch_merge_init(const Shape& sh, const DevState& ds, uint64_t seed, int64_t n1,
+                             const int32_t* ids1, const void* dist1, const int32_t* ids2,
+                             const void* dist2, hipStream_t st);
+hipError_t launch_merge_final(const Shape& sh, const DevState& ds, int32_t* ids_out,
+                              void* dist_out, hipStream_t st);
+hipError_t launch_exact_knn(const void* vec, int64_t n, int32_t d, int32_t metric,
+                            const int32_t* queries, int64_t nq, int32_t K, int32_t* ids_out,
+                            void* dist_out, hipStream_t st);
+hipError_t launch_zero_u32(uint32_t* p, size_t count, hipStream_t st);
+
+// Exclusive scan of `count` uint32 into uint64 offsets out[0..count] (out[count] = total).
+hipError_t launch_scan(const uint32_t* in, uint64_t* out, uint64_t* tmp, int64_t count,
+                       hipStream_t st);
+size_t scan_tmp_elems(int64_t count);
+
+}  // namespace gnnd

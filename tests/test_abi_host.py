@@ -1,0 +1,67 @@
+"""Host-only checks of the C ABI library: it loads without a GPU, exports every
+symbol include/gnnd.h declares, sizes workspaces and refuses bad arguments
+before anything is launched.  No compute calls."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def amd():
+    import paper_2103_15386_amd as amd
+    from paper_2103_15386_amd import build
+    if not os.path.exists(amd.library_path()):
+        build.build_library()
+    return amd
+
+
+def test_library_exports_every_declared_symbol(amd):
+    header = open(os.path.join(ROOT, "include", "gnnd.h")).read()
+    declared = set(re.findall(r"\b(gnnd_[a-z_]+)\s*\(", header))
+    declared -= {"gnnd_workspace_bytes()"}
+    assert {"gnnd_init_random", "gnnd_iterate", "gnnd_build", "gnnd_merge"} <= declared
+    lib = C.CDLL(amd.library_path())
+    for name in sorted(declared):
+        assert hasattr(lib, name), f"{name} is declared but not exported"
+    from paper_2103_15386_amd import binding
+    assert set(binding.EXPORTS) == declared
+
+
+def test_workspace_size_and_parameter_validation(amd):
+    from paper_2103_15386_amd import binding
+    lib = amd.load_library()
+    small = amd.workspace_bytes(4096, 16, 10, 8, amd.L2SQ_F32)
+    big = amd.workspace_bytes(1_000_000, 128, 32, 32, amd.L2SQ_F32)
+    assert 0 < small < big < 8 << 30
+    assert amd.workspace_bytes(10, 16, 10, 8, amd.L2SQ_F32) == 0      # k >= n
+    assert amd.workspace_bytes(4096, 16, 65, 8, amd.L2SQ_F32) == 0    # k > 64
+    assert amd.workspace_bytes(4096, 16, 10, 11, amd.L2SQ_F32) == 0   # p > k
+    assert amd.workspace_bytes(4096, 16, 40, 33, amd.L2SQ_F32) == 0   # p > 32
+    assert amd.workspace_bytes(4096, 0, 10, 8, amd.L2SQ_F32) == 0     # d < 1
+    assert amd.workspace_bytes(4096, 16, 10, 8, 7) == 0               # metric
+    # gnnd_create validates before touching the GPU: errors come back as codes
+    ctx = C.c_void_p()
+    prm = binding.make_params(50, 8, 50, 8, amd.L2SQ_F32)
+    assert lib.gnnd_create(C.byref(ctx), C.byref(prm), 0x1000) == binding.EINVAL
+    assert b"n must exceed k" in lib.gnnd_last_error(None)
+    prm = binding.make_params(100, 8, 10, 8, amd.L2SQ_F32)
+    assert lib.gnnd_create(C.byref(ctx), C.byref(prm), None) == binding.EINVAL
+    prm.workspace_dev, prm.workspace_bytes = 0x100000, 16
+    assert lib.gnnd_create(C.byref(ctx), C.byref(prm), 0x1000) == binding.ENOSPC
+    assert b"workspace too small" in lib.gnnd_last_error(None)
+    prm.workspace_dev = 0x100001
+    assert lib.gnnd_create(C.byref(ctx), C.byref(prm), 0x1000) == binding.EINVAL
+    assert lib.gnnd_iterate(None, None) == binding.EINVAL
+    assert lib.gnnd_exact_knn(None, 10, 4, 0, None, 1, 3, None, None, None) == binding.EINVAL
+
+
+def test_product_path_refuses_cpu_tensors(amd):
+    import torch
+    with pytest.raises(amd.GnndError):
+        amd.Gnnd(torch.zeros(100, 8), 10, 8)
+    with pytest.raises(amd.GnndError):
+        amd.exact_knn(torch.zeros(100, 8), torch.zeros(4, dtype=torch.int32), 3)

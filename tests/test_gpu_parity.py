@@ -1,0 +1,184 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on
+the same seeded inputs, element by element.  With the per-pair in-order fused
+arithmetic both sides compute the same float32 bits, so ids, distances, flags,
+sample lists and counters are compared for equality."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as og
+import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+SEED = W.ALGO_SEED
+
+
+def _amd():
+    import paper_2103_15386_amd as amd
+    return amd
+
+
+def _dev(x):
+    return torch.from_numpy(np.ascontiguousarray(x)).cuda()
+
+
+def _graph_np(ctx):
+    ids, dist, flags = ctx.graph(with_flags=True)
+    return ids.cpu().numpy(), dist.cpu().numpy().astype(np.float64), flags.cpu().numpy()
+
+
+def _assert_graph_equal(ctx, g, what):
+    ids, dist, flags = _graph_np(ctx)
+    assert (ids == g.ids).all(), f"{what}: ids differ in {(ids != g.ids).any(1).sum()} rows"
+    assert (dist == g.dist).all(), f"{what}: distances differ"
+    assert (flags == g.isnew).all(), f"{what}: NEW flags differ"
+
+
+CASES = {
+    # name: (generator, metric, k, p, iters)
+    "uniform_c1": (lambda: W.uniform_f32(4096, 16, seed=1001), og.L2SQ_F32, 10, 8, 8),
+    "sift_cut": (lambda: W.sift_like_f32(3000, 128, seed=1002, n_comp=16), og.L2SQ_F32, 32, 32, 5),
+    "deep_cut_angular": (lambda: W.deep_like_f32(2500, 96, seed=1004, n_comp=16),
+                         og.ANGULAR_F32, 20, 12, 5),
+    "u8_cut": (lambda: W.sift_like_u8(2500, 128, seed=1005, n_comp=16), og.L2SQ_U8, 32, 16, 5),
+    "ragged_d13_k64": (lambda: W.uniform_f32(1500, 13, seed=5), og.L2SQ_F32, 64, 32, 4),
+    "gist_cut_d200": (lambda: W.gist_like_f32(1200, 200, seed=1003, n_comp=8),
+                      og.L2SQ_F32, 16, 16, 4),
+    "tiny_n": (lambda: W.uniform_f32(70, 7, seed=6), og.L2SQ_F32, 5, 3, 4),
+    "u8_d30": (lambda: W.sift_like_u8(900, 30, seed=8, n_comp=4), og.L2SQ_U8, 12, 12, 4),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_init_matches_oracle(name):
+    amd = _amd()
+    gen, metric, k, p, _ = CASES[name]
+    x = gen()
+    ctx = amd.Gnnd(_dev(x), k, p, metric, SEED)
+    ctx.init_random()
+    _assert_graph_equal(ctx, og.init_random(x, k, metric, SEED), "init")
+    ctx.close()
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_every_stage_of_every_iteration_matches_oracle(name):
+    amd = _amd()
+    gen, metric, k, p, iters = CASES[name]
+    x = gen()
+    n = len(x)
+    ctx = amd.Gnnd(_dev(x), k, p, metric, SEED, amd.JOIN_VALU)
+    ctx.init_random()
+    g = og.init_random(x, k, metric, SEED)
+    for it in range(1, iters + 1):
+        before = g.copy()
+        # --- sampling -----------------------------------------------------
+        ctx.step_sample()
+        snew, cnew, sold, cold = og.sample(g, p, SEED, it)
+        gs = [t.cpu().numpy() for t in ctx.samples()]
+        assert (gs[1] == cnew).all() and (gs[3] == cold).all(), f"it {it}: sample sizes"
+        assert (gs[0] == snew).all() and (gs[2] == sold).all(), f"it {it}: sample lists"
+        # --- cross-matching + nearest objects ------------------------------
+        ctx.step_join()
+        pu, pv, pd, pcnt, evals = og.join(x, metric, p, snew, cnew, sold, cold)
+        gu, gv, gd = [t.cpu().numpy() for t in ctx.proposals()]
+        want = {}
+        for s in range(n):
+            for j in range(pcnt[s]):
+                want.setdefault(s, set()).add((int(pu[s, j]), int(pv[s, j]), float(pd[s, j])))
+        kth = before.dist[:, k - 1]
+        for s in range(n):
+            got = {(int(a), int(b), float(c)) for a, b, c in zip(gu[s], gv[s], gd[s]) if a >= 0}
+            exp = want.get(s, set())
+            assert got <= exp, f"it {it} node {s}: GPU proposed something the oracle did not"
+            for (u, v, dd) in exp - got:  # only hopeless results may be dropped early
+                assert dd > kth[u], f"it {it} node {s}: dropped an admissible proposal"
+        # --- update ----------------------------------------------------------
+        st = ctx.step_update()
+        ins = og.update(g, p, pu, pv, pd, pcnt)
+        _assert_graph_equal(ctx, g, f"iteration {it}")
+        assert st["iter"] == it
+        assert st["inserts"] == ins
+        assert st["dist_evals"] == evals
+        assert st["sum_new"] == int(cnew.sum()) and st["sum_old"] == int(cold.sum())
+        assert st["proposals"] == int(pcnt.sum())
+    ctx.close()
+
+
+def test_build_equals_stepwise_and_is_deterministic():
+    amd = _amd()
+    x = W.uniform_f32(4096, 16, seed=1001)
+    xd = _dev(x)
+    ids_a, dist_a, ctx_a = amd.gnnd_build(xd, 10, 8, amd.L2SQ_F32, SEED, iters=8)
+    ids_b, dist_b, ctx_b = amd.gnnd_build(xd, 10, 8, amd.L2SQ_F32, SEED, iters=8)
+    assert torch.equal(ids_a, ids_b) and torch.equal(dist_a, dist_b)
+    g, _ = og.build(x, 10, 8, og.L2SQ_F32, SEED, 8)
+    _assert_graph_equal(ctx_a, g, "build")
+    # end-to-end quality agrees with the oracle's (identical graphs => identical recall)
+    q = torch.arange(4096, dtype=torch.int32, device="cuda")
+    tids, tdist = amd.exact_knn(xd, q, 10, amd.L2SQ_F32)
+    r_gpu = amd.recall_at(dist_a, tdist, 10)
+    oi, od = og.bruteforce(x, og.L2SQ_F32, np.arange(4096), 10)
+    r_cpu, _ = og.recall_at(g.ids, g.dist, oi, od, 10)
+    assert abs(r_gpu - r_cpu) <= 0.005 and r_gpu > 0.85
+    # a different seed gives a different graph
+    ids_c, _, ctx_c = amd.gnnd_build(xd, 10, 8, amd.L2SQ_F32, SEED + 1, iters=2)
+    ids_d, _, ctx_d = amd.gnnd_build(xd, 10, 8, amd.L2SQ_F32, SEED, iters=2)
+    assert not torch.equal(ids_c, ids_d)
+    for c in (ctx_a, ctx_b, ctx_c, ctx_d):
+        c.close()
+
+
+def test_resume_from_saved_graph_gives_the_same_bytes():
+    amd = _amd()
+    x = W.uniform_f32(2000, 12, seed=77)
+    xd = _dev(x)
+    a = amd.Gnnd(xd, 12, 6, amd.L2SQ_F32, SEED)
+    a.init_random()
+    for _ in range(2):
+        a.iterate(False)
+    ids, dist, flags = a.graph(with_flags=True)
+    b = amd.Gnnd(xd, 12, 6, amd.L2SQ_F32, SEED)
+    b.set_graph(ids, dist, flags, 2)
+    for _ in range(2):
+        a.iterate(False)
+        b.iterate(False)
+    ga, gb = a.graph(with_flags=True), b.graph(with_flags=True)
+    assert all(torch.equal(s, t) for s, t in zip(ga, gb))
+    a.close()
+    b.close()
+
+
+@pytest.mark.parametrize("metric,gen", [
+    (og.L2SQ_F32, lambda: W.uniform_f32(3000, 24, seed=91)),
+    (og.ANGULAR_F32, lambda: W.deep_like_f32(3000, 32, seed=92, n_comp=8)),
+    (og.L2SQ_U8, lambda: W.sift_like_u8(3000, 40, seed=93, n_comp=8)),
+    (og.L2SQ_F32, lambda: W.small_integer_f32(2000, 5, seed=94, hi=4)),  # masses of ties
+])
+def test_exact_knn_matches_oracle_brute_force(metric, gen):
+    amd = _amd()
+    x = gen()
+    q = W.sample_nodes(len(x), 200, seed=3)
+    ids, dist = amd.exact_knn(_dev(x), _dev(q), 10, metric)
+    oi, od = og.bruteforce(x, metric, q, 10)
+    assert (ids.cpu().numpy() == oi).all()
+    assert (dist.cpu().numpy().astype(np.float64) == od).all()
+
+
+def test_errors_are_reported_not_fatal():
+    amd = _amd()
+    x = _dev(W.uniform_f32(100, 8, seed=1))
+    with pytest.raises(amd.GnndError):
+        amd.Gnnd(x, 100, 8)  # k >= n
+    with pytest.raises(amd.GnndError):
+        amd.Gnnd(x, 10, 11)  # p > k
+    ctx = amd.Gnnd(x, 10, 8)
+    with pytest.raises(amd.GnndError) as e:
+        ctx.iterate()  # no graph yet
+    assert e.value.code == -3
+    ctx.init_random()
+    with pytest.raises(amd.GnndError):
+        ctx.step_join()  # out of order
+    ctx.close()
+    with pytest.raises(amd.GnndError):
+        amd.Gnnd(torch.zeros(100, 8), 10, 8)  # CPU tensor: no CPU path
