@@ -1,0 +1,170 @@
+#!/usr/bin/env python3
+"""Benchmark of the GNND build on one MI355X.
+
+Workload: n = 1,000,000 float32 vectors, d = 128, SIFT-shaped synthetic mixture
+(a stand-in for SIFT1M, which is not available), k = 32, p = 32, squared L2.
+A step is one complete build: random initial graph plus T iterations of
+sampling, cross-matching and list update, where T is the first iteration after
+which Recall@10 (on a seeded sample of nodes, against exhaustive search) is at
+least 0.95; T is found in an untimed calibration build, then K builds are timed
+with the vectors resident in HBM.  Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0
+PEAK_FP32_TFLOPS = 157.3
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--n", type=int, default=1_000_000)
+    ap.add_argument("--d", type=int, default=128)
+    ap.add_argument("--k", type=int, default=32)
+    ap.add_argument("--p", type=int, default=32)
+    ap.add_argument("--max-iters", type=int, default=12)
+    ap.add_argument("--target", type=float, default=0.95)
+    ap.add_argument("--eval-nodes", type=int, default=2000)
+    ap.add_argument("--join", choices=["auto", "valu", "mfma"], default="auto")
+    ap.add_argument("--cpu-sample-n", type=int, default=40_000)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def cpu_baseline(args, iters):
+    """The oracle as it stands, timed on this host's cores on a cut of the same
+    generator (same d, k, p, same number of iterations)."""
+    import oracle as og
+    import workloads as W
+
+    cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")))
+    og.set_threads(cores)
+    n = min(args.cpu_sample_n, args.n)
+    x = W.sift_like_f32(n, args.d, seed=1002)
+    t0 = time.perf_counter()
+    g = og.init_random(x, args.k, og.L2SQ_F32, W.ALGO_SEED)
+    evals = 0
+    for it in range(1, iters + 1):
+        evals += og.iterate(x, og.L2SQ_F32, g, args.p, W.ALGO_SEED, it)["dist_evals"]
+    dt = time.perf_counter() - t0
+    return {"value": evals / dt, "unit": "dist_evals/s", "cores": cores, "kind": "oracle",
+            "build_s_on_sample": dt,
+            "sample": f"n={n} cut of the same generator, d={args.d}, k={args.k}, p={args.p}, "
+                      f"{iters} iterations, init + all stages"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding or collectives); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    import paper_2103_15386_amd as amd
+    import workloads as W
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    x = W.sift_like_f32(args.n, args.d, seed=1002)
+    xd = torch.from_numpy(x).to(dev)
+    del x
+    join_path = {"auto": amd.JOIN_AUTO, "valu": amd.JOIN_VALU, "mfma": amd.JOIN_MFMA}[args.join]
+    seed = W.ALGO_SEED
+
+    # ground truth for the recall evaluation: exhaustive search on sampled nodes
+    q = torch.from_numpy(W.sample_nodes(args.n, args.eval_nodes)).to(dev)
+    _, tdist = amd.exact_knn(xd, q, 10, amd.L2SQ_F32)
+    ql = q.long()
+
+    ctx = amd.Gnnd(xd, args.k, args.p, amd.L2SQ_F32, seed, join_path)
+
+    # calibration build (untimed): recall and per-stage times after every iteration
+    ctx.init_random()
+    trace, T = [], None
+    for it in range(1, args.max_iters + 1):
+        st = ctx.iterate()
+        _, dist = ctx.graph()
+        st["recall_at_10"] = amd.recall_at(dist[ql], tdist, 10)
+        trace.append(st)
+        if T is None and st["recall_at_10"] >= args.target:
+            T = it
+            break
+    reached = T is not None
+    if not reached:
+        T = args.max_iters
+    best = max(t["recall_at_10"] for t in trace)
+
+    stream = torch.cuda.current_stream(dev)
+
+    def one_build():
+        ctx.build(T, want_stats=False)
+
+    for _ in range(args.warmup):
+        one_build()
+    stream.synchronize()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_build()
+    stream.synchronize()
+    torch.cuda.synchronize()
+    build_s = (time.perf_counter() - t0) / args.steps
+
+    total_evals = sum(t["dist_evals"] for t in trace[:T])
+    join_ms = sum(t["ms_join"] for t in trace[:T])
+    sample_ms = sum(t["ms_sample"] for t in trace[:T])
+    update_ms = sum(t["ms_update"] for t in trace[:T])
+
+    # roofline of the dominant kernel (the join), per launch = per iteration:
+    # algorithmic bytes = every sampled vector read once per joined node
+    elem = 4
+    alg_bytes = sum((t["sum_new"] + t["sum_old"]) * args.d * elem for t in trace[:T]) / T
+    alg_flops = sum(t["dist_evals"] * args.d * 3 for t in trace[:T]) / T
+    avg_join_s = join_ms / T / 1e3
+    hbm = {"bound": "hbm", "achieved": alg_bytes / avg_join_s / 1e9, "peak": PEAK_HBM_GBS,
+           "unit": "GB/s", "traffic": None}
+    hbm["frac"] = hbm["achieved"] / hbm["peak"]
+    alu = {"bound": "alu", "achieved": alg_flops / avg_join_s / 1e12, "peak": PEAK_FP32_TFLOPS,
+           "unit": "TFLOP/s", "traffic": None}
+    alu["frac"] = alu["achieved"] / alu["peak"]
+    roof = alu if alu["frac"] >= hbm["frac"] else hbm
+    roof["kernel"] = "join"
+    roof["other_bound"] = hbm if roof is alu else alu
+
+    out = {
+        "metric": "build_seconds_to_recall@10>=%.2f" % args.target,
+        "value": build_s, "unit": "s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": build_s * 1e3, "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"sift-shaped GMM n={args.n} d={args.d} f32, k={args.k} "
+                               f"p={args.p}, squared L2, random init + {T} iterations",
+                   "join_path": args.join, "eval_nodes": args.eval_nodes},
+        "reached_target": reached, "iterations": T, "recall_at_10": trace[T - 1]["recall_at_10"],
+        "best_recall_at_10": best,
+        "dist_evals": total_evals, "dist_evals_per_s": total_evals / build_s,
+        "join_dist_evals_per_s": total_evals / (join_ms / 1e3),
+        "stage_ms": {"sample": sample_ms, "join": join_ms, "update": update_ms},
+        "per_iteration": [{k: (round(v, 4) if isinstance(v, float) else v) for k, v in t.items()}
+                          for t in trace],
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args, T)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
