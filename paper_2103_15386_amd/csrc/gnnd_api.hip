@@ -20,7 +20,7 @@ thread_local std::string g_last_error = "";
 struct Layout {
   size_t off_G, off_kth, off_snew, off_sold, off_cnew, off_cold, off_rcn, off_rco, off_ron,
       off_roo, off_csn, off_cso, off_pcnt, off_poff, off_pdest, off_pkey, off_bins, off_scan,
-      off_cnt, off_snap, off_aside, total;
+      off_cnt, off_snap, off_aside, off_shadow, off_norms, off_flag, total;
 };
 
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -38,6 +38,13 @@ const char* check_params(const gnnd_params* q) {
   if (q->join_path < GNND_JOIN_AUTO || q->join_path > GNND_JOIN_MFMA) return "unknown join_path";
   if (q->reserved != 0) return "reserved must be 0";
   return nullptr;
+}
+
+// The matrix-core join handles byte-valued data of up to 128 dimensions: uint8
+// vectors, or float32 vectors that turn out to hold only integers 0..255.
+bool mfma_possible(const gnnd_params* q) {
+  return q->join_path != GNND_JOIN_VALU && q->d <= 128 &&
+         (q->metric == GNND_L2SQ_U8 || q->metric == GNND_L2SQ_F32);
 }
 
 Layout make_layout(const gnnd_params* q, bool with_aside) {
@@ -70,6 +77,10 @@ Layout make_layout(const gnnd_params* q, bool with_aside) {
   L.off_cnt = take((size_t)kStripes * C_SLOTS * 8);
   L.off_snap = take((size_t)kStripes * C_SLOTS * 8);
   L.off_aside = take(with_aside ? n * (k / 2) * 8 : 0);
+  const bool shadow = mfma_possible(q);
+  L.off_shadow = take(shadow ? n * (size_t)((q->d + 31) & ~31) : 0);
+  L.off_norms = take(shadow ? n * 4 : 0);
+  L.off_flag = take(256);
   L.total = o;
   return L;
 }
@@ -85,6 +96,8 @@ struct gnnd_ctx {
   int stage;          // 0 = ready for sample, 1 = sampled, 2 = joined
   bool has_graph;
   bool merge_mode;
+  bool use_mfma;
+  int* flag_dev;
   hipEvent_t ev[4];
   bool have_events;
   uint64_t* snap;  // device copy of the counters taken when the iteration began
@@ -126,6 +139,9 @@ void bind(gnnd_ctx* c, const Layout& L) {
   d.counters = (uint64_t*)(w + L.off_cnt);
   d.aside = (uint64_t*)(w + L.off_aside);
   c->snap = (uint64_t*)(w + L.off_snap);
+  d.shadow = (int8_t*)(w + L.off_shadow);
+  d.norms = (int32_t*)(w + L.off_norms);
+  c->flag_dev = (int*)(w + L.off_flag);
 }
 
 // Shared by gnnd_create and gnnd_merge.
@@ -168,6 +184,29 @@ int create_impl(gnnd_ctx** out, const gnnd_params* prm, const void* vec_a, const
     int rc = hip_fail(nullptr, e, "clearing workspace counters");
     delete c;
     return rc;
+  }
+  // matrix-core path: build the int8 copy; float data qualifies only when every
+  // value is an integer in 0..255 (then all distances are exact either way)
+  c->use_mfma = false;
+  if (mfma_possible(prm)) {
+    int bad = 0;
+    e = launch_zero_u32((uint32_t*)c->flag_dev, 1, c->stream);
+    if (e == hipSuccess) e = launch_pack_i8(c->sh, c->ds, c->flag_dev, c->stream);
+    if (e == hipSuccess)
+      e = hipMemcpyAsync(&bad, c->flag_dev, sizeof bad, hipMemcpyDeviceToHost, c->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+    if (e != hipSuccess) {
+      int rc = hip_fail(nullptr, e, "packing vectors to int8");
+      delete c;
+      return rc;
+    }
+    c->use_mfma = (bad == 0);
+  }
+  if (prm->join_path == GNND_JOIN_MFMA && !c->use_mfma) {
+    delete c;
+    return fail(nullptr, GNND_EINVAL,
+                "GNND_JOIN_MFMA needs d <= 128 and uint8 vectors or float32 vectors holding "
+                "integers 0..255 with the squared-L2 metric");
   }
   *out = c;
   return GNND_OK;
@@ -218,7 +257,8 @@ int step_sample(gnnd_ctx* c) {
 }
 int step_join(gnnd_ctx* c) {
   if (c->stage != 1) return fail(c, GNND_ESTATE, "stage order is sample, join, update");
-  hipError_t e = launch_join(c->sh, c->ds, c->prm.join_path, c->merge_mode, c->stream);
+  hipError_t e = c->use_mfma ? launch_join_mfma(c->sh, c->ds, c->merge_mode, c->stream)
+                             : launch_join(c->sh, c->ds, c->prm.join_path, c->merge_mode, c->stream);
   if (e != hipSuccess) return hip_fail(c, e, "join kernel");
   c->stage = 2;
   return GNND_OK;

@@ -32,6 +32,8 @@ struct DevState {
   uint64_t* scan_tmp;  // block sums of the scans
   uint64_t* counters;  // kStripes * C_SLOTS
   uint64_t* aside;     // merge only: n * floor(k/2) set-aside entries
+  int8_t* shadow;      // matrix-core path: n rows of dpad int8 (value - 128), zero padded
+  int32_t* norms;      // matrix-core path: squared norm of every shadow row
 };
 
 struct Shape {
@@ -47,6 +49,8 @@ hipError_t launch_sample(const Shape& sh, const DevState& ds, uint64_t seed, uin
                          hipStream_t st);
 hipError_t launch_join(const Shape& sh, const DevState& ds, int path, bool merge_mode,
                        hipStream_t st);
+hipError_t launch_join_mfma(const Shape& sh, const DevState& ds, bool merge_mode, hipStream_t st);
+hipError_t launch_pack_i8(const Shape& sh, const DevState& ds, int* bad_flag_dev, hipStream_t st);
 hipError_t launch_update(const Shape& sh, const DevState& ds, hipStream_t st);
 hipError_t launch_get_graph(const Shape& sh, const DevState& ds, int32_t* ids, void* dist,
                             uint8_t* isnew, hipStream_t st);

@@ -61,13 +61,21 @@ def test_init_matches_oracle(name):
     ctx.close()
 
 
-@pytest.mark.parametrize("name", list(CASES))
-def test_every_stage_of_every_iteration_matches_oracle(name):
+MFMA_CASES = ["sift_cut", "u8_cut", "u8_d30", "sift_d100_k64", "u8_small_lists"]
+CASES["sift_d100_k64"] = (lambda: W.sift_like_f32(2000, 100, seed=1012, n_comp=8),
+                          og.L2SQ_F32, 64, 32, 4)
+CASES["u8_small_lists"] = (lambda: W.sift_like_u8(1500, 64, seed=1013, n_comp=4),
+                           og.L2SQ_U8, 8, 5, 5)
+
+
+@pytest.mark.parametrize("name,path", [(n, "valu") for n in CASES] +
+                         [(n, "mfma") for n in MFMA_CASES])
+def test_every_stage_of_every_iteration_matches_oracle(name, path):
     amd = _amd()
     gen, metric, k, p, iters = CASES[name]
     x = gen()
     n = len(x)
-    ctx = amd.Gnnd(_dev(x), k, p, metric, SEED, amd.JOIN_VALU)
+    ctx = amd.Gnnd(_dev(x), k, p, metric, SEED, amd.JOIN_VALU if path == "valu" else amd.JOIN_MFMA)
     ctx.init_random()
     g = og.init_random(x, k, metric, SEED)
     for it in range(1, iters + 1):
@@ -182,3 +190,5 @@ def test_errors_are_reported_not_fatal():
     ctx.close()
     with pytest.raises(amd.GnndError):
         amd.Gnnd(torch.zeros(100, 8), 10, 8)  # CPU tensor: no CPU path
+    with pytest.raises(amd.GnndError):  # matrix-core path refuses non-integer floats
+        amd.Gnnd(x, 10, 8, amd.L2SQ_F32, 42, amd.JOIN_MFMA)
