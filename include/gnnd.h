@@ -81,7 +81,8 @@ typedef struct gnnd_iter_stats {
   uint64_t dist_evals; /* distances evaluated by the cross-matching                */
   uint64_t sum_new;    /* total size of all NEW sample lists                       */
   uint64_t sum_old;    /* total size of all OLD sample lists                       */
-  uint64_t proposals;  /* nearest-object results handed to the list update         */
+  uint64_t proposals;  /* nearest-object results found (Alg. 2 outputs)            */
+  uint64_t dropped;    /* results lost to a full proposal segment: always 0        */
   float ms_sample, ms_join, ms_update;
   float reserved2;
 } gnnd_iter_stats;
@@ -139,12 +140,12 @@ int gnnd_set_graph(gnnd_ctx* ctx, const int32_t* ids_dev, const void* dist_dev,
 int gnnd_get_samples(gnnd_ctx* ctx, int32_t* new_dev, int32_t* cnt_new_dev, int32_t* old_dev,
                      int32_t* cnt_old_dev);
 
-/* Nearest-object results of the last gnnd_step_join (Alg. 2 outputs), dense:
- * n rows of 6p slots = [NEW u: nearest other NEW | NEW u: nearest OLD |
- * OLD u: nearest NEW], 2p slots each, slot i belonging to the i-th sample.
- * u_dev = list to insert into (-1 = no result, or dropped because it cannot
- * beat the list's last entry), v_dev = object to insert, dist_dev = distance
- * (float32 / int32 by metric). */
+/* Nearest-object results of the last gnnd_step_join (Alg. 2 outputs) that can
+ * still enter a list, i.e. whose distance does not exceed the distance of the
+ * destination list's last entry: three arrays of n*6p slots.  Results are
+ * grouped by destination list in no particular order; u_dev = list to insert
+ * into, or -1 for an unused slot; v_dev = object to insert; dist_dev = its
+ * distance (float32 / int32 by metric).  Valid between join and update only. */
 int gnnd_get_proposals(gnnd_ctx* ctx, int32_t* u_dev, int32_t* v_dev, void* dist_dev);
 
 /* GGM (Sec. 5.1, Alg. 3): merge the k-NN graph G1 of S1 (n1 vectors at

@@ -19,7 +19,7 @@ thread_local std::string g_last_error = "";
 
 struct Layout {
   size_t off_G, off_kth, off_snew, off_sold, off_cnew, off_cold, off_rcn, off_rco, off_ron,
-      off_roo, off_csn, off_cso, off_pcnt, off_poff, off_pdest, off_pkey, off_bins, off_scan,
+      off_roo, off_csn, off_cso, off_capn, off_capo, off_pcnt, off_poff, off_bins, off_scan,
       off_cnt, off_snap, off_aside, off_shadow, off_norms, off_flag, total;
 };
 
@@ -68,10 +68,10 @@ Layout make_layout(const gnnd_params* q, bool with_aside) {
   L.off_roo = take((n + 1) * 8);
   L.off_csn = take(n * p * 4);
   L.off_cso = take(n * p * 4);
+  L.off_capn = take(n * 4);
+  L.off_capo = take(n * 4);
   L.off_pcnt = take(n * 4);
   L.off_poff = take((n + 1) * 8);
-  L.off_pdest = take(n * 6 * p * 4);
-  L.off_pkey = take(n * 6 * p * 8);
   L.off_bins = take(n * 6 * p * 8);
   L.off_scan = take(scan_tmp_elems((int64_t)n) * 8);
   L.off_cnt = take((size_t)kStripes * C_SLOTS * 8);
@@ -132,8 +132,8 @@ void bind(gnnd_ctx* c, const Layout& L) {
   d.csr_old = (int32_t*)(w + L.off_cso);
   d.pcnt = (uint32_t*)(w + L.off_pcnt);
   d.poff = (uint64_t*)(w + L.off_poff);
-  d.prop_dest = (int32_t*)(w + L.off_pdest);
-  d.prop_key = (uint64_t*)(w + L.off_pkey);
+  d.capn = (uint32_t*)(w + L.off_capn);
+  d.capo = (uint32_t*)(w + L.off_capo);
   d.bins = (uint64_t*)(w + L.off_bins);
   d.scan_tmp = (uint64_t*)(w + L.off_scan);
   d.counters = (uint64_t*)(w + L.off_cnt);
@@ -240,6 +240,7 @@ int read_stats(gnnd_ctx* c, gnnd_iter_stats* out) {
   out->sum_new = tot[C_SUMNEW];
   out->sum_old = tot[C_SUMOLD];
   out->proposals = tot[C_PROPS];
+  out->dropped = tot[C_OVERFLOW];
   return GNND_OK;
 }
 

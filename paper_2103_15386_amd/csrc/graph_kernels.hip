@@ -121,6 +121,7 @@ __global__ __launch_bounds__(kBlock) void k_rev_select(int64_t n, int p, uint64_
                                                        const uint64_t* roff_old,
                                                        const int32_t* csr_new,
                                                        const int32_t* csr_old,
+                                                       uint32_t* capn, uint32_t* capo,
                                                        uint64_t* counters) {
   const int64_t v = wave_global_index();
   if (v >= n) return;
@@ -169,22 +170,17 @@ __global__ __launch_bounds__(kBlock) void k_rev_select(int64_t n, int p, uint64_
   if (lane == 0) {
     cnt[v] = count;
     counter_add(counters, kind ? C_SUMOLD : C_SUMNEW, v, (uint64_t)count);
+    // v can only sit in the sample list of a node that holds v as a forward
+    // sample (deg of them) or that v holds as one (nf): that bounds the number
+    // of joins v takes part in, hence the nearest-object results it can
+    // receive - two per join as a NEW sample, one as an OLD sample.
+    const uint64_t joins = deg + (uint64_t)nf;
+    if (kind) capo[v] = (uint32_t)joins;
+    else capn[v] = (uint32_t)(2 * joins);
   }
 }
 
 // ---------------------------------------------------------------------------
-// Proposals grouped by destination list (same count-down slot scheme).
-__global__ __launch_bounds__(kBlock) void k_prop_fill(int64_t slots, const int32_t* prop_dest,
-                                                      const uint64_t* prop_key, uint32_t* pcnt,
-                                                      const uint64_t* poff, uint64_t* bins) {
-  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (i >= slots) return;
-  const int32_t u = prop_dest[i];
-  if (u < 0) return;
-  uint32_t pos = atomicSub(&pcnt[u], 1u) - 1u;
-  bins[poff[u] + pos] = prop_key[i];
-}
-
 // Drop from `pk` (one candidate per lane, kKeyMax = none) what cannot enter the
 // ascending list `row` of k entries: not closer than its last entry, already
 // in it, or a repeat of another candidate.  Returns the survivors ascending.
@@ -211,14 +207,16 @@ __device__ inline uint64_t filter_candidates(uint64_t pk, uint64_t row, int k, i
 // objects, one entry per id - what inserting them one by one under a lock
 // gives in any order.  Admitted entries are flagged NEW.
 __global__ __launch_bounds__(kBlock) void k_update(int64_t n, int k, uint64_t* G, uint32_t* kth,
-                                                   const uint64_t* poff, const uint64_t* bins,
-                                                   uint64_t* counters) {
+                                                   uint32_t* pcnt, const uint64_t* poff,
+                                                   const uint64_t* bins, uint64_t* counters) {
   const int64_t u = wave_global_index();
   if (u >= n) return;
-  const uint64_t beg = poff[u];
-  const uint64_t cnt = poff[u + 1] - beg;
+  uint64_t cnt = pcnt[u];
   if (cnt == 0) return;
   const int lane = lane_id();
+  if (lane == 0) pcnt[u] = 0;  // ready for the next iteration
+  const uint64_t beg = poff[u], cap = poff[u + 1] - beg;
+  cnt = cnt < cap ? cnt : cap;
   uint64_t row = lane < k ? G[u * k + lane] : kKeyMax;
   bool changed = false;
   for (uint64_t c = 0; c < cnt; c += kWave) {
@@ -265,19 +263,31 @@ __global__ __launch_bounds__(kBlock) void k_set_graph(int64_t total, int k, uint
   if ((i % k) == k - 1) kth[i / k] = code;
 }
 
+// Copy the proposal segments out: slot j of destination u's segment holds u and
+// the proposed (object, distance) when filled, -1 otherwise.
 template <bool FLOAT>
-__global__ __launch_bounds__(kBlock) void k_get_proposals(int64_t slots,
-                                                          const int32_t* prop_dest,
-                                                          const uint64_t* prop_key, int32_t* u,
-                                                          int32_t* v, void* dist) {
-  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (i >= slots) return;
-  const int32_t dest = prop_dest[i];
-  const uint64_t e = prop_key[i];
-  u[i] = dest;
-  v[i] = dest < 0 ? -1 : (int32_t)entry_id(e);
-  if (FLOAT) reinterpret_cast<float*>(dist)[i] = dest < 0 ? 0.f : unord_f32(entry_code(e));
-  else reinterpret_cast<int32_t*>(dist)[i] = dest < 0 ? 0 : unord_i32(entry_code(e));
+__global__ __launch_bounds__(kBlock) void k_get_proposals(int64_t n, const uint32_t* pcnt,
+                                                          const uint64_t* poff,
+                                                          const uint64_t* bins, int32_t* u_out,
+                                                          int32_t* v_out, void* dist) {
+  const int64_t u = wave_global_index();
+  if (u >= n) return;
+  const uint64_t beg = poff[u], cap = poff[u + 1] - beg, cnt = pcnt[u];
+  for (uint64_t i = lane_id(); i < cap; i += kWave) {
+    const bool have = i < cnt;
+    const uint64_t e = have ? bins[beg + i] : 0ull;
+    u_out[beg + i] = have ? (int32_t)u : -1;
+    v_out[beg + i] = have ? (int32_t)entry_id(e) : -1;
+    if (FLOAT) reinterpret_cast<float*>(dist)[beg + i] = have ? unord_f32(entry_code(e)) : 0.f;
+    else reinterpret_cast<int32_t*>(dist)[beg + i] = have ? unord_i32(entry_code(e)) : 0;
+  }
+}
+
+// Slots beyond the last segment (the segments need not fill the whole array).
+__global__ __launch_bounds__(kBlock) void k_fill_i32(int32_t* p, const uint64_t* from,
+                                                     int64_t end, int32_t value) {
+  const int64_t i = (int64_t)(*from) + (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i < end) p[i] = value;
 }
 
 __global__ __launch_bounds__(kBlock) void k_zero_u32(uint32_t* p, size_t count) {
@@ -436,14 +446,15 @@ __device__ inline uint64_t block_exclusive_scan(uint64_t v, uint64_t* total) {
   return before + inc - v;
 }
 
-__global__ __launch_bounds__(kBlock) void k_scan_local(const uint32_t* in, uint64_t* out,
-                                                       uint64_t* bsum, int64_t count) {
+__global__ __launch_bounds__(kBlock) void k_scan_local(const uint32_t* in, const uint32_t* in2,
+                                                       uint64_t* out, uint64_t* bsum,
+                                                       int64_t count) {
   const int64_t i0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * kScanPerThread;
   uint32_t v[kScanPerThread];
   uint64_t sum = 0;
 #pragma unroll
   for (int j = 0; j < kScanPerThread; ++j) {
-    v[j] = (i0 + j < count) ? in[i0 + j] : 0u;
+    v[j] = (i0 + j < count) ? in[i0 + j] + (in2 ? in2[i0 + j] : 0u) : 0u;
     sum += v[j];
   }
   uint64_t total;
@@ -479,10 +490,10 @@ __global__ __launch_bounds__(kBlock) void k_scan_add(uint64_t* out, const uint64
 
 size_t scan_tmp_elems(int64_t count) { return (size_t)((count + 1 + kScanPerBlock - 1) / kScanPerBlock); }
 
-hipError_t launch_scan(const uint32_t* in, uint64_t* out, uint64_t* tmp, int64_t count,
-                       hipStream_t st) {
+hipError_t launch_scan(const uint32_t* in, const uint32_t* in2, uint64_t* out, uint64_t* tmp,
+                       int64_t count, hipStream_t st) {
   const int64_t nb = (count + 1 + kScanPerBlock - 1) / kScanPerBlock;
-  k_scan_local<<<(unsigned)nb, kBlock, 0, st>>>(in, out, tmp, count);
+  k_scan_local<<<(unsigned)nb, kBlock, 0, st>>>(in, in2, out, tmp, count);
   k_scan_bsum<<<1, kBlock, 0, st>>>(tmp, nb);
   k_scan_add<<<(unsigned)nb, kBlock, 0, st>>>(out, tmp, count);
   return hipGetLastError();
@@ -520,27 +531,24 @@ hipError_t launch_sample(const Shape& sh, const DevState& ds, uint64_t seed, uin
   const unsigned grid = blocks_for_waves(sh.n);
   k_sample_fwd<<<grid, kBlock, 0, st>>>(sh.n, sh.k, sh.p, ds.G, ds.snew, ds.sold, ds.cnew,
                                         ds.cold, ds.rcnt_new, ds.rcnt_old);
-  hipError_t e = launch_scan(ds.rcnt_new, ds.roff_new, ds.scan_tmp, sh.n, st);
+  hipError_t e = launch_scan(ds.rcnt_new, nullptr, ds.roff_new, ds.scan_tmp, sh.n, st);
   if (e != hipSuccess) return e;
-  e = launch_scan(ds.rcnt_old, ds.roff_old, ds.scan_tmp, sh.n, st);
+  e = launch_scan(ds.rcnt_old, nullptr, ds.roff_old, ds.scan_tmp, sh.n, st);
   if (e != hipSuccess) return e;
   k_rev_fill<<<grid, kBlock, 0, st>>>(sh.n, sh.p, ds.snew, ds.sold, ds.cnew, ds.cold,
                                       ds.rcnt_new, ds.rcnt_old, ds.roff_new, ds.roff_old,
                                       ds.csr_new, ds.csr_old);
   k_rev_select<<<dim3(grid, 2), kBlock, 0, st>>>(
       sh.n, sh.p, hash_base(seed, kTagRevNew), hash_base(seed, kTagRevOld), iter, ds.snew,
-      ds.sold, ds.cnew, ds.cold, ds.roff_new, ds.roff_old, ds.csr_new, ds.csr_old, ds.counters);
-  return hipGetLastError();
+      ds.sold, ds.cnew, ds.cold, ds.roff_new, ds.roff_old, ds.csr_new, ds.csr_old, ds.capn,
+      ds.capo, ds.counters);
+  // one segment of the proposal array per destination, sized by its bound
+  return launch_scan(ds.capn, ds.capo, ds.poff, ds.scan_tmp, sh.n, st);
 }
 
 hipError_t launch_update(const Shape& sh, const DevState& ds, hipStream_t st) {
-  hipError_t e = launch_scan(ds.pcnt, ds.poff, ds.scan_tmp, sh.n, st);
-  if (e != hipSuccess) return e;
-  const int64_t slots = sh.n * 6 * sh.p;
-  k_prop_fill<<<(unsigned)((slots + kBlock - 1) / kBlock), kBlock, 0, st>>>(
-      slots, ds.prop_dest, ds.prop_key, ds.pcnt, ds.poff, ds.bins);
-  k_update<<<blocks_for_waves(sh.n), kBlock, 0, st>>>(sh.n, sh.k, ds.G, ds.kth, ds.poff, ds.bins,
-                                                      ds.counters);
+  k_update<<<blocks_for_waves(sh.n), kBlock, 0, st>>>(sh.n, sh.k, ds.G, ds.kth, ds.pcnt, ds.poff,
+                                                      ds.bins, ds.counters);
   return hipGetLastError();
 }
 
@@ -566,12 +574,15 @@ hipError_t launch_set_graph(const Shape& sh, const DevState& ds, const int32_t* 
 
 hipError_t launch_get_proposals(const Shape& sh, const DevState& ds, int32_t* u, int32_t* v,
                                 void* dist, hipStream_t st) {
-  const int64_t slots = sh.n * 6 * sh.p;
-  const unsigned grid = (unsigned)((slots + kBlock - 1) / kBlock);
+  const unsigned grid = blocks_for_waves(sh.n);
   if (sh.metric == kL2U8)
-    k_get_proposals<false><<<grid, kBlock, 0, st>>>(slots, ds.prop_dest, ds.prop_key, u, v, dist);
+    k_get_proposals<false><<<grid, kBlock, 0, st>>>(sh.n, ds.pcnt, ds.poff, ds.bins, u, v, dist);
   else
-    k_get_proposals<true><<<grid, kBlock, 0, st>>>(slots, ds.prop_dest, ds.prop_key, u, v, dist);
+    k_get_proposals<true><<<grid, kBlock, 0, st>>>(sh.n, ds.pcnt, ds.poff, ds.bins, u, v, dist);
+  const int64_t slots = sh.n * 6 * sh.p;
+  const unsigned g2 = (unsigned)((slots + kBlock - 1) / kBlock);
+  k_fill_i32<<<g2, kBlock, 0, st>>>(u, ds.poff + sh.n, slots, -1);
+  k_fill_i32<<<g2, kBlock, 0, st>>>(v, ds.poff + sh.n, slots, -1);
   return hipGetLastError();
 }
 

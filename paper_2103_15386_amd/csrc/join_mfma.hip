@@ -124,8 +124,8 @@ __global__ __launch_bounds__(kMB) void k_join_mfma(
     const int8_t* __restrict__ shadow, const int32_t* __restrict__ norms, int dpad, int64_t n,
     int p, int64_t split, const int32_t* __restrict__ snew, const int32_t* __restrict__ sold,
     const int32_t* __restrict__ cnew, const int32_t* __restrict__ cold,
-    const uint32_t* __restrict__ kth, uint32_t* pcnt, int32_t* __restrict__ prop_dest,
-    uint64_t* __restrict__ prop_key, uint64_t* counters) {
+    const uint32_t* __restrict__ kth, uint32_t* pcnt, const uint64_t* __restrict__ poff,
+    uint64_t* __restrict__ bins, uint64_t* counters) {
   // per wave: norms of the 128 rows (NEW 0..63, OLD 64..127) and their ids
   __shared__ __attribute__((aligned(16))) int32_t s_norm[4][128];
   __shared__ int32_t s_id[4][128];
@@ -134,13 +134,8 @@ __global__ __launch_bounds__(kMB) void k_join_mfma(
   if (s >= n) return;
   const int L = 2 * p;
   const int nn = cnew[s], no = cold[s];
-  int32_t* out_dest = prop_dest + s * 3 * L;
-  uint64_t* out_key = prop_key + s * 3 * L;
   const bool do_nn = !MERGE && nn > 1;
-  if (nn == 0 || (!do_nn && no == 0)) {
-    for (int i = lane; i < 3 * L; i += kWave) out_dest[i] = -1;
-    return;
-  }
+  if (nn == 0 || (!do_nn && no == 0)) return;
   const int32_t id_new = lane < nn ? snew[s * L + lane] : -1;
   const int32_t id_old = lane < no ? sold[s * L + lane] : -1;
 
@@ -292,7 +287,7 @@ __global__ __launch_bounds__(kMB) void k_join_mfma(
   const int32_t ra = half ? a1 : a0, rb = half ? b1 : b0, rc = half ? c1 : c0;
 
   // lane l now answers for sample l of its list, three results
-  uint32_t found_total = 0;
+  uint32_t found_total = 0, over_total = 0;
 #pragma unroll
   for (int kind = 0; kind < 3; ++kind) {
     const int32_t res = kind == 0 ? ra : (kind == 1 ? rb : rc);
@@ -305,12 +300,15 @@ __global__ __launch_bounds__(kMB) void k_join_mfma(
     const int32_t other = found ? s_id[wave][(kind == 0 ? 0 : (kind == 1 ? 64 : 0)) + pos] : 0;
     const uint32_t code = FCODE ? ord_f32((float)dist) : ord_i32(dist);
     const bool pass = found && code <= kth[found ? self : 0];
-    if (lane < L) {
-      out_dest[kind * L + lane] = pass ? self : -1;
-      out_key[kind * L + lane] = make_entry(code, (uint32_t)other, 3u);
+    bool overflow = false;
+    if (pass) {  // into the destination's segment of the proposal array
+      const uint64_t beg = poff[self], cap = poff[self + 1] - beg;
+      const uint32_t pos = atomicAdd(&pcnt[self], 1u);
+      if (pos < cap) bins[beg + pos] = make_entry(code, (uint32_t)other, 3u);
+      else overflow = true;
     }
-    if (pass) atomicAdd(&pcnt[self], 1u);
     found_total += (uint32_t)__popcll(__ballot(found));
+    over_total += (uint32_t)__popcll(__ballot(overflow));
   }
   if (lane == 0) {
     uint64_t ev;
@@ -325,6 +323,8 @@ __global__ __launch_bounds__(kMB) void k_join_mfma(
     uint64_t* cs = counters + (s & (kStripes - 1)) * C_SLOTS;
     if (found_total) atomicAdd(reinterpret_cast<unsigned long long*>(cs + C_PROPS),
                                (unsigned long long)found_total);
+    if (over_total) atomicAdd(reinterpret_cast<unsigned long long*>(cs + C_OVERFLOW),
+                              (unsigned long long)over_total);
     if (ev) atomicAdd(reinterpret_cast<unsigned long long*>(cs + C_EVALS), (unsigned long long)ev);
   }
 }
@@ -333,7 +333,7 @@ template <int KSTEPS>
 static void launch_k(bool fcode, bool merge, unsigned grid, hipStream_t st, const int8_t* shadow,
                      const int32_t* norms, int dpad, const Shape& sh, const DevState& ds) {
 #define GNND_ARGS shadow, norms, dpad, sh.n, sh.p, sh.split, ds.snew, ds.sold, ds.cnew, ds.cold, \
-                  ds.kth, ds.pcnt, ds.prop_dest, ds.prop_key, ds.counters
+                  ds.kth, ds.pcnt, ds.poff, ds.bins, ds.counters
   if (fcode) {
     if (merge) k_join_mfma<KSTEPS, true, true><<<grid, kMB, 0, st>>>(GNND_ARGS);
     else k_join_mfma<KSTEPS, true, false><<<grid, kMB, 0, st>>>(GNND_ARGS);

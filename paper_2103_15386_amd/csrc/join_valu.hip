@@ -96,7 +96,7 @@ __global__ __launch_bounds__(kJB) void k_join_valu(
     VecSrc vs, int64_t n, int p, int merge_mode, const int32_t* __restrict__ snew,
     const int32_t* __restrict__ sold, const int32_t* __restrict__ cnew,
     const int32_t* __restrict__ cold, const uint32_t* __restrict__ kth, uint32_t* pcnt,
-    int32_t* __restrict__ prop_dest, uint64_t* __restrict__ prop_key, uint64_t* counters) {
+    const uint64_t* __restrict__ poff, uint64_t* __restrict__ bins, uint64_t* counters) {
   using TR = JoinTraits<METRIC>;
   using T = typename TR::elem;
   using ACC = typename TR::acc;
@@ -108,8 +108,6 @@ __global__ __launch_bounds__(kJB) void k_join_valu(
   const int tid = threadIdx.x;
   const int L = 2 * p;
   const int nn = cnew[s], no = cold[s];
-  int32_t* out_dest = prop_dest + s * 3 * L;
-  uint64_t* out_key = prop_key + s * 3 * L;
 
   if (tid < 128) {
     int32_t id = -1;
@@ -121,10 +119,7 @@ __global__ __launch_bounds__(kJB) void k_join_valu(
     ids[tid] = id;
   }
   const bool do_nn = !merge_mode && nn > 1;
-  if (nn == 0 || (!do_nn && no == 0)) {  // nothing to evaluate: all slots empty
-    for (int i = tid; i < 3 * L; i += kJB) out_dest[i] = -1;
-    return;
-  }
+  if (nn == 0 || (!do_nn && no == 0)) return;  // nothing to evaluate
   __syncthreads();
 
   const int tx = tid & 15, ty = tid >> 4;
@@ -259,17 +254,24 @@ __global__ __launch_bounds__(kJB) void k_join_valu(
   const bool found = best != kKeyMax;
   // a result that cannot beat the last entry of the destination list is dropped here
   const bool pass = found && (uint32_t)(best >> 32) <= kth[self < 0 ? 0 : self];
-  if (lane < L) {
-    out_dest[wave * L + lane] = pass ? self : -1;
-    out_key[wave * L + lane] = make_entry((uint32_t)(best >> 32), (uint32_t)best, 3u);
+  // hand the result to the destination's segment of the proposal array
+  bool overflow = false;
+  if (pass) {
+    const uint64_t beg = poff[self], cap = poff[self + 1] - beg;
+    const uint32_t pos = atomicAdd(&pcnt[self], 1u);
+    if (pos < cap) bins[beg + pos] = make_entry((uint32_t)(best >> 32), (uint32_t)best, 3u);
+    else overflow = true;
   }
-  if (pass) atomicAdd(&pcnt[self], 1u);
+  const uint64_t nover = __popcll(__ballot(overflow));
   const uint64_t nfound = __popcll(__ballot(found));
   if (wave == 1) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) evaluated += __shfl_xor(evaluated, off, kWave);
   }
   if (lane == 0) {
+    if (nover) atomicAdd(reinterpret_cast<unsigned long long*>(
+                             counters + (s & (kStripes - 1)) * C_SLOTS + C_OVERFLOW),
+                         (unsigned long long)nover);
     if (nfound) atomicAdd(reinterpret_cast<unsigned long long*>(
                               counters + (s & (kStripes - 1)) * C_SLOTS + C_PROPS),
                           (unsigned long long)nfound);
@@ -291,17 +293,17 @@ hipError_t launch_join(const Shape& sh, const DevState& ds, int path, bool merge
     case kL2F32:
       k_join_valu<kL2F32><<<grid, kJB, 0, st>>>(vs, sh.n, sh.p, merge_mode ? 1 : 0, ds.snew,
                                                 ds.sold, ds.cnew, ds.cold, ds.kth, ds.pcnt,
-                                                ds.prop_dest, ds.prop_key, ds.counters);
+                                                ds.poff, ds.bins, ds.counters);
       break;
     case kAngularF32:
       k_join_valu<kAngularF32><<<grid, kJB, 0, st>>>(vs, sh.n, sh.p, merge_mode ? 1 : 0, ds.snew,
                                                      ds.sold, ds.cnew, ds.cold, ds.kth, ds.pcnt,
-                                                     ds.prop_dest, ds.prop_key, ds.counters);
+                                                     ds.poff, ds.bins, ds.counters);
       break;
     default:
       k_join_valu<kL2U8><<<grid, kJB, 0, st>>>(vs, sh.n, sh.p, merge_mode ? 1 : 0, ds.snew,
                                                ds.sold, ds.cnew, ds.cold, ds.kth, ds.pcnt,
-                                               ds.prop_dest, ds.prop_key, ds.counters);
+                                               ds.poff, ds.bins, ds.counters);
   }
   return hipGetLastError();
 }

@@ -7,7 +7,11 @@
 
 namespace gnnd {
 
-enum : int { C_INSERTS = 0, C_EVALS = 1, C_SUMNEW = 2, C_SUMOLD = 3, C_PROPS = 4, C_SLOTS = 8 };
+enum : int {
+  C_INSERTS = 0, C_EVALS = 1, C_SUMNEW = 2, C_SUMOLD = 3, C_PROPS = 4,
+  C_OVERFLOW = 5,  // proposals that found their destination segment full (must stay 0)
+  C_SLOTS = 8
+};
 constexpr int kStripes = 64;  // counters are striped to spread same-address atomics
 
 // Everything lives in the caller's workspace; sizes in elements.
@@ -24,11 +28,11 @@ struct DevState {
   uint64_t* roff_old;  // n+1
   int32_t* csr_new;    // n*p reverse candidates grouped by target
   int32_t* csr_old;    // n*p
-  uint32_t* pcnt;      // n proposals per destination (zero between iterations)
-  uint64_t* poff;      // n+1 offsets into bins
-  int32_t* prop_dest;  // n*6p dense proposal slots: destination list or -1
-  uint64_t* prop_key;  // n*6p: packed (distance, object, flags) of the slot
-  uint64_t* bins;      // n*6p proposals grouped by destination
+  uint32_t* capn;      // n: upper bound of the proposals a node can receive as a NEW sample
+  uint32_t* capo;      // n: ... as an OLD sample
+  uint32_t* pcnt;      // n proposals received per destination (zero between iterations)
+  uint64_t* poff;      // n+1 segment offsets into bins (exclusive scan of capn + capo)
+  uint64_t* bins;      // n*6p packed proposals, one segment per destination
   uint64_t* scan_tmp;  // block sums of the scans
   uint64_t* counters;  // kStripes * C_SLOTS
   uint64_t* aside;     // merge only: n * floor(k/2) set-aside entries
@@ -69,8 +73,9 @@ hipError_t launch_exact_knn(const void* vec, int64_t n, int32_t d, int32_t metri
 hipError_t launch_zero_u32(uint32_t* p, size_t count, hipStream_t st);
 
 // Exclusive scan of `count` uint32 into uint64 offsets out[0..count] (out[count] = total).
-hipError_t launch_scan(const uint32_t* in, uint64_t* out, uint64_t* tmp, int64_t count,
-                       hipStream_t st);
+// (in2 may be NULL; otherwise the scanned values are in[i] + in2[i])
+hipError_t launch_scan(const uint32_t* in, const uint32_t* in2, uint64_t* out, uint64_t* tmp,
+                       int64_t count, hipStream_t st);
 size_t scan_tmp_elems(int64_t count);
 
 }  // namespace gnnd

@@ -44,6 +44,7 @@ def test_merge_matches_oracle(metric, gen, k, p, n1, iters, path):
     for a, b in zip(stats[:iters], wstats):
         for key in ("inserts", "dist_evals", "sum_new", "sum_old", "proposals"):
             assert a[key] == b[key], (key, a, b)
+        assert a["dropped"] == 0
 
 
 def test_merge_rejects_bad_arguments():
