@@ -191,27 +191,38 @@ static void draw_distinct(uint64_t seed, uint32_t tag, uint32_t s, int count, ui
  * Reading: the listing says "p random objects" but the list has fixed degree k
  * (Sec. 4, first paragraphs; Sec. 3.1 step 1 says k random neighbours), so k
  * distinct ids other than s are drawn; "ascending" = by (distance, id). */
+static void init_row(const void* vec, int64_t n, int d, int k, int metric, uint64_t seed,
+                     int64_t s, entry_t* row, int32_t* draw, int32_t* ids, double* dist,
+                     uint8_t* isnew) {
+  draw_distinct(seed, OG_TAG_INIT, (uint32_t)s, k, (uint32_t)n, 0, (int32_t)s, draw);
+  for (int j = 0; j < k; ++j) {
+    row[j].id = draw[j];
+    row[j].d = og_distance(metric, d, vec, s, draw[j]);
+    row[j].isnew = 1;
+    row[j].fresh = 0;
+  }
+  qsort(row, (size_t)k, sizeof(entry_t), entry_cmp);
+  for (int j = 0; j < k; ++j) {
+    ids[j] = row[j].id;
+    dist[j] = row[j].d;
+    isnew[j] = 1;
+  }
+}
+
+/* Rows are independent of each other, so the loop may run on several threads. */
 void og_init_random(const void* vec, int64_t n, int d, int k, int metric, uint64_t seed,
                     int32_t* ids, double* dist, uint8_t* isnew) {
-  entry_t* row = (entry_t*)malloc(sizeof(entry_t) * (size_t)k);
-  int32_t* draw = (int32_t*)malloc(sizeof(int32_t) * (size_t)k);
-  for (int64_t s = 0; s < n; ++s) {
-    draw_distinct(seed, OG_TAG_INIT, (uint32_t)s, k, (uint32_t)n, 0, (int32_t)s, draw);
-    for (int j = 0; j < k; ++j) {
-      row[j].id = draw[j];
-      row[j].d = og_distance(metric, d, vec, s, draw[j]);
-      row[j].isnew = 1;
-      row[j].fresh = 0;
-    }
-    qsort(row, (size_t)k, sizeof(entry_t), entry_cmp);
-    for (int j = 0; j < k; ++j) {
-      ids[s * k + j] = row[j].id;
-      dist[s * k + j] = row[j].d;
-      isnew[s * k + j] = 1;
-    }
+#pragma omp parallel
+  {
+    entry_t* row = (entry_t*)malloc(sizeof(entry_t) * (size_t)k);
+    int32_t* draw = (int32_t*)malloc(sizeof(int32_t) * (size_t)k);
+#pragma omp for schedule(static)
+    for (int64_t s = 0; s < n; ++s)
+      init_row(vec, n, d, k, metric, seed, s, row, draw, ids + s * k, dist + s * k,
+               isnew + s * k);
+    free(row);
+    free(draw);
   }
-  free(row);
-  free(draw);
 }
 
 /* ------------------------------------------------------------------------- */
