@@ -23,6 +23,7 @@ if ROOT not in sys.path:
 
 PEAK_HBM_GBS = 8000.0
 PEAK_FP32_TFLOPS = 157.3
+PEAK_INT8_TOPS = 5000.0
 
 
 def parse():
@@ -40,6 +41,9 @@ def parse():
     ap.add_argument("--join", choices=["auto", "valu", "mfma"], default="auto")
     ap.add_argument("--cpu-sample-n", type=int, default=40_000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calib-mib", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (a dispatch of known "
+                         "size to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters with)")
     return ap.parse_args()
 
 
@@ -81,6 +85,12 @@ def main():
     x = W.sift_like_f32(args.n, args.d, seed=1002)
     xd = torch.from_numpy(x).to(dev)
     del x
+    if args.copy_calib_mib:
+        src = torch.empty(args.copy_calib_mib << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     join_path = {"auto": amd.JOIN_AUTO, "valu": amd.JOIN_VALU, "mfma": amd.JOIN_MFMA}[args.join]
     seed = W.ALGO_SEED
 
@@ -108,12 +118,15 @@ def main():
     best = max(t["recall_at_10"] for t in trace)
 
     stream = torch.cuda.current_stream(dev)
+    mfma = ctx.join_path() == amd.JOIN_MFMA
 
     def one_build():
         ctx.build(T, want_stats=False)
 
     for _ in range(args.warmup):
         one_build()
+    # stage events are recorded on the stream inside the timed builds (no sync in the loop)
+    ctx.set_profiling(True)
     stream.synchronize()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -122,36 +135,55 @@ def main():
     stream.synchronize()
     torch.cuda.synchronize()
     build_s = (time.perf_counter() - t0) / args.steps
+    n_rec, sample_ms, join_ms, update_ms = ctx.stage_ms()
+    assert n_rec == T * args.steps, (n_rec, T, args.steps)
+    sample_ms, join_ms, update_ms = (v / args.steps for v in (sample_ms, join_ms, update_ms))
 
     total_evals = sum(t["dist_evals"] for t in trace[:T])
-    join_ms = sum(t["ms_join"] for t in trace[:T])
-    sample_ms = sum(t["ms_sample"] for t in trace[:T])
-    update_ms = sum(t["ms_update"] for t in trace[:T])
 
-    # roofline of the dominant kernel (the join), per launch = per iteration:
-    # algorithmic bytes = every sampled vector read once per joined node
-    elem = 4
-    alg_bytes = sum((t["sum_new"] + t["sum_old"]) * args.d * elem for t in trace[:T]) / T
-    alg_flops = sum(t["dist_evals"] * args.d * 3 for t in trace[:T]) / T
+    # Roofline of the dominant kernel, the cross-matching join; one launch = one
+    # iteration.  Algorithmic bytes per launch: every sampled vector is read once
+    # per joined node (d elements of e bytes: e = 1 for the int8 copy the
+    # matrix-core kernel reads, 4 for float32) plus its 4-byte id.
+    # Algorithmic operations: 3 per dimension and evaluated pair in the direct
+    # form (subtract, multiply, add), 2 in the Gram form.
+    elem = 1 if mfma else 4
+    drow = ((args.d + 31) // 32 * 32) if mfma else args.d
+    vectors = sum(t["sum_new"] + t["sum_old"] for t in trace[:T]) / T
+    alg_bytes = vectors * (drow * elem + 4)
     avg_join_s = join_ms / T / 1e3
     hbm = {"bound": "hbm", "achieved": alg_bytes / avg_join_s / 1e9, "peak": PEAK_HBM_GBS,
            "unit": "GB/s", "traffic": None}
     hbm["frac"] = hbm["achieved"] / hbm["peak"]
-    alu = {"bound": "alu", "achieved": alg_flops / avg_join_s / 1e12, "peak": PEAK_FP32_TFLOPS,
-           "unit": "TFLOP/s", "traffic": None}
-    alu["frac"] = alu["achieved"] / alu["peak"]
-    roof = alu if alu["frac"] >= hbm["frac"] else hbm
-    roof["kernel"] = "join"
-    roof["other_bound"] = hbm if roof is alu else alu
+    if mfma:
+        ops = total_evals / T * args.d * 2
+        other = {"bound": "mfma", "achieved": ops / avg_join_s / 1e12, "peak": PEAK_INT8_TOPS,
+                 "unit": "TOP/s"}
+    else:
+        ops = total_evals / T * args.d * 3
+        other = {"bound": "alu", "achieved": ops / avg_join_s / 1e12, "peak": PEAK_FP32_TFLOPS,
+                 "unit": "TFLOP/s"}
+    other["frac"] = other["achieved"] / other["peak"]
+    roof = dict(hbm)
+    if other["frac"] > hbm["frac"]:
+        roof = dict(other)
+        roof["traffic"] = None
+        roof["other_bound"] = hbm
+    else:
+        roof["other_bound"] = other
+    roof["kernel"] = "k_join_mfma" if mfma else "k_join_valu"
+    roof["avg_launch_ms"] = avg_join_s * 1e3
+    roof["algorithmic_bytes_per_launch"] = alg_bytes
 
     out = {
         "metric": "build_seconds_to_recall@10>=%.2f" % args.target,
         "value": build_s, "unit": "s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": build_s * 1e3, "higher_is_better": False, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "vs_baseline": None, "dtype": "i8" if mfma else "f32",
+        "data": "synthetic",
         "config": {"workload": f"sift-shaped GMM n={args.n} d={args.d} f32, k={args.k} "
                                f"p={args.p}, squared L2, random init + {T} iterations",
-                   "join_path": args.join, "eval_nodes": args.eval_nodes},
+                   "join_path": "mfma_i8" if mfma else "valu", "eval_nodes": args.eval_nodes},
         "reached_target": reached, "iterations": T, "recall_at_10": trace[T - 1]["recall_at_10"],
         "best_recall_at_10": best,
         "dist_evals": total_evals, "dist_evals_per_s": total_evals / build_s,

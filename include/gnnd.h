@@ -101,6 +101,25 @@ void gnnd_destroy(gnnd_ctx* ctx);
  * context-free call when ctx is NULL).  Never NULL. */
 const char* gnnd_last_error(const gnnd_ctx* ctx);
 
+/* Which evaluation of the cross-matching distances (Sec. 4.2) this context
+ * uses: GNND_JOIN_VALU or GNND_JOIN_MFMA (GNND_JOIN_AUTO resolved at creation:
+ * the matrix-core form is taken when it is exact - squared L2, d <= 128, uint8
+ * vectors or float32 vectors holding only integers 0..255).  Negative on a
+ * NULL context. */
+int gnnd_join_path(const gnnd_ctx* ctx);
+
+/* Stage timing without synchronising inside the loop.  While profiling is on,
+ * every iteration that is run without statistics (gnnd_iterate with NULL,
+ * gnnd_build) records four HIP events on the stream - before sampling, before
+ * the cross-matching, before the update, after it - for up to 64 iterations
+ * since the last call of gnnd_set_profiling / gnnd_get_stage_ms.
+ * gnnd_get_stage_ms synchronises the stream, returns the number of recorded
+ * iterations and the summed milliseconds of each stage over them (all host
+ * pointers, required), and starts a new recording window. */
+int gnnd_set_profiling(gnnd_ctx* ctx, int on);
+int gnnd_get_stage_ms(gnnd_ctx* ctx, int32_t* count_host, float* ms_sample_host,
+                      float* ms_join_host, float* ms_update_host);
+
 /* Alg. 1, first loop: every list gets k distinct random objects other than the
  * node itself, with their distances, ascending by (distance, id), all flagged
  * NEW.  Resets the iteration counter to 0. */

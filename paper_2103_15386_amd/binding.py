@@ -19,7 +19,7 @@ EXPORTS = [
     "gnnd_workspace_bytes", "gnnd_create", "gnnd_destroy", "gnnd_last_error", "gnnd_init_random",
     "gnnd_iterate", "gnnd_step_sample", "gnnd_step_join", "gnnd_step_update", "gnnd_build",
     "gnnd_get_graph", "gnnd_set_graph", "gnnd_get_samples", "gnnd_get_proposals", "gnnd_merge",
-    "gnnd_exact_knn",
+    "gnnd_exact_knn", "gnnd_join_path", "gnnd_set_profiling", "gnnd_get_stage_ms",
 ]
 
 
@@ -89,6 +89,13 @@ def load_library():
     lib.gnnd_get_proposals.argtypes = [vp, vp, vp, vp]
     lib.gnnd_merge.restype = C.c_int
     lib.gnnd_merge.argtypes = [PP, vp, i64, vp, i64, vp, vp, vp, vp, i32, vp, vp, SP]
+    lib.gnnd_join_path.restype = C.c_int
+    lib.gnnd_join_path.argtypes = [vp]
+    lib.gnnd_set_profiling.restype = C.c_int
+    lib.gnnd_set_profiling.argtypes = [vp, C.c_int]
+    lib.gnnd_get_stage_ms.restype = C.c_int
+    lib.gnnd_get_stage_ms.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_float), C.POINTER(C.c_float),
+                                      C.POINTER(C.c_float)]
     lib.gnnd_exact_knn.restype = C.c_int
     lib.gnnd_exact_knn.argtypes = [vp, i64, i32, i32, vp, i64, i32, vp, vp, vp]
     _lib = lib
@@ -170,6 +177,20 @@ class Gnnd:
             self._ctx = None
 
     __del__ = close
+
+    def join_path(self):
+        """JOIN_VALU or JOIN_MFMA: the distance evaluation this context resolved to."""
+        return int(self._lib.gnnd_join_path(self._ctx))
+
+    def set_profiling(self, on=True):
+        _check(self._lib.gnnd_set_profiling(self._ctx, int(on)), self._ctx)
+
+    def stage_ms(self):
+        """(iterations recorded, ms sampling, ms cross-matching, ms update) since the last call."""
+        cnt, a, b, c = C.c_int32(), C.c_float(), C.c_float(), C.c_float()
+        _check(self._lib.gnnd_get_stage_ms(self._ctx, C.byref(cnt), C.byref(a), C.byref(b),
+                                           C.byref(c)), self._ctx)
+        return cnt.value, a.value, b.value, c.value
 
     def init_random(self):
         _check(self._lib.gnnd_init_random(self._ctx), self._ctx)

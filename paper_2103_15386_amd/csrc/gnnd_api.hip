@@ -87,6 +87,8 @@ Layout make_layout(const gnnd_params* q, bool with_aside) {
 
 }  // namespace
 
+constexpr int kProfIters = 64;
+
 struct gnnd_ctx {
   gnnd_params prm;
   Shape sh;
@@ -100,6 +102,11 @@ struct gnnd_ctx {
   int* flag_dev;
   hipEvent_t ev[4];
   bool have_events;
+  // profiling mode: four events per iteration, recorded without synchronising
+  bool prof_on;
+  int prof_count;
+  hipEvent_t prof[kProfIters][4];
+  bool have_prof;
   uint64_t* snap;  // device copy of the counters taken when the iteration began
   std::string err;
 };
@@ -173,6 +180,9 @@ int create_impl(gnnd_ctx** out, const gnnd_params* prm, const void* vec_a, const
   c->has_graph = false;
   c->merge_mode = merge_mode;
   c->have_events = false;
+  c->prof_on = false;
+  c->prof_count = 0;
+  c->have_prof = false;
   bind(c, L);
   // counters that must start at zero (they return to zero after every iteration)
   hipError_t e = launch_zero_u32(c->ds.rcnt_new, (size_t)prm->n, c->stream);
@@ -275,6 +285,18 @@ int step_update(gnnd_ctx* c) {
 
 int iterate_impl(gnnd_ctx* c, gnnd_iter_stats* out) {
   int rc;
+  if (!out && c->prof_on && c->prof_count < kProfIters) {
+    hipEvent_t* ev = c->prof[c->prof_count];
+    (void)hipEventRecord(ev[0], c->stream);
+    if ((rc = step_sample(c)) != GNND_OK) return rc;
+    (void)hipEventRecord(ev[1], c->stream);
+    if ((rc = step_join(c)) != GNND_OK) return rc;
+    (void)hipEventRecord(ev[2], c->stream);
+    if ((rc = step_update(c)) != GNND_OK) return rc;
+    (void)hipEventRecord(ev[3], c->stream);
+    c->prof_count += 1;
+    return GNND_OK;
+  }
   if (out) {
     if ((rc = ensure_events(c)) != GNND_OK) return rc;
     (void)hipEventRecord(c->ev[0], c->stream);
@@ -311,10 +333,55 @@ void gnnd_destroy(gnnd_ctx* c) {
   if (!c) return;
   if (c->have_events)
     for (int i = 0; i < 4; ++i) (void)hipEventDestroy(c->ev[i]);
+  if (c->have_prof)
+    for (int t = 0; t < kProfIters; ++t)
+      for (int i = 0; i < 4; ++i) (void)hipEventDestroy(c->prof[t][i]);
   delete c;
 }
 
 const char* gnnd_last_error(const gnnd_ctx* c) { return c ? c->err.c_str() : g_last_error.c_str(); }
+
+int gnnd_join_path(const gnnd_ctx* c) {
+  if (!c) return GNND_EINVAL;
+  return c->use_mfma ? GNND_JOIN_MFMA : GNND_JOIN_VALU;
+}
+
+int gnnd_set_profiling(gnnd_ctx* c, int on) {
+  if (!c) return fail(nullptr, GNND_EINVAL, "ctx is NULL");
+  if (on && !c->have_prof) {
+    for (int t = 0; t < kProfIters; ++t)
+      for (int i = 0; i < 4; ++i) {
+        hipError_t e = hipEventCreate(&c->prof[t][i]);
+        if (e != hipSuccess) return hip_fail(c, e, "hipEventCreate");
+      }
+    c->have_prof = true;
+  }
+  c->prof_on = on != 0;
+  c->prof_count = 0;
+  return GNND_OK;
+}
+
+int gnnd_get_stage_ms(gnnd_ctx* c, int32_t* count, float* ms_sample, float* ms_join,
+                      float* ms_update) {
+  if (!c) return fail(nullptr, GNND_EINVAL, "ctx is NULL");
+  if (!count || !ms_sample || !ms_join || !ms_update)
+    return fail(c, GNND_EINVAL, "NULL output pointer");
+  hipError_t e = hipStreamSynchronize(c->stream);
+  if (e != hipSuccess) return hip_fail(c, e, "hipStreamSynchronize");
+  *count = c->prof_count;
+  *ms_sample = *ms_join = *ms_update = 0.f;
+  for (int t = 0; t < c->prof_count; ++t) {
+    float a = 0, b = 0, d = 0;
+    (void)hipEventElapsedTime(&a, c->prof[t][0], c->prof[t][1]);
+    (void)hipEventElapsedTime(&b, c->prof[t][1], c->prof[t][2]);
+    (void)hipEventElapsedTime(&d, c->prof[t][2], c->prof[t][3]);
+    *ms_sample += a;
+    *ms_join += b;
+    *ms_update += d;
+  }
+  c->prof_count = 0;
+  return GNND_OK;
+}
 
 int gnnd_init_random(gnnd_ctx* c) {
   if (!c) return fail(nullptr, GNND_EINVAL, "ctx is NULL");
