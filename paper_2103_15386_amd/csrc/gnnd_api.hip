@@ -57,7 +57,7 @@ Layout make_layout(const gnnd_params* q, bool with_aside) {
     return at;
   };
   L.off_G = take(n * k * 8);
-  L.off_kth = take(n * 4);
+  L.off_kth = take(n * sizeof(NodeMeta));
   L.off_snew = take(n * 2 * p * 4);
   L.off_sold = take(n * 2 * p * 4);
   L.off_cnew = take(n * 4);
@@ -79,7 +79,7 @@ Layout make_layout(const gnnd_params* q, bool with_aside) {
   L.off_aside = take(with_aside ? n * (k / 2) * 8 : 0);
   const bool shadow = mfma_possible(q);
   L.off_shadow = take(shadow ? n * (size_t)((q->d + 31) & ~31) : 0);
-  L.off_norms = take(shadow ? n * 4 : 0);
+  L.off_norms = 0;
   L.off_flag = take(256);
   L.total = o;
   return L;
@@ -126,7 +126,7 @@ void bind(gnnd_ctx* c, const Layout& L) {
   char* w = (char*)c->prm.workspace_dev;
   DevState& d = c->ds;
   d.G = (uint64_t*)(w + L.off_G);
-  d.kth = (uint32_t*)(w + L.off_kth);
+  d.meta = (NodeMeta*)(w + L.off_kth);
   d.snew = (int32_t*)(w + L.off_snew);
   d.sold = (int32_t*)(w + L.off_sold);
   d.cnew = (int32_t*)(w + L.off_cnew);
@@ -147,7 +147,6 @@ void bind(gnnd_ctx* c, const Layout& L) {
   d.aside = (uint64_t*)(w + L.off_aside);
   c->snap = (uint64_t*)(w + L.off_snap);
   d.shadow = (int8_t*)(w + L.off_shadow);
-  d.norms = (int32_t*)(w + L.off_norms);
   c->flag_dev = (int*)(w + L.off_flag);
 }
 

@@ -30,7 +30,7 @@ __device__ inline void counter_add(uint64_t* counters, int which, int64_t stripe
 template <int METRIC>
 __global__ __launch_bounds__(kBlock) void k_init_random(VecSrc vs, int64_t n, int k,
                                                         uint64_t base_hash, uint64_t* G,
-                                                        uint32_t* kth) {
+                                                        NodeMeta* meta) {
   using D = DistOf<METRIC>;
   using T = typename D::elem;
   const int64_t s = wave_global_index();
@@ -44,7 +44,7 @@ __global__ __launch_bounds__(kBlock) void k_init_random(VecSrc vs, int64_t n, in
   }
   e = wave_sort(e, lane);
   if (lane < k) G[s * k + lane] = e;
-  if (lane == k - 1) kth[s] = entry_code(e);
+  if (lane == k - 1) meta[s].kth = entry_code(e);
 }
 
 // ---------------------------------------------------------------------------
@@ -206,7 +206,7 @@ __device__ inline uint64_t filter_candidates(uint64_t pk, uint64_t row, int k, i
 // list becomes the best k, by (distance, id), of its entries and the proposed
 // objects, one entry per id - what inserting them one by one under a lock
 // gives in any order.  Admitted entries are flagged NEW.
-__global__ __launch_bounds__(kBlock) void k_update(int64_t n, int k, uint64_t* G, uint32_t* kth,
+__global__ __launch_bounds__(kBlock) void k_update(int64_t n, int k, uint64_t* G, NodeMeta* meta,
                                                    uint32_t* pcnt, const uint64_t* poff,
                                                    const uint64_t* bins, uint64_t* counters) {
   const int64_t u = wave_global_index();
@@ -231,7 +231,7 @@ __global__ __launch_bounds__(kBlock) void k_update(int64_t n, int k, uint64_t* G
   if (!changed) return;
   const uint64_t admitted = __ballot(lane < k && (row & 2ull));
   if (lane < k) G[u * k + lane] = row & ~2ull;
-  if (lane == k - 1) kth[u] = entry_code(row);
+  if (lane == k - 1) meta[u].kth = entry_code(row);
   if (lane == 0) counter_add(counters, C_INSERTS, u, (uint64_t)__popcll(admitted));
 }
 
@@ -253,14 +253,14 @@ __global__ __launch_bounds__(kBlock) void k_get_graph(int64_t total, const uint6
 
 template <bool FLOAT>
 __global__ __launch_bounds__(kBlock) void k_set_graph(int64_t total, int k, uint64_t* G,
-                                                      uint32_t* kth, const int32_t* ids,
+                                                      NodeMeta* meta, const int32_t* ids,
                                                       const void* dist, const uint8_t* isnew) {
   const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i >= total) return;
   uint32_t code = FLOAT ? ord_f32(reinterpret_cast<const float*>(dist)[i])
                         : ord_i32(reinterpret_cast<const int32_t*>(dist)[i]);
   G[i] = make_entry(code, (uint32_t)ids[i], isnew ? (uint32_t)(isnew[i] & 1) : 0u);
-  if ((i % k) == k - 1) kth[i / k] = code;
+  if ((i % k) == k - 1) meta[i / k].kth = code;
 }
 
 // Copy the proposal segments out: slot j of destination u's segment holds u and
@@ -304,7 +304,7 @@ __global__ __launch_bounds__(kBlock) void k_merge_init(VecSrc vs, int64_t n, int
                                                        uint64_t base_hash, const int32_t* ids1,
                                                        const void* dist1, const int32_t* ids2,
                                                        const void* dist2, uint64_t* G,
-                                                       uint32_t* kth, uint64_t* aside) {
+                                                       NodeMeta* meta, uint64_t* aside) {
   using D = DistOf<METRIC>;
   using T = typename D::elem;
   const int64_t s = wave_global_index();
@@ -338,7 +338,7 @@ __global__ __launch_bounds__(kBlock) void k_merge_init(VecSrc vs, int64_t n, int
   }
   e = wave_sort(e, lane);
   if (lane < k) G[s * k + lane] = e;
-  if (lane == k - 1) kth[s] = entry_code(e);
+  if (lane == k - 1) meta[s].kth = entry_code(e);
 }
 
 // GGM, Alg. 3 "Merge and Sort": best k of the refined list and the set-aside half.
@@ -514,14 +514,14 @@ hipError_t launch_init_random(const Shape& sh, const DevState& ds, uint64_t seed
   const uint64_t base = hash_base(seed, kTagInit);
   switch (sh.metric) {
     case kL2F32:
-      k_init_random<kL2F32><<<grid, kBlock, 0, st>>>(vec_src(sh), sh.n, sh.k, base, ds.G, ds.kth);
+      k_init_random<kL2F32><<<grid, kBlock, 0, st>>>(vec_src(sh), sh.n, sh.k, base, ds.G, ds.meta);
       break;
     case kAngularF32:
       k_init_random<kAngularF32><<<grid, kBlock, 0, st>>>(vec_src(sh), sh.n, sh.k, base, ds.G,
-                                                          ds.kth);
+                                                          ds.meta);
       break;
     default:
-      k_init_random<kL2U8><<<grid, kBlock, 0, st>>>(vec_src(sh), sh.n, sh.k, base, ds.G, ds.kth);
+      k_init_random<kL2U8><<<grid, kBlock, 0, st>>>(vec_src(sh), sh.n, sh.k, base, ds.G, ds.meta);
   }
   return hipGetLastError();
 }
@@ -547,7 +547,7 @@ hipError_t launch_sample(const Shape& sh, const DevState& ds, uint64_t seed, uin
 }
 
 hipError_t launch_update(const Shape& sh, const DevState& ds, hipStream_t st) {
-  k_update<<<blocks_for_waves(sh.n), kBlock, 0, st>>>(sh.n, sh.k, ds.G, ds.kth, ds.pcnt, ds.poff,
+  k_update<<<blocks_for_waves(sh.n), kBlock, 0, st>>>(sh.n, sh.k, ds.G, ds.meta, ds.pcnt, ds.poff,
                                                       ds.bins, ds.counters);
   return hipGetLastError();
 }
@@ -566,9 +566,9 @@ hipError_t launch_set_graph(const Shape& sh, const DevState& ds, const int32_t* 
   const int64_t total = sh.n * sh.k;
   const unsigned grid = (unsigned)((total + kBlock - 1) / kBlock);
   if (sh.metric == kL2U8)
-    k_set_graph<false><<<grid, kBlock, 0, st>>>(total, sh.k, ds.G, ds.kth, ids, dist, isnew);
+    k_set_graph<false><<<grid, kBlock, 0, st>>>(total, sh.k, ds.G, ds.meta, ids, dist, isnew);
   else
-    k_set_graph<true><<<grid, kBlock, 0, st>>>(total, sh.k, ds.G, ds.kth, ids, dist, isnew);
+    k_set_graph<true><<<grid, kBlock, 0, st>>>(total, sh.k, ds.G, ds.meta, ids, dist, isnew);
   return hipGetLastError();
 }
 
@@ -594,16 +594,16 @@ hipError_t launch_merge_init(const Shape& sh, const DevState& ds, uint64_t seed,
   switch (sh.metric) {
     case kL2F32:
       k_merge_init<kL2F32><<<grid, kBlock, 0, st>>>(vec_src(sh), sh.n, n1, sh.k, base, ids1, dist1,
-                                                    ids2, dist2, ds.G, ds.kth, ds.aside);
+                                                    ids2, dist2, ds.G, ds.meta, ds.aside);
       break;
     case kAngularF32:
       k_merge_init<kAngularF32><<<grid, kBlock, 0, st>>>(vec_src(sh), sh.n, n1, sh.k, base, ids1,
-                                                         dist1, ids2, dist2, ds.G, ds.kth,
+                                                         dist1, ids2, dist2, ds.G, ds.meta,
                                                          ds.aside);
       break;
     default:
       k_merge_init<kL2U8><<<grid, kBlock, 0, st>>>(vec_src(sh), sh.n, n1, sh.k, base, ids1, dist1,
-                                                   ids2, dist2, ds.G, ds.kth, ds.aside);
+                                                   ids2, dist2, ds.G, ds.meta, ds.aside);
   }
   return hipGetLastError();
 }

@@ -20,7 +20,8 @@ namespace gnnd {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-constexpr int kMB = 256;  // 4 waves = 4 nodes per workgroup
+constexpr int kMB = 256;  // 4 waves = 4 nodes in flight per workgroup
+constexpr int64_t kJoinGrid = 256 * 3 * 2;  // 256 CUs x 3 resident workgroups x 2
 constexpr int32_t kFar = 1 << 24;  // "norm" of an absent row: above every real distance
 
 // Convert float32 rows holding integers 0..255 (or uint8 rows) to int8 rows
@@ -29,7 +30,7 @@ constexpr int32_t kFar = 1 << 24;  // "norm" of an absent row: above every real 
 template <typename T>
 __global__ __launch_bounds__(256) void k_pack_i8(const void* vec_a, const void* vec_b,
                                                  int64_t split, int64_t n, int d, int dpad,
-                                                 int8_t* shadow, int32_t* norms, int* bad) {
+                                                 int8_t* shadow, NodeMeta* meta, int* bad) {
   const int lane = lane_id();
   const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= n) return;
@@ -50,45 +51,45 @@ __global__ __launch_bounds__(256) void k_pack_i8(const void* vec_a, const void* 
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, kWave);
-  if (lane == 0) norms[row] = acc;
+  if (lane == 0) meta[row].norm = acc;
   if (__ballot(is_bad) != 0ull && lane == 0) atomicOr(bad, 1);
 }
 
-// min over the 16 accumulator registers of a tile, per lane (= per column), of
-// the signed key (row_norm - 2 G) << 6 | row position, rows flagged in `excl`
-// skipped.  Row of register r for this lane: 8*(r/4) + 4*half + (r%4).  Adding
-// the column's own norm to key >> 6 afterwards gives the squared distance; the
-// shift keeps the order because |row_norm - 2 G| stays below 2^25.
-constexpr int32_t kNone = 0x7fffffff;
+// Best row per column of one 32x32 accumulator tile.  For row r the LDS array
+// holds negR = -((norm_r << 6) | position_r); then t = (G << 7) + negR is
+// -(((norm_r - 2 G) << 6) | position_r), so the maximum of t over the rows is
+// the row with the smallest (norm_r - 2 G), ties to the smallest position -
+// one shift-add and half a max3 per accumulator register.  Adding the column's
+// own norm to ((-t) >> 6) gives the squared distance; |.| stays below 2^31
+// because norms are below 2^22 (absent rows: 2^24 with G = 0).  Rows flagged
+// in `excl` are skipped.  Row of register r for this lane: 8*(r/4) + 4*half + r%4.
+constexpr int32_t kNone = (int32_t)0x80000000;
 
 template <bool MASKED>
-__device__ inline int32_t tile_col_min(const v16i& g, const int32_t* row_norm_lds, int half,
-                                       int row_base, uint32_t excl) {
+__device__ inline int32_t tile_col_best(const v16i& g, const int32_t* negr_lds, int half,
+                                        uint32_t excl) {
   int32_t best = kNone;
   const uint32_t ex = excl >> (4 * half);
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
-    const int4 nr = *reinterpret_cast<const int4*>(row_norm_lds + 8 * q + 4 * half);
-    const int32_t nrm[4] = {nr.x, nr.y, nr.z, nr.w};
+    const int4 nr = *reinterpret_cast<const int4*>(negr_lds + 8 * q + 4 * half);
+    const int32_t negr[4] = {nr.x, nr.y, nr.z, nr.w};
+    int32_t t[4];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      const int r = 4 * q + t;
-      const int32_t part = nrm[t] - 2 * g[r];
-      int32_t key = (int32_t)(((uint32_t)part << 6) | (uint32_t)(row_base + 8 * q + 4 * half + t));
-      if (MASKED) {
-        const uint32_t bit = 1u << (8 * q + t);
-        key = (ex & bit) ? kNone : key;
-      }
-      best = key < best ? key : best;
+    for (int i = 0; i < 4; ++i) {
+      t[i] = (int32_t)(((uint32_t)g[4 * q + i] << 7) + (uint32_t)negr[i]);
+      if (MASKED) t[i] = (ex & (1u << (8 * q + i))) ? kNone : t[i];
     }
+    best = max(best, max(t[0], t[1]));
+    best = max(best, max(t[2], t[3]));
   }
   return best;
 }
 
-__device__ inline int32_t both_halves_min(int32_t x) {
+__device__ inline int32_t both_halves_max(int32_t x) {
   auto sw = __builtin_amdgcn_permlane32_swap((uint32_t)x, (uint32_t)x, false, false);
   int32_t a = (int32_t)sw[0], b = (int32_t)sw[1];
-  return a < b ? a : b;
+  return a > b ? a : b;
 }
 
 struct Operand {
@@ -119,221 +120,289 @@ __device__ inline v16i gram(const Operand& rows, const Operand& cols) {
 
 // FCODE: distances are reported as float32 codes (float input data) instead of
 // int32 codes.  MERGE: GGM mode - no NEW x NEW, only pairs from different sets.
+//
+// Each wavefront walks over nodes s, s + W, s + 2W, ... (W = wavefronts in the
+// grid) as a software pipeline, because a node costs three dependent memory
+// round trips (sample ids -> vector rows -> result slots): while the tiles of
+// node i are evaluated the ids of node i+1 are already in flight, and as soon
+// as the last tile has consumed the operand registers the rows of node i+1 are
+// requested, before the results of node i are handed out.
 template <int KSTEPS, bool FCODE, bool MERGE>
 __global__ __launch_bounds__(kMB) void k_join_mfma(
-    const int8_t* __restrict__ shadow, const int32_t* __restrict__ norms, int dpad, int64_t n,
+    const int8_t* __restrict__ shadow, const NodeMeta* __restrict__ meta, int dpad, int64_t n,
     int p, int64_t split, const int32_t* __restrict__ snew, const int32_t* __restrict__ sold,
-    const int32_t* __restrict__ cnew, const int32_t* __restrict__ cold,
-    const uint32_t* __restrict__ kth, uint32_t* pcnt, const uint64_t* __restrict__ poff,
-    uint64_t* __restrict__ bins, uint64_t* counters) {
-  // per wave: norms of the 128 rows (NEW 0..63, OLD 64..127) and their ids
+    uint32_t* pcnt, const uint64_t* __restrict__ poff, uint64_t* __restrict__ bins,
+    uint64_t* counters) {
+  // per wave, for the 128 rows (NEW 0..63, OLD 64..127): -((norm << 6) | position), the ids
+  // (absent = INT_MAX so that both halves stay ascending), and a scratch row
   __shared__ __attribute__((aligned(16))) int32_t s_norm[4][128];
   __shared__ int32_t s_id[4][128];
+  __shared__ int32_t s_eq[4][64];
   const int wave = threadIdx.x >> 6, lane = lane_id(), half = lane >> 5, col = lane & 31;
-  const int64_t s = (int64_t)blockIdx.x * 4 + wave;
+  const int64_t W = (int64_t)gridDim.x * 4;
+  int64_t s = (int64_t)blockIdx.x * 4 + wave;
   if (s >= n) return;
   const int L = 2 * p;
-  const int nn = cnew[s], no = cold[s];
-  const bool do_nn = !MERGE && nn > 1;
-  if (nn == 0 || (!do_nn && no == 0)) return;
-  const int32_t id_new = lane < nn ? snew[s * L + lane] : -1;
-  const int32_t id_old = lane < no ? sold[s * L + lane] : -1;
+  const bool in_list = lane < L;
+  const uint2 m_none = make_uint2(0, (uint32_t)kFar);
 
-  // operands: block b of a list = its rows 32b..32b+31; lane (col, half) holds
-  // bytes [32s + 16 half, +16) of row `col` of the block for every step s
-  const int32_t rid_n0 = __shfl(id_new, col, kWave), rid_n1 = __shfl(id_new, 32 + col, kWave);
-  const int32_t rid_o0 = __shfl(id_old, col, kWave), rid_o1 = __shfl(id_old, 32 + col, kWave);
-  const Operand N0 = load_block<KSTEPS>(shadow, dpad, rid_n0, half);
-  const Operand N1 = load_block<KSTEPS>(shadow, dpad, nn > 32 ? rid_n1 : -1, half);
-  const Operand O0 = load_block<KSTEPS>(shadow, dpad, rid_o0, half);
-  const Operand O1 = load_block<KSTEPS>(shadow, dpad, no > 32 ? rid_o1 : -1, half);
-
-  const int32_t nrm_new = id_new >= 0 ? norms[id_new] : kFar;
-  const int32_t nrm_old = id_old >= 0 ? norms[id_old] : kFar;
-  s_norm[wave][lane] = nrm_new;
-  s_norm[wave][64 + lane] = nrm_old;
-  s_id[wave][lane] = id_new;
-  s_id[wave][64 + lane] = id_old;
-  // the wave reads these back below: order its own LDS writes before its reads
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-
-  // objects sampled both as NEW and as OLD: that pair is not a pair.  eq_old =
-  // position in the OLD list of this lane's NEW object (or -1), and vice versa.
-  int eq_old = -1, eq_new = -1;
-  uint32_t dups = 0;
-  if (no > 0) {
-    for (int i = 0; i < no; ++i) {
-      const int32_t oid = __builtin_amdgcn_readlane(id_old, i);
-      if (id_new == oid) eq_old = i;
-    }
-    const uint64_t m = __ballot(eq_old >= 0);
-    dups = (uint32_t)__popcll(m);
-    if (dups) {
-      for (int i = 0; i < nn; ++i) {
-        const int32_t nid = __builtin_amdgcn_readlane(id_new, i);
-        if (id_old == nid && id_old >= 0) eq_new = i;
-      }
-    }
+  // unused list slots hold -1, so the ids alone say how long a list is
+  int32_t id_new = in_list ? snew[s * L + lane] : -1;
+  int32_t id_old = in_list ? sold[s * L + lane] : -1;
+  int32_t nx_new = -1, nx_old = -1;
+  if (s + W < n && in_list) {
+    nx_new = snew[(s + W) * L + lane];
+    nx_old = sold[(s + W) * L + lane];
   }
-  // per-lane exclusion masks (bit r = row r of the block is not a partner of
-  // this lane's column object); lanes l and l+32 serve column l%32 of block 0,
-  // results of block 1 are selected into lanes 32..63 at the end
-  const int eq_old_c0 = __shfl(eq_old, col, kWave), eq_old_c1 = __shfl(eq_old, 32 + col, kWave);
-  const int eq_new_c0 = __shfl(eq_new, col, kWave), eq_new_c1 = __shfl(eq_new, 32 + col, kWave);
-  // merge mode: rows whose set equals the column object's set are excluded
-  uint32_t cls_new0 = 0, cls_new1 = 0, cls_old0 = 0, cls_old1 = 0;
-  if (MERGE) {
-    const uint64_t cn = __ballot(id_new >= 0 && (int64_t)id_new >= split);
-    const uint64_t co = __ballot(id_old >= 0 && (int64_t)id_old >= split);
-    cls_new0 = (uint32_t)cn; cls_new1 = (uint32_t)(cn >> 32);
-    cls_old0 = (uint32_t)co; cls_old1 = (uint32_t)(co >> 32);
-  }
-  auto excl_rows = [&](int eq_row, int row_block, uint32_t cls_rows, int32_t col_id) {
-    uint32_t m = 0;
-    if (eq_row >= 0 && (eq_row >> 5) == row_block) m |= 1u << (eq_row & 31);
-    if (MERGE) m |= ((int64_t)col_id >= split) ? cls_rows : ~cls_rows;
-    return m;
+  Operand N0, N1, O0, O1;
+  uint2 m_new, m_old;
+  auto request_rows = [&](int32_t idn, int32_t ido) {
+    // block b of a list = its rows 32b..32b+31; lane (col, half) holds bytes
+    // [32 step + 16 half, +16) of row `col` of the block for every step
+    N0 = load_block<KSTEPS>(shadow, dpad, __shfl(idn, col, kWave), half);
+    N1 = load_block<KSTEPS>(shadow, dpad, __shfl(idn, 32 + col, kWave), half);
+    O0 = load_block<KSTEPS>(shadow, dpad, __shfl(ido, col, kWave), half);
+    O1 = load_block<KSTEPS>(shadow, dpad, __shfl(ido, 32 + col, kWave), half);
+    // one 8-byte gather per sampled object: list threshold and norm
+    m_new = idn >= 0 ? *reinterpret_cast<const uint2*>(meta + idn) : m_none;
+    m_old = ido >= 0 ? *reinterpret_cast<const uint2*>(meta + ido) : m_none;
   };
-  const bool masked_no = MERGE || dups != 0;
+  request_rows(id_new, id_old);
 
-  const int32_t* normN = s_norm[wave];
-  const int32_t* normO = s_norm[wave] + 64;
-  int32_t a0 = kNone, a1 = kNone;  // NEW column blocks: nearest other NEW
-  int32_t b0 = kNone, b1 = kNone;  // NEW column blocks: nearest OLD
-  int32_t c0 = kNone, c1 = kNone;  // OLD column blocks: nearest NEW
+  for (;;) {
+    const int nn = __popcll(__ballot(id_new >= 0)), no = __popcll(__ballot(id_old >= 0));
+    const bool do_nn = !MERGE && nn > 1;
+    const bool active = nn > 0 && (do_nn || no > 0);
+    const uint2 cm_new = m_new, cm_old = m_old;  // this node's thresholds and norms
+    int32_t a0 = kNone, a1 = kNone;  // NEW column blocks: nearest other NEW
+    int32_t b0 = kNone, b1 = kNone;  // NEW column blocks: nearest OLD
+    int32_t c0 = kNone, c1 = kNone;  // OLD column blocks: nearest NEW
+    uint32_t dups = 0;
+    uint32_t cls_new0 = 0, cls_new1 = 0, cls_old0 = 0, cls_old1 = 0;
+    if (active) {
+      s_norm[wave][lane] = -(int32_t)((cm_new.y << 6) | (uint32_t)lane);
+      s_norm[wave][64 + lane] = -(int32_t)((cm_old.y << 6) | (uint32_t)lane);
+      s_id[wave][lane] = id_new >= 0 ? id_new : 0x7fffffff;
+      s_id[wave][64 + lane] = id_old >= 0 ? id_old : 0x7fffffff;
+      s_eq[wave][lane] = -1;
+      // the wave reads these back below: order its own LDS writes before its reads
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-  if (do_nn) {
-    {  // rows N0, columns N0: the diagonal pairs an object with itself
-      v16i g = gram<KSTEPS>(N0, N0);
-      a0 = min(a0, tile_col_min<true>(g, normN, half, 0, 1u << col));
-    }
-    if (nn > 32) {
-      {
-        v16i g = gram<KSTEPS>(N1, N0);
-        a0 = min(a0, tile_col_min<false>(g, normN + 32, half, 32, 0u));
-      }
-      {
-        v16i g = gram<KSTEPS>(N0, N1);
-        a1 = min(a1, tile_col_min<false>(g, normN, half, 0, 0u));
-      }
-      {
-        v16i g = gram<KSTEPS>(N1, N1);
-        a1 = min(a1, tile_col_min<true>(g, normN + 32, half, 32, 1u << col));
-      }
-    }
-  }
-  if (no > 0) {
-    // columns = NEW objects, rows = OLD objects: nearest OLD of every NEW
-    {
-      v16i g = gram<KSTEPS>(O0, N0);
-      b0 = min(b0, masked_no ? tile_col_min<true>(g, normO, half, 0,
-                                                  excl_rows(eq_old_c0, 0, cls_old0, rid_n0))
-                             : tile_col_min<false>(g, normO, half, 0, 0u));
-    }
-    if (no > 32) {
-      v16i g = gram<KSTEPS>(O1, N0);
-      b0 = min(b0, masked_no ? tile_col_min<true>(g, normO + 32, half, 32,
-                                                  excl_rows(eq_old_c0, 1, cls_old1, rid_n0))
-                             : tile_col_min<false>(g, normO + 32, half, 32, 0u));
-    }
-    if (nn > 32) {
-      {
-        v16i g = gram<KSTEPS>(O0, N1);
-        b1 = min(b1, masked_no ? tile_col_min<true>(g, normO, half, 0,
-                                                    excl_rows(eq_old_c1, 0, cls_old0, rid_n1))
-                               : tile_col_min<false>(g, normO, half, 0, 0u));
-      }
-      if (no > 32) {
-        v16i g = gram<KSTEPS>(O1, N1);
-        b1 = min(b1, masked_no ? tile_col_min<true>(g, normO + 32, half, 32,
-                                                    excl_rows(eq_old_c1, 1, cls_old1, rid_n1))
-                               : tile_col_min<false>(g, normO + 32, half, 32, 0u));
-      }
-    }
-    // columns = OLD objects, rows = NEW objects: nearest NEW of every OLD
-    {
-      v16i g = gram<KSTEPS>(N0, O0);
-      c0 = min(c0, masked_no ? tile_col_min<true>(g, normN, half, 0,
-                                                  excl_rows(eq_new_c0, 0, cls_new0, rid_o0))
-                             : tile_col_min<false>(g, normN, half, 0, 0u));
-    }
-    if (nn > 32) {
-      v16i g = gram<KSTEPS>(N1, O0);
-      c0 = min(c0, masked_no ? tile_col_min<true>(g, normN + 32, half, 32,
-                                                  excl_rows(eq_new_c0, 1, cls_new1, rid_o0))
-                             : tile_col_min<false>(g, normN + 32, half, 32, 0u));
-    }
-    if (no > 32) {
-      {
-        v16i g = gram<KSTEPS>(N0, O1);
-        c1 = min(c1, masked_no ? tile_col_min<true>(g, normN, half, 0,
-                                                    excl_rows(eq_new_c1, 0, cls_new0, rid_o1))
-                               : tile_col_min<false>(g, normN, half, 0, 0u));
-      }
-      if (nn > 32) {
-        v16i g = gram<KSTEPS>(N1, O1);
-        c1 = min(c1, masked_no ? tile_col_min<true>(g, normN + 32, half, 32,
-                                                    excl_rows(eq_new_c1, 1, cls_new1, rid_o1))
-                               : tile_col_min<false>(g, normN + 32, half, 32, 0u));
-      }
-    }
-  }
-  // combine the two row halves; lanes 0..31 take column block 0, lanes 32..63 block 1
-  a0 = both_halves_min(a0); a1 = both_halves_min(a1);
-  b0 = both_halves_min(b0); b1 = both_halves_min(b1);
-  c0 = both_halves_min(c0); c1 = both_halves_min(c1);
-  const int32_t ra = half ? a1 : a0, rb = half ? b1 : b0, rc = half ? c1 : c0;
-
-  // lane l now answers for sample l of its list, three results
-  uint32_t found_total = 0, over_total = 0;
+      // objects sampled both as NEW and as OLD: that pair is not a pair.  eq_old =
+      // position in the OLD list of this lane's NEW object (or -1), and vice versa.
+      // Both lists ascend, so each NEW lane binary-searches its id in the OLD list.
+      int eq_old = -1, eq_new = -1;
+      if (no > 0) {
+        int lo = 0, hi = 64;  // lower bound of id_new in the OLD list, in [0, 64]
 #pragma unroll
-  for (int kind = 0; kind < 3; ++kind) {
-    const int32_t res = kind == 0 ? ra : (kind == 1 ? rb : rc);
-    const int32_t self = kind == 2 ? id_old : id_new;
-    const int32_t self_norm = kind == 2 ? nrm_old : nrm_new;
-    const int32_t part = res >> 6;  // row_norm - 2 G (arithmetic shift); absent rows sit at kFar
-    const bool found = self >= 0 && res != kNone && part < (kFar >> 1);
-    const int32_t dist = part + self_norm;
-    const int pos = res & 63;
-    const int32_t other = found ? s_id[wave][(kind == 0 ? 0 : (kind == 1 ? 64 : 0)) + pos] : 0;
-    const uint32_t code = FCODE ? ord_f32((float)dist) : ord_i32(dist);
-    const bool pass = found && code <= kth[found ? self : 0];
-    bool overflow = false;
-    if (pass) {  // into the destination's segment of the proposal array
-      const uint64_t beg = poff[self], cap = poff[self + 1] - beg;
-      const uint32_t pos = atomicAdd(&pcnt[self], 1u);
-      if (pos < cap) bins[beg + pos] = make_entry(code, (uint32_t)other, 3u);
-      else overflow = true;
+        for (int step = 0; step < 7; ++step) {
+          const bool go = lo < hi;
+          const int mid = (lo + hi) >> 1;  // <= 63 while lo < hi
+          const bool below = go && s_id[wave][64 + (mid & 63)] < id_new;
+          lo = below ? mid + 1 : lo;
+          hi = (go && !below) ? mid : hi;
+        }
+        if (id_new >= 0 && lo < 64 && s_id[wave][64 + lo] == id_new) eq_old = lo;
+        dups = (uint32_t)__popcll(__ballot(eq_old >= 0));
+        if (dups) {
+          if (eq_old >= 0) s_eq[wave][eq_old] = lane;
+          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+          __builtin_amdgcn_wave_barrier();
+          __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+          eq_new = s_eq[wave][lane];
+        }
+      }
+      // per-lane exclusion masks (bit r = row r of the block is not a partner of
+      // this lane's column object); lanes l and l+32 serve column l%32 of block 0,
+      // results of block 1 are selected into lanes 32..63 at the end
+      const int eq_old_c0 = __shfl(eq_old, col, kWave), eq_old_c1 = __shfl(eq_old, 32 + col, kWave);
+      const int eq_new_c0 = __shfl(eq_new, col, kWave), eq_new_c1 = __shfl(eq_new, 32 + col, kWave);
+      const int32_t rid_n0 = __shfl(id_new, col, kWave), rid_n1 = __shfl(id_new, 32 + col, kWave);
+      const int32_t rid_o0 = __shfl(id_old, col, kWave), rid_o1 = __shfl(id_old, 32 + col, kWave);
+      // merge mode: rows whose set equals the column object's set are excluded
+      if (MERGE) {
+        const uint64_t cn = __ballot(id_new >= 0 && (int64_t)id_new >= split);
+        const uint64_t co = __ballot(id_old >= 0 && (int64_t)id_old >= split);
+        cls_new0 = (uint32_t)cn; cls_new1 = (uint32_t)(cn >> 32);
+        cls_old0 = (uint32_t)co; cls_old1 = (uint32_t)(co >> 32);
+      }
+      auto excl_rows = [&](int eq_row, int row_block, uint32_t cls_rows, int32_t col_id) {
+        uint32_t m = 0;
+        if (eq_row >= 0 && (eq_row >> 5) == row_block) m |= 1u << (eq_row & 31);
+        if (MERGE) m |= ((int64_t)col_id >= split) ? cls_rows : ~cls_rows;
+        return m;
+      };
+      const bool masked_no = MERGE || dups != 0;
+      const int32_t* normN = s_norm[wave];
+      const int32_t* normO = s_norm[wave] + 64;
+
+      if (do_nn) {
+        {  // rows N0, columns N0: the diagonal pairs an object with itself
+          v16i g = gram<KSTEPS>(N0, N0);
+          a0 = max(a0, tile_col_best<true>(g, normN, half, 1u << col));
+        }
+        if (nn > 32) {
+          {
+            v16i g = gram<KSTEPS>(N1, N0);
+            a0 = max(a0, tile_col_best<false>(g, normN + 32, half, 0u));
+          }
+          {
+            v16i g = gram<KSTEPS>(N0, N1);
+            a1 = max(a1, tile_col_best<false>(g, normN, half, 0u));
+          }
+          {
+            v16i g = gram<KSTEPS>(N1, N1);
+            a1 = max(a1, tile_col_best<true>(g, normN + 32, half, 1u << col));
+          }
+        }
+      }
+      if (no > 0) {
+        // columns = NEW objects, rows = OLD objects: nearest OLD of every NEW
+        {
+          v16i g = gram<KSTEPS>(O0, N0);
+          b0 = max(b0, masked_no ? tile_col_best<true>(g, normO, half,
+                                                      excl_rows(eq_old_c0, 0, cls_old0, rid_n0))
+                                 : tile_col_best<false>(g, normO, half, 0u));
+        }
+        if (no > 32) {
+          v16i g = gram<KSTEPS>(O1, N0);
+          b0 = max(b0, masked_no ? tile_col_best<true>(g, normO + 32, half,
+                                                      excl_rows(eq_old_c0, 1, cls_old1, rid_n0))
+                                 : tile_col_best<false>(g, normO + 32, half, 0u));
+        }
+        if (nn > 32) {
+          {
+            v16i g = gram<KSTEPS>(O0, N1);
+            b1 = max(b1, masked_no ? tile_col_best<true>(g, normO, half,
+                                                        excl_rows(eq_old_c1, 0, cls_old0, rid_n1))
+                                   : tile_col_best<false>(g, normO, half, 0u));
+          }
+          if (no > 32) {
+            v16i g = gram<KSTEPS>(O1, N1);
+            b1 = max(b1, masked_no ? tile_col_best<true>(g, normO + 32, half,
+                                                        excl_rows(eq_old_c1, 1, cls_old1, rid_n1))
+                                   : tile_col_best<false>(g, normO + 32, half, 0u));
+          }
+        }
+        // columns = OLD objects, rows = NEW objects: nearest NEW of every OLD
+        {
+          v16i g = gram<KSTEPS>(N0, O0);
+          c0 = max(c0, masked_no ? tile_col_best<true>(g, normN, half,
+                                                      excl_rows(eq_new_c0, 0, cls_new0, rid_o0))
+                                 : tile_col_best<false>(g, normN, half, 0u));
+        }
+        if (nn > 32) {
+          v16i g = gram<KSTEPS>(N1, O0);
+          c0 = max(c0, masked_no ? tile_col_best<true>(g, normN + 32, half,
+                                                      excl_rows(eq_new_c0, 1, cls_new1, rid_o0))
+                                 : tile_col_best<false>(g, normN + 32, half, 0u));
+        }
+        if (no > 32) {
+          {
+            v16i g = gram<KSTEPS>(N0, O1);
+            c1 = max(c1, masked_no ? tile_col_best<true>(g, normN, half,
+                                                        excl_rows(eq_new_c1, 0, cls_new0, rid_o1))
+                                   : tile_col_best<false>(g, normN, half, 0u));
+          }
+          if (nn > 32) {
+            v16i g = gram<KSTEPS>(N1, O1);
+            c1 = max(c1, masked_no ? tile_col_best<true>(g, normN + 32, half,
+                                                        excl_rows(eq_new_c1, 1, cls_new1, rid_o1))
+                                   : tile_col_best<false>(g, normN + 32, half, 0u));
+          }
+        }
+      }
     }
-    found_total += (uint32_t)__popcll(__ballot(found));
-    over_total += (uint32_t)__popcll(__ballot(overflow));
-  }
-  if (lane == 0) {
-    uint64_t ev;
-    if (MERGE) {
-      const uint64_t cn = ((uint64_t)cls_new1 << 32) | cls_new0;
-      const uint64_t co = ((uint64_t)cls_old1 << 32) | cls_old0;
-      const uint64_t n1 = __popcll(cn), o1 = __popcll(co);
-      ev = n1 * ((uint64_t)no - o1) + ((uint64_t)nn - n1) * o1;
+
+    // ---- hand the results out: lane l answers for sample l of its list -------
+    uint32_t found_total = 0, over_total = 0;
+    bool pass[3];
+    uint64_t entry[3];
+    int32_t self[3];
+    if (active) {
+      // combine the two row halves; lanes 0..31 take column block 0, lanes 32..63 block 1
+      a0 = both_halves_max(a0); a1 = both_halves_max(a1);
+      b0 = both_halves_max(b0); b1 = both_halves_max(b1);
+      c0 = both_halves_max(c0); c1 = both_halves_max(c1);
+      const int32_t res3[3] = {half ? a1 : a0, half ? b1 : b0, half ? c1 : c0};
+#pragma unroll
+      for (int kind = 0; kind < 3; ++kind) {
+        const int32_t res = -res3[kind];  // ((row_norm - 2 G) << 6) | row position
+        self[kind] = kind == 2 ? id_old : id_new;
+        const uint2 cm = kind == 2 ? cm_old : cm_new;
+        const int32_t part = res >> 6;  // arithmetic shift; absent rows sit at kFar
+        const bool found = self[kind] >= 0 && res3[kind] != kNone && part < (kFar >> 1);
+        const int32_t dist = part + (int32_t)cm.y;
+        const int32_t other = found ? s_id[wave][(kind == 1 ? 64 : 0) + (res & 63)] : 0;
+        const uint32_t code = FCODE ? ord_f32((float)dist) : ord_i32(dist);
+        // a result that cannot beat the last entry of the destination list is dropped
+        pass[kind] = found && code <= cm.x;
+        entry[kind] = make_entry(code, (uint32_t)other, 3u);
+        found_total += (uint32_t)__popcll(__ballot(found));
+      }
     } else {
-      ev = (do_nn ? (uint64_t)nn * (nn - 1) / 2 : 0) + (uint64_t)nn * no - dups;
+      pass[0] = pass[1] = pass[2] = false;
     }
-    uint64_t* cs = counters + (s & (kStripes - 1)) * C_SLOTS;
-    if (found_total) atomicAdd(reinterpret_cast<unsigned long long*>(cs + C_PROPS),
-                               (unsigned long long)found_total);
-    if (over_total) atomicAdd(reinterpret_cast<unsigned long long*>(cs + C_OVERFLOW),
-                              (unsigned long long)over_total);
-    if (ev) atomicAdd(reinterpret_cast<unsigned long long*>(cs + C_EVALS), (unsigned long long)ev);
+    // slot requests for all three results first ...
+    uint32_t slot[3] = {0, 0, 0};
+    uint64_t beg[3] = {0, 0, 0}, end[3] = {0, 0, 0};
+#pragma unroll
+    for (int kind = 0; kind < 3; ++kind)
+      if (pass[kind]) {
+        slot[kind] = atomicAdd(&pcnt[self[kind]], 1u);
+        beg[kind] = poff[self[kind]];
+        end[kind] = poff[self[kind] + 1];
+      }
+    // ... then, with the operand registers free, the next node's rows ...
+    const int64_t s_next = s + W;
+    const bool more = s_next < n;
+    int32_t nn_new = -1, nn_old = -1;
+    if (more) {
+      request_rows(nx_new, nx_old);
+      if (s_next + W < n && in_list) {
+        nn_new = snew[(s_next + W) * L + lane];
+        nn_old = sold[(s_next + W) * L + lane];
+      }
+    }
+    // ... and only now the slots are used
+#pragma unroll
+    for (int kind = 0; kind < 3; ++kind)
+      if (pass[kind]) {
+        if (slot[kind] < end[kind] - beg[kind]) bins[beg[kind] + slot[kind]] = entry[kind];
+        else ++over_total;
+      }
+    over_total = (uint32_t)__popcll(__ballot(over_total != 0));  // at most one kind overflows per lane in practice; counted per lane
+    if (active && lane == 0) {
+      uint64_t ev;
+      if (MERGE) {
+        const uint64_t cn = ((uint64_t)cls_new1 << 32) | cls_new0;
+        const uint64_t co = ((uint64_t)cls_old1 << 32) | cls_old0;
+        const uint64_t n1 = __popcll(cn), o1 = __popcll(co);
+        ev = n1 * ((uint64_t)no - o1) + ((uint64_t)nn - n1) * o1;
+      } else {
+        ev = (do_nn ? (uint64_t)nn * (nn - 1) / 2 : 0) + (uint64_t)nn * no - dups;
+      }
+      uint64_t* cs = counters + (s & (kStripes - 1)) * C_SLOTS;
+      if (found_total) atomicAdd(reinterpret_cast<unsigned long long*>(cs + C_PROPS),
+                                 (unsigned long long)found_total);
+      if (over_total) atomicAdd(reinterpret_cast<unsigned long long*>(cs + C_OVERFLOW),
+                                (unsigned long long)over_total);
+      if (ev) atomicAdd(reinterpret_cast<unsigned long long*>(cs + C_EVALS), (unsigned long long)ev);
+    }
+    if (!more) break;
+    s = s_next;
+    id_new = nx_new; id_old = nx_old;
+    nx_new = nn_new; nx_old = nn_old;
   }
 }
 
 template <int KSTEPS>
 static void launch_k(bool fcode, bool merge, unsigned grid, hipStream_t st, const int8_t* shadow,
-                     const int32_t* norms, int dpad, const Shape& sh, const DevState& ds) {
-#define GNND_ARGS shadow, norms, dpad, sh.n, sh.p, sh.split, ds.snew, ds.sold, ds.cnew, ds.cold, \
-                  ds.kth, ds.pcnt, ds.poff, ds.bins, ds.counters
+                     const NodeMeta* meta, int dpad, const Shape& sh, const DevState& ds) {
+#define GNND_ARGS shadow, meta, dpad, sh.n, sh.p, sh.split, ds.snew, ds.sold, \
+                  ds.pcnt, ds.poff, ds.bins, ds.counters
   if (fcode) {
     if (merge) k_join_mfma<KSTEPS, true, true><<<grid, kMB, 0, st>>>(GNND_ARGS);
     else k_join_mfma<KSTEPS, true, false><<<grid, kMB, 0, st>>>(GNND_ARGS);
@@ -348,13 +417,15 @@ hipError_t launch_join_mfma(const Shape& sh, const DevState& ds, bool merge_mode
                             hipStream_t st) {
   const int dpad = (sh.d + 31) & ~31;
   const int ksteps = dpad / 32;
-  const unsigned grid = (unsigned)((sh.n + 3) / 4);
+  // persistent wavefronts: about two resident sets of workgroups, each wave strides over nodes
+  const int64_t want = (sh.n + 3) / 4;
+  const unsigned grid = (unsigned)(want < kJoinGrid ? want : kJoinGrid);
   const bool fcode = sh.metric != kL2U8;
   switch (ksteps) {
-    case 1: launch_k<1>(fcode, merge_mode, grid, st, ds.shadow, ds.norms, dpad, sh, ds); break;
-    case 2: launch_k<2>(fcode, merge_mode, grid, st, ds.shadow, ds.norms, dpad, sh, ds); break;
-    case 3: launch_k<3>(fcode, merge_mode, grid, st, ds.shadow, ds.norms, dpad, sh, ds); break;
-    default: launch_k<4>(fcode, merge_mode, grid, st, ds.shadow, ds.norms, dpad, sh, ds);
+    case 1: launch_k<1>(fcode, merge_mode, grid, st, ds.shadow, ds.meta, dpad, sh, ds); break;
+    case 2: launch_k<2>(fcode, merge_mode, grid, st, ds.shadow, ds.meta, dpad, sh, ds); break;
+    case 3: launch_k<3>(fcode, merge_mode, grid, st, ds.shadow, ds.meta, dpad, sh, ds); break;
+    default: launch_k<4>(fcode, merge_mode, grid, st, ds.shadow, ds.meta, dpad, sh, ds);
   }
   return hipGetLastError();
 }
@@ -365,10 +436,10 @@ hipError_t launch_pack_i8(const Shape& sh, const DevState& ds, int* bad_flag_dev
   const unsigned grid = (unsigned)((sh.n + 3) / 4);
   if (sh.metric == kL2U8)
     k_pack_i8<uint8_t><<<grid, 256, 0, st>>>(sh.vec_a, sh.vec_b, sh.split, sh.n, sh.d, dpad,
-                                             ds.shadow, ds.norms, bad_flag_dev);
+                                             ds.shadow, ds.meta, bad_flag_dev);
   else
     k_pack_i8<float><<<grid, 256, 0, st>>>(sh.vec_a, sh.vec_b, sh.split, sh.n, sh.d, dpad,
-                                           ds.shadow, ds.norms, bad_flag_dev);
+                                           ds.shadow, ds.meta, bad_flag_dev);
   return hipGetLastError();
 }
 

@@ -95,7 +95,7 @@ template <int METRIC>
 __global__ __launch_bounds__(kJB) void k_join_valu(
     VecSrc vs, int64_t n, int p, int merge_mode, const int32_t* __restrict__ snew,
     const int32_t* __restrict__ sold, const int32_t* __restrict__ cnew,
-    const int32_t* __restrict__ cold, const uint32_t* __restrict__ kth, uint32_t* pcnt,
+    const int32_t* __restrict__ cold, const NodeMeta* __restrict__ meta, uint32_t* pcnt,
     const uint64_t* __restrict__ poff, uint64_t* __restrict__ bins, uint64_t* counters) {
   using TR = JoinTraits<METRIC>;
   using T = typename TR::elem;
@@ -253,7 +253,7 @@ __global__ __launch_bounds__(kJB) void k_join_valu(
   }
   const bool found = best != kKeyMax;
   // a result that cannot beat the last entry of the destination list is dropped here
-  const bool pass = found && (uint32_t)(best >> 32) <= kth[self < 0 ? 0 : self];
+  const bool pass = found && (uint32_t)(best >> 32) <= meta[self < 0 ? 0 : self].kth;
   // hand the result to the destination's segment of the proposal array
   bool overflow = false;
   if (pass) {
@@ -292,17 +292,17 @@ hipError_t launch_join(const Shape& sh, const DevState& ds, int path, bool merge
   switch (sh.metric) {
     case kL2F32:
       k_join_valu<kL2F32><<<grid, kJB, 0, st>>>(vs, sh.n, sh.p, merge_mode ? 1 : 0, ds.snew,
-                                                ds.sold, ds.cnew, ds.cold, ds.kth, ds.pcnt,
+                                                ds.sold, ds.cnew, ds.cold, ds.meta, ds.pcnt,
                                                 ds.poff, ds.bins, ds.counters);
       break;
     case kAngularF32:
       k_join_valu<kAngularF32><<<grid, kJB, 0, st>>>(vs, sh.n, sh.p, merge_mode ? 1 : 0, ds.snew,
-                                                     ds.sold, ds.cnew, ds.cold, ds.kth, ds.pcnt,
+                                                     ds.sold, ds.cnew, ds.cold, ds.meta, ds.pcnt,
                                                      ds.poff, ds.bins, ds.counters);
       break;
     default:
       k_join_valu<kL2U8><<<grid, kJB, 0, st>>>(vs, sh.n, sh.p, merge_mode ? 1 : 0, ds.snew,
-                                               ds.sold, ds.cnew, ds.cold, ds.kth, ds.pcnt,
+                                               ds.sold, ds.cnew, ds.cold, ds.meta, ds.pcnt,
                                                ds.poff, ds.bins, ds.counters);
   }
   return hipGetLastError();

@@ -14,10 +14,19 @@ enum : int {
 };
 constexpr int kStripes = 64;  // counters are striped to spread same-address atomics
 
+// What the join gathers per sampled object besides its vector, kept small (8
+// bytes, 8 MB per million nodes) so that the array stays cache resident: the
+// distance code of its list's last entry (nothing farther can enter) and the
+// squared norm of its int8 row.
+struct alignas(8) NodeMeta {
+  uint32_t kth;
+  int32_t norm;
+};
+
 // Everything lives in the caller's workspace; sizes in elements.
 struct DevState {
   uint64_t* G;         // n*k packed entries, row per node, ascending
-  uint32_t* kth;       // n: distance code of the last entry of each list
+  NodeMeta* meta;      // n: per-node record gathered by the join (see NodeMeta)
   int32_t* snew;       // n*2p NEW sample lists
   int32_t* sold;       // n*2p OLD sample lists
   int32_t* cnew;       // n list sizes
@@ -37,7 +46,7 @@ struct DevState {
   uint64_t* counters;  // kStripes * C_SLOTS
   uint64_t* aside;     // merge only: n * floor(k/2) set-aside entries
   int8_t* shadow;      // matrix-core path: n rows of dpad int8 (value - 128), zero padded
-  int32_t* norms;      // matrix-core path: squared norm of every shadow row
+
 };
 
 struct Shape {
