@@ -315,7 +315,7 @@ void og_sample(int64_t n, int k, int p, uint64_t seed, uint32_t iter, const int3
     int a = 0, b = 0;
     for (int j = 0; j < k; ++j) {
       int32_t v = ids[s * k + j];
-      if (v < 0) continue; /* empty slot (never produced by og_init_random) */
+      if (v < 0 || v >= n) continue; /* empty slot, or a frozen entry of a merge */
       if (isnew[s * k + j]) {
         if (a < p) {
           fnew[s * p + a++] = v;
@@ -563,18 +563,40 @@ uint64_t og_update(int64_t n, int k, int p, int32_t* ids, double* dist, uint8_t*
 }
 
 /* ------------------------------------------------------------------------- */
+/* Numbering inside one merge.  The two sets occupy the id ranges
+ * [base1, base1 + n1) and [base2, base2 + n2) of a larger collection (the
+ * shards of Sec. 5.1).  Inside the merge the objects of S1 are numbered
+ * 0..n1-1 and those of S2 n1..n-1 (n = n1 + n2); any other object - a list
+ * entry that came from an earlier merge with a third shard - is numbered
+ * n + its collection id.  Reading (the paper is silent on such entries): they
+ * are frozen - they keep their place in the list by their stored distance and
+ * compete with every insertion, but they are never sampled and so never take
+ * part in a join, because their vectors are not there. */
+int32_t og_to_internal(int64_t g, int64_t n1, int64_t base1, int64_t n2, int64_t base2) {
+  if (g >= base1 && g < base1 + n1) return (int32_t)(g - base1);
+  if (g >= base2 && g < base2 + n2) return (int32_t)(n1 + g - base2);
+  return (int32_t)(n1 + n2 + g);
+}
+
+int32_t og_to_global(int64_t i, int64_t n1, int64_t base1, int64_t n2, int64_t base2) {
+  if (i < n1) return (int32_t)(base1 + i);
+  if (i < n1 + n2) return (int32_t)(base2 + i - n1);
+  return (int32_t)(i - n1 - n2);
+}
+
 /* GGM initialisation (Alg. 3, "Divide" and "Append" steps; Sec. 5.1).
- * The merged graph has n1 + n2 lists, S1's nodes first; ids of G2 are shifted
- * by n1.  Every list keeps its first ceil(k/2) entries, flagged OLD; the other
+ * The merged graph has n1 + n2 lists, S1's nodes first; the input lists carry
+ * collection ids, which are renumbered as above.
+ * Every list keeps its first ceil(k/2) entries, flagged OLD; the other
  * floor(k/2) entries are set aside (aside_*: n rows of floor(k/2)) and replaced
  * by floor(k/2) distinct random objects of the other subset with their
  * distances, flagged NEW.  Reading: the refilled list is put back into
  * (distance, id) order, because sampling takes "the first p" of a sorted list.
  * Requires min(n1, n2) >= floor(k/2). */
-void og_merge_init(const void* vec, int64_t n1, int64_t n2, int d, int k, int metric,
-                   uint64_t seed, const int32_t* ids1, const double* dist1, const int32_t* ids2,
-                   const double* dist2, int32_t* ids, double* dist, uint8_t* isnew,
-                   int32_t* aside_ids, double* aside_dist) {
+void og_merge_init(const void* vec, int64_t n1, int64_t base1, int64_t n2, int64_t base2, int d,
+                   int k, int metric, uint64_t seed, const int32_t* ids1, const double* dist1,
+                   const int32_t* ids2, const double* dist2, int32_t* ids, double* dist,
+                   uint8_t* isnew, int32_t* aside_ids, double* aside_dist) {
   const int keep = (k + 1) / 2, fill = k / 2;
   const int64_t n = n1 + n2;
   entry_t* row = (entry_t*)malloc(sizeof(entry_t) * (size_t)k);
@@ -583,15 +605,14 @@ void og_merge_init(const void* vec, int64_t n1, int64_t n2, int d, int k, int me
     const int first = s < n1;
     const int32_t* sid = first ? ids1 + s * k : ids2 + (s - n1) * k;
     const double* sdist = first ? dist1 + s * k : dist2 + (s - n1) * k;
-    const int32_t shift = first ? 0 : (int32_t)n1;
     for (int j = 0; j < keep; ++j) {
-      row[j].id = sid[j] + shift;
+      row[j].id = og_to_internal(sid[j], n1, base1, n2, base2);
       row[j].d = sdist[j];
       row[j].isnew = 0;
       row[j].fresh = 0;
     }
     for (int j = 0; j < fill; ++j) {
-      aside_ids[s * fill + j] = sid[keep + j] + shift;
+      aside_ids[s * fill + j] = og_to_internal(sid[keep + j], n1, base1, n2, base2);
       aside_dist[s * fill + j] = sdist[keep + j];
     }
     draw_distinct(seed, OG_TAG_MERGE, (uint32_t)s, fill, (uint32_t)(first ? n2 : n1),
@@ -648,4 +669,25 @@ void og_merge_final(int64_t n, int k, int32_t* ids, double* dist, const int32_t*
     }
   }
   free(pool);
+}
+
+/* Back to collection ids after a merge: renumber every entry and restore the
+ * (distance, id) order of each list under the collection ids. */
+void og_merge_to_global(int64_t n1, int64_t base1, int64_t n2, int64_t base2, int k,
+                        int32_t* ids, double* dist) {
+  entry_t* row = (entry_t*)malloc(sizeof(entry_t) * (size_t)k);
+  for (int64_t s = 0; s < n1 + n2; ++s) {
+    for (int j = 0; j < k; ++j) {
+      row[j].id = og_to_global(ids[s * k + j], n1, base1, n2, base2);
+      row[j].d = dist[s * k + j];
+      row[j].isnew = 0;
+      row[j].fresh = 0;
+    }
+    qsort(row, (size_t)k, sizeof(entry_t), entry_cmp);
+    for (int j = 0; j < k; ++j) {
+      ids[s * k + j] = row[j].id;
+      dist[s * k + j] = row[j].d;
+    }
+  }
+  free(row);
 }

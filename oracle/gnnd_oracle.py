@@ -68,9 +68,12 @@ def _load():
     lib.og_update.argtypes = [C.c_int64, C.c_int, C.c_int, i32p, f64p, u8p, i32p, i32p, f64p,
                               i32p]
     lib.og_merge_init.restype = None
-    lib.og_merge_init.argtypes = [vp, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int,
-                                  C.c_uint64, i32p, f64p, i32p, f64p, i32p, f64p, u8p, i32p,
-                                  f64p]
+    lib.og_merge_init.argtypes = [vp, C.c_int64, C.c_int64, C.c_int64, C.c_int64, C.c_int,
+                                  C.c_int, C.c_int, C.c_uint64, i32p, f64p, i32p, f64p, i32p,
+                                  f64p, u8p, i32p, f64p]
+    lib.og_merge_to_global.restype = None
+    lib.og_merge_to_global.argtypes = [C.c_int64, C.c_int64, C.c_int64, C.c_int64, C.c_int,
+                                       i32p, f64p]
     lib.og_merge_final.restype = None
     lib.og_merge_final.argtypes = [C.c_int64, C.c_int, i32p, f64p, i32p, f64p]
     _lib = lib
@@ -199,16 +202,22 @@ def build(vectors, k, p, metric, seed, iters):
     return g, stats
 
 
-def merge_init(vectors, n1, k, metric, seed, g1, g2):
+def merge_init(vectors, n1, k, metric, seed, g1, g2, base1=0, base2=None):
+    """g1, g2 carry collection ids: S1 = [base1, base1+n1), S2 = [base2, base2+n2).
+    The returned graph uses the merge's own numbering (S1 rows, S2 rows, then
+    n + collection id for entries that belong to neither set)."""
     v = _vec(vectors, metric)
     n, d = v.shape
     n2 = n - n1
+    base2 = n1 if base2 is None else base2
     fill = k // 2
     g = Graph(np.empty((n, k), np.int32), np.empty((n, k), np.float64), np.empty((n, k), np.uint8))
     aside_ids = np.empty((n, fill), np.int32)
     aside_dist = np.empty((n, fill), np.float64)
-    _load().og_merge_init(v.ctypes.data, n1, n2, d, k, metric, seed, g1.ids, g1.dist, g2.ids,
-                          g2.dist, g.ids, g.dist, g.isnew, aside_ids, aside_dist)
+    _load().og_merge_init(v.ctypes.data, n1, base1, n2, base2, d, k, metric, seed,
+                          np.ascontiguousarray(g1.ids), np.ascontiguousarray(g1.dist),
+                          np.ascontiguousarray(g2.ids), np.ascontiguousarray(g2.dist),
+                          g.ids, g.dist, g.isnew, aside_ids, aside_dist)
     return g, aside_ids, aside_dist
 
 
@@ -217,17 +226,50 @@ def merge_final(g, aside_ids, aside_dist):
     _load().og_merge_final(n, k, g.ids, g.dist, aside_ids, aside_dist)
 
 
-def merge(vectors, n1, k, p, metric, seed, g1, g2, iters):
-    """Alg. 3 as a whole.  vectors = S1 rows then S2 rows; g2 holds ids local to
-    S2.  Returns the merged graph (global ids) and per-iteration statistics."""
-    g, aside_ids, aside_dist = merge_init(vectors, n1, k, metric, seed, g1, g2)
+def merge(vectors, n1, k, p, metric, seed, g1, g2, iters, base1=0, base2=None):
+    """Alg. 3 as a whole.  vectors = S1 rows then S2 rows; g1 and g2 carry
+    collection ids (S1 = [base1, base1+n1), S2 = [base2, base2+n2), default
+    0 and n1: the union itself).  Returns the merged graph in collection ids,
+    lists ascending by (distance, id), and per-iteration statistics."""
+    n = len(vectors)
+    base2 = n1 if base2 is None else base2
+    g, aside_ids, aside_dist = merge_init(vectors, n1, k, metric, seed, g1, g2, base1, base2)
     stats = []
     for it in range(1, iters + 1):
         st = iterate(vectors, metric, g, p, seed, it, split=n1)
         stats.append({key: st[key] for key in ("iter", "inserts", "dist_evals", "sum_new",
                                                "sum_old", "proposals")})
     merge_final(g, aside_ids, aside_dist)
+    _load().og_merge_to_global(n1, base1, n - n1, base2, k, g.ids, g.dist)
     return g, stats
+
+
+def build_sharded(vectors, shards, k, p, metric, seed, build_iters, merge_iters):
+    """Sec. 5.1 out-of-core scheme on equal shards of consecutive rows: a graph
+    per shard (seed + shard number), then every pair of shards merged once, in
+    the order (0,1), (0,2), ..., (1,2), ...; each merged graph is stored back as
+    the two shards' sub-graphs.  Merge number m uses seed + 1000 + m."""
+    n = len(vectors)
+    size = n // shards
+    bases = [i * size for i in range(shards)]
+    sizes = [size] * (shards - 1) + [n - size * (shards - 1)]
+    graphs = []
+    for i in range(shards):
+        g, _ = build(vectors[bases[i]:bases[i] + sizes[i]], k, p, metric, seed + i, build_iters)
+        graphs.append(Graph(g.ids + bases[i], g.dist, g.isnew))
+    m = 0
+    for i in range(shards):
+        for j in range(i + 1, shards):
+            x = np.concatenate([vectors[bases[i]:bases[i] + sizes[i]],
+                                vectors[bases[j]:bases[j] + sizes[j]]])
+            g, _ = merge(x, sizes[i], k, p, metric, seed + 1000 + m, graphs[i], graphs[j],
+                         merge_iters, bases[i], bases[j])
+            graphs[i] = Graph(g.ids[:sizes[i]].copy(), g.dist[:sizes[i]].copy(), None)
+            graphs[j] = Graph(g.ids[sizes[i]:].copy(), g.dist[sizes[i]:].copy(), None)
+            m += 1
+    ids = np.concatenate([g.ids for g in graphs])
+    dist = np.concatenate([g.dist for g in graphs])
+    return Graph(ids, dist, np.zeros_like(ids, dtype=np.uint8))
 
 
 # --- evaluation formulas ----------------------------------------------------

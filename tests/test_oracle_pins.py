@@ -439,16 +439,17 @@ def test_recall_formula_on_a_hand_made_case():
 
 
 # ------------------------------------------------------------- merge --------
-def _exact_graph(x, metric, k):
+def _exact_graph(x, metric, k, base=0):
+    """Exact k-NN graph of x; ids shifted to the collection range [base, base + n)."""
     ids, dist = og.bruteforce(x, metric, np.arange(len(x)), k)
-    return og.Graph(ids, dist, np.zeros_like(ids, dtype=np.uint8))
+    return og.Graph(ids + base, dist, np.zeros_like(ids, dtype=np.uint8))
 
 
 def test_merge_final_is_top_k_of_union_with_the_set_aside_half():
     k, n1, n2 = 9, 40, 30
     x = W.uniform_f32(n1 + n2, 6, seed=72)
     g1 = _exact_graph(x[:n1], og.L2SQ_F32, k)
-    g2 = _exact_graph(x[n1:], og.L2SQ_F32, k)
+    g2 = _exact_graph(x[n1:], og.L2SQ_F32, k, base=n1)
     g, aside_ids, aside_dist = og.merge_init(x, n1, k, og.L2SQ_F32, 4, g1, g2)
     og.iterate(x, og.L2SQ_F32, g, k, 4, 1, split=n1)
     before = g.copy()
@@ -469,7 +470,7 @@ def test_merge_with_no_iterations_keeps_each_input_list():
     k, n1, n2 = 8, 30, 25
     x = W.uniform_f32(n1 + n2, 5, seed=76)
     g1 = _exact_graph(x[:n1], og.L2SQ_F32, k)
-    g2 = _exact_graph(x[n1:], og.L2SQ_F32, k)
+    g2 = _exact_graph(x[n1:], og.L2SQ_F32, k, base=n1)
     g, _ = og.merge(x, n1, k, k, og.L2SQ_F32, 5, g1, g2, 0)
     assert (g.dist[:n1] <= g1.dist).all() and (g.dist[n1:] <= g2.dist).all()
     for s in range(n1):
@@ -481,14 +482,14 @@ def test_merge_init_structure():
     k, n1, n2, seed = 9, 40, 30, 4
     x = W.uniform_f32(n1 + n2, 6, seed=73)
     g1 = _exact_graph(x[:n1], og.L2SQ_F32, k)
-    g2 = _exact_graph(x[n1:], og.L2SQ_F32, k)
+    g2 = _exact_graph(x[n1:], og.L2SQ_F32, k, base=n1)
     g, aside_ids, aside_dist = og.merge_init(x, n1, k, og.L2SQ_F32, seed, g1, g2)
     keep, fill = 5, 4
     for s in range(n1 + n2):
         first = s < n1
         src = g1 if first else g2
         loc = s if first else s - n1
-        shift = 0 if first else n1
+        shift = 0  # the input lists already carry the ids of the union
         kept = (src.ids[loc, :keep] + shift).tolist()
         aside = (src.ids[loc, keep:] + shift).tolist()
         assert aside_ids[s].tolist() == aside and (aside_dist[s] == src.dist[loc, keep:]).all()
@@ -512,7 +513,7 @@ def test_merge_of_exact_subgraphs_recovers_the_exact_graph_and_never_worsens():
     k, p, n1, n2 = 10, 10, 150, 130
     x = W.uniform_f32(n1 + n2, 6, seed=74)
     g1 = _exact_graph(x[:n1], og.L2SQ_F32, k)
-    g2 = _exact_graph(x[n1:], og.L2SQ_F32, k)
+    g2 = _exact_graph(x[n1:], og.L2SQ_F32, k, base=n1)
     g, stats = og.merge(x, n1, k, p, og.L2SQ_F32, 11, g1, g2, 6)
     n = n1 + n2
     _check_lists(g, x, og.L2SQ_F32)
@@ -532,7 +533,7 @@ def test_merge_join_only_proposes_cross_subset_pairs():
     k, p, n1, n2 = 8, 8, 50, 40
     x = W.uniform_f32(n1 + n2, 5, seed=75)
     g1 = _exact_graph(x[:n1], og.L2SQ_F32, k)
-    g2 = _exact_graph(x[n1:], og.L2SQ_F32, k)
+    g2 = _exact_graph(x[n1:], og.L2SQ_F32, k, base=n1)
     g, aside_ids, aside_dist = og.merge_init(x, n1, k, og.L2SQ_F32, 3, g1, g2)
     for it in range(1, 4):
         snew, cnew, sold, cold = og.sample(g, p, 3, it)
@@ -545,3 +546,78 @@ def test_merge_join_only_proposes_cross_subset_pairs():
             for j in range(pcnt[s]):
                 assert (pu[s, j] < n1) != (pv[s, j] < n1)
         og.update(g, p, pu, pv, pd, pcnt)
+
+
+# ------------------------------------------------- shards and frozen entries -
+def test_merge_keeps_third_shard_entries_frozen():
+    # Three shards A, B, C of one collection.  After merging (A, B), A's lists
+    # hold ids of B; in the merge (A, C) those entries are frozen: they stay in
+    # place by their stored distance unless something closer displaces them, and
+    # no join ever involves them.
+    k, p, m = 8, 8, 60
+    x = W.uniform_f32(3 * m, 5, seed=81)
+    A, B, Cc = (slice(0, m), slice(m, 2 * m), slice(2 * m, 3 * m))
+    gA = _exact_graph(x[A], og.L2SQ_F32, k, base=0)
+    gB = _exact_graph(x[B], og.L2SQ_F32, k, base=m)
+    gC = _exact_graph(x[Cc], og.L2SQ_F32, k, base=2 * m)
+    gAB, _ = og.merge(np.concatenate([x[A], x[B]]), m, k, p, og.L2SQ_F32, 7, gA, gB, 4, 0, m)
+    gA2 = og.Graph(gAB.ids[:m].copy(), gAB.dist[:m].copy(), None)
+    assert (gA2.ids >= m).any()  # A's lists now point into B
+    xAC = np.concatenate([x[A], x[Cc]])
+    g, aside_ids, aside_dist = og.merge_init(xAC, m, k, og.L2SQ_F32, 9, gA2, gC, 0, 2 * m)
+    n = 2 * m
+    frozen_before = {s: {int(v) for v in np.concatenate([g.ids[s], aside_ids[s]]) if v >= n}
+                     for s in range(n)}
+    assert any(frozen_before.values())
+    for it in range(1, 4):
+        st = og.iterate(xAC, og.L2SQ_F32, g, p, 9, it, split=m)
+        for arr in (st["snew"], st["sold"]):
+            assert arr.max() < n  # frozen entries are never sampled
+    og.merge_final(g, aside_ids, aside_dist)
+    for s in range(n):  # a frozen entry only leaves when k closer entries exist
+        now = {int(v) for v in g.ids[s] if v >= n}
+        assert now <= frozen_before[s]
+        kth = g.dist[s, -1]
+        pool = dict(zip(np.concatenate([aside_ids[s]]).tolist(), aside_dist[s].tolist()))
+        for v in frozen_before[s] - now:
+            if v in pool:
+                assert pool[v] >= kth
+    # full merge in collection ids: sorted by (distance, id), true distances, better than before
+    out, _ = og.merge(xAC, m, k, p, og.L2SQ_F32, 9, gA2, gC, 3, 0, 2 * m)
+    for s in range(n):
+        keys = list(zip(out.dist[s].tolist(), out.ids[s].tolist()))
+        assert keys == sorted(keys) and len(set(out.ids[s].tolist())) == k
+        g_s = s if s < m else s + m  # collection id of row s
+        for v, dd in zip(out.ids[s], out.dist[s]):
+            assert dd == og.distance(x, og.L2SQ_F32, g_s, int(v))
+    assert (out.dist[:m] <= gA2.dist).all() and (out.dist[m:] <= gC.dist).all()
+
+
+def test_renumbering_round_trip():
+    lib = og.gnnd_oracle._load()
+    n1, b1, n2, b2 = 5, 40, 7, 10
+    seen = set()
+    for gid in range(0, 60):
+        i = lib.og_to_internal(gid, n1, b1, n2, b2)
+        assert lib.og_to_global(i, n1, b1, n2, b2) == gid
+        assert (i < n1) == (b1 <= gid < b1 + n1)
+        assert (n1 <= i < n1 + n2) == (b2 <= gid < b2 + n2)
+        seen.add(i)
+    assert len(seen) == 60
+
+
+def test_sharded_build_covers_the_whole_collection():
+    n, shards, k, p = 1200, 4, 10, 10
+    x = W.uniform_f32(n, 6, seed=82)
+    g = og.build_sharded(x, shards, k, p, og.L2SQ_F32, 42, 6, 4)
+    ids, dist = og.bruteforce(x, og.L2SQ_F32, np.arange(n), k)
+    tol, _ = og.recall_at(g.ids, g.dist, ids, dist, k)
+    assert tol > 0.9, tol
+    for s in range(0, n, 13):
+        keys = list(zip(g.dist[s].tolist(), g.ids[s].tolist()))
+        assert keys == sorted(keys) and s not in g.ids[s]
+        for v, dd in zip(g.ids[s], g.dist[s]):
+            assert dd == og.distance(x, og.L2SQ_F32, s, int(v))
+    # every shard's lists reach into the other shards
+    own = (g.ids // (n // shards)) == (np.arange(n)[:, None] // (n // shards))
+    assert 0.1 < own.mean() < 0.6
