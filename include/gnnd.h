@@ -169,17 +169,51 @@ int gnnd_get_proposals(gnnd_ctx* ctx, int32_t* u_dev, int32_t* v_dev, void* dist
 
 /* GGM (Sec. 5.1, Alg. 3): merge the k-NN graph G1 of S1 (n1 vectors at
  * vec1_dev) and G2 of S2 (n2 vectors at vec2_dev) into the graph of S1 u S2,
- * prm->n = n1 + n2, rows 0..n1-1 = S1 then S2; input ids are local to their
- * set, output ids are rows of the union.  Each list keeps its first ceil(k/2)
- * entries, the rest is set aside and replaced by floor(k/2) random objects of
- * the other set flagged NEW; `iters` GNND iterations then evaluate only pairs
- * from different sets (and no NEW x NEW pairs); finally each list is the best k
- * of the refined list and its set-aside half.  Needs min(n1, n2) >= floor(k/2).
+ * prm->n = n1 + n2, output rows 0..n1-1 = S1 then S2.
+ * Ids are ids of a collection of id_space objects in which S1 is the range
+ * [base1, base1 + n1) and S2 is [base2, base2 + n2) (disjoint; for two halves
+ * of one array: base1 = 0, base2 = n1, id_space = n).  Input lists may also
+ * hold ids outside both ranges (left by an earlier merge with a third shard,
+ * Sec. 5.1): such entries are frozen - they compete for their place with their
+ * stored distance but are never sampled.  A list must not yet hold ids of the
+ * other set.  Needs n + id_space <= 2^30.
+ * Each list keeps its first ceil(k/2) entries, the rest is set aside and
+ * replaced by floor(k/2) random objects of the other set flagged NEW; `iters`
+ * GNND iterations then evaluate only pairs from different sets (and no
+ * NEW x NEW pairs); finally each list is the best k of the refined list and its
+ * set-aside half, in collection ids, ascending by (distance, id).
  * Synchronises when stats_host (array of `iters` entries, may be NULL) is given. */
-int gnnd_merge(const gnnd_params* prm, const void* vec1_dev, int64_t n1, const void* vec2_dev,
-               int64_t n2, const int32_t* ids1_dev, const void* dist1_dev,
-               const int32_t* ids2_dev, const void* dist2_dev, int32_t iters,
-               int32_t* ids_out_dev, void* dist_out_dev, gnnd_iter_stats* stats_host);
+int gnnd_merge(const gnnd_params* prm, const void* vec1_dev, int64_t n1, int64_t base1,
+               const void* vec2_dev, int64_t n2, int64_t base2, int64_t id_space,
+               const int32_t* ids1_dev, const void* dist1_dev, const int32_t* ids2_dev,
+               const void* dist2_dev, int32_t iters, int32_t* ids_out_dev, void* dist_out_dev,
+               gnnd_iter_stats* stats_host);
+
+/* Out-of-core construction (Sec. 5.1) on one GPU.  The collection of prm->n
+ * vectors stays in pinned host memory (vectors_host, n*d elements); it is cut
+ * into `shards` shards of floor(n/shards) consecutive rows (the last takes the
+ * remainder).  Every shard is built on its own (gnnd_build with seed + shard
+ * number, build_iters iterations), then every pair of shards is merged once by
+ * GGM (merge number m, in rounds of disjoint pairs, with seed + 1000 + m and
+ * merge_iters iterations) and stored back as the two shards' sub-graphs.  Only
+ * two shards are resident at a time; prm->workspace_dev / workspace_bytes is a
+ * device arena of gnnd_sharded_arena_bytes() bytes holding two alternating
+ * slots plus the scratch of one merge; uploads and downloads run on copy_stream
+ * (a second stream, required) while prm->stream computes.
+ * ids_host / dist_host (pinned host memory, n*k each) receive the final graph
+ * in collection ids and hold the sub-graphs in between.  The call returns after
+ * both streams have drained.  stats_host may be NULL. */
+typedef struct gnnd_shard_stats {
+  int32_t builds, merges;
+  float ms_build; /* compute-stream time of the shard builds (events)  */
+  float ms_merge; /* compute-stream time of all pairwise merges        */
+  float ms_total; /* host wall time of the whole call, copies included */
+  float reserved;
+} gnnd_shard_stats;
+size_t gnnd_sharded_arena_bytes(const gnnd_params* prm, int32_t shards);
+int gnnd_build_sharded(const gnnd_params* prm, const void* vectors_host, int32_t shards,
+                       int32_t build_iters, int32_t merge_iters, int32_t* ids_host,
+                       void* dist_host, void* copy_stream, gnnd_shard_stats* stats_host);
 
 /* Exact K nearest neighbours by exhaustive search (the ground truth of
  * Recall@K, Sec. 6.1) of nq query nodes (ids in queries_dev) against all n

@@ -244,11 +244,26 @@ def merge(vectors, n1, k, p, metric, seed, g1, g2, iters, base1=0, base2=None):
     return g, stats
 
 
+def pair_schedule(shards):
+    """Every pair of shards once ("any two sub-graphs has been merged once",
+    Sec. 5.1), as a round-robin tournament: rounds of disjoint pairs, the last
+    shard fixed and the others rotating around it (an odd count gets a bye)."""
+    m = shards + (shards % 2)
+    ring = m - 1
+    order = []
+    for r in range(ring):
+        for i in range(m // 2):
+            a, b = (m - 1, r) if i == 0 else ((r + i) % ring, (r - i) % ring)
+            if a < shards and b < shards:
+                order.append((min(a, b), max(a, b)))
+    return order
+
+
 def build_sharded(vectors, shards, k, p, metric, seed, build_iters, merge_iters):
     """Sec. 5.1 out-of-core scheme on equal shards of consecutive rows: a graph
-    per shard (seed + shard number), then every pair of shards merged once, in
-    the order (0,1), (0,2), ..., (1,2), ...; each merged graph is stored back as
-    the two shards' sub-graphs.  Merge number m uses seed + 1000 + m."""
+    per shard (seed + shard number), then every pair of shards merged once in
+    the order of pair_schedule(); each merged graph is stored back as the two
+    shards' sub-graphs.  Merge number m uses seed + 1000 + m."""
     n = len(vectors)
     size = n // shards
     bases = [i * size for i in range(shards)]
@@ -257,16 +272,13 @@ def build_sharded(vectors, shards, k, p, metric, seed, build_iters, merge_iters)
     for i in range(shards):
         g, _ = build(vectors[bases[i]:bases[i] + sizes[i]], k, p, metric, seed + i, build_iters)
         graphs.append(Graph(g.ids + bases[i], g.dist, g.isnew))
-    m = 0
-    for i in range(shards):
-        for j in range(i + 1, shards):
-            x = np.concatenate([vectors[bases[i]:bases[i] + sizes[i]],
-                                vectors[bases[j]:bases[j] + sizes[j]]])
-            g, _ = merge(x, sizes[i], k, p, metric, seed + 1000 + m, graphs[i], graphs[j],
-                         merge_iters, bases[i], bases[j])
-            graphs[i] = Graph(g.ids[:sizes[i]].copy(), g.dist[:sizes[i]].copy(), None)
-            graphs[j] = Graph(g.ids[sizes[i]:].copy(), g.dist[sizes[i]:].copy(), None)
-            m += 1
+    for m, (i, j) in enumerate(pair_schedule(shards)):
+        x = np.concatenate([vectors[bases[i]:bases[i] + sizes[i]],
+                            vectors[bases[j]:bases[j] + sizes[j]]])
+        g, _ = merge(x, sizes[i], k, p, metric, seed + 1000 + m, graphs[i], graphs[j],
+                     merge_iters, bases[i], bases[j])
+        graphs[i] = Graph(g.ids[:sizes[i]].copy(), g.dist[:sizes[i]].copy(), None)
+        graphs[j] = Graph(g.ids[sizes[i]:].copy(), g.dist[sizes[i]:].copy(), None)
     ids = np.concatenate([g.ids for g in graphs])
     dist = np.concatenate([g.dist for g in graphs])
     return Graph(ids, dist, np.zeros_like(ids, dtype=np.uint8))

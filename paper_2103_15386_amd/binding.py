@@ -20,6 +20,7 @@ EXPORTS = [
     "gnnd_iterate", "gnnd_step_sample", "gnnd_step_join", "gnnd_step_update", "gnnd_build",
     "gnnd_get_graph", "gnnd_set_graph", "gnnd_get_samples", "gnnd_get_proposals", "gnnd_merge",
     "gnnd_exact_knn", "gnnd_join_path", "gnnd_set_profiling", "gnnd_get_stage_ms",
+    "gnnd_sharded_arena_bytes", "gnnd_build_sharded",
 ]
 
 
@@ -44,6 +45,11 @@ class IterStats(C.Structure):
 
     def as_dict(self):
         return {f: getattr(self, f) for f, _ in self._fields_ if not f.startswith("reserved")}
+
+
+class ShardStats(C.Structure):
+    _fields_ = [("builds", C.c_int32), ("merges", C.c_int32), ("ms_build", C.c_float),
+                ("ms_merge", C.c_float), ("ms_total", C.c_float), ("reserved", C.c_float)]
 
 
 def library_path():
@@ -88,7 +94,11 @@ def load_library():
     lib.gnnd_get_proposals.restype = C.c_int
     lib.gnnd_get_proposals.argtypes = [vp, vp, vp, vp]
     lib.gnnd_merge.restype = C.c_int
-    lib.gnnd_merge.argtypes = [PP, vp, i64, vp, i64, vp, vp, vp, vp, i32, vp, vp, SP]
+    lib.gnnd_merge.argtypes = [PP, vp, i64, i64, vp, i64, i64, i64, vp, vp, vp, vp, i32, vp, vp, SP]
+    lib.gnnd_sharded_arena_bytes.restype = C.c_size_t
+    lib.gnnd_sharded_arena_bytes.argtypes = [PP, i32]
+    lib.gnnd_build_sharded.restype = C.c_int
+    lib.gnnd_build_sharded.argtypes = [PP, vp, i32, i32, i32, vp, vp, vp, C.POINTER(ShardStats)]
     lib.gnnd_join_path.restype = C.c_int
     lib.gnnd_join_path.argtypes = [vp]
     lib.gnnd_set_profiling.restype = C.c_int
@@ -274,8 +284,10 @@ def gnnd_build(vectors, k, p, metric=L2SQ_F32, seed=42, iters=12, join_path=JOIN
 
 
 def gnnd_merge(vec1, vec2, ids1, dist1, ids2, dist2, k, p, metric=L2SQ_F32, seed=42, iters=6,
-               join_path=JOIN_AUTO, want_stats=False):
-    """GGM of two graphs; returns (ids, dist[, stats]) over the union, S1 rows first."""
+               join_path=JOIN_AUTO, want_stats=False, base1=0, base2=None, id_space=None):
+    """GGM of two graphs given in collection ids (S1 = [base1, base1+n1), S2 =
+    [base2, base2+n2); default: the two halves of one array); returns (ids,
+    dist[, stats]) for the rows of S1 then S2, in collection ids."""
     lib = load_library()
     et, dt = _elem_dtype(metric), _dist_dtype(metric)
     _require_device(vec1, et, "vec1")
@@ -286,6 +298,8 @@ def gnnd_merge(vec1, vec2, ids1, dist1, ids2, dist2, k, p, metric=L2SQ_F32, seed
     n1, d = vec1.shape
     n2 = vec2.shape[0]
     n = n1 + n2
+    base2 = n1 if base2 is None else base2
+    id_space = max(base1 + n1, base2 + n2) if id_space is None else id_space
     need = workspace_bytes(n, d, k, p, metric)
     dev = vec1.device
     ws = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
@@ -293,14 +307,46 @@ def gnnd_merge(vec1, vec2, ids1, dist1, ids2, dist2, k, p, metric=L2SQ_F32, seed
     ids = torch.empty((n, k), dtype=torch.int32, device=dev)
     dist = torch.empty((n, k), dtype=dt, device=dev)
     stats = (IterStats * max(iters, 1))()
-    rc = lib.gnnd_merge(C.byref(prm), vec1.data_ptr(), n1, vec2.data_ptr(), n2, ids1.data_ptr(),
-                        dist1.data_ptr(), ids2.data_ptr(), dist2.data_ptr(), iters,
-                        ids.data_ptr(), dist.data_ptr(), stats if want_stats else None)
+    rc = lib.gnnd_merge(C.byref(prm), vec1.data_ptr(), n1, base1, vec2.data_ptr(), n2, base2,
+                        id_space, ids1.data_ptr(), dist1.data_ptr(), ids2.data_ptr(),
+                        dist2.data_ptr(), iters, ids.data_ptr(), dist.data_ptr(),
+                        stats if want_stats else None)
     _check(rc)
     torch.cuda.current_stream(dev).synchronize()  # the workspace dies with this frame
     if want_stats:
         return ids, dist, [stats[i].as_dict() for i in range(iters)]
     return ids, dist
+
+
+def gnnd_build_sharded(vectors_host, shards, k, p, metric=L2SQ_F32, seed=42, build_iters=8,
+                       merge_iters=4, join_path=JOIN_AUTO, device="cuda:0"):
+    """Out-of-core build (Sec. 5.1): `vectors_host` is a pinned host tensor that
+    never becomes resident as a whole.  Returns (ids, dist, stats): pinned host
+    tensors n x k in collection ids, and the timing record."""
+    lib = load_library()
+    et, dt = _elem_dtype(metric), _dist_dtype(metric)
+    if (not isinstance(vectors_host, torch.Tensor) or vectors_host.is_cuda
+            or not vectors_host.is_pinned() or vectors_host.dtype != et
+            or not vectors_host.is_contiguous()):
+        raise GnndError(EINVAL, f"vectors_host must be a contiguous pinned host tensor of {et}")
+    n, d = vectors_host.shape
+    dev = torch.device(device)
+    prm = make_params(n, d, k, p, metric, seed, join_path)
+    need = int(lib.gnnd_sharded_arena_bytes(C.byref(prm), shards))
+    if need == 0:
+        rc = lib.gnnd_build_sharded(C.byref(prm), vectors_host.data_ptr(), shards, build_iters,
+                                    merge_iters, None, None, None, None)
+        raise GnndError(rc, _err())
+    arena = torch.empty(need, dtype=torch.uint8, device=dev)
+    copy_stream = torch.cuda.Stream(device=dev)
+    prm = make_params(n, d, k, p, metric, seed, join_path, _stream_ptr(dev), arena)
+    ids = torch.empty((n, k), dtype=torch.int32).pin_memory()
+    dist = torch.empty((n, k), dtype=dt).pin_memory()
+    st = ShardStats()
+    _check(lib.gnnd_build_sharded(C.byref(prm), vectors_host.data_ptr(), shards, build_iters,
+                                  merge_iters, ids.data_ptr(), dist.data_ptr(),
+                                  copy_stream.cuda_stream, C.byref(st)))
+    return ids, dist, {f: getattr(st, f) for f, _ in st._fields_ if f != "reserved"}
 
 
 def exact_knn(vectors, queries, K, metric=L2SQ_F32):

@@ -224,6 +224,25 @@ struct VecSrc {
   }
 };
 
+// Numbering inside one merge (Sec. 5.1 shards).  The two sets are the ranges
+// [base1, base1 + n1) and [base2, base2 + n2) of a larger collection; inside
+// the merge S1 is 0..n1-1, S2 is n1..n-1, and any other object (a list entry
+// left by an earlier merge with a third shard: "frozen", never sampled) is
+// n + its collection id.
+struct MergeIds {
+  int64_t n1, base1, n2, base2;
+  __host__ __device__ uint32_t to_internal(int64_t g) const {
+    if (g >= base1 && g < base1 + n1) return (uint32_t)(g - base1);
+    if (g >= base2 && g < base2 + n2) return (uint32_t)(n1 + g - base2);
+    return (uint32_t)(n1 + n2 + g);
+  }
+  __host__ __device__ int32_t to_global(int64_t i) const {
+    if (i < n1) return (int32_t)(base1 + i);
+    if (i < n1 + n2) return (int32_t)(base2 + i - n1);
+    return (int32_t)(i - n1 - n2);
+  }
+};
+
 // Draw `count` (<= 64) distinct ids out of [0, range) + base for node s, one per
 // lane: slot j takes hash(base_hash, s, j, attempt) mapped onto the range for
 // attempt = 0, 1, ... until the id differs from `forbid` and from the ids of

@@ -3,12 +3,16 @@
 // allocated here; every array is carved out of the caller's workspace.
 #include <hip/hip_runtime.h>
 
+#include <chrono>
 #include <cstdio>
 #include <cstring>
 #include <new>
 #include <string>
+#include <utility>
+#include <vector>
 
 #include "../../include/gnnd.h"
+#include "device_utils.hpp"
 #include "kernels.hpp"
 
 using namespace gnnd;
@@ -315,6 +319,291 @@ int iterate_impl(gnnd_ctx* c, gnnd_iter_stats* out) {
   return GNND_OK;
 }
 
+// ---------------------------------------------------------------------------
+// GGM on two sets given in collection ids (shared by gnnd_merge and the shard driver).
+int merge_impl(const gnnd_params* prm, const void* vec1, int64_t n1, int64_t base1,
+               const void* vec2, int64_t n2, int64_t base2, int64_t id_space,
+               const int32_t* ids1, const void* dist1, const int32_t* ids2, const void* dist2,
+               int32_t iters, int32_t* ids_out, void* dist_out, gnnd_iter_stats* stats) {
+  if (const char* m = check_params(prm)) return fail(nullptr, GNND_EINVAL, m);
+  if (n1 <= 0 || n2 <= 0 || n1 + n2 != prm->n)
+    return fail(nullptr, GNND_EINVAL, "n1 + n2 must equal params.n, both positive");
+  if (n1 <= prm->k || n2 <= prm->k)
+    return fail(nullptr, GNND_EINVAL, "each input graph needs more than k nodes");
+  if (base1 < 0 || base2 < 0 || base1 + n1 > id_space || base2 + n2 > id_space ||
+      (base1 < base2 + n2 && base2 < base1 + n1))
+    return fail(nullptr, GNND_EINVAL, "the two id ranges must be disjoint and inside id_space");
+  if (prm->n + id_space > ((int64_t)1 << 30))
+    return fail(nullptr, GNND_EINVAL, "n + id_space must be <= 2^30");
+  if (iters < 0) return fail(nullptr, GNND_EINVAL, "iters must be >= 0");
+  if (!vec2 || !ids1 || !dist1 || !ids2 || !dist2 || !ids_out || !dist_out)
+    return fail(nullptr, GNND_EINVAL, "NULL pointer argument");
+  gnnd_ctx* c = nullptr;
+  int rc = create_impl(&c, prm, vec1, vec2, n1, true);
+  if (rc != GNND_OK) return rc;
+  const MergeIds mi{n1, base1, n2, base2};
+  hipError_t e = launch_merge_init(c->sh, c->ds, prm->seed, mi, ids1, dist1, ids2, dist2, c->stream);
+  if (e != hipSuccess) {
+    rc = hip_fail(nullptr, e, "merge init kernel");
+  } else {
+    c->has_graph = true;
+    for (int32_t t = 0; t < iters && rc == GNND_OK; ++t)
+      rc = iterate_impl(c, stats ? stats + t : nullptr);
+    if (rc == GNND_OK) {
+      e = launch_merge_final(c->sh, c->ds, mi, ids_out, dist_out, c->stream);
+      if (e != hipSuccess) rc = hip_fail(nullptr, e, "merge final kernel");
+    } else {
+      g_last_error = c->err;
+    }
+  }
+  gnnd_destroy(c);
+  return rc;
+}
+
+// ---------------------------------------------------------------------------
+// Out-of-core scheme of Sec. 5.1 on one GPU: equal shards of consecutive rows
+// live in (pinned) host memory; each is built on its own, then every pair of
+// shards is merged once and stored back as two sub-graphs.  Two device slots
+// alternate, so a copy stream moves the next step's data in and the previous
+// step's results out while the compute stream works.
+struct ShardPlan {
+  int shards;
+  int64_t size, last, maxs;  // rows per shard, rows of the last shard, larger of the two
+  size_t elem, vec_bytes, graph_bytes, off_vec[2][2], off_ids[2][2], off_dist[2][2],
+      off_oids[2], off_odist[2], off_ws, ws_bytes, total;
+};
+
+const char* plan_shards(const gnnd_params* prm, int32_t shards, ShardPlan* pl) {
+  if (!prm) return "params is NULL";
+  if (shards < 2 || shards > 1024) return "shards must be in [2, 1024]";
+  gnnd_params q = *prm;
+  pl->shards = shards;
+  pl->size = prm->n / shards;
+  pl->last = prm->n - pl->size * (shards - 1);
+  pl->maxs = pl->last > pl->size ? pl->last : pl->size;
+  if (pl->size <= prm->k) return "every shard needs more than k rows";
+  q.n = pl->size + pl->maxs;  // the largest merge
+  if (const char* m = check_params(&q)) return m;
+  if (q.n + prm->n > ((int64_t)1 << 30)) return "collection too large: 2 shards + n must be <= 2^30";
+  pl->elem = prm->metric == GNND_L2SQ_U8 ? 1 : 4;
+  pl->vec_bytes = (size_t)pl->maxs * prm->d * pl->elem;
+  pl->graph_bytes = (size_t)pl->maxs * prm->k * 4;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
+  for (int s = 0; s < 2; ++s) {
+    for (int h = 0; h < 2; ++h) {
+      pl->off_vec[s][h] = take(pl->vec_bytes);
+      pl->off_ids[s][h] = take(pl->graph_bytes);
+      pl->off_dist[s][h] = take(pl->graph_bytes);
+    }
+    pl->off_oids[s] = take(2 * pl->graph_bytes);
+    pl->off_odist[s] = take(2 * pl->graph_bytes);
+  }
+  pl->ws_bytes = make_layout(&q, true).total;
+  pl->off_ws = take(pl->ws_bytes);
+  pl->total = o;
+  return nullptr;
+}
+
+// Every unordered pair of 0..S-1 exactly once, as rounds of disjoint pairs
+// (circle method): consecutive merges mostly touch different shards.
+std::vector<std::pair<int, int>> pair_schedule(int S) {
+  std::vector<std::pair<int, int>> out;
+  const int m = (S % 2) ? S + 1 : S;  // odd: one bye per round
+  for (int r = 0; r < m - 1; ++r)
+    for (int i = 0; i < m / 2; ++i) {
+      int a = i == 0 ? m - 1 : (r + i) % (m - 1);
+      int b = i == 0 ? r : (r - i + (m - 1)) % (m - 1);
+      if (a >= S || b >= S) continue;
+      out.emplace_back(a < b ? a : b, a < b ? b : a);
+    }
+  return out;
+}
+
+#define GNND_HIP(call, what)                        \
+  do {                                              \
+    hipError_t e_ = (call);                         \
+    if (e_ != hipSuccess) { rc = hip_fail(nullptr, e_, what); goto done; } \
+  } while (0)
+
+int run_sharded(const gnnd_params* prm, const ShardPlan& pl, const void* vectors_host,
+                int32_t build_iters, int32_t merge_iters, int32_t* ids_host, void* dist_host,
+                hipStream_t copy, gnnd_shard_stats* stats) {
+  int rc = GNND_OK;
+  char* arena = (char*)prm->workspace_dev;
+  hipStream_t comp = (hipStream_t)prm->stream;
+  const int k = prm->k;
+  const size_t row_vec = (size_t)prm->d * pl.elem, row_g = (size_t)k * 4;
+  auto base_of = [&](int s) { return (int64_t)s * pl.size; };
+  auto rows_of = [&](int s) { return s == pl.shards - 1 ? pl.last : pl.size; };
+  hipEvent_t ev_up[2] = {nullptr, nullptr}, ev_done[2] = {nullptr, nullptr}, t0 = nullptr,
+             t1 = nullptr, t2 = nullptr;
+  const auto pairs = pair_schedule(pl.shards);
+  const auto wall0 = std::chrono::steady_clock::now();
+  for (int i = 0; i < 2; ++i) {
+    GNND_HIP(hipEventCreateWithFlags(&ev_up[i], hipEventDisableTiming), "hipEventCreate");
+    GNND_HIP(hipEventCreateWithFlags(&ev_done[i], hipEventDisableTiming), "hipEventCreate");
+  }
+  GNND_HIP(hipEventCreate(&t0), "hipEventCreate");
+  GNND_HIP(hipEventCreate(&t1), "hipEventCreate");
+  GNND_HIP(hipEventCreate(&t2), "hipEventCreate");
+  GNND_HIP(hipEventRecord(t0, comp), "hipEventRecord");
+
+  // ---- phase 1: one graph per shard ------------------------------------------
+  {
+    auto upload = [&](int s) {  // vectors of shard s into slot s % 2
+      return hipMemcpyAsync(arena + pl.off_vec[s % 2][0],
+                            (const char*)vectors_host + (size_t)base_of(s) * row_vec,
+                            (size_t)rows_of(s) * row_vec, hipMemcpyHostToDevice, copy);
+    };
+    GNND_HIP(upload(0), "shard upload");
+    GNND_HIP(hipEventRecord(ev_up[0], copy), "hipEventRecord");
+    for (int s = 0; s < pl.shards; ++s) {
+      const int slot = s % 2;
+      if (s + 1 < pl.shards) {  // next shard's vectors travel while this one is built
+        if (s >= 1) GNND_HIP(hipStreamWaitEvent(copy, ev_done[1 - slot], 0), "hipStreamWaitEvent");
+        GNND_HIP(upload(s + 1), "shard upload");
+        GNND_HIP(hipEventRecord(ev_up[1 - slot], copy), "hipEventRecord");
+      }
+      GNND_HIP(hipStreamWaitEvent(comp, ev_up[slot], 0), "hipStreamWaitEvent");
+      gnnd_params q = *prm;
+      q.n = rows_of(s);
+      q.seed = prm->seed + (uint64_t)s;
+      q.workspace_dev = arena + pl.off_ws;
+      q.workspace_bytes = pl.ws_bytes;
+      gnnd_ctx* c = nullptr;
+      rc = create_impl(&c, &q, arena + pl.off_vec[slot][0], nullptr, q.n, false);
+      if (rc != GNND_OK) goto done;
+      rc = gnnd_build(c, build_iters, 0.f, nullptr);
+      if (rc == GNND_OK) {
+        hipError_t e = launch_get_graph(c->sh, c->ds, (int32_t*)(arena + pl.off_oids[slot]),
+                                        arena + pl.off_odist[slot], nullptr,
+                                        (int32_t)base_of(s), comp);
+        if (e != hipSuccess) rc = hip_fail(nullptr, e, "get_graph kernel");
+      } else {
+        g_last_error = c->err;
+      }
+      gnnd_destroy(c);
+      if (rc != GNND_OK) goto done;
+      GNND_HIP(hipEventRecord(ev_done[slot], comp), "hipEventRecord");
+      GNND_HIP(hipStreamWaitEvent(copy, ev_done[slot], 0), "hipStreamWaitEvent");
+      GNND_HIP(hipMemcpyAsync((char*)ids_host + (size_t)base_of(s) * row_g,
+                              arena + pl.off_oids[slot], (size_t)rows_of(s) * row_g,
+                              hipMemcpyDeviceToHost, copy), "graph download");
+      GNND_HIP(hipMemcpyAsync((char*)dist_host + (size_t)base_of(s) * row_g,
+                              arena + pl.off_odist[slot], (size_t)rows_of(s) * row_g,
+                              hipMemcpyDeviceToHost, copy), "graph download");
+    }
+  }
+  GNND_HIP(hipEventRecord(t1, comp), "hipEventRecord");
+
+  // ---- phase 2: every pair of shards merged once -------------------------------
+  {
+    // what of merge m can travel before merge m-1 has delivered: the vectors, and the
+    // graph of a shard that merge m-1 does not touch
+    auto up_vec = [&](int m) {
+      const int slot = m % 2;
+      const int sh[2] = {pairs[m].first, pairs[m].second};
+      for (int h = 0; h < 2; ++h) {
+        hipError_t e = hipMemcpyAsync(arena + pl.off_vec[slot][h],
+                                      (const char*)vectors_host + (size_t)base_of(sh[h]) * row_vec,
+                                      (size_t)rows_of(sh[h]) * row_vec, hipMemcpyHostToDevice, copy);
+        if (e != hipSuccess) return e;
+      }
+      return hipSuccess;
+    };
+    auto up_graph = [&](int m, int h) {
+      const int slot = m % 2;
+      const int s = h ? pairs[m].second : pairs[m].first;
+      hipError_t e = hipMemcpyAsync(arena + pl.off_ids[slot][h],
+                                    (const char*)ids_host + (size_t)base_of(s) * row_g,
+                                    (size_t)rows_of(s) * row_g, hipMemcpyHostToDevice, copy);
+      if (e != hipSuccess) return e;
+      return hipMemcpyAsync(arena + pl.off_dist[slot][h],
+                            (const char*)dist_host + (size_t)base_of(s) * row_g,
+                            (size_t)rows_of(s) * row_g, hipMemcpyHostToDevice, copy);
+    };
+    auto touches = [&](int m, int s) { return pairs[m].first == s || pairs[m].second == s; };
+    const int M = (int)pairs.size();
+    // merge 0: everything is on the host already (the downloads above are earlier in `copy`)
+    GNND_HIP(up_vec(0), "merge upload");
+    GNND_HIP(up_graph(0, 0), "merge upload");
+    GNND_HIP(up_graph(0, 1), "merge upload");
+    GNND_HIP(hipEventRecord(ev_up[0], copy), "hipEventRecord");
+    for (int m = 0; m < M; ++m) {
+      const int slot = m % 2;
+      const int sa = pairs[m].first, sb = pairs[m].second;
+      bool late[2] = {false, false};
+      if (m + 1 < M) {
+        // slot 1-slot was last read by merge m-1 and its results were fetched after
+        // ev_done[1-slot]; both are earlier in `copy` than what follows
+        GNND_HIP(up_vec(m + 1), "merge upload");
+        for (int h = 0; h < 2; ++h) {
+          const int s = h ? pairs[m + 1].second : pairs[m + 1].first;
+          late[h] = touches(m, s);
+          if (!late[h]) GNND_HIP(up_graph(m + 1, h), "merge upload");
+        }
+      }
+      GNND_HIP(hipStreamWaitEvent(comp, ev_up[slot], 0), "hipStreamWaitEvent");
+      gnnd_params q = *prm;
+      q.n = rows_of(sa) + rows_of(sb);
+      q.seed = prm->seed + 1000 + (uint64_t)m;
+      q.workspace_dev = arena + pl.off_ws;
+      q.workspace_bytes = pl.ws_bytes;
+      rc = merge_impl(&q, arena + pl.off_vec[slot][0], rows_of(sa), base_of(sa),
+                      arena + pl.off_vec[slot][1], rows_of(sb), base_of(sb), prm->n,
+                      (const int32_t*)(arena + pl.off_ids[slot][0]), arena + pl.off_dist[slot][0],
+                      (const int32_t*)(arena + pl.off_ids[slot][1]), arena + pl.off_dist[slot][1],
+                      merge_iters, (int32_t*)(arena + pl.off_oids[slot]),
+                      arena + pl.off_odist[slot], nullptr);
+      if (rc != GNND_OK) goto done;
+      GNND_HIP(hipEventRecord(ev_done[slot], comp), "hipEventRecord");
+      GNND_HIP(hipStreamWaitEvent(copy, ev_done[slot], 0), "hipStreamWaitEvent");
+      // results: rows of shard sa, then rows of shard sb
+      const size_t na = (size_t)rows_of(sa), nb = (size_t)rows_of(sb);
+      GNND_HIP(hipMemcpyAsync((char*)ids_host + (size_t)base_of(sa) * row_g,
+                              arena + pl.off_oids[slot], na * row_g, hipMemcpyDeviceToHost, copy),
+               "merge download");
+      GNND_HIP(hipMemcpyAsync((char*)ids_host + (size_t)base_of(sb) * row_g,
+                              arena + pl.off_oids[slot] + na * row_g, nb * row_g,
+                              hipMemcpyDeviceToHost, copy), "merge download");
+      GNND_HIP(hipMemcpyAsync((char*)dist_host + (size_t)base_of(sa) * row_g,
+                              arena + pl.off_odist[slot], na * row_g, hipMemcpyDeviceToHost, copy),
+               "merge download");
+      GNND_HIP(hipMemcpyAsync((char*)dist_host + (size_t)base_of(sb) * row_g,
+                              arena + pl.off_odist[slot] + na * row_g, nb * row_g,
+                              hipMemcpyDeviceToHost, copy), "merge download");
+      if (m + 1 < M) {
+        for (int h = 0; h < 2; ++h)
+          if (late[h]) GNND_HIP(up_graph(m + 1, h), "merge upload");
+        GNND_HIP(hipEventRecord(ev_up[1 - slot], copy), "hipEventRecord");
+      }
+    }
+  }
+  GNND_HIP(hipEventRecord(t2, comp), "hipEventRecord");
+  GNND_HIP(hipStreamSynchronize(copy), "hipStreamSynchronize");
+  GNND_HIP(hipStreamSynchronize(comp), "hipStreamSynchronize");
+  if (stats) {
+    memset(stats, 0, sizeof *stats);
+    stats->builds = pl.shards;
+    stats->merges = (int32_t)pairs.size();
+    (void)hipEventElapsedTime(&stats->ms_build, t0, t1);
+    (void)hipEventElapsedTime(&stats->ms_merge, t1, t2);
+    stats->ms_total = std::chrono::duration<float, std::milli>(
+                          std::chrono::steady_clock::now() - wall0).count();
+  }
+done:
+  for (int i = 0; i < 2; ++i) {
+    if (ev_up[i]) (void)hipEventDestroy(ev_up[i]);
+    if (ev_done[i]) (void)hipEventDestroy(ev_done[i]);
+  }
+  if (t0) (void)hipEventDestroy(t0);
+  if (t1) (void)hipEventDestroy(t1);
+  if (t2) (void)hipEventDestroy(t2);
+  return rc;
+}
+#undef GNND_HIP
+
 }  // namespace
 
 extern "C" {
@@ -434,7 +723,7 @@ int gnnd_build(gnnd_ctx* c, int32_t max_iters, float delta, gnnd_iter_stats* las
 int gnnd_get_graph(gnnd_ctx* c, int32_t* ids, void* dist, uint8_t* isnew) {
   if (!c) return fail(nullptr, GNND_EINVAL, "ctx is NULL");
   if (!c->has_graph) return fail(c, GNND_ESTATE, "no graph yet");
-  hipError_t e = launch_get_graph(c->sh, c->ds, ids, dist, isnew, c->stream);
+  hipError_t e = launch_get_graph(c->sh, c->ds, ids, dist, isnew, 0, c->stream);
   return e == hipSuccess ? GNND_OK : hip_fail(c, e, "get_graph kernel");
 }
 
@@ -474,36 +763,35 @@ int gnnd_get_proposals(gnnd_ctx* c, int32_t* u, int32_t* v, void* dist) {
   return e == hipSuccess ? GNND_OK : hip_fail(c, e, "get_proposals kernel");
 }
 
-int gnnd_merge(const gnnd_params* prm, const void* vec1, int64_t n1, const void* vec2, int64_t n2,
+int gnnd_merge(const gnnd_params* prm, const void* vec1, int64_t n1, int64_t base1,
+               const void* vec2, int64_t n2, int64_t base2, int64_t id_space,
                const int32_t* ids1, const void* dist1, const int32_t* ids2, const void* dist2,
                int32_t iters, int32_t* ids_out, void* dist_out, gnnd_iter_stats* stats) {
-  if (const char* m = check_params(prm)) return fail(nullptr, GNND_EINVAL, m);
-  if (n1 <= 0 || n2 <= 0 || n1 + n2 != prm->n)
-    return fail(nullptr, GNND_EINVAL, "n1 + n2 must equal params.n, both positive");
-  if (n1 <= prm->k || n2 <= prm->k)
-    return fail(nullptr, GNND_EINVAL, "each input graph needs more than k nodes");
-  if (iters < 0) return fail(nullptr, GNND_EINVAL, "iters must be >= 0");
-  if (!vec2 || !ids1 || !dist1 || !ids2 || !dist2 || !ids_out || !dist_out)
+  return merge_impl(prm, vec1, n1, base1, vec2, n2, base2, id_space, ids1, dist1, ids2, dist2,
+                    iters, ids_out, dist_out, stats);
+}
+
+size_t gnnd_sharded_arena_bytes(const gnnd_params* prm, int32_t shards) {
+  ShardPlan pl;
+  if (plan_shards(prm, shards, &pl)) return 0;
+  return pl.total;
+}
+
+int gnnd_build_sharded(const gnnd_params* prm, const void* vectors_host, int32_t shards,
+                       int32_t build_iters, int32_t merge_iters, int32_t* ids_host,
+                       void* dist_host, void* copy_stream, gnnd_shard_stats* stats) {
+  ShardPlan pl;
+  if (const char* m = plan_shards(prm, shards, &pl)) return fail(nullptr, GNND_EINVAL, m);
+  if (!vectors_host || !ids_host || !dist_host)
     return fail(nullptr, GNND_EINVAL, "NULL pointer argument");
-  gnnd_ctx* c = nullptr;
-  int rc = create_impl(&c, prm, vec1, vec2, n1, true);
-  if (rc != GNND_OK) return rc;
-  hipError_t e = launch_merge_init(c->sh, c->ds, prm->seed, n1, ids1, dist1, ids2, dist2, c->stream);
-  if (e != hipSuccess) {
-    rc = hip_fail(nullptr, e, "merge init kernel");
-  } else {
-    c->has_graph = true;
-    for (int32_t t = 0; t < iters && rc == GNND_OK; ++t)
-      rc = iterate_impl(c, stats ? stats + t : nullptr);
-    if (rc == GNND_OK) {
-      e = launch_merge_final(c->sh, c->ds, ids_out, dist_out, c->stream);
-      if (e != hipSuccess) rc = hip_fail(nullptr, e, "merge final kernel");
-    } else {
-      g_last_error = c->err;
-    }
-  }
-  gnnd_destroy(c);
-  return rc;
+  if (build_iters < 0 || merge_iters < 0) return fail(nullptr, GNND_EINVAL, "negative iteration count");
+  if (!prm->workspace_dev || ((uintptr_t)prm->workspace_dev & 255))
+    return fail(nullptr, GNND_EINVAL, "arena must be a 256-byte aligned device pointer");
+  if (prm->workspace_bytes < pl.total) return fail(nullptr, GNND_ENOSPC, "arena too small");
+  if (!copy_stream || copy_stream == prm->stream)
+    return fail(nullptr, GNND_EINVAL, "copy_stream must be a stream of its own");
+  return run_sharded(prm, pl, vectors_host, build_iters, merge_iters, ids_host, dist_host,
+                     (hipStream_t)copy_stream, stats);
 }
 
 int gnnd_exact_knn(const void* vec, int64_t n, int32_t d, int32_t metric, const int32_t* queries,

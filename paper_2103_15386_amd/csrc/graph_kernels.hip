@@ -58,8 +58,9 @@ __global__ __launch_bounds__(kBlock) void k_sample_fwd(int64_t n, int k, int p, 
   const int64_t s = wave_global_index();
   if (s >= n) return;
   const int lane = lane_id();
-  const bool valid = lane < k;
-  uint64_t e = valid ? G[s * k + lane] : 0ull;
+  uint64_t e = lane < k ? G[s * k + lane] : 0ull;
+  // entries numbered beyond n are frozen leftovers of an earlier merge: not sampled
+  const bool valid = lane < k && (int64_t)entry_id(e) < n;
   const bool isnew = valid && (e & 1ull);
   const bool isold = valid && !(e & 1ull);
   const uint64_t mn = __ballot(isnew), mo = __ballot(isold);
@@ -238,12 +239,12 @@ __global__ __launch_bounds__(kBlock) void k_update(int64_t n, int k, uint64_t* G
 // ---------------------------------------------------------------------------
 template <bool FLOAT>
 __global__ __launch_bounds__(kBlock) void k_get_graph(int64_t total, const uint64_t* G,
-                                                      int32_t* ids, void* dist,
-                                                      uint8_t* isnew) {
+                                                      int32_t* ids, void* dist, uint8_t* isnew,
+                                                      int32_t id_offset) {
   const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i >= total) return;
   const uint64_t e = G[i];
-  if (ids) ids[i] = (int32_t)entry_id(e);
+  if (ids) ids[i] = (int32_t)entry_id(e) + id_offset;
   if (isnew) isnew[i] = (uint8_t)(e & 1ull);
   if (dist) {
     if (FLOAT) reinterpret_cast<float*>(dist)[i] = unord_f32(entry_code(e));
@@ -300,7 +301,7 @@ __global__ __launch_bounds__(kBlock) void k_zero_u32(uint32_t* p, size_t count) 
 // the rest aside, refill with floor(k/2) random objects of the other set (NEW)
 // and restore the (distance, id) order.
 template <int METRIC>
-__global__ __launch_bounds__(kBlock) void k_merge_init(VecSrc vs, int64_t n, int64_t n1, int k,
+__global__ __launch_bounds__(kBlock) void k_merge_init(VecSrc vs, int64_t n, MergeIds mi, int k,
                                                        uint64_t base_hash, const int32_t* ids1,
                                                        const void* dist1, const int32_t* ids2,
                                                        const void* dist2, uint64_t* G,
@@ -310,15 +311,15 @@ __global__ __launch_bounds__(kBlock) void k_merge_init(VecSrc vs, int64_t n, int
   const int64_t s = wave_global_index();
   if (s >= n) return;
   const int lane = lane_id();
+  const int64_t n1 = mi.n1;
   const bool first = s < n1;
   const int64_t loc = first ? s : s - n1;
   const int32_t* sid = (first ? ids1 : ids2) + loc * k;
   const void* sdist = first ? dist1 : dist2;
-  const uint32_t shift = first ? 0u : (uint32_t)n1;
   const int keep = (k + 1) / 2, fill = k / 2;
   uint32_t id_in = 0, code_in = 0;
   if (lane < k) {
-    id_in = (uint32_t)sid[lane] + shift;
+    id_in = mi.to_internal(sid[lane]);  // collection id -> numbering of this merge
     code_in = METRIC == kL2U8
                   ? ord_i32(reinterpret_cast<const int32_t*>(sdist)[loc * k + lane])
                   : ord_f32(reinterpret_cast<const float*>(sdist)[loc * k + lane]);
@@ -341,11 +342,12 @@ __global__ __launch_bounds__(kBlock) void k_merge_init(VecSrc vs, int64_t n, int
   if (lane == k - 1) meta[s].kth = entry_code(e);
 }
 
-// GGM, Alg. 3 "Merge and Sort": best k of the refined list and the set-aside half.
+// GGM, Alg. 3 "Merge and Sort": best k of the refined list and the set-aside
+// half, handed out under collection ids, ascending by (distance, collection id).
 template <bool FLOAT>
-__global__ __launch_bounds__(kBlock) void k_merge_final(int64_t n, int k, const uint64_t* G,
-                                                        const uint64_t* aside, int32_t* ids_out,
-                                                        void* dist_out) {
+__global__ __launch_bounds__(kBlock) void k_merge_final(int64_t n, MergeIds mi, int k,
+                                                        const uint64_t* G, const uint64_t* aside,
+                                                        int32_t* ids_out, void* dist_out) {
   const int64_t s = wave_global_index();
   if (s >= n) return;
   const int lane = lane_id();
@@ -359,6 +361,10 @@ __global__ __launch_bounds__(kBlock) void k_merge_final(int64_t n, int k, const 
   if (any) {
     row = wave_merge_smallest(row, pk, lane);
   }
+  // renumber, then restore the order under the new ids (only ties can move)
+  row = lane < k ? make_entry(entry_code(row), (uint32_t)mi.to_global(entry_id(row)), 0u)
+                 : kKeyMax;
+  row = wave_sort(row, lane);
   if (lane < k) {
     ids_out[s * k + lane] = (int32_t)entry_id(row);
     if (FLOAT) reinterpret_cast<float*>(dist_out)[s * k + lane] = unord_f32(entry_code(row));
@@ -553,11 +559,13 @@ hipError_t launch_update(const Shape& sh, const DevState& ds, hipStream_t st) {
 }
 
 hipError_t launch_get_graph(const Shape& sh, const DevState& ds, int32_t* ids, void* dist,
-                            uint8_t* isnew, hipStream_t st) {
+                            uint8_t* isnew, int32_t id_offset, hipStream_t st) {
   const int64_t total = sh.n * sh.k;
   const unsigned grid = (unsigned)((total + kBlock - 1) / kBlock);
-  if (sh.metric == kL2U8) k_get_graph<false><<<grid, kBlock, 0, st>>>(total, ds.G, ids, dist, isnew);
-  else k_get_graph<true><<<grid, kBlock, 0, st>>>(total, ds.G, ids, dist, isnew);
+  if (sh.metric == kL2U8)
+    k_get_graph<false><<<grid, kBlock, 0, st>>>(total, ds.G, ids, dist, isnew, id_offset);
+  else
+    k_get_graph<true><<<grid, kBlock, 0, st>>>(total, ds.G, ids, dist, isnew, id_offset);
   return hipGetLastError();
 }
 
@@ -586,35 +594,37 @@ hipError_t launch_get_proposals(const Shape& sh, const DevState& ds, int32_t* u,
   return hipGetLastError();
 }
 
-hipError_t launch_merge_init(const Shape& sh, const DevState& ds, uint64_t seed, int64_t n1,
-                             const int32_t* ids1, const void* dist1, const int32_t* ids2,
-                             const void* dist2, hipStream_t st) {
+hipError_t launch_merge_init(const Shape& sh, const DevState& ds, uint64_t seed,
+                             const MergeIds& mi, const int32_t* ids1, const void* dist1,
+                             const int32_t* ids2, const void* dist2, hipStream_t st) {
   const unsigned grid = blocks_for_waves(sh.n);
   const uint64_t base = hash_base(seed, kTagMerge);
   switch (sh.metric) {
     case kL2F32:
-      k_merge_init<kL2F32><<<grid, kBlock, 0, st>>>(vec_src(sh), sh.n, n1, sh.k, base, ids1, dist1,
+      k_merge_init<kL2F32><<<grid, kBlock, 0, st>>>(vec_src(sh), sh.n, mi, sh.k, base, ids1, dist1,
                                                     ids2, dist2, ds.G, ds.meta, ds.aside);
       break;
     case kAngularF32:
-      k_merge_init<kAngularF32><<<grid, kBlock, 0, st>>>(vec_src(sh), sh.n, n1, sh.k, base, ids1,
+      k_merge_init<kAngularF32><<<grid, kBlock, 0, st>>>(vec_src(sh), sh.n, mi, sh.k, base, ids1,
                                                          dist1, ids2, dist2, ds.G, ds.meta,
                                                          ds.aside);
       break;
     default:
-      k_merge_init<kL2U8><<<grid, kBlock, 0, st>>>(vec_src(sh), sh.n, n1, sh.k, base, ids1, dist1,
+      k_merge_init<kL2U8><<<grid, kBlock, 0, st>>>(vec_src(sh), sh.n, mi, sh.k, base, ids1, dist1,
                                                    ids2, dist2, ds.G, ds.meta, ds.aside);
   }
   return hipGetLastError();
 }
 
-hipError_t launch_merge_final(const Shape& sh, const DevState& ds, int32_t* ids_out,
-                              void* dist_out, hipStream_t st) {
+hipError_t launch_merge_final(const Shape& sh, const DevState& ds, const MergeIds& mi,
+                              int32_t* ids_out, void* dist_out, hipStream_t st) {
   const unsigned grid = blocks_for_waves(sh.n);
   if (sh.metric == kL2U8)
-    k_merge_final<false><<<grid, kBlock, 0, st>>>(sh.n, sh.k, ds.G, ds.aside, ids_out, dist_out);
+    k_merge_final<false><<<grid, kBlock, 0, st>>>(sh.n, mi, sh.k, ds.G, ds.aside, ids_out,
+                                                  dist_out);
   else
-    k_merge_final<true><<<grid, kBlock, 0, st>>>(sh.n, sh.k, ds.G, ds.aside, ids_out, dist_out);
+    k_merge_final<true><<<grid, kBlock, 0, st>>>(sh.n, mi, sh.k, ds.G, ds.aside, ids_out,
+                                                 dist_out);
   return hipGetLastError();
 }
 

@@ -66,16 +66,17 @@ hipError_t launch_join_mfma(const Shape& sh, const DevState& ds, bool merge_mode
 hipError_t launch_pack_i8(const Shape& sh, const DevState& ds, int* bad_flag_dev, hipStream_t st);
 hipError_t launch_update(const Shape& sh, const DevState& ds, hipStream_t st);
 hipError_t launch_get_graph(const Shape& sh, const DevState& ds, int32_t* ids, void* dist,
-                            uint8_t* isnew, hipStream_t st);
+                            uint8_t* isnew, int32_t id_offset, hipStream_t st);
 hipError_t launch_set_graph(const Shape& sh, const DevState& ds, const int32_t* ids,
                             const void* dist, const uint8_t* isnew, hipStream_t st);
 hipError_t launch_get_proposals(const Shape& sh, const DevState& ds, int32_t* u, int32_t* v,
                                 void* dist, hipStream_t st);
-hipError_t launch_merge_init(const Shape& sh, const DevState& ds, uint64_t seed, int64_t n1,
-                             const int32_t* ids1, const void* dist1, const int32_t* ids2,
-                             const void* dist2, hipStream_t st);
-hipError_t launch_merge_final(const Shape& sh, const DevState& ds, int32_t* ids_out,
-                              void* dist_out, hipStream_t st);
+struct MergeIds;
+hipError_t launch_merge_init(const Shape& sh, const DevState& ds, uint64_t seed,
+                             const MergeIds& mi, const int32_t* ids1, const void* dist1,
+                             const int32_t* ids2, const void* dist2, hipStream_t st);
+hipError_t launch_merge_final(const Shape& sh, const DevState& ds, const MergeIds& mi,
+                              int32_t* ids_out, void* dist_out, hipStream_t st);
 hipError_t launch_exact_knn(const void* vec, int64_t n, int32_t d, int32_t metric,
                             const int32_t* queries, int64_t nq, int32_t K, int32_t* ids_out,
                             void* dist_out, hipStream_t st);

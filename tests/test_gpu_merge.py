@@ -32,6 +32,7 @@ def test_merge_matches_oracle(metric, gen, k, p, n1, iters, path):
     x = gen(n)
     g1 = _exact(x[:n1], metric, k)
     g2 = _exact(x[n1:], metric, k)
+    g2.ids += n1  # lists carry the ids of the union
     want, wstats = og.merge(x, n1, k, p, metric, SEED, g1, g2, iters)
     dt = np.int32 if metric == og.L2SQ_U8 else np.float32
     out = amd.gnnd_merge(_dev(x[:n1]), _dev(x[n1:]), _dev(g1.ids), _dev(g1.dist.astype(dt)),
@@ -54,3 +55,55 @@ def test_merge_rejects_bad_arguments():
     dist = torch.zeros((20, 10), dtype=torch.float32, device="cuda")
     with pytest.raises(amd.GnndError):  # 20 nodes per side cannot hold k = 32 lists
         amd.gnnd_merge(x[:20].contiguous(), x[20:].contiguous(), ids, dist, ids, dist, 32, 8)
+
+
+def test_merge_with_frozen_third_shard_entries_matches_oracle():
+    # shards A, B, C of one collection: merge (A, B), then (A, C) where A's lists
+    # already point into B - those entries are frozen during the second merge.
+    import paper_2103_15386_amd as amd
+    k, p, m, metric = 16, 16, 700, og.L2SQ_U8
+    x = W.sift_like_u8(3 * m, 64, seed=301, n_comp=6)
+    A, B, Cc = slice(0, m), slice(m, 2 * m), slice(2 * m, 3 * m)
+    gA, gB, gC = _exact(x[A], metric, k), _exact(x[B], metric, k), _exact(x[Cc], metric, k)
+    gB.ids += m
+    gC.ids += 2 * m
+    xAB = np.concatenate([x[A], x[B]])
+    wAB, _ = og.merge(xAB, m, k, p, metric, SEED, gA, gB, 3, 0, m)
+    ids, dist = amd.gnnd_merge(_dev(x[A]), _dev(x[B]), _dev(gA.ids), _dev(gA.dist.astype(np.int32)),
+                               _dev(gB.ids), _dev(gB.dist.astype(np.int32)), k, p, metric, SEED, 3,
+                               base1=0, base2=m, id_space=3 * m)
+    assert (ids.cpu().numpy() == wAB.ids).all() and (dist.cpu().numpy() == wAB.dist).all()
+    gA2 = og.Graph(wAB.ids[:m].copy(), wAB.dist[:m].copy(), None)
+    assert (gA2.ids >= m).any()
+    # second merge with the ranges in "wrong" order: S1 = C, S2 = A
+    xCA = np.concatenate([x[Cc], x[A]])
+    wCA, wst = og.merge(xCA, m, k, p, metric, SEED + 1, gC, gA2, 3, 2 * m, 0)
+    ids, dist, st = amd.gnnd_merge(_dev(x[Cc]), _dev(x[A]), _dev(gC.ids),
+                                   _dev(gC.dist.astype(np.int32)), _dev(gA2.ids),
+                                   _dev(gA2.dist.astype(np.int32)), k, p, metric, SEED + 1, 3,
+                                   want_stats=True, base1=2 * m, base2=0, id_space=3 * m)
+    assert (ids.cpu().numpy() == wCA.ids).all() and (dist.cpu().numpy() == wCA.dist).all()
+    for a, b in zip(st, wst):
+        assert a["inserts"] == b["inserts"] and a["dist_evals"] == b["dist_evals"]
+    assert (wCA.ids[m:] >= m).any() and ((wCA.ids[m:] >= m) & (wCA.ids[m:] < 2 * m)).any()
+
+
+@pytest.mark.parametrize("metric,gen,shards,n", [
+    (og.L2SQ_U8, lambda n: W.sift_like_u8(n, 128, seed=302, n_comp=8), 4, 4000),
+    (og.L2SQ_F32, lambda n: W.uniform_f32(n, 10, seed=303), 3, 2001),
+])
+def test_sharded_build_matches_oracle(metric, gen, shards, n):
+    import paper_2103_15386_amd as amd
+    k, p = 12, 12
+    x = gen(n)
+    want = og.build_sharded(x, shards, k, p, metric, SEED, 5, 3)
+    xh = torch.from_numpy(x).pin_memory()
+    ids, dist, st = amd.gnnd_build_sharded(xh, shards, k, p, metric, SEED, 5, 3)
+    assert (ids.numpy() == want.ids).all()
+    assert (dist.numpy().astype(np.float64) == want.dist).all()
+    assert st["builds"] == shards and st["merges"] == shards * (shards - 1) // 2
+    # quality: the sharded graph is close to the exact one
+    q = W.sample_nodes(n, 300, seed=5)
+    ti, td = og.bruteforce(x, metric, q, 10)
+    rec, _ = og.recall_at(want.ids[q], want.dist[q], ti, td, 10)
+    assert rec > 0.85, rec
