@@ -41,6 +41,10 @@ def parse():
     ap.add_argument("--join", choices=["auto", "valu", "mfma"], default="auto")
     ap.add_argument("--cpu-sample-n", type=int, default=40_000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--workload", choices=["sift1m", "sharded"], default="sift1m")
+    ap.add_argument("--shards", type=int, default=4)
+    ap.add_argument("--build-iters", type=int, default=8)
+    ap.add_argument("--merge-iters", type=int, default=4)
     ap.add_argument("--copy-calib-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (a dispatch of known "
                          "size to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters with)")
@@ -69,6 +73,44 @@ def cpu_baseline(args, iters):
                       f"{iters} iterations, init + all stages"}
 
 
+def sharded(args, torch, amd, W, dev):
+    """The merge workload: uint8 vectors, d = 128, SIFT-shaped 64-component
+    mixture; graphs of `--shards` equal shards are built one at a time and merged
+    pairwise with GGM, the collection staying in pinned host memory (only two
+    shards resident).  Not the headline metric: an extra line for that path."""
+    n, d, k, p = args.n, args.d, args.k, args.p
+    g = torch.Generator(device=dev).manual_seed(1005)
+    centres = torch.rand((64, d), generator=g, device=dev) * 128.0
+    xh = torch.empty((n, d), dtype=torch.uint8, pin_memory=True)
+    xd = torch.empty((n, d), dtype=torch.uint8, device=dev)  # for the ground truth only
+    step = 1 << 21
+    for lo in range(0, n, step):
+        hi = min(n, lo + step)
+        comp = torch.randint(0, 64, (hi - lo,), generator=g, device=dev)
+        v = centres[comp] + 20.0 * torch.randn((hi - lo, d), generator=g, device=dev)
+        xd[lo:hi] = v.clamp_(0.0, 255.0).round_().to(torch.uint8)
+        xh[lo:hi].copy_(xd[lo:hi])
+    torch.cuda.synchronize()
+    q = torch.from_numpy(W.sample_nodes(n, args.eval_nodes)).to(dev)
+    _, tdist = amd.exact_knn(xd, q, 10, amd.L2SQ_U8)
+    del xd
+    torch.cuda.empty_cache()
+    t0 = time.perf_counter()
+    ids, dist, st = amd.gnnd_build_sharded(xh, args.shards, k, p, amd.L2SQ_U8, W.ALGO_SEED,
+                                           args.build_iters, args.merge_iters)
+    wall = time.perf_counter() - t0
+    rec = amd.recall_at(dist[q.cpu().long()].to(dev), tdist, 10)
+    out = {"metric": "sharded_build_seconds", "value": st["ms_total"] / 1e3, "unit": "s",
+           "n_gpus": 1, "steps": 1, "warmup": 0, "ms_per_step": st["ms_total"],
+           "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "i8",
+           "data": "synthetic",
+           "config": {"workload": f"uint8 sift-shaped GMM n={n} d={d}, {args.shards} shards in "
+                                  f"pinned host memory, k={k} p={p}, {args.build_iters} build + "
+                                  f"{args.merge_iters} merge iterations, all pairs merged once"},
+           "recall_at_10": rec, "stats": st, "wall_s_including_arena_alloc": wall}
+    print(json.dumps(out))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -82,6 +124,8 @@ def main():
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.workload == "sharded":
+        return sharded(args, torch, amd, W, dev)
     x = W.sift_like_f32(args.n, args.d, seed=1002)
     xd = torch.from_numpy(x).to(dev)
     del x

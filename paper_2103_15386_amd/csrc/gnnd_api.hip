@@ -24,7 +24,7 @@ thread_local std::string g_last_error = "";
 struct Layout {
   size_t off_G, off_kth, off_snew, off_sold, off_cnew, off_cold, off_rcn, off_rco, off_ron,
       off_roo, off_csn, off_cso, off_capn, off_capo, off_pcnt, off_poff, off_bins, off_scan,
-      off_cnt, off_snap, off_aside, off_shadow, off_norms, off_flag, total;
+      off_cnt, off_snap, off_aside, off_shadow, off_norms, off_flag, off_bkc, off_bko, total;
 };
 
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -85,6 +85,8 @@ Layout make_layout(const gnnd_params* q, bool with_aside) {
   L.off_shadow = take(shadow ? n * (size_t)((q->d + 31) & ~31) : 0);
   L.off_norms = 0;
   L.off_flag = take(256);
+  L.off_bkc = take(2 * 4096 * 4);
+  L.off_bko = take(2 * 4097 * 8);
   L.total = o;
   return L;
 }
@@ -152,6 +154,8 @@ void bind(gnnd_ctx* c, const Layout& L) {
   c->snap = (uint64_t*)(w + L.off_snap);
   d.shadow = (int8_t*)(w + L.off_shadow);
   c->flag_dev = (int*)(w + L.off_flag);
+  d.bk_cnt = (uint32_t*)(w + L.off_bkc);
+  d.bk_off = (uint64_t*)(w + L.off_bko);
 }
 
 // Shared by gnnd_create and gnnd_merge.
@@ -191,6 +195,7 @@ int create_impl(gnnd_ctx** out, const gnnd_params* prm, const void* vec_a, const
   hipError_t e = launch_zero_u32(c->ds.rcnt_new, (size_t)prm->n, c->stream);
   if (e == hipSuccess) e = launch_zero_u32(c->ds.rcnt_old, (size_t)prm->n, c->stream);
   if (e == hipSuccess) e = launch_zero_u32(c->ds.pcnt, (size_t)prm->n, c->stream);
+  if (e == hipSuccess) e = launch_zero_u32(c->ds.bk_cnt, 2 * 4096, c->stream);
   if (e == hipSuccess)
     e = launch_zero_u32((uint32_t*)c->ds.counters, (size_t)kStripes * C_SLOTS * 2, c->stream);
   if (e != hipSuccess) {

@@ -535,15 +535,22 @@ hipError_t launch_init_random(const Shape& sh, const DevState& ds, uint64_t seed
 hipError_t launch_sample(const Shape& sh, const DevState& ds, uint64_t seed, uint32_t iter,
                          hipStream_t st) {
   const unsigned grid = blocks_for_waves(sh.n);
-  k_sample_fwd<<<grid, kBlock, 0, st>>>(sh.n, sh.k, sh.p, ds.G, ds.snew, ds.sold, ds.cnew,
-                                        ds.cold, ds.rcnt_new, ds.rcnt_old);
-  hipError_t e = launch_scan(ds.rcnt_new, nullptr, ds.roff_new, ds.scan_tmp, sh.n, st);
-  if (e != hipSuccess) return e;
-  e = launch_scan(ds.rcnt_old, nullptr, ds.roff_old, ds.scan_tmp, sh.n, st);
-  if (e != hipSuccess) return e;
-  k_rev_fill<<<grid, kBlock, 0, st>>>(sh.n, sh.p, ds.snew, ds.sold, ds.cnew, ds.cold,
-                                      ds.rcnt_new, ds.rcnt_old, ds.roff_new, ds.roff_old,
-                                      ds.csr_new, ds.csr_old);
+  if (sample_buckets_possible(sh.n)) {
+    // reverse candidates grouped by a two-level counting sort (few global atomics)
+    hipError_t e = launch_sample_buckets(sh, ds, st);
+    if (e != hipSuccess) return e;
+  } else {
+    // very large n: one global atomic per edge for counting, one for placing
+    k_sample_fwd<<<grid, kBlock, 0, st>>>(sh.n, sh.k, sh.p, ds.G, ds.snew, ds.sold, ds.cnew,
+                                          ds.cold, ds.rcnt_new, ds.rcnt_old);
+    hipError_t e = launch_scan(ds.rcnt_new, nullptr, ds.roff_new, ds.scan_tmp, sh.n, st);
+    if (e != hipSuccess) return e;
+    e = launch_scan(ds.rcnt_old, nullptr, ds.roff_old, ds.scan_tmp, sh.n, st);
+    if (e != hipSuccess) return e;
+    k_rev_fill<<<grid, kBlock, 0, st>>>(sh.n, sh.p, ds.snew, ds.sold, ds.cnew, ds.cold,
+                                        ds.rcnt_new, ds.rcnt_old, ds.roff_new, ds.roff_old,
+                                        ds.csr_new, ds.csr_old);
+  }
   k_rev_select<<<dim3(grid, 2), kBlock, 0, st>>>(
       sh.n, sh.p, hash_base(seed, kTagRevNew), hash_base(seed, kTagRevOld), iter, ds.snew,
       ds.sold, ds.cnew, ds.cold, ds.roff_new, ds.roff_old, ds.csr_new, ds.csr_old, ds.capn,

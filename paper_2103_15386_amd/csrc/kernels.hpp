@@ -46,6 +46,8 @@ struct DevState {
   uint64_t* counters;  // kStripes * C_SLOTS
   uint64_t* aside;     // merge only: n * floor(k/2) set-aside entries
   int8_t* shadow;      // matrix-core path: n rows of dpad int8 (value - 128), zero padded
+  uint32_t* bk_cnt;    // 2 x 4096 bucket counters of the bucketed reverse-candidate sort
+  uint64_t* bk_off;    // 2 x 4097 bucket offsets
 
 };
 
@@ -64,6 +66,8 @@ hipError_t launch_join(const Shape& sh, const DevState& ds, int path, bool merge
                        hipStream_t st);
 hipError_t launch_join_mfma(const Shape& sh, const DevState& ds, bool merge_mode, hipStream_t st);
 hipError_t launch_pack_i8(const Shape& sh, const DevState& ds, int* bad_flag_dev, hipStream_t st);
+bool sample_buckets_possible(int64_t n);
+hipError_t launch_sample_buckets(const Shape& sh, const DevState& ds, hipStream_t st);
 hipError_t launch_update(const Shape& sh, const DevState& ds, hipStream_t st);
 hipError_t launch_get_graph(const Shape& sh, const DevState& ds, int32_t* ids, void* dist,
                             uint8_t* isnew, int32_t id_offset, hipStream_t st);
