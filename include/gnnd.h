@@ -83,6 +83,7 @@ typedef struct gnnd_iter_stats {
   uint64_t sum_old;    /* total size of all OLD sample lists                       */
   uint64_t proposals;  /* nearest-object results found (Alg. 2 outputs)            */
   uint64_t dropped;    /* results lost to a full proposal segment: always 0        */
+  uint64_t passed;     /* results handed to the list update (after the early drop) */
   float ms_sample, ms_join, ms_update;
   float reserved2;
 } gnnd_iter_stats;

@@ -40,7 +40,8 @@ class Params(C.Structure):
 class IterStats(C.Structure):
     _fields_ = [("iter", C.c_int32), ("reserved", C.c_int32), ("inserts", C.c_uint64),
                 ("dist_evals", C.c_uint64), ("sum_new", C.c_uint64), ("sum_old", C.c_uint64),
-                ("proposals", C.c_uint64), ("dropped", C.c_uint64), ("ms_sample", C.c_float), ("ms_join", C.c_float),
+                ("proposals", C.c_uint64), ("dropped", C.c_uint64), ("passed", C.c_uint64),
+                ("ms_sample", C.c_float), ("ms_join", C.c_float),
                 ("ms_update", C.c_float), ("reserved2", C.c_float)]
 
     def as_dict(self):

@@ -259,6 +259,7 @@ int read_stats(gnnd_ctx* c, gnnd_iter_stats* out) {
   out->sum_old = tot[C_SUMOLD];
   out->proposals = tot[C_PROPS];
   out->dropped = tot[C_OVERFLOW];
+  out->passed = tot[C_PASSED];
   return GNND_OK;
 }
 

@@ -128,7 +128,7 @@ __device__ inline v16i gram(const Operand& rows, const Operand& cols) {
 // as the last tile has consumed the operand registers the rows of node i+1 are
 // requested, before the results of node i are handed out.
 template <int KSTEPS, bool FCODE, bool MERGE>
-__global__ __launch_bounds__(kMB) void k_join_mfma(
+__global__ __launch_bounds__(kMB) __attribute__((amdgpu_waves_per_eu(3, 3))) void k_join_mfma(
     const int8_t* __restrict__ shadow, const NodeMeta* __restrict__ meta, int dpad, int64_t n,
     int p, int64_t split, const int32_t* __restrict__ snew, const int32_t* __restrict__ sold,
     uint32_t* pcnt, const uint64_t* __restrict__ poff, uint64_t* __restrict__ bins,
@@ -346,15 +346,23 @@ __global__ __launch_bounds__(kMB) void k_join_mfma(
       pass[0] = pass[1] = pass[2] = false;
     }
     // slot requests for all three results first ...
-    uint32_t slot[3] = {0, 0, 0};
-    uint64_t beg[3] = {0, 0, 0}, end[3] = {0, 0, 0};
-#pragma unroll
-    for (int kind = 0; kind < 3; ++kind)
-      if (pass[kind]) {
-        slot[kind] = atomicAdd(&pcnt[self[kind]], 1u);
-        beg[kind] = poff[self[kind]];
-        end[kind] = poff[self[kind] + 1];
-      }
+    // (the two results of a NEW sample go to the same list: one request for both)
+    uint32_t slot_n = 0, slot_o = 0;
+    uint64_t beg_n = 0, end_n = 0, beg_o = 0, end_o = 0;
+    const uint32_t want_n = (pass[0] ? 1u : 0u) + (pass[1] ? 1u : 0u);
+    if (want_n) {
+      slot_n = atomicAdd(&pcnt[id_new], want_n);
+      beg_n = poff[id_new];
+      end_n = poff[id_new + 1];
+    }
+    if (pass[2]) {
+      slot_o = atomicAdd(&pcnt[id_old], 1u);
+      beg_o = poff[id_old];
+      end_o = poff[id_old + 1];
+    }
+    const uint32_t passed_total =
+        (uint32_t)__popcll(__ballot(pass[0])) + (uint32_t)__popcll(__ballot(pass[1])) +
+        (uint32_t)__popcll(__ballot(pass[2]));
     // ... then, with the operand registers free, the next node's rows ...
     const int64_t s_next = s + W;
     const bool more = s_next < n;
@@ -367,13 +375,21 @@ __global__ __launch_bounds__(kMB) void k_join_mfma(
       }
     }
     // ... and only now the slots are used
+    if (pass[0]) {
+      if (slot_n < end_n - beg_n) bins[beg_n + slot_n] = entry[0];
+      else ++over_total;
+    }
+    if (pass[1]) {
+      const uint32_t at = slot_n + (pass[0] ? 1u : 0u);
+      if (at < end_n - beg_n) bins[beg_n + at] = entry[1];
+      else ++over_total;
+    }
+    if (pass[2]) {
+      if (slot_o < end_o - beg_o) bins[beg_o + slot_o] = entry[2];
+      else ++over_total;
+    }
 #pragma unroll
-    for (int kind = 0; kind < 3; ++kind)
-      if (pass[kind]) {
-        if (slot[kind] < end[kind] - beg[kind]) bins[beg[kind] + slot[kind]] = entry[kind];
-        else ++over_total;
-      }
-    over_total = (uint32_t)__popcll(__ballot(over_total != 0));  // at most one kind overflows per lane in practice; counted per lane
+    for (int off = 32; off > 0; off >>= 1) over_total += __shfl_xor(over_total, off, kWave);
     if (active && lane == 0) {
       uint64_t ev;
       if (MERGE) {
@@ -385,6 +401,8 @@ __global__ __launch_bounds__(kMB) void k_join_mfma(
         ev = (do_nn ? (uint64_t)nn * (nn - 1) / 2 : 0) + (uint64_t)nn * no - dups;
       }
       uint64_t* cs = counters + (s & (kStripes - 1)) * C_SLOTS;
+      if (passed_total) atomicAdd(reinterpret_cast<unsigned long long*>(cs + C_PASSED),
+                                  (unsigned long long)passed_total);
       if (found_total) atomicAdd(reinterpret_cast<unsigned long long*>(cs + C_PROPS),
                                  (unsigned long long)found_total);
       if (over_total) atomicAdd(reinterpret_cast<unsigned long long*>(cs + C_OVERFLOW),

@@ -264,11 +264,15 @@ __global__ __launch_bounds__(kJB) void k_join_valu(
   }
   const uint64_t nover = __popcll(__ballot(overflow));
   const uint64_t nfound = __popcll(__ballot(found));
+  const uint64_t npass = __popcll(__ballot(pass));
   if (wave == 1) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) evaluated += __shfl_xor(evaluated, off, kWave);
   }
   if (lane == 0) {
+    if (npass) atomicAdd(reinterpret_cast<unsigned long long*>(
+                             counters + (s & (kStripes - 1)) * C_SLOTS + C_PASSED),
+                         (unsigned long long)npass);
     if (nover) atomicAdd(reinterpret_cast<unsigned long long*>(
                              counters + (s & (kStripes - 1)) * C_SLOTS + C_OVERFLOW),
                          (unsigned long long)nover);

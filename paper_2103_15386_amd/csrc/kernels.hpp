@@ -10,6 +10,7 @@ namespace gnnd {
 enum : int {
   C_INSERTS = 0, C_EVALS = 1, C_SUMNEW = 2, C_SUMOLD = 3, C_PROPS = 4,
   C_OVERFLOW = 5,  // proposals that found their destination segment full (must stay 0)
+  C_PASSED = 6,    // results that survived the early drop and went to the update
   C_SLOTS = 8
 };
 constexpr int kStripes = 64;  // counters are striped to spread same-address atomics
