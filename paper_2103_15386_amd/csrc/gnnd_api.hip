@@ -680,7 +680,8 @@ int gnnd_get_stage_ms(gnnd_ctx* c, int32_t* count, float* ms_sample, float* ms_j
 int gnnd_init_random(gnnd_ctx* c) {
   if (!c) return fail(nullptr, GNND_EINVAL, "ctx is NULL");
   if (c->merge_mode) return fail(c, GNND_ESTATE, "context belongs to a merge");
-  hipError_t e = launch_init_random(c->sh, c->ds, c->prm.seed, c->stream);
+  hipError_t e = c->use_mfma ? launch_init_random_i8(c->sh, c->ds, c->prm.seed, c->stream)
+                             : launch_init_random(c->sh, c->ds, c->prm.seed, c->stream);
   if (e != hipSuccess) return hip_fail(c, e, "init kernel");
   c->has_graph = true;
   c->iter = 0;

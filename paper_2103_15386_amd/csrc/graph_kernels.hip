@@ -191,9 +191,16 @@ __device__ inline uint64_t filter_candidates(uint64_t pk, uint64_t row, int k, i
   if (pk != kKeyMax && entry_key(pk) >= entry_key(last)) pk = kKeyMax;
   any = __ballot(pk != kKeyMax) != 0ull;
   if (!any) return pk;
-  bool dup = false;
-  for (int i = 0; i < k; ++i) dup |= (entry_key(pk) == entry_key(readlane64(row, i)));
-  if (dup) pk = kKeyMax;
+  // already in the list?  The 64 lanes of `row` ascend (unused lanes hold the
+  // maximum), so each candidate finds its lower bound in six halving steps.
+  const uint64_t kk = entry_key(pk);
+  int pos = 0;
+#pragma unroll
+  for (int step = kWave / 2; step > 0; step >>= 1) {
+    const uint64_t r = __shfl(row, pos + step - 1, kWave);
+    pos += (entry_key(r) < kk) ? step : 0;
+  }
+  if (entry_key(__shfl(row, pos, kWave)) == kk) pk = kKeyMax;
   any = __ballot(pk != kKeyMax) != 0ull;
   if (!any) return pk;
   pk = wave_sort(pk, lane);

@@ -55,6 +55,36 @@ __global__ __launch_bounds__(256) void k_pack_i8(const void* vec_a, const void* 
   if (__ballot(is_bad) != 0ull && lane == 0) atomicOr(bad, 1);
 }
 
+// Alg. 1, first loop, on the int8 rows: k distinct random neighbours per node,
+// exact distances |a|^2 + |b|^2 - 2 a.b (four products per v_dot4), sorted
+// ascending by (distance, id), flagged NEW.  One wavefront per node, one
+// neighbour per lane; a row is dpad <= 128 bytes, i.e. one cache line.
+template <bool FCODE>
+__global__ __launch_bounds__(256) void k_init_random_i8(const int8_t* __restrict__ shadow,
+                                                        NodeMeta* meta, int dpad, int64_t n, int k,
+                                                        uint64_t base_hash, uint64_t* G) {
+  const int lane = lane_id();
+  const int64_t s = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (s >= n) return;
+  const uint32_t id = draw_distinct(base_hash, (uint32_t)s, k, (uint32_t)n, 0u, (uint32_t)s, lane);
+  uint64_t e = kKeyMax;
+  if (lane < k) {
+    const v4i* a = reinterpret_cast<const v4i*>(shadow + s * dpad);
+    const v4i* b = reinterpret_cast<const v4i*>(shadow + (int64_t)id * dpad);
+    int32_t dot = 0;
+    for (int q = 0; q < dpad / 16; ++q) {
+      const v4i x = a[q], y = b[q];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) dot = __builtin_amdgcn_sdot4(x[t], y[t], dot, false);
+    }
+    const int32_t dist = meta[s].norm + meta[id].norm - 2 * dot;
+    e = make_entry(FCODE ? ord_f32((float)dist) : ord_i32(dist), id, 1u);
+  }
+  e = wave_sort(e, lane);
+  if (lane < k) G[s * k + lane] = e;
+  if (lane == k - 1) meta[s].kth = entry_code(e);
+}
+
 // Best row per column of one 32x32 accumulator tile.  For row r the LDS array
 // holds negR = -((norm_r << 6) | position_r); then t = (G << 7) + negR is
 // -(((norm_r - 2 G) << 6) | position_r), so the maximum of t over the rows is
@@ -445,6 +475,18 @@ hipError_t launch_join_mfma(const Shape& sh, const DevState& ds, bool merge_mode
     case 3: launch_k<3>(fcode, merge_mode, grid, st, ds.shadow, ds.meta, dpad, sh, ds); break;
     default: launch_k<4>(fcode, merge_mode, grid, st, ds.shadow, ds.meta, dpad, sh, ds);
   }
+  return hipGetLastError();
+}
+
+hipError_t launch_init_random_i8(const Shape& sh, const DevState& ds, uint64_t seed,
+                                 hipStream_t st) {
+  const int dpad = (sh.d + 31) & ~31;
+  const unsigned grid = (unsigned)((sh.n + 3) / 4);
+  const uint64_t base = hash_base(seed, kTagInit);
+  if (sh.metric != kL2U8)
+    k_init_random_i8<true><<<grid, 256, 0, st>>>(ds.shadow, ds.meta, dpad, sh.n, sh.k, base, ds.G);
+  else
+    k_init_random_i8<false><<<grid, 256, 0, st>>>(ds.shadow, ds.meta, dpad, sh.n, sh.k, base, ds.G);
   return hipGetLastError();
 }
 

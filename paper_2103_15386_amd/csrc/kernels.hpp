@@ -67,6 +67,8 @@ hipError_t launch_join(const Shape& sh, const DevState& ds, int path, bool merge
                        hipStream_t st);
 hipError_t launch_join_mfma(const Shape& sh, const DevState& ds, bool merge_mode, hipStream_t st);
 hipError_t launch_pack_i8(const Shape& sh, const DevState& ds, int* bad_flag_dev, hipStream_t st);
+hipError_t launch_init_random_i8(const Shape& sh, const DevState& ds, uint64_t seed,
+                                 hipStream_t st);
 bool sample_buckets_possible(int64_t n);
 hipError_t launch_sample_buckets(const Shape& sh, const DevState& ds, hipStream_t st);
 hipError_t launch_update(const Shape& sh, const DevState& ds, hipStream_t st);
