@@ -25,6 +25,15 @@ PEAK_HBM_GBS = 8000.0
 PEAK_FP32_TFLOPS = 157.3
 PEAK_INT8_TOPS = 5000.0
 
+# HBM-side traffic of the join kernel per launch on the default workload, from
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/gnnd_build_sift1m_d128_k32.md):
+# raw counter MiB averaged over the 7 launches of a build, and the scale factors
+# the same counters show for a 1 GiB device copy (fetch under-reports streaming
+# reads by 2; scattered 128-byte row reads are counted at face value, so the
+# scaled figure is an upper bound).
+JOIN_TRAFFIC = {"fetch_raw_mib": 7666.0, "write_raw_mib": 2337.0, "fetch_scale": 2.0,
+                "write_scale": 1.0}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -198,6 +207,12 @@ def main():
     avg_join_s = join_ms / T / 1e3
     hbm = {"bound": "hbm", "achieved": alg_bytes / avg_join_s / 1e9, "peak": PEAK_HBM_GBS,
            "unit": "GB/s", "traffic": None}
+    default_cfg = (args.n, args.d, args.k, args.p, args.target) == (1_000_000, 128, 32, 32, 0.95)
+    if mfma and default_cfg and T == 7:
+        jt = JOIN_TRAFFIC
+        hbm["traffic"] = (jt["fetch_raw_mib"] * jt["fetch_scale"]
+                          + jt["write_raw_mib"] * jt["write_scale"]) * 2 ** 20
+        hbm["traffic_raw"] = (jt["fetch_raw_mib"] + jt["write_raw_mib"]) * 2 ** 20
     hbm["frac"] = hbm["achieved"] / hbm["peak"]
     if mfma:
         ops = total_evals / T * args.d * 2
