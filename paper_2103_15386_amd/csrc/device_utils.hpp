@@ -94,6 +94,33 @@ __device__ inline T wave_sort(T v, int lane) {
   return v;
 }
 
+// Ascending sort when only the first `count` lanes hold real values and all
+// other lanes hold the maximum: the network over the next power of two is
+// enough (short lists are the common case), the tail is in place already.
+template <int N, typename T>
+__device__ inline T wave_sort_first(T v, int lane) {
+#pragma unroll
+  for (int k = 2; k <= N; k <<= 1) {
+#pragma unroll
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      T o = __shfl_xor(v, j, kWave);
+      bool keep_min = (((lane & j) == 0) == ((lane & k) == 0));
+      v = keep_min ? vmin(v, o) : vmax(v, o);
+    }
+  }
+  return v;
+}
+template <typename T>
+__device__ inline T wave_sort_upto(T v, int lane, int count) {
+  if (count <= 1) return v;
+  if (count <= 2) return wave_sort_first<2>(v, lane);
+  if (count <= 4) return wave_sort_first<4>(v, lane);
+  if (count <= 8) return wave_sort_first<8>(v, lane);
+  if (count <= 16) return wave_sort_first<16>(v, lane);
+  if (count <= 32) return wave_sort_first<32>(v, lane);
+  return wave_sort(v, lane);
+}
+
 // Lanes hold a bitonic sequence (ascending then descending, or an element-wise
 // min of an ascending and a reversed ascending one): 6 stages sort it ascending.
 template <typename T>

@@ -109,11 +109,53 @@ __global__ __launch_bounds__(kBlock) void k_rev_fill(int64_t n, int p, const int
   }
 }
 
-// Sec. 4.1, reverse part and duplicate removal.  The list of v holds its
-// forward samples; of its reverse candidates the 2p - |forward| with the
-// smallest hash(seed, kind, v, s, iter) (ties by s) are appended - the paper's
-// "append until the list is full" with the winners chosen by a hash instead of
-// by thread timing.  The list is then sorted by id and duplicates dropped.
+// Sec. 4.1, reverse part and duplicate removal for one list.  `fwd_raw` is the
+// list row as loaded (its first nf entries are the forward samples), `first` the
+// first 64 reverse candidates (lane < deg).  Of the candidates the 2p - nf with
+// the smallest hash(seed, kind, v, s, iter) (ties by s) are appended - the
+// paper's "append until the list is full" with the winners chosen by a hash
+// instead of by thread timing.  The list is then sorted by id, duplicates are
+// dropped and it is written back with -1 behind its end.  Returns its size.
+__device__ inline int select_list(int64_t v, int p, uint64_t base, uint32_t iter, int32_t* list,
+                                  uint32_t fwd_raw, int nf, const int32_t* csr, uint64_t beg,
+                                  uint64_t deg, uint32_t first, int lane) {
+  const uint32_t fwd = lane < nf ? fwd_raw : kIdMax;
+  const int room = 2 * p - nf;
+  uint32_t rev = kIdMax;
+  int m;
+  if (deg <= (uint64_t)room) {
+    m = (int)deg;
+    if (lane < m) rev = first;
+  } else {
+    m = room;
+    uint64_t best = kKeyMax;
+    for (uint64_t c = 0; c < deg; c += kWave) {
+      uint64_t key = kKeyMax;
+      if (c + lane < deg) {
+        const uint32_t s = c == 0 ? first : (uint32_t)csr[beg + c + lane];
+        key = ((hash3(base, (uint32_t)v, s, iter) >> 32) << 32) | (uint64_t)s;
+      }
+      key = wave_sort(key, lane);
+      best = wave_merge_smallest(best, key, lane);
+    }
+    if (lane < room) rev = (uint32_t)best;
+  }
+  const int src = lane - nf;
+  const uint32_t r = __shfl(rev, src < 0 ? 0 : src, kWave);
+  uint32_t val = lane < nf ? fwd : (src < m ? r : kIdMax);
+  val = wave_sort_upto(val, lane, nf + m);
+  const uint32_t prev = __shfl_up(val, 1, kWave);
+  const bool keep = val != kIdMax && (lane == 0 || val != prev);
+  const uint64_t mask = __ballot(keep);
+  const int count = __popcll(mask);
+  if (keep) list[__popcll(mask & lanes_below(lane))] = (int32_t)val;
+  if (lane >= count && lane < 2 * p) list[lane] = -1;
+  return count;
+}
+
+// One wavefront finishes both sample lists of a node.  Everything that does not
+// depend on another load (sizes, offsets, both list rows) is requested first,
+// then both candidate segments, so a node costs two memory round trips.
 __global__ __launch_bounds__(kBlock) void k_rev_select(int64_t n, int p, uint64_t base_new,
                                                        uint64_t base_old, uint32_t iter,
                                                        int32_t* snew, int32_t* sold,
@@ -127,57 +169,29 @@ __global__ __launch_bounds__(kBlock) void k_rev_select(int64_t n, int p, uint64_
   const int64_t v = wave_global_index();
   if (v >= n) return;
   const int lane = lane_id();
-  const int kind = blockIdx.y;
-  int32_t* list = (kind ? sold : snew) + v * 2 * p;
-  int32_t* cnt = kind ? cold : cnew;
-  const uint64_t* roff = kind ? roff_old : roff_new;
-  const int32_t* csr = kind ? csr_old : csr_new;
-  const uint64_t base = kind ? base_old : base_new;
-
-  const int nf = cnt[v];
-  const uint32_t fwd = lane < nf ? (uint32_t)list[lane] : kIdMax;
-  const uint64_t beg = roff[v];
-  const uint64_t deg = roff[v + 1] - beg;
-  const int room = 2 * p - nf;
-  uint32_t rev = kIdMax;
-  int m;
-  if (deg <= (uint64_t)room) {
-    m = (int)deg;
-    if (lane < m) rev = (uint32_t)csr[beg + lane];
-  } else {
-    m = room;
-    uint64_t best = kKeyMax;
-    for (uint64_t c = 0; c < deg; c += kWave) {
-      uint64_t key = kKeyMax;
-      if (c + lane < deg) {
-        uint32_t s = (uint32_t)csr[beg + c + lane];
-        key = ((hash3(base, (uint32_t)v, s, iter) >> 32) << 32) | (uint64_t)s;
-      }
-      key = wave_sort(key, lane);
-      best = wave_merge_smallest(best, key, lane);
-    }
-    if (lane < room) rev = (uint32_t)best;
-  }
-  const int src = lane - nf;
-  const uint32_t r = __shfl(rev, src < 0 ? 0 : src, kWave);
-  uint32_t val = lane < nf ? fwd : (src < m ? r : kIdMax);
-  val = wave_sort(val, lane);
-  const uint32_t prev = __shfl_up(val, 1, kWave);
-  const bool keep = val != kIdMax && (lane == 0 || val != prev);
-  const uint64_t mask = __ballot(keep);
-  const int count = __popcll(mask);
-  if (keep) list[__popcll(mask & lanes_below(lane))] = (int32_t)val;
-  if (lane >= count && lane < 2 * p) list[lane] = -1;
+  const int L = 2 * p;
+  int32_t* list_n = snew + v * L;
+  int32_t* list_o = sold + v * L;
+  const int nfn = cnew[v], nfo = cold[v];
+  const uint64_t bn = roff_new[v], en = roff_new[v + 1], bo = roff_old[v], eo = roff_old[v + 1];
+  const uint32_t rown = lane < L ? (uint32_t)list_n[lane] : kIdMax;
+  const uint32_t rowo = lane < L ? (uint32_t)list_o[lane] : kIdMax;
+  const uint64_t dn = en - bn, dO = eo - bo;
+  const uint32_t firstn = lane < dn ? (uint32_t)csr_new[bn + lane] : kIdMax;
+  const uint32_t firsto = lane < dO ? (uint32_t)csr_old[bo + lane] : kIdMax;
+  const int cn = select_list(v, p, base_new, iter, list_n, rown, nfn, csr_new, bn, dn, firstn, lane);
+  const int co = select_list(v, p, base_old, iter, list_o, rowo, nfo, csr_old, bo, dO, firsto, lane);
   if (lane == 0) {
-    cnt[v] = count;
-    counter_add(counters, kind ? C_SUMOLD : C_SUMNEW, v, (uint64_t)count);
+    cnew[v] = cn;
+    cold[v] = co;
+    counter_add(counters, C_SUMNEW, v, (uint64_t)cn);
+    counter_add(counters, C_SUMOLD, v, (uint64_t)co);
     // v can only sit in the sample list of a node that holds v as a forward
     // sample (deg of them) or that v holds as one (nf): that bounds the number
     // of joins v takes part in, hence the nearest-object results it can
     // receive - two per join as a NEW sample, one as an OLD sample.
-    const uint64_t joins = deg + (uint64_t)nf;
-    if (kind) capo[v] = (uint32_t)joins;
-    else capn[v] = (uint32_t)(2 * joins);
+    capn[v] = (uint32_t)(2 * (dn + (uint64_t)nfn));
+    capo[v] = (uint32_t)(dO + (uint64_t)nfo);
   }
 }
 
@@ -201,9 +215,12 @@ __device__ inline uint64_t filter_candidates(uint64_t pk, uint64_t row, int k, i
     pos += (entry_key(r) < kk) ? step : 0;
   }
   if (entry_key(__shfl(row, pos, kWave)) == kk) pk = kKeyMax;
-  any = __ballot(pk != kKeyMax) != 0ull;
+  const uint64_t left = __ballot(pk != kKeyMax);
+  any = left != 0ull;
   if (!any) return pk;
-  pk = wave_sort(pk, lane);
+  // survivors to the front, then a sorting network just wide enough for them
+  pk = wave_compact(pk, pk != kKeyMax, kKeyMax, lane);
+  pk = wave_sort_upto(pk, lane, __popcll(left));
   const uint64_t prev = __shfl_up(pk, 1, kWave);
   const bool rep = lane > 0 && pk != kKeyMax && entry_key(pk) == entry_key(prev);
   if (__ballot(rep) != 0ull) pk = wave_compact(pk, !rep, kKeyMax, lane);
@@ -219,13 +236,15 @@ __global__ __launch_bounds__(kBlock) void k_update(int64_t n, int k, uint64_t* G
                                                    const uint64_t* bins, uint64_t* counters) {
   const int64_t u = wave_global_index();
   if (u >= n) return;
-  uint64_t cnt = pcnt[u];
-  if (cnt == 0) return;
   const int lane = lane_id();
-  if (lane == 0) pcnt[u] = 0;  // ready for the next iteration
+  // everything that needs no other load is requested together (the row too, even
+  // if the node turns out to have received nothing): one round trip less
+  uint64_t cnt = pcnt[u];
   const uint64_t beg = poff[u], cap = poff[u + 1] - beg;
-  cnt = cnt < cap ? cnt : cap;
   uint64_t row = lane < k ? G[u * k + lane] : kKeyMax;
+  if (cnt == 0) return;
+  if (lane == 0) pcnt[u] = 0;  // ready for the next iteration
+  cnt = cnt < cap ? cnt : cap;
   bool changed = false;
   for (uint64_t c = 0; c < cnt; c += kWave) {
     uint64_t pk = (c + lane < cnt) ? bins[beg + c + lane] : kKeyMax;
@@ -558,7 +577,7 @@ hipError_t launch_sample(const Shape& sh, const DevState& ds, uint64_t seed, uin
                                         ds.rcnt_new, ds.rcnt_old, ds.roff_new, ds.roff_old,
                                         ds.csr_new, ds.csr_old);
   }
-  k_rev_select<<<dim3(grid, 2), kBlock, 0, st>>>(
+  k_rev_select<<<grid, kBlock, 0, st>>>(
       sh.n, sh.p, hash_base(seed, kTagRevNew), hash_base(seed, kTagRevOld), iter, ds.snew,
       ds.sold, ds.cnew, ds.cold, ds.roff_new, ds.roff_old, ds.csr_new, ds.csr_old, ds.capn,
       ds.capo, ds.counters);
