@@ -74,7 +74,7 @@ Layout make_layout(const gnnd_params* q, bool with_aside) {
   L.off_cso = take(n * p * 4);
   L.off_capn = take(n * 4);
   L.off_capo = take(n * 4);
-  L.off_pcnt = take(n * 4);
+  L.off_pcnt = take(n * 8);
   L.off_poff = take((n + 1) * 8);
   L.off_bins = take(n * 6 * p * 8);
   L.off_scan = take(scan_tmp_elems((int64_t)n) * 8);
@@ -143,7 +143,7 @@ void bind(gnnd_ctx* c, const Layout& L) {
   d.roff_old = (uint64_t*)(w + L.off_roo);
   d.csr_new = (int32_t*)(w + L.off_csn);
   d.csr_old = (int32_t*)(w + L.off_cso);
-  d.pcnt = (uint32_t*)(w + L.off_pcnt);
+  d.pslot = (uint64_t*)(w + L.off_pcnt);
   d.poff = (uint64_t*)(w + L.off_poff);
   d.capn = (uint32_t*)(w + L.off_capn);
   d.capo = (uint32_t*)(w + L.off_capo);
@@ -194,7 +194,7 @@ int create_impl(gnnd_ctx** out, const gnnd_params* prm, const void* vec_a, const
   // counters that must start at zero (they return to zero after every iteration)
   hipError_t e = launch_zero_u32(c->ds.rcnt_new, (size_t)prm->n, c->stream);
   if (e == hipSuccess) e = launch_zero_u32(c->ds.rcnt_old, (size_t)prm->n, c->stream);
-  if (e == hipSuccess) e = launch_zero_u32(c->ds.pcnt, (size_t)prm->n, c->stream);
+  if (e == hipSuccess) e = launch_zero_u32((uint32_t*)c->ds.pslot, 2 * (size_t)prm->n, c->stream);
   if (e == hipSuccess) e = launch_zero_u32(c->ds.bk_cnt, 2 * 4096, c->stream);
   if (e == hipSuccess)
     e = launch_zero_u32((uint32_t*)c->ds.counters, (size_t)kStripes * C_SLOTS * 2, c->stream);

@@ -232,19 +232,21 @@ __device__ inline uint64_t filter_candidates(uint64_t pk, uint64_t row, int k, i
 // objects, one entry per id - what inserting them one by one under a lock
 // gives in any order.  Admitted entries are flagged NEW.
 __global__ __launch_bounds__(kBlock) void k_update(int64_t n, int k, uint64_t* G, NodeMeta* meta,
-                                                   uint32_t* pcnt, const uint64_t* poff,
+                                                   const uint64_t* pslot, const uint64_t* poff,
                                                    const uint64_t* bins, uint64_t* counters) {
   const int64_t u = wave_global_index();
   if (u >= n) return;
   const int lane = lane_id();
   // everything that needs no other load is requested together (the row too, even
   // if the node turns out to have received nothing): one round trip less
-  uint64_t cnt = pcnt[u];
+  uint64_t cnt = pslot[u] & kSlotCountMask;
   const uint64_t beg = poff[u], cap = poff[u + 1] - beg;
   uint64_t row = lane < k ? G[u * k + lane] : kKeyMax;
   if (cnt == 0) return;
-  if (lane == 0) pcnt[u] = 0;  // ready for the next iteration
-  cnt = cnt < cap ? cnt : cap;
+  if (cnt > cap) {  // cannot happen: a segment is sized by the bound of what its node can receive
+    if (lane == 0) counter_add(counters, C_OVERFLOW, u, cnt - cap);
+    cnt = cap;
+  }
   bool changed = false;
   for (uint64_t c = 0; c < cnt; c += kWave) {
     uint64_t pk = (c + lane < cnt) ? bins[beg + c + lane] : kKeyMax;
@@ -293,13 +295,13 @@ __global__ __launch_bounds__(kBlock) void k_set_graph(int64_t total, int k, uint
 // Copy the proposal segments out: slot j of destination u's segment holds u and
 // the proposed (object, distance) when filled, -1 otherwise.
 template <bool FLOAT>
-__global__ __launch_bounds__(kBlock) void k_get_proposals(int64_t n, const uint32_t* pcnt,
+__global__ __launch_bounds__(kBlock) void k_get_proposals(int64_t n, const uint64_t* pslot,
                                                           const uint64_t* poff,
                                                           const uint64_t* bins, int32_t* u_out,
                                                           int32_t* v_out, void* dist) {
   const int64_t u = wave_global_index();
   if (u >= n) return;
-  const uint64_t beg = poff[u], cap = poff[u + 1] - beg, cnt = pcnt[u];
+  const uint64_t beg = poff[u], cap = poff[u + 1] - beg, cnt = pslot[u] & kSlotCountMask;
   for (uint64_t i = lane_id(); i < cap; i += kWave) {
     const bool have = i < cnt;
     const uint64_t e = have ? bins[beg + i] : 0ull;
@@ -480,7 +482,7 @@ __device__ inline uint64_t block_exclusive_scan(uint64_t v, uint64_t* total) {
 
 __global__ __launch_bounds__(kBlock) void k_scan_local(const uint32_t* in, const uint32_t* in2,
                                                        uint64_t* out, uint64_t* bsum,
-                                                       int64_t count) {
+                                                       uint64_t* counters, int64_t count) {
   const int64_t i0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * kScanPerThread;
   uint32_t v[kScanPerThread];
   uint64_t sum = 0;
@@ -488,6 +490,8 @@ __global__ __launch_bounds__(kBlock) void k_scan_local(const uint32_t* in, const
   for (int j = 0; j < kScanPerThread; ++j) {
     v[j] = (i0 + j < count) ? in[i0 + j] + (in2 ? in2[i0 + j] : 0u) : 0u;
     sum += v[j];
+    // a segment longer than the count field of the slot word can hold is reported
+    if (counters && v[j] > kSlotCountMask) counter_add(counters, C_OVERFLOW, i0 + j, v[j]);
   }
   uint64_t total;
   uint64_t run = block_exclusive_scan(sum, &total);
@@ -511,23 +515,28 @@ __global__ __launch_bounds__(kBlock) void k_scan_bsum(uint64_t* bsum, int64_t nb
   }
 }
 
-__global__ __launch_bounds__(kBlock) void k_scan_add(uint64_t* out, const uint64_t* bsum,
-                                                     int64_t count) {
+__global__ __launch_bounds__(kBlock) void k_scan_add(uint64_t* out, uint64_t* packed,
+                                                     const uint64_t* bsum, int64_t count) {
   const int64_t i0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * kScanPerThread;
   const uint64_t add = bsum[blockIdx.x];
 #pragma unroll
   for (int j = 0; j < kScanPerThread; ++j)
-    if (i0 + j <= count) out[i0 + j] += add;
+    if (i0 + j <= count) {
+      const uint64_t v = out[i0 + j] + add;
+      out[i0 + j] = v;
+      // slot word of element i0 + j: its offset, nothing received yet
+      if (packed && i0 + j < count) packed[i0 + j] = v << kSlotCountBits;
+    }
 }
 
 size_t scan_tmp_elems(int64_t count) { return (size_t)((count + 1 + kScanPerBlock - 1) / kScanPerBlock); }
 
-hipError_t launch_scan(const uint32_t* in, const uint32_t* in2, uint64_t* out, uint64_t* tmp,
-                       int64_t count, hipStream_t st) {
+hipError_t launch_scan(const uint32_t* in, const uint32_t* in2, uint64_t* out, uint64_t* packed,
+                       uint64_t* counters, uint64_t* tmp, int64_t count, hipStream_t st) {
   const int64_t nb = (count + 1 + kScanPerBlock - 1) / kScanPerBlock;
-  k_scan_local<<<(unsigned)nb, kBlock, 0, st>>>(in, in2, out, tmp, count);
+  k_scan_local<<<(unsigned)nb, kBlock, 0, st>>>(in, in2, out, tmp, counters, count);
   k_scan_bsum<<<1, kBlock, 0, st>>>(tmp, nb);
-  k_scan_add<<<(unsigned)nb, kBlock, 0, st>>>(out, tmp, count);
+  k_scan_add<<<(unsigned)nb, kBlock, 0, st>>>(out, packed, tmp, count);
   return hipGetLastError();
 }
 
@@ -569,9 +578,10 @@ hipError_t launch_sample(const Shape& sh, const DevState& ds, uint64_t seed, uin
     // very large n: one global atomic per edge for counting, one for placing
     k_sample_fwd<<<grid, kBlock, 0, st>>>(sh.n, sh.k, sh.p, ds.G, ds.snew, ds.sold, ds.cnew,
                                           ds.cold, ds.rcnt_new, ds.rcnt_old);
-    hipError_t e = launch_scan(ds.rcnt_new, nullptr, ds.roff_new, ds.scan_tmp, sh.n, st);
+    hipError_t e = launch_scan(ds.rcnt_new, nullptr, ds.roff_new, nullptr, nullptr, ds.scan_tmp,
+                               sh.n, st);
     if (e != hipSuccess) return e;
-    e = launch_scan(ds.rcnt_old, nullptr, ds.roff_old, ds.scan_tmp, sh.n, st);
+    e = launch_scan(ds.rcnt_old, nullptr, ds.roff_old, nullptr, nullptr, ds.scan_tmp, sh.n, st);
     if (e != hipSuccess) return e;
     k_rev_fill<<<grid, kBlock, 0, st>>>(sh.n, sh.p, ds.snew, ds.sold, ds.cnew, ds.cold,
                                         ds.rcnt_new, ds.rcnt_old, ds.roff_new, ds.roff_old,
@@ -582,11 +592,11 @@ hipError_t launch_sample(const Shape& sh, const DevState& ds, uint64_t seed, uin
       ds.sold, ds.cnew, ds.cold, ds.roff_new, ds.roff_old, ds.csr_new, ds.csr_old, ds.capn,
       ds.capo, ds.counters);
   // one segment of the proposal array per destination, sized by its bound
-  return launch_scan(ds.capn, ds.capo, ds.poff, ds.scan_tmp, sh.n, st);
+  return launch_scan(ds.capn, ds.capo, ds.poff, ds.pslot, ds.counters, ds.scan_tmp, sh.n, st);
 }
 
 hipError_t launch_update(const Shape& sh, const DevState& ds, hipStream_t st) {
-  k_update<<<blocks_for_waves(sh.n), kBlock, 0, st>>>(sh.n, sh.k, ds.G, ds.meta, ds.pcnt, ds.poff,
+  k_update<<<blocks_for_waves(sh.n), kBlock, 0, st>>>(sh.n, sh.k, ds.G, ds.meta, ds.pslot, ds.poff,
                                                       ds.bins, ds.counters);
   return hipGetLastError();
 }
@@ -617,9 +627,9 @@ hipError_t launch_get_proposals(const Shape& sh, const DevState& ds, int32_t* u,
                                 void* dist, hipStream_t st) {
   const unsigned grid = blocks_for_waves(sh.n);
   if (sh.metric == kL2U8)
-    k_get_proposals<false><<<grid, kBlock, 0, st>>>(sh.n, ds.pcnt, ds.poff, ds.bins, u, v, dist);
+    k_get_proposals<false><<<grid, kBlock, 0, st>>>(sh.n, ds.pslot, ds.poff, ds.bins, u, v, dist);
   else
-    k_get_proposals<true><<<grid, kBlock, 0, st>>>(sh.n, ds.pcnt, ds.poff, ds.bins, u, v, dist);
+    k_get_proposals<true><<<grid, kBlock, 0, st>>>(sh.n, ds.pslot, ds.poff, ds.bins, u, v, dist);
   const int64_t slots = sh.n * 6 * sh.p;
   const unsigned g2 = (unsigned)((slots + kBlock - 1) / kBlock);
   k_fill_i32<<<g2, kBlock, 0, st>>>(u, ds.poff + sh.n, slots, -1);

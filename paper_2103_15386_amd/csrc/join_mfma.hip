@@ -161,8 +161,7 @@ template <int KSTEPS, bool FCODE, bool MERGE>
 __global__ __launch_bounds__(kMB) __attribute__((amdgpu_waves_per_eu(3, 3))) void k_join_mfma(
     const int8_t* __restrict__ shadow, const NodeMeta* __restrict__ meta, int dpad, int64_t n,
     int p, int64_t split, const int32_t* __restrict__ snew, const int32_t* __restrict__ sold,
-    uint32_t* pcnt, const uint64_t* __restrict__ poff, uint64_t* __restrict__ bins,
-    uint64_t* counters) {
+    uint64_t* pslot, uint64_t slots, uint64_t* __restrict__ bins, uint64_t* counters) {
   // per wave, for the 128 rows (NEW 0..63, OLD 64..127): -((norm << 6) | position), the ids
   // (absent = INT_MAX so that both halves stay ascending), and a scratch row
   __shared__ __attribute__((aligned(16))) int32_t s_norm[4][128];
@@ -377,19 +376,15 @@ __global__ __launch_bounds__(kMB) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     }
     // slot requests for all three results first ...
     // (the two results of a NEW sample go to the same list: one request for both)
-    uint32_t slot_n = 0, slot_o = 0;
-    uint64_t beg_n = 0, end_n = 0, beg_o = 0, end_o = 0;
+    // one returning add on the destination's slot word yields the segment start
+    // and the place in it
+    uint64_t word_n = 0, word_o = 0;
     const uint32_t want_n = (pass[0] ? 1u : 0u) + (pass[1] ? 1u : 0u);
-    if (want_n) {
-      slot_n = atomicAdd(&pcnt[id_new], want_n);
-      beg_n = poff[id_new];
-      end_n = poff[id_new + 1];
-    }
-    if (pass[2]) {
-      slot_o = atomicAdd(&pcnt[id_old], 1u);
-      beg_o = poff[id_old];
-      end_o = poff[id_old + 1];
-    }
+    if (want_n)
+      word_n = atomicAdd(reinterpret_cast<unsigned long long*>(&pslot[id_new]),
+                         (unsigned long long)want_n);
+    if (pass[2])
+      word_o = atomicAdd(reinterpret_cast<unsigned long long*>(&pslot[id_old]), 1ull);
     const uint32_t passed_total =
         (uint32_t)__popcll(__ballot(pass[0])) + (uint32_t)__popcll(__ballot(pass[1])) +
         (uint32_t)__popcll(__ballot(pass[2]));
@@ -405,17 +400,21 @@ __global__ __launch_bounds__(kMB) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
       }
     }
     // ... and only now the slots are used
+    // (segments cannot overflow, see the sampling stage; the test against the
+    // array size only keeps a violated bound from writing outside the array)
+    const uint64_t at_n = (word_n >> kSlotCountBits) + (word_n & kSlotCountMask);
+    const uint64_t at_o = (word_o >> kSlotCountBits) + (word_o & kSlotCountMask);
     if (pass[0]) {
-      if (slot_n < end_n - beg_n) bins[beg_n + slot_n] = entry[0];
+      if (at_n < slots) bins[at_n] = entry[0];
       else ++over_total;
     }
     if (pass[1]) {
-      const uint32_t at = slot_n + (pass[0] ? 1u : 0u);
-      if (at < end_n - beg_n) bins[beg_n + at] = entry[1];
+      const uint64_t at = at_n + (pass[0] ? 1u : 0u);
+      if (at < slots) bins[at] = entry[1];
       else ++over_total;
     }
     if (pass[2]) {
-      if (slot_o < end_o - beg_o) bins[beg_o + slot_o] = entry[2];
+      if (at_o < slots) bins[at_o] = entry[2];
       else ++over_total;
     }
 #pragma unroll
@@ -450,7 +449,7 @@ template <int KSTEPS>
 static void launch_k(bool fcode, bool merge, unsigned grid, hipStream_t st, const int8_t* shadow,
                      const NodeMeta* meta, int dpad, const Shape& sh, const DevState& ds) {
 #define GNND_ARGS shadow, meta, dpad, sh.n, sh.p, sh.split, ds.snew, ds.sold, \
-                  ds.pcnt, ds.poff, ds.bins, ds.counters
+                  ds.pslot, (uint64_t)sh.n * 6 * sh.p, ds.bins, ds.counters
   if (fcode) {
     if (merge) k_join_mfma<KSTEPS, true, true><<<grid, kMB, 0, st>>>(GNND_ARGS);
     else k_join_mfma<KSTEPS, true, false><<<grid, kMB, 0, st>>>(GNND_ARGS);

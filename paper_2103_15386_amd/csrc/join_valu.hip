@@ -95,8 +95,8 @@ template <int METRIC>
 __global__ __launch_bounds__(kJB) void k_join_valu(
     VecSrc vs, int64_t n, int p, int merge_mode, const int32_t* __restrict__ snew,
     const int32_t* __restrict__ sold, const int32_t* __restrict__ cnew,
-    const int32_t* __restrict__ cold, const NodeMeta* __restrict__ meta, uint32_t* pcnt,
-    const uint64_t* __restrict__ poff, uint64_t* __restrict__ bins, uint64_t* counters) {
+    const int32_t* __restrict__ cold, const NodeMeta* __restrict__ meta, uint64_t* pslot,
+    uint64_t slots, uint64_t* __restrict__ bins, uint64_t* counters) {
   using TR = JoinTraits<METRIC>;
   using T = typename TR::elem;
   using ACC = typename TR::acc;
@@ -257,9 +257,10 @@ __global__ __launch_bounds__(kJB) void k_join_valu(
   // hand the result to the destination's segment of the proposal array
   bool overflow = false;
   if (pass) {
-    const uint64_t beg = poff[self], cap = poff[self + 1] - beg;
-    const uint32_t pos = atomicAdd(&pcnt[self], 1u);
-    if (pos < cap) bins[beg + pos] = make_entry((uint32_t)(best >> 32), (uint32_t)best, 3u);
+    // one returning add: the segment start and this result's place in it
+    const uint64_t w = atomicAdd(reinterpret_cast<unsigned long long*>(&pslot[self]), 1ull);
+    const uint64_t at = (w >> kSlotCountBits) + (w & kSlotCountMask);
+    if (at < slots) bins[at] = make_entry((uint32_t)(best >> 32), (uint32_t)best, 3u);
     else overflow = true;
   }
   const uint64_t nover = __popcll(__ballot(overflow));
@@ -293,21 +294,22 @@ hipError_t launch_join(const Shape& sh, const DevState& ds, int path, bool merge
   (void)path;
   VecSrc vs{sh.vec_a, sh.vec_b, sh.split, sh.d};
   const unsigned grid = (unsigned)sh.n;
+  const uint64_t slots = (uint64_t)sh.n * 6 * sh.p;  // size of the proposal array
   switch (sh.metric) {
     case kL2F32:
       k_join_valu<kL2F32><<<grid, kJB, 0, st>>>(vs, sh.n, sh.p, merge_mode ? 1 : 0, ds.snew,
-                                                ds.sold, ds.cnew, ds.cold, ds.meta, ds.pcnt,
-                                                ds.poff, ds.bins, ds.counters);
+                                                ds.sold, ds.cnew, ds.cold, ds.meta, ds.pslot,
+                                                slots, ds.bins, ds.counters);
       break;
     case kAngularF32:
       k_join_valu<kAngularF32><<<grid, kJB, 0, st>>>(vs, sh.n, sh.p, merge_mode ? 1 : 0, ds.snew,
-                                                     ds.sold, ds.cnew, ds.cold, ds.meta, ds.pcnt,
-                                                     ds.poff, ds.bins, ds.counters);
+                                                     ds.sold, ds.cnew, ds.cold, ds.meta, ds.pslot,
+                                                     slots, ds.bins, ds.counters);
       break;
     default:
       k_join_valu<kL2U8><<<grid, kJB, 0, st>>>(vs, sh.n, sh.p, merge_mode ? 1 : 0, ds.snew,
-                                               ds.sold, ds.cnew, ds.cold, ds.meta, ds.pcnt,
-                                               ds.poff, ds.bins, ds.counters);
+                                               ds.sold, ds.cnew, ds.cold, ds.meta, ds.pslot,
+                                               slots, ds.bins, ds.counters);
   }
   return hipGetLastError();
 }

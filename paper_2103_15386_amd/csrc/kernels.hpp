@@ -15,6 +15,12 @@ enum : int {
 };
 constexpr int kStripes = 64;  // counters are striped to spread same-address atomics
 
+// One 64-bit word per destination serves the hand-out of results: the low
+// kSlotCountBits bits count the results received so far, the rest is the first
+// slot of the destination's segment.  A single returning atomic add yields both.
+constexpr int kSlotCountBits = 24;
+constexpr uint64_t kSlotCountMask = (1ull << kSlotCountBits) - 1;
+
 // What the join gathers per sampled object besides its vector, kept small (8
 // bytes, 8 MB per million nodes) so that the array stays cache resident: the
 // distance code of its list's last entry (nothing farther can enter) and the
@@ -40,7 +46,7 @@ struct DevState {
   int32_t* csr_old;    // n*p
   uint32_t* capn;      // n: upper bound of the proposals a node can receive as a NEW sample
   uint32_t* capo;      // n: ... as an OLD sample
-  uint32_t* pcnt;      // n proposals received per destination (zero between iterations)
+  uint64_t* pslot;     // n: (segment start << 24) | proposals received; rewritten by every sampling
   uint64_t* poff;      // n+1 segment offsets into bins (exclusive scan of capn + capo)
   uint64_t* bins;      // n*6p packed proposals, one segment per destination
   uint64_t* scan_tmp;  // block sums of the scans
@@ -91,7 +97,8 @@ hipError_t launch_zero_u32(uint32_t* p, size_t count, hipStream_t st);
 
 // Exclusive scan of `count` uint32 into uint64 offsets out[0..count] (out[count] = total).
 // (in2 may be NULL; otherwise the scanned values are in[i] + in2[i])
-hipError_t launch_scan(const uint32_t* in, const uint32_t* in2, uint64_t* out, uint64_t* tmp,
+hipError_t launch_scan(const uint32_t* in, const uint32_t* in2, uint64_t* out, uint64_t* packed,
+                       uint64_t* counters, uint64_t* tmp,
                        int64_t count, hipStream_t st);
 size_t scan_tmp_elems(int64_t count);
 
