@@ -57,8 +57,11 @@ __global__ __launch_bounds__(256) void k_pack_i8(const void* vec_a, const void* 
 
 // Alg. 1, first loop, on the int8 rows: k distinct random neighbours per node,
 // exact distances |a|^2 + |b|^2 - 2 a.b (four products per v_dot4), sorted
-// ascending by (distance, id), flagged NEW.  One wavefront per node, one
-// neighbour per lane; a row is dpad <= 128 bytes, i.e. one cache line.
+// ascending by (distance, id), flagged NEW.  One wavefront per node.  A row is
+// C = dpad / 16 <= 8 chunks of 16 bytes; the C lanes of a group read one
+// neighbour's row as one contiguous line (64 / C neighbours per load), multiply
+// it with the node's own chunk and add up across the group; the sums are then
+// handed to the lanes that hold the neighbours, one per lane, for the sort.
 template <bool FCODE>
 __global__ __launch_bounds__(256) void k_init_random_i8(const int8_t* __restrict__ shadow,
                                                         NodeMeta* meta, int dpad, int64_t n, int k,
@@ -67,17 +70,36 @@ __global__ __launch_bounds__(256) void k_init_random_i8(const int8_t* __restrict
   const int64_t s = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (s >= n) return;
   const uint32_t id = draw_distinct(base_hash, (uint32_t)s, k, (uint32_t)n, 0u, (uint32_t)s, lane);
+  const int C = dpad >> 4, per_load = kWave / C;
+  const int grp = lane / C, sub = lane - grp * C;
+  const bool lane_used = grp < per_load;  // C = 6 leaves four lanes without a group
+  const v4i x = *reinterpret_cast<const v4i*>(shadow + s * dpad + 16 * sub);
+  const int32_t norm_s = meta[s].norm;
+  int32_t dot = 0, norm_id = 0;
+  if (lane < k) norm_id = meta[id].norm;
+  for (int r0 = 0; r0 < k; r0 += per_load) {
+    const int j = r0 + grp;  // the neighbour this group reads
+    const bool act = lane_used && j < k;
+    const uint32_t nid = __shfl(id, act ? j : 0, kWave);
+    int32_t part = 0;
+    if (act) {
+      const v4i y = *reinterpret_cast<const v4i*>(shadow + (int64_t)nid * dpad + 16 * sub);
+#pragma unroll
+      for (int t = 0; t < 4; ++t) part = __builtin_amdgcn_sdot4(x[t], y[t], part, false);
+    }
+    int32_t total = part;
+    for (int off = 1; off < C; ++off) {
+      int o = sub + off;
+      o = o >= C ? o - C : o;
+      total += __shfl(part, (grp * C + o) & 63, kWave);
+    }
+    // neighbour j = lane sits in group lane - r0
+    const int32_t got = __shfl(total, ((lane - r0) * C) & 63, kWave);
+    if (lane >= r0 && lane < r0 + per_load) dot = got;
+  }
   uint64_t e = kKeyMax;
   if (lane < k) {
-    const v4i* a = reinterpret_cast<const v4i*>(shadow + s * dpad);
-    const v4i* b = reinterpret_cast<const v4i*>(shadow + (int64_t)id * dpad);
-    int32_t dot = 0;
-    for (int q = 0; q < dpad / 16; ++q) {
-      const v4i x = a[q], y = b[q];
-#pragma unroll
-      for (int t = 0; t < 4; ++t) dot = __builtin_amdgcn_sdot4(x[t], y[t], dot, false);
-    }
-    const int32_t dist = meta[s].norm + meta[id].norm - 2 * dot;
+    const int32_t dist = norm_s + norm_id - 2 * dot;
     e = make_entry(FCODE ? ord_f32((float)dist) : ord_i32(dist), id, 1u);
   }
   e = wave_sort(e, lane);
