@@ -144,6 +144,8 @@ __device__ inline int32_t both_halves_max(int32_t x) {
   return a > b ? a : b;
 }
 
+typedef uint64_t EntryPair __attribute__((ext_vector_type(2), aligned(8)));
+
 struct Operand {
   v4i k[4];  // 4 steps of 32 dimensions, 16 bytes of this lane each
 };
@@ -426,13 +428,11 @@ __global__ __launch_bounds__(kMB) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     // array size only keeps a violated bound from writing outside the array)
     const uint64_t at_n = (word_n >> kSlotCountBits) + (word_n & kSlotCountMask);
     const uint64_t at_o = (word_o >> kSlotCountBits) + (word_o & kSlotCountMask);
-    if (pass[0]) {
-      if (at_n < slots) bins[at_n] = entry[0];
-      else ++over_total;
-    }
-    if (pass[1]) {
-      const uint64_t at = at_n + (pass[0] ? 1u : 0u);
-      if (at < slots) bins[at] = entry[1];
+    if (pass[0] && pass[1]) {  // neighbouring slots: one 16-byte store
+      if (at_n + 1 < slots) *reinterpret_cast<EntryPair*>(bins + at_n) = EntryPair{entry[0], entry[1]};
+      else over_total += 2;
+    } else if (want_n) {
+      if (at_n < slots) bins[at_n] = pass[0] ? entry[0] : entry[1];
       else ++over_total;
     }
     if (pass[2]) {

@@ -9,9 +9,9 @@
 //                      >> tb), flushed with one global atomic per bucket.
 //   2. k_bucket_scan - exclusive scan of the <= 4096 bucket totals per kind.
 //   3. k_fwd_scatter - every workgroup reserves, per bucket, a run in that
-//                      bucket's region (one global atomic per bucket) and
-//                      writes its (target, source) edges there, ranked by LDS
-//                      atomics.
+//                      bucket's region (one global atomic per bucket, sized by
+//                      the histogram it kept in step 1) and writes its (target,
+//                      source) edges there, ranked by LDS atomics.
 //   4. k_bucket_csr  - one workgroup per bucket: LDS counters per target,
 //                      block scan = the targets' segment offsets, second sweep
 //                      places the sources.  Buckets are in target order, so the
@@ -56,17 +56,20 @@ __device__ inline void forward_sample_row(int64_t s, int64_t n, int k, int p, ui
     sold[s * L + ro] = id;
     v_old = id;
   }
+  const int cn = __popcll(mn) < p ? __popcll(mn) : p, co = __popcll(mo) < p ? __popcll(mo) : p;
+  // the rest of the forward part reads "nothing", so that the scatter pass needs no counts
+  if (lane >= cn && lane < p) snew[s * L + lane] = -1;
+  if (lane >= co && lane < p) sold[s * L + lane] = -1;
   if (lane == 0) {
-    const int cn = __popcll(mn), co = __popcll(mo);
-    cnew[s] = cn < p ? cn : p;
-    cold[s] = co < p ? co : p;
+    cnew[s] = cn;
+    cold[s] = co;
   }
 }
 
 __global__ __launch_bounds__(kSB) void k_fwd_count(int64_t n, int k, int p, BucketGeom g,
                                                    uint64_t* G, int32_t* snew, int32_t* sold,
                                                    int32_t* cnew, int32_t* cold,
-                                                   uint32_t* bcnt) {
+                                                   uint32_t* bcnt, uint32_t* wg_hist) {
   __shared__ uint32_t hist[2 * kMaxBuckets];
   for (int i = threadIdx.x; i < 2 * g.nb; i += kSB) hist[i] = 0;
   __syncthreads();
@@ -80,8 +83,12 @@ __global__ __launch_bounds__(kSB) void k_fwd_count(int64_t n, int k, int p, Buck
     if (vo >= 0) atomicAdd(&hist[g.nb + (vo >> g.tb)], 1u);
   }
   __syncthreads();
-  for (int i = threadIdx.x; i < 2 * g.nb; i += kSB)
-    if (hist[i]) atomicAdd(&bcnt[i], hist[i]);
+  uint32_t* mine = wg_hist + (size_t)blockIdx.x * 2 * g.nb;  // read back by the scatter pass
+  for (int i = threadIdx.x; i < 2 * g.nb; i += kSB) {
+    const uint32_t c = hist[i];
+    mine[i] = c;
+    if (c) atomicAdd(&bcnt[i], c);
+  }
 }
 
 // boff[kind][0..nb] = exclusive scan of bcnt[kind][0..nb); the counters become
@@ -120,38 +127,46 @@ __global__ __launch_bounds__(kCsrBlock) void k_bucket_scan(int nb, uint32_t* bcn
 
 __global__ __launch_bounds__(kSB) void k_fwd_scatter(int64_t n, int p, BucketGeom g,
                                                      const int32_t* snew, const int32_t* sold,
-                                                     const int32_t* cnew, const int32_t* cold,
+                                                     const uint32_t* wg_hist,
                                                      const uint64_t* boff, uint32_t* bcur,
                                                      uint2* edges_new, uint2* edges_old) {
-  __shared__ uint32_t hist[2 * kMaxBuckets];  // counts, then this workgroup's run starts
-  for (int i = threadIdx.x; i < 2 * g.nb; i += kSB) hist[i] = 0;
+  __shared__ uint32_t hist[2 * kMaxBuckets];  // this workgroup's write cursors, per bucket
+  const uint32_t* mine = wg_hist + (size_t)blockIdx.x * 2 * g.nb;
+  for (int i = threadIdx.x; i < 2 * g.nb; i += kSB) {
+    const uint32_t c = mine[i];
+    hist[i] = c ? atomicAdd(&bcur[i], c) : 0u;  // start of this workgroup's run in the bucket
+  }
   __syncthreads();
   const int lane = lane_id(), wave = threadIdx.x >> 6;
   const int L = 2 * p;
   const int64_t row0 = (int64_t)blockIdx.x * g.rows_per_wg;
   const int64_t row1 = row0 + g.rows_per_wg < n ? row0 + g.rows_per_wg : n;
-  for (int64_t s = row0 + wave; s < row1; s += kSB / kWave) {
-    if (lane < cnew[s]) atomicAdd(&hist[snew[s * L + lane] >> g.tb], 1u);
-    if (lane < cold[s]) atomicAdd(&hist[g.nb + (sold[s * L + lane] >> g.tb)], 1u);
-  }
-  __syncthreads();
-  for (int i = threadIdx.x; i < 2 * g.nb; i += kSB) {
-    const uint32_t c = hist[i];
-    hist[i] = c ? atomicAdd(&bcur[i], c) : 0u;  // start of this workgroup's run in the bucket
-  }
-  __syncthreads();
-  for (int64_t s = row0 + wave; s < row1; s += kSB / kWave) {
-    if (lane < cnew[s]) {
-      const uint32_t v = (uint32_t)snew[s * L + lane];
-      const uint32_t b = v >> g.tb;
-      const uint32_t pos = atomicAdd(&hist[b], 1u);
-      edges_new[boff[b] + pos] = make_uint2(v, (uint32_t)s);
+  constexpr int kRowsAtOnce = 4;  // rows in flight per wavefront
+  constexpr int kStep = kRowsAtOnce * (kSB / kWave);
+  for (int64_t s0 = row0 + wave; s0 < row1; s0 += kStep) {
+    int32_t vn[kRowsAtOnce], vo[kRowsAtOnce];
+#pragma unroll
+    for (int r = 0; r < kRowsAtOnce; ++r) {
+      const int64_t s = s0 + r * (kSB / kWave);
+      const bool have = s < row1 && lane < p;
+      vn[r] = have ? snew[s * L + lane] : -1;
+      vo[r] = have ? sold[s * L + lane] : -1;
     }
-    if (lane < cold[s]) {
-      const uint32_t v = (uint32_t)sold[s * L + lane];
-      const uint32_t b = v >> g.tb;
-      const uint32_t pos = atomicAdd(&hist[g.nb + b], 1u);
-      edges_old[boff[g.nb + 1 + b] + pos] = make_uint2(v, (uint32_t)s);
+#pragma unroll
+    for (int r = 0; r < kRowsAtOnce; ++r) {
+      const int64_t s = s0 + r * (kSB / kWave);
+      if (vn[r] >= 0) {
+        const uint32_t v = (uint32_t)vn[r];
+        const uint32_t b = v >> g.tb;
+        const uint32_t pos = atomicAdd(&hist[b], 1u);
+        edges_new[boff[b] + pos] = make_uint2(v, (uint32_t)s);
+      }
+      if (vo[r] >= 0) {
+        const uint32_t v = (uint32_t)vo[r];
+        const uint32_t b = v >> g.tb;
+        const uint32_t pos = atomicAdd(&hist[g.nb + b], 1u);
+        edges_old[boff[g.nb + 1 + b] + pos] = make_uint2(v, (uint32_t)s);
+      }
     }
   }
 }
@@ -177,7 +192,18 @@ __global__ __launch_bounds__(kCsrBlock) void k_bucket_csr(int64_t n, BucketGeom 
   const uint32_t mask = (uint32_t)T - 1u;
   for (int i = threadIdx.x; i < T; i += kCsrBlock) cnt[i] = 0;
   __syncthreads();
-  for (uint64_t e = beg + threadIdx.x; e < end; e += kCsrBlock) atomicAdd(&cnt[edges[e].x & mask], 1u);
+  constexpr int kAtOnce = 4;  // edges in flight per thread
+  for (uint64_t e0 = beg + threadIdx.x; e0 < end; e0 += kAtOnce * kCsrBlock) {
+    uint32_t t[kAtOnce];
+#pragma unroll
+    for (int r = 0; r < kAtOnce; ++r) {
+      const uint64_t e = e0 + (uint64_t)r * kCsrBlock;
+      t[r] = e < end ? edges[e].x : 0xffffffffu;
+    }
+#pragma unroll
+    for (int r = 0; r < kAtOnce; ++r)
+      if (t[r] != 0xffffffffu) atomicAdd(&cnt[t[r] & mask], 1u);
+  }
   __syncthreads();
   // exclusive scan over the T counters: T / 1024 consecutive counters per thread
   const int per = T / kCsrBlock;  // T >= 4096
@@ -214,10 +240,19 @@ __global__ __launch_bounds__(kCsrBlock) void k_bucket_csr(int64_t n, BucketGeom 
   if (b == g.nb - 1 && threadIdx.x == 0) roff[n] = bo[g.nb];
   if (threadIdx.x == 0) bcnt[kind * g.nb + b] = 0;  // the next iteration counts from zero
   __syncthreads();
-  for (uint64_t e = beg + threadIdx.x; e < end; e += kCsrBlock) {
-    const uint2 ed = edges[e];
-    const uint32_t pos = atomicAdd(&cnt[ed.x & mask], 1u);
-    csr[beg + pos] = (int32_t)ed.y;
+  for (uint64_t e0 = beg + threadIdx.x; e0 < end; e0 += kAtOnce * kCsrBlock) {
+    uint2 ed[kAtOnce];
+#pragma unroll
+    for (int r = 0; r < kAtOnce; ++r) {
+      const uint64_t e = e0 + (uint64_t)r * kCsrBlock;
+      ed[r] = e < end ? edges[e] : make_uint2(0xffffffffu, 0u);
+    }
+#pragma unroll
+    for (int r = 0; r < kAtOnce; ++r)
+      if (ed[r].x != 0xffffffffu) {
+        const uint32_t pos = atomicAdd(&cnt[ed[r].x & mask], 1u);
+        csr[beg + pos] = (int32_t)ed[r].y;
+      }
   }
 }
 
@@ -247,12 +282,14 @@ hipError_t launch_sample_buckets(const Shape& sh, const DevState& ds, hipStream_
   uint64_t* boff = ds.bk_off;
   uint2* edges_new = reinterpret_cast<uint2*>(ds.bins);
   uint2* edges_old = edges_new + sh.n * sh.p;
+  // per-workgroup bucket histograms, behind the edges in the same (still unused) array
+  uint32_t* wg_hist = reinterpret_cast<uint32_t*>(edges_old + sh.n * sh.p);
   const unsigned grid = (unsigned)((sh.n + g.rows_per_wg - 1) / g.rows_per_wg);
   k_fwd_count<<<grid, kSB, 0, st>>>(sh.n, sh.k, sh.p, g, ds.G, ds.snew, ds.sold, ds.cnew, ds.cold,
-                                    bcnt);
+                                    bcnt, wg_hist);
   k_bucket_scan<<<1, kCsrBlock, 0, st>>>(g.nb, bcnt, boff);
-  k_fwd_scatter<<<grid, kSB, 0, st>>>(sh.n, sh.p, g, ds.snew, ds.sold, ds.cnew, ds.cold, boff,
-                                      bcnt, edges_new, edges_old);
+  k_fwd_scatter<<<grid, kSB, 0, st>>>(sh.n, sh.p, g, ds.snew, ds.sold, wg_hist, boff, bcnt,
+                                      edges_new, edges_old);
   k_bucket_csr<<<dim3((unsigned)g.nb, 2), kCsrBlock, (size_t)4 << g.tb, st>>>(
       sh.n, g, boff, bcnt, edges_new, edges_old, ds.roff_new, ds.roff_old, ds.csr_new,
       ds.csr_old);
