@@ -1,21 +1,24 @@
-// Reverse-neighbour candidates (Sec. 4.1) grouped by target without one global
-// atomic per edge.  Device-wide atomics run at a fixed ~27 G/s (12 G/s when the
-// old value is needed), which made them the cost of the sampling stage, so the
+// Reverse-neighbour candidates (Sec. 4.1) grouped by target without global
+// atomics.  Device-wide atomics run at a fixed ~27 G/s (12 G/s when the old
+// value is needed), which made them the cost of the sampling stage, so the
 // transpose "s samples v  ->  s is a candidate of v" is done as a two-level
 // counting sort instead:
 //   1. k_fwd_count   - forward sampling of every list (first p NEW / first p
 //                      OLD entries, sampled NEW flagged OLD); per workgroup an
 //                      LDS histogram of the targets' buckets (bucket = target id
-//                      >> tb), flushed with one global atomic per bucket.
-//   2. k_bucket_scan - exclusive scan of the <= 4096 bucket totals per kind.
-//   3. k_fwd_scatter - every workgroup reserves, per bucket, a run in that
-//                      bucket's region (one global atomic per bucket, sized by
-//                      the histogram it kept in step 1) and writes its (target,
-//                      source) edges there, ranked by LDS atomics.
+//                      >> tb), kept as one column of a (bucket x workgroup)
+//                      matrix.
+//   2. k_wg_scan     - exclusive scan along the matrix rows: every workgroup's
+//                      run start inside every bucket, and the bucket sizes.
+//      k_bucket_scan - exclusive scan of the <= 4096 bucket sizes per kind.
+//   3. k_fwd_scatter - every workgroup writes its (target, source) edges into
+//                      its runs, ranked by LDS atomics.
 //   4. k_bucket_csr  - one workgroup per bucket: LDS counters per target,
 //                      block scan = the targets' segment offsets, second sweep
 //                      places the sources.  Buckets are in target order, so the
 //                      result is the same CSR a global scan would give.
+// The loops over rows and edges keep several independent loads in flight per
+// thread; with one load per trip they are bound by memory latency.
 #include "device_utils.hpp"
 #include "kernels.hpp"
 
@@ -35,9 +38,9 @@ struct BucketGeom {
 // (or -1) for each kind and writes the forward parts of the sample rows.
 __device__ inline void forward_sample_row(int64_t s, int64_t n, int k, int p, uint64_t* G,
                                           int32_t* snew, int32_t* sold, int32_t* cnew,
-                                          int32_t* cold, int lane, int32_t& v_new,
+                                          int32_t* cold, int lane, uint64_t e, int32_t& v_new,
                                           int32_t& v_old) {
-  uint64_t e = lane < k ? G[s * k + lane] : 0ull;
+  // e = this lane's entry of the row (lanes >= k: anything)
   // entries numbered beyond n are frozen leftovers of an earlier merge: not sampled
   const bool valid = lane < k && (int64_t)entry_id(e) < n;
   const bool isnew = valid && (e & 1ull);
@@ -69,26 +72,70 @@ __device__ inline void forward_sample_row(int64_t s, int64_t n, int k, int p, ui
 __global__ __launch_bounds__(kSB) void k_fwd_count(int64_t n, int k, int p, BucketGeom g,
                                                    uint64_t* G, int32_t* snew, int32_t* sold,
                                                    int32_t* cnew, int32_t* cold,
-                                                   uint32_t* bcnt, uint32_t* wg_hist) {
+                                                   uint32_t* wg_hist) {
   __shared__ uint32_t hist[2 * kMaxBuckets];
   for (int i = threadIdx.x; i < 2 * g.nb; i += kSB) hist[i] = 0;
   __syncthreads();
   const int lane = lane_id(), wave = threadIdx.x >> 6;
   const int64_t row0 = (int64_t)blockIdx.x * g.rows_per_wg;
   const int64_t row1 = row0 + g.rows_per_wg < n ? row0 + g.rows_per_wg : n;
-  for (int64_t s = row0 + wave; s < row1; s += kSB / kWave) {
-    int32_t vn, vo;
-    forward_sample_row(s, n, k, p, G, snew, sold, cnew, cold, lane, vn, vo);
-    if (vn >= 0) atomicAdd(&hist[vn >> g.tb], 1u);
-    if (vo >= 0) atomicAdd(&hist[g.nb + (vo >> g.tb)], 1u);
+  constexpr int kRowsAtOnce = 4;  // rows in flight per wavefront
+  constexpr int kStep = kRowsAtOnce * (kSB / kWave);
+  for (int64_t s0 = row0 + wave; s0 < row1; s0 += kStep) {
+    uint64_t e[kRowsAtOnce];
+#pragma unroll
+    for (int r = 0; r < kRowsAtOnce; ++r) {
+      const int64_t s = s0 + r * (kSB / kWave);
+      e[r] = (s < row1 && lane < k) ? G[s * k + lane] : 0ull;
+    }
+#pragma unroll
+    for (int r = 0; r < kRowsAtOnce; ++r) {
+      const int64_t s = s0 + r * (kSB / kWave);
+      if (s >= row1) break;
+      int32_t vn, vo;
+      forward_sample_row(s, n, k, p, G, snew, sold, cnew, cold, lane, e[r], vn, vo);
+      if (vn >= 0) atomicAdd(&hist[vn >> g.tb], 1u);
+      if (vo >= 0) atomicAdd(&hist[g.nb + (vo >> g.tb)], 1u);
+    }
   }
   __syncthreads();
-  uint32_t* mine = wg_hist + (size_t)blockIdx.x * 2 * g.nb;  // read back by the scatter pass
-  for (int i = threadIdx.x; i < 2 * g.nb; i += kSB) {
-    const uint32_t c = hist[i];
-    mine[i] = c;
-    if (c) atomicAdd(&bcnt[i], c);
+  // column blockIdx.x of the (bucket x workgroup) count matrix
+  for (int i = threadIdx.x; i < 2 * g.nb; i += kSB) wg_hist[(size_t)i * gridDim.x + blockIdx.x] = hist[i];
+}
+
+// Exclusive scan along every row of the (bucket x workgroup) count matrix: the
+// entry of workgroup w becomes the start of w's run inside the bucket, the row
+// total the bucket's size.  One wavefront per row - no atomics, and the edge
+// order inside a bucket no longer depends on timing.
+__global__ __launch_bounds__(kSB) void k_wg_scan(int W, int rows, uint32_t* wg_hist,
+                                                 uint32_t* bcnt) {
+  const int c = blockIdx.x * (kSB / kWave) + (threadIdx.x >> 6);
+  if (c >= rows) return;
+  const int lane = lane_id();
+  uint32_t* row = wg_hist + (size_t)c * W;
+  constexpr int kChunks = 4;  // chunks of 64 entries in flight
+  uint32_t carry = 0;
+  for (int w0 = 0; w0 < W; w0 += kChunks * kWave) {
+    uint32_t v[kChunks];
+#pragma unroll
+    for (int r = 0; r < kChunks; ++r) {
+      const int w = w0 + r * kWave + lane;
+      v[r] = w < W ? row[w] : 0u;
+    }
+#pragma unroll
+    for (int r = 0; r < kChunks; ++r) {
+      const int w = w0 + r * kWave + lane;
+      uint32_t inc = v[r];
+#pragma unroll
+      for (int off = 1; off < kWave; off <<= 1) {
+        const uint32_t o = __shfl_up(inc, off, kWave);
+        if (lane >= off) inc += o;
+      }
+      if (w < W) row[w] = carry + inc - v[r];
+      carry += __shfl(inc, kWave - 1, kWave);
+    }
   }
+  if (lane == 0) bcnt[c] = carry;
 }
 
 // boff[kind][0..nb] = exclusive scan of bcnt[kind][0..nb); the counters become
@@ -128,20 +175,17 @@ __global__ __launch_bounds__(kCsrBlock) void k_bucket_scan(int nb, uint32_t* bcn
 __global__ __launch_bounds__(kSB) void k_fwd_scatter(int64_t n, int p, BucketGeom g,
                                                      const int32_t* snew, const int32_t* sold,
                                                      const uint32_t* wg_hist,
-                                                     const uint64_t* boff, uint32_t* bcur,
+                                                     const uint64_t* boff,
                                                      uint2* edges_new, uint2* edges_old) {
   __shared__ uint32_t hist[2 * kMaxBuckets];  // this workgroup's write cursors, per bucket
-  const uint32_t* mine = wg_hist + (size_t)blockIdx.x * 2 * g.nb;
-  for (int i = threadIdx.x; i < 2 * g.nb; i += kSB) {
-    const uint32_t c = mine[i];
-    hist[i] = c ? atomicAdd(&bcur[i], c) : 0u;  // start of this workgroup's run in the bucket
-  }
+  for (int i = threadIdx.x; i < 2 * g.nb; i += kSB)
+    hist[i] = wg_hist[(size_t)i * gridDim.x + blockIdx.x];  // start of its run in the bucket
   __syncthreads();
   const int lane = lane_id(), wave = threadIdx.x >> 6;
   const int L = 2 * p;
   const int64_t row0 = (int64_t)blockIdx.x * g.rows_per_wg;
   const int64_t row1 = row0 + g.rows_per_wg < n ? row0 + g.rows_per_wg : n;
-  constexpr int kRowsAtOnce = 4;  // rows in flight per wavefront
+  constexpr int kRowsAtOnce = 8;  // rows in flight per wavefront
   constexpr int kStep = kRowsAtOnce * (kSB / kWave);
   for (int64_t s0 = row0 + wave; s0 < row1; s0 += kStep) {
     int32_t vn[kRowsAtOnce], vo[kRowsAtOnce];
@@ -192,7 +236,7 @@ __global__ __launch_bounds__(kCsrBlock) void k_bucket_csr(int64_t n, BucketGeom 
   const uint32_t mask = (uint32_t)T - 1u;
   for (int i = threadIdx.x; i < T; i += kCsrBlock) cnt[i] = 0;
   __syncthreads();
-  constexpr int kAtOnce = 4;  // edges in flight per thread
+  constexpr int kAtOnce = 8;  // edges in flight per thread
   for (uint64_t e0 = beg + threadIdx.x; e0 < end; e0 += kAtOnce * kCsrBlock) {
     uint32_t t[kAtOnce];
 #pragma unroll
@@ -259,11 +303,11 @@ __global__ __launch_bounds__(kCsrBlock) void k_bucket_csr(int64_t n, BucketGeom 
 // The bucket layout for n targets, or tb = 0 when n is beyond what one
 // workgroup's LDS can count (then the caller uses per-edge atomics instead).
 static BucketGeom bucket_geom(int64_t n) {
-  BucketGeom g{12, 0, 256};
+  BucketGeom g{10, 0, 256};
   while (((n + (1ll << g.tb) - 1) >> g.tb) > kMaxBuckets) ++g.tb;
   if (g.tb > 15) return BucketGeom{0, 0, 0};
   g.nb = (int)((n + (1ll << g.tb) - 1) >> g.tb);
-  g.rows_per_wg = g.nb / 4 > 256 ? g.nb / 4 : 256;
+  g.rows_per_wg = g.nb > 256 ? g.nb : 256;
   return g;
 }
 
@@ -286,9 +330,11 @@ hipError_t launch_sample_buckets(const Shape& sh, const DevState& ds, hipStream_
   uint32_t* wg_hist = reinterpret_cast<uint32_t*>(edges_old + sh.n * sh.p);
   const unsigned grid = (unsigned)((sh.n + g.rows_per_wg - 1) / g.rows_per_wg);
   k_fwd_count<<<grid, kSB, 0, st>>>(sh.n, sh.k, sh.p, g, ds.G, ds.snew, ds.sold, ds.cnew, ds.cold,
-                                    bcnt, wg_hist);
+                                    wg_hist);
+  k_wg_scan<<<(unsigned)((2 * g.nb + kSB / kWave - 1) / (kSB / kWave)), kSB, 0, st>>>(
+      (int)grid, 2 * g.nb, wg_hist, bcnt);
   k_bucket_scan<<<1, kCsrBlock, 0, st>>>(g.nb, bcnt, boff);
-  k_fwd_scatter<<<grid, kSB, 0, st>>>(sh.n, sh.p, g, ds.snew, ds.sold, wg_hist, boff, bcnt,
+  k_fwd_scatter<<<grid, kSB, 0, st>>>(sh.n, sh.p, g, ds.snew, ds.sold, wg_hist, boff,
                                       edges_new, edges_old);
   k_bucket_csr<<<dim3((unsigned)g.nb, 2), kCsrBlock, (size_t)4 << g.tb, st>>>(
       sh.n, g, boff, bcnt, edges_new, edges_old, ds.roff_new, ds.roff_old, ds.csr_new,
