@@ -177,9 +177,13 @@ __global__ __launch_bounds__(kSB) void k_fwd_scatter(int64_t n, int p, BucketGeo
                                                      const uint32_t* wg_hist,
                                                      const uint64_t* boff,
                                                      uint2* edges_new, uint2* edges_old) {
-  __shared__ uint32_t hist[2 * kMaxBuckets];  // this workgroup's write cursors, per bucket
-  for (int i = threadIdx.x; i < 2 * g.nb; i += kSB)
-    hist[i] = wg_hist[(size_t)i * gridDim.x + blockIdx.x];  // start of its run in the bucket
+  // this workgroup's write cursors, per bucket: bucket start + start of its run in the
+  // bucket (positions fit 32 bits: at most n * p <= 2^32 edges per kind on this path)
+  __shared__ uint32_t hist[2 * kMaxBuckets];
+  for (int i = threadIdx.x; i < 2 * g.nb; i += kSB) {
+    const uint64_t bucket_start = i < g.nb ? boff[i] : boff[i + 1];  // second kind: nb + 1 offsets in
+    hist[i] = (uint32_t)bucket_start + wg_hist[(size_t)i * gridDim.x + blockIdx.x];
+  }
   __syncthreads();
   const int lane = lane_id(), wave = threadIdx.x >> 6;
   const int L = 2 * p;
@@ -203,13 +207,13 @@ __global__ __launch_bounds__(kSB) void k_fwd_scatter(int64_t n, int p, BucketGeo
         const uint32_t v = (uint32_t)vn[r];
         const uint32_t b = v >> g.tb;
         const uint32_t pos = atomicAdd(&hist[b], 1u);
-        edges_new[boff[b] + pos] = make_uint2(v, (uint32_t)s);
+        edges_new[pos] = make_uint2(v, (uint32_t)s);
       }
       if (vo[r] >= 0) {
         const uint32_t v = (uint32_t)vo[r];
         const uint32_t b = v >> g.tb;
         const uint32_t pos = atomicAdd(&hist[g.nb + b], 1u);
-        edges_old[boff[g.nb + 1 + b] + pos] = make_uint2(v, (uint32_t)s);
+        edges_old[pos] = make_uint2(v, (uint32_t)s);
       }
     }
   }
