@@ -79,6 +79,58 @@ __device__ inline T vmin(T a, T b) { return a < b ? a : b; }
 template <typename T>
 __device__ inline T vmax(T a, T b) { return a < b ? b : a; }
 
+// Value of lane (lane ^ j), j a power of two, without going through LDS: data
+// parallel primitives inside a row of 16 lanes (quad permutes, row shifts under
+// bank masks, row rotate) and the row / half swaps across rows.  `j` must be a
+// compile-time constant after unrolling.
+__device__ inline uint32_t xor_lanes(uint32_t v, int j, int lane) {
+  switch (j) {
+    case 1: return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0xB1, 0xF, 0xF, true);  // quad_perm:[1,0,3,2]
+    case 2: return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x4E, 0xF, 0xF, true);  // quad_perm:[2,3,0,1]
+    case 4: {
+      // lanes 0-3 and 8-11 of a row read 4 lanes up (row_shl:4), the others 4 lanes down (row_shr:4)
+      int r = __builtin_amdgcn_update_dpp(0, (int)v, 0x104, 0xF, 0x5, false);
+      r = __builtin_amdgcn_update_dpp(r, (int)v, 0x114, 0xF, 0xA, false);
+      return (uint32_t)r;
+    }
+    case 8: return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x128, 0xF, 0xF, true);  // row_ror:8
+    case 16: {
+      // rows 1 and 3 of the first copy change places with rows 0 and 2 of the second
+      auto sw = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+      return (lane & 16) ? sw[0] : sw[1];
+    }
+    default: {
+      // the upper half of the first copy changes places with the lower half of the second
+      auto sw = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+      return (lane & 32) ? sw[0] : sw[1];
+    }
+  }
+}
+__device__ inline uint64_t xor_lanes(uint64_t v, int j, int lane) {
+  const uint32_t lo = xor_lanes((uint32_t)v, j, lane);
+  const uint32_t hi = xor_lanes((uint32_t)(v >> 32), j, lane);
+  return ((uint64_t)hi << 32) | lo;
+}
+
+// Value of lane 63 - lane: mirror inside the row, then swap rows and halves.
+__device__ inline uint32_t reverse_lanes(uint32_t v, int lane) {
+  const uint32_t m = (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x140, 0xF, 0xF, true);  // row_mirror
+  return xor_lanes(xor_lanes(m, 16, lane), 32, lane);
+}
+__device__ inline uint64_t reverse_lanes(uint64_t v, int lane) {
+  const uint32_t lo = reverse_lanes((uint32_t)v, lane);
+  const uint32_t hi = reverse_lanes((uint32_t)(v >> 32), lane);
+  return ((uint64_t)hi << 32) | lo;
+}
+
+// One compare-exchange of a sorting network: this lane keeps the smaller of
+// its value and its partner's when keep_min, else the larger.  (Equal values:
+// either.)  One comparison; the lane pattern keep_min folds into the mask.
+template <typename T>
+__device__ inline T exchange(T v, T o, bool keep_min) {
+  return ((o < v) == keep_min) ? o : v;
+}
+
 // Full ascending sort of 64 lane values (bitonic network, 21 exchange stages).
 template <typename T>
 __device__ inline T wave_sort(T v, int lane) {
@@ -86,9 +138,8 @@ __device__ inline T wave_sort(T v, int lane) {
   for (int k = 2; k <= kWave; k <<= 1) {
 #pragma unroll
     for (int j = k >> 1; j > 0; j >>= 1) {
-      T o = __shfl_xor(v, j, kWave);
-      bool keep_min = (((lane & j) == 0) == ((lane & k) == 0));
-      v = keep_min ? vmin(v, o) : vmax(v, o);
+      const T o = xor_lanes(v, j, lane);
+      v = exchange(v, o, ((lane & j) == 0) == ((lane & k) == 0));
     }
   }
   return v;
@@ -103,9 +154,8 @@ __device__ inline T wave_sort_first(T v, int lane) {
   for (int k = 2; k <= N; k <<= 1) {
 #pragma unroll
     for (int j = k >> 1; j > 0; j >>= 1) {
-      T o = __shfl_xor(v, j, kWave);
-      bool keep_min = (((lane & j) == 0) == ((lane & k) == 0));
-      v = keep_min ? vmin(v, o) : vmax(v, o);
+      const T o = xor_lanes(v, j, lane);
+      v = exchange(v, o, ((lane & j) == 0) == ((lane & k) == 0));
     }
   }
   return v;
@@ -127,8 +177,8 @@ template <typename T>
 __device__ inline T wave_bitonic_merge(T v, int lane) {
 #pragma unroll
   for (int j = kWave >> 1; j > 0; j >>= 1) {
-    T o = __shfl_xor(v, j, kWave);
-    v = ((lane & j) == 0) ? vmin(v, o) : vmax(v, o);
+    const T o = xor_lanes(v, j, lane);
+    v = exchange(v, o, (lane & j) == 0);
   }
   return v;
 }
@@ -136,7 +186,7 @@ __device__ inline T wave_bitonic_merge(T v, int lane) {
 // The 64 smallest of two ascending 64-lane sequences, ascending.
 template <typename T>
 __device__ inline T wave_merge_smallest(T a_sorted, T b_sorted, int lane) {
-  T br = __shfl(b_sorted, kWave - 1 - lane, kWave);
+  const T br = reverse_lanes(b_sorted, lane);
   return wave_bitonic_merge(vmin(a_sorted, br), lane);
 }
 
