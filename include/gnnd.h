@@ -190,6 +190,20 @@ int gnnd_merge(const gnnd_params* prm, const void* vec1_dev, int64_t n1, int64_t
                const void* dist2_dev, int32_t iters, int32_t* ids_out_dev, void* dist_out_dev,
                gnnd_iter_stats* stats_host);
 
+/* Incremental construction (Sec. 5.1, its remark on data that arrive later): a
+ * batch S2 of n2 new vectors (vec2_dev) joins the collection S1 of n1 vectors
+ * (vec1_dev) whose graph G1 (ids1_dev, dist1_dev: n1*k, ids 0..n1-1) exists.
+ * GNND first builds the sub-graph of S2 on its own (random initial graph and
+ * build_iters iterations, with seed + 1), then GGM joins it into G1
+ * (gnnd_merge with base1 = 0, base2 = n1, id_space = n, merge_iters iterations,
+ * with seed).  prm->n = n1 + n2; the workspace for prm serves both steps.
+ * Output as gnnd_merge: n*k entries, rows 0..n1-1 = S1 then S2, ids 0..n-1
+ * with the new objects numbered n1..n-1.  Both sets need more than k objects.
+ * Enqueues on prm->stream and returns without synchronising. */
+int gnnd_append(const gnnd_params* prm, const void* vec1_dev, int64_t n1, const int32_t* ids1_dev,
+                const void* dist1_dev, const void* vec2_dev, int64_t n2, int32_t build_iters,
+                int32_t merge_iters, int32_t* ids_out_dev, void* dist_out_dev);
+
 /* Out-of-core construction (Sec. 5.1) on one GPU.  The collection of prm->n
  * vectors stays in pinned host memory (vectors_host, n*d elements); it is cut
  * into `shards` shards of floor(n/shards) consecutive rows (the last takes the

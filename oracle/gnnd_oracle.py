@@ -244,6 +244,17 @@ def merge(vectors, n1, k, p, metric, seed, g1, g2, iters, base1=0, base2=None):
     return g, stats
 
 
+def append(vectors, n1, g1, k, p, metric, seed, build_iters, merge_iters):
+    """Incremental construction (Sec. 5.1): rows n1.. of `vectors` are a batch
+    that joins the collection of rows 0..n1-1 with graph g1.  The batch's own
+    graph is built first (Alg. 1, seed + 1), then merged into g1 (Alg. 3, seed).
+    Returns the graph of the union in ids 0..n-1."""
+    sub, _ = build(np.ascontiguousarray(vectors[n1:]), k, p, metric, seed + 1, build_iters)
+    g2 = Graph(sub.ids + np.int32(n1), sub.dist, sub.isnew)
+    g, _ = merge(vectors, n1, k, p, metric, seed, g1, g2, merge_iters)
+    return g
+
+
 def pair_schedule(shards):
     """Every pair of shards once ("any two sub-graphs has been merged once",
     Sec. 5.1), as a round-robin tournament: rounds of disjoint pairs, the last

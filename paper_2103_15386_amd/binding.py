@@ -20,7 +20,7 @@ EXPORTS = [
     "gnnd_iterate", "gnnd_step_sample", "gnnd_step_join", "gnnd_step_update", "gnnd_build",
     "gnnd_get_graph", "gnnd_set_graph", "gnnd_get_samples", "gnnd_get_proposals", "gnnd_merge",
     "gnnd_exact_knn", "gnnd_join_path", "gnnd_set_profiling", "gnnd_get_stage_ms",
-    "gnnd_sharded_arena_bytes", "gnnd_build_sharded",
+    "gnnd_sharded_arena_bytes", "gnnd_build_sharded", "gnnd_append",
 ]
 
 
@@ -96,6 +96,8 @@ def load_library():
     lib.gnnd_get_proposals.argtypes = [vp, vp, vp, vp]
     lib.gnnd_merge.restype = C.c_int
     lib.gnnd_merge.argtypes = [PP, vp, i64, i64, vp, i64, i64, i64, vp, vp, vp, vp, i32, vp, vp, SP]
+    lib.gnnd_append.restype = C.c_int
+    lib.gnnd_append.argtypes = [PP, vp, i64, vp, vp, vp, i64, i32, i32, vp, vp]
     lib.gnnd_sharded_arena_bytes.restype = C.c_size_t
     lib.gnnd_sharded_arena_bytes.argtypes = [PP, i32]
     lib.gnnd_build_sharded.restype = C.c_int
@@ -316,6 +318,32 @@ def gnnd_merge(vec1, vec2, ids1, dist1, ids2, dist2, k, p, metric=L2SQ_F32, seed
     torch.cuda.current_stream(dev).synchronize()  # the workspace dies with this frame
     if want_stats:
         return ids, dist, [stats[i].as_dict() for i in range(iters)]
+    return ids, dist
+
+
+def gnnd_append(vec1, ids1, dist1, vec2, k, p, metric=L2SQ_F32, seed=42, build_iters=8,
+                merge_iters=6, join_path=JOIN_AUTO):
+    """Incremental construction: the batch vec2 joins the collection vec1 whose
+    graph is (ids1, dist1); returns (ids, dist) of the union, rows of vec1 first,
+    the new objects numbered n1.."""
+    lib = load_library()
+    et, dt = _elem_dtype(metric), _dist_dtype(metric)
+    _require_device(vec1, et, "vec1")
+    _require_device(vec2, et, "vec2")
+    _require_device(ids1, torch.int32, "ids1")
+    _require_device(dist1, dt, "dist1")
+    n1, d = vec1.shape
+    n2 = vec2.shape[0]
+    n = n1 + n2
+    dev = vec1.device
+    ws = torch.empty(max(workspace_bytes(n, d, k, p, metric), 256), dtype=torch.uint8, device=dev)
+    prm = make_params(n, d, k, p, metric, seed, join_path, _stream_ptr(dev), ws)
+    ids = torch.empty((n, k), dtype=torch.int32, device=dev)
+    dist = torch.empty((n, k), dtype=dt, device=dev)
+    _check(lib.gnnd_append(C.byref(prm), vec1.data_ptr(), n1, ids1.data_ptr(), dist1.data_ptr(),
+                           vec2.data_ptr(), n2, build_iters, merge_iters, ids.data_ptr(),
+                           dist.data_ptr()))
+    torch.cuda.current_stream(dev).synchronize()  # the workspace dies with this frame
     return ids, dist
 
 

@@ -778,6 +778,41 @@ int gnnd_merge(const gnnd_params* prm, const void* vec1, int64_t n1, int64_t bas
                     iters, ids_out, dist_out, stats);
 }
 
+int gnnd_append(const gnnd_params* prm, const void* vec1, int64_t n1, const int32_t* ids1,
+                const void* dist1, const void* vec2, int64_t n2, int32_t build_iters,
+                int32_t merge_iters, int32_t* ids_out, void* dist_out) {
+  if (const char* m = check_params(prm)) return fail(nullptr, GNND_EINVAL, m);
+  if (n1 <= 0 || n2 <= 0 || n1 + n2 != prm->n)
+    return fail(nullptr, GNND_EINVAL, "n1 + n2 must equal params.n, both positive");
+  if (n1 <= prm->k || n2 <= prm->k)
+    return fail(nullptr, GNND_EINVAL, "each set needs more than k objects");
+  if (build_iters < 0 || merge_iters < 0)
+    return fail(nullptr, GNND_EINVAL, "negative iteration count");
+  if (!vec1 || !vec2 || !ids1 || !dist1 || !ids_out || !dist_out)
+    return fail(nullptr, GNND_EINVAL, "NULL pointer argument");
+  // sub-graph of the batch, written where the merge will read it: the last n2 rows of the output
+  gnnd_params sub = *prm;
+  sub.n = n2;
+  sub.seed = prm->seed + 1;
+  gnnd_ctx* c = nullptr;
+  int rc = create_impl(&c, &sub, vec2, nullptr, n2, false);
+  if (rc != GNND_OK) return rc;
+  rc = gnnd_build(c, build_iters, 0.f, nullptr);
+  int32_t* ids2 = ids_out + n1 * prm->k;
+  void* dist2 = static_cast<char*>(dist_out) + (size_t)n1 * prm->k * 4;
+  if (rc == GNND_OK) {
+    hipError_t e = launch_get_graph(c->sh, c->ds, ids2, dist2, nullptr, (int32_t)n1, c->stream);
+    if (e != hipSuccess) rc = hip_fail(nullptr, e, "get_graph kernel");
+  } else {
+    g_last_error = c->err;
+  }
+  gnnd_destroy(c);
+  if (rc != GNND_OK) return rc;
+  // the merge reads ids2/dist2 in its first kernel and writes the output in its last
+  return merge_impl(prm, vec1, n1, 0, vec2, n2, n1, prm->n, ids1, dist1, ids2, dist2, merge_iters,
+                    ids_out, dist_out, nullptr);
+}
+
 size_t gnnd_sharded_arena_bytes(const gnnd_params* prm, int32_t shards) {
   ShardPlan pl;
   if (plan_shards(prm, shards, &pl)) return 0;

@@ -107,3 +107,29 @@ def test_sharded_build_matches_oracle(metric, gen, shards, n):
     ti, td = og.bruteforce(x, metric, q, 10)
     rec, _ = og.recall_at(want.ids[q], want.dist[q], ti, td, 10)
     assert rec > 0.85, rec
+
+
+@pytest.mark.parametrize("metric,gen,n1,n2", [
+    (og.L2SQ_F32, lambda n: W.uniform_f32(n, 12, seed=304), 1300, 700),
+    (og.L2SQ_U8, lambda n: W.sift_like_u8(n, 128, seed=305, n_comp=8), 900, 1100),
+])
+def test_append_matches_oracle(metric, gen, n1, n2):
+    import paper_2103_15386_amd as amd
+    k, p = 12, 12
+    x = gen(n1 + n2)
+    g1 = _exact(x[:n1], metric, k)
+    want = og.append(x, n1, g1, k, p, metric, SEED, 5, 4)
+    dt = np.int32 if metric == og.L2SQ_U8 else np.float32
+    ids, dist = amd.gnnd_append(_dev(x[:n1]), _dev(g1.ids), _dev(g1.dist.astype(dt)),
+                                _dev(x[n1:]), k, p, metric, SEED, 5, 4)
+    assert (ids.cpu().numpy() == want.ids).all()
+    assert (dist.cpu().numpy().astype(np.float64) == want.dist).all()
+
+
+def test_append_rejects_a_batch_smaller_than_k():
+    import paper_2103_15386_amd as amd
+    x = _dev(W.uniform_f32(60, 4, seed=2))
+    ids = torch.zeros((50, 16), dtype=torch.int32, device="cuda")
+    dist = torch.zeros((50, 16), dtype=torch.float32, device="cuda")
+    with pytest.raises(amd.GnndError):
+        amd.gnnd_append(x[:50].contiguous(), ids, dist, x[50:].contiguous(), 16, 8)

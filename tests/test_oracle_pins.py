@@ -623,3 +623,32 @@ def test_sharded_build_covers_the_whole_collection():
     # every shard's lists reach into the other shards
     own = (g.ids // (n // shards)) == (np.arange(n)[:, None] // (n // shards))
     assert 0.1 < own.mean() < 0.6
+
+
+def test_append_is_a_sub_build_followed_by_a_merge_and_lifts_recall():
+    # Incremental construction (Sec. 5.1): the batch's sub-graph is built on the
+    # batch alone, with ids of its own, and only then joined to the resident
+    # graph.  Pins: (a) the result equals the two documented steps done by hand;
+    # (b) rows of the resident collection can only improve, rank by rank;
+    # (c) the appended graph is close to the exact graph of the union and far
+    # better than the two separate graphs are for the union.
+    k, p, n1, n2, seed = 10, 10, 160, 120, 21
+    x = W.uniform_f32(n1 + n2, 6, seed=75)
+    g1 = _exact_graph(x[:n1], og.L2SQ_F32, k)
+    g = og.append(x, n1, g1, k, p, og.L2SQ_F32, seed, 6, 6)
+    sub, _ = og.build(np.ascontiguousarray(x[n1:]), k, p, og.L2SQ_F32, seed + 1, 6)
+    assert sub.ids.min() >= 0 and sub.ids.max() < n2  # built on the batch alone
+    by_hand, _ = og.merge(x, n1, k, p, og.L2SQ_F32, seed,
+                          g1, og.Graph(sub.ids + np.int32(n1), sub.dist, sub.isnew), 6)
+    assert (g.ids == by_hand.ids).all() and (g.dist == by_hand.dist).all()
+    assert (g.dist[:n1] <= g1.dist).all()
+    q = np.arange(n1 + n2, dtype=np.int32)
+    ti, td = og.bruteforce(x, og.L2SQ_F32, q, k)
+    rec, _ = og.recall_at(g.ids, g.dist, ti, td, 10)
+    apart = np.concatenate([g1.ids, sub.ids + np.int32(n1)])
+    apart_d = np.concatenate([g1.dist, sub.dist])
+    rec0, _ = og.recall_at(apart, apart_d, ti, td, 10)
+    assert rec > 0.95 and rec0 < 0.8, (rec, rec0)
+    for s in range(n1 + n2):  # well formed lists in the ids of the union
+        row = g.ids[s].tolist()
+        assert len(set(row)) == k and s not in row and 0 <= min(row) and max(row) < n1 + n2
