@@ -32,7 +32,8 @@ inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 const char* check_params(const gnnd_params* q) {
   if (!q) return "params is NULL";
   if (q->metric < GNND_L2SQ_F32 || q->metric > GNND_L2SQ_U8) return "unknown metric";
-  if (q->k < 2 || q->k > 64) return "k must be in [2, 64]";
+  if (q->k < 2 || q->k > 128) return "k must be in [2, 128]";
+  if (q->k > 64 && q->n > ((int64_t)1 << 27)) return "k above 64 needs n <= 2^27";
   if (q->p < 1 || q->p > 32 || q->p > q->k) return "p must be in [1, min(k, 32)]";
   if (q->d < 1) return "d must be >= 1";
   if (q->metric == GNND_L2SQ_U8 && q->d > 32768) return "d must be <= 32768 for uint8 vectors";

@@ -551,6 +551,7 @@ hipError_t launch_zero_u32(uint32_t* p, size_t count, hipStream_t st) {
 
 hipError_t launch_init_random(const Shape& sh, const DevState& ds, uint64_t seed,
                               hipStream_t st) {
+  if (sh.k > kWave) return launch_init_random_wide(sh, ds, seed, st);
   const unsigned grid = blocks_for_waves(sh.n);
   const uint64_t base = hash_base(seed, kTagInit);
   switch (sh.metric) {
@@ -596,6 +597,7 @@ hipError_t launch_sample(const Shape& sh, const DevState& ds, uint64_t seed, uin
 }
 
 hipError_t launch_update(const Shape& sh, const DevState& ds, hipStream_t st) {
+  if (sh.k > kWave) return launch_update_wide(sh, ds, st);
   k_update<<<blocks_for_waves(sh.n), kBlock, 0, st>>>(sh.n, sh.k, ds.G, ds.meta, ds.pslot, ds.poff,
                                                       ds.bins, ds.counters);
   return hipGetLastError();
@@ -640,6 +642,7 @@ hipError_t launch_get_proposals(const Shape& sh, const DevState& ds, int32_t* u,
 hipError_t launch_merge_init(const Shape& sh, const DevState& ds, uint64_t seed,
                              const MergeIds& mi, const int32_t* ids1, const void* dist1,
                              const int32_t* ids2, const void* dist2, hipStream_t st) {
+  if (sh.k > kWave) return launch_merge_init_wide(sh, ds, seed, mi, ids1, dist1, ids2, dist2, st);
   const unsigned grid = blocks_for_waves(sh.n);
   const uint64_t base = hash_base(seed, kTagMerge);
   switch (sh.metric) {
@@ -661,6 +664,7 @@ hipError_t launch_merge_init(const Shape& sh, const DevState& ds, uint64_t seed,
 
 hipError_t launch_merge_final(const Shape& sh, const DevState& ds, const MergeIds& mi,
                               int32_t* ids_out, void* dist_out, hipStream_t st) {
+  if (sh.k > kWave) return launch_merge_final_wide(sh, ds, mi, ids_out, dist_out, st);
   const unsigned grid = blocks_for_waves(sh.n);
   if (sh.metric == kL2U8)
     k_merge_final<false><<<grid, kBlock, 0, st>>>(sh.n, mi, sh.k, ds.G, ds.aside, ids_out,

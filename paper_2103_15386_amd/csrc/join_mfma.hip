@@ -501,6 +501,8 @@ hipError_t launch_join_mfma(const Shape& sh, const DevState& ds, bool merge_mode
 
 hipError_t launch_init_random_i8(const Shape& sh, const DevState& ds, uint64_t seed,
                                  hipStream_t st) {
+  // long lists: the general kernel on the original vectors gives the same integers
+  if (sh.k > kWave) return launch_init_random_wide(sh, ds, seed, st);
   const int dpad = (sh.d + 31) & ~31;
   const unsigned grid = (unsigned)((sh.n + 3) / 4);
   const uint64_t base = hash_base(seed, kTagInit);

@@ -78,6 +78,10 @@ hipError_t launch_init_random_i8(const Shape& sh, const DevState& ds, uint64_t s
 bool sample_buckets_possible(int64_t n);
 hipError_t launch_sample_buckets(const Shape& sh, const DevState& ds, hipStream_t st);
 hipError_t launch_update(const Shape& sh, const DevState& ds, hipStream_t st);
+// lists of 65..128 entries (two per lane); the launchers above forward to these
+hipError_t launch_init_random_wide(const Shape& sh, const DevState& ds, uint64_t seed,
+                                   hipStream_t st);
+hipError_t launch_update_wide(const Shape& sh, const DevState& ds, hipStream_t st);
 hipError_t launch_get_graph(const Shape& sh, const DevState& ds, int32_t* ids, void* dist,
                             uint8_t* isnew, int32_t id_offset, hipStream_t st);
 hipError_t launch_set_graph(const Shape& sh, const DevState& ds, const int32_t* ids,
@@ -90,6 +94,11 @@ hipError_t launch_merge_init(const Shape& sh, const DevState& ds, uint64_t seed,
                              const int32_t* ids2, const void* dist2, hipStream_t st);
 hipError_t launch_merge_final(const Shape& sh, const DevState& ds, const MergeIds& mi,
                               int32_t* ids_out, void* dist_out, hipStream_t st);
+hipError_t launch_merge_init_wide(const Shape& sh, const DevState& ds, uint64_t seed,
+                                  const MergeIds& mi, const int32_t* ids1, const void* dist1,
+                                  const int32_t* ids2, const void* dist2, hipStream_t st);
+hipError_t launch_merge_final_wide(const Shape& sh, const DevState& ds, const MergeIds& mi,
+                                   int32_t* ids_out, void* dist_out, hipStream_t st);
 hipError_t launch_exact_knn(const void* vec, int64_t n, int32_t d, int32_t metric,
                             const int32_t* queries, int64_t nq, int32_t K, int32_t* ids_out,
                             void* dist_out, hipStream_t st);

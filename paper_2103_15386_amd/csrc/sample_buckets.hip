@@ -69,6 +69,51 @@ __device__ inline void forward_sample_row(int64_t s, int64_t n, int k, int p, ui
   }
 }
 
+// The same for a list of 65..128 entries, two per lane (e0 = entry lane, e1 =
+// entry lane + 64 or 0): ranks run through the first register, then the second.
+__device__ inline void forward_sample_row_wide(int64_t s, int64_t n, int k, int p, uint64_t* G,
+                                               int32_t* snew, int32_t* sold, int32_t* cnew,
+                                               int32_t* cold, int lane, uint64_t e0, uint64_t e1,
+                                               int32_t (&v_new)[2], int32_t (&v_old)[2]) {
+  const uint64_t e[2] = {e0, e1};
+  uint64_t mn[2], mo[2];
+  bool isnew[2], isold[2];
+#pragma unroll
+  for (int r = 0; r < 2; ++r) {
+    const bool valid = lane + r * kWave < k && (int64_t)entry_id(e[r]) < n;
+    isnew[r] = valid && (e[r] & 1ull);
+    isold[r] = valid && !(e[r] & 1ull);
+    mn[r] = __ballot(isnew[r]);
+    mo[r] = __ballot(isold[r]);
+  }
+  const int L = 2 * p;
+#pragma unroll
+  for (int r = 0; r < 2; ++r) {
+    const int rn = (r ? __popcll(mn[0]) : 0) + __popcll(mn[r] & lanes_below(lane));
+    const int ro = (r ? __popcll(mo[0]) : 0) + __popcll(mo[r] & lanes_below(lane));
+    const int32_t id = (int32_t)entry_id(e[r]);
+    v_new[r] = v_old[r] = -1;
+    if (isnew[r] && rn < p) {
+      snew[s * L + rn] = id;
+      G[s * k + r * kWave + lane] = e[r] & ~1ull;
+      v_new[r] = id;
+    }
+    if (isold[r] && ro < p) {
+      sold[s * L + ro] = id;
+      v_old[r] = id;
+    }
+  }
+  const int tn = __popcll(mn[0]) + __popcll(mn[1]), to = __popcll(mo[0]) + __popcll(mo[1]);
+  const int cn = tn < p ? tn : p, co = to < p ? to : p;
+  if (lane >= cn && lane < p) snew[s * L + lane] = -1;
+  if (lane >= co && lane < p) sold[s * L + lane] = -1;
+  if (lane == 0) {
+    cnew[s] = cn;
+    cold[s] = co;
+  }
+}
+
+template <bool WIDE>
 __global__ __launch_bounds__(kSB) void k_fwd_count(int64_t n, int k, int p, BucketGeom g,
                                                    uint64_t* G, int32_t* snew, int32_t* sold,
                                                    int32_t* cnew, int32_t* cold,
@@ -82,20 +127,31 @@ __global__ __launch_bounds__(kSB) void k_fwd_count(int64_t n, int k, int p, Buck
   constexpr int kRowsAtOnce = 4;  // rows in flight per wavefront
   constexpr int kStep = kRowsAtOnce * (kSB / kWave);
   for (int64_t s0 = row0 + wave; s0 < row1; s0 += kStep) {
-    uint64_t e[kRowsAtOnce];
+    uint64_t e[kRowsAtOnce], e1[kRowsAtOnce];
 #pragma unroll
     for (int r = 0; r < kRowsAtOnce; ++r) {
       const int64_t s = s0 + r * (kSB / kWave);
       e[r] = (s < row1 && lane < k) ? G[s * k + lane] : 0ull;
+      if (WIDE) e1[r] = (s < row1 && lane + kWave < k) ? G[s * k + kWave + lane] : 0ull;
     }
 #pragma unroll
     for (int r = 0; r < kRowsAtOnce; ++r) {
       const int64_t s = s0 + r * (kSB / kWave);
       if (s >= row1) break;
-      int32_t vn, vo;
-      forward_sample_row(s, n, k, p, G, snew, sold, cnew, cold, lane, e[r], vn, vo);
-      if (vn >= 0) atomicAdd(&hist[vn >> g.tb], 1u);
-      if (vo >= 0) atomicAdd(&hist[g.nb + (vo >> g.tb)], 1u);
+      if (WIDE) {
+        int32_t vn[2], vo[2];
+        forward_sample_row_wide(s, n, k, p, G, snew, sold, cnew, cold, lane, e[r], e1[r], vn, vo);
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+          if (vn[q] >= 0) atomicAdd(&hist[vn[q] >> g.tb], 1u);
+          if (vo[q] >= 0) atomicAdd(&hist[g.nb + (vo[q] >> g.tb)], 1u);
+        }
+      } else {
+        int32_t vn, vo;
+        forward_sample_row(s, n, k, p, G, snew, sold, cnew, cold, lane, e[r], vn, vo);
+        if (vn >= 0) atomicAdd(&hist[vn >> g.tb], 1u);
+        if (vo >= 0) atomicAdd(&hist[g.nb + (vo >> g.tb)], 1u);
+      }
     }
   }
   __syncthreads();
@@ -333,8 +389,12 @@ hipError_t launch_sample_buckets(const Shape& sh, const DevState& ds, hipStream_
   // per-workgroup bucket histograms, behind the edges in the same (still unused) array
   uint32_t* wg_hist = reinterpret_cast<uint32_t*>(edges_old + sh.n * sh.p);
   const unsigned grid = (unsigned)((sh.n + g.rows_per_wg - 1) / g.rows_per_wg);
-  k_fwd_count<<<grid, kSB, 0, st>>>(sh.n, sh.k, sh.p, g, ds.G, ds.snew, ds.sold, ds.cnew, ds.cold,
-                                    wg_hist);
+  if (sh.k > kWave)
+    k_fwd_count<true><<<grid, kSB, 0, st>>>(sh.n, sh.k, sh.p, g, ds.G, ds.snew, ds.sold, ds.cnew,
+                                            ds.cold, wg_hist);
+  else
+    k_fwd_count<false><<<grid, kSB, 0, st>>>(sh.n, sh.k, sh.p, g, ds.G, ds.snew, ds.sold, ds.cnew,
+                                             ds.cold, wg_hist);
   k_wg_scan<<<(unsigned)((2 * g.nb + kSB / kWave - 1) / (kSB / kWave)), kSB, 0, st>>>(
       (int)grid, 2 * g.nb, wg_hist, bcnt);
   k_bucket_scan<<<1, kCsrBlock, 0, st>>>(g.nb, bcnt, boff);

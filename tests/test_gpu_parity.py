@@ -49,6 +49,11 @@ CASES = {
                       og.L2SQ_F32, 16, 16, 4),
     "tiny_n": (lambda: W.uniform_f32(70, 7, seed=6), og.L2SQ_F32, 5, 3, 4),
     "u8_d30": (lambda: W.sift_like_u8(900, 30, seed=8, n_comp=4), og.L2SQ_U8, 12, 12, 4),
+    # lists longer than one wavefront (two entries per lane)
+    "k128_uniform": (lambda: W.uniform_f32(1800, 10, seed=1021), og.L2SQ_F32, 128, 32, 4),
+    "k100_angular": (lambda: W.deep_like_f32(1500, 48, seed=1022, n_comp=8),
+                     og.ANGULAR_F32, 100, 24, 4),
+    "k65_tiny": (lambda: W.uniform_f32(140, 6, seed=1023), og.L2SQ_F32, 65, 9, 3),
 }
 
 
@@ -63,7 +68,11 @@ def test_init_matches_oracle(name):
     ctx.close()
 
 
-MFMA_CASES = ["sift_cut", "u8_cut", "u8_d30", "sift_d100_k64", "u8_small_lists"]
+MFMA_CASES = ["sift_cut", "u8_cut", "u8_d30", "sift_d100_k64", "u8_small_lists", "u8_k96",
+              "sift_k128"]
+CASES["u8_k96"] = (lambda: W.sift_like_u8(1600, 96, seed=1024, n_comp=8), og.L2SQ_U8, 96, 32, 4)
+CASES["sift_k128"] = (lambda: W.sift_like_f32(1700, 128, seed=1025, n_comp=8),
+                      og.L2SQ_F32, 128, 20, 3)
 CASES["sift_d100_k64"] = (lambda: W.sift_like_f32(2000, 100, seed=1012, n_comp=8),
                           og.L2SQ_F32, 64, 32, 4)
 CASES["u8_small_lists"] = (lambda: W.sift_like_u8(1500, 64, seed=1013, n_comp=4),
