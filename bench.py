@@ -48,6 +48,9 @@ def parse():
     ap.add_argument("--target", type=float, default=0.95)
     ap.add_argument("--eval-nodes", type=int, default=2000)
     ap.add_argument("--join", choices=["auto", "valu", "mfma"], default="auto")
+    ap.add_argument("--update", choices=["selective", "all-pairs"], default="selective",
+                    help="all-pairs: the ablation variant that proposes every evaluated pair "
+                         "(runs with the valu join; ~100 KB of workspace per node at p = 32)")
     ap.add_argument("--cpu-sample-n", type=int, default=40_000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--workload", choices=["sift1m", "sharded"], default="sift1m")
@@ -152,7 +155,8 @@ def main():
     _, tdist = amd.exact_knn(xd, q, 10, amd.L2SQ_F32)
     ql = q.long()
 
-    ctx = amd.Gnnd(xd, args.k, args.p, amd.L2SQ_F32, seed, join_path)
+    update_mode = amd.UPDATE_ALL_PAIRS if args.update == "all-pairs" else amd.UPDATE_SELECTIVE
+    ctx = amd.Gnnd(xd, args.k, args.p, amd.L2SQ_F32, seed, join_path, update_mode)
 
     # calibration build (untimed): recall and per-stage times after every iteration
     ctx.init_random()
@@ -242,7 +246,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"sift-shaped GMM n={args.n} d={args.d} f32, k={args.k} "
                                f"p={args.p}, squared L2, random init + {T} iterations",
-                   "join_path": "mfma_i8" if mfma else "valu", "eval_nodes": args.eval_nodes},
+                   "join_path": "mfma_i8" if mfma else "valu", "update": args.update,
+                   "eval_nodes": args.eval_nodes},
         "reached_target": reached, "iterations": T, "recall_at_10": trace[T - 1]["recall_at_10"],
         "best_recall_at_10": best,
         "dist_evals": total_evals, "dist_evals_per_s": total_evals / build_s,

@@ -59,6 +59,16 @@ enum {
   GNND_JOIN_MFMA = 2  /* Gram-block form on the matrix cores (exact for uint8 data)  */
 };
 
+/* Which cross-matching results go to the list update. */
+enum {
+  GNND_UPDATE_SELECTIVE = 0, /* per sample only its nearest partners (Sec. 4.3, Alg. 2) */
+  GNND_UPDATE_ALL_PAIRS = 1  /* every evaluated pair, both ways: the variant the paper's
+                                ablation (Sec. 6.2) calls GNND-r1.  Same lists for a given
+                                set of proposals, many more proposals: the proposal array
+                                grows from 6p to 2p(6p - 1) slots per node, and the join
+                                runs in the GNND_JOIN_VALU form only                    */
+};
+
 typedef struct gnnd_params {
   int64_t n;      /* number of vectors, k < n <= 2^30                               */
   int32_t d;      /* dimension, >= 1 (float metrics: multiple of 4 reads fastest)   */
@@ -70,7 +80,7 @@ typedef struct gnnd_params {
   void* workspace_dev;    /* device scratch, 256-byte aligned, caller-owned         */
   size_t workspace_bytes; /* its size, >= gnnd_workspace_bytes()                    */
   int32_t join_path;      /* GNND_JOIN_*                                            */
-  int32_t reserved;       /* must be 0                                              */
+  int32_t update_mode;    /* GNND_UPDATE_*; 0 = the method as published             */
 } gnnd_params;
 
 /* Counters of one iteration.  ms_* are stream times from HIP events. */

@@ -463,6 +463,50 @@ uint64_t og_join(const void* vec, int64_t n, int d, int p, int metric, const int
   return evals;
 }
 
+/* The join without the selective update of Sec. 4.3 (the variant the ablation of
+ * Sec. 6.2 calls GNND-r1): the same pairs are evaluated, and every evaluated
+ * pair (a, b) is proposed both ways, b for the list of a and a for the list of
+ * b.  Output rows of 2p(6p - 1) slots per node: NEW x NEW gives nn(nn - 1)
+ * proposals, NEW x OLD 2 nn no, with nn, no <= 2p.  Returns the number of
+ * distances evaluated. */
+uint64_t og_join_all(const void* vec, int64_t n, int d, int p, int metric, const int32_t* snew,
+                     const int32_t* cnew, const int32_t* sold, const int32_t* cold, int64_t split,
+                     int32_t* pu, int32_t* pv, double* pd, int32_t* pcnt) {
+  const int L = 2 * p;
+  const int64_t P = (int64_t)L * (3 * L - 1);
+  uint64_t evals = 0;
+#pragma omp parallel for schedule(dynamic, 16) reduction(+ : evals)
+  for (int64_t s = 0; s < n; ++s) {
+    const int32_t* N = snew + s * L;
+    const int32_t* O = sold + s * L;
+    const int nn = cnew[s], no = cold[s];
+    int32_t* qu = pu + s * P;
+    int32_t* qv = pv + s * P;
+    double* qd = pd + s * P;
+    int m = 0;
+    if (split < 0) {
+      for (int a = 1; a < nn; ++a)
+        for (int b = 0; b < a; ++b) {
+          const double dist = og_distance(metric, d, vec, N[a], N[b]);
+          ++evals;
+          qu[m] = N[a]; qv[m] = N[b]; qd[m] = dist; ++m;
+          qu[m] = N[b]; qv[m] = N[a]; qd[m] = dist; ++m;
+        }
+    }
+    for (int a = 0; a < nn; ++a)
+      for (int b = 0; b < no; ++b) {
+        if (N[a] == O[b]) continue;
+        if (split >= 0 && ((N[a] < split) == (O[b] < split))) continue;
+        const double dist = og_distance(metric, d, vec, N[a], O[b]);
+        ++evals;
+        qu[m] = N[a]; qv[m] = O[b]; qd[m] = dist; ++m;
+        qu[m] = O[b]; qv[m] = N[a]; qd[m] = dist; ++m;
+      }
+    pcnt[s] = m;
+  }
+  return evals;
+}
+
 /* ------------------------------------------------------------------------- */
 /* InsertIntoNNList for one (v, d) into one sorted list of k entries
  * (Sec. 4.3): refused when v is already present or when (d, v) is not closer
@@ -495,9 +539,17 @@ int og_insert_one(int k, int32_t* ids, double* dist, uint8_t* isnew, int32_t v, 
  * flag; admitted ones are NEW (Sec. 4, "newly inserted ... marked as NEW").
  * Returns the number of admitted entries (list members that were not members
  * before). */
+uint64_t og_update_rows(int64_t n, int k, int P, int32_t* ids, double* dist, uint8_t* isnew,
+                        const int32_t* pu, const int32_t* pv, const double* pd,
+                        const int32_t* pcnt);
 uint64_t og_update(int64_t n, int k, int p, int32_t* ids, double* dist, uint8_t* isnew,
                    const int32_t* pu, const int32_t* pv, const double* pd, const int32_t* pcnt) {
-  const int P = 6 * p;
+  return og_update_rows(n, k, 6 * p, ids, dist, isnew, pu, pv, pd, pcnt);
+}
+/* The same with proposal rows of P slots per joined node. */
+uint64_t og_update_rows(int64_t n, int k, int P, int32_t* ids, double* dist, uint8_t* isnew,
+                        const int32_t* pu, const int32_t* pv, const double* pd,
+                        const int32_t* pcnt) {
   int64_t* off = (int64_t*)calloc((size_t)n + 1, sizeof(int64_t));
   for (int64_t s = 0; s < n; ++s)
     for (int j = 0; j < pcnt[s]; ++j) off[pu[s * P + j] + 1]++;

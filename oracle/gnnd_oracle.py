@@ -64,6 +64,11 @@ def _load():
                             C.c_int64, i32p, i32p, f64p, i32p]
     lib.og_insert_one.restype = C.c_int
     lib.og_insert_one.argtypes = [C.c_int, i32p, f64p, u8p, C.c_int32, C.c_double]
+    lib.og_join_all.restype = C.c_uint64
+    lib.og_join_all.argtypes = lib.og_join.argtypes
+    lib.og_update_rows.restype = C.c_uint64
+    lib.og_update_rows.argtypes = [C.c_int64, C.c_int, C.c_int, i32p, f64p, u8p, i32p, i32p, f64p,
+                                   i32p]
     lib.og_update.restype = C.c_uint64
     lib.og_update.argtypes = [C.c_int64, C.c_int, C.c_int, i32p, f64p, u8p, i32p, i32p, f64p,
                               i32p]
@@ -157,17 +162,20 @@ def sample(g, p, seed, it):
     return snew, cnew, sold, cold
 
 
-def join(vectors, metric, p, snew, cnew, sold, cold, split=-1):
+def join(vectors, metric, p, snew, cnew, sold, cold, split=-1, all_pairs=False):
     """Returns (pu, pv, pd, pcnt, dist_evals): proposals 'insert pv with distance
-    pd into the list of pu', up to 6p per joined node."""
+    pd into the list of pu', up to 6p per joined node (Alg. 2: nearest partners
+    only), or with all_pairs every evaluated pair both ways, up to 2p(6p - 1)
+    per node (the ablation variant without the selective update, Sec. 6.2)."""
     v = _vec(vectors, metric)
     n, d = v.shape
-    pu = np.full((n, 6 * p), -1, np.int32)
-    pv = np.full((n, 6 * p), -1, np.int32)
-    pd = np.full((n, 6 * p), np.inf, np.float64)
+    width = 2 * p * (6 * p - 1) if all_pairs else 6 * p
+    pu = np.full((n, width), -1, np.int32)
+    pv = np.full((n, width), -1, np.int32)
+    pd = np.full((n, width), np.inf, np.float64)
     pcnt = np.zeros(n, np.int32)
-    ev = _load().og_join(v.ctypes.data, n, d, p, metric, snew, cnew, sold, cold, split, pu, pv,
-                         pd, pcnt)
+    fn = _load().og_join_all if all_pairs else _load().og_join
+    ev = fn(v.ctypes.data, n, d, p, metric, snew, cnew, sold, cold, split, pu, pv, pd, pcnt)
     return pu, pv, pd, pcnt, int(ev)
 
 
@@ -177,26 +185,29 @@ def insert_one(ids_row, dist_row, isnew_row, v, d):
 
 def update(g, p, pu, pv, pd, pcnt):
     n, k = g.ids.shape
+    if pu.shape[1] != 6 * p:  # rows of the all-pairs join
+        return int(_load().og_update_rows(n, k, pu.shape[1], g.ids, g.dist, g.isnew, pu, pv, pd,
+                                          pcnt))
     return int(_load().og_update(n, k, p, g.ids, g.dist, g.isnew, pu, pv, pd, pcnt))
 
 
-def iterate(vectors, metric, g, p, seed, it, split=-1):
+def iterate(vectors, metric, g, p, seed, it, split=-1, all_pairs=False):
     """One GNND iteration (Alg. 1 loop body) in place; `it` counts from 1.
     Returns a dict of statistics and the intermediate sample lists/proposals."""
     snew, cnew, sold, cold = sample(g, p, seed, it)
-    pu, pv, pd, pcnt, ev = join(vectors, metric, p, snew, cnew, sold, cold, split)
+    pu, pv, pd, pcnt, ev = join(vectors, metric, p, snew, cnew, sold, cold, split, all_pairs)
     ins = update(g, p, pu, pv, pd, pcnt)
     return dict(iter=it, inserts=ins, dist_evals=ev, sum_new=int(cnew.sum()),
                 sum_old=int(cold.sum()), proposals=int(pcnt.sum()),
                 snew=snew, cnew=cnew, sold=sold, cold=cold)
 
 
-def build(vectors, k, p, metric, seed, iters):
+def build(vectors, k, p, metric, seed, iters, all_pairs=False):
     """Alg. 1 as a whole: random initial graph, then `iters` iterations."""
     g = init_random(vectors, k, metric, seed)
     stats = []
     for it in range(1, iters + 1):
-        st = iterate(vectors, metric, g, p, seed, it)
+        st = iterate(vectors, metric, g, p, seed, it, all_pairs=all_pairs)
         stats.append({key: st[key] for key in ("iter", "inserts", "dist_evals", "sum_new",
                                                "sum_old", "proposals")})
     return g, stats

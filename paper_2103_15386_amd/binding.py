@@ -9,6 +9,7 @@ import torch
 
 L2SQ_F32, ANGULAR_F32, L2SQ_U8 = 0, 1, 2
 JOIN_AUTO, JOIN_VALU, JOIN_MFMA = 0, 1, 2
+UPDATE_SELECTIVE, UPDATE_ALL_PAIRS = 0, 1
 OK, EINVAL, ENOSPC, ESTATE, EHIP = 0, -1, -2, -3, -4
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -34,7 +35,7 @@ class Params(C.Structure):
     _fields_ = [("n", C.c_int64), ("d", C.c_int32), ("k", C.c_int32), ("p", C.c_int32),
                 ("metric", C.c_int32), ("seed", C.c_uint64), ("stream", C.c_void_p),
                 ("workspace_dev", C.c_void_p), ("workspace_bytes", C.c_size_t),
-                ("join_path", C.c_int32), ("reserved", C.c_int32)]
+                ("join_path", C.c_int32), ("update_mode", C.c_int32)]
 
 
 class IterStats(C.Structure):
@@ -144,42 +145,46 @@ def _stream_ptr(device):
     return torch.cuda.current_stream(device).cuda_stream
 
 
-def make_params(n, d, k, p, metric, seed=42, join_path=JOIN_AUTO, stream=0, workspace=None):
+def make_params(n, d, k, p, metric, seed=42, join_path=JOIN_AUTO, stream=0, workspace=None,
+                update_mode=UPDATE_SELECTIVE):
     prm = Params()
     prm.n, prm.d, prm.k, prm.p, prm.metric = n, d, k, p, metric
     prm.seed = seed
     prm.stream = stream
     prm.join_path = join_path
-    prm.reserved = 0
+    prm.update_mode = update_mode
     if workspace is not None:
         prm.workspace_dev = workspace.data_ptr()
         prm.workspace_bytes = workspace.numel() * workspace.element_size()
     return prm
 
 
-def workspace_bytes(n, d, k, p, metric):
+def workspace_bytes(n, d, k, p, metric, update_mode=UPDATE_SELECTIVE):
     """Bytes of device scratch a context with these parameters needs (0 = invalid)."""
-    prm = make_params(n, d, k, p, metric)
+    prm = make_params(n, d, k, p, metric, update_mode=update_mode)
     return int(load_library().gnnd_workspace_bytes(C.byref(prm)))
 
 
 class Gnnd:
     """One GNND context over a resident vector tensor (n x d, float32 or uint8)."""
 
-    def __init__(self, vectors, k, p, metric=L2SQ_F32, seed=42, join_path=JOIN_AUTO):
+    def __init__(self, vectors, k, p, metric=L2SQ_F32, seed=42, join_path=JOIN_AUTO,
+                 update_mode=UPDATE_SELECTIVE):
         lib = load_library()
         self.vectors = _require_device(vectors, _elem_dtype(metric), "vectors")
         self.n, self.d = vectors.shape
         self.k, self.p, self.metric, self.seed = k, p, metric, seed
-        need = workspace_bytes(self.n, self.d, k, p, metric)
+        self.update_mode = update_mode
+        need = workspace_bytes(self.n, self.d, k, p, metric, update_mode)
         if need == 0:
-            prm = make_params(self.n, self.d, k, p, metric, seed, join_path)
+            prm = make_params(self.n, self.d, k, p, metric, seed, join_path,
+                              update_mode=update_mode)
             ctx = C.c_void_p()
             rc = lib.gnnd_create(C.byref(ctx), C.byref(prm), vectors.data_ptr())
             raise GnndError(rc, _err())
         self.workspace = torch.empty(need, dtype=torch.uint8, device=vectors.device)
         self.prm = make_params(self.n, self.d, k, p, metric, seed, join_path,
-                               _stream_ptr(vectors.device), self.workspace)
+                               _stream_ptr(vectors.device), self.workspace, update_mode)
         self._ctx = C.c_void_p()
         _check(lib.gnnd_create(C.byref(self._ctx), C.byref(self.prm), vectors.data_ptr()))
         self._lib = lib
@@ -260,7 +265,9 @@ class Gnnd:
 
     def proposals(self):
         dev = self.vectors.device
-        shape = (self.n, 6 * self.p)
+        per_node = 6 * self.p if self.update_mode == UPDATE_SELECTIVE \
+            else 2 * self.p * (6 * self.p - 1)
+        shape = (self.n, per_node)
         u = torch.empty(shape, dtype=torch.int32, device=dev)
         v = torch.empty(shape, dtype=torch.int32, device=dev)
         dist = torch.empty(shape, dtype=_dist_dtype(self.metric), device=dev)
@@ -278,9 +285,10 @@ def gnnd_iterate(ctx: Gnnd, want_stats=True):
     return ctx.iterate(want_stats)
 
 
-def gnnd_build(vectors, k, p, metric=L2SQ_F32, seed=42, iters=12, join_path=JOIN_AUTO):
+def gnnd_build(vectors, k, p, metric=L2SQ_F32, seed=42, iters=12, join_path=JOIN_AUTO,
+               update_mode=UPDATE_SELECTIVE):
     """Build a graph from scratch; returns (ids, dist, context)."""
-    ctx = Gnnd(vectors, k, p, metric, seed, join_path)
+    ctx = Gnnd(vectors, k, p, metric, seed, join_path, update_mode)
     ctx.build(iters, want_stats=False)
     ids, dist = ctx.graph()
     return ids, dist, ctx

@@ -41,14 +41,17 @@ const char* check_params(const gnnd_params* q) {
   if (q->n > ((int64_t)1 << 30)) return "n must be <= 2^30";
   if (q->n * (int64_t)q->p >= ((int64_t)1 << 32)) return "n * p must be below 2^32";
   if (q->join_path < GNND_JOIN_AUTO || q->join_path > GNND_JOIN_MFMA) return "unknown join_path";
-  if (q->reserved != 0) return "reserved must be 0";
+  if (q->update_mode != GNND_UPDATE_SELECTIVE && q->update_mode != GNND_UPDATE_ALL_PAIRS)
+    return "unknown update_mode";
+  if (q->update_mode == GNND_UPDATE_ALL_PAIRS && q->join_path == GNND_JOIN_MFMA)
+    return "GNND_UPDATE_ALL_PAIRS runs with GNND_JOIN_VALU (or GNND_JOIN_AUTO) only";
   return nullptr;
 }
 
 // The matrix-core join handles byte-valued data of up to 128 dimensions: uint8
 // vectors, or float32 vectors that turn out to hold only integers 0..255.
 bool mfma_possible(const gnnd_params* q) {
-  return q->join_path != GNND_JOIN_VALU && q->d <= 128 &&
+  return q->join_path != GNND_JOIN_VALU && q->update_mode == GNND_UPDATE_SELECTIVE && q->d <= 128 &&
          (q->metric == GNND_L2SQ_U8 || q->metric == GNND_L2SQ_F32);
 }
 
@@ -77,7 +80,9 @@ Layout make_layout(const gnnd_params* q, bool with_aside) {
   L.off_capo = take(n * 4);
   L.off_pcnt = take(n * 8);
   L.off_poff = take((n + 1) * 8);
-  L.off_bins = take(n * 6 * p * 8);
+  const size_t slots_per_node =
+      q->update_mode == GNND_UPDATE_ALL_PAIRS ? 2 * p * (6 * p - 1) : 6 * p;
+  L.off_bins = take(n * slots_per_node * 8);
   L.off_scan = take(scan_tmp_elems((int64_t)n) * 8);
   L.off_cnt = take((size_t)kStripes * C_SLOTS * 8);
   L.off_snap = take((size_t)kStripes * C_SLOTS * 8);
@@ -182,7 +187,8 @@ int create_impl(gnnd_ctx** out, const gnnd_params* prm, const void* vec_a, const
   if (!c) return fail(nullptr, GNND_EINVAL, "out of host memory");
   c->prm = *prm;
   c->stream = (hipStream_t)prm->stream;
-  c->sh = Shape{prm->n, prm->d, prm->k, prm->p, prm->metric, split, vec_a, vec_b};
+  c->sh = Shape{prm->n, prm->d, prm->k, prm->p, prm->metric, split, vec_a, vec_b,
+                prm->update_mode == GNND_UPDATE_ALL_PAIRS ? 1 : 0};
   c->iter = 0;
   c->stage = 0;
   c->has_graph = false;

@@ -165,6 +165,7 @@ __global__ __launch_bounds__(kBlock) void k_rev_select(int64_t n, int p, uint64_
                                                        const int32_t* csr_new,
                                                        const int32_t* csr_old,
                                                        uint32_t* capn, uint32_t* capo,
+                                                       uint32_t per_new, uint32_t per_old,
                                                        uint64_t* counters) {
   const int64_t v = wave_global_index();
   if (v >= n) return;
@@ -189,9 +190,10 @@ __global__ __launch_bounds__(kBlock) void k_rev_select(int64_t n, int p, uint64_
     // v can only sit in the sample list of a node that holds v as a forward
     // sample (deg of them) or that v holds as one (nf): that bounds the number
     // of joins v takes part in, hence the nearest-object results it can
-    // receive - two per join as a NEW sample, one as an OLD sample.
-    capn[v] = (uint32_t)(2 * (dn + (uint64_t)nfn));
-    capo[v] = (uint32_t)(dO + (uint64_t)nfo);
+    // receive - two per join as a NEW sample, one as an OLD sample (per_new, per_old;
+    // when every pair is proposed: one per possible partner).
+    capn[v] = (uint32_t)(per_new * (dn + (uint64_t)nfn));
+    capo[v] = (uint32_t)(per_old * (dO + (uint64_t)nfo));
   }
 }
 
@@ -591,7 +593,8 @@ hipError_t launch_sample(const Shape& sh, const DevState& ds, uint64_t seed, uin
   k_rev_select<<<grid, kBlock, 0, st>>>(
       sh.n, sh.p, hash_base(seed, kTagRevNew), hash_base(seed, kTagRevOld), iter, ds.snew,
       ds.sold, ds.cnew, ds.cold, ds.roff_new, ds.roff_old, ds.csr_new, ds.csr_old, ds.capn,
-      ds.capo, ds.counters);
+      ds.capo, (uint32_t)sh.slots_new_per_appearance(), (uint32_t)sh.slots_old_per_appearance(),
+      ds.counters);
   // one segment of the proposal array per destination, sized by its bound
   return launch_scan(ds.capn, ds.capo, ds.poff, ds.pslot, ds.counters, ds.scan_tmp, sh.n, st);
 }
@@ -632,7 +635,7 @@ hipError_t launch_get_proposals(const Shape& sh, const DevState& ds, int32_t* u,
     k_get_proposals<false><<<grid, kBlock, 0, st>>>(sh.n, ds.pslot, ds.poff, ds.bins, u, v, dist);
   else
     k_get_proposals<true><<<grid, kBlock, 0, st>>>(sh.n, ds.pslot, ds.poff, ds.bins, u, v, dist);
-  const int64_t slots = sh.n * 6 * sh.p;
+  const int64_t slots = sh.slots();
   const unsigned g2 = (unsigned)((slots + kBlock - 1) / kBlock);
   k_fill_i32<<<g2, kBlock, 0, st>>>(u, ds.poff + sh.n, slots, -1);
   k_fill_i32<<<g2, kBlock, 0, st>>>(v, ds.poff + sh.n, slots, -1);

@@ -471,7 +471,7 @@ template <int KSTEPS>
 static void launch_k(bool fcode, bool merge, unsigned grid, hipStream_t st, const int8_t* shadow,
                      const NodeMeta* meta, int dpad, const Shape& sh, const DevState& ds) {
 #define GNND_ARGS shadow, meta, dpad, sh.n, sh.p, sh.split, ds.snew, ds.sold, \
-                  ds.pslot, (uint64_t)sh.n * 6 * sh.p, ds.bins, ds.counters
+                  ds.pslot, (uint64_t)sh.slots(), ds.bins, ds.counters
   if (fcode) {
     if (merge) k_join_mfma<KSTEPS, true, true><<<grid, kMB, 0, st>>>(GNND_ARGS);
     else k_join_mfma<KSTEPS, true, false><<<grid, kMB, 0, st>>>(GNND_ARGS);

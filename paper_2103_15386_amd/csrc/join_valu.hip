@@ -91,7 +91,10 @@ __device__ inline void stage_row(ACC* dst, const uint8_t* src, int d, int d0, in
   *reinterpret_cast<int4*>(dst + part * 4) = v;
 }
 
-template <int METRIC>
+// ALL: every evaluated pair is proposed to both of its objects (the ablation
+// variant without the selective update of Sec. 4.3) instead of only the nearest
+// partner per sample.
+template <int METRIC, bool ALL>
 __global__ __launch_bounds__(kJB) void k_join_valu(
     VecSrc vs, int64_t n, int p, int merge_mode, const int32_t* __restrict__ snew,
     const int32_t* __restrict__ sold, const int32_t* __restrict__ cnew,
@@ -215,102 +218,106 @@ __global__ __launch_bounds__(kJB) void k_join_valu(
   uint64_t best = kKeyMax;
   int32_t self = -1;
   uint32_t evaluated = 0;
+  uint32_t n_found = 0, n_pass = 0, n_over = 0;  // this lane's results
   if (wave == 0) {
-    if (do_nn && lane < nn) {
-      self = ids[lane];
+    if (do_nn && lane < nn) self = ids[lane];
+  } else if (wave == 1) {
+    if (lane < nn) self = ids[lane];
+  } else {
+    if (lane < no) self = ids[64 + lane];
+  }
+  // nothing farther than the last entry of the destination list can enter it
+  const uint32_t kth_self = self >= 0 ? meta[self].kth : 0u;
+  // hand a result to the destination's segment of the proposal array: one
+  // returning add yields the segment start and this result's place in it
+  auto hand_on = [&](uint64_t key) {
+    ++n_found;
+    if ((uint32_t)(key >> 32) > kth_self) return;  // dropped here already
+    ++n_pass;
+    const uint64_t w = atomicAdd(reinterpret_cast<unsigned long long*>(&pslot[self]), 1ull);
+    const uint64_t at = (w >> kSlotCountBits) + (w & kSlotCountMask);
+    if (at < slots) bins[at] = make_entry((uint32_t)(key >> 32), (uint32_t)key, 3u);
+    else ++n_over;
+  };
+  auto offer = [&](uint64_t key) {
+    if (ALL) hand_on(key);
+    else best = key < best ? key : best;
+  };
+  if (wave == 0) {
+    if (self >= 0) {
       for (int v = 0; v < nn; ++v) {
         if (v == lane) continue;
         const uint32_t code = ((v >> 4) <= (lane >> 4)) ? Dm[lane * kDLD + v] : Dm[v * kDLD + lane];
-        const uint64_t key = ((uint64_t)code << 32) | (uint32_t)ids[v];
-        best = key < best ? key : best;
+        offer(((uint64_t)code << 32) | (uint32_t)ids[v]);
       }
     }
   } else if (wave == 1) {
-    if (lane < nn) {
-      self = ids[lane];
+    if (self >= 0) {
       for (int o = 0; o < no; ++o) {
         const int32_t other = ids[64 + o];
         bool ok = other != self;
         if (merge_mode) ok = ok && (((int64_t)self < split) != ((int64_t)other < split));
         if (!ok) continue;
         ++evaluated;
-        const uint64_t key = ((uint64_t)Dm[lane * kDLD + 64 + o] << 32) | (uint32_t)other;
-        best = key < best ? key : best;
+        offer(((uint64_t)Dm[lane * kDLD + 64 + o] << 32) | (uint32_t)other);
       }
     }
   } else {
-    if (lane < no) {
-      self = ids[64 + lane];
+    if (self >= 0) {
       for (int u = 0; u < nn; ++u) {
         const int32_t other = ids[u];
         bool ok = other != self;
         if (merge_mode) ok = ok && (((int64_t)self < split) != ((int64_t)other < split));
         if (!ok) continue;
-        const uint64_t key = ((uint64_t)Dm[u * kDLD + 64 + lane] << 32) | (uint32_t)other;
-        best = key < best ? key : best;
+        offer(((uint64_t)Dm[u * kDLD + 64 + lane] << 32) | (uint32_t)other);
       }
     }
   }
-  const bool found = best != kKeyMax;
-  // a result that cannot beat the last entry of the destination list is dropped here
-  const bool pass = found && (uint32_t)(best >> 32) <= meta[self < 0 ? 0 : self].kth;
-  // hand the result to the destination's segment of the proposal array
-  bool overflow = false;
-  if (pass) {
-    // one returning add: the segment start and this result's place in it
-    const uint64_t w = atomicAdd(reinterpret_cast<unsigned long long*>(&pslot[self]), 1ull);
-    const uint64_t at = (w >> kSlotCountBits) + (w & kSlotCountMask);
-    if (at < slots) bins[at] = make_entry((uint32_t)(best >> 32), (uint32_t)best, 3u);
-    else overflow = true;
-  }
-  const uint64_t nover = __popcll(__ballot(overflow));
-  const uint64_t nfound = __popcll(__ballot(found));
-  const uint64_t npass = __popcll(__ballot(pass));
-  if (wave == 1) {
+  if (!ALL && best != kKeyMax) hand_on(best);
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) evaluated += __shfl_xor(evaluated, off, kWave);
+  for (int off = 32; off > 0; off >>= 1) {
+    n_found += __shfl_xor(n_found, off, kWave);
+    n_pass += __shfl_xor(n_pass, off, kWave);
+    n_over += __shfl_xor(n_over, off, kWave);
+    evaluated += __shfl_xor(evaluated, off, kWave);
   }
   if (lane == 0) {
-    if (npass) atomicAdd(reinterpret_cast<unsigned long long*>(
-                             counters + (s & (kStripes - 1)) * C_SLOTS + C_PASSED),
-                         (unsigned long long)npass);
-    if (nover) atomicAdd(reinterpret_cast<unsigned long long*>(
-                             counters + (s & (kStripes - 1)) * C_SLOTS + C_OVERFLOW),
-                         (unsigned long long)nover);
-    if (nfound) atomicAdd(reinterpret_cast<unsigned long long*>(
-                              counters + (s & (kStripes - 1)) * C_SLOTS + C_PROPS),
-                          (unsigned long long)nfound);
+    uint64_t* cs = counters + (s & (kStripes - 1)) * C_SLOTS;
+    if (n_pass) atomicAdd(reinterpret_cast<unsigned long long*>(cs + C_PASSED),
+                          (unsigned long long)n_pass);
+    if (n_over) atomicAdd(reinterpret_cast<unsigned long long*>(cs + C_OVERFLOW),
+                          (unsigned long long)n_over);
+    if (n_found) atomicAdd(reinterpret_cast<unsigned long long*>(cs + C_PROPS),
+                           (unsigned long long)n_found);
     if (wave == 1) {
-      uint64_t ev = (uint64_t)evaluated + (do_nn ? (uint64_t)nn * (nn - 1) / 2 : 0);
-      if (ev) atomicAdd(reinterpret_cast<unsigned long long*>(
-                            counters + (s & (kStripes - 1)) * C_SLOTS + C_EVALS),
+      const uint64_t ev = (uint64_t)evaluated + (do_nn ? (uint64_t)nn * (nn - 1) / 2 : 0);
+      if (ev) atomicAdd(reinterpret_cast<unsigned long long*>(cs + C_EVALS),
                         (unsigned long long)ev);
     }
   }
 }
 
+template <bool ALL>
+static void launch_join_as(const Shape& sh, const DevState& ds, bool merge_mode, hipStream_t st) {
+  VecSrc vs{sh.vec_a, sh.vec_b, sh.split, sh.d};
+  const unsigned grid = (unsigned)sh.n;
+  const uint64_t slots = (uint64_t)sh.slots();  // size of the proposal array
+  const int mm = merge_mode ? 1 : 0;
+#define GNND_JOIN_ARGS vs, sh.n, sh.p, mm, ds.snew, ds.sold, ds.cnew, ds.cold, ds.meta, ds.pslot, \
+                       slots, ds.bins, ds.counters
+  switch (sh.metric) {
+    case kL2F32: k_join_valu<kL2F32, ALL><<<grid, kJB, 0, st>>>(GNND_JOIN_ARGS); break;
+    case kAngularF32: k_join_valu<kAngularF32, ALL><<<grid, kJB, 0, st>>>(GNND_JOIN_ARGS); break;
+    default: k_join_valu<kL2U8, ALL><<<grid, kJB, 0, st>>>(GNND_JOIN_ARGS);
+  }
+#undef GNND_JOIN_ARGS
+}
+
 hipError_t launch_join(const Shape& sh, const DevState& ds, int path, bool merge_mode,
                        hipStream_t st) {
   (void)path;
-  VecSrc vs{sh.vec_a, sh.vec_b, sh.split, sh.d};
-  const unsigned grid = (unsigned)sh.n;
-  const uint64_t slots = (uint64_t)sh.n * 6 * sh.p;  // size of the proposal array
-  switch (sh.metric) {
-    case kL2F32:
-      k_join_valu<kL2F32><<<grid, kJB, 0, st>>>(vs, sh.n, sh.p, merge_mode ? 1 : 0, ds.snew,
-                                                ds.sold, ds.cnew, ds.cold, ds.meta, ds.pslot,
-                                                slots, ds.bins, ds.counters);
-      break;
-    case kAngularF32:
-      k_join_valu<kAngularF32><<<grid, kJB, 0, st>>>(vs, sh.n, sh.p, merge_mode ? 1 : 0, ds.snew,
-                                                     ds.sold, ds.cnew, ds.cold, ds.meta, ds.pslot,
-                                                     slots, ds.bins, ds.counters);
-      break;
-    default:
-      k_join_valu<kL2U8><<<grid, kJB, 0, st>>>(vs, sh.n, sh.p, merge_mode ? 1 : 0, ds.snew,
-                                               ds.sold, ds.cnew, ds.cold, ds.meta, ds.pslot,
-                                               slots, ds.bins, ds.counters);
-  }
+  if (sh.all_pairs) launch_join_as<true>(sh, ds, merge_mode, st);
+  else launch_join_as<false>(sh, ds, merge_mode, st);
   return hipGetLastError();
 }
 

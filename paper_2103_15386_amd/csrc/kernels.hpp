@@ -64,6 +64,16 @@ struct Shape {
   int64_t split;  // merge: first id of the second set; otherwise n
   const void* vec_a;
   const void* vec_b;
+  int32_t all_pairs;  // 1: every evaluated pair is proposed (ablation), 0: nearest partners only
+  // slots of the proposal array: per appearance in a NEW list two results (all pairs: one per
+  // possible partner, 2 * 2p - 1), in an OLD list one (all pairs: 2p); at most 2np appearances each
+  __host__ __device__ int64_t slots_new_per_appearance() const {
+    return all_pairs ? 4 * p - 1 : 2;
+  }
+  __host__ __device__ int64_t slots_old_per_appearance() const { return all_pairs ? 2 * p : 1; }
+  __host__ __device__ int64_t slots() const {
+    return n * 2 * p * (slots_new_per_appearance() + slots_old_per_appearance());
+  }
 };
 
 hipError_t launch_init_random(const Shape& sh, const DevState& ds, uint64_t seed, hipStream_t st);

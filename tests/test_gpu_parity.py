@@ -79,14 +79,21 @@ CASES["u8_small_lists"] = (lambda: W.sift_like_u8(1500, 64, seed=1013, n_comp=4)
                            og.L2SQ_U8, 8, 5, 5)
 
 
+# "all": the variant that proposes every evaluated pair (no selective update)
+ALL_PAIRS_CASES = ["uniform_c1", "u8_cut", "deep_cut_angular", "tiny_n", "k100_angular"]
+
+
 @pytest.mark.parametrize("name,path", [(n, "valu") for n in CASES] +
-                         [(n, "mfma") for n in MFMA_CASES])
+                         [(n, "mfma") for n in MFMA_CASES] +
+                         [(n, "all") for n in ALL_PAIRS_CASES])
 def test_every_stage_of_every_iteration_matches_oracle(name, path):
     amd = _amd()
     gen, metric, k, p, iters = CASES[name]
     x = gen()
     n = len(x)
-    ctx = amd.Gnnd(_dev(x), k, p, metric, SEED, amd.JOIN_VALU if path == "valu" else amd.JOIN_MFMA)
+    every = path == "all"
+    ctx = amd.Gnnd(_dev(x), k, p, metric, SEED, amd.JOIN_MFMA if path == "mfma" else amd.JOIN_VALU,
+                   amd.UPDATE_ALL_PAIRS if every else amd.UPDATE_SELECTIVE)
     ctx.init_random()
     g = og.init_random(x, k, metric, SEED)
     for it in range(1, iters + 1):
@@ -99,7 +106,7 @@ def test_every_stage_of_every_iteration_matches_oracle(name, path):
         assert (gs[0] == snew).all() and (gs[2] == sold).all(), f"it {it}: sample lists"
         # --- cross-matching + nearest objects ------------------------------
         ctx.step_join()
-        pu, pv, pd, pcnt, evals = og.join(x, metric, p, snew, cnew, sold, cold)
+        pu, pv, pd, pcnt, evals = og.join(x, metric, p, snew, cnew, sold, cold, all_pairs=every)
         gu, gv, gd = [t.cpu().numpy().ravel() for t in ctx.proposals()]
         used = gu >= 0
         got = Counter(zip(gu[used].tolist(), gv[used].tolist(), gd[used].astype(np.float64).tolist()))

@@ -652,3 +652,60 @@ def test_append_is_a_sub_build_followed_by_a_merge_and_lifts_recall():
     for s in range(n1 + n2):  # well formed lists in the ids of the union
         row = g.ids[s].tolist()
         assert len(set(row)) == k and s not in row and 0 <= min(row) and max(row) < n1 + n2
+
+
+def test_all_pairs_join_proposes_every_evaluated_pair_both_ways():
+    # The variant without the selective update (ablation of Sec. 6.2): same pairs
+    # evaluated, each proposed to both of its objects.  Pins: the count identity
+    # proposals = 2 x evaluations; every proposal carries the true distance and
+    # has its mirror image; the selective join's results are exactly the
+    # per-(node, destination, partner kind) minima of this set.
+    k, p, seed = 8, 5, 9
+    x = W.uniform_f32(300, 6, seed=81)
+    g = og.init_random(x, k, og.L2SQ_F32, seed)
+    og.iterate(x, og.L2SQ_F32, g, p, seed, 1)
+    snew, cnew, sold, cold = og.sample(g, p, seed, 2)
+    pu, pv, pd, pcnt, ev = og.join(x, og.L2SQ_F32, p, snew, cnew, sold, cold)
+    au, av, ad, acnt, aev = og.join(x, og.L2SQ_F32, p, snew, cnew, sold, cold, all_pairs=True)
+    assert aev == ev and int(acnt.sum()) == 2 * ev
+    for s in range(300):
+        every = [(int(au[s, j]), int(av[s, j]), float(ad[s, j])) for j in range(acnt[s])]
+        # (an object sampled both as NEW and as OLD meets a NEW partner twice, so
+        # the same proposal can occur twice: compare as sets)
+        for u, v, dd in every:
+            assert dd == og.distance(x, og.L2SQ_F32, u, v) and (v, u, dd) in set(every)
+        news = set(snew[s, :cnew[s]].tolist())
+        olds = set(sold[s, :cold[s]].tolist())
+        # nearest partner of u among the NEW (resp. OLD) samples, by (distance, id)
+        want = set()
+        for u in news | olds:
+            mine = [(dd, v) for uu, v, dd in every if uu == u]
+            if u in news:
+                for pool in (news, olds):
+                    cand = [(dd, v) for dd, v in mine if v in pool and v != u]
+                    # NEW x NEW and NEW x OLD only: a pair of two OLD samples is never evaluated
+                    if cand:
+                        dd, v = min(cand)
+                        want.add((u, v, dd))
+            if u in olds:
+                cand = [(dd, v) for dd, v in mine if v in news and v != u]
+                if cand:
+                    dd, v = min(cand)
+                    want.add((u, v, dd))
+        got = set((int(pu[s, j]), int(pv[s, j]), float(pd[s, j])) for j in range(pcnt[s]))
+        assert got == want, s
+
+
+def test_all_pairs_build_is_at_least_as_good_per_iteration_and_costs_more_proposals():
+    k, p, seed = 10, 8, 42
+    x = W.uniform_f32(600, 8, seed=3)
+    g_sel, st_sel = og.build(x, k, p, og.L2SQ_F32, seed, 5)
+    g_all, st_all = og.build(x, k, p, og.L2SQ_F32, seed, 5, all_pairs=True)
+    ti, td = og.bruteforce(x, og.L2SQ_F32, np.arange(600, dtype=np.int32), k)
+    r_sel, _ = og.recall_at(g_sel.ids, g_sel.dist, ti, td, 10)
+    r_all, _ = og.recall_at(g_all.ids, g_all.dist, ti, td, 10)
+    assert r_all >= r_sel and r_all > 0.97
+    assert st_all[0]["proposals"] > 5 * st_sel[0]["proposals"]
+    # the first iteration sees the same samples, hence the same evaluations
+    assert st_all[0]["dist_evals"] == st_sel[0]["dist_evals"]
+    _check_lists(g_all, x, og.L2SQ_F32)
