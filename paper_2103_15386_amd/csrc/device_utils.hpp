@@ -130,6 +130,12 @@ template <typename T>
 __device__ inline T exchange(T v, T o, bool keep_min) {
   return ((o < v) == keep_min) ? o : v;
 }
+// 32-bit values: min and max can take the partner straight from the lane
+// permutation (no separate move), then one select on the lane pattern.
+__device__ inline uint32_t exchange(uint32_t v, uint32_t o, bool keep_min) {
+  const uint32_t lo = v < o ? v : o, hi = v < o ? o : v;
+  return keep_min ? lo : hi;
+}
 
 // Full ascending sort of 64 lane values (bitonic network, 21 exchange stages).
 template <typename T>
