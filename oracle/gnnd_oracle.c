@@ -531,6 +531,46 @@ int og_insert_one(int k, int32_t* ids, double* dist, uint8_t* isnew, int32_t v, 
   return 1;
 }
 
+/* The local join of classic NN-Descent (Sec. 3, the CPU scheme the paper starts
+ * from), for comparison only: node after node, every NEW x NEW and NEW x OLD
+ * pair of the node's sample lists is evaluated and tried at once on both
+ * lists (og_insert_one), so later joins of the same iteration see the lists
+ * as earlier ones left them.  Sequential by definition.  Returns the number
+ * of distances evaluated; *inserts counts the accepted insertions. */
+uint64_t og_classic_join_update(const void* vec, int64_t n, int d, int k, int p, int metric,
+                                const int32_t* snew, const int32_t* cnew, const int32_t* sold,
+                                const int32_t* cold, int32_t* ids, double* dist, uint8_t* isnew,
+                                uint64_t* inserts) {
+  const int L = 2 * p;
+  uint64_t evals = 0, ins = 0;
+  for (int64_t s = 0; s < n; ++s) {
+    const int32_t* N = snew + s * L;
+    const int32_t* O = sold + s * L;
+    const int nn = cnew[s], no = cold[s];
+    for (int a = 0; a < nn; ++a) {
+      for (int b = 0; b < a; ++b) {
+        const double dd = og_distance(metric, d, vec, N[a], N[b]);
+        ++evals;
+        ins += (uint64_t)og_insert_one(k, ids + (int64_t)N[a] * k, dist + (int64_t)N[a] * k,
+                                       isnew + (int64_t)N[a] * k, N[b], dd);
+        ins += (uint64_t)og_insert_one(k, ids + (int64_t)N[b] * k, dist + (int64_t)N[b] * k,
+                                       isnew + (int64_t)N[b] * k, N[a], dd);
+      }
+      for (int b = 0; b < no; ++b) {
+        if (N[a] == O[b]) continue;
+        const double dd = og_distance(metric, d, vec, N[a], O[b]);
+        ++evals;
+        ins += (uint64_t)og_insert_one(k, ids + (int64_t)N[a] * k, dist + (int64_t)N[a] * k,
+                                       isnew + (int64_t)N[a] * k, O[b], dd);
+        ins += (uint64_t)og_insert_one(k, ids + (int64_t)O[b] * k, dist + (int64_t)O[b] * k,
+                                       isnew + (int64_t)O[b] * k, N[a], dd);
+      }
+    }
+  }
+  *inserts = ins;
+  return evals;
+}
+
 /* Graph update of one iteration (all InsertIntoNNList calls of Alg. 1).
  * The paper inserts concurrently under (segment) spinlocks.  Reading: the list
  * of u after the iteration is the first k, by (distance, id), of its entries

@@ -69,6 +69,10 @@ def _load():
     lib.og_update_rows.restype = C.c_uint64
     lib.og_update_rows.argtypes = [C.c_int64, C.c_int, C.c_int, i32p, f64p, u8p, i32p, i32p, f64p,
                                    i32p]
+    lib.og_classic_join_update.restype = C.c_uint64
+    lib.og_classic_join_update.argtypes = [vp, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int,
+                                           i32p, i32p, i32p, i32p, i32p, f64p, u8p,
+                                           np.ctypeslib.ndpointer(np.uint64, flags="C")]
     lib.og_update.restype = C.c_uint64
     lib.og_update.argtypes = [C.c_int64, C.c_int, C.c_int, i32p, f64p, u8p, i32p, i32p, f64p,
                               i32p]
@@ -211,6 +215,23 @@ def build(vectors, k, p, metric, seed, iters, all_pairs=False):
         stats.append({key: st[key] for key in ("iter", "inserts", "dist_evals", "sum_new",
                                                "sum_old", "proposals")})
     return g, stats
+
+
+def build_classic(vectors, k, p, metric, seed, iters):
+    """Classic NN-Descent (Sec. 3) for comparison: the same initial graph and the
+    same sampling as build(), but every evaluated pair is inserted into both lists
+    at once, node after node.  Returns the graph and phi after every iteration."""
+    v = _vec(vectors, metric)
+    n, d = v.shape
+    g = init_random(vectors, k, metric, seed)
+    trend = []
+    for it in range(1, iters + 1):
+        snew, cnew, sold, cold = sample(g, p, seed, it)
+        ins = np.zeros(1, np.uint64)
+        _load().og_classic_join_update(v.ctypes.data, n, d, k, p, metric, snew, cnew, sold, cold,
+                                       g.ids, g.dist, g.isnew, ins)
+        trend.append(phi(g.dist))
+    return g, trend
 
 
 def merge_init(vectors, n1, k, metric, seed, g1, g2, base1=0, base2=None):

@@ -709,3 +709,26 @@ def test_all_pairs_build_is_at_least_as_good_per_iteration_and_costs_more_propos
     # the first iteration sees the same samples, hence the same evaluations
     assert st_all[0]["dist_evals"] == st_sel[0]["dist_evals"]
     _check_lists(g_all, x, og.L2SQ_F32)
+
+
+def test_phi_trend_of_gnnd_overlaps_classic_nn_descent():
+    # The paper's own check of the selective update (Sec. 4.3, the phi(G) figure):
+    # the sum of all list distances falls along the same curve as under classic
+    # NN-Descent, which inserts every evaluated pair at once.  Classic NN-Descent
+    # here is a separate sequential routine that shares only the sampling.
+    k, p, seed, iters = 10, 8, 42, 8
+    x = W.uniform_f32(4096, 16, seed=1001)
+    g_classic, trend_classic = og.build_classic(x, k, p, og.L2SQ_F32, seed, iters)
+    g = og.init_random(x, k, og.L2SQ_F32, seed)
+    trend = []
+    for it in range(1, iters + 1):
+        og.iterate(x, og.L2SQ_F32, g, p, seed, it)
+        trend.append(og.phi(g.dist))
+    assert all(b <= a for a, b in zip(trend, trend[1:]))
+    assert all(b <= a for a, b in zip(trend_classic, trend_classic[1:]))
+    for a, b in zip(trend, trend_classic):
+        assert abs(a - b) / b < 0.05, (trend, trend_classic)
+    _, td = og.bruteforce(x, og.L2SQ_F32, np.arange(4096, dtype=np.int32), k)
+    exact = og.phi(td)
+    assert exact <= trend_classic[-1] <= 1.02 * exact and exact <= trend[-1] <= 1.02 * exact
+    _check_lists(g_classic, x, og.L2SQ_F32)
