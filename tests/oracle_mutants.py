@@ -32,6 +32,11 @@ muts = [
  ("merge fill flagged old", "row[keep + j].isnew = 1;", "row[keep + j].isnew = 0;"),
  ("frozen sampled", "if (v < 0 || v >= n) continue;", "if (v < 0) continue;"),
  ("to_global wrong base", "return (int32_t)(base2 + i - n1);", "return (int32_t)(base1 + i);"),
+ ("all-pairs one way only", "          qu[m] = N[a]; qv[m] = N[b]; qd[m] = dist; ++m;\n          qu[m] = N[b]; qv[m] = N[a]; qd[m] = dist; ++m;", "          qu[m] = N[a]; qv[m] = N[b]; qd[m] = dist; ++m;"),
+ ("all-pairs same id not skipped", "        if (N[a] == O[b]) continue;\n        if (split >= 0", "        if (split >= 0"),
+ ("all-pairs old x old evaluated", "        qu[m] = N[a]; qv[m] = O[b]; qd[m] = dist; ++m;\n        qu[m] = O[b]; qv[m] = N[a]; qd[m] = dist; ++m;", "        qu[m] = N[a]; qv[m] = O[b]; qd[m] = dist; ++m;\n        qu[m] = O[b]; qv[m] = O[b > 0 ? b - 1 : 0]; qd[m] = dist; ++m;"),
+ ("update rows stride", "return og_update_rows(n, k, 6 * p, ids, dist, isnew, pu, pv, pd, pcnt);", "return og_update_rows(n, k, 6 * p + 1, ids, dist, isnew, pu, pv, pd, pcnt);"),
+ ("classic inserts one side only", "        ins += (uint64_t)og_insert_one(k, ids + (int64_t)N[b] * k, dist + (int64_t)N[b] * k,\n                                       isnew + (int64_t)N[b] * k, N[a], dd);\n", ""),
 ]
 root=os.path.dirname(os.path.dirname(os.path.abspath(__file__))); tmp="/tmp/gnnd_oracle_mutants"
 src=open(root+"/oracle/gnnd_oracle.c").read()
