@@ -41,7 +41,9 @@ typedef struct gnnd_ctx gnnd_ctx; /* opaque, host-side, owned by the library */
 enum {
   GNND_L2SQ_F32 = 0,    /* squared L2, float32 vectors, float32 result            */
   GNND_ANGULAR_F32 = 1, /* 1 - dot product, float32 (unit) vectors, float32 result */
-  GNND_L2SQ_U8 = 2      /* squared L2, uint8 vectors, exact int32 result           */
+  GNND_L2SQ_U8 = 2,     /* squared L2, uint8 vectors, exact int32 result           */
+  GNND_CHI2_F32 = 3     /* chi-square, sum of (a-b)^2/(a+b) over the dimensions with
+                           a+b > 0, non-negative float32 vectors, float32 result   */
 };
 
 enum {

@@ -30,7 +30,7 @@
 #include <stdlib.h>
 #include <string.h>
 
-enum { OG_L2SQ_F32 = 0, OG_ANGULAR_F32 = 1, OG_L2SQ_U8 = 2 };
+enum { OG_L2SQ_F32 = 0, OG_ANGULAR_F32 = 1, OG_L2SQ_U8 = 2, OG_CHI2_F32 = 3 };
 enum { OG_TAG_INIT = 1, OG_TAG_REV_NEW = 2, OG_TAG_REV_OLD = 3, OG_TAG_MERGE = 4 };
 enum { OG_HASH_ATTEMPTS = 256 };
 
@@ -87,7 +87,29 @@ __attribute__((target_clones("fma", "default"))) static float dot_f32(const floa
   return acc;
 }
 
+/* Chi-square distance of two non-negative vectors (Sec. 4.2 names it next to the
+ * l2-norm as a metric the tile kernel can evaluate): sum over the dimensions of
+ * (a - b)^2 / (a + b), a dimension with a + b = 0 adding nothing.  Reading: float32,
+ * dimension order, every operation rounded on its own (no fused multiply-add;
+ * the build switches contraction off). */
+static float chi2_f32(const float* a, const float* b, int d) {
+  float acc = 0.0f;
+  for (int j = 0; j < d; ++j) {
+    const float diff = a[j] - b[j];
+    const float sum = a[j] + b[j];
+    if (sum > 0.0f) {
+      const float sq = diff * diff;
+      acc = acc + sq / sum;
+    }
+  }
+  return acc;
+}
+
 double og_distance(int metric, int d, const void* vec, int64_t i, int64_t j) {
+  if (metric == OG_CHI2_F32) {
+    const float* x = (const float*)vec;
+    return (double)chi2_f32(x + i * d, x + j * d, d);
+  }
   if (metric == OG_L2SQ_F32) {
     const float* x = (const float*)vec;
     return (double)l2sq_f32(x + i * d, x + j * d, d);

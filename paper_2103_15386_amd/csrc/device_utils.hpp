@@ -11,7 +11,7 @@ constexpr int kWave = 64;
 constexpr uint64_t kKeyMax = ~0ull;
 constexpr uint32_t kIdMax = 0x7fffffffu;
 
-enum : int { kL2F32 = 0, kAngularF32 = 1, kL2U8 = 2 };
+enum : int { kL2F32 = 0, kAngularF32 = 1, kL2U8 = 2, kChi2F32 = 3 };
 enum : uint32_t { kTagInit = 1, kTagRevNew = 2, kTagRevOld = 3, kTagMerge = 4 };
 constexpr uint32_t kHashAttempts = 256;
 
@@ -263,6 +263,23 @@ struct DistOf<kAngularF32> {
       for (; j < d; ++j) acc = __fmaf_rn(a[j], b[j], acc);
     }
     return ord_f32(1.0f - acc);
+  }
+};
+
+// Chi-square distance of non-negative vectors: sum of (a - b)^2 / (a + b) over
+// the dimensions with a + b > 0; every operation rounded on its own (there is no
+// multiply feeding an add, so nothing can fuse), correctly rounded division.
+__device__ inline float chi2_term(float a, float b, float acc) {
+  const float diff = __fsub_rn(a, b), sum = __fadd_rn(a, b);
+  return sum > 0.f ? __fadd_rn(acc, __fdiv_rn(__fmul_rn(diff, diff), sum)) : acc;
+}
+template <>
+struct DistOf<kChi2F32> {
+  using elem = float;
+  __device__ static uint32_t eval(const float* a, const float* b, int d) {
+    float acc = 0.f;
+    for (int j = 0; j < d; ++j) acc = chi2_term(a[j], b[j], acc);
+    return ord_f32(acc);
   }
 };
 

@@ -31,7 +31,7 @@ inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
 const char* check_params(const gnnd_params* q) {
   if (!q) return "params is NULL";
-  if (q->metric < GNND_L2SQ_F32 || q->metric > GNND_L2SQ_U8) return "unknown metric";
+  if (q->metric < GNND_L2SQ_F32 || q->metric > GNND_CHI2_F32) return "unknown metric";
   if (q->k < 2 || q->k > 128) return "k must be in [2, 128]";
   if (q->k > 64 && q->n > ((int64_t)1 << 27)) return "k above 64 needs n <= 2^27";
   if (q->p < 1 || q->p > 32 || q->p > q->k) return "p must be in [1, min(k, 32)]";
@@ -847,7 +847,8 @@ int gnnd_exact_knn(const void* vec, int64_t n, int32_t d, int32_t metric, const 
                    int64_t nq, int32_t K, int32_t* ids_out, void* dist_out, void* stream) {
   if (!vec || !queries || !ids_out || !dist_out)
     return fail(nullptr, GNND_EINVAL, "NULL pointer argument");
-  if (metric < GNND_L2SQ_F32 || metric > GNND_L2SQ_U8) return fail(nullptr, GNND_EINVAL, "unknown metric");
+  if (metric < GNND_L2SQ_F32 || metric > GNND_CHI2_F32)
+    return fail(nullptr, GNND_EINVAL, "unknown metric");
   if (n < 2 || n > ((int64_t)1 << 30) || d < 1 || nq < 0 || K < 1 || K > 64)
     return fail(nullptr, GNND_EINVAL, "need 2 <= n <= 2^30, d >= 1, nq >= 0, 1 <= K <= 64");
   if ((uintptr_t)vec & 15) return fail(nullptr, GNND_EINVAL, "vectors must be 16-byte aligned");

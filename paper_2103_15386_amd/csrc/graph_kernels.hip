@@ -564,6 +564,10 @@ hipError_t launch_init_random(const Shape& sh, const DevState& ds, uint64_t seed
       k_init_random<kAngularF32><<<grid, kBlock, 0, st>>>(vec_src(sh), sh.n, sh.k, base, ds.G,
                                                           ds.meta);
       break;
+    case kChi2F32:
+      k_init_random<kChi2F32><<<grid, kBlock, 0, st>>>(vec_src(sh), sh.n, sh.k, base, ds.G,
+                                                       ds.meta);
+      break;
     default:
       k_init_random<kL2U8><<<grid, kBlock, 0, st>>>(vec_src(sh), sh.n, sh.k, base, ds.G, ds.meta);
   }
@@ -658,6 +662,10 @@ hipError_t launch_merge_init(const Shape& sh, const DevState& ds, uint64_t seed,
                                                          dist1, ids2, dist2, ds.G, ds.meta,
                                                          ds.aside);
       break;
+    case kChi2F32:
+      k_merge_init<kChi2F32><<<grid, kBlock, 0, st>>>(vec_src(sh), sh.n, mi, sh.k, base, ids1,
+                                                      dist1, ids2, dist2, ds.G, ds.meta, ds.aside);
+      break;
     default:
       k_merge_init<kL2U8><<<grid, kBlock, 0, st>>>(vec_src(sh), sh.n, mi, sh.k, base, ids1, dist1,
                                                    ids2, dist2, ds.G, ds.meta, ds.aside);
@@ -689,6 +697,9 @@ hipError_t launch_exact_knn(const void* vec, int64_t n, int32_t d, int32_t metri
       break;
     case kAngularF32:
       k_exact_knn<kAngularF32><<<grid, kBlock, 0, st>>>(vec, n, d, queries, K, ids_out, dist_out);
+      break;
+    case kChi2F32:
+      k_exact_knn<kChi2F32><<<grid, kBlock, 0, st>>>(vec, n, d, queries, K, ids_out, dist_out);
       break;
     default:
       k_exact_knn<kL2U8><<<grid, kBlock, 0, st>>>(vec, n, d, queries, K, ids_out, dist_out);

@@ -42,6 +42,13 @@ struct JoinTraits<kAngularF32> {
   __device__ static uint32_t code(float s) { return ord_f32(1.0f - s); }
 };
 template <>
+struct JoinTraits<kChi2F32> {
+  using elem = float;
+  using acc = float;
+  __device__ static void step(float a, float b, float& s) { s = chi2_term(a, b, s); }
+  __device__ static uint32_t code(float s) { return ord_f32(s); }
+};
+template <>
 struct JoinTraits<kL2U8> {
   using elem = uint8_t;
   using acc = int32_t;
@@ -308,6 +315,7 @@ static void launch_join_as(const Shape& sh, const DevState& ds, bool merge_mode,
   switch (sh.metric) {
     case kL2F32: k_join_valu<kL2F32, ALL><<<grid, kJB, 0, st>>>(GNND_JOIN_ARGS); break;
     case kAngularF32: k_join_valu<kAngularF32, ALL><<<grid, kJB, 0, st>>>(GNND_JOIN_ARGS); break;
+    case kChi2F32: k_join_valu<kChi2F32, ALL><<<grid, kJB, 0, st>>>(GNND_JOIN_ARGS); break;
     default: k_join_valu<kL2U8, ALL><<<grid, kJB, 0, st>>>(GNND_JOIN_ARGS);
   }
 #undef GNND_JOIN_ARGS

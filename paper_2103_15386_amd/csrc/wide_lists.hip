@@ -278,6 +278,10 @@ hipError_t launch_init_random_wide(const Shape& sh, const DevState& ds, uint64_t
       k_init_random_wide<kAngularF32><<<grid, kWB, 0, st>>>(wide_vec_src(sh), sh.n, sh.k, base,
                                                             ds.G, ds.meta);
       break;
+    case kChi2F32:
+      k_init_random_wide<kChi2F32><<<grid, kWB, 0, st>>>(wide_vec_src(sh), sh.n, sh.k, base, ds.G,
+                                                         ds.meta);
+      break;
     default:
       k_init_random_wide<kL2U8><<<grid, kWB, 0, st>>>(wide_vec_src(sh), sh.n, sh.k, base, ds.G,
                                                       ds.meta);
@@ -305,6 +309,11 @@ hipError_t launch_merge_init_wide(const Shape& sh, const DevState& ds, uint64_t 
       k_merge_init_wide<kAngularF32><<<grid, kWB, 0, st>>>(wide_vec_src(sh), sh.n, mi, sh.k, base,
                                                            ids1, dist1, ids2, dist2, ds.G, ds.meta,
                                                            ds.aside);
+      break;
+    case kChi2F32:
+      k_merge_init_wide<kChi2F32><<<grid, kWB, 0, st>>>(wide_vec_src(sh), sh.n, mi, sh.k, base,
+                                                        ids1, dist1, ids2, dist2, ds.G, ds.meta,
+                                                        ds.aside);
       break;
     default:
       k_merge_init_wide<kL2U8><<<grid, kWB, 0, st>>>(wide_vec_src(sh), sh.n, mi, sh.k, base, ids1,

@@ -27,6 +27,7 @@ def _exact(x, metric, k):
     (og.ANGULAR_F32, lambda n: W.deep_like_f32(n, 48, seed=204, n_comp=8), 16, 16, 1000, 0),
     (og.L2SQ_U8, lambda n: W.sift_like_u8(n, 64, seed=205, n_comp=8), 97, 32, 1000, 3),  # long lists
     (og.L2SQ_F32, lambda n: W.uniform_f32(n, 9, seed=206), 128, 16, 800, 2),
+    (og.CHI2_F32, lambda n: W.gist_like_f32(n, 40, seed=207, n_comp=8), 14, 10, 1200, 3),
 ])
 def test_merge_matches_oracle(metric, gen, k, p, n1, iters, path):
     import paper_2103_15386_amd as amd

@@ -49,6 +49,10 @@ CASES = {
                       og.L2SQ_F32, 16, 16, 4),
     "tiny_n": (lambda: W.uniform_f32(70, 7, seed=6), og.L2SQ_F32, 5, 3, 4),
     "u8_d30": (lambda: W.sift_like_u8(900, 30, seed=8, n_comp=4), og.L2SQ_U8, 12, 12, 4),
+    # chi-square distance on histogram-like (non-negative, L1-normalised) vectors
+    "chi2_gist_cut": (lambda: W.gist_like_f32(1500, 96, seed=1031, n_comp=8),
+                      og.CHI2_F32, 20, 16, 4),
+    "chi2_ragged_d7": (lambda: W.gist_like_f32(600, 7, seed=1032, n_comp=4), og.CHI2_F32, 9, 6, 4),
     # lists longer than one wavefront (two entries per lane)
     "k128_uniform": (lambda: W.uniform_f32(1800, 10, seed=1021), og.L2SQ_F32, 128, 32, 4),
     "k100_angular": (lambda: W.deep_like_f32(1500, 48, seed=1022, n_comp=8),
@@ -177,6 +181,7 @@ def test_resume_from_saved_graph_gives_the_same_bytes():
     (og.ANGULAR_F32, lambda: W.deep_like_f32(3000, 32, seed=92, n_comp=8)),
     (og.L2SQ_U8, lambda: W.sift_like_u8(3000, 40, seed=93, n_comp=8)),
     (og.L2SQ_F32, lambda: W.small_integer_f32(2000, 5, seed=94, hi=4)),  # masses of ties
+    (og.CHI2_F32, lambda: W.gist_like_f32(2500, 30, seed=95, n_comp=8)),
 ])
 def test_exact_knn_matches_oracle_brute_force(metric, gen):
     amd = _amd()

@@ -105,6 +105,33 @@ def test_angular_is_one_minus_float32_fused_dot():
             assert Fraction(og.distance(x, og.ANGULAR_F32, i, j)) == want
 
 
+def test_chi_square_is_float32_term_by_term_with_zero_sums_skipped():
+    # sum over the dimensions of (a - b)^2 / (a + b), every operation rounded to
+    # float32 on its own (exact rational arithmetic with explicit rounding), a
+    # dimension where both entries are zero adding nothing; symmetric; zero on
+    # equal vectors; close to the float64 value of the textbook formula.
+    rng = np.random.default_rng(6)
+    x = np.abs(rng.standard_normal((6, 13))).astype(np.float32)
+    x[:, 4] = 0.0   # a dimension that is empty everywhere
+    x[2, 7] = 0.0
+    for i in range(6):
+        for j in range(6):
+            acc = Fraction(0)
+            for q in range(x.shape[1]):
+                diff = _round_f32(_fr(x[i, q]) - _fr(x[j, q]))
+                tot = _round_f32(_fr(x[i, q]) + _fr(x[j, q]))
+                if tot > 0:
+                    acc = _round_f32(acc + _round_f32(_round_f32(diff * diff) / tot))
+            got = og.distance(x, og.CHI2_F32, i, j)
+            assert Fraction(got) == acc
+            assert got == og.distance(x, og.CHI2_F32, j, i)
+            a, b = x[i].astype(np.float64), x[j].astype(np.float64)
+            ok = (a + b) > 0
+            ref = (((a - b) ** 2)[ok] / (a + b)[ok]).sum()
+            assert abs(got - ref) <= 1e-5 * max(ref, 1e-3)
+        assert og.distance(x, og.CHI2_F32, i, i) == 0.0
+
+
 def test_u8_distance_is_exact_integer():
     rng = np.random.default_rng(5)
     x = rng.integers(0, 256, size=(8, 37)).astype(np.uint8)
@@ -119,6 +146,10 @@ def _numpy_knn(x, metric, K):
     xd = x.astype(np.float64)
     if metric == og.ANGULAR_F32:
         D = 1.0 - xd @ xd.T
+    elif metric == og.CHI2_F32:
+        tot = xd[:, None, :] + xd[None, :, :]
+        D = np.where(tot > 0, (xd[:, None, :] - xd[None, :, :]) ** 2 / np.where(tot > 0, tot, 1),
+                     0.0).sum(-1)
     else:
         D = ((xd[:, None, :] - xd[None, :, :]) ** 2).sum(-1)
     n = len(x)
@@ -147,6 +178,19 @@ def test_bruteforce_angular_close_to_float64():
     ref = np.take_along_axis(D, ids.astype(np.int64), 1)
     assert np.abs(dist - ref).max() < 1e-6
     assert (ids == want).mean() > 0.99  # only float32 near-ties may differ
+
+
+def test_bruteforce_chi_square_close_to_float64_and_build_converges():
+    x = W.gist_like_f32(300, 20, seed=14, n_comp=6)
+    ids, dist = og.bruteforce(x, og.CHI2_F32, np.arange(300), 10)
+    want, D = _numpy_knn(x, og.CHI2_F32, 10)
+    ref = np.take_along_axis(D, ids.astype(np.int64), 1)
+    assert np.abs(dist - ref).max() < 1e-6
+    assert (ids == want).mean() > 0.99  # only float32 near-ties may differ
+    g, _ = og.build(x, 16, 16, og.CHI2_F32, 7, 8)
+    rec, _ = og.recall_at(g.ids, g.dist, ids, dist, 10)
+    assert rec > 0.97
+    _check_lists(g, x, og.CHI2_F32)
 
 
 def test_bruteforce_points_on_a_line():
