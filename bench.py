@@ -51,7 +51,7 @@ def parse():
     ap.add_argument("--update", choices=["selective", "all-pairs"], default="selective",
                     help="all-pairs: the ablation variant that proposes every evaluated pair "
                          "(runs with the valu join; ~100 KB of workspace per node at p = 32)")
-    ap.add_argument("--cpu-sample-n", type=int, default=40_000)
+    ap.add_argument("--cpu-sample-n", type=int, default=200_000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--workload", choices=["sift1m", "sharded"], default="sift1m")
     ap.add_argument("--shards", type=int, default=4)
