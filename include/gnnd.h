@@ -72,9 +72,9 @@ enum {
 };
 
 typedef struct gnnd_params {
-  int64_t n;      /* number of vectors, k < n <= 2^30                               */
+  int64_t n;      /* number of vectors, k < n <= 2^27                               */
   int32_t d;      /* dimension, >= 1 (float metrics: multiple of 4 reads fastest)   */
-  int32_t k;      /* list length, 2 <= k <= 128 (above 64: n <= 2^27)               */
+  int32_t k;      /* list length, 2 <= k <= 128                                     */
   int32_t p;      /* sample number of Sec. 4.1, 1 <= p <= min(k, 32)                */
   int32_t metric; /* GNND_L2SQ_F32 / GNND_ANGULAR_F32 / GNND_L2SQ_U8               */
   uint64_t seed;  /* seed of all random draws                                       */

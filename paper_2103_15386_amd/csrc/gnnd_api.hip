@@ -22,7 +22,7 @@ namespace {
 thread_local std::string g_last_error = "";
 
 struct Layout {
-  size_t off_G, off_kth, off_snew, off_sold, off_cnew, off_cold, off_rcn, off_rco, off_ron,
+  size_t off_G, off_kth, off_snew, off_sold, off_cnew, off_cold, off_ron,
       off_roo, off_csn, off_cso, off_capn, off_capo, off_pcnt, off_poff, off_bins, off_scan,
       off_cnt, off_snap, off_aside, off_shadow, off_norms, off_flag, off_bkc, off_bko, total;
 };
@@ -33,12 +33,11 @@ const char* check_params(const gnnd_params* q) {
   if (!q) return "params is NULL";
   if (q->metric < GNND_L2SQ_F32 || q->metric > GNND_CHI2_F32) return "unknown metric";
   if (q->k < 2 || q->k > 128) return "k must be in [2, 128]";
-  if (q->k > 64 && q->n > ((int64_t)1 << 27)) return "k above 64 needs n <= 2^27";
   if (q->p < 1 || q->p > 32 || q->p > q->k) return "p must be in [1, min(k, 32)]";
   if (q->d < 1) return "d must be >= 1";
   if (q->metric == GNND_L2SQ_U8 && q->d > 32768) return "d must be <= 32768 for uint8 vectors";
   if (q->n <= q->k) return "n must exceed k";
-  if (q->n > ((int64_t)1 << 30)) return "n must be <= 2^30";
+  if (q->n > ((int64_t)1 << 27)) return "n must be <= 2^27";
   if (q->n * (int64_t)q->p >= ((int64_t)1 << 32)) return "n * p must be below 2^32";
   if (q->join_path < GNND_JOIN_AUTO || q->join_path > GNND_JOIN_MFMA) return "unknown join_path";
   if (q->update_mode != GNND_UPDATE_SELECTIVE && q->update_mode != GNND_UPDATE_ALL_PAIRS)
@@ -70,8 +69,6 @@ Layout make_layout(const gnnd_params* q, bool with_aside) {
   L.off_sold = take(n * 2 * p * 4);
   L.off_cnew = take(n * 4);
   L.off_cold = take(n * 4);
-  L.off_rcn = take(n * 4);
-  L.off_rco = take(n * 4);
   L.off_ron = take((n + 1) * 8);
   L.off_roo = take((n + 1) * 8);
   L.off_csn = take(n * p * 4);
@@ -143,8 +140,6 @@ void bind(gnnd_ctx* c, const Layout& L) {
   d.sold = (int32_t*)(w + L.off_sold);
   d.cnew = (int32_t*)(w + L.off_cnew);
   d.cold = (int32_t*)(w + L.off_cold);
-  d.rcnt_new = (uint32_t*)(w + L.off_rcn);
-  d.rcnt_old = (uint32_t*)(w + L.off_rco);
   d.roff_new = (uint64_t*)(w + L.off_ron);
   d.roff_old = (uint64_t*)(w + L.off_roo);
   d.csr_new = (int32_t*)(w + L.off_csn);
@@ -199,9 +194,7 @@ int create_impl(gnnd_ctx** out, const gnnd_params* prm, const void* vec_a, const
   c->have_prof = false;
   bind(c, L);
   // counters that must start at zero (they return to zero after every iteration)
-  hipError_t e = launch_zero_u32(c->ds.rcnt_new, (size_t)prm->n, c->stream);
-  if (e == hipSuccess) e = launch_zero_u32(c->ds.rcnt_old, (size_t)prm->n, c->stream);
-  if (e == hipSuccess) e = launch_zero_u32((uint32_t*)c->ds.pslot, 2 * (size_t)prm->n, c->stream);
+  hipError_t e = launch_zero_u32((uint32_t*)c->ds.pslot, 2 * (size_t)prm->n, c->stream);
   if (e == hipSuccess) e = launch_zero_u32(c->ds.bk_cnt, 2 * 4096, c->stream);
   if (e == hipSuccess)
     e = launch_zero_u32((uint32_t*)c->ds.counters, (size_t)kStripes * C_SLOTS * 2, c->stream);

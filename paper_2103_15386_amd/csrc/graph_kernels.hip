@@ -48,67 +48,6 @@ __global__ __launch_bounds__(kBlock) void k_init_random(VecSrc vs, int64_t n, in
 }
 
 // ---------------------------------------------------------------------------
-// Sec. 4.1, forward part: the first p NEW and the first p OLD entries of each
-// list go to the front of the node's sample rows; the sampled NEW entries are
-// flagged OLD; every sampled v counts one reverse candidate for v.
-__global__ __launch_bounds__(kBlock) void k_sample_fwd(int64_t n, int k, int p, uint64_t* G,
-                                                       int32_t* snew, int32_t* sold,
-                                                       int32_t* cnew, int32_t* cold,
-                                                       uint32_t* rcnt_new, uint32_t* rcnt_old) {
-  const int64_t s = wave_global_index();
-  if (s >= n) return;
-  const int lane = lane_id();
-  uint64_t e = lane < k ? G[s * k + lane] : 0ull;
-  // entries numbered beyond n are frozen leftovers of an earlier merge: not sampled
-  const bool valid = lane < k && (int64_t)entry_id(e) < n;
-  const bool isnew = valid && (e & 1ull);
-  const bool isold = valid && !(e & 1ull);
-  const uint64_t mn = __ballot(isnew), mo = __ballot(isold);
-  const int rn = __popcll(mn & lanes_below(lane)), ro = __popcll(mo & lanes_below(lane));
-  const uint32_t id = entry_id(e);
-  const int L = 2 * p;
-  if (isnew && rn < p) {
-    snew[s * L + rn] = (int32_t)id;
-    G[s * k + lane] = e & ~1ull;
-    atomicAdd(&rcnt_new[id], 1u);
-  }
-  if (isold && ro < p) {
-    sold[s * L + ro] = (int32_t)id;
-    atomicAdd(&rcnt_old[id], 1u);
-  }
-  if (lane == 0) {
-    int cn = __popcll(mn), co = __popcll(mo);
-    cnew[s] = cn < p ? cn : p;
-    cold[s] = co < p ? co : p;
-  }
-}
-
-// Reverse candidates grouped by target: s goes into the segment of every
-// forward sample v of s.  Counting down the candidate counters hands out the
-// slots and leaves the counters at zero for the next iteration.
-__global__ __launch_bounds__(kBlock) void k_rev_fill(int64_t n, int p, const int32_t* snew,
-                                                     const int32_t* sold, const int32_t* cnew,
-                                                     const int32_t* cold, uint32_t* rcnt_new,
-                                                     uint32_t* rcnt_old,
-                                                     const uint64_t* roff_new,
-                                                     const uint64_t* roff_old, int32_t* csr_new,
-                                                     int32_t* csr_old) {
-  const int64_t s = wave_global_index();
-  if (s >= n) return;
-  const int lane = lane_id();
-  const int L = 2 * p;
-  if (lane < cnew[s]) {
-    int32_t v = snew[s * L + lane];
-    uint32_t pos = atomicSub(&rcnt_new[v], 1u) - 1u;
-    csr_new[roff_new[v] + pos] = (int32_t)s;
-  }
-  if (lane < cold[s]) {
-    int32_t v = sold[s * L + lane];
-    uint32_t pos = atomicSub(&rcnt_old[v], 1u) - 1u;
-    csr_old[roff_old[v] + pos] = (int32_t)s;
-  }
-}
-
 // Sec. 4.1, reverse part and duplicate removal for one list.  `fwd_raw` is the
 // list row as loaded (its first nf entries are the forward samples), `first` the
 // first 64 reverse candidates (lane < deg).  Of the candidates the 2p - nf with
@@ -577,23 +516,9 @@ hipError_t launch_init_random(const Shape& sh, const DevState& ds, uint64_t seed
 hipError_t launch_sample(const Shape& sh, const DevState& ds, uint64_t seed, uint32_t iter,
                          hipStream_t st) {
   const unsigned grid = blocks_for_waves(sh.n);
-  if (sample_buckets_possible(sh.n)) {
-    // reverse candidates grouped by a two-level counting sort (few global atomics)
-    hipError_t e = launch_sample_buckets(sh, ds, st);
-    if (e != hipSuccess) return e;
-  } else {
-    // very large n: one global atomic per edge for counting, one for placing
-    k_sample_fwd<<<grid, kBlock, 0, st>>>(sh.n, sh.k, sh.p, ds.G, ds.snew, ds.sold, ds.cnew,
-                                          ds.cold, ds.rcnt_new, ds.rcnt_old);
-    hipError_t e = launch_scan(ds.rcnt_new, nullptr, ds.roff_new, nullptr, nullptr, ds.scan_tmp,
-                               sh.n, st);
-    if (e != hipSuccess) return e;
-    e = launch_scan(ds.rcnt_old, nullptr, ds.roff_old, nullptr, nullptr, ds.scan_tmp, sh.n, st);
-    if (e != hipSuccess) return e;
-    k_rev_fill<<<grid, kBlock, 0, st>>>(sh.n, sh.p, ds.snew, ds.sold, ds.cnew, ds.cold,
-                                        ds.rcnt_new, ds.rcnt_old, ds.roff_new, ds.roff_old,
-                                        ds.csr_new, ds.csr_old);
-  }
+  // forward sampling, and the reverse candidates grouped by target (two-level counting sort)
+  hipError_t e = launch_sample_buckets(sh, ds, st);
+  if (e != hipSuccess) return e;
   k_rev_select<<<grid, kBlock, 0, st>>>(
       sh.n, sh.p, hash_base(seed, kTagRevNew), hash_base(seed, kTagRevOld), iter, ds.snew,
       ds.sold, ds.cnew, ds.cold, ds.roff_new, ds.roff_old, ds.csr_new, ds.csr_old, ds.capn,

@@ -38,8 +38,6 @@ struct DevState {
   int32_t* sold;       // n*2p OLD sample lists
   int32_t* cnew;       // n list sizes
   int32_t* cold;       // n
-  uint32_t* rcnt_new;  // n reverse-candidate counts (zero between iterations)
-  uint32_t* rcnt_old;  // n
   uint64_t* roff_new;  // n+1 offsets into csr_new
   uint64_t* roff_old;  // n+1
   int32_t* csr_new;    // n*p reverse candidates grouped by target
@@ -85,7 +83,6 @@ hipError_t launch_join_mfma(const Shape& sh, const DevState& ds, bool merge_mode
 hipError_t launch_pack_i8(const Shape& sh, const DevState& ds, int* bad_flag_dev, hipStream_t st);
 hipError_t launch_init_random_i8(const Shape& sh, const DevState& ds, uint64_t seed,
                                  hipStream_t st);
-bool sample_buckets_possible(int64_t n);
 hipError_t launch_sample_buckets(const Shape& sh, const DevState& ds, hipStream_t st);
 hipError_t launch_update(const Shape& sh, const DevState& ds, hipStream_t st);
 // lists of 65..128 entries (two per lane); the launchers above forward to these

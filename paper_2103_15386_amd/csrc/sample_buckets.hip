@@ -409,18 +409,15 @@ __global__ __launch_bounds__(kCsrBlock) void k_bucket_csr(int64_t n, BucketGeom 
   }
 }
 
-// The bucket layout for n targets, or tb = 0 when n is beyond what one
-// workgroup's LDS can count (then the caller uses per-edge atomics instead).
+// The bucket layout for n <= 2^27 targets: at most 4096 buckets of 2^tb <= 2^15
+// targets (one workgroup's LDS counts a bucket's targets).
 static BucketGeom bucket_geom(int64_t n) {
   BucketGeom g{10, 0, 256};
   while (((n + (1ll << g.tb) - 1) >> g.tb) > kMaxBuckets) ++g.tb;
-  if (g.tb > 15) return BucketGeom{0, 0, 0};
   g.nb = (int)((n + (1ll << g.tb) - 1) >> g.tb);
   g.rows_per_wg = g.nb > 256 ? g.nb : 256;
   return g;
 }
-
-bool sample_buckets_possible(int64_t n) { return bucket_geom(n).tb != 0; }
 
 hipError_t launch_sample_buckets(const Shape& sh, const DevState& ds, hipStream_t st) {
   const BucketGeom g = bucket_geom(sh.n);

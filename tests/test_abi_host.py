@@ -40,7 +40,8 @@ def test_workspace_size_and_parameter_validation(amd):
     assert amd.workspace_bytes(10, 16, 10, 8, amd.L2SQ_F32) == 0      # k >= n
     assert amd.workspace_bytes(4096, 16, 129, 8, amd.L2SQ_F32) == 0   # k > 128
     assert amd.workspace_bytes(4096, 16, 128, 8, amd.L2SQ_F32) > 0
-    assert amd.workspace_bytes((1 << 27) + 1, 16, 65, 8, amd.L2SQ_F32) == 0  # long lists: n <= 2^27
+    assert amd.workspace_bytes((1 << 27) + 1, 16, 10, 8, amd.L2SQ_F32) == 0  # n <= 2^27
+    assert amd.workspace_bytes(1 << 27, 16, 10, 8, amd.L2SQ_F32) > 0
     assert amd.workspace_bytes(4096, 16, 10, 11, amd.L2SQ_F32) == 0   # p > k
     assert amd.workspace_bytes(4096, 16, 40, 33, amd.L2SQ_F32) == 0   # p > 32
     assert amd.workspace_bytes(4096, 0, 10, 8, amd.L2SQ_F32) == 0     # d < 1
