@@ -212,3 +212,44 @@ def test_errors_are_reported_not_fatal():
         amd.Gnnd(torch.zeros(100, 8), 10, 8)  # CPU tensor: no CPU path
     with pytest.raises(amd.GnndError):  # matrix-core path refuses non-integer floats
         amd.Gnnd(x, 10, 8, amd.L2SQ_F32, 42, amd.JOIN_MFMA)
+
+
+def test_build_with_the_delta_rule_stops_where_the_oracle_does():
+    # optional termination (off by default): stop after the first iteration that
+    # admits fewer than delta * n * k entries
+    amd = _amd()
+    x = W.uniform_f32(3000, 12, seed=61)
+    k, p, delta = 12, 8, 0.02
+    ctx = amd.Gnnd(_dev(x), k, p, amd.L2SQ_F32, SEED)
+    last = ctx.build(30, delta=delta)
+    g = og.init_random(x, k, og.L2SQ_F32, SEED)
+    stopped_at = None
+    for it in range(1, 31):
+        st = og.iterate(x, og.L2SQ_F32, g, p, SEED, it)
+        if st["inserts"] < delta * len(x) * k:
+            stopped_at = it
+            break
+    assert stopped_at is not None and 2 < stopped_at < 30
+    assert last["iter"] == stopped_at and last["inserts"] == st["inserts"]
+    _assert_graph_equal(ctx, g, "build with delta")
+    ctx.close()
+
+
+def test_stage_times_are_recorded_per_iteration():
+    amd = _amd()
+    x = W.sift_like_u8(20000, 64, seed=62, n_comp=8)
+    ctx = amd.Gnnd(_dev(x), 16, 16, amd.L2SQ_U8, SEED)
+    ctx.set_profiling(True)
+    torch.cuda.synchronize()
+    import time
+    t0 = time.perf_counter()
+    ctx.build(5, want_stats=False)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    count, ms_sample, ms_join, ms_update = ctx.stage_ms()
+    assert count == 5
+    assert ms_sample > 0 and ms_join > 0 and ms_update > 0
+    assert ms_sample + ms_join + ms_update <= wall_ms
+    count, *_ = ctx.stage_ms()  # reading clears the record
+    assert count == 0
+    ctx.close()
