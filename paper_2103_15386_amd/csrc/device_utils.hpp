@@ -324,6 +324,103 @@ struct VecSrc {
   }
 };
 
+// The same arithmetic one step at a time (one dimension of one pair), for the
+// kernels that walk many pairs through staged chunks of dimensions.
+template <int METRIC>
+struct JoinTraits;
+template <>
+struct JoinTraits<kL2F32> {
+  using elem = float;
+  using acc = float;
+  __device__ static void step(float a, float b, float& s) {
+    float t = a - b;
+    s = __fmaf_rn(t, t, s);
+  }
+  __device__ static uint32_t code(float s) { return ord_f32(s); }
+};
+template <>
+struct JoinTraits<kAngularF32> {
+  using elem = float;
+  using acc = float;
+  __device__ static void step(float a, float b, float& s) { s = __fmaf_rn(a, b, s); }
+  __device__ static uint32_t code(float s) { return ord_f32(1.0f - s); }
+};
+template <>
+struct JoinTraits<kChi2F32> {
+  using elem = float;
+  using acc = float;
+  __device__ static void step(float a, float b, float& s) { s = chi2_term(a, b, s); }
+  __device__ static uint32_t code(float s) { return ord_f32(s); }
+};
+template <>
+struct JoinTraits<kL2U8> {
+  using elem = uint8_t;
+  using acc = int32_t;
+  __device__ static void step(int32_t a, int32_t b, int32_t& s) {
+    int32_t t = a - b;
+    s += __mul24(t, t);
+  }
+  __device__ static uint32_t code(int32_t s) { return ord_i32(s); }
+};
+
+// Canonical distances from object s to one object per lane (`id`, meaningful
+// where `on`).  The 64 rows and the row of s are staged through the wave's LDS
+// tile in chunks of kEvalChunk dimensions with coalesced reads (8 lanes per row
+// chunk), then every lane accumulates its own pair in dimension order: the
+// arithmetic of DistOf<METRIC>::eval, without 64 lanes each walking a row of its
+// own through HBM.  All 64 lanes must call it together.
+constexpr int kEvalChunk = 32;
+constexpr int kEvalStride = kEvalChunk + 1;  // odd stride: lanes walk their rows free of bank conflicts
+constexpr int kEvalTileWords = 65 * kEvalStride;
+
+template <int METRIC>
+__device__ inline uint32_t wave_distances(const VecSrc& vs, uint32_t s, uint32_t id, bool on,
+                                          uint32_t* tile_raw, int lane) {
+  using TR = JoinTraits<METRIC>;
+  using T = typename TR::elem;
+  using ACC = typename TR::acc;
+  ACC* tile = reinterpret_cast<ACC*>(tile_raw);
+  const int d = vs.d;
+  const bool aligned = (d & 3) == 0;
+  const int part = lane & 7, rsel = lane >> 3;
+  ACC acc = 0;
+  for (int d0 = 0; d0 < d; d0 += kEvalChunk) {
+#pragma unroll
+    for (int r0 = 0; r0 < 72; r0 += 8) {  // rows 0..63: the lanes' objects, row 64: s
+      const int r = r0 + rsel;
+      const uint32_t rid = __shfl(id, r & 63, kWave);
+      const int ron = __shfl((int)on, r & 63, kWave);
+      const bool want = r < 64 ? ron != 0 : r == 64;
+      if (want) {
+        const T* src = vs.row<T>(r < 64 ? rid : s);
+        const int j = d0 + part * 4;
+        ACC v[4] = {0, 0, 0, 0};
+        if (sizeof(T) == 4 && aligned && j + 3 < d) {
+          const float4 f = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(src) + j);
+          v[0] = (ACC)f.x; v[1] = (ACC)f.y; v[2] = (ACC)f.z; v[3] = (ACC)f.w;
+        } else {
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            if (j + q < d) v[q] = (ACC)src[j + q];
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) tile[r * kEvalStride + part * 4 + q] = v[q];
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const int width = d - d0 < kEvalChunk ? d - d0 : kEvalChunk;
+    if (on)
+      for (int j = 0; j < width; ++j)
+        TR::step(tile[64 * kEvalStride + j], tile[lane * kEvalStride + j], acc);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  }
+  return TR::code(acc);
+}
+
 // Numbering inside one merge (Sec. 5.1 shards).  The two sets are the ranges
 // [base1, base1 + n1) and [base2, base2 + n2) of a larger collection; inside
 // the merge S1 is 0..n1-1, S2 is n1..n-1, and any other object (a list entry

@@ -31,17 +31,14 @@ template <int METRIC>
 __global__ __launch_bounds__(kBlock) void k_init_random(VecSrc vs, int64_t n, int k,
                                                         uint64_t base_hash, uint64_t* G,
                                                         NodeMeta* meta) {
-  using D = DistOf<METRIC>;
-  using T = typename D::elem;
+  __shared__ uint32_t tile[kWavesPerBlock][kEvalTileWords];
   const int64_t s = wave_global_index();
   if (s >= n) return;
   const int lane = lane_id();
   uint32_t id = draw_distinct(base_hash, (uint32_t)s, k, (uint32_t)n, 0u, (uint32_t)s, lane);
-  uint64_t e = kKeyMax;
-  if (lane < k) {
-    uint32_t code = D::eval(vs.row<T>((uint32_t)s), vs.row<T>(id), vs.d);
-    e = make_entry(code, id, 1u);
-  }
+  const uint32_t code =
+      wave_distances<METRIC>(vs, (uint32_t)s, id, lane < k, tile[threadIdx.x >> 6], lane);
+  uint64_t e = lane < k ? make_entry(code, id, 1u) : kKeyMax;
   e = wave_sort(e, lane);
   if (lane < k) G[s * k + lane] = e;
   if (lane == k - 1) meta[s].kth = entry_code(e);
@@ -275,8 +272,7 @@ __global__ __launch_bounds__(kBlock) void k_merge_init(VecSrc vs, int64_t n, Mer
                                                        const void* dist1, const int32_t* ids2,
                                                        const void* dist2, uint64_t* G,
                                                        NodeMeta* meta, uint64_t* aside) {
-  using D = DistOf<METRIC>;
-  using T = typename D::elem;
+  __shared__ uint32_t tile[kWavesPerBlock][kEvalTileWords];
   const int64_t s = wave_global_index();
   if (s >= n) return;
   const int lane = lane_id();
@@ -299,13 +295,11 @@ __global__ __launch_bounds__(kBlock) void k_merge_init(VecSrc vs, int64_t n, Mer
                                       0xffffffffu, lane);
   const int src = lane - keep;
   const uint32_t did = __shfl(draw, src < 0 ? 0 : src, kWave);
+  const uint32_t code = wave_distances<METRIC>(vs, (uint32_t)s, did, lane >= keep && lane < k,
+                                               tile[threadIdx.x >> 6], lane);
   uint64_t e = kKeyMax;
-  if (lane < keep) {
-    e = make_entry(code_in, id_in, 0u);
-  } else if (lane < k) {
-    uint32_t code = D::eval(vs.row<T>((uint32_t)s), vs.row<T>(did), vs.d);
-    e = make_entry(code, did, 1u);
-  }
+  if (lane < keep) e = make_entry(code_in, id_in, 0u);
+  else if (lane < k) e = make_entry(code, did, 1u);
   e = wave_sort(e, lane);
   if (lane < k) G[s * k + lane] = e;
   if (lane == k - 1) meta[s].kth = entry_code(e);

@@ -22,43 +22,6 @@ constexpr int kDC = 64;       // dimensions per staged chunk
 constexpr int kLD = kDC + 4;  // LDS row stride (elements), keeps 16-byte alignment
 constexpr int kDLD = 129;     // row stride of the distance matrix in LDS
 
-template <int METRIC>
-struct JoinTraits;
-template <>
-struct JoinTraits<kL2F32> {
-  using elem = float;
-  using acc = float;
-  __device__ static void step(float a, float b, float& s) {
-    float t = a - b;
-    s = __fmaf_rn(t, t, s);
-  }
-  __device__ static uint32_t code(float s) { return ord_f32(s); }
-};
-template <>
-struct JoinTraits<kAngularF32> {
-  using elem = float;
-  using acc = float;
-  __device__ static void step(float a, float b, float& s) { s = __fmaf_rn(a, b, s); }
-  __device__ static uint32_t code(float s) { return ord_f32(1.0f - s); }
-};
-template <>
-struct JoinTraits<kChi2F32> {
-  using elem = float;
-  using acc = float;
-  __device__ static void step(float a, float b, float& s) { s = chi2_term(a, b, s); }
-  __device__ static uint32_t code(float s) { return ord_f32(s); }
-};
-template <>
-struct JoinTraits<kL2U8> {
-  using elem = uint8_t;
-  using acc = int32_t;
-  __device__ static void step(int32_t a, int32_t b, int32_t& s) {
-    int32_t t = a - b;
-    s += __mul24(t, t);
-  }
-  __device__ static uint32_t code(int32_t s) { return ord_i32(s); }
-};
-
 // Stage dimensions [d0, d0 + kDC) of one vector into an LDS row (as the
 // accumulation type), zero beyond the vector's end.  16 threads per row.
 template <typename ACC>

@@ -127,17 +127,17 @@ template <int METRIC>
 __global__ __launch_bounds__(kWB) void k_init_random_wide(VecSrc vs, int64_t n, int k,
                                                           uint64_t base_hash, uint64_t* G,
                                                           NodeMeta* meta) {
-  using D = DistOf<METRIC>;
-  using T = typename D::elem;
+  __shared__ uint32_t tile[kWavesPerWB][kEvalTileWords];
   const int64_t s = wide_wave_index();
   if (s >= n) return;
   const int lane = lane_id();
   uint32_t id0, id1;
   draw_distinct_wide(base_hash, (uint32_t)s, k, (uint32_t)n, 0u, (uint32_t)s, lane, id0, id1);
-  const T* mine = vs.row<T>((uint32_t)s);
-  uint64_t lo = make_entry(D::eval(mine, vs.row<T>(id0), vs.d), id0, 1u);
-  uint64_t hi = kKeyMax;
-  if (lane + kWave < k) hi = make_entry(D::eval(mine, vs.row<T>(id1), vs.d), id1, 1u);
+  uint32_t* my_tile = tile[threadIdx.x >> 6];
+  const uint32_t c0 = wave_distances<METRIC>(vs, (uint32_t)s, id0, true, my_tile, lane);
+  const uint32_t c1 = wave_distances<METRIC>(vs, (uint32_t)s, id1, lane + kWave < k, my_tile, lane);
+  uint64_t lo = make_entry(c0, id0, 1u);
+  uint64_t hi = lane + kWave < k ? make_entry(c1, id1, 1u) : kKeyMax;
   sort128(lo, hi, lane);
   G[s * k + lane] = lo;
   if (lane + kWave < k) G[s * k + kWave + lane] = hi;
@@ -194,8 +194,7 @@ __global__ __launch_bounds__(kWB) void k_merge_init_wide(VecSrc vs, int64_t n, M
                                                          const void* dist1, const int32_t* ids2,
                                                          const void* dist2, uint64_t* G,
                                                          NodeMeta* meta, uint64_t* aside) {
-  using D = DistOf<METRIC>;
-  using T = typename D::elem;
+  __shared__ uint32_t tile[kWavesPerWB][kEvalTileWords];
   const int64_t s = wide_wave_index();
   if (s >= n) return;
   const int lane = lane_id();
@@ -220,9 +219,9 @@ __global__ __launch_bounds__(kWB) void k_merge_init_wide(VecSrc vs, int64_t n, M
                                       (uint32_t)(first ? n - n1 : n1), first ? (uint32_t)n1 : 0u,
                                       0xffffffffu, lane);
   uint64_t lo = lane < keep ? in0 : kKeyMax;
-  uint64_t hi = kKeyMax;
-  if (lane < fill)
-    hi = make_entry(D::eval(vs.row<T>((uint32_t)s), vs.row<T>(draw), vs.d), draw, 1u);
+  const uint32_t cd =
+      wave_distances<METRIC>(vs, (uint32_t)s, draw, lane < fill, tile[threadIdx.x >> 6], lane);
+  uint64_t hi = lane < fill ? make_entry(cd, draw, 1u) : kKeyMax;
   sort128(lo, hi, lane);
   G[s * k + lane] = lo;
   if (lane + kWave < k) G[s * k + kWave + lane] = hi;
