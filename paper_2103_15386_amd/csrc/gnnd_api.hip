@@ -23,7 +23,7 @@ thread_local std::string g_last_error = "";
 
 struct Layout {
   size_t off_G, off_kth, off_snew, off_sold, off_cnew, off_cold, off_ron,
-      off_roo, off_csn, off_cso, off_capn, off_capo, off_pcnt, off_poff, off_bins, off_scan,
+      off_roo, off_csn, off_cso, off_capn, off_capo, off_pslot, off_poff, off_bins, off_scan,
       off_cnt, off_snap, off_aside, off_shadow, off_norms, off_flag, off_bkc, off_bko, total;
 };
 
@@ -75,7 +75,7 @@ Layout make_layout(const gnnd_params* q, bool with_aside) {
   L.off_cso = take(n * p * 4);
   L.off_capn = take(n * 4);
   L.off_capo = take(n * 4);
-  L.off_pcnt = take(n * 8);
+  L.off_pslot = take(n * 8);
   L.off_poff = take((n + 1) * 8);
   const size_t slots_per_node =
       q->update_mode == GNND_UPDATE_ALL_PAIRS ? 2 * p * (6 * p - 1) : 6 * p;
@@ -144,7 +144,7 @@ void bind(gnnd_ctx* c, const Layout& L) {
   d.roff_old = (uint64_t*)(w + L.off_roo);
   d.csr_new = (int32_t*)(w + L.off_csn);
   d.csr_old = (int32_t*)(w + L.off_cso);
-  d.pslot = (uint64_t*)(w + L.off_pcnt);
+  d.pslot = (uint64_t*)(w + L.off_pslot);
   d.poff = (uint64_t*)(w + L.off_poff);
   d.capn = (uint32_t*)(w + L.off_capn);
   d.capo = (uint32_t*)(w + L.off_capo);
@@ -193,9 +193,9 @@ int create_impl(gnnd_ctx** out, const gnnd_params* prm, const void* vec_a, const
   c->prof_count = 0;
   c->have_prof = false;
   bind(c, L);
-  // counters that must start at zero (they return to zero after every iteration)
+  // the statistics counters start at zero; the slot words read "nothing received" until the
+  // first sampling stage writes them
   hipError_t e = launch_zero_u32((uint32_t*)c->ds.pslot, 2 * (size_t)prm->n, c->stream);
-  if (e == hipSuccess) e = launch_zero_u32(c->ds.bk_cnt, 2 * 4096, c->stream);
   if (e == hipSuccess)
     e = launch_zero_u32((uint32_t*)c->ds.counters, (size_t)kStripes * C_SLOTS * 2, c->stream);
   if (e != hipSuccess) {

@@ -51,7 +51,7 @@ struct DevState {
   uint64_t* counters;  // kStripes * C_SLOTS
   uint64_t* aside;     // merge only: n * floor(k/2) set-aside entries
   int8_t* shadow;      // matrix-core path: n rows of dpad int8 (value - 128), zero padded
-  uint32_t* bk_cnt;    // 2 x 4096 bucket counters of the bucketed reverse-candidate sort
+  uint32_t* bk_cnt;    // 2 x 4096 bucket sizes of the bucketed reverse-candidate sort
   uint64_t* bk_off;    // 2 x 4097 bucket offsets
 
 };

@@ -194,13 +194,12 @@ __global__ __launch_bounds__(kSB) void k_wg_scan(int W, int rows, uint32_t* wg_h
   if (lane == 0) bcnt[c] = carry;
 }
 
-// boff[kind][0..nb] = exclusive scan of bcnt[kind][0..nb); the counters become
-// the buckets' write cursors (zero) for the scatter pass.
-__global__ __launch_bounds__(kCsrBlock) void k_bucket_scan(int nb, uint32_t* bcnt,
+// boff[kind][0..nb] = exclusive scan of the bucket sizes bcnt[kind][0..nb).
+__global__ __launch_bounds__(kCsrBlock) void k_bucket_scan(int nb, const uint32_t* bcnt,
                                                            uint64_t* boff) {
   __shared__ uint64_t part[kCsrBlock];
   for (int kind = 0; kind < 2; ++kind) {
-    uint32_t* c = bcnt + kind * nb;
+    const uint32_t* c = bcnt + kind * nb;
     uint64_t* o = boff + kind * (nb + 1);
     const int per = (nb + kCsrBlock - 1) / kCsrBlock;
     const int lo = threadIdx.x * per;
@@ -222,7 +221,6 @@ __global__ __launch_bounds__(kCsrBlock) void k_bucket_scan(int nb, uint32_t* bcn
     for (int i = lo; i < lo + per && i < nb; ++i) {
       o[i] = run;
       run += c[i];
-      c[i] = 0;
     }
     __syncthreads();
   }
@@ -327,7 +325,7 @@ static size_t staged_lds_bytes(const BucketGeom& g) {
 // One workgroup per (bucket, kind): counting sort of the bucket's edges by
 // target.  LDS holds one counter per target of the bucket (dynamic size).
 __global__ __launch_bounds__(kCsrBlock) void k_bucket_csr(int64_t n, BucketGeom g,
-                                                          const uint64_t* boff, uint32_t* bcnt,
+                                                          const uint64_t* boff,
                                                           const uint2* edges_new,
                                                           const uint2* edges_old,
                                                           uint64_t* roff_new, uint64_t* roff_old,
@@ -391,7 +389,6 @@ __global__ __launch_bounds__(kCsrBlock) void k_bucket_csr(int64_t n, BucketGeom 
     run += c;
   }
   if (b == g.nb - 1 && threadIdx.x == 0) roff[n] = bo[g.nb];
-  if (threadIdx.x == 0) bcnt[kind * g.nb + b] = 0;  // the next iteration counts from zero
   __syncthreads();
   for (uint64_t e0 = beg + threadIdx.x; e0 < end; e0 += kAtOnce * kCsrBlock) {
     uint2 ed[kAtOnce];
@@ -454,7 +451,7 @@ hipError_t launch_sample_buckets(const Shape& sh, const DevState& ds, hipStream_
   k_fwd_scatter_staged<<<grid, kStBlock, staged_lds_bytes(g), st>>>(
       sh.n, sh.p, g, ds.snew, ds.sold, wg_hist, boff, edges_new, edges_old);
   k_bucket_csr<<<dim3((unsigned)g.nb, 2), kCsrBlock, (size_t)4 << g.tb, st>>>(
-      sh.n, g, boff, bcnt, edges_new, edges_old, ds.roff_new, ds.roff_old, ds.csr_new,
+      sh.n, g, boff, edges_new, edges_old, ds.roff_new, ds.roff_old, ds.csr_new,
       ds.csr_old);
   return hipGetLastError();
 }
