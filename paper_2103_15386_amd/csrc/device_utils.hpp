@@ -446,20 +446,31 @@ struct MergeIds {
 // the slots before it; after kHashAttempts failures it walks to the next free
 // id cyclically.  Wave-uniform loop; returns the id of slot `lane` (lanes >=
 // count: undefined).
+// First attempt of slot `lane`.  When the first attempts of all slots are
+// pairwise distinct and none is `forbid`, the slot-by-slot rule accepts every
+// one of them as it stands (a slot only ever looks at the slots before it).
+__device__ inline uint32_t draw_first(uint64_t base_hash, uint32_t s, uint32_t range,
+                                      uint32_t base, int lane) {
+  return bounded(hash3(base_hash, s, (uint32_t)lane, 0u), range) + base;
+}
+__device__ inline uint32_t draw_slot_by_slot(uint64_t base_hash, uint32_t s, int count,
+                                             uint32_t range, uint32_t base, uint32_t forbid,
+                                             int lane);
 __device__ inline uint32_t draw_distinct(uint64_t base_hash, uint32_t s, int count,
                                          uint32_t range, uint32_t base, uint32_t forbid,
                                          int lane) {
-  // All first attempts at once, one slot per lane: when they are pairwise
-  // distinct and none is `forbid`, the slot-by-slot rule accepts every one of
-  // them as it stands (a slot only ever looks at the slots before it).
-  const uint32_t first = bounded(hash3(base_hash, s, (uint32_t)lane, 0u), range) + base;
+  const uint32_t first = draw_first(base_hash, s, range, base, lane);
   bool clash_any = lane < count && first == forbid;
   for (int j = 0; j + 1 < count; ++j) {
     const uint32_t cj = (uint32_t)__builtin_amdgcn_readlane((int)first, j);
     clash_any |= lane > j && lane < count && first == cj;
   }
   if (__ballot(clash_any) == 0ull) return first;
-  // otherwise slot by slot
+  return draw_slot_by_slot(base_hash, s, count, range, base, forbid, lane);
+}
+__device__ inline uint32_t draw_slot_by_slot(uint64_t base_hash, uint32_t s, int count,
+                                             uint32_t range, uint32_t base, uint32_t forbid,
+                                             int lane) {
   uint32_t mine = 0xffffffffu;
   for (int j = 0; j < count; ++j) {
     uint32_t cand = 0;

@@ -69,12 +69,14 @@ __global__ __launch_bounds__(256) void k_init_random_i8(const int8_t* __restrict
   const int lane = lane_id();
   const int64_t s = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (s >= n) return;
-  const uint32_t id = draw_distinct(base_hash, (uint32_t)s, k, (uint32_t)n, 0u, (uint32_t)s, lane);
   const int C = dpad >> 4, per_load = kWave / C;
   const int grp = lane / C, sub = lane - grp * C;
   const bool lane_used = grp < per_load;  // C = 6 leaves four lanes without a group
+  const bool pow2 = (C & (C - 1)) == 0;
   const v4i x = *reinterpret_cast<const v4i*>(shadow + s * dpad + 16 * sub);
   const int32_t norm_s = meta[s].norm;
+  // the list for one id per lane, ascending
+  auto list_of = [&](uint32_t id) {
   int32_t dot = 0, norm_id = 0;
   if (lane < k) norm_id = meta[id].norm;
   for (int r0 = 0; r0 < k; r0 += per_load) {
@@ -88,10 +90,16 @@ __global__ __launch_bounds__(256) void k_init_random_i8(const int8_t* __restrict
       for (int t = 0; t < 4; ++t) part = __builtin_amdgcn_sdot4(x[t], y[t], part, false);
     }
     int32_t total = part;
-    for (int off = 1; off < C; ++off) {
-      int o = sub + off;
-      o = o >= C ? o - C : o;
-      total += __shfl(part, (grp * C + o) & 63, kWave);
+    if (pow2) {  // groups are aligned blocks of 2, 4 or 8 lanes: butterfly sum
+      if (C > 1) total += (int32_t)xor_lanes((uint32_t)total, 1, lane);
+      if (C > 2) total += (int32_t)xor_lanes((uint32_t)total, 2, lane);
+      if (C > 4) total += (int32_t)xor_lanes((uint32_t)total, 4, lane);
+    } else {
+      for (int off = 1; off < C; ++off) {
+        int o = sub + off;
+        o = o >= C ? o - C : o;
+        total += __shfl(part, (grp * C + o) & 63, kWave);
+      }
     }
     // neighbour j = lane sits in group lane - r0
     const int32_t got = __shfl(total, ((lane - r0) * C) & 63, kWave);
@@ -102,7 +110,17 @@ __global__ __launch_bounds__(256) void k_init_random_i8(const int8_t* __restrict
     const int32_t dist = norm_s + norm_id - 2 * dot;
     e = make_entry(FCODE ? ord_f32((float)dist) : ord_i32(dist), id, 1u);
   }
-  e = wave_sort(e, lane);
+  return wave_sort_upto(e, lane, k);
+  };
+  // First attempts of all slots at once.  Whether they are valid (pairwise distinct,
+  // none the node itself) shows after the sort: equal ids have equal distances and
+  // end up next to each other.  Only then the slot-by-slot rule has to run.
+  uint64_t e = list_of(draw_first(base_hash, (uint32_t)s, (uint32_t)n, 0u, lane));
+  const uint64_t prev = __shfl_up(e, 1, kWave);
+  const bool bad = lane < k && (entry_id(e) == (uint32_t)s ||
+                                (lane > 0 && entry_id(e) == entry_id(prev)));
+  if (__ballot(bad) != 0ull)
+    e = list_of(draw_slot_by_slot(base_hash, (uint32_t)s, k, (uint32_t)n, 0u, (uint32_t)s, lane));
   if (lane < k) G[s * k + lane] = e;
   if (lane == k - 1) meta[s].kth = entry_code(e);
 }
