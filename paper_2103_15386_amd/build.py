@@ -45,7 +45,28 @@ def build_library(force=False, verbose=False):
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.run(cmd, check=True)
+    build_abi_demo(force or any(rebuilt), verbose)
     return LIB
+
+
+DEMO = os.path.join(HERE, "abi_demo")
+
+
+def build_abi_demo(force=False, verbose=False):
+    """The plain-C caller of the library (csrc/abi_demo.c), compiled by gcc as C11:
+    proof that the boundary needs neither C++ nor Python."""
+    src = os.path.join(CSRC, "abi_demo.c")
+    if not force and os.path.exists(DEMO) and os.path.getmtime(DEMO) >= os.path.getmtime(src):
+        return DEMO
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=c11", "-O2", "-Wall", "-D__HIP_PLATFORM_AMD__",
+           "-I", os.path.join(os.path.dirname(HERE), "include"), "-I", os.path.join(rocm, "include"),
+           src, "-o", DEMO, "-L", HERE, "-lgnnd_hip", "-L", os.path.join(rocm, "lib"),
+           "-lamdhip64", "-Wl,-rpath,$ORIGIN", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return DEMO
 
 
 if __name__ == "__main__":
