@@ -136,3 +136,41 @@ def test_append_rejects_a_batch_smaller_than_k():
     dist = torch.zeros((50, 16), dtype=torch.float32, device="cuda")
     with pytest.raises(amd.GnndError):
         amd.gnnd_append(x[:50].contiguous(), ids, dist, x[50:].contiguous(), 16, 8)
+
+
+@pytest.mark.parametrize("case_seed", list(range(3001, 3013)))
+def test_random_merge_configurations_match_oracle(case_seed):
+    # seeded draws of (n1, n2, d, k, p, metric, iterations); the inputs are graphs
+    # the oracle built with a few iterations (not exact ones), in collection ids
+    import paper_2103_15386_amd as amd
+    rng = np.random.default_rng(case_seed)
+    metric = int(rng.choice([og.L2SQ_F32, og.ANGULAR_F32, og.L2SQ_U8, og.CHI2_F32]))
+    k = int(rng.choice([2, 5, 16, 31, 32, 40, 64, 65, 100, 128]))
+    p = int(rng.integers(1, min(k, 32) + 1))
+    n1 = int(rng.integers(k + 1, 800))
+    n2 = int(rng.integers(k + 1, 800))
+    d = int(rng.choice([2, 7, 16, 33, 64, 128]))
+    iters = int(rng.integers(0, 4))
+    seed = int(rng.integers(1, 1 << 30))
+    n = n1 + n2
+    if metric == og.L2SQ_U8:
+        x = W.sift_like_u8(n, d, seed=seed, n_comp=4)
+    elif metric == og.ANGULAR_F32:
+        x = W.deep_like_f32(n, d, seed=seed, n_comp=4)
+    elif metric == og.CHI2_F32:
+        x = W.gist_like_f32(n, d, seed=seed, n_comp=4)
+    else:
+        x = W.small_integer_f32(n, d, seed=seed) if rng.random() < 0.5 else \
+            W.uniform_f32(n, d, seed=seed)
+    algo_seed = int(rng.integers(0, 1 << 40))
+    g1, _ = og.build(np.ascontiguousarray(x[:n1]), k, p, metric, algo_seed + 1, 2)
+    g2, _ = og.build(np.ascontiguousarray(x[n1:]), k, p, metric, algo_seed + 2, 2)
+    g2.ids += n1
+    want, _ = og.merge(x, n1, k, p, metric, algo_seed, g1, g2, iters)
+    dt = np.int32 if metric == og.L2SQ_U8 else np.float32
+    ids, dist = amd.gnnd_merge(_dev(x[:n1]), _dev(x[n1:]), _dev(g1.ids), _dev(g1.dist.astype(dt)),
+                               _dev(g2.ids), _dev(g2.dist.astype(dt)), k, p, metric, algo_seed,
+                               iters)
+    what = f"n1={n1} n2={n2} d={d} k={k} p={p} metric={metric} iters={iters}"
+    assert (ids.cpu().numpy() == want.ids).all(), what
+    assert (dist.cpu().numpy().astype(np.float64) == want.dist).all(), what

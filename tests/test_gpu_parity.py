@@ -275,3 +275,42 @@ def test_the_library_serves_a_plain_c_program():
     r2 = subprocess.run([exe, "20000", "16", "16", "8", "8"], capture_output=True, text=True,
                         timeout=120)
     assert r2.stdout == r.stdout  # deterministic
+
+
+def _random_case(rng):
+    metric = int(rng.choice([og.L2SQ_F32, og.ANGULAR_F32, og.L2SQ_U8, og.CHI2_F32]))
+    k = int(rng.choice([2, 3, 7, 16, 31, 32, 33, 50, 64, 65, 90, 128]))
+    p = int(rng.integers(1, min(k, 32) + 1))
+    n = int(rng.integers(k + 2, 1400))
+    d = int(rng.choice([1, 2, 3, 5, 8, 17, 32, 33, 64, 100, 128, 131]))
+    seed = int(rng.integers(1, 1 << 30))
+    if metric == og.L2SQ_U8:
+        x = W.sift_like_u8(n, d, seed=seed, n_comp=4)
+    elif metric == og.ANGULAR_F32:
+        x = W.deep_like_f32(n, d, seed=seed, n_comp=4)
+    elif metric == og.CHI2_F32:
+        x = W.gist_like_f32(n, d, seed=seed, n_comp=4)
+    else:
+        x = W.uniform_f32(n, d, seed=seed) if rng.random() < 0.5 else \
+            W.small_integer_f32(n, d, seed=seed)  # the second kind takes the matrix-core path
+    return x, metric, k, p
+
+
+@pytest.mark.parametrize("case_seed", list(range(2001, 2025)))
+def test_random_configurations_match_oracle(case_seed):
+    # seeded draws of (n, d, k, p, metric, data): three iterations, whole graph compared
+    amd = _amd()
+    rng = np.random.default_rng(case_seed)
+    x, metric, k, p = _random_case(rng)
+    algo_seed = int(rng.integers(0, 1 << 40))
+    ctx = amd.Gnnd(_dev(x), k, p, metric, algo_seed)
+    ctx.init_random()
+    g = og.init_random(x, k, metric, algo_seed)
+    _assert_graph_equal(ctx, g, f"init {x.shape} k={k} p={p} metric={metric}")
+    for it in range(1, 4):
+        st = ctx.iterate()
+        want = og.iterate(x, metric, g, p, algo_seed, it)
+        _assert_graph_equal(ctx, g, f"iteration {it} {x.shape} k={k} p={p} metric={metric}")
+        for key in ("inserts", "dist_evals", "sum_new", "sum_old", "proposals"):
+            assert st[key] == want[key], (key, st, x.shape, k, p, metric)
+    ctx.close()
