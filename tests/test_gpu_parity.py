@@ -314,3 +314,26 @@ def test_random_configurations_match_oracle(case_seed):
         for key in ("inserts", "dist_evals", "sum_new", "sum_old", "proposals"):
             assert st[key] == want[key], (key, st, x.shape, k, p, metric)
     ctx.close()
+
+
+def test_work_runs_on_the_stream_it_is_given():
+    # the context enqueues on the caller's stream (here a side stream of torch's,
+    # default priority); the result equals the default-stream one and arrives on
+    # that stream - an event recorded on it covers the whole build
+    amd = _amd()
+    x = W.sift_like_u8(30000, 64, seed=63, n_comp=8)
+    xd = _dev(x)
+    ids_a, dist_a, ctx_a = amd.gnnd_build(xd, 16, 16, amd.L2SQ_U8, SEED, iters=4)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        ctx_b = amd.Gnnd(xd, 16, 16, amd.L2SQ_U8, SEED)
+        assert ctx_b.prm.stream == side.cuda_stream
+        ctx_b.build(4, want_stats=False)
+        ids_b, dist_b = ctx_b.graph()
+        done = torch.cuda.Event()
+        done.record(side)
+    done.synchronize()
+    assert torch.equal(ids_a, ids_b) and torch.equal(dist_a, dist_b)
+    ctx_a.close()
+    ctx_b.close()
