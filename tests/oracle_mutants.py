@@ -36,6 +36,9 @@ muts = [
  ("all-pairs same id not skipped", "        if (N[a] == O[b]) continue;\n        if (split >= 0", "        if (split >= 0"),
  ("all-pairs old x old evaluated", "        qu[m] = N[a]; qv[m] = O[b]; qd[m] = dist; ++m;\n        qu[m] = O[b]; qv[m] = N[a]; qd[m] = dist; ++m;", "        qu[m] = N[a]; qv[m] = O[b]; qd[m] = dist; ++m;\n        qu[m] = O[b]; qv[m] = O[b > 0 ? b - 1 : 0]; qd[m] = dist; ++m;"),
  ("update rows stride", "return og_update_rows(n, k, 6 * p, ids, dist, isnew, pu, pv, pd, pcnt);", "return og_update_rows(n, k, 6 * p + 1, ids, dist, isnew, pu, pv, pd, pcnt);"),
+ ("chi2 divides by the difference", "      acc = acc + sq / sum;", "      acc = acc + sq / (diff != 0.0f ? diff : 1.0f);"),
+ ("chi2 fused", "      const float sq = diff * diff;\n      acc = acc + sq / sum;", "      acc = fmaf(diff, diff / sum, acc);"),
+ ("chi2 counts empty dimensions", "    if (sum > 0.0f) {\n      const float sq = diff * diff;", "    if (sum >= 0.0f) {\n      const float sq = diff * diff;"),
  ("classic inserts one side only", "        ins += (uint64_t)og_insert_one(k, ids + (int64_t)N[b] * k, dist + (int64_t)N[b] * k,\n                                       isnew + (int64_t)N[b] * k, N[a], dd);\n", ""),
 ]
 root=os.path.dirname(os.path.dirname(os.path.abspath(__file__))); tmp="/tmp/gnnd_oracle_mutants"
