@@ -75,21 +75,29 @@ __global__ __launch_bounds__(kJB) void k_join_valu(
   using ACC = typename TR::acc;
   __shared__ __attribute__((aligned(16))) ACC tile[128 * kLD];
   __shared__ int32_t ids[128];
+  // per sample the nearest partner: NEW towards NEW, NEW towards OLD, OLD towards NEW
+  __shared__ uint64_t nearest[192];
+  __shared__ uint32_t pair_count;
   static_assert(128 * kLD >= 64 * kDLD, "distance matrix must fit in the staging tile");
 
   const int64_t s = blockIdx.x;
   const int tid = threadIdx.x;
   const int L = 2 * p;
+  const int wave = tid >> 6, lane = tid & 63;
+  // Wavefronts 0 and 1 each hold the NEW sample, wavefront 2 the OLD sample, one
+  // object per lane; these lanes later hand on that object's result, so the
+  // threshold of its list is requested now and arrives behind the staging.
+  int32_t self = -1;
+  if (wave < 3 && lane < L) self = (wave < 2 ? snew : sold)[s * L + lane];
   const int nn = cnew[s], no = cold[s];
-
-  if (tid < 128) {
-    int32_t id = -1;
-    if (tid < 64) {
-      if (tid < nn) id = snew[s * L + tid];
-    } else if (tid - 64 < no) {
-      id = sold[s * L + tid - 64];
-    }
-    ids[tid] = id;
+  if (lane >= (wave < 2 ? nn : no)) self = -1;
+  // nothing farther than the last entry of the destination list can enter it
+  const uint32_t kth_self = self >= 0 ? meta[self].kth : 0u;
+  if (wave == 0) ids[lane] = self;
+  else if (wave == 2) ids[64 + lane] = self;
+  if (!ALL) {
+    if (tid < 192) nearest[tid] = kKeyMax;
+    if (tid == 0) pair_count = 0;
   }
   const bool do_nn = !merge_mode && nn > 1;
   if (nn == 0 || (!do_nn && no == 0)) return;  // nothing to evaluate
@@ -167,37 +175,101 @@ __global__ __launch_bounds__(kJB) void k_join_valu(
     __syncthreads();
   }
 
-  // distances (as order-preserving codes) to LDS: Dm[row][col], col < 64 NEW, >= 64 OLD
+  const int64_t split = vs.split;
   uint32_t* Dm = reinterpret_cast<uint32_t*>(tile);
+  if constexpr (ALL) {
+    // distances (as order-preserving codes) to LDS: Dm[row][col], col < 64 NEW, >= 64 OLD
 #pragma unroll
-  for (int r = 0; r < 4; ++r)
+    for (int r = 0; r < 4; ++r)
 #pragma unroll
-    for (int c = 0; c < 8; ++c) {
-      const bool on = r < RB && (c < 4 ? (do_nn && c <= r) : (c - 4 < CO));
-      if (on) {
-        const int col = c < 4 ? (tx + 16 * c) : (64 + tx + 16 * (c - 4));
-        Dm[(ty + 16 * r) * kDLD + col] = TR::code(acc[r][c]);
+      for (int c = 0; c < 8; ++c) {
+        const bool on = r < RB && (c < 4 ? (do_nn && c <= r) : (c - 4 < CO));
+        if (on) {
+          const int col = c < 4 ? (tx + 16 * c) : (64 + tx + 16 * (c - 4));
+          Dm[(ty + 16 * r) * kDLD + col] = TR::code(acc[r][c]);
+        }
+      }
+  } else {
+    // Nearest-object search straight from the register tiles.  A thread holds
+    // rows R = ty + 16r and columns tx + 16c: the minimum along a row is
+    // completed over the 16 lanes that share ty, the minimum along a column
+    // over the lanes of the wavefront that share tx and then over the four
+    // wavefronts through LDS.  Keys are (distance code, partner id), so equal
+    // distances resolve to the smaller id whatever the order of reduction.
+    int32_t idc[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) idc[c] = ids[c < 4 ? (tx + 16 * c) : (64 + tx + 16 * (c - 4))];
+    uint64_t down[8];  // per column: nearest row object seen by this thread
+#pragma unroll
+    for (int c = 0; c < 8; ++c) down[c] = kKeyMax;
+    uint32_t pairs = 0;  // NEW x OLD pairs that count as evaluated
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      if (r < RB) {  // uniform over the workgroup
+        const int R = ty + 16 * r;
+        const int32_t idr = ids[R];
+        uint64_t to_new = kKeyMax, to_old = kKeyMax;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+          const bool on = c < 4 ? (do_nn && c <= r) : (c - 4 < CO);
+          if (!on) continue;
+          const int32_t other = idc[c];
+          bool ok = idr >= 0 && other >= 0;
+          if (c < 4) {
+            ok = ok && (c < r || tx != ty);  // the diagonal block holds both orders of a pair
+          } else {
+            ok = ok && other != idr;
+            if (merge_mode) ok = ok && (((int64_t)idr < split) != ((int64_t)other < split));
+          }
+          if (!ok) continue;
+          const uint64_t code = (uint64_t)TR::code(acc[r][c]) << 32;
+          const uint64_t here = code | (uint32_t)other, there = code | (uint32_t)idr;
+          if (c < 4) {
+            to_new = vmin(to_new, here);
+            if (c < r) down[c] = vmin(down[c], there);
+          } else {
+            ++pairs;
+            to_old = vmin(to_old, here);
+            down[c] = vmin(down[c], there);
+          }
+        }
+#pragma unroll
+        for (int j = 1; j < 16; j <<= 1) {
+          to_new = vmin(to_new, xor_lanes(to_new, j, lane));
+          to_old = vmin(to_old, xor_lanes(to_old, j, lane));
+        }
+        if (tx == 0) {
+          if (to_new != kKeyMax) atomicMin(reinterpret_cast<unsigned long long*>(&nearest[R]),
+                                           (unsigned long long)to_new);
+          if (to_old != kKeyMax) nearest[64 + R] = to_old;  // rows have one writer
+        }
       }
     }
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      const bool on = c < 4 ? (do_nn && c + 1 < RB) : (c - 4 < CO);
+      if (on) {  // uniform over the workgroup
+        uint64_t v = down[c];
+        v = vmin(v, xor_lanes(v, 16, lane));
+        v = vmin(v, xor_lanes(v, 32, lane));
+        if (ty == (wave << 2) && v != kKeyMax)
+          atomicMin(reinterpret_cast<unsigned long long*>(
+                        &nearest[c < 4 ? (tx + 16 * c) : (128 + tx + 16 * (c - 4))]),
+                    (unsigned long long)v);
+      }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) pairs += __shfl_xor(pairs, off, kWave);
+    if (lane == 0 && pairs) atomicAdd(&pair_count, pairs);
+  }
   __syncthreads();
 
-  // nearest-object search: wave 0 NEW->NEW, wave 1 NEW->OLD, wave 2 OLD->NEW
-  const int wave = tid >> 6, lane = tid & 63;
+  // wave 0: NEW samples towards NEW, wave 1: NEW towards OLD, wave 2: OLD towards NEW
   if (wave > 2) return;
-  const int64_t split = vs.split;
   uint64_t best = kKeyMax;
-  int32_t self = -1;
   uint32_t evaluated = 0;
   uint32_t n_found = 0, n_pass = 0, n_over = 0;  // this lane's results
-  if (wave == 0) {
-    if (do_nn && lane < nn) self = ids[lane];
-  } else if (wave == 1) {
-    if (lane < nn) self = ids[lane];
-  } else {
-    if (lane < no) self = ids[64 + lane];
-  }
-  // nothing farther than the last entry of the destination list can enter it
-  const uint32_t kth_self = self >= 0 ? meta[self].kth : 0u;
+  if (wave == 0 && !do_nn) self = -1;
   // hand a result to the destination's segment of the proposal array: one
   // returning add yields the segment start and this result's place in it
   auto hand_on = [&](uint64_t key) {
@@ -209,39 +281,40 @@ __global__ __launch_bounds__(kJB) void k_join_valu(
     if (at < slots) bins[at] = make_entry((uint32_t)(key >> 32), (uint32_t)key, 3u);
     else ++n_over;
   };
-  auto offer = [&](uint64_t key) {
-    if (ALL) hand_on(key);
-    else best = key < best ? key : best;
-  };
-  if (wave == 0) {
-    if (self >= 0) {
-      for (int v = 0; v < nn; ++v) {
-        if (v == lane) continue;
-        const uint32_t code = ((v >> 4) <= (lane >> 4)) ? Dm[lane * kDLD + v] : Dm[v * kDLD + lane];
-        offer(((uint64_t)code << 32) | (uint32_t)ids[v]);
+  if constexpr (ALL) {
+    if (wave == 0) {
+      if (self >= 0) {
+        for (int v = 0; v < nn; ++v) {
+          if (v == lane) continue;
+          const uint32_t code = ((v >> 4) <= (lane >> 4)) ? Dm[lane * kDLD + v] : Dm[v * kDLD + lane];
+          hand_on(((uint64_t)code << 32) | (uint32_t)ids[v]);
+        }
       }
-    }
-  } else if (wave == 1) {
-    if (self >= 0) {
-      for (int o = 0; o < no; ++o) {
-        const int32_t other = ids[64 + o];
-        bool ok = other != self;
-        if (merge_mode) ok = ok && (((int64_t)self < split) != ((int64_t)other < split));
-        if (!ok) continue;
-        ++evaluated;
-        offer(((uint64_t)Dm[lane * kDLD + 64 + o] << 32) | (uint32_t)other);
+    } else if (wave == 1) {
+      if (self >= 0) {
+        for (int o = 0; o < no; ++o) {
+          const int32_t other = ids[64 + o];
+          bool ok = other != self;
+          if (merge_mode) ok = ok && (((int64_t)self < split) != ((int64_t)other < split));
+          if (!ok) continue;
+          ++evaluated;
+          hand_on(((uint64_t)Dm[lane * kDLD + 64 + o] << 32) | (uint32_t)other);
+        }
+      }
+    } else {
+      if (self >= 0) {
+        for (int u = 0; u < nn; ++u) {
+          const int32_t other = ids[u];
+          bool ok = other != self;
+          if (merge_mode) ok = ok && (((int64_t)self < split) != ((int64_t)other < split));
+          if (!ok) continue;
+          hand_on(((uint64_t)Dm[u * kDLD + 64 + lane] << 32) | (uint32_t)other);
+        }
       }
     }
   } else {
-    if (self >= 0) {
-      for (int u = 0; u < nn; ++u) {
-        const int32_t other = ids[u];
-        bool ok = other != self;
-        if (merge_mode) ok = ok && (((int64_t)self < split) != ((int64_t)other < split));
-        if (!ok) continue;
-        offer(((uint64_t)Dm[u * kDLD + 64 + lane] << 32) | (uint32_t)other);
-      }
-    }
+    if (self >= 0) best = nearest[wave * 64 + lane];
+    if (wave == 1 && lane == 0) evaluated = pair_count;
   }
   if (!ALL && best != kKeyMax) hand_on(best);
 #pragma unroll
