@@ -51,7 +51,8 @@ enum {
   GNND_EINVAL = -1, /* bad argument                                   */
   GNND_ENOSPC = -2, /* workspace too small                            */
   GNND_ESTATE = -3, /* call out of order (e.g. iterate before a graph) */
-  GNND_EHIP = -4    /* a HIP runtime call or kernel launch failed      */
+  GNND_EHIP = -4,   /* a HIP runtime call or kernel launch failed      */
+  GNND_EIO = -5     /* a file could not be opened, read or written     */
 };
 
 /* How the cross-matching distances (Sec. 4.2) are evaluated. */
@@ -241,6 +242,25 @@ size_t gnnd_sharded_arena_bytes(const gnnd_params* prm, int32_t shards);
 int gnnd_build_sharded(const gnnd_params* prm, const void* vectors_host, int32_t shards,
                        int32_t build_iters, int32_t merge_iters, int32_t* ids_host,
                        void* dist_host, void* copy_stream, gnnd_shard_stats* stats_host);
+
+/* The same out-of-core construction with the collection and the graph in files
+ * (Sec. 5.1: sub-graphs are saved to external storage, and reading and writing
+ * them runs beside the GPU's work).  vectors_path: n*d elements, row-major, read
+ * only.  ids_path / dist_path: created or overwritten, n*k int32 and n*k
+ * distances; they hold the sub-graphs in between and the final graph (collection
+ * ids) at the end.  staging_host: pinned host memory of staging_bytes (>= 1 MiB;
+ * a few hundred MiB keeps the pieces large), the only host buffer used: every
+ * transfer is cut into pieces of half that size; host functions on a stream the
+ * call creates for itself read or write one half while copy_stream moves the
+ * other half over the bus and prm->stream computes.  Procedure, seeds, arena and
+ * result are those of gnnd_build_sharded: the files end up holding the same
+ * bytes as its ids_host / dist_host.  Files are checked and sized before any
+ * GPU work; a later read or write failure returns GNND_EIO once all streams
+ * have drained (the files' contents are then undefined). */
+int gnnd_build_sharded_files(const gnnd_params* prm, const char* vectors_path, int32_t shards,
+                             int32_t build_iters, int32_t merge_iters, const char* ids_path,
+                             const char* dist_path, void* staging_host, size_t staging_bytes,
+                             void* copy_stream, gnnd_shard_stats* stats_host);
 
 /* Exact K nearest neighbours by exhaustive search (the ground truth of
  * Recall@K, Sec. 6.1) of nq query nodes (ids in queries_dev) against all n

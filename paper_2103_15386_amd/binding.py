@@ -10,7 +10,7 @@ import torch
 L2SQ_F32, ANGULAR_F32, L2SQ_U8, CHI2_F32 = 0, 1, 2, 3
 JOIN_AUTO, JOIN_VALU, JOIN_MFMA = 0, 1, 2
 UPDATE_SELECTIVE, UPDATE_ALL_PAIRS = 0, 1
-OK, EINVAL, ENOSPC, ESTATE, EHIP = 0, -1, -2, -3, -4
+OK, EINVAL, ENOSPC, ESTATE, EHIP, EIO = 0, -1, -2, -3, -4, -5
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libgnnd_hip.so")
@@ -21,7 +21,7 @@ EXPORTS = [
     "gnnd_iterate", "gnnd_step_sample", "gnnd_step_join", "gnnd_step_update", "gnnd_build",
     "gnnd_get_graph", "gnnd_set_graph", "gnnd_get_samples", "gnnd_get_proposals", "gnnd_merge",
     "gnnd_exact_knn", "gnnd_join_path", "gnnd_set_profiling", "gnnd_get_stage_ms",
-    "gnnd_sharded_arena_bytes", "gnnd_build_sharded", "gnnd_append",
+    "gnnd_sharded_arena_bytes", "gnnd_build_sharded", "gnnd_build_sharded_files", "gnnd_append",
 ]
 
 
@@ -103,6 +103,9 @@ def load_library():
     lib.gnnd_sharded_arena_bytes.argtypes = [PP, i32]
     lib.gnnd_build_sharded.restype = C.c_int
     lib.gnnd_build_sharded.argtypes = [PP, vp, i32, i32, i32, vp, vp, vp, C.POINTER(ShardStats)]
+    lib.gnnd_build_sharded_files.restype = C.c_int
+    lib.gnnd_build_sharded_files.argtypes = [PP, C.c_char_p, i32, i32, i32, C.c_char_p, C.c_char_p,
+                                             vp, C.c_size_t, vp, C.POINTER(ShardStats)]
     lib.gnnd_join_path.restype = C.c_int
     lib.gnnd_join_path.argtypes = [vp]
     lib.gnnd_set_profiling.restype = C.c_int
@@ -384,6 +387,34 @@ def gnnd_build_sharded(vectors_host, shards, k, p, metric=L2SQ_F32, seed=42, bui
                                   merge_iters, ids.data_ptr(), dist.data_ptr(),
                                   copy_stream.cuda_stream, C.byref(st)))
     return ids, dist, {f: getattr(st, f) for f, _ in st._fields_ if f != "reserved"}
+
+
+def gnnd_build_sharded_files(vectors_path, n, d, shards, k, p, ids_path, dist_path,
+                             metric=L2SQ_F32, seed=42, build_iters=8, merge_iters=4,
+                             join_path=JOIN_AUTO, staging_bytes=256 << 20, device="cuda:0"):
+    """Out-of-core build with the collection and the graph in files (Sec. 5.1):
+    `vectors_path` holds n x d elements row-major; `ids_path` / `dist_path` are
+    created and receive the n x k graph in collection ids.  One pinned staging
+    buffer of `staging_bytes` is the only host memory used.  Returns the timing
+    record."""
+    lib = load_library()
+    dev = torch.device(device)
+    prm = make_params(n, d, k, p, metric, seed, join_path)
+    need = int(lib.gnnd_sharded_arena_bytes(C.byref(prm), shards))
+    paths = [str(x).encode() for x in (vectors_path, ids_path, dist_path)]
+    if need == 0:
+        rc = lib.gnnd_build_sharded_files(C.byref(prm), paths[0], shards, build_iters, merge_iters,
+                                          paths[1], paths[2], None, 0, None, None)
+        raise GnndError(rc, _err())
+    arena = torch.empty(need, dtype=torch.uint8, device=dev)
+    staging = torch.empty(int(staging_bytes), dtype=torch.uint8).pin_memory()
+    copy_stream = torch.cuda.Stream(device=dev)
+    prm = make_params(n, d, k, p, metric, seed, join_path, _stream_ptr(dev), arena)
+    st = ShardStats()
+    _check(lib.gnnd_build_sharded_files(C.byref(prm), paths[0], shards, build_iters, merge_iters,
+                                        paths[1], paths[2], staging.data_ptr(), staging.numel(),
+                                        copy_stream.cuda_stream, C.byref(st)))
+    return {f: getattr(st, f) for f, _ in st._fields_ if f != "reserved"}
 
 
 def exact_knn(vectors, queries, K, metric=L2SQ_F32):

@@ -3,11 +3,19 @@
 // allocated here; every array is carved out of the caller's workspace.
 #include <hip/hip_runtime.h>
 
+#include <fcntl.h>
+#include <sys/stat.h>
+#include <unistd.h>
+
+#include <atomic>
+#include <cerrno>
 #include <chrono>
 #include <cstdio>
+#include <deque>
 #include <cstring>
 #include <new>
 #include <string>
+#include <thread>
 #include <utility>
 #include <vector>
 
@@ -432,9 +440,131 @@ std::vector<std::pair<int, int>> pair_schedule(int S) {
     if (e_ != hipSuccess) { rc = hip_fail(nullptr, e_, what); goto done; } \
   } while (0)
 
-int run_sharded(const gnnd_params* prm, const ShardPlan& pl, const void* vectors_host,
-                int32_t build_iters, int32_t merge_iters, int32_t* ids_host, void* dist_host,
-                hipStream_t copy, gnnd_shard_stats* stats) {
+// Where the collection and its graph live while they are not on the GPU:
+// pinned host arrays, or three files behind one pinned staging buffer.  In file
+// mode every transfer is cut into pieces of half the staging buffer; a piece is
+// read (or written) by a host function on a stream of the store's own while the
+// copy stream moves the other half over the bus, so file access, bus transfers
+// and the compute stream's kernels all overlap (Sec. 5.1: reading and writing
+// the sub-graphs takes place while the GPU works).  All file accesses run in the
+// order they were enqueued, so a sub-graph is read back only after it has been
+// written.  A failed read leaves zeros in the buffer (valid ids and distances)
+// and is reported when the call ends.
+struct ShardStore {
+  enum Which { kVec = 0, kIds = 1, kDist = 2 };
+  char* mem[3] = {nullptr, nullptr, nullptr};
+  int fd[3] = {-1, -1, -1};
+  char* staging = nullptr;
+  size_t half = 0;                  // bytes per half of the staging buffer
+  hipStream_t io = nullptr;         // runs the host functions that touch the files
+  hipEvent_t filled[2] = {nullptr, nullptr};   // a half holds a piece ready to leave
+  hipEvent_t drained[2] = {nullptr, nullptr};  // a half's piece has left (copied or written)
+  unsigned piece = 0;
+  std::atomic<int> io_errno{0};
+  struct Job { ShardStore* st; int fd; bool write; char* buf; size_t bytes; off_t at; };
+  std::deque<Job> jobs;  // stable addresses until the streams have drained
+
+  bool files() const { return staging != nullptr; }
+  hipError_t open_streams() {
+    hipError_t e = hipStreamCreateWithFlags(&io, hipStreamNonBlocking);
+    for (int i = 0; i < 2 && e == hipSuccess; ++i) {
+      e = hipEventCreateWithFlags(&filled[i], hipEventDisableTiming);
+      if (e == hipSuccess) e = hipEventCreateWithFlags(&drained[i], hipEventDisableTiming);
+    }
+    return e;
+  }
+  hipError_t drain() { return io ? hipStreamSynchronize(io) : hipSuccess; }
+  ~ShardStore() {
+    if (io) {
+      (void)hipStreamSynchronize(io);
+      (void)hipStreamDestroy(io);
+    }
+    for (int i = 0; i < 2; ++i) {
+      if (filled[i]) (void)hipEventDestroy(filled[i]);
+      if (drained[i]) (void)hipEventDestroy(drained[i]);
+    }
+    for (int i = 0; i < 3; ++i)
+      if (fd[i] >= 0) ::close(fd[i]);
+  }
+  // one contiguous range of a piece, read or written to the end
+  static void transfer(Job* j, size_t from, size_t to) {
+    size_t done = from;
+    while (done < to) {
+      const ssize_t r = j->write ? ::pwrite(j->fd, j->buf + done, to - done, j->at + (off_t)done)
+                                 : ::pread(j->fd, j->buf + done, to - done, j->at + (off_t)done);
+      if (r > 0) { done += (size_t)r; continue; }
+      if (r < 0 && errno == EINTR) continue;
+      int expected = 0;
+      j->st->io_errno.compare_exchange_strong(expected, r < 0 ? errno : EIO);
+      if (!j->write) memset(j->buf + done, 0, to - done);
+      break;
+    }
+  }
+  // a piece: large ones are split over a few threads (one thread copies from
+  // the page cache at a fraction of what the bus moves)
+  static void run(void* arg) {
+    Job* j = static_cast<Job*>(arg);
+    constexpr size_t kPerThread = (size_t)8 << 20;
+    constexpr int kMaxThreads = 4;
+    int parts = (int)(j->bytes / kPerThread);
+    parts = parts < 1 ? 1 : (parts > kMaxThreads ? kMaxThreads : parts);
+    const size_t step = ((j->bytes + parts - 1) / parts + 4095) & ~(size_t)4095;
+    std::thread helpers[kMaxThreads - 1];
+    int started = 0;
+    for (int t = 1; t < parts; ++t) {
+      const size_t from = (size_t)t * step, to = from + step < j->bytes ? from + step : j->bytes;
+      if (from >= to) break;
+      try {
+        helpers[started] = std::thread(transfer, j, from, to);
+        ++started;
+      } catch (...) {
+        transfer(j, from, to);  // no thread to be had: do it here
+      }
+    }
+    transfer(j, 0, step < j->bytes ? step : j->bytes);
+    for (int t = 0; t < started; ++t) helpers[t].join();
+  }
+  hipError_t up(hipStream_t copy, void* dev, int which, size_t at, size_t bytes) {
+    if (!files()) return hipMemcpyAsync(dev, mem[which] + at, bytes, hipMemcpyHostToDevice, copy);
+    for (size_t o = 0; o < bytes; o += half) {
+      const size_t len = bytes - o < half ? bytes - o : half;
+      const int h = (int)(piece++ & 1);
+      char* buf = staging + (size_t)h * half;
+      hipError_t e = hipStreamWaitEvent(io, drained[h], 0);
+      if (e != hipSuccess) return e;
+      jobs.push_back(Job{this, fd[which], false, buf, len, (off_t)(at + o)});
+      if ((e = hipLaunchHostFunc(io, &ShardStore::run, &jobs.back())) != hipSuccess) return e;
+      if ((e = hipEventRecord(filled[h], io)) != hipSuccess) return e;
+      if ((e = hipStreamWaitEvent(copy, filled[h], 0)) != hipSuccess) return e;
+      e = hipMemcpyAsync((char*)dev + o, buf, len, hipMemcpyHostToDevice, copy);
+      if (e != hipSuccess) return e;
+      if ((e = hipEventRecord(drained[h], copy)) != hipSuccess) return e;
+    }
+    return hipSuccess;
+  }
+  hipError_t down(hipStream_t copy, int which, size_t at, const void* dev, size_t bytes) {
+    if (!files()) return hipMemcpyAsync(mem[which] + at, dev, bytes, hipMemcpyDeviceToHost, copy);
+    for (size_t o = 0; o < bytes; o += half) {
+      const size_t len = bytes - o < half ? bytes - o : half;
+      const int h = (int)(piece++ & 1);
+      char* buf = staging + (size_t)h * half;
+      hipError_t e = hipStreamWaitEvent(copy, drained[h], 0);
+      if (e != hipSuccess) return e;
+      e = hipMemcpyAsync(buf, (const char*)dev + o, len, hipMemcpyDeviceToHost, copy);
+      if (e != hipSuccess) return e;
+      if ((e = hipEventRecord(filled[h], copy)) != hipSuccess) return e;
+      if ((e = hipStreamWaitEvent(io, filled[h], 0)) != hipSuccess) return e;
+      jobs.push_back(Job{this, fd[which], true, buf, len, (off_t)(at + o)});
+      if ((e = hipLaunchHostFunc(io, &ShardStore::run, &jobs.back())) != hipSuccess) return e;
+      if ((e = hipEventRecord(drained[h], io)) != hipSuccess) return e;
+    }
+    return hipSuccess;
+  }
+};
+
+int run_sharded(const gnnd_params* prm, const ShardPlan& pl, ShardStore& store,
+                int32_t build_iters, int32_t merge_iters, hipStream_t copy,
+                gnnd_shard_stats* stats) {
   int rc = GNND_OK;
   char* arena = (char*)prm->workspace_dev;
   hipStream_t comp = (hipStream_t)prm->stream;
@@ -458,9 +588,8 @@ int run_sharded(const gnnd_params* prm, const ShardPlan& pl, const void* vectors
   // ---- phase 1: one graph per shard ------------------------------------------
   {
     auto upload = [&](int s) {  // vectors of shard s into slot s % 2
-      return hipMemcpyAsync(arena + pl.off_vec[s % 2][0],
-                            (const char*)vectors_host + (size_t)base_of(s) * row_vec,
-                            (size_t)rows_of(s) * row_vec, hipMemcpyHostToDevice, copy);
+      return store.up(copy, arena + pl.off_vec[s % 2][0], ShardStore::kVec,
+                      (size_t)base_of(s) * row_vec, (size_t)rows_of(s) * row_vec);
     };
     GNND_HIP(upload(0), "shard upload");
     GNND_HIP(hipEventRecord(ev_up[0], copy), "hipEventRecord");
@@ -493,12 +622,10 @@ int run_sharded(const gnnd_params* prm, const ShardPlan& pl, const void* vectors
       if (rc != GNND_OK) goto done;
       GNND_HIP(hipEventRecord(ev_done[slot], comp), "hipEventRecord");
       GNND_HIP(hipStreamWaitEvent(copy, ev_done[slot], 0), "hipStreamWaitEvent");
-      GNND_HIP(hipMemcpyAsync((char*)ids_host + (size_t)base_of(s) * row_g,
-                              arena + pl.off_oids[slot], (size_t)rows_of(s) * row_g,
-                              hipMemcpyDeviceToHost, copy), "graph download");
-      GNND_HIP(hipMemcpyAsync((char*)dist_host + (size_t)base_of(s) * row_g,
-                              arena + pl.off_odist[slot], (size_t)rows_of(s) * row_g,
-                              hipMemcpyDeviceToHost, copy), "graph download");
+      GNND_HIP(store.down(copy, ShardStore::kIds, (size_t)base_of(s) * row_g,
+                          arena + pl.off_oids[slot], (size_t)rows_of(s) * row_g), "graph download");
+      GNND_HIP(store.down(copy, ShardStore::kDist, (size_t)base_of(s) * row_g,
+                          arena + pl.off_odist[slot], (size_t)rows_of(s) * row_g), "graph download");
     }
   }
   GNND_HIP(hipEventRecord(t1, comp), "hipEventRecord");
@@ -511,9 +638,8 @@ int run_sharded(const gnnd_params* prm, const ShardPlan& pl, const void* vectors
       const int slot = m % 2;
       const int sh[2] = {pairs[m].first, pairs[m].second};
       for (int h = 0; h < 2; ++h) {
-        hipError_t e = hipMemcpyAsync(arena + pl.off_vec[slot][h],
-                                      (const char*)vectors_host + (size_t)base_of(sh[h]) * row_vec,
-                                      (size_t)rows_of(sh[h]) * row_vec, hipMemcpyHostToDevice, copy);
+        hipError_t e = store.up(copy, arena + pl.off_vec[slot][h], ShardStore::kVec,
+                                (size_t)base_of(sh[h]) * row_vec, (size_t)rows_of(sh[h]) * row_vec);
         if (e != hipSuccess) return e;
       }
       return hipSuccess;
@@ -521,13 +647,11 @@ int run_sharded(const gnnd_params* prm, const ShardPlan& pl, const void* vectors
     auto up_graph = [&](int m, int h) {
       const int slot = m % 2;
       const int s = h ? pairs[m].second : pairs[m].first;
-      hipError_t e = hipMemcpyAsync(arena + pl.off_ids[slot][h],
-                                    (const char*)ids_host + (size_t)base_of(s) * row_g,
-                                    (size_t)rows_of(s) * row_g, hipMemcpyHostToDevice, copy);
+      hipError_t e = store.up(copy, arena + pl.off_ids[slot][h], ShardStore::kIds,
+                              (size_t)base_of(s) * row_g, (size_t)rows_of(s) * row_g);
       if (e != hipSuccess) return e;
-      return hipMemcpyAsync(arena + pl.off_dist[slot][h],
-                            (const char*)dist_host + (size_t)base_of(s) * row_g,
-                            (size_t)rows_of(s) * row_g, hipMemcpyHostToDevice, copy);
+      return store.up(copy, arena + pl.off_dist[slot][h], ShardStore::kDist,
+                      (size_t)base_of(s) * row_g, (size_t)rows_of(s) * row_g);
     };
     auto touches = [&](int m, int s) { return pairs[m].first == s || pairs[m].second == s; };
     const int M = (int)pairs.size();
@@ -567,18 +691,14 @@ int run_sharded(const gnnd_params* prm, const ShardPlan& pl, const void* vectors
       GNND_HIP(hipStreamWaitEvent(copy, ev_done[slot], 0), "hipStreamWaitEvent");
       // results: rows of shard sa, then rows of shard sb
       const size_t na = (size_t)rows_of(sa), nb = (size_t)rows_of(sb);
-      GNND_HIP(hipMemcpyAsync((char*)ids_host + (size_t)base_of(sa) * row_g,
-                              arena + pl.off_oids[slot], na * row_g, hipMemcpyDeviceToHost, copy),
-               "merge download");
-      GNND_HIP(hipMemcpyAsync((char*)ids_host + (size_t)base_of(sb) * row_g,
-                              arena + pl.off_oids[slot] + na * row_g, nb * row_g,
-                              hipMemcpyDeviceToHost, copy), "merge download");
-      GNND_HIP(hipMemcpyAsync((char*)dist_host + (size_t)base_of(sa) * row_g,
-                              arena + pl.off_odist[slot], na * row_g, hipMemcpyDeviceToHost, copy),
-               "merge download");
-      GNND_HIP(hipMemcpyAsync((char*)dist_host + (size_t)base_of(sb) * row_g,
-                              arena + pl.off_odist[slot] + na * row_g, nb * row_g,
-                              hipMemcpyDeviceToHost, copy), "merge download");
+      GNND_HIP(store.down(copy, ShardStore::kIds, (size_t)base_of(sa) * row_g,
+                          arena + pl.off_oids[slot], na * row_g), "merge download");
+      GNND_HIP(store.down(copy, ShardStore::kIds, (size_t)base_of(sb) * row_g,
+                          arena + pl.off_oids[slot] + na * row_g, nb * row_g), "merge download");
+      GNND_HIP(store.down(copy, ShardStore::kDist, (size_t)base_of(sa) * row_g,
+                          arena + pl.off_odist[slot], na * row_g), "merge download");
+      GNND_HIP(store.down(copy, ShardStore::kDist, (size_t)base_of(sb) * row_g,
+                          arena + pl.off_odist[slot] + na * row_g, nb * row_g), "merge download");
       if (m + 1 < M) {
         for (int h = 0; h < 2; ++h)
           if (late[h]) GNND_HIP(up_graph(m + 1, h), "merge upload");
@@ -589,6 +709,7 @@ int run_sharded(const gnnd_params* prm, const ShardPlan& pl, const void* vectors
   GNND_HIP(hipEventRecord(t2, comp), "hipEventRecord");
   GNND_HIP(hipStreamSynchronize(copy), "hipStreamSynchronize");
   GNND_HIP(hipStreamSynchronize(comp), "hipStreamSynchronize");
+  GNND_HIP(store.drain(), "hipStreamSynchronize");
   if (stats) {
     memset(stats, 0, sizeof *stats);
     stats->builds = pl.shards;
@@ -598,7 +719,14 @@ int run_sharded(const gnnd_params* prm, const ShardPlan& pl, const void* vectors
     stats->ms_total = std::chrono::duration<float, std::milli>(
                           std::chrono::steady_clock::now() - wall0).count();
   }
+  if (const int err = store.io_errno.load())
+    rc = fail(nullptr, GNND_EIO, (std::string("file access failed: ") + strerror(err)).c_str());
 done:
+  if (rc != GNND_OK && rc != GNND_EIO) {  // nothing enqueued may outlive the store
+    (void)hipStreamSynchronize(copy);
+    (void)hipStreamSynchronize(comp);
+    (void)store.drain();
+  }
   for (int i = 0; i < 2; ++i) {
     if (ev_up[i]) (void)hipEventDestroy(ev_up[i]);
     if (ev_done[i]) (void)hipEventDestroy(ev_done[i]);
@@ -832,8 +960,50 @@ int gnnd_build_sharded(const gnnd_params* prm, const void* vectors_host, int32_t
   if (prm->workspace_bytes < pl.total) return fail(nullptr, GNND_ENOSPC, "arena too small");
   if (!copy_stream || copy_stream == prm->stream)
     return fail(nullptr, GNND_EINVAL, "copy_stream must be a stream of its own");
-  return run_sharded(prm, pl, vectors_host, build_iters, merge_iters, ids_host, dist_host,
-                     (hipStream_t)copy_stream, stats);
+  ShardStore store;
+  store.mem[ShardStore::kVec] = (char*)const_cast<void*>(vectors_host);
+  store.mem[ShardStore::kIds] = (char*)ids_host;
+  store.mem[ShardStore::kDist] = (char*)dist_host;
+  return run_sharded(prm, pl, store, build_iters, merge_iters, (hipStream_t)copy_stream, stats);
+}
+
+int gnnd_build_sharded_files(const gnnd_params* prm, const char* vectors_path, int32_t shards,
+                             int32_t build_iters, int32_t merge_iters, const char* ids_path,
+                             const char* dist_path, void* staging_host, size_t staging_bytes,
+                             void* copy_stream, gnnd_shard_stats* stats) {
+  ShardPlan pl;
+  if (const char* m = plan_shards(prm, shards, &pl)) return fail(nullptr, GNND_EINVAL, m);
+  if (!vectors_path || !ids_path || !dist_path || !staging_host)
+    return fail(nullptr, GNND_EINVAL, "NULL pointer argument");
+  if (build_iters < 0 || merge_iters < 0) return fail(nullptr, GNND_EINVAL, "negative iteration count");
+  if (staging_bytes < ((size_t)1 << 20))
+    return fail(nullptr, GNND_EINVAL, "staging buffer must hold at least 1 MiB");
+  if (!prm->workspace_dev || ((uintptr_t)prm->workspace_dev & 255))
+    return fail(nullptr, GNND_EINVAL, "arena must be a 256-byte aligned device pointer");
+  if (prm->workspace_bytes < pl.total) return fail(nullptr, GNND_ENOSPC, "arena too small");
+  if (!copy_stream || copy_stream == prm->stream)
+    return fail(nullptr, GNND_EINVAL, "copy_stream must be a stream of its own");
+  ShardStore store;
+  store.staging = static_cast<char*>(staging_host);
+  store.half = (staging_bytes / 2) & ~(size_t)4095;
+  const size_t vec_total = (size_t)prm->n * prm->d * pl.elem, g_total = (size_t)prm->n * prm->k * 4;
+  store.fd[ShardStore::kVec] = ::open(vectors_path, O_RDONLY);
+  if (store.fd[ShardStore::kVec] < 0)
+    return fail(nullptr, GNND_EIO, (std::string("cannot open ") + vectors_path + ": " +
+                                    strerror(errno)).c_str());
+  struct stat sb;
+  if (::fstat(store.fd[ShardStore::kVec], &sb) != 0 || (size_t)sb.st_size < vec_total)
+    return fail(nullptr, GNND_EIO, "the vector file is shorter than n*d elements");
+  const char* out_path[2] = {ids_path, dist_path};
+  for (int i = 0; i < 2; ++i) {
+    const int fd = ::open(out_path[i], O_RDWR | O_CREAT, 0644);
+    store.fd[ShardStore::kIds + i] = fd;
+    if (fd < 0 || ::ftruncate(fd, (off_t)g_total) != 0)
+      return fail(nullptr, GNND_EIO, (std::string("cannot create ") + out_path[i] + ": " +
+                                      strerror(errno)).c_str());
+  }
+  if (hipError_t e = store.open_streams()) return hip_fail(nullptr, e, "creating the file stream");
+  return run_sharded(prm, pl, store, build_iters, merge_iters, (hipStream_t)copy_stream, stats);
 }
 
 int gnnd_exact_knn(const void* vec, int64_t n, int32_t d, int32_t metric, const int32_t* queries,

@@ -9,9 +9,10 @@
 // block of distances [NEW x (NEW | OLD)] is register-tiled 4 x 8 per thread
 // over a 16 x 16 thread grid with the rows/columns of a thread 16 apart, so
 // partially filled lists switch whole 16 x 16 sub-blocks off uniformly.  Only
-// the lower block triangle of NEW x NEW is evaluated.  The distances then go
-// to LDS and three wavefronts pick, per sample, the nearest other NEW sample,
-// the nearest OLD sample, and per OLD sample the nearest NEW sample.
+// the lower block triangle of NEW x NEW is evaluated.  Per sample the nearest
+// other NEW sample, the nearest OLD sample, and per OLD sample the nearest NEW
+// sample are reduced straight from the register tiles; three wavefronts, one
+// lane per sample, hand the results on.
 #include "device_utils.hpp"
 #include "kernels.hpp"
 

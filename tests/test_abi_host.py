@@ -68,3 +68,28 @@ def test_product_path_refuses_cpu_tensors(amd):
         amd.Gnnd(torch.zeros(100, 8), 10, 8)
     with pytest.raises(amd.GnndError):
         amd.exact_knn(torch.zeros(100, 8), torch.zeros(4, dtype=torch.int32), 3)
+
+
+def test_file_backed_shard_driver_checks_its_files_before_any_gpu_work(amd, tmp_path):
+    """Arguments and files are validated on the host; the pointers below are never
+    dereferenced because every call fails first."""
+    import numpy as np
+    from paper_2103_15386_amd import binding
+    lib = amd.load_library()
+    prm = binding.make_params(2000, 8, 8, 8, amd.L2SQ_F32)
+    prm.workspace_dev, prm.workspace_bytes = 0x100000, 1 << 40
+    prm.stream = 0x10
+    args = (2, 4, 2, str(tmp_path / "i.bin").encode(), str(tmp_path / "d.bin").encode())
+    call = lambda vec, stg, stg_bytes, copy: lib.gnnd_build_sharded_files(
+        C.byref(prm), vec, args[0], args[1], args[2], args[3], args[4], stg, stg_bytes, copy, None)
+    missing = str(tmp_path / "missing.bin").encode()
+    assert call(missing, 0x2000, 1 << 20, 0x20) == binding.EIO
+    assert b"cannot open" in lib.gnnd_last_error(None)
+    assert call(missing, 0x2000, 1 << 10, 0x20) == binding.EINVAL   # staging too small
+    assert call(missing, None, 1 << 20, 0x20) == binding.EINVAL     # no staging buffer
+    assert call(missing, 0x2000, 1 << 20, 0x10) == binding.EINVAL   # copy stream = compute stream
+    short = tmp_path / "short.bin"
+    np.zeros(1000 * 8, dtype=np.float32).tofile(short)
+    assert call(str(short).encode(), 0x2000, 1 << 20, 0x20) == binding.EIO
+    assert b"shorter" in lib.gnnd_last_error(None)
+    assert not (tmp_path / "i.bin").exists()  # nothing is created before the input is accepted

@@ -112,6 +112,45 @@ def test_sharded_build_matches_oracle(metric, gen, shards, n):
     assert rec > 0.85, rec
 
 
+@pytest.mark.parametrize("metric,gen,shards,n,staging", [
+    (og.L2SQ_U8, lambda n: W.sift_like_u8(n, 128, seed=302, n_comp=8), 4, 4000, 1 << 20),
+    (og.L2SQ_F32, lambda n: W.uniform_f32(n, 300, seed=306), 3, 3001, (1 << 20) + 4096),
+])
+def test_sharded_build_from_files_matches_oracle(metric, gen, shards, n, staging, tmp_path):
+    """The collection and the graph live in files; transfers go through one pinned
+    staging buffer.  In the second case a shard's vectors (1.2 MB) exceed it, so
+    those transfers are cut into pieces, the last one ragged."""
+    import paper_2103_15386_amd as amd
+    k, p = 12, 12
+    x = gen(n)
+    want = og.build_sharded(x, shards, k, p, metric, SEED, 5, 3)
+    x.tofile(tmp_path / "vectors.bin")
+    (tmp_path / "ids.bin").write_bytes(b"\xff" * 10)  # an older, shorter file is overwritten
+    st = amd.gnnd_build_sharded_files(tmp_path / "vectors.bin", n, x.shape[1], shards, k, p,
+                                      tmp_path / "ids.bin", tmp_path / "dist.bin", metric, SEED,
+                                      5, 3, staging_bytes=staging)
+    dt = np.int32 if metric == og.L2SQ_U8 else np.float32
+    ids = np.fromfile(tmp_path / "ids.bin", dtype=np.int32).reshape(n, k)
+    dist = np.fromfile(tmp_path / "dist.bin", dtype=dt).reshape(n, k)
+    assert (ids == want.ids).all()
+    assert (dist.astype(np.float64) == want.dist).all()
+    assert st["builds"] == shards and st["merges"] == shards * (shards - 1) // 2
+
+
+def test_sharded_build_from_files_reports_file_errors(tmp_path):
+    import paper_2103_15386_amd as amd
+    x = W.uniform_f32(2000, 8, seed=307)
+    with pytest.raises(amd.GnndError) as e:
+        amd.gnnd_build_sharded_files(tmp_path / "missing.bin", 2000, 8, 2, 8, 8,
+                                     tmp_path / "i.bin", tmp_path / "d.bin")
+    assert e.value.code == amd.binding.EIO
+    x[:1000].tofile(tmp_path / "short.bin")
+    with pytest.raises(amd.GnndError) as e:
+        amd.gnnd_build_sharded_files(tmp_path / "short.bin", 2000, 8, 2, 8, 8,
+                                     tmp_path / "i.bin", tmp_path / "d.bin")
+    assert e.value.code == amd.binding.EIO and "shorter" in str(e.value)
+
+
 @pytest.mark.parametrize("metric,gen,n1,n2", [
     (og.L2SQ_F32, lambda n: W.uniform_f32(n, 12, seed=304), 1300, 700),
     (og.L2SQ_U8, lambda n: W.sift_like_u8(n, 128, seed=305, n_comp=8), 900, 1100),
