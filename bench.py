@@ -40,8 +40,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--n", type=int, default=1_000_000)
-    ap.add_argument("--d", type=int, default=128)
+    ap.add_argument("--n", type=int, default=None, help="default: the workload's size")
+    ap.add_argument("--d", type=int, default=None)
     ap.add_argument("--k", type=int, default=32)
     ap.add_argument("--p", type=int, default=32)
     ap.add_argument("--max-iters", type=int, default=12)
@@ -51,9 +51,14 @@ def parse():
     ap.add_argument("--update", choices=["selective", "all-pairs"], default="selective",
                     help="all-pairs: the ablation variant that proposes every evaluated pair "
                          "(runs with the valu join; ~100 KB of workspace per node at p = 32)")
-    ap.add_argument("--cpu-sample-n", type=int, default=200_000)
+    ap.add_argument("--cpu-sample-n", type=int, default=None,
+                    help="rows of the oracle's timed sample (default 200000; 30000 at d = 960)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", choices=["sift1m", "sharded"], default="sift1m")
+    ap.add_argument("--workload", choices=["sift1m", "gist1m", "deep10m", "sharded"],
+                    default="sift1m",
+                    help="sift1m is the metric's workload; gist1m (960-d, squared L2) and deep10m "
+                         "(96-d unit vectors, angular) are the paper's other float shapes, extra "
+                         "lines through the general float join; sharded is the merge workload")
     ap.add_argument("--shards", type=int, default=4)
     ap.add_argument("--store", choices=["memory", "files"], default="memory",
                     help="sharded workload: keep collection and graph in pinned host memory, or "
@@ -65,7 +70,26 @@ def parse():
     ap.add_argument("--copy-calib-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (a dispatch of known "
                          "size to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters with)")
-    return ap.parse_args()
+    args = ap.parse_args()
+    n, d = {"sift1m": (1_000_000, 128), "gist1m": (1_000_000, 960), "deep10m": (10_000_000, 96),
+            "sharded": (100_000_000, 128)}[args.workload]
+    args.n = args.n or n
+    args.d = args.d or d
+    args.cpu_sample_n = args.cpu_sample_n or (30_000 if args.d > 512 else 200_000)
+    return args
+
+
+def float_workload(args, W, amd_or_og):
+    """Generator, metric and description of the float workloads."""
+    name = args.workload
+    if name == "gist1m":
+        return (lambda n: W.gist_like_f32(n, args.d), amd_or_og.L2SQ_F32,
+                "gist-shaped L1-normalised mixture", "squared L2")
+    if name == "deep10m":
+        return (lambda n: W.deep_like_f32(n, args.d), amd_or_og.ANGULAR_F32,
+                "deep-shaped unit-length mixture", "angular (1 - dot)")
+    return (lambda n: W.sift_like_f32(n, args.d, seed=1002), amd_or_og.L2SQ_F32,
+            "sift-shaped GMM", "squared L2")
 
 
 def cpu_baseline(args, iters):
@@ -77,12 +101,13 @@ def cpu_baseline(args, iters):
     cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")))
     og.set_threads(cores)
     n = min(args.cpu_sample_n, args.n)
-    x = W.sift_like_f32(n, args.d, seed=1002)
+    gen, metric, _, _ = float_workload(args, W, og)
+    x = gen(n)
     t0 = time.perf_counter()
-    g = og.init_random(x, args.k, og.L2SQ_F32, W.ALGO_SEED)
+    g = og.init_random(x, args.k, metric, W.ALGO_SEED)
     evals = 0
     for it in range(1, iters + 1):
-        evals += og.iterate(x, og.L2SQ_F32, g, args.p, W.ALGO_SEED, it)["dist_evals"]
+        evals += og.iterate(x, metric, g, args.p, W.ALGO_SEED, it)["dist_evals"]
     dt = time.perf_counter() - t0
     return {"value": evals / dt, "unit": "dist_evals/s", "cores": cores, "kind": "oracle",
             "build_s_on_sample": dt,
@@ -165,7 +190,8 @@ def main():
     torch.cuda.set_device(dev)
     if args.workload == "sharded":
         return sharded(args, torch, amd, W, dev)
-    x = W.sift_like_f32(args.n, args.d, seed=1002)
+    gen, metric, shape_name, metric_name = float_workload(args, W, amd)
+    x = gen(args.n)
     xd = torch.from_numpy(x).to(dev)
     del x
     if args.copy_calib_mib:
@@ -179,11 +205,11 @@ def main():
 
     # ground truth for the recall evaluation: exhaustive search on sampled nodes
     q = torch.from_numpy(W.sample_nodes(args.n, args.eval_nodes)).to(dev)
-    _, tdist = amd.exact_knn(xd, q, 10, amd.L2SQ_F32)
+    _, tdist = amd.exact_knn(xd, q, 10, metric)
     ql = q.long()
 
     update_mode = amd.UPDATE_ALL_PAIRS if args.update == "all-pairs" else amd.UPDATE_SELECTIVE
-    ctx = amd.Gnnd(xd, args.k, args.p, amd.L2SQ_F32, seed, join_path, update_mode)
+    ctx = amd.Gnnd(xd, args.k, args.p, metric, seed, join_path, update_mode)
 
     # calibration build (untimed): recall and per-stage times after every iteration
     ctx.init_random()
@@ -250,7 +276,7 @@ def main():
         other = {"bound": "mfma", "achieved": ops / avg_join_s / 1e12, "peak": PEAK_INT8_TOPS,
                  "unit": "TOP/s"}
     else:
-        ops = total_evals / T * args.d * 3
+        ops = total_evals / T * args.d * (2 if metric == amd.ANGULAR_F32 else 3)
         other = {"bound": "alu", "achieved": ops / avg_join_s / 1e12, "peak": PEAK_FP32_TFLOPS,
                  "unit": "TFLOP/s"}
     other["frac"] = other["achieved"] / other["peak"]
@@ -271,8 +297,8 @@ def main():
         "ms_per_step": build_s * 1e3, "higher_is_better": False, "scaling": "weak",
         "vs_baseline": None, "dtype": "i8" if mfma else "f32",
         "data": "synthetic",
-        "config": {"workload": f"sift-shaped GMM n={args.n} d={args.d} f32, k={args.k} "
-                               f"p={args.p}, squared L2, random init + {T} iterations",
+        "config": {"workload": f"{shape_name} n={args.n} d={args.d} f32, k={args.k} "
+                               f"p={args.p}, {metric_name}, random init + {T} iterations",
                    "join_path": "mfma_i8" if mfma else "valu", "update": args.update,
                    "eval_nodes": args.eval_nodes},
         "reached_target": reached, "iterations": T, "recall_at_10": trace[T - 1]["recall_at_10"],
