@@ -398,6 +398,10 @@ __device__ inline uint32_t wave_distances(const VecSrc& vs, uint32_t s, uint32_t
         if (sizeof(T) == 4 && aligned && j + 3 < d) {
           const float4 f = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(src) + j);
           v[0] = (ACC)f.x; v[1] = (ACC)f.y; v[2] = (ACC)f.z; v[3] = (ACC)f.w;
+        } else if (sizeof(T) == 1 && aligned && j + 3 < d) {  // four bytes in one load
+          const uint32_t w = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const uint8_t*>(src) + j);
+          v[0] = (ACC)(w & 0xff); v[1] = (ACC)((w >> 8) & 0xff);
+          v[2] = (ACC)((w >> 16) & 0xff); v[3] = (ACC)(w >> 24);
         } else {
 #pragma unroll
           for (int q = 0; q < 4; ++q)

@@ -55,6 +55,36 @@ __global__ __launch_bounds__(256) void k_pack_i8(const void* vec_a, const void* 
   if (__ballot(is_bad) != 0ull && lane == 0) atomicOr(bad, 1);
 }
 
+// The same for uint8 rows whose length is a multiple of 16: a lane moves 16
+// bytes (x - 128 is x ^ 0x80 in every byte), C = dpad / 16 neighbouring lanes
+// share a row, so loads and stores of a wavefront are contiguous.
+__global__ __launch_bounds__(256) void k_pack_u8_wide(const uint8_t* vec_a, const uint8_t* vec_b,
+                                                      int64_t split, int64_t n, int d, int dpad,
+                                                      int8_t* shadow, NodeMeta* meta) {
+  const int lane = lane_id();
+  const int C = dpad >> 4, per_wave = kWave / C;
+  const int grp = lane / C, sub = lane - grp * C;
+  const int64_t row = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * per_wave + grp;
+  const bool on = grp < per_wave && row < n;
+  int32_t part = 0;
+  if (on) {
+    v4i q = {0, 0, 0, 0};
+    if (16 * sub < d) {
+      const uint8_t* src = row < split ? vec_a + row * d : vec_b + (row - split) * d;
+      q = *reinterpret_cast<const v4i*>(src + 16 * sub);
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        q[t] ^= (int)0x80808080;
+        part = __builtin_amdgcn_sdot4(q[t], q[t], part, false);
+      }
+    }
+    *reinterpret_cast<v4i*>(shadow + row * dpad + 16 * sub) = q;
+  }
+  int32_t total = 0;
+  for (int t = 0; t < C; ++t) total += __shfl(part, (grp * C + t) & 63, kWave);
+  if (on && sub == 0) meta[row].norm = total;
+}
+
 // Alg. 1, first loop, on the int8 rows: k distinct random neighbours per node,
 // exact distances |a|^2 + |b|^2 - 2 a.b (four products per v_dot4), sorted
 // ascending by (distance, id), flagged NEW.  One wavefront per node.  A row is
@@ -535,7 +565,12 @@ hipError_t launch_pack_i8(const Shape& sh, const DevState& ds, int* bad_flag_dev
                           hipStream_t st) {
   const int dpad = (sh.d + 31) & ~31;
   const unsigned grid = (unsigned)((sh.n + 3) / 4);
-  if (sh.metric == kL2U8)
+  if (sh.metric == kL2U8 && (sh.d & 15) == 0) {
+    const int64_t per_block = 4 * (kWave / (dpad >> 4));  // rows per workgroup
+    k_pack_u8_wide<<<(unsigned)((sh.n + per_block - 1) / per_block), 256, 0, st>>>(
+        static_cast<const uint8_t*>(sh.vec_a), static_cast<const uint8_t*>(sh.vec_b), sh.split,
+        sh.n, sh.d, dpad, ds.shadow, ds.meta);
+  } else if (sh.metric == kL2U8)
     k_pack_i8<uint8_t><<<grid, 256, 0, st>>>(sh.vec_a, sh.vec_b, sh.split, sh.n, sh.d, dpad,
                                              ds.shadow, ds.meta, bad_flag_dev);
   else
