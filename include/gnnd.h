@@ -42,8 +42,14 @@ enum {
   GNND_L2SQ_F32 = 0,    /* squared L2, float32 vectors, float32 result            */
   GNND_ANGULAR_F32 = 1, /* 1 - dot product, float32 (unit) vectors, float32 result */
   GNND_L2SQ_U8 = 2,     /* squared L2, uint8 vectors, exact int32 result           */
-  GNND_CHI2_F32 = 3     /* chi-square, sum of (a-b)^2/(a+b) over the dimensions with
+  GNND_CHI2_F32 = 3,    /* chi-square, sum of (a-b)^2/(a+b) over the dimensions with
                            a+b > 0, non-negative float32 vectors, float32 result   */
+  GNND_COSINE_F32 = 4   /* cosine distance of float32 vectors of any length,
+                           1 - a.b / sqrt(|a|^2 |b|^2), float32 result; a zero vector
+                           is at distance 1 from everything (Sec. 1: the method keeps
+                           NN-Descent's genericness over metrics; this one carries a
+                           per-vector quantity, the squared norm, kept in 4 more bytes
+                           of workspace per vector)                                  */
 };
 
 enum {
@@ -77,7 +83,7 @@ typedef struct gnnd_params {
   int32_t d;      /* dimension, >= 1 (float metrics: multiple of 4 reads fastest)   */
   int32_t k;      /* list length, 2 <= k <= 128                                     */
   int32_t p;      /* sample number of Sec. 4.1, 1 <= p <= min(k, 32)                */
-  int32_t metric; /* GNND_L2SQ_F32 / GNND_ANGULAR_F32 / GNND_L2SQ_U8               */
+  int32_t metric; /* one of the distance constants above                            */
   uint64_t seed;  /* seed of all random draws                                       */
   void* stream;   /* hipStream_t; NULL = the default stream                         */
   void* workspace_dev;    /* device scratch, 256-byte aligned, caller-owned         */

@@ -30,7 +30,7 @@
 #include <stdlib.h>
 #include <string.h>
 
-enum { OG_L2SQ_F32 = 0, OG_ANGULAR_F32 = 1, OG_L2SQ_U8 = 2, OG_CHI2_F32 = 3 };
+enum { OG_L2SQ_F32 = 0, OG_ANGULAR_F32 = 1, OG_L2SQ_U8 = 2, OG_CHI2_F32 = 3, OG_COSINE_F32 = 4 };
 enum { OG_TAG_INIT = 1, OG_TAG_REV_NEW = 2, OG_TAG_REV_OLD = 3, OG_TAG_MERGE = 4 };
 enum { OG_HASH_ATTEMPTS = 256 };
 
@@ -105,7 +105,27 @@ static float chi2_f32(const float* a, const float* b, int d) {
   return acc;
 }
 
+/* Cosine distance of vectors that are not unit length (Sec. 1: the method keeps
+ * NN-Descent's genericness over distance metrics; this one needs the two norms
+ * besides the inner product):
+ * 1 - a.b / sqrt(|a|^2 |b|^2).  Reading: float32; the inner product and the two
+ * squared norms each accumulated with one fused multiply-add per dimension, in
+ * dimension order (a squared norm is a property of its vector alone); product,
+ * square root, quotient and difference each rounded on their own; a zero vector
+ * is at distance 1 from everything. */
+static float cosine_f32(const float* a, const float* b, int d) {
+  const float dot = dot_f32(a, b, d);
+  const float na = dot_f32(a, a, d);
+  const float nb = dot_f32(b, b, d);
+  const float den = sqrtf(na * nb);
+  return den > 0.0f ? 1.0f - dot / den : 1.0f;
+}
+
 double og_distance(int metric, int d, const void* vec, int64_t i, int64_t j) {
+  if (metric == OG_COSINE_F32) {
+    const float* x = (const float*)vec;
+    return (double)cosine_f32(x + i * d, x + j * d, d);
+  }
   if (metric == OG_CHI2_F32) {
     const float* x = (const float*)vec;
     return (double)chi2_f32(x + i * d, x + j * d, d);

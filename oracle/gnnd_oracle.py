@@ -12,7 +12,7 @@ import subprocess
 
 import numpy as np
 
-L2SQ_F32, ANGULAR_F32, L2SQ_U8, CHI2_F32 = 0, 1, 2, 3
+L2SQ_F32, ANGULAR_F32, L2SQ_U8, CHI2_F32, COSINE_F32 = 0, 1, 2, 3, 4
 TAG_INIT, TAG_REV_NEW, TAG_REV_OLD, TAG_MERGE = 1, 2, 3, 4
 
 _HERE = os.path.dirname(os.path.abspath(__file__))

@@ -7,7 +7,7 @@ import os
 import numpy as np
 import torch
 
-L2SQ_F32, ANGULAR_F32, L2SQ_U8, CHI2_F32 = 0, 1, 2, 3
+L2SQ_F32, ANGULAR_F32, L2SQ_U8, CHI2_F32, COSINE_F32 = 0, 1, 2, 3, 4
 JOIN_AUTO, JOIN_VALU, JOIN_MFMA = 0, 1, 2
 UPDATE_SELECTIVE, UPDATE_ALL_PAIRS = 0, 1
 OK, EINVAL, ENOSPC, ESTATE, EHIP, EIO = 0, -1, -2, -3, -4, -5

@@ -11,7 +11,7 @@ constexpr int kWave = 64;
 constexpr uint64_t kKeyMax = ~0ull;
 constexpr uint32_t kIdMax = 0x7fffffffu;
 
-enum : int { kL2F32 = 0, kAngularF32 = 1, kL2U8 = 2, kChi2F32 = 3 };
+enum : int { kL2F32 = 0, kAngularF32 = 1, kL2U8 = 2, kChi2F32 = 3, kCosineF32 = 4 };
 enum : uint32_t { kTagInit = 1, kTagRevNew = 2, kTagRevOld = 3, kTagMerge = 4 };
 constexpr uint32_t kHashAttempts = 256;
 
@@ -283,6 +283,32 @@ struct DistOf<kChi2F32> {
   }
 };
 
+// Cosine distance of vectors of any length: 1 - a.b / sqrt(|a|^2 |b|^2); a zero
+// vector is at distance 1 from everything.  The inner product and the squared
+// norms are accumulated like the angular inner product (a squared norm belongs
+// to its vector alone, so it can be computed once and kept); product, root,
+// quotient and difference are each rounded on their own.
+__device__ inline uint32_t cosine_code(float dot, float na, float nb) {
+  // sqrtf is the correctly rounded root (the compiler's default for HIP); the
+  // intrinsic named after round-to-nearest maps to the approximate instruction
+  const float den = sqrtf(__fmul_rn(na, nb));
+  return ord_f32(den > 0.f ? __fsub_rn(1.0f, __fdiv_rn(dot, den)) : 1.0f);
+}
+template <>
+struct DistOf<kCosineF32> {
+  using elem = float;
+  __device__ static uint32_t eval(const float* a, const float* b, int d) {
+    float dot = 0.f, na = 0.f, nb = 0.f;
+    for (int j = 0; j < d; ++j) {
+      const float x = a[j], y = b[j];
+      dot = __fmaf_rn(x, y, dot);
+      na = __fmaf_rn(x, x, na);
+      nb = __fmaf_rn(y, y, nb);
+    }
+    return cosine_code(dot, na, nb);
+  }
+};
+
 template <>
 struct DistOf<kL2U8> {
   using elem = uint8_t;
@@ -317,6 +343,7 @@ struct VecSrc {
   const void* b;
   int64_t split;
   int32_t d;
+  const float* norms = nullptr;  // squared norm per id where the metric needs it (cosine)
   template <typename T>
   __device__ const T* row(uint32_t id) const {
     return ((int64_t)id < split) ? reinterpret_cast<const T*>(a) + (int64_t)id * d
@@ -337,6 +364,7 @@ struct JoinTraits<kL2F32> {
     s = __fmaf_rn(t, t, s);
   }
   __device__ static uint32_t code(float s) { return ord_f32(s); }
+  __device__ static uint32_t code(float s, float, float) { return code(s); }
 };
 template <>
 struct JoinTraits<kAngularF32> {
@@ -344,6 +372,16 @@ struct JoinTraits<kAngularF32> {
   using acc = float;
   __device__ static void step(float a, float b, float& s) { s = __fmaf_rn(a, b, s); }
   __device__ static uint32_t code(float s) { return ord_f32(1.0f - s); }
+  __device__ static uint32_t code(float s, float, float) { return code(s); }
+};
+// cosine: the running sum is the inner product; the squared norms of the two
+// vectors come from the per-id array (VecSrc::norms)
+template <>
+struct JoinTraits<kCosineF32> {
+  using elem = float;
+  using acc = float;
+  __device__ static void step(float a, float b, float& s) { s = __fmaf_rn(a, b, s); }
+  __device__ static uint32_t code(float s, float na, float nb) { return cosine_code(s, na, nb); }
 };
 template <>
 struct JoinTraits<kChi2F32> {
@@ -351,6 +389,7 @@ struct JoinTraits<kChi2F32> {
   using acc = float;
   __device__ static void step(float a, float b, float& s) { s = chi2_term(a, b, s); }
   __device__ static uint32_t code(float s) { return ord_f32(s); }
+  __device__ static uint32_t code(float s, float, float) { return code(s); }
 };
 template <>
 struct JoinTraits<kL2U8> {
@@ -361,6 +400,7 @@ struct JoinTraits<kL2U8> {
     s += __mul24(t, t);
   }
   __device__ static uint32_t code(int32_t s) { return ord_i32(s); }
+  __device__ static uint32_t code(int32_t s, float, float) { return code(s); }
 };
 
 // Canonical distances from object s to one object per lane (`id`, meaningful
@@ -422,7 +462,8 @@ __device__ inline uint32_t wave_distances(const VecSrc& vs, uint32_t s, uint32_t
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   }
-  return TR::code(acc);
+  if constexpr (METRIC == kCosineF32) return TR::code(acc, vs.norms[s], on ? vs.norms[id] : 0.f);
+  else return TR::code(acc);
 }
 
 // Numbering inside one merge (Sec. 5.1 shards).  The two sets are the ranges

@@ -39,7 +39,7 @@ inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
 const char* check_params(const gnnd_params* q) {
   if (!q) return "params is NULL";
-  if (q->metric < GNND_L2SQ_F32 || q->metric > GNND_CHI2_F32) return "unknown metric";
+  if (q->metric < GNND_L2SQ_F32 || q->metric > GNND_COSINE_F32) return "unknown metric";
   if (q->k < 2 || q->k > 128) return "k must be in [2, 128]";
   if (q->p < 1 || q->p > 32 || q->p > q->k) return "p must be in [1, min(k, 32)]";
   if (q->d < 1) return "d must be >= 1";
@@ -94,7 +94,7 @@ Layout make_layout(const gnnd_params* q, bool with_aside) {
   L.off_aside = take(with_aside ? n * (k / 2) * 8 : 0);
   const bool shadow = mfma_possible(q);
   L.off_shadow = take(shadow ? n * (size_t)((q->d + 31) & ~31) : 0);
-  L.off_norms = 0;
+  L.off_norms = take(q->metric == GNND_COSINE_F32 ? n * 4 : 0);  // squared norms (cosine only)
   L.off_flag = take(256);
   L.off_bkc = take(2 * 4096 * 4);
   L.off_bko = take(2 * 4097 * 8);
@@ -210,6 +210,16 @@ int create_impl(gnnd_ctx** out, const gnnd_params* prm, const void* vec_a, const
     int rc = hip_fail(nullptr, e, "clearing workspace counters");
     delete c;
     return rc;
+  }
+  if (prm->metric == GNND_COSINE_F32) {  // the squared norms the cosine distance divides by
+    float* norms = reinterpret_cast<float*>(static_cast<char*>(prm->workspace_dev) + L.off_norms);
+    c->sh.norms = norms;
+    e = launch_row_norms(c->sh, norms, c->stream);
+    if (e != hipSuccess) {
+      int rc = hip_fail(nullptr, e, "row norm kernel");
+      delete c;
+      return rc;
+    }
   }
   // matrix-core path: build the int8 copy; float data qualifies only when every
   // value is an integer in 0..255 (then all distances are exact either way)
@@ -1010,7 +1020,7 @@ int gnnd_exact_knn(const void* vec, int64_t n, int32_t d, int32_t metric, const 
                    int64_t nq, int32_t K, int32_t* ids_out, void* dist_out, void* stream) {
   if (!vec || !queries || !ids_out || !dist_out)
     return fail(nullptr, GNND_EINVAL, "NULL pointer argument");
-  if (metric < GNND_L2SQ_F32 || metric > GNND_CHI2_F32)
+  if (metric < GNND_L2SQ_F32 || metric > GNND_COSINE_F32)
     return fail(nullptr, GNND_EINVAL, "unknown metric");
   if (n < 2 || n > ((int64_t)1 << 30) || d < 1 || nq < 0 || K < 1 || K > 64)
     return fail(nullptr, GNND_EINVAL, "need 2 <= n <= 2^30, d >= 1, nq >= 0, 1 <= K <= 64");

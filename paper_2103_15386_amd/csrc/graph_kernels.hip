@@ -476,11 +476,61 @@ hipError_t launch_scan(const uint32_t* in, const uint32_t* in2, uint64_t* out, u
 }
 
 // ---------------------------------------------------------------------------
-static VecSrc vec_src(const Shape& sh) { return VecSrc{sh.vec_a, sh.vec_b, sh.split, sh.d}; }
+static VecSrc vec_src(const Shape& sh) {
+  return VecSrc{sh.vec_a, sh.vec_b, sh.split, sh.d, sh.norms};
+}
 
 hipError_t launch_zero_u32(uint32_t* p, size_t count, hipStream_t st) {
   if (count == 0) return hipSuccess;
   k_zero_u32<<<(unsigned)((count + kBlock - 1) / kBlock), kBlock, 0, st>>>(p, count);
+  return hipGetLastError();
+}
+
+// Squared norm of every row, one fused multiply-add per dimension in dimension
+// order (what the cosine distance divides by).  A wavefront takes 64 rows: chunks
+// of kEvalChunk dimensions go through LDS with coalesced reads (8 lanes per row
+// chunk), then each lane adds up its own row.
+__global__ __launch_bounds__(kBlock) void k_row_norms(VecSrc vs, int64_t n, float* norms) {
+  __shared__ float tile[kWavesPerBlock][64 * kEvalStride];
+  const int lane = lane_id();
+  float* my = tile[threadIdx.x >> 6];
+  const int64_t row0 = ((int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6)) * 64;
+  if (row0 >= n) return;
+  const int d = vs.d;
+  const int part = lane & 7, rsel = lane >> 3;
+  float acc = 0.f;
+  for (int d0 = 0; d0 < d; d0 += kEvalChunk) {
+#pragma unroll
+    for (int r0 = 0; r0 < 64; r0 += 8) {
+      const int r = r0 + rsel;
+      if (row0 + r < n) {
+        const float* src = vs.row<float>((uint32_t)(row0 + r));
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int j = d0 + part * 4 + q;
+          my[r * kEvalStride + part * 4 + q] = j < d ? src[j] : 0.f;
+        }
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const int width = d - d0 < kEvalChunk ? d - d0 : kEvalChunk;
+    for (int j = 0; j < width; ++j) {
+      const float x = my[lane * kEvalStride + j];
+      acc = __fmaf_rn(x, x, acc);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  }
+  if (row0 + lane < n) norms[row0 + lane] = acc;
+}
+
+hipError_t launch_row_norms(const Shape& sh, float* norms, hipStream_t st) {
+  const int64_t waves = (sh.n + 63) / 64;
+  k_row_norms<<<(unsigned)((waves + kWavesPerBlock - 1) / kWavesPerBlock), kBlock, 0, st>>>(
+      vec_src(sh), sh.n, norms);
   return hipGetLastError();
 }
 
@@ -500,6 +550,10 @@ hipError_t launch_init_random(const Shape& sh, const DevState& ds, uint64_t seed
     case kChi2F32:
       k_init_random<kChi2F32><<<grid, kBlock, 0, st>>>(vec_src(sh), sh.n, sh.k, base, ds.G,
                                                        ds.meta);
+      break;
+    case kCosineF32:
+      k_init_random<kCosineF32><<<grid, kBlock, 0, st>>>(vec_src(sh), sh.n, sh.k, base, ds.G,
+                                                         ds.meta);
       break;
     default:
       k_init_random<kL2U8><<<grid, kBlock, 0, st>>>(vec_src(sh), sh.n, sh.k, base, ds.G, ds.meta);
@@ -585,6 +639,11 @@ hipError_t launch_merge_init(const Shape& sh, const DevState& ds, uint64_t seed,
       k_merge_init<kChi2F32><<<grid, kBlock, 0, st>>>(vec_src(sh), sh.n, mi, sh.k, base, ids1,
                                                       dist1, ids2, dist2, ds.G, ds.meta, ds.aside);
       break;
+    case kCosineF32:
+      k_merge_init<kCosineF32><<<grid, kBlock, 0, st>>>(vec_src(sh), sh.n, mi, sh.k, base, ids1,
+                                                        dist1, ids2, dist2, ds.G, ds.meta,
+                                                        ds.aside);
+      break;
     default:
       k_merge_init<kL2U8><<<grid, kBlock, 0, st>>>(vec_src(sh), sh.n, mi, sh.k, base, ids1, dist1,
                                                    ids2, dist2, ds.G, ds.meta, ds.aside);
@@ -619,6 +678,9 @@ hipError_t launch_exact_knn(const void* vec, int64_t n, int32_t d, int32_t metri
       break;
     case kChi2F32:
       k_exact_knn<kChi2F32><<<grid, kBlock, 0, st>>>(vec, n, d, queries, K, ids_out, dist_out);
+      break;
+    case kCosineF32:
+      k_exact_knn<kCosineF32><<<grid, kBlock, 0, st>>>(vec, n, d, queries, K, ids_out, dist_out);
       break;
     default:
       k_exact_knn<kL2U8><<<grid, kBlock, 0, st>>>(vec, n, d, queries, K, ids_out, dist_out);

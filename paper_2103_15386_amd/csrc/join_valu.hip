@@ -79,6 +79,8 @@ __global__ __launch_bounds__(kJB) void k_join_valu(
   // per sample the nearest partner: NEW towards NEW, NEW towards OLD, OLD towards NEW
   __shared__ uint64_t nearest[192];
   __shared__ uint32_t pair_count;
+  __shared__ float norms_s[128];  // squared norms of the samples (cosine only)
+  constexpr bool kNorms = METRIC == kCosineF32;
   static_assert(128 * kLD >= 64 * kDLD, "distance matrix must fit in the staging tile");
 
   const int64_t s = blockIdx.x;
@@ -96,6 +98,8 @@ __global__ __launch_bounds__(kJB) void k_join_valu(
   const uint32_t kth_self = self >= 0 ? meta[self].kth : 0u;
   if (wave == 0) ids[lane] = self;
   else if (wave == 2) ids[64 + lane] = self;
+  if (kNorms && (wave == 0 || wave == 2))
+    norms_s[(wave == 0 ? 0 : 64) + lane] = self >= 0 ? vs.norms[self] : 0.f;
   if (!ALL) {
     if (tid < 192) nearest[tid] = kKeyMax;
     if (tid == 0) pair_count = 0;
@@ -187,7 +191,8 @@ __global__ __launch_bounds__(kJB) void k_join_valu(
         const bool on = r < RB && (c < 4 ? (do_nn && c <= r) : (c - 4 < CO));
         if (on) {
           const int col = c < 4 ? (tx + 16 * c) : (64 + tx + 16 * (c - 4));
-          Dm[(ty + 16 * r) * kDLD + col] = TR::code(acc[r][c]);
+          Dm[(ty + 16 * r) * kDLD + col] =
+              TR::code(acc[r][c], kNorms ? norms_s[ty + 16 * r] : 0.f, kNorms ? norms_s[col] : 0.f);
         }
       }
   } else {
@@ -198,8 +203,12 @@ __global__ __launch_bounds__(kJB) void k_join_valu(
     // wavefronts through LDS.  Keys are (distance code, partner id), so equal
     // distances resolve to the smaller id whatever the order of reduction.
     int32_t idc[8];
+    float normc[8];
 #pragma unroll
-    for (int c = 0; c < 8; ++c) idc[c] = ids[c < 4 ? (tx + 16 * c) : (64 + tx + 16 * (c - 4))];
+    for (int c = 0; c < 8; ++c) {
+      idc[c] = ids[c < 4 ? (tx + 16 * c) : (64 + tx + 16 * (c - 4))];
+      normc[c] = kNorms ? norms_s[c < 4 ? (tx + 16 * c) : (64 + tx + 16 * (c - 4))] : 0.f;
+    }
     uint64_t down[8];  // per column: nearest row object seen by this thread
 #pragma unroll
     for (int c = 0; c < 8; ++c) down[c] = kKeyMax;
@@ -223,7 +232,8 @@ __global__ __launch_bounds__(kJB) void k_join_valu(
             if (merge_mode) ok = ok && (((int64_t)idr < split) != ((int64_t)other < split));
           }
           if (!ok) continue;
-          const uint64_t code = (uint64_t)TR::code(acc[r][c]) << 32;
+          const uint64_t code = (uint64_t)TR::code(acc[r][c], kNorms ? norms_s[R] : 0.f,
+                                                   kNorms ? normc[c] : 0.f) << 32;
           const uint64_t here = code | (uint32_t)other, there = code | (uint32_t)idr;
           if (c < 4) {
             to_new = vmin(to_new, here);
@@ -343,7 +353,7 @@ __global__ __launch_bounds__(kJB) void k_join_valu(
 
 template <bool ALL>
 static void launch_join_as(const Shape& sh, const DevState& ds, bool merge_mode, hipStream_t st) {
-  VecSrc vs{sh.vec_a, sh.vec_b, sh.split, sh.d};
+  VecSrc vs{sh.vec_a, sh.vec_b, sh.split, sh.d, sh.norms};
   const unsigned grid = (unsigned)sh.n;
   const uint64_t slots = (uint64_t)sh.slots();  // size of the proposal array
   const int mm = merge_mode ? 1 : 0;
@@ -353,6 +363,7 @@ static void launch_join_as(const Shape& sh, const DevState& ds, bool merge_mode,
     case kL2F32: k_join_valu<kL2F32, ALL><<<grid, kJB, 0, st>>>(GNND_JOIN_ARGS); break;
     case kAngularF32: k_join_valu<kAngularF32, ALL><<<grid, kJB, 0, st>>>(GNND_JOIN_ARGS); break;
     case kChi2F32: k_join_valu<kChi2F32, ALL><<<grid, kJB, 0, st>>>(GNND_JOIN_ARGS); break;
+    case kCosineF32: k_join_valu<kCosineF32, ALL><<<grid, kJB, 0, st>>>(GNND_JOIN_ARGS); break;
     default: k_join_valu<kL2U8, ALL><<<grid, kJB, 0, st>>>(GNND_JOIN_ARGS);
   }
 #undef GNND_JOIN_ARGS

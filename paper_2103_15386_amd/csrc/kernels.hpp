@@ -63,6 +63,7 @@ struct Shape {
   const void* vec_a;
   const void* vec_b;
   int32_t all_pairs;  // 1: every evaluated pair is proposed (ablation), 0: nearest partners only
+  const float* norms = nullptr;  // squared norm per node, where the metric needs it (cosine)
   // slots of the proposal array: per appearance in a NEW list two results (all pairs: one per
   // possible partner, 2 * 2p - 1), in an OLD list one (all pairs: 2p); at most 2np appearances each
   __host__ __device__ int64_t slots_new_per_appearance() const {
@@ -75,6 +76,8 @@ struct Shape {
 };
 
 hipError_t launch_init_random(const Shape& sh, const DevState& ds, uint64_t seed, hipStream_t st);
+// squared norms of all rows, one fused multiply-add per dimension in dimension order
+hipError_t launch_row_norms(const Shape& sh, float* norms, hipStream_t st);
 hipError_t launch_sample(const Shape& sh, const DevState& ds, uint64_t seed, uint32_t iter,
                          hipStream_t st);
 hipError_t launch_join(const Shape& sh, const DevState& ds, int path, bool merge_mode,

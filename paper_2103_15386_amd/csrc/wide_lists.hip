@@ -260,7 +260,9 @@ __global__ __launch_bounds__(kWB) void k_merge_final_wide(int64_t n, MergeIds mi
   if (lane + kWave < k) store(lane + kWave, hi);
 }
 
-VecSrc wide_vec_src(const Shape& sh) { return VecSrc{sh.vec_a, sh.vec_b, sh.split, sh.d}; }
+VecSrc wide_vec_src(const Shape& sh) {
+  return VecSrc{sh.vec_a, sh.vec_b, sh.split, sh.d, sh.norms};
+}
 
 }  // namespace
 
@@ -280,6 +282,10 @@ hipError_t launch_init_random_wide(const Shape& sh, const DevState& ds, uint64_t
     case kChi2F32:
       k_init_random_wide<kChi2F32><<<grid, kWB, 0, st>>>(wide_vec_src(sh), sh.n, sh.k, base, ds.G,
                                                          ds.meta);
+      break;
+    case kCosineF32:
+      k_init_random_wide<kCosineF32><<<grid, kWB, 0, st>>>(wide_vec_src(sh), sh.n, sh.k, base,
+                                                           ds.G, ds.meta);
       break;
     default:
       k_init_random_wide<kL2U8><<<grid, kWB, 0, st>>>(wide_vec_src(sh), sh.n, sh.k, base, ds.G,
@@ -313,6 +319,11 @@ hipError_t launch_merge_init_wide(const Shape& sh, const DevState& ds, uint64_t 
       k_merge_init_wide<kChi2F32><<<grid, kWB, 0, st>>>(wide_vec_src(sh), sh.n, mi, sh.k, base,
                                                         ids1, dist1, ids2, dist2, ds.G, ds.meta,
                                                         ds.aside);
+      break;
+    case kCosineF32:
+      k_merge_init_wide<kCosineF32><<<grid, kWB, 0, st>>>(wide_vec_src(sh), sh.n, mi, sh.k, base,
+                                                          ids1, dist1, ids2, dist2, ds.G, ds.meta,
+                                                          ds.aside);
       break;
     default:
       k_merge_init_wide<kL2U8><<<grid, kWB, 0, st>>>(wide_vec_src(sh), sh.n, mi, sh.k, base, ids1,

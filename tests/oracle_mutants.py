@@ -39,6 +39,10 @@ muts = [
  ("chi2 divides by the difference", "      acc = acc + sq / sum;", "      acc = acc + sq / (diff != 0.0f ? diff : 1.0f);"),
  ("chi2 fused", "      const float sq = diff * diff;\n      acc = acc + sq / sum;", "      acc = fmaf(diff, diff / sum, acc);"),
  ("chi2 counts empty dimensions", "    if (sum > 0.0f) {\n      const float sq = diff * diff;", "    if (sum >= 0.0f) {\n      const float sq = diff * diff;"),
+ ("cosine without the root", "  const float den = sqrtf(na * nb);", "  const float den = na * nb;"),
+ ("cosine norm of the wrong vector", "  const float nb = dot_f32(b, b, d);", "  const float nb = dot_f32(a, a, d);"),
+ ("cosine zero vector at distance 0", "  return den > 0.0f ? 1.0f - dot / den : 1.0f;", "  return den > 0.0f ? 1.0f - dot / den : 0.0f;"),
+ ("cosine two roots", "  const float den = sqrtf(na * nb);", "  const float den = sqrtf(na) * sqrtf(nb);"),
  ("classic inserts one side only", "        ins += (uint64_t)og_insert_one(k, ids + (int64_t)N[b] * k, dist + (int64_t)N[b] * k,\n                                       isnew + (int64_t)N[b] * k, N[a], dd);\n", ""),
 ]
 root=os.path.dirname(os.path.dirname(os.path.abspath(__file__))); tmp="/tmp/gnnd_oracle_mutants"

@@ -28,6 +28,8 @@ def _exact(x, metric, k):
     (og.L2SQ_U8, lambda n: W.sift_like_u8(n, 64, seed=205, n_comp=8), 97, 32, 1000, 3),  # long lists
     (og.L2SQ_F32, lambda n: W.uniform_f32(n, 9, seed=206), 128, 16, 800, 2),
     (og.CHI2_F32, lambda n: W.gist_like_f32(n, 40, seed=207, n_comp=8), 14, 10, 1200, 3),
+    (og.COSINE_F32, lambda n: W.scaled_directions_f32(n, 24, seed=208, n_comp=8), 16, 12, 1000, 3),
+    (og.COSINE_F32, lambda n: W.scaled_directions_f32(n, 10, seed=209, n_comp=4), 70, 16, 900, 2),
 ])
 def test_merge_matches_oracle(metric, gen, k, p, n1, iters, path):
     import paper_2103_15386_amd as amd

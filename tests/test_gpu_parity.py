@@ -53,6 +53,14 @@ CASES = {
     "chi2_gist_cut": (lambda: W.gist_like_f32(1500, 96, seed=1031, n_comp=8),
                       og.CHI2_F32, 20, 16, 4),
     "chi2_ragged_d7": (lambda: W.gist_like_f32(600, 7, seed=1032, n_comp=4), og.CHI2_F32, 9, 6, 4),
+    # cosine distance of vectors of any length (per-vector squared norms), with zero vectors
+    "cosine_raw_d96": (lambda: W.scaled_directions_f32(2500, 96, seed=1061, n_comp=16),
+                       og.COSINE_F32, 20, 12, 5),
+    "cosine_ragged_d11_zero_rows": (lambda: W.scaled_directions_f32(700, 11, seed=1062, n_comp=4,
+                                                                    zero_rows=3),
+                                    og.COSINE_F32, 9, 6, 4),
+    "cosine_k80": (lambda: W.scaled_directions_f32(1500, 32, seed=1063, n_comp=8),
+                   og.COSINE_F32, 80, 20, 3),
     # lists longer than one wavefront (two entries per lane)
     "k128_uniform": (lambda: W.uniform_f32(1800, 10, seed=1021), og.L2SQ_F32, 128, 32, 4),
     "k100_angular": (lambda: W.deep_like_f32(1500, 48, seed=1022, n_comp=8),
@@ -84,7 +92,8 @@ CASES["u8_small_lists"] = (lambda: W.sift_like_u8(1500, 64, seed=1013, n_comp=4)
 
 
 # "all": the variant that proposes every evaluated pair (no selective update)
-ALL_PAIRS_CASES = ["uniform_c1", "u8_cut", "deep_cut_angular", "tiny_n", "k100_angular"]
+ALL_PAIRS_CASES = ["uniform_c1", "u8_cut", "deep_cut_angular", "tiny_n", "k100_angular",
+                   "cosine_ragged_d11_zero_rows"]
 
 
 @pytest.mark.parametrize("name,path", [(n, "valu") for n in CASES] +
@@ -182,6 +191,7 @@ def test_resume_from_saved_graph_gives_the_same_bytes():
     (og.L2SQ_U8, lambda: W.sift_like_u8(3000, 40, seed=93, n_comp=8)),
     (og.L2SQ_F32, lambda: W.small_integer_f32(2000, 5, seed=94, hi=4)),  # masses of ties
     (og.CHI2_F32, lambda: W.gist_like_f32(2500, 30, seed=95, n_comp=8)),
+    (og.COSINE_F32, lambda: W.scaled_directions_f32(2500, 30, seed=96, n_comp=8, zero_rows=2)),
 ])
 def test_exact_knn_matches_oracle_brute_force(metric, gen):
     amd = _amd()

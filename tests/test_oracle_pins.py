@@ -132,6 +132,68 @@ def test_chi_square_is_float32_term_by_term_with_zero_sums_skipped():
         assert og.distance(x, og.CHI2_F32, i, i) == 0.0
 
 
+def _sqrt_f32(p):
+    """Correctly rounded float32 square root of the exact rational p >= 0, decided
+    by comparing p with the squares of the midpoints between neighbouring floats."""
+    if p == 0:
+        return Fraction(0)
+    c = np.float32(np.sqrt(float(p)))
+    for cand in (c, np.nextafter(c, np.float32(0)), np.nextafter(c, np.float32(np.inf))):
+        lo = (_fr(np.nextafter(cand, np.float32(-np.inf))) + _fr(cand)) / 2
+        hi = (_fr(cand) + _fr(np.nextafter(cand, np.float32(np.inf)))) / 2
+        if lo * lo <= p <= hi * hi:
+            return _fr(cand)
+    raise AssertionError("no float32 neighbour brackets the root")
+
+
+def test_cosine_distance_is_float32_step_by_step():
+    # 1 - a.b / sqrt(|a|^2 |b|^2): inner product and squared norms with one fused
+    # multiply-add per dimension in order, then product, root, quotient and
+    # difference each rounded to float32 (exact rational arithmetic, explicit
+    # rounding, the root bracketed by midpoints); a zero vector is at distance 1.
+    rng = np.random.default_rng(8)
+    x = (rng.standard_normal((6, 11)) * rng.uniform(0.1, 30.0, size=(6, 1))).astype(np.float32)
+    x[5] = 0.0
+
+    def fdot(a, b):
+        acc = Fraction(0)
+        for q in range(len(a)):
+            acc = _round_f32(_fr(a[q]) * _fr(b[q]) + acc)
+        return acc
+
+    for i in range(6):
+        for j in range(6):
+            dot, na, nb = fdot(x[i], x[j]), fdot(x[i], x[i]), fdot(x[j], x[j])
+            den = _sqrt_f32(_round_f32(na * nb))
+            want = _round_f32(1 - _round_f32(dot / den)) if den > 0 else Fraction(1)
+            got = og.distance(x, og.COSINE_F32, i, j)
+            assert Fraction(got) == want, (i, j)
+            assert got == og.distance(x, og.COSINE_F32, j, i)
+            if i < 5 and j < 5:
+                a, b = x[i].astype(np.float64), x[j].astype(np.float64)
+                assert abs(got - (1 - a @ b / np.sqrt((a @ a) * (b @ b)))) < 3e-7
+
+
+def test_cosine_distance_ignores_length_and_has_the_textbook_special_cases():
+    rng = np.random.default_rng(9)
+    x = rng.standard_normal((4, 9)).astype(np.float32)
+    base = og.distance(x, og.COSINE_F32, 0, 1)
+    for e0, e1 in ((3, 0), (-2, 5), (7, -7), (10, 11)):  # powers of two scale exactly
+        y = x.copy()
+        y[0] *= np.float32(2.0 ** e0)
+        y[1] *= np.float32(2.0 ** e1)
+        assert og.distance(y, og.COSINE_F32, 0, 1) == base
+    assert abs(og.distance(x, og.COSINE_F32, 2, 2)) < 2e-7
+    y = np.stack([x[3], -3 * x[3]]).astype(np.float32)
+    assert abs(og.distance(y, og.COSINE_F32, 0, 1) - 2.0) < 3e-7
+    z = np.zeros((3, 9), np.float32)
+    z[0, 0], z[0, 1] = 3.0, 4.0          # |a| = 5
+    z[1, 1] = 5.0                        # |b| = 5, a.b = 20
+    z[2, 4] = 7.0                        # orthogonal to both
+    assert og.distance(z, og.COSINE_F32, 0, 1) == float(np.float32(1) - np.float32(20) / np.float32(25))
+    assert og.distance(z, og.COSINE_F32, 0, 2) == 1.0 and og.distance(z, og.COSINE_F32, 1, 2) == 1.0
+
+
 def test_u8_distance_is_exact_integer():
     rng = np.random.default_rng(5)
     x = rng.integers(0, 256, size=(8, 37)).astype(np.uint8)
@@ -146,6 +208,9 @@ def _numpy_knn(x, metric, K):
     xd = x.astype(np.float64)
     if metric == og.ANGULAR_F32:
         D = 1.0 - xd @ xd.T
+    elif metric == og.COSINE_F32:
+        nrm = np.sqrt((xd ** 2).sum(1))
+        D = 1.0 - (xd @ xd.T) / (nrm[:, None] * nrm[None, :])
     elif metric == og.CHI2_F32:
         tot = xd[:, None, :] + xd[None, :, :]
         D = np.where(tot > 0, (xd[:, None, :] - xd[None, :, :]) ** 2 / np.where(tot > 0, tot, 1),
@@ -191,6 +256,24 @@ def test_bruteforce_chi_square_close_to_float64_and_build_converges():
     rec, _ = og.recall_at(g.ids, g.dist, ids, dist, 10)
     assert rec > 0.97
     _check_lists(g, x, og.CHI2_F32)
+
+
+def test_bruteforce_cosine_close_to_float64_and_build_converges():
+    # vectors of very different lengths: the ranking is that of the angles
+    x = W.deep_like_f32(300, 24, seed=15, n_comp=6)
+    x = (x * np.random.default_rng(15).uniform(0.05, 40.0, size=(300, 1))).astype(np.float32)
+    ids, dist = og.bruteforce(x, og.COSINE_F32, np.arange(300), 10)
+    want, D = _numpy_knn(x, og.COSINE_F32, 10)
+    ref = np.take_along_axis(D, ids.astype(np.int64), 1)
+    assert np.abs(dist - ref).max() < 1e-6
+    assert (ids == want).mean() > 0.99  # only float32 near-ties may differ
+    unit = (x / np.linalg.norm(x.astype(np.float64), axis=1, keepdims=True)).astype(np.float32)
+    ids_unit, _ = og.bruteforce(unit, og.ANGULAR_F32, np.arange(300), 10)
+    assert (ids == ids_unit).mean() > 0.98
+    g, _ = og.build(x, 16, 16, og.COSINE_F32, 7, 8)
+    rec, _ = og.recall_at(g.ids, g.dist, ids, dist, 10)
+    assert rec > 0.97
+    _check_lists(g, x, og.COSINE_F32)
 
 
 def test_bruteforce_points_on_a_line():

@@ -69,6 +69,17 @@ def deep_like_f32(n=10_000_000, d=96, seed=1004, n_comp=1024):
     return x
 
 
+def scaled_directions_f32(n, d, seed, n_comp=16, zero_rows=0):
+    """Vectors of very different lengths (for the cosine distance): DEEP-shaped
+    directions times log-uniform lengths in [0.05, 40); the first `zero_rows`
+    rows are zero vectors."""
+    x = deep_like_f32(n, d, seed=seed, n_comp=n_comp)
+    rng = np.random.default_rng(seed + 7)
+    x *= np.exp(rng.uniform(np.log(0.05), np.log(40.0), size=(n, 1))).astype(np.float32)
+    x[:zero_rows] = 0.0
+    return np.ascontiguousarray(x, dtype=np.float32)
+
+
 def small_integer_f32(n, d, seed, hi=16):
     """Tiny integer-valued float vectors: every distance is an exact small
     integer in any summation order (handy for exact pins)."""
