@@ -68,6 +68,14 @@ __device__ inline uint64_t entry_key(uint64_t e) { return e >> 2; }  // (distanc
 __device__ inline int lane_id() { return (int)(threadIdx.x & (kWave - 1)); }
 __device__ inline uint64_t lanes_below(int lane) { return (1ull << lane) - 1ull; }
 
+// A launch may not span 2^32 threads in one grid dimension (16 M workgroups of
+// 256); launches over more workgroups fold them into two dimensions, and the
+// kernels number their workgroups with this.  Workgroups past the end of the
+// work (the last row of the fold) must leave on their own index checks.
+__device__ inline int64_t block_linear() {
+  return (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
+}
+
 __device__ inline uint64_t readlane64(uint64_t x, int l) {
   uint32_t lo = __builtin_amdgcn_readlane((uint32_t)x, l);
   uint32_t hi = __builtin_amdgcn_readlane((uint32_t)(x >> 32), l);

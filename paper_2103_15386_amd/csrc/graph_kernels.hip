@@ -11,10 +11,10 @@ constexpr int kBlock = 256;
 constexpr int kWavesPerBlock = kBlock / kWave;
 
 __device__ inline int64_t wave_global_index() {
-  return (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+  return block_linear() * kWavesPerBlock + (threadIdx.x >> 6);
 }
-static inline unsigned blocks_for_waves(int64_t waves) {
-  return (unsigned)((waves + kWavesPerBlock - 1) / kWavesPerBlock);
+static inline dim3 blocks_for_waves(int64_t waves) {
+  return grid_blocks((waves + kWavesPerBlock - 1) / kWavesPerBlock);
 }
 
 __device__ inline void counter_add(uint64_t* counters, int which, int64_t stripe_hint,
@@ -207,7 +207,7 @@ template <bool FLOAT>
 __global__ __launch_bounds__(kBlock) void k_get_graph(int64_t total, const uint64_t* G,
                                                       int32_t* ids, void* dist, uint8_t* isnew,
                                                       int32_t id_offset) {
-  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  const int64_t i = block_linear() * kBlock + threadIdx.x;
   if (i >= total) return;
   const uint64_t e = G[i];
   if (ids) ids[i] = (int32_t)entry_id(e) + id_offset;
@@ -222,7 +222,7 @@ template <bool FLOAT>
 __global__ __launch_bounds__(kBlock) void k_set_graph(int64_t total, int k, uint64_t* G,
                                                       NodeMeta* meta, const int32_t* ids,
                                                       const void* dist, const uint8_t* isnew) {
-  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  const int64_t i = block_linear() * kBlock + threadIdx.x;
   if (i >= total) return;
   uint32_t code = FLOAT ? ord_f32(reinterpret_cast<const float*>(dist)[i])
                         : ord_i32(reinterpret_cast<const int32_t*>(dist)[i]);
@@ -253,12 +253,12 @@ __global__ __launch_bounds__(kBlock) void k_get_proposals(int64_t n, const uint6
 // Slots beyond the last segment (the segments need not fill the whole array).
 __global__ __launch_bounds__(kBlock) void k_fill_i32(int32_t* p, const uint64_t* from,
                                                      int64_t end, int32_t value) {
-  const int64_t i = (int64_t)(*from) + (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  const int64_t i = (int64_t)(*from) + block_linear() * kBlock + threadIdx.x;
   if (i < end) p[i] = value;
 }
 
 __global__ __launch_bounds__(kBlock) void k_zero_u32(uint32_t* p, size_t count) {
-  const size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x;
+  const size_t i = (size_t)block_linear() * kBlock + threadIdx.x;
   if (i < count) p[i] = 0u;
 }
 
@@ -482,7 +482,7 @@ static VecSrc vec_src(const Shape& sh) {
 
 hipError_t launch_zero_u32(uint32_t* p, size_t count, hipStream_t st) {
   if (count == 0) return hipSuccess;
-  k_zero_u32<<<(unsigned)((count + kBlock - 1) / kBlock), kBlock, 0, st>>>(p, count);
+  k_zero_u32<<<grid_blocks((int64_t)((count + kBlock - 1) / kBlock)), kBlock, 0, st>>>(p, count);
   return hipGetLastError();
 }
 
@@ -494,7 +494,7 @@ __global__ __launch_bounds__(kBlock) void k_row_norms(VecSrc vs, int64_t n, floa
   __shared__ float tile[kWavesPerBlock][64 * kEvalStride];
   const int lane = lane_id();
   float* my = tile[threadIdx.x >> 6];
-  const int64_t row0 = ((int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6)) * 64;
+  const int64_t row0 = (block_linear() * kWavesPerBlock + (threadIdx.x >> 6)) * 64;
   if (row0 >= n) return;
   const int d = vs.d;
   const int part = lane & 7, rsel = lane >> 3;
@@ -529,7 +529,7 @@ __global__ __launch_bounds__(kBlock) void k_row_norms(VecSrc vs, int64_t n, floa
 
 hipError_t launch_row_norms(const Shape& sh, float* norms, hipStream_t st) {
   const int64_t waves = (sh.n + 63) / 64;
-  k_row_norms<<<(unsigned)((waves + kWavesPerBlock - 1) / kWavesPerBlock), kBlock, 0, st>>>(
+  k_row_norms<<<grid_blocks((waves + kWavesPerBlock - 1) / kWavesPerBlock), kBlock, 0, st>>>(
       vec_src(sh), sh.n, norms);
   return hipGetLastError();
 }
@@ -537,7 +537,7 @@ hipError_t launch_row_norms(const Shape& sh, float* norms, hipStream_t st) {
 hipError_t launch_init_random(const Shape& sh, const DevState& ds, uint64_t seed,
                               hipStream_t st) {
   if (sh.k > kWave) return launch_init_random_wide(sh, ds, seed, st);
-  const unsigned grid = blocks_for_waves(sh.n);
+  const dim3 grid = blocks_for_waves(sh.n);
   const uint64_t base = hash_base(seed, kTagInit);
   switch (sh.metric) {
     case kL2F32:
@@ -563,7 +563,7 @@ hipError_t launch_init_random(const Shape& sh, const DevState& ds, uint64_t seed
 
 hipError_t launch_sample(const Shape& sh, const DevState& ds, uint64_t seed, uint32_t iter,
                          hipStream_t st) {
-  const unsigned grid = blocks_for_waves(sh.n);
+  const dim3 grid = blocks_for_waves(sh.n);
   // forward sampling, and the reverse candidates grouped by target (two-level counting sort)
   hipError_t e = launch_sample_buckets(sh, ds, st);
   if (e != hipSuccess) return e;
@@ -586,7 +586,7 @@ hipError_t launch_update(const Shape& sh, const DevState& ds, hipStream_t st) {
 hipError_t launch_get_graph(const Shape& sh, const DevState& ds, int32_t* ids, void* dist,
                             uint8_t* isnew, int32_t id_offset, hipStream_t st) {
   const int64_t total = sh.n * sh.k;
-  const unsigned grid = (unsigned)((total + kBlock - 1) / kBlock);
+  const dim3 grid = grid_blocks((total + kBlock - 1) / kBlock);
   if (sh.metric == kL2U8)
     k_get_graph<false><<<grid, kBlock, 0, st>>>(total, ds.G, ids, dist, isnew, id_offset);
   else
@@ -597,7 +597,7 @@ hipError_t launch_get_graph(const Shape& sh, const DevState& ds, int32_t* ids, v
 hipError_t launch_set_graph(const Shape& sh, const DevState& ds, const int32_t* ids,
                             const void* dist, const uint8_t* isnew, hipStream_t st) {
   const int64_t total = sh.n * sh.k;
-  const unsigned grid = (unsigned)((total + kBlock - 1) / kBlock);
+  const dim3 grid = grid_blocks((total + kBlock - 1) / kBlock);
   if (sh.metric == kL2U8)
     k_set_graph<false><<<grid, kBlock, 0, st>>>(total, sh.k, ds.G, ds.meta, ids, dist, isnew);
   else
@@ -607,13 +607,13 @@ hipError_t launch_set_graph(const Shape& sh, const DevState& ds, const int32_t* 
 
 hipError_t launch_get_proposals(const Shape& sh, const DevState& ds, int32_t* u, int32_t* v,
                                 void* dist, hipStream_t st) {
-  const unsigned grid = blocks_for_waves(sh.n);
+  const dim3 grid = blocks_for_waves(sh.n);
   if (sh.metric == kL2U8)
     k_get_proposals<false><<<grid, kBlock, 0, st>>>(sh.n, ds.pslot, ds.poff, ds.bins, u, v, dist);
   else
     k_get_proposals<true><<<grid, kBlock, 0, st>>>(sh.n, ds.pslot, ds.poff, ds.bins, u, v, dist);
   const int64_t slots = sh.slots();
-  const unsigned g2 = (unsigned)((slots + kBlock - 1) / kBlock);
+  const dim3 g2 = grid_blocks((slots + kBlock - 1) / kBlock);
   k_fill_i32<<<g2, kBlock, 0, st>>>(u, ds.poff + sh.n, slots, -1);
   k_fill_i32<<<g2, kBlock, 0, st>>>(v, ds.poff + sh.n, slots, -1);
   return hipGetLastError();
@@ -623,7 +623,7 @@ hipError_t launch_merge_init(const Shape& sh, const DevState& ds, uint64_t seed,
                              const MergeIds& mi, const int32_t* ids1, const void* dist1,
                              const int32_t* ids2, const void* dist2, hipStream_t st) {
   if (sh.k > kWave) return launch_merge_init_wide(sh, ds, seed, mi, ids1, dist1, ids2, dist2, st);
-  const unsigned grid = blocks_for_waves(sh.n);
+  const dim3 grid = blocks_for_waves(sh.n);
   const uint64_t base = hash_base(seed, kTagMerge);
   switch (sh.metric) {
     case kL2F32:
@@ -654,7 +654,7 @@ hipError_t launch_merge_init(const Shape& sh, const DevState& ds, uint64_t seed,
 hipError_t launch_merge_final(const Shape& sh, const DevState& ds, const MergeIds& mi,
                               int32_t* ids_out, void* dist_out, hipStream_t st) {
   if (sh.k > kWave) return launch_merge_final_wide(sh, ds, mi, ids_out, dist_out, st);
-  const unsigned grid = blocks_for_waves(sh.n);
+  const dim3 grid = blocks_for_waves(sh.n);
   if (sh.metric == kL2U8)
     k_merge_final<false><<<grid, kBlock, 0, st>>>(sh.n, mi, sh.k, ds.G, ds.aside, ids_out,
                                                   dist_out);

@@ -32,7 +32,7 @@ __global__ __launch_bounds__(256) void k_pack_i8(const void* vec_a, const void* 
                                                  int64_t split, int64_t n, int d, int dpad,
                                                  int8_t* shadow, NodeMeta* meta, int* bad) {
   const int lane = lane_id();
-  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int64_t row = block_linear() * 4 + (threadIdx.x >> 6);
   if (row >= n) return;
   const T* src = row < split ? reinterpret_cast<const T*>(vec_a) + row * d
                              : reinterpret_cast<const T*>(vec_b) + (row - split) * d;
@@ -64,7 +64,7 @@ __global__ __launch_bounds__(256) void k_pack_u8_wide(const uint8_t* vec_a, cons
   const int lane = lane_id();
   const int C = dpad >> 4, per_wave = kWave / C;
   const int grp = lane / C, sub = lane - grp * C;
-  const int64_t row = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * per_wave + grp;
+  const int64_t row = (block_linear() * 4 + (threadIdx.x >> 6)) * per_wave + grp;
   const bool on = grp < per_wave && row < n;
   int32_t part = 0;
   if (on) {
@@ -97,7 +97,7 @@ __global__ __launch_bounds__(256) void k_init_random_i8(const int8_t* __restrict
                                                         NodeMeta* meta, int dpad, int64_t n, int k,
                                                         uint64_t base_hash, uint64_t* G) {
   const int lane = lane_id();
-  const int64_t s = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int64_t s = block_linear() * 4 + (threadIdx.x >> 6);
   if (s >= n) return;
   const int C = dpad >> 4, per_load = kWave / C;
   const int grp = lane / C, sub = lane - grp * C;
@@ -552,7 +552,7 @@ hipError_t launch_init_random_i8(const Shape& sh, const DevState& ds, uint64_t s
   // long lists: the general kernel on the original vectors gives the same integers
   if (sh.k > kWave) return launch_init_random_wide(sh, ds, seed, st);
   const int dpad = (sh.d + 31) & ~31;
-  const unsigned grid = (unsigned)((sh.n + 3) / 4);
+  const dim3 grid = grid_blocks((sh.n + 3) / 4);
   const uint64_t base = hash_base(seed, kTagInit);
   if (sh.metric != kL2U8)
     k_init_random_i8<true><<<grid, 256, 0, st>>>(ds.shadow, ds.meta, dpad, sh.n, sh.k, base, ds.G);
@@ -564,10 +564,10 @@ hipError_t launch_init_random_i8(const Shape& sh, const DevState& ds, uint64_t s
 hipError_t launch_pack_i8(const Shape& sh, const DevState& ds, int* bad_flag_dev,
                           hipStream_t st) {
   const int dpad = (sh.d + 31) & ~31;
-  const unsigned grid = (unsigned)((sh.n + 3) / 4);
+  const dim3 grid = grid_blocks((sh.n + 3) / 4);
   if (sh.metric == kL2U8 && (sh.d & 15) == 0) {
     const int64_t per_block = 4 * (kWave / (dpad >> 4));  // rows per workgroup
-    k_pack_u8_wide<<<(unsigned)((sh.n + per_block - 1) / per_block), 256, 0, st>>>(
+    k_pack_u8_wide<<<grid_blocks((sh.n + per_block - 1) / per_block), 256, 0, st>>>(
         static_cast<const uint8_t*>(sh.vec_a), static_cast<const uint8_t*>(sh.vec_b), sh.split,
         sh.n, sh.d, dpad, ds.shadow, ds.meta);
   } else if (sh.metric == kL2U8)

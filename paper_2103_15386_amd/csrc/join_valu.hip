@@ -83,7 +83,8 @@ __global__ __launch_bounds__(kJB) void k_join_valu(
   constexpr bool kNorms = METRIC == kCosineF32;
   static_assert(128 * kLD >= 64 * kDLD, "distance matrix must fit in the staging tile");
 
-  const int64_t s = blockIdx.x;
+  const int64_t s = block_linear();
+  if (s >= n) return;  // a folded grid may be longer than the node list
   const int tid = threadIdx.x;
   const int L = 2 * p;
   const int wave = tid >> 6, lane = tid & 63;
@@ -354,7 +355,7 @@ __global__ __launch_bounds__(kJB) void k_join_valu(
 template <bool ALL>
 static void launch_join_as(const Shape& sh, const DevState& ds, bool merge_mode, hipStream_t st) {
   VecSrc vs{sh.vec_a, sh.vec_b, sh.split, sh.d, sh.norms};
-  const unsigned grid = (unsigned)sh.n;
+  const dim3 grid = grid_blocks(sh.n);
   const uint64_t slots = (uint64_t)sh.slots();  // size of the proposal array
   const int mm = merge_mode ? 1 : 0;
 #define GNND_JOIN_ARGS vs, sh.n, sh.p, mm, ds.snew, ds.sold, ds.cnew, ds.cold, ds.meta, ds.pslot, \

@@ -75,6 +75,14 @@ struct Shape {
   }
 };
 
+// Grid of `blocks` workgroups, folded into two dimensions beyond 2^22 (device side:
+// block_linear()); the fold may add up to 2^22 - 1 workgroups past the end.
+inline dim3 grid_blocks(int64_t blocks) {
+  constexpr int64_t kRow = (int64_t)1 << 22;
+  if (blocks <= kRow) return dim3((unsigned)(blocks > 0 ? blocks : 1));
+  return dim3((unsigned)kRow, (unsigned)((blocks + kRow - 1) / kRow));
+}
+
 hipError_t launch_init_random(const Shape& sh, const DevState& ds, uint64_t seed, hipStream_t st);
 // squared norms of all rows, one fused multiply-add per dimension in dimension order
 hipError_t launch_row_norms(const Shape& sh, float* norms, hipStream_t st);

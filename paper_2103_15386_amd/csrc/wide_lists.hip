@@ -17,10 +17,10 @@ constexpr int kWB = 256;
 constexpr int kWavesPerWB = kWB / kWave;
 
 __device__ inline int64_t wide_wave_index() {
-  return (int64_t)blockIdx.x * kWavesPerWB + (threadIdx.x >> 6);
+  return block_linear() * kWavesPerWB + (threadIdx.x >> 6);
 }
-inline unsigned wide_blocks(int64_t waves) {
-  return (unsigned)((waves + kWavesPerWB - 1) / kWavesPerWB);
+inline dim3 wide_blocks(int64_t waves) {
+  return grid_blocks((waves + kWavesPerWB - 1) / kWavesPerWB);
 }
 
 // 128 values ascending over (lo, hi).
@@ -268,7 +268,7 @@ VecSrc wide_vec_src(const Shape& sh) {
 
 hipError_t launch_init_random_wide(const Shape& sh, const DevState& ds, uint64_t seed,
                                    hipStream_t st) {
-  const unsigned grid = wide_blocks(sh.n);
+  const dim3 grid = wide_blocks(sh.n);
   const uint64_t base = hash_base(seed, kTagInit);
   switch (sh.metric) {
     case kL2F32:
@@ -303,7 +303,7 @@ hipError_t launch_update_wide(const Shape& sh, const DevState& ds, hipStream_t s
 hipError_t launch_merge_init_wide(const Shape& sh, const DevState& ds, uint64_t seed,
                                   const MergeIds& mi, const int32_t* ids1, const void* dist1,
                                   const int32_t* ids2, const void* dist2, hipStream_t st) {
-  const unsigned grid = wide_blocks(sh.n);
+  const dim3 grid = wide_blocks(sh.n);
   const uint64_t base = hash_base(seed, kTagMerge);
   switch (sh.metric) {
     case kL2F32:
@@ -334,7 +334,7 @@ hipError_t launch_merge_init_wide(const Shape& sh, const DevState& ds, uint64_t 
 
 hipError_t launch_merge_final_wide(const Shape& sh, const DevState& ds, const MergeIds& mi,
                                    int32_t* ids_out, void* dist_out, hipStream_t st) {
-  const unsigned grid = wide_blocks(sh.n);
+  const dim3 grid = wide_blocks(sh.n);
   if (sh.metric == kL2U8)
     k_merge_final_wide<false><<<grid, kWB, 0, st>>>(sh.n, mi, sh.k, ds.G, ds.aside, ids_out,
                                                     dist_out);

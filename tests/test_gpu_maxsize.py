@@ -1,0 +1,81 @@
+"""The largest context the library accepts: n = 2^27 nodes (ids, offsets and slot
+counts at their widest), short vectors and lists so that it fits a test.  The
+oracle cannot replay this size; the graph is checked through properties that
+hold at any size, computed on the GPU with torch, and through sampled rows and
+sampled nodes that the oracle recomputes one by one."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as og
+import workloads as W
+
+pytestmark = pytest.mark.gpu
+SEED = W.ALGO_SEED
+N = 1 << 27
+
+
+def _check_graph(ids, dist, n, k):
+    rows = torch.arange(n, device=ids.device, dtype=torch.int32)[:, None]
+    assert int(ids.min()) >= 0 and int(ids.max()) < n
+    assert not bool((ids == rows).any()), "self loop"
+    srt, _ = torch.sort(ids, dim=1)
+    assert bool((srt[:, 1:] != srt[:, :-1]).all()), "duplicate neighbour"
+    assert bool((dist[:, 1:] >= dist[:, :-1]).all()), "list not ascending"
+    tie = dist[:, 1:] == dist[:, :-1]
+    assert bool((ids[:, 1:][tie] > ids[:, :-1][tie]).all()), "equal distances not ordered by id"
+
+
+@pytest.mark.parametrize("kind", ["f32_valu", "u8_mfma"])
+def test_largest_context_builds_a_valid_improving_graph(kind):
+    import paper_2103_15386_amd as amd
+    k, p, iters = 4, 2, 3
+    rng = np.random.default_rng(77)
+    if kind == "u8_mfma":
+        d, metric = 8, og.L2SQ_U8
+        x = rng.integers(0, 256, size=(N, d), dtype=np.uint8)
+    else:
+        d, metric = 4, og.L2SQ_F32
+        x = rng.random((N, d), dtype=np.float32)
+    xd = torch.from_numpy(x).cuda()
+    ctx = amd.Gnnd(xd, k, p, metric, SEED)
+    assert ctx.join_path() == (amd.JOIN_MFMA if kind == "u8_mfma" else amd.JOIN_VALU)
+    ctx.init_random()
+    ids0, dist0 = ctx.graph()
+    _check_graph(ids0, dist0, N, k)
+    print(kind, "init valid", flush=True)
+    # the last rows and some in between: init is the oracle's, row by row
+    probe = np.concatenate([np.arange(5), np.arange(N - 5, N),
+                            W.sample_nodes(N, 30, seed=5)]).astype(np.int64)
+    got_i = ids0[torch.from_numpy(probe).cuda()].cpu().numpy()
+    got_d = dist0[torch.from_numpy(probe).cuda()].cpu().numpy().astype(np.float64)
+    for r, s in enumerate(probe):
+        for j in range(k):
+            assert got_d[r, j] == og.distance(x, metric, int(s), int(got_i[r, j]))
+    q = W.sample_nodes(N, 64, seed=9)
+    og.set_threads(16)
+    tids, tdist = og.bruteforce(x, metric, q, k)
+    qd = torch.from_numpy(q.astype(np.int64)).cuda()
+    prev, recalls, phi = dist0, [], float(dist0.double().sum())
+    for it in range(1, iters + 1):
+        st = ctx.iterate()
+        ids, dist = ctx.graph()
+        assert st["iter"] == it and st["dropped"] == 0 and st["inserts"] > 0
+        assert st["sum_new"] <= 2 * p * N and st["sum_old"] <= 2 * p * N
+        _check_graph(ids, dist, N, k)
+        assert bool((dist <= prev).all()), "a rank of a list got worse"
+        now = float(dist.double().sum())  # the paper's phi(G): falls with every iteration
+        assert now < phi
+        phi = now
+        gi, gd = ids[qd].cpu().numpy(), dist[qd].cpu().numpy().astype(np.float64)
+        for r, s in enumerate(q[:16]):
+            for j in range(k):
+                assert gd[r, j] == og.distance(x, metric, int(s), int(gi[r, j]))
+        rec, _ = og.recall_at(gi, gd, tids, tdist, k)
+        recalls.append(rec)
+        prev = dist
+        print(kind, "iteration", it, "inserts", st["inserts"], "phi", now, "recall", round(rec, 4),
+              flush=True)
+    # three iterations with k = 4 on 1.3e8 points are far from convergence: recall only must not fall
+    assert recalls == sorted(recalls), recalls
+    ctx.close()
