@@ -53,6 +53,12 @@ CASES = {
     "chi2_gist_cut": (lambda: W.gist_like_f32(1500, 96, seed=1031, n_comp=8),
                       og.CHI2_F32, 20, 16, 4),
     "chi2_ragged_d7": (lambda: W.gist_like_f32(600, 7, seed=1032, n_comp=4), og.CHI2_F32, 9, 6, 4),
+    # long vectors: many staged chunks, ragged ends; bytes beyond the matrix-core kernel's 128
+    "l2_d1031": (lambda: W.uniform_f32(400, 1031, seed=1071), og.L2SQ_F32, 8, 4, 3),
+    "u8_d1000": (lambda: W.sift_like_u8(500, 1000, seed=1072, n_comp=4), og.L2SQ_U8, 10, 10, 3),
+    "u8_d257": (lambda: W.sift_like_u8(500, 257, seed=1073, n_comp=4), og.L2SQ_U8, 6, 3, 3),
+    "cosine_d515": (lambda: W.scaled_directions_f32(400, 515, seed=1074, n_comp=4),
+                    og.COSINE_F32, 7, 7, 3),
     # cosine distance of vectors of any length (per-vector squared norms), with zero vectors
     "cosine_raw_d96": (lambda: W.scaled_directions_f32(2500, 96, seed=1061, n_comp=16),
                        og.COSINE_F32, 20, 12, 5),
