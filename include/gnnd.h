@@ -170,7 +170,9 @@ int gnnd_get_graph(gnnd_ctx* ctx, int32_t* ids_dev, void* dist_dev, uint8_t* isn
 
 /* Load a graph (same layout; rows must be sorted by (distance, id) and hold k
  * distinct ids) and set the iteration counter: continuing from a saved graph
- * gives the same bytes as an uninterrupted run. */
+ * gives the same bytes as an uninterrupted run.  Ids are checked on the device:
+ * one outside 0..n-1, or a node in its own list, gives GNND_EINVAL and leaves
+ * the context without a graph.  Synchronises the stream. */
 int gnnd_set_graph(gnnd_ctx* ctx, const int32_t* ids_dev, const void* dist_dev,
                    const uint8_t* isnew_dev, int32_t iter);
 

@@ -877,8 +877,19 @@ int gnnd_set_graph(gnnd_ctx* c, const int32_t* ids, const void* dist, const uint
   if (!c) return fail(nullptr, GNND_EINVAL, "ctx is NULL");
   if (!ids || !dist) return fail(c, GNND_EINVAL, "ids and dist are required");
   if (iter < 0) return fail(c, GNND_EINVAL, "iter must be >= 0");
-  hipError_t e = launch_set_graph(c->sh, c->ds, ids, dist, isnew, c->stream);
+  if (c->merge_mode) return fail(c, GNND_ESTATE, "context belongs to a merge");
+  // ids are checked on the device (they become row numbers); the verdict is fetched here
+  int bad = 0;
+  hipError_t e = launch_zero_u32((uint32_t*)c->flag_dev, 1, c->stream);
+  if (e == hipSuccess) e = launch_set_graph(c->sh, c->ds, ids, dist, isnew, c->flag_dev, c->stream);
+  if (e == hipSuccess)
+    e = hipMemcpyAsync(&bad, c->flag_dev, sizeof bad, hipMemcpyDeviceToHost, c->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
   if (e != hipSuccess) return hip_fail(c, e, "set_graph kernel");
+  if (bad) {
+    c->has_graph = false;
+    return fail(c, GNND_EINVAL, "graph holds ids outside 0..n-1 or a node in its own list");
+  }
   c->has_graph = true;
   c->iter = iter;
   c->stage = 0;

@@ -218,15 +218,25 @@ __global__ __launch_bounds__(kBlock) void k_get_graph(int64_t total, const uint6
   }
 }
 
+// An id that is no node of the graph, or the row's own node, would later be
+// used as a row number: it raises `bad` and is replaced by a valid id, so that
+// nothing can read out of bounds even if the caller ignores the error.
 template <bool FLOAT>
-__global__ __launch_bounds__(kBlock) void k_set_graph(int64_t total, int k, uint64_t* G,
+__global__ __launch_bounds__(kBlock) void k_set_graph(int64_t total, int64_t n, int k, uint64_t* G,
                                                       NodeMeta* meta, const int32_t* ids,
-                                                      const void* dist, const uint8_t* isnew) {
+                                                      const void* dist, const uint8_t* isnew,
+                                                      int* bad) {
   const int64_t i = block_linear() * kBlock + threadIdx.x;
   if (i >= total) return;
   uint32_t code = FLOAT ? ord_f32(reinterpret_cast<const float*>(dist)[i])
                         : ord_i32(reinterpret_cast<const int32_t*>(dist)[i]);
-  G[i] = make_entry(code, (uint32_t)ids[i], isnew ? (uint32_t)(isnew[i] & 1) : 0u);
+  const int64_t row = i / k;
+  uint32_t id = (uint32_t)ids[i];
+  if ((int64_t)id >= n || (int64_t)id == row) {
+    atomicOr(bad, 1);
+    id = (uint32_t)((row + 1 + i % k) % n);
+  }
+  G[i] = make_entry(code, id, isnew ? (uint32_t)(isnew[i] & 1) : 0u);
   if ((i % k) == k - 1) meta[i / k].kth = code;
 }
 
@@ -595,13 +605,16 @@ hipError_t launch_get_graph(const Shape& sh, const DevState& ds, int32_t* ids, v
 }
 
 hipError_t launch_set_graph(const Shape& sh, const DevState& ds, const int32_t* ids,
-                            const void* dist, const uint8_t* isnew, hipStream_t st) {
+                            const void* dist, const uint8_t* isnew, int* bad_flag_dev,
+                            hipStream_t st) {
   const int64_t total = sh.n * sh.k;
   const dim3 grid = grid_blocks((total + kBlock - 1) / kBlock);
   if (sh.metric == kL2U8)
-    k_set_graph<false><<<grid, kBlock, 0, st>>>(total, sh.k, ds.G, ds.meta, ids, dist, isnew);
+    k_set_graph<false><<<grid, kBlock, 0, st>>>(total, sh.n, sh.k, ds.G, ds.meta, ids, dist, isnew,
+                                                bad_flag_dev);
   else
-    k_set_graph<true><<<grid, kBlock, 0, st>>>(total, sh.k, ds.G, ds.meta, ids, dist, isnew);
+    k_set_graph<true><<<grid, kBlock, 0, st>>>(total, sh.n, sh.k, ds.G, ds.meta, ids, dist, isnew,
+                                               bad_flag_dev);
   return hipGetLastError();
 }
 

@@ -103,7 +103,8 @@ hipError_t launch_update_wide(const Shape& sh, const DevState& ds, hipStream_t s
 hipError_t launch_get_graph(const Shape& sh, const DevState& ds, int32_t* ids, void* dist,
                             uint8_t* isnew, int32_t id_offset, hipStream_t st);
 hipError_t launch_set_graph(const Shape& sh, const DevState& ds, const int32_t* ids,
-                            const void* dist, const uint8_t* isnew, hipStream_t st);
+                            const void* dist, const uint8_t* isnew, int* bad_flag_dev,
+                            hipStream_t st);
 hipError_t launch_get_proposals(const Shape& sh, const DevState& ds, int32_t* u, int32_t* v,
                                 void* dist, hipStream_t st);
 struct MergeIds;

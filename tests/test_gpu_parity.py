@@ -228,6 +228,22 @@ def test_errors_are_reported_not_fatal():
         amd.Gnnd(torch.zeros(100, 8), 10, 8)  # CPU tensor: no CPU path
     with pytest.raises(amd.GnndError):  # matrix-core path refuses non-integer floats
         amd.Gnnd(x, 10, 8, amd.L2SQ_F32, 42, amd.JOIN_MFMA)
+    # a graph with an id that is no node, or a node in its own list, is refused on loading
+    # (ids become row numbers), and the context goes on working with a valid one
+    ctx = amd.Gnnd(x, 10, 8)
+    ctx.init_random()
+    ids, dist, flags = ctx.graph(with_flags=True)
+    for row, col, value in ((3, 2, 100), (7, 0, -1), (11, 4, 11), (99, 9, 1 << 30)):
+        broken = ids.clone()
+        broken[row, col] = value
+        with pytest.raises(amd.GnndError) as e:
+            ctx.set_graph(broken, dist, flags, 0)
+        assert e.value.code == -1
+        with pytest.raises(amd.GnndError):
+            ctx.iterate()  # no graph any more
+    ctx.set_graph(ids, dist, flags, 0)
+    assert ctx.iterate()["inserts"] > 0
+    ctx.close()
 
 
 def test_build_with_the_delta_rule_stops_where_the_oracle_does():
