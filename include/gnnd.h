@@ -273,7 +273,9 @@ int gnnd_build_sharded_files(const gnnd_params* prm, const char* vectors_path, i
 /* Exact K nearest neighbours by exhaustive search (the ground truth of
  * Recall@K, Sec. 6.1) of nq query nodes (ids in queries_dev) against all n
  * vectors, the node itself excluded: nq*K ids and distances ascending by
- * (distance, id).  K <= 64.  Needs no context and no workspace. */
+ * (distance, id).  K <= 64.  Needs no context and no workspace.  A query id
+ * outside 0..n-1 (and any rank beyond n-1 neighbours) gets id -1 and the
+ * largest distance. */
 int gnnd_exact_knn(const void* vectors_dev, int64_t n, int32_t d, int32_t metric,
                    const int32_t* queries_dev, int64_t nq, int32_t K, int32_t* ids_out_dev,
                    void* dist_out_dev, void* stream);

@@ -361,9 +361,11 @@ __global__ __launch_bounds__(kBlock) void k_exact_knn(const void* vec, int64_t n
   const int64_t q = blockIdx.x;
   const uint32_t s = (uint32_t)queries[q];
   const T* base = reinterpret_cast<const T*>(vec);
-  const T* qrow = base + (int64_t)s * d;
+  // a query id that is no node reads nothing and gets the "none" answer (-1, largest distance)
+  const bool valid = (int64_t)s < n;
+  const T* qrow = base + (valid ? (int64_t)s * d : 0);
   uint64_t best = kKeyMax;  // ascending in lanes; lanes >= K stay unused
-  for (int64_t c0 = (int64_t)wave * kWave; c0 < n; c0 += kBlock) {
+  for (int64_t c0 = (int64_t)wave * kWave; valid && c0 < n; c0 += kBlock) {
     const int64_t c = c0 + lane;
     uint64_t key = kKeyMax;
     if (c < n && c != (int64_t)s) {

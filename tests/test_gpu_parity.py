@@ -207,6 +207,10 @@ def test_exact_knn_matches_oracle_brute_force(metric, gen):
     oi, od = og.bruteforce(x, metric, q, 10)
     assert (ids.cpu().numpy() == oi).all()
     assert (dist.cpu().numpy().astype(np.float64) == od).all()
+    # query ids that are no nodes are answered with "none", not read
+    bad = torch.tensor([len(x), -1, 5], dtype=torch.int32, device="cuda")
+    ids, dist = amd.exact_knn(_dev(x), bad, 10, metric)
+    assert (ids[:2] == -1).all() and (ids[2] >= 0).all()
 
 
 def test_errors_are_reported_not_fatal():
