@@ -14,13 +14,13 @@
  *    frees device memory: vectors, workspace and outputs belong to the caller
  *    and must outlive the context that uses them.
  *  - Work is enqueued on `stream` (a hipStream_t passed as void*).  Calls that
- *    hand scalars back to the host (statistics) synchronise the stream first;
- *    the others return after enqueueing.
+ *    hand scalars back to the host (statistics, the verdict on a loaded graph)
+ *    synchronise the stream first; the others return after enqueueing.
  *  - Every function returns GNND_OK or a negative error code and never aborts;
  *    gnnd_last_error() gives the text.  Arguments are validated before anything
  *    is launched.
  *  - Ids are int32, 0-based row numbers of the vector array.  Distances are
- *    float32 for the two float metrics and int32 for GNND_L2SQ_U8.
+ *    float32 for the float metrics and int32 for GNND_L2SQ_U8.
  *  - All random draws come from a counter-based hash of (seed, purpose, node,
  *    slot, attempt/iteration): results do not depend on thread timing, and two
  *    runs with the same seed produce the same bytes.
