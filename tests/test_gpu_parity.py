@@ -352,6 +352,34 @@ def test_random_configurations_match_oracle(case_seed):
     ctx.close()
 
 
+@pytest.mark.parametrize("case_seed", list(range(3001, 3011)))
+def test_random_cosine_configurations_match_oracle(case_seed):
+    # the same for the metric with per-vector norms: random lengths, a few zero vectors,
+    # both update modes
+    amd = _amd()
+    rng = np.random.default_rng(case_seed)
+    k = int(rng.choice([2, 5, 16, 32, 33, 64, 70, 128]))
+    p = int(rng.integers(1, min(k, 32) + 1))
+    n = int(rng.integers(k + 2, 1200))
+    d = int(rng.choice([1, 3, 8, 31, 64, 96, 130]))
+    every = bool(rng.random() < 0.3) and p <= 8
+    x = W.scaled_directions_f32(n, d, seed=int(rng.integers(1, 1 << 30)), n_comp=4,
+                                zero_rows=int(rng.integers(0, 4)))
+    algo_seed = int(rng.integers(0, 1 << 40))
+    ctx = amd.Gnnd(_dev(x), k, p, og.COSINE_F32, algo_seed, amd.JOIN_AUTO,
+                   amd.UPDATE_ALL_PAIRS if every else amd.UPDATE_SELECTIVE)
+    ctx.init_random()
+    g = og.init_random(x, k, og.COSINE_F32, algo_seed)
+    _assert_graph_equal(ctx, g, f"init {x.shape} k={k} p={p}")
+    for it in range(1, 4):
+        st = ctx.iterate()
+        want = og.iterate(x, og.COSINE_F32, g, p, algo_seed, it, all_pairs=every)
+        _assert_graph_equal(ctx, g, f"iteration {it} {x.shape} k={k} p={p} all_pairs={every}")
+        for key in ("inserts", "dist_evals", "sum_new", "sum_old", "proposals"):
+            assert st[key] == want[key], (key, st, x.shape, k, p)
+    ctx.close()
+
+
 def test_work_runs_on_the_stream_it_is_given():
     # the context enqueues on the caller's stream (here a side stream of torch's,
     # default priority); the result equals the default-stream one and arrives on
