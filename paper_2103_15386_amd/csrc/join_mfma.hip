@@ -477,14 +477,15 @@ __global__ __launch_bounds__(kMB) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     const uint64_t at_n = (word_n >> kSlotCountBits) + (word_n & kSlotCountMask);
     const uint64_t at_o = (word_o >> kSlotCountBits) + (word_o & kSlotCountMask);
     if (pass[0] && pass[1]) {  // neighbouring slots: one 16-byte store
-      if (at_n + 1 < slots) *reinterpret_cast<EntryPair*>(bins + at_n) = EntryPair{entry[0], entry[1]};
+      if (at_n + 1 < slots)
+        __builtin_nontemporal_store(EntryPair{entry[0], entry[1]}, reinterpret_cast<EntryPair*>(bins + at_n));
       else over_total += 2;
     } else if (want_n) {
-      if (at_n < slots) bins[at_n] = pass[0] ? entry[0] : entry[1];
+      if (at_n < slots) __builtin_nontemporal_store(pass[0] ? entry[0] : entry[1], &bins[at_n]);
       else ++over_total;
     }
     if (pass[2]) {
-      if (at_o < slots) bins[at_o] = entry[2];
+      if (at_o < slots) __builtin_nontemporal_store(entry[2], &bins[at_o]);
       else ++over_total;
     }
 #pragma unroll
