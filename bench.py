@@ -31,7 +31,7 @@ PEAK_INT8_TOPS = 5000.0
 # the same counters show for a 1 GiB device copy (fetch under-reports streaming
 # reads by 2; scattered 128-byte row reads are counted at face value, so the
 # scaled figure is an upper bound).
-JOIN_TRAFFIC = {"fetch_raw_mib": 5524.0, "write_raw_mib": 2311.0, "fetch_scale": 2.0,
+JOIN_TRAFFIC = {"fetch_raw_mib": 5382.0, "write_raw_mib": 2315.0, "fetch_scale": 2.0,
                 "write_scale": 1.0}
 
 
