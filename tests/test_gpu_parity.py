@@ -401,3 +401,38 @@ def test_work_runs_on_the_stream_it_is_given():
     assert torch.equal(ids_a, ids_b) and torch.equal(dist_a, dist_b)
     ctx_a.close()
     ctx_b.close()
+
+
+def test_two_contexts_on_two_streams_do_not_disturb_each_other():
+    # two builds of different shapes and metrics enqueued in alternation on two streams
+    # (default priority), each in its own workspace: both end with the graph a build on
+    # its own produces - the library keeps no state outside the context
+    amd = _amd()
+    xa = _dev(W.sift_like_u8(40000, 64, seed=64, n_comp=8))
+    xb = _dev(W.deep_like_f32(30000, 48, seed=65, n_comp=8))
+    ref_a = amd.gnnd_build(xa, 16, 16, amd.L2SQ_U8, SEED, iters=5)
+    ref_b = amd.gnnd_build(xb, 24, 12, amd.ANGULAR_F32, SEED + 1, iters=5)
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    for s in (sa, sb):
+        s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(sa):
+        ca = amd.Gnnd(xa, 16, 16, amd.L2SQ_U8, SEED)
+        ca.init_random()
+    with torch.cuda.stream(sb):
+        cb = amd.Gnnd(xb, 24, 12, amd.ANGULAR_F32, SEED + 1)
+        cb.init_random()
+    for _ in range(5):
+        with torch.cuda.stream(sa):
+            ca.iterate(want_stats=False)
+        with torch.cuda.stream(sb):
+            cb.iterate(want_stats=False)
+    with torch.cuda.stream(sa):
+        ga = ca.graph()
+    with torch.cuda.stream(sb):
+        gb = cb.graph()
+    sa.synchronize()
+    sb.synchronize()
+    assert torch.equal(ga[0], ref_a[0]) and torch.equal(ga[1], ref_a[1])
+    assert torch.equal(gb[0], ref_b[0]) and torch.equal(gb[1], ref_b[1])
+    for c in (ca, cb, ref_a[2], ref_b[2]):
+        c.close()
