@@ -366,7 +366,10 @@ int merge_impl(const gnnd_params* prm, const void* vec1, int64_t n1, int64_t bas
   int rc = create_impl(&c, prm, vec1, vec2, n1, true);
   if (rc != GNND_OK) return rc;
   const MergeIds mi{n1, base1, n2, base2};
-  hipError_t e = launch_merge_init(c->sh, c->ds, prm->seed, mi, ids1, dist1, ids2, dist2, c->stream);
+  hipError_t e =
+      c->use_mfma
+          ? launch_merge_init_i8(c->sh, c->ds, prm->seed, mi, ids1, dist1, ids2, dist2, c->stream)
+          : launch_merge_init(c->sh, c->ds, prm->seed, mi, ids1, dist1, ids2, dist2, c->stream);
   if (e != hipSuccess) {
     rc = hip_fail(nullptr, e, "merge init kernel");
   } else {

@@ -85,33 +85,27 @@ __global__ __launch_bounds__(256) void k_pack_u8_wide(const uint8_t* vec_a, cons
   if (on && sub == 0) meta[row].norm = total;
 }
 
-// Alg. 1, first loop, on the int8 rows: k distinct random neighbours per node,
-// exact distances |a|^2 + |b|^2 - 2 a.b (four products per v_dot4), sorted
-// ascending by (distance, id), flagged NEW.  One wavefront per node.  A row is
-// C = dpad / 16 <= 8 chunks of 16 bytes; the C lanes of a group read one
-// neighbour's row as one contiguous line (64 / C neighbours per load), multiply
+// Exact squared distances |a|^2 + |b|^2 - 2 a.b (four products per v_dot4) on
+// the int8 rows, from node s to one object per lane: `id` of lanes < count.
+// A row is C = dpad / 16 <= 8 chunks of 16 bytes; the C lanes of a group read
+// one object's row as one contiguous line (64 / C objects per load), multiply
 // it with the node's own chunk and add up across the group; the sums are then
-// handed to the lanes that hold the neighbours, one per lane, for the sort.
-template <bool FCODE>
-__global__ __launch_bounds__(256) void k_init_random_i8(const int8_t* __restrict__ shadow,
-                                                        NodeMeta* meta, int dpad, int64_t n, int k,
-                                                        uint64_t base_hash, uint64_t* G) {
-  const int lane = lane_id();
-  const int64_t s = block_linear() * 4 + (threadIdx.x >> 6);
-  if (s >= n) return;
+// handed to the lanes that hold the objects.  All 64 lanes call it together;
+// lanes >= count get 0.
+__device__ inline int32_t wave_distances_i8(const int8_t* __restrict__ shadow,
+                                            const NodeMeta* meta, int dpad, int64_t s, uint32_t id,
+                                            int count, int lane) {
   const int C = dpad >> 4, per_load = kWave / C;
   const int grp = lane / C, sub = lane - grp * C;
   const bool lane_used = grp < per_load;  // C = 6 leaves four lanes without a group
   const bool pow2 = (C & (C - 1)) == 0;
   const v4i x = *reinterpret_cast<const v4i*>(shadow + s * dpad + 16 * sub);
   const int32_t norm_s = meta[s].norm;
-  // the list for one id per lane, ascending
-  auto list_of = [&](uint32_t id) {
   int32_t dot = 0, norm_id = 0;
-  if (lane < k) norm_id = meta[id].norm;
-  for (int r0 = 0; r0 < k; r0 += per_load) {
-    const int j = r0 + grp;  // the neighbour this group reads
-    const bool act = lane_used && j < k;
+  if (lane < count) norm_id = meta[id].norm;
+  for (int r0 = 0; r0 < count; r0 += per_load) {
+    const int j = r0 + grp;  // the object this group reads
+    const bool act = lane_used && j < count;
     const uint32_t nid = __shfl(id, act ? j : 0, kWave);
     int32_t part = 0;
     if (act) {
@@ -131,16 +125,29 @@ __global__ __launch_bounds__(256) void k_init_random_i8(const int8_t* __restrict
         total += __shfl(part, (grp * C + o) & 63, kWave);
       }
     }
-    // neighbour j = lane sits in group lane - r0
+    // object j = lane sits in group lane - r0
     const int32_t got = __shfl(total, ((lane - r0) * C) & 63, kWave);
     if (lane >= r0 && lane < r0 + per_load) dot = got;
   }
-  uint64_t e = kKeyMax;
-  if (lane < k) {
-    const int32_t dist = norm_s + norm_id - 2 * dot;
-    e = make_entry(FCODE ? ord_f32((float)dist) : ord_i32(dist), id, 1u);
-  }
-  return wave_sort_upto(e, lane, k);
+  return lane < count ? norm_s + norm_id - 2 * dot : 0;
+}
+
+// Alg. 1, first loop, on the int8 rows: k distinct random neighbours per node,
+// exact distances, sorted ascending by (distance, id), flagged NEW.  One
+// wavefront per node.
+template <bool FCODE>
+__global__ __launch_bounds__(256) void k_init_random_i8(const int8_t* __restrict__ shadow,
+                                                        NodeMeta* meta, int dpad, int64_t n, int k,
+                                                        uint64_t base_hash, uint64_t* G) {
+  const int lane = lane_id();
+  const int64_t s = block_linear() * 4 + (threadIdx.x >> 6);
+  if (s >= n) return;
+  // the list for one id per lane, ascending
+  auto list_of = [&](uint32_t id) {
+    const int32_t dist = wave_distances_i8(shadow, meta, dpad, s, id, k, lane);
+    uint64_t e = kKeyMax;
+    if (lane < k) e = make_entry(FCODE ? ord_f32((float)dist) : ord_i32(dist), id, 1u);
+    return wave_sort_upto(e, lane, k);
   };
   // First attempts of all slots at once.  Whether they are valid (pairwise distinct,
   // none the node itself) shows after the sort: equal ids have equal distances and
@@ -151,6 +158,48 @@ __global__ __launch_bounds__(256) void k_init_random_i8(const int8_t* __restrict
                                 (lane > 0 && entry_id(e) == entry_id(prev)));
   if (__ballot(bad) != 0ull)
     e = list_of(draw_slot_by_slot(base_hash, (uint32_t)s, k, (uint32_t)n, 0u, (uint32_t)s, lane));
+  if (lane < k) G[s * k + lane] = e;
+  if (lane == k - 1) meta[s].kth = entry_code(e);
+}
+
+// GGM, Alg. 3 "Divide" + "Append" on the int8 rows: keep the first ceil(k/2)
+// entries (OLD), set the rest aside, refill with floor(k/2) random objects of
+// the other set (NEW, exact distances) and restore the (distance, id) order.
+template <bool FCODE>
+__global__ __launch_bounds__(256) void k_merge_init_i8(const int8_t* __restrict__ shadow,
+                                                       NodeMeta* meta, int dpad, int64_t n,
+                                                       MergeIds mi, int k, uint64_t base_hash,
+                                                       const int32_t* ids1, const void* dist1,
+                                                       const int32_t* ids2, const void* dist2,
+                                                       uint64_t* G, uint64_t* aside) {
+  const int lane = lane_id();
+  const int64_t s = block_linear() * 4 + (threadIdx.x >> 6);
+  if (s >= n) return;
+  const int64_t n1 = mi.n1;
+  const bool first = s < n1;
+  const int64_t loc = first ? s : s - n1;
+  const int32_t* sid = (first ? ids1 : ids2) + loc * k;
+  const void* sdist = first ? dist1 : dist2;
+  const int keep = (k + 1) / 2, fill = k / 2;
+  uint32_t id_in = 0, code_in = 0;
+  if (lane < k) {
+    id_in = mi.to_internal(sid[lane]);  // collection id -> numbering of this merge
+    code_in = FCODE ? ord_f32(reinterpret_cast<const float*>(sdist)[loc * k + lane])
+                    : ord_i32(reinterpret_cast<const int32_t*>(sdist)[loc * k + lane]);
+  }
+  if (lane >= keep && lane < k) aside[s * fill + (lane - keep)] = make_entry(code_in, id_in, 0u);
+  const uint32_t draw = draw_distinct(base_hash, (uint32_t)s, fill,
+                                      (uint32_t)(first ? n - n1 : n1), first ? (uint32_t)n1 : 0u,
+                                      0xffffffffu, lane);
+  const int32_t dist = wave_distances_i8(shadow, meta, dpad, s, draw, fill, lane);
+  const uint32_t code_of_draw = FCODE ? ord_f32((float)dist) : ord_i32(dist);
+  const int src = lane - keep;
+  const uint32_t did = __shfl(draw, src < 0 ? 0 : src, kWave);
+  const uint32_t code = __shfl(code_of_draw, src < 0 ? 0 : src, kWave);
+  uint64_t e = kKeyMax;
+  if (lane < keep) e = make_entry(code_in, id_in, 0u);
+  else if (lane < k) e = make_entry(code, did, 1u);
+  e = wave_sort(e, lane);
   if (lane < k) G[s * k + lane] = e;
   if (lane == k - 1) meta[s].kth = entry_code(e);
 }
@@ -559,6 +608,23 @@ hipError_t launch_init_random_i8(const Shape& sh, const DevState& ds, uint64_t s
     k_init_random_i8<true><<<grid, 256, 0, st>>>(ds.shadow, ds.meta, dpad, sh.n, sh.k, base, ds.G);
   else
     k_init_random_i8<false><<<grid, 256, 0, st>>>(ds.shadow, ds.meta, dpad, sh.n, sh.k, base, ds.G);
+  return hipGetLastError();
+}
+
+hipError_t launch_merge_init_i8(const Shape& sh, const DevState& ds, uint64_t seed,
+                                const MergeIds& mi, const int32_t* ids1, const void* dist1,
+                                const int32_t* ids2, const void* dist2, hipStream_t st) {
+  // long lists: the general kernel on the original vectors gives the same integers
+  if (sh.k > kWave) return launch_merge_init(sh, ds, seed, mi, ids1, dist1, ids2, dist2, st);
+  const int dpad = (sh.d + 31) & ~31;
+  const dim3 grid = grid_blocks((sh.n + 3) / 4);
+  const uint64_t base = hash_base(seed, kTagMerge);
+  if (sh.metric != kL2U8)
+    k_merge_init_i8<true><<<grid, 256, 0, st>>>(ds.shadow, ds.meta, dpad, sh.n, mi, sh.k, base, ids1,
+                                                dist1, ids2, dist2, ds.G, ds.aside);
+  else
+    k_merge_init_i8<false><<<grid, 256, 0, st>>>(ds.shadow, ds.meta, dpad, sh.n, mi, sh.k, base,
+                                                 ids1, dist1, ids2, dist2, ds.G, ds.aside);
   return hipGetLastError();
 }
 

@@ -113,6 +113,10 @@ hipError_t launch_merge_init(const Shape& sh, const DevState& ds, uint64_t seed,
                              const int32_t* ids2, const void* dist2, hipStream_t st);
 hipError_t launch_merge_final(const Shape& sh, const DevState& ds, const MergeIds& mi,
                               int32_t* ids_out, void* dist_out, hipStream_t st);
+// the same on the int8 rows of the matrix-core path (exact integers either way)
+hipError_t launch_merge_init_i8(const Shape& sh, const DevState& ds, uint64_t seed,
+                                const MergeIds& mi, const int32_t* ids1, const void* dist1,
+                                const int32_t* ids2, const void* dist2, hipStream_t st);
 hipError_t launch_merge_init_wide(const Shape& sh, const DevState& ds, uint64_t seed,
                                   const MergeIds& mi, const int32_t* ids1, const void* dist1,
                                   const int32_t* ids2, const void* dist2, hipStream_t st);
