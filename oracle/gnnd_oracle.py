@@ -302,11 +302,15 @@ def pair_schedule(shards):
     return order
 
 
-def build_sharded(vectors, shards, k, p, metric, seed, build_iters, merge_iters):
+def build_sharded(vectors, shards, k, p, metric, seed, build_iters, merge_iters, schedule=None,
+                  after_merge=None):
     """Sec. 5.1 out-of-core scheme on equal shards of consecutive rows: a graph
     per shard (seed + shard number), then every pair of shards merged once in
-    the order of pair_schedule(); each merged graph is stored back as the two
-    shards' sub-graphs.  Merge number m uses seed + 1000 + m."""
+    the order of pair_schedule() (or of `schedule`, a list of pairs, for
+    comparisons of orders); each merged graph is stored back as the two shards'
+    sub-graphs.  Merge number m uses seed + 1000 + m.  `after_merge(m, i, j,
+    before_i, before_j, after_i, after_j)` is called with the two sub-graphs as
+    they were and as they are stored back (a hook for invariant checks)."""
     n = len(vectors)
     size = n // shards
     bases = [i * size for i in range(shards)]
@@ -315,13 +319,16 @@ def build_sharded(vectors, shards, k, p, metric, seed, build_iters, merge_iters)
     for i in range(shards):
         g, _ = build(vectors[bases[i]:bases[i] + sizes[i]], k, p, metric, seed + i, build_iters)
         graphs.append(Graph(g.ids + bases[i], g.dist, g.isnew))
-    for m, (i, j) in enumerate(pair_schedule(shards)):
+    for m, (i, j) in enumerate(pair_schedule(shards) if schedule is None else schedule):
         x = np.concatenate([vectors[bases[i]:bases[i] + sizes[i]],
                             vectors[bases[j]:bases[j] + sizes[j]]])
         g, _ = merge(x, sizes[i], k, p, metric, seed + 1000 + m, graphs[i], graphs[j],
                      merge_iters, bases[i], bases[j])
+        before = graphs[i], graphs[j]
         graphs[i] = Graph(g.ids[:sizes[i]].copy(), g.dist[:sizes[i]].copy(), None)
         graphs[j] = Graph(g.ids[sizes[i]:].copy(), g.dist[sizes[i]:].copy(), None)
+        if after_merge is not None:
+            after_merge(m, i, j, before[0], before[1], graphs[i], graphs[j])
     ids = np.concatenate([g.ids for g in graphs])
     dist = np.concatenate([g.dist for g in graphs])
     return Graph(ids, dist, np.zeros_like(ids, dtype=np.uint8))

@@ -43,6 +43,9 @@ muts = [
  ("cosine norm of the wrong vector", "  const float nb = dot_f32(b, b, d);", "  const float nb = dot_f32(a, a, d);"),
  ("cosine zero vector at distance 0", "  return den > 0.0f ? 1.0f - dot / den : 1.0f;", "  return den > 0.0f ? 1.0f - dot / den : 0.0f;"),
  ("cosine two roots", "  const float den = sqrtf(na * nb);", "  const float den = sqrtf(na) * sqrtf(nb);"),
+ ("merge final without the set-aside half", "    for (int j = 0; j < fill; ++j) {\n      pool[m].id = aside_ids[s * fill + j];", "    for (int j = 0; j < 0; ++j) {\n      pool[m].id = aside_ids[s * fill + j];"),
+ ("merge sets aside one entry twice", "aside_ids[s * fill + j] = og_to_internal(sid[keep + j], n1, base1, n2, base2);\n      aside_dist[s * fill + j] = sdist[keep + j];", "aside_ids[s * fill + j] = og_to_internal(sid[keep + (j ? j - 1 : 0)], n1, base1, n2, base2);\n      aside_dist[s * fill + j] = sdist[keep + (j ? j - 1 : 0)];"),
+ ("merge fill distance to the wrong node", "row[keep + j].d = og_distance(metric, d, vec, s, draw[j]);", "row[keep + j].d = og_distance(metric, d, vec, s > 0 ? s - 1 : s, draw[j]);"),
  ("classic inserts one side only", "        ins += (uint64_t)og_insert_one(k, ids + (int64_t)N[b] * k, dist + (int64_t)N[b] * k,\n                                       isnew + (int64_t)N[b] * k, N[a], dd);\n", ""),
 ]
 root=os.path.dirname(os.path.dirname(os.path.abspath(__file__))); tmp="/tmp/gnnd_oracle_mutants"
