@@ -1,9 +1,11 @@
-"""Full-size checks on the benchmark workload (n = 1,000,000, d = 128, k = 32,
-p = 32, the launch configuration bench.py times): the initial graph and the
-whole first iteration are compared with the oracle element by element; later
-iterations, which the oracle cannot replay within the test budget, are checked
-through properties that hold at any size and through sampled rows the oracle
-can recompute one by one."""
+"""Full-size parity on the benchmark workload (n = 1,000,000, d = 128, k = 32,
+p = 32, the launch configuration bench.py times, matrix-core join): the
+initial graph and the graph after every one of the 7 iterations of a build
+are compared with the oracle element by element (ids, distances, NEW flags,
+counters), the sample lists of every iteration too; Recall@10 on the
+benchmark's 2000 evaluation nodes is computed on both sides (Sec. 6.1
+equation) and must agree within 0.005.  The oracle runs its join on 16 host
+threads (its results do not depend on the thread count)."""
 import numpy as np
 import pytest
 import torch
@@ -14,6 +16,7 @@ import workloads as W
 pytestmark = pytest.mark.gpu
 SEED = W.ALGO_SEED
 N, D, K, P = 1_000_000, 128, 32, 32
+ITERS = 7
 
 
 @pytest.fixture(scope="module")
@@ -22,7 +25,10 @@ def full():
     x = W.sift_like_f32(N, D, seed=1002)
     xd = torch.from_numpy(x).cuda()
     ctx = amd.Gnnd(xd, K, P, amd.L2SQ_F32, SEED)  # auto path, as in bench.py
-    yield amd, x, xd, ctx
+    assert ctx.join_path() == amd.JOIN_MFMA
+    og.set_threads(16)
+    state = {"g": None, "it": 0}
+    yield amd, x, xd, ctx, state
     ctx.close()
 
 
@@ -31,56 +37,69 @@ def _np(ctx):
     return ids.cpu().numpy(), dist.cpu().numpy(), flags.cpu().numpy()
 
 
-def test_first_iteration_equals_oracle_everywhere(full):
-    amd, x, xd, ctx = full
-    og.set_threads(16)
+def _one_iteration(ctx, x, g, it):
+    """GPU stage by stage, oracle stage by stage; everything compared."""
+    ctx.step_sample()
+    snew, cnew, sold, cold = og.sample(g, P, SEED, it)
+    gs = [t.cpu().numpy() for t in ctx.samples()]
+    assert (gs[1] == cnew).all() and (gs[0] == snew).all(), f"NEW samples differ, iteration {it}"
+    assert (gs[3] == cold).all() and (gs[2] == sold).all(), f"OLD samples differ, iteration {it}"
+    del gs
+    ctx.step_join()
+    st = ctx.step_update()
+    pu, pv, pd, pcnt, evals = og.join(x, og.L2SQ_F32, P, snew, cnew, sold, cold)
+    ins = og.update(g, P, pu, pv, pd, pcnt)
+    del pu, pv, pd
+    ids, dist, flags = _np(ctx)
+    assert (ids == g.ids).all(), f"iteration {it}: {(ids != g.ids).any(1).sum()} rows differ"
+    assert (dist.astype(np.float64) == g.dist).all() and (flags == g.isnew).all()
+    assert st["iter"] == it and st["dropped"] == 0
+    assert st["inserts"] == ins and st["dist_evals"] == evals
+    assert st["sum_new"] == int(cnew.sum()) and st["sum_old"] == int(cold.sum())
+    assert st["proposals"] == int(pcnt.sum())
+    print(f"iteration {it} equal: inserts {ins}, evaluations {evals}", flush=True)
+
+
+def test_initial_graph_and_first_iterations_equal_the_oracle_everywhere(full):
+    amd, x, xd, ctx, state = full
     ctx.init_random()
     g = og.init_random(x, K, og.L2SQ_F32, SEED)
     ids, dist, flags = _np(ctx)
     assert (ids == g.ids).all() and (dist.astype(np.float64) == g.dist).all() and flags.all()
     print("init equal", flush=True)
-    ctx.step_sample()
-    snew, cnew, sold, cold = og.sample(g, P, SEED, 1)
-    gs = [t.cpu().numpy() for t in ctx.samples()]
-    assert (gs[1] == cnew).all() and (gs[0] == snew).all()
-    assert (gs[3] == cold).all() and (gs[2] == sold).all()
-    print("samples equal", flush=True)
-    ctx.step_join()
-    st = ctx.step_update()
-    pu, pv, pd, pcnt, evals = og.join(x, og.L2SQ_F32, P, snew, cnew, sold, cold)
-    print("oracle join done", flush=True)
-    ins = og.update(g, P, pu, pv, pd, pcnt)
-    ids, dist, flags = _np(ctx)
-    assert (ids == g.ids).all(), f"{(ids != g.ids).any(1).sum()} rows differ"
-    assert (dist.astype(np.float64) == g.dist).all() and (flags == g.isnew).all()
-    assert st["inserts"] == ins and st["dist_evals"] == evals and st["dropped"] == 0
-    assert st["sum_new"] == int(cnew.sum()) and st["proposals"] == int(pcnt.sum())
+    for it in (1, 2, 3):
+        _one_iteration(ctx, x, g, it)
+    state["g"], state["it"] = g, 3
 
 
-def test_later_iterations_keep_every_invariant(full):
-    amd, x, xd, ctx = full
-    ids0, dist0, _ = _np(ctx)  # state after the first iteration (previous test)
-    rows = W.sample_nodes(N, 300, seed=11)
+def test_late_iterations_equal_the_oracle_everywhere(full):
+    # short NEW lists, long OLD lists, objects sampled as NEW and OLD at once:
+    # the masked tile paths of the matrix-core join, at full size
+    amd, x, xd, ctx, state = full
+    assert state["it"] == 3, "runs after the first three iterations"
+    g = state["g"]
+    for it in range(4, ITERS + 1):
+        _one_iteration(ctx, x, g, it)
+    state["it"] = ITERS
+
+
+def test_recall_of_the_full_size_build_agrees_with_the_oracle(full):
+    amd, x, xd, ctx, state = full
+    assert state["it"] == ITERS
+    g = state["g"]
+    rows = W.sample_nodes(N, 2000)  # the benchmark's evaluation nodes
     tids, tdist = og.bruteforce(x, og.L2SQ_F32, rows, 10)
-    recalls = []
-    for it in range(2, 8):
-        st = ctx.iterate()
-        ids, dist, flags = _np(ctx)
-        assert st["iter"] == it and st["dropped"] == 0
-        assert (dist <= dist0).all()  # every rank of every list only improves
-        assert (np.diff(dist, axis=1) >= 0).all()  # ascending
-        srt = np.sort(ids, axis=1)
-        assert (srt[:, 1:] != srt[:, :-1]).all()  # distinct ids
-        assert (ids != np.arange(N)[:, None]).all() and ids.min() >= 0 and ids.max() < N
-        assert int(flags.sum()) <= st["inserts"]  # p = k: NEW entries are this round's inserts
-        # equal distances are ordered by id
-        tie = dist[:, 1:] == dist[:, :-1]
-        assert (ids[:, 1:][tie] > ids[:, :-1][tie]).all()
-        # sampled rows: stored distances are the true distances of the stored ids
-        for r in rows[:40]:
-            for j in (0, 7, 31):
-                assert dist[r, j] == og.distance(x, og.L2SQ_F32, int(r), int(ids[r, j]))
-        rec, _ = og.recall_at(ids[rows], dist[rows].astype(np.float64), tids, tdist, 10)
-        recalls.append(rec)
-        ids0, dist0 = ids, dist
-    assert recalls == sorted(recalls) and recalls[-1] > 0.9, recalls
+    rec_oracle, _ = og.recall_at(g.ids[rows], g.dist[rows], tids, tdist, 10)
+    q = torch.from_numpy(rows).cuda()
+    gt_ids, gt_dist = amd.exact_knn(xd, q, 10, amd.L2SQ_F32)
+    assert (gt_ids.cpu().numpy() == tids).all()
+    assert (gt_dist.cpu().numpy().astype(np.float64) == tdist).all()
+    _, dist = ctx.graph()
+    rec_gpu = amd.recall_at(dist[q.long()], gt_dist, 10)
+    assert abs(rec_gpu - rec_oracle) <= 0.005, (rec_gpu, rec_oracle)
+    assert rec_gpu >= 0.95, rec_gpu  # the benchmark's target after 7 iterations
+    # a build in one call (the timed form) ends in the same graph
+    ctx.build(ITERS, want_stats=False)
+    ids, dist, flags = _np(ctx)
+    assert (ids == g.ids).all() and (dist.astype(np.float64) == g.dist).all()
+    assert (flags == g.isnew).all()
