@@ -25,14 +25,22 @@ PEAK_HBM_GBS = 8000.0
 PEAK_FP32_TFLOPS = 157.3
 PEAK_INT8_TOPS = 5000.0
 
-# HBM-side traffic of the join kernel per launch on the default workload, from
-# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/gnnd_build_sift1m_d128_k32.md):
-# raw counter MiB averaged over the 7 launches of a build, and the scale factors
-# the same counters show for a 1 GiB device copy (fetch under-reports streaming
-# reads by 2; scattered 128-byte row reads are counted at face value, so the
-# scaled figure is an upper bound).
-JOIN_TRAFFIC = {"fetch_raw_mib": 5382.0, "write_raw_mib": 2315.0, "fetch_scale": 2.0,
-                "write_scale": 1.0}
+# HBM-side traffic of the join kernel on the default workload, from rocprofv3
+# --pmc FETCH_SIZE / WRITE_SIZE (profiles/gnnd_build_sift1m_d128_k32.md): raw counter
+# MiB of every launch of one build (iteration 1, 2, ...), and the factors by which the
+# same counters misread a 1 GiB device copy.  Keyed by (workload, n, d, k, p, join
+# kernel): any other run reports "traffic": null.  A build of T iterations takes the
+# mean of the first T entries; T beyond the table also gives null.
+JOIN_TRAFFIC = {}
+
+
+def join_traffic(key, T):
+    rec = JOIN_TRAFFIC.get(key)
+    if rec is None or T > len(rec["fetch_raw_mib"]) or T > len(rec["write_raw_mib"]):
+        return None, None
+    f = sum(rec["fetch_raw_mib"][:T]) / T
+    w = sum(rec["write_raw_mib"][:T]) / T
+    return ((f * rec["fetch_scale"] + w * rec["write_scale"]) * 2 ** 20, (f + w) * 2 ** 20)
 
 
 def parse():
@@ -54,6 +62,10 @@ def parse():
     ap.add_argument("--cpu-sample-n", type=int, default=None,
                     help="rows of the oracle's timed sample (default 200000; 30000 at d = 960)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-one-thread-n", type=int, default=None,
+                    help="rows of the oracle's one-thread timing (default 30000; 2000 at d = 960)")
+    ap.add_argument("--no-valu-line", action="store_true",
+                    help="skip the extra timing of the same workload through the float32 join")
     ap.add_argument("--workload", choices=["sift1m", "gist1m", "deep10m", "sharded"],
                     default="sift1m",
                     help="sift1m is the metric's workload; gist1m (960-d, squared L2) and deep10m "
@@ -76,6 +88,7 @@ def parse():
     args.n = args.n or n
     args.d = args.d or d
     args.cpu_sample_n = args.cpu_sample_n or (30_000 if args.d > 512 else 200_000)
+    args.cpu_one_thread_n = args.cpu_one_thread_n or (2_000 if args.d > 512 else 30_000)
     return args
 
 
@@ -92,15 +105,13 @@ def float_workload(args, W, amd_or_og):
             "sift-shaped GMM", "squared L2")
 
 
-def cpu_baseline(args, iters):
-    """The oracle as it stands, timed on this host's cores on a cut of the same
-    generator (same d, k, p, same number of iterations)."""
+def time_oracle(args, iters, n, threads):
+    """One oracle build (random initial graph + `iters` iterations) of the first n
+    rows of the workload's generator on `threads` host threads."""
     import oracle as og
     import workloads as W
 
-    cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")))
-    og.set_threads(cores)
-    n = min(args.cpu_sample_n, args.n)
+    og.set_threads(threads)
     gen, metric, _, _ = float_workload(args, W, og)
     x = gen(n)
     t0 = time.perf_counter()
@@ -109,10 +120,26 @@ def cpu_baseline(args, iters):
     for it in range(1, iters + 1):
         evals += og.iterate(x, metric, g, args.p, W.ALGO_SEED, it)["dist_evals"]
     dt = time.perf_counter() - t0
+    return evals, dt
+
+
+def cpu_baseline(args, iters):
+    """The oracle as it stands, timed on this host's cores on cuts of the same
+    generator (same d, k, p, same number of iterations): all cores on the larger
+    cut (the reported value) and one thread on a smaller one (the paper's own
+    baseline is a single thread)."""
+    cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")))
+    n = min(args.cpu_sample_n, args.n)
+    evals, dt = time_oracle(args, iters, n, cores)
+    n1 = min(args.cpu_one_thread_n, args.n)
+    evals1, dt1 = time_oracle(args, iters, n1, 1)
+    what = f"d={args.d}, k={args.k}, p={args.p}, {iters} iterations, init + all stages"
     return {"value": evals / dt, "unit": "dist_evals/s", "cores": cores, "kind": "oracle",
             "build_s_on_sample": dt,
-            "sample": f"n={n} cut of the same generator, d={args.d}, k={args.k}, p={args.p}, "
-                      f"{iters} iterations, init + all stages"}
+            "sample": f"n={n} cut of the same generator, {what}",
+            "one_thread": {"value": evals1 / dt1, "unit": "dist_evals/s", "cores": 1,
+                           "build_s_on_sample": dt1,
+                           "sample": f"n={n1} cut of the same generator, {what}"}}
 
 
 def sharded(args, torch, amd, W, dev):
@@ -230,24 +257,31 @@ def main():
     stream = torch.cuda.current_stream(dev)
     mfma = ctx.join_path() == amd.JOIN_MFMA
 
-    def one_build():
-        ctx.build(T, want_stats=False)
+    def timed_builds(c, steps, warmup):
+        """`steps` builds of T iterations on context c after `warmup` untimed ones: seconds
+        per build by the host clock around the whole loop, and per-build stage milliseconds
+        from HIP events recorded on the stream inside those same builds (a window sized
+        for all of them, created before the clock starts; nothing synchronises in the loop)."""
+        for _ in range(warmup):
+            c.build(T, want_stats=False)
+        c.set_profiling(max(1, T * steps))
+        stream.synchronize()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            c.build(T, want_stats=False)
+        stream.synchronize()
+        torch.cuda.synchronize()
+        per_build = (time.perf_counter() - t0) / steps
+        n_rec, missed, sample_ms, join_ms, update_ms = c.stage_ms()
+        c.set_profiling(0)
+        builds_rec = n_rec / T if n_rec else float("nan")
+        stages = {"sample": sample_ms / builds_rec, "join": join_ms / builds_rec,
+                  "update": update_ms / builds_rec}
+        return per_build, stages, {"recorded": n_rec, "missed": missed, "expected": T * steps}
 
-    for _ in range(args.warmup):
-        one_build()
-    # stage events are recorded on the stream inside the timed builds (no sync in the loop)
-    ctx.set_profiling(True)
-    stream.synchronize()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        one_build()
-    stream.synchronize()
-    torch.cuda.synchronize()
-    build_s = (time.perf_counter() - t0) / args.steps
-    n_rec, sample_ms, join_ms, update_ms = ctx.stage_ms()
-    assert n_rec == T * args.steps, (n_rec, T, args.steps)
-    sample_ms, join_ms, update_ms = (v / args.steps for v in (sample_ms, join_ms, update_ms))
+    build_s, stage, stage_records = timed_builds(ctx, args.steps, args.warmup)
+    sample_ms, join_ms, update_ms = stage["sample"], stage["join"], stage["update"]
 
     total_evals = sum(t["dist_evals"] for t in trace[:T])
 
@@ -264,12 +298,9 @@ def main():
     avg_join_s = join_ms / T / 1e3
     hbm = {"bound": "hbm", "achieved": alg_bytes / avg_join_s / 1e9, "peak": PEAK_HBM_GBS,
            "unit": "GB/s", "traffic": None}
-    default_cfg = (args.n, args.d, args.k, args.p, args.target) == (1_000_000, 128, 32, 32, 0.95)
-    if mfma and default_cfg and T == 7:
-        jt = JOIN_TRAFFIC
-        hbm["traffic"] = (jt["fetch_raw_mib"] * jt["fetch_scale"]
-                          + jt["write_raw_mib"] * jt["write_scale"]) * 2 ** 20
-        hbm["traffic_raw"] = (jt["fetch_raw_mib"] + jt["write_raw_mib"]) * 2 ** 20
+    kernel_name = "k_join_mfma" if mfma else "k_join_valu"
+    hbm["traffic"], hbm["traffic_raw"] = join_traffic(
+        (args.workload, args.n, args.d, args.k, args.p, kernel_name, args.update), T)
     hbm["frac"] = hbm["achieved"] / hbm["peak"]
     if mfma:
         ops = total_evals / T * args.d * 2
@@ -287,7 +318,7 @@ def main():
         roof["other_bound"] = hbm
     else:
         roof["other_bound"] = other
-    roof["kernel"] = "k_join_mfma" if mfma else "k_join_valu"
+    roof["kernel"] = kernel_name
     roof["avg_launch_ms"] = avg_join_s * 1e3
     roof["algorithmic_bytes_per_launch"] = alg_bytes
 
@@ -306,12 +337,32 @@ def main():
         "dist_evals": total_evals, "dist_evals_per_s": total_evals / build_s,
         "join_dist_evals_per_s": total_evals / (join_ms / 1e3),
         "stage_ms": {"sample": sample_ms, "join": join_ms, "update": update_ms},
+        "stage_records": stage_records,
         "per_iteration": [{k: (round(v, 4) if isinstance(v, float) else v) for k, v in t.items()}
                           for t in trace],
         "roofline": roof,
     }
+    if mfma and not args.no_valu_line:
+        # the same workload through the general float32 join (the paper's arithmetic:
+        # one fused multiply-add per dimension and pair), same T, as an extra figure
+        ctx.close()
+        del ctx
+        vctx = amd.Gnnd(xd, args.k, args.p, metric, seed, amd.JOIN_VALU, update_mode)
+        v_s, v_stage, v_rec = timed_builds(vctx, min(args.steps, 3), 1)
+        v_bytes = vectors * (args.d * 4 + 4)
+        v_join_s = v_stage["join"] / T / 1e3
+        out["f32_valu_join"] = {
+            "build_s": v_s, "stage_ms": v_stage, "stage_records": v_rec, "dtype": "f32",
+            "kernel": "k_join_valu", "avg_launch_ms": v_join_s * 1e3,
+            "hbm_frac": v_bytes / v_join_s / 1e9 / PEAK_HBM_GBS,
+            "alu_frac": total_evals / T * args.d * 3 / v_join_s / 1e12 / PEAK_FP32_TFLOPS}
+        vctx.close()
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(args, T)
+        try:
+            out["cpu_baseline"] = cpu_baseline(args, T)
+        except Exception as exc:  # the line is printed whatever happens to the baseline leg
+            out["cpu_baseline"] = {"value": None, "unit": "dist_evals/s", "cores": 0,
+                                   "kind": "oracle", "sample": f"failed: {exc!r}"}
     print(json.dumps(out))
 
 

@@ -128,17 +128,21 @@ const char* gnnd_last_error(const gnnd_ctx* ctx);
  * NULL context. */
 int gnnd_join_path(const gnnd_ctx* ctx);
 
-/* Stage timing without synchronising inside the loop.  While profiling is on,
- * every iteration that is run without statistics (gnnd_iterate with NULL,
- * gnnd_build) records four HIP events on the stream - before sampling, before
- * the cross-matching, before the update, after it - for up to 64 iterations
- * since the last call of gnnd_set_profiling / gnnd_get_stage_ms.
+/* Stage timing without synchronising inside the loop.  gnnd_set_profiling(ctx,
+ * iterations) opens a recording window of that many iterations (at least 64;
+ * at most 65536; 0 switches profiling off); the HIP events of the window are
+ * created by this call.  While profiling is on, every iteration that is run
+ * without statistics (gnnd_iterate with NULL, gnnd_build) records four events on
+ * the stream - before sampling, before the cross-matching, before the update,
+ * after it.  An iteration that finds the window full runs as usual, is not
+ * recorded and is counted as missed.
  * gnnd_get_stage_ms synchronises the stream, returns the number of recorded
- * iterations and the summed milliseconds of each stage over them (all host
- * pointers, required), and starts a new recording window. */
-int gnnd_set_profiling(gnnd_ctx* ctx, int on);
-int gnnd_get_stage_ms(gnnd_ctx* ctx, int32_t* count_host, float* ms_sample_host,
-                      float* ms_join_host, float* ms_update_host);
+ * iterations, the number of missed ones and the summed milliseconds of each
+ * stage over the recorded ones (all host pointers, required), and starts a new
+ * window of the same size. */
+int gnnd_set_profiling(gnnd_ctx* ctx, int iterations);
+int gnnd_get_stage_ms(gnnd_ctx* ctx, int32_t* count_host, int32_t* missed_host,
+                      float* ms_sample_host, float* ms_join_host, float* ms_update_host);
 
 /* Alg. 1, first loop: every list gets k distinct random objects other than the
  * node itself, with their distances, ascending by (distance, id), all flagged

@@ -111,8 +111,8 @@ def load_library():
     lib.gnnd_set_profiling.restype = C.c_int
     lib.gnnd_set_profiling.argtypes = [vp, C.c_int]
     lib.gnnd_get_stage_ms.restype = C.c_int
-    lib.gnnd_get_stage_ms.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_float), C.POINTER(C.c_float),
-                                      C.POINTER(C.c_float)]
+    lib.gnnd_get_stage_ms.argtypes = [vp, C.POINTER(i32), C.POINTER(i32), C.POINTER(C.c_float),
+                                      C.POINTER(C.c_float), C.POINTER(C.c_float)]
     lib.gnnd_exact_knn.restype = C.c_int
     lib.gnnd_exact_knn.argtypes = [vp, i64, i32, i32, vp, i64, i32, vp, vp, vp]
     _lib = lib
@@ -203,15 +203,17 @@ class Gnnd:
         """JOIN_VALU or JOIN_MFMA: the distance evaluation this context resolved to."""
         return int(self._lib.gnnd_join_path(self._ctx))
 
-    def set_profiling(self, on=True):
-        _check(self._lib.gnnd_set_profiling(self._ctx, int(on)), self._ctx)
+    def set_profiling(self, iterations=64):
+        """Open a recording window of `iterations` iterations (0 / False: off)."""
+        _check(self._lib.gnnd_set_profiling(self._ctx, int(iterations)), self._ctx)
 
     def stage_ms(self):
-        """(iterations recorded, ms sampling, ms cross-matching, ms update) since the last call."""
-        cnt, a, b, c = C.c_int32(), C.c_float(), C.c_float(), C.c_float()
-        _check(self._lib.gnnd_get_stage_ms(self._ctx, C.byref(cnt), C.byref(a), C.byref(b),
-                                           C.byref(c)), self._ctx)
-        return cnt.value, a.value, b.value, c.value
+        """(iterations recorded, iterations missed because the window was full, ms sampling,
+        ms cross-matching, ms update) since the last call."""
+        cnt, miss, a, b, c = C.c_int32(), C.c_int32(), C.c_float(), C.c_float(), C.c_float()
+        _check(self._lib.gnnd_get_stage_ms(self._ctx, C.byref(cnt), C.byref(miss), C.byref(a),
+                                           C.byref(b), C.byref(c)), self._ctx)
+        return cnt.value, miss.value, a.value, b.value, c.value
 
     def init_random(self):
         _check(self._lib.gnnd_init_random(self._ctx), self._ctx)

@@ -104,7 +104,8 @@ Layout make_layout(const gnnd_params* q, bool with_aside) {
 
 }  // namespace
 
-constexpr int kProfIters = 64;
+constexpr int kProfItersDefault = 64;    // window of gnnd_set_profiling(ctx, 1)
+constexpr int kProfItersMax = 1 << 16;   // largest window a caller may ask for
 
 struct gnnd_ctx {
   gnnd_params prm;
@@ -121,9 +122,9 @@ struct gnnd_ctx {
   bool have_events;
   // profiling mode: four events per iteration, recorded without synchronising
   bool prof_on;
-  int prof_count;
-  hipEvent_t prof[kProfIters][4];
-  bool have_prof;
+  int prof_count;   // iterations recorded in the current window
+  int prof_missed;  // iterations that found the window full (not recorded)
+  std::vector<hipEvent_t> prof;  // 4 events per iteration of the window
   uint64_t* snap;  // device copy of the counters taken when the iteration began
   std::string err;
 };
@@ -199,7 +200,7 @@ int create_impl(gnnd_ctx** out, const gnnd_params* prm, const void* vec_a, const
   c->have_events = false;
   c->prof_on = false;
   c->prof_count = 0;
-  c->have_prof = false;
+  c->prof_missed = 0;
   bind(c, L);
   // the statistics counters start at zero; the slot words read "nothing received" until the
   // first sampling stage writes them
@@ -312,8 +313,9 @@ int step_update(gnnd_ctx* c) {
 
 int iterate_impl(gnnd_ctx* c, gnnd_iter_stats* out) {
   int rc;
-  if (!out && c->prof_on && c->prof_count < kProfIters) {
-    hipEvent_t* ev = c->prof[c->prof_count];
+  if (!out && c->prof_on && (size_t)c->prof_count * 4 >= c->prof.size()) c->prof_missed += 1;
+  if (!out && c->prof_on && (size_t)c->prof_count * 4 < c->prof.size()) {
+    hipEvent_t* ev = &c->prof[(size_t)c->prof_count * 4];
     (void)hipEventRecord(ev[0], c->stream);
     if ((rc = step_sample(c)) != GNND_OK) return rc;
     (void)hipEventRecord(ev[1], c->stream);
@@ -768,9 +770,7 @@ void gnnd_destroy(gnnd_ctx* c) {
   if (!c) return;
   if (c->have_events)
     for (int i = 0; i < 4; ++i) (void)hipEventDestroy(c->ev[i]);
-  if (c->have_prof)
-    for (int t = 0; t < kProfIters; ++t)
-      for (int i = 0; i < 4; ++i) (void)hipEventDestroy(c->prof[t][i]);
+  for (hipEvent_t ev : c->prof) (void)hipEventDestroy(ev);
   delete c;
 }
 
@@ -781,40 +781,54 @@ int gnnd_join_path(const gnnd_ctx* c) {
   return c->use_mfma ? GNND_JOIN_MFMA : GNND_JOIN_VALU;
 }
 
-int gnnd_set_profiling(gnnd_ctx* c, int on) {
+int gnnd_set_profiling(gnnd_ctx* c, int iterations) {
   if (!c) return fail(nullptr, GNND_EINVAL, "ctx is NULL");
-  if (on && !c->have_prof) {
-    for (int t = 0; t < kProfIters; ++t)
-      for (int i = 0; i < 4; ++i) {
-        hipError_t e = hipEventCreate(&c->prof[t][i]);
-        if (e != hipSuccess) return hip_fail(c, e, "hipEventCreate");
-      }
-    c->have_prof = true;
+  if (iterations < 0 || iterations > kProfItersMax)
+    return fail(c, GNND_EINVAL, "profiling window must be 0 (off) .. 65536 iterations");
+  if (iterations > 0) {
+    // the events are created here, outside any timed loop; a window never shrinks
+    const size_t want =
+        4 * (size_t)(iterations < kProfItersDefault ? kProfItersDefault : iterations);
+    try {
+      c->prof.reserve(want);
+    } catch (...) {
+      return fail(c, GNND_EINVAL, "out of host memory");
+    }
+    while (c->prof.size() < want) {
+      hipEvent_t ev;
+      hipError_t e = hipEventCreate(&ev);
+      if (e != hipSuccess) return hip_fail(c, e, "hipEventCreate");
+      c->prof.push_back(ev);
+    }
   }
-  c->prof_on = on != 0;
+  c->prof_on = iterations != 0;
   c->prof_count = 0;
+  c->prof_missed = 0;
   return GNND_OK;
 }
 
-int gnnd_get_stage_ms(gnnd_ctx* c, int32_t* count, float* ms_sample, float* ms_join,
-                      float* ms_update) {
+int gnnd_get_stage_ms(gnnd_ctx* c, int32_t* count, int32_t* missed, float* ms_sample,
+                      float* ms_join, float* ms_update) {
   if (!c) return fail(nullptr, GNND_EINVAL, "ctx is NULL");
-  if (!count || !ms_sample || !ms_join || !ms_update)
+  if (!count || !missed || !ms_sample || !ms_join || !ms_update)
     return fail(c, GNND_EINVAL, "NULL output pointer");
   hipError_t e = hipStreamSynchronize(c->stream);
   if (e != hipSuccess) return hip_fail(c, e, "hipStreamSynchronize");
   *count = c->prof_count;
+  *missed = c->prof_missed;
   *ms_sample = *ms_join = *ms_update = 0.f;
   for (int t = 0; t < c->prof_count; ++t) {
+    const hipEvent_t* ev = &c->prof[(size_t)t * 4];
     float a = 0, b = 0, d = 0;
-    (void)hipEventElapsedTime(&a, c->prof[t][0], c->prof[t][1]);
-    (void)hipEventElapsedTime(&b, c->prof[t][1], c->prof[t][2]);
-    (void)hipEventElapsedTime(&d, c->prof[t][2], c->prof[t][3]);
+    (void)hipEventElapsedTime(&a, ev[0], ev[1]);
+    (void)hipEventElapsedTime(&b, ev[1], ev[2]);
+    (void)hipEventElapsedTime(&d, ev[2], ev[3]);
     *ms_sample += a;
     *ms_join += b;
     *ms_update += d;
   }
   c->prof_count = 0;
+  c->prof_missed = 0;
   return GNND_OK;
 }
 

@@ -275,19 +275,31 @@ def test_stage_times_are_recorded_per_iteration():
     amd = _amd()
     x = W.sift_like_u8(20000, 64, seed=62, n_comp=8)
     ctx = amd.Gnnd(_dev(x), 16, 16, amd.L2SQ_U8, SEED)
-    ctx.set_profiling(True)
+    ctx.set_profiling(1)
     torch.cuda.synchronize()
     import time
     t0 = time.perf_counter()
     ctx.build(5, want_stats=False)
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
-    count, ms_sample, ms_join, ms_update = ctx.stage_ms()
-    assert count == 5
+    count, missed, ms_sample, ms_join, ms_update = ctx.stage_ms()
+    assert count == 5 and missed == 0
     assert ms_sample > 0 and ms_join > 0 and ms_update > 0
     assert ms_sample + ms_join + ms_update <= wall_ms
-    count, *_ = ctx.stage_ms()  # reading clears the record
-    assert count == 0
+    count, missed, *_ = ctx.stage_ms()  # reading clears the record
+    assert count == 0 and missed == 0
+    # a window holds what was asked for (never fewer than 64 iterations); what does not
+    # fit is counted, not dropped silently: 20 builds of 7 iterations against a window of 100
+    ctx.set_profiling(100)
+    for _ in range(20):
+        ctx.build(7, want_stats=False)
+    count, missed, *_ = ctx.stage_ms()
+    assert (count, missed) == (100, 40)
+    ctx.set_profiling(140)
+    for _ in range(20):
+        ctx.build(7, want_stats=False)
+    count, missed, ms_sample, ms_join, ms_update = ctx.stage_ms()
+    assert (count, missed) == (140, 0) and min(ms_sample, ms_join, ms_update) > 0
     ctx.close()
 
 
