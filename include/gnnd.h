@@ -274,6 +274,35 @@ int gnnd_build_sharded_files(const gnnd_params* prm, const char* vectors_path, i
                              const char* dist_path, void* staging_host, size_t staging_bytes,
                              void* copy_stream, gnnd_shard_stats* stats_host);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): gnnd_build + gnnd_get_graph
+ * in one call whose scratch is a static device array inside the library instead
+ * of a caller's workspace.  prm->workspace_dev / workspace_bytes are ignored;
+ * vectors_dev (n*d, as for gnnd_create) and the outputs ids_out_dev (n*k int32)
+ * and dist_out_dev (n*k float32 / int32 by metric) are the caller's.  Random
+ * initial graph, then exactly max_iters iterations; same result as gnnd_create +
+ * gnnd_build + gnnd_get_graph with the same parameters.
+ *  - The array holds GNND_STATIC_SCRATCH_BYTES = 64 MiB per GPU (about 23,000
+ *    nodes at k = p = 32, d = 128); parameters whose gnnd_workspace_bytes() need
+ *    exceeds it are refused with GNND_ENOSPC before anything is launched.
+ *  - Nothing is allocated or freed, on the device or on the host, and the call
+ *    never synchronises: it enqueues on prm->stream and returns.  The device
+ *    that owns the stream must be the current device.  The first call on a
+ *    device looks the array's address up (the HIP runtime sets the array up on
+ *    that device at this point, and the device holds it until the process
+ *    ends): make one call per device before capturing or entering a loop that
+ *    must not touch the allocator.
+ *  - GNND_JOIN_AUTO takes the matrix-core join for uint8 vectors (d <= 128) and
+ *    the general join for float32 vectors (deciding that float data are byte
+ *    valued would need a synchronisation); GNND_JOIN_MFMA with float32 vectors
+ *    is refused.
+ *  - All calls on one GPU share that GPU's array: two calls that overlap in time
+ *    on one GPU (different streams or threads) race.  Each call clears what it
+ *    needs cleared; nothing is kept from one call to the next. */
+#define GNND_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+int gnnd_build_static(const gnnd_params* prm, const void* vectors_dev, int32_t max_iters,
+                      int32_t* ids_out_dev, void* dist_out_dev);
+
 /* Exact K nearest neighbours by exhaustive search (the ground truth of
  * Recall@K, Sec. 6.1) of nq query nodes (ids in queries_dev) against all n
  * vectors, the node itself excluded: nq*K ids and distances ascending by

@@ -11,6 +11,7 @@ L2SQ_F32, ANGULAR_F32, L2SQ_U8, CHI2_F32, COSINE_F32 = 0, 1, 2, 3, 4
 JOIN_AUTO, JOIN_VALU, JOIN_MFMA = 0, 1, 2
 UPDATE_SELECTIVE, UPDATE_ALL_PAIRS = 0, 1
 OK, EINVAL, ENOSPC, ESTATE, EHIP, EIO = 0, -1, -2, -3, -4, -5
+STATIC_SCRATCH_BYTES = 64 << 20  # GNND_STATIC_SCRATCH_BYTES of include/gnnd.h
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libgnnd_hip.so")
@@ -22,6 +23,7 @@ EXPORTS = [
     "gnnd_get_graph", "gnnd_set_graph", "gnnd_get_samples", "gnnd_get_proposals", "gnnd_merge",
     "gnnd_exact_knn", "gnnd_join_path", "gnnd_set_profiling", "gnnd_get_stage_ms",
     "gnnd_sharded_arena_bytes", "gnnd_build_sharded", "gnnd_build_sharded_files", "gnnd_append",
+    "gnnd_build_static",
 ]
 
 
@@ -113,6 +115,8 @@ def load_library():
     lib.gnnd_get_stage_ms.restype = C.c_int
     lib.gnnd_get_stage_ms.argtypes = [vp, C.POINTER(i32), C.POINTER(i32), C.POINTER(C.c_float),
                                       C.POINTER(C.c_float), C.POINTER(C.c_float)]
+    lib.gnnd_build_static.restype = C.c_int
+    lib.gnnd_build_static.argtypes = [PP, vp, i32, vp, vp]
     lib.gnnd_exact_knn.restype = C.c_int
     lib.gnnd_exact_knn.argtypes = [vp, i64, i32, i32, vp, i64, i32, vp, vp, vp]
     _lib = lib
@@ -297,6 +301,26 @@ def gnnd_build(vectors, k, p, metric=L2SQ_F32, seed=42, iters=12, join_path=JOIN
     ctx.build(iters, want_stats=False)
     ids, dist = ctx.graph()
     return ids, dist, ctx
+
+
+def gnnd_build_static(vectors, k, p, metric=L2SQ_F32, seed=42, iters=12, join_path=JOIN_AUTO,
+                      ids_out=None, dist_out=None):
+    """gnnd_build through the library's static scratch array (no workspace is
+    allocated or passed); returns (ids, dist).  The outputs may be handed in."""
+    lib = load_library()
+    _require_device(vectors, _elem_dtype(metric), "vectors")
+    n, d = vectors.shape
+    dev = vectors.device
+    ids = torch.empty((n, k), dtype=torch.int32, device=dev) if ids_out is None else ids_out
+    dist = (torch.empty((n, k), dtype=_dist_dtype(metric), device=dev) if dist_out is None
+            else dist_out)
+    _require_device(ids, torch.int32, "ids_out")
+    _require_device(dist, _dist_dtype(metric), "dist_out")
+    prm = make_params(n, d, k, p, metric, seed, join_path, _stream_ptr(dev))
+    with torch.cuda.device(dev):
+        _check(lib.gnnd_build_static(C.byref(prm), vectors.data_ptr(), iters, ids.data_ptr(),
+                                     dist.data_ptr()))
+    return ids, dist
 
 
 def gnnd_merge(vec1, vec2, ids1, dist1, ids2, dist2, k, p, metric=L2SQ_F32, seed=42, iters=6,

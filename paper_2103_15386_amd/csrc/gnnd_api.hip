@@ -12,6 +12,7 @@
 #include <chrono>
 #include <cstdio>
 #include <deque>
+#include <mutex>
 #include <cstring>
 #include <new>
 #include <string>
@@ -24,6 +25,13 @@
 #include "kernels.hpp"
 
 using namespace gnnd;
+
+// Workspace of gnnd_build_static: one array per GPU, part of the loaded code
+// object, so the entry point needs no allocation.  Host code never uses this
+// name as an address; it asks the runtime for the array's device address once
+// per device (static_scratch_of) and passes that pointer on.
+constexpr size_t kStaticScratchBytes = GNND_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {
 
@@ -168,27 +176,13 @@ void bind(gnnd_ctx* c, const Layout& L) {
   d.bk_off = (uint64_t*)(w + L.off_bko);
 }
 
-// Shared by gnnd_create and gnnd_merge.
-int create_impl(gnnd_ctx** out, const gnnd_params* prm, const void* vec_a, const void* vec_b,
-                int64_t split, bool merge_mode) {
-  if (!out) return fail(nullptr, GNND_EINVAL, "out is NULL");
-  *out = nullptr;
-  if (const char* m = check_params(prm)) return fail(nullptr, GNND_EINVAL, m);
-  if (!vec_a) return fail(nullptr, GNND_EINVAL, "vectors pointer is NULL");
-  if (((uintptr_t)vec_a & 15) || ((uintptr_t)vec_b & 15))
-    return fail(nullptr, GNND_EINVAL, "vectors must be 16-byte aligned");
-  if (!prm->workspace_dev) return fail(nullptr, GNND_EINVAL, "workspace is NULL");
-  if ((uintptr_t)prm->workspace_dev & 255)
-    return fail(nullptr, GNND_EINVAL, "workspace must be 256-byte aligned");
-  Layout L = make_layout(prm, merge_mode);
-  if (prm->workspace_bytes < L.total) {
-    char buf[128];
-    snprintf(buf, sizeof buf, "workspace too small: %zu bytes given, %zu needed",
-             prm->workspace_bytes, L.total);
-    return fail(nullptr, GNND_ENOSPC, buf);
-  }
-  gnnd_ctx* c = new (std::nothrow) gnnd_ctx();
-  if (!c) return fail(nullptr, GNND_EINVAL, "out of host memory");
+// Fill in a default-constructed context (no allocation of any kind): layout,
+// cleared counters, per-vector norms, int8 copy.  `may_sync` = the caller allows
+// a stream synchronisation: float32 data qualify for the matrix-core join only
+// after a device-side check whose verdict has to be read back; without it float
+// data take the general join (uint8 data always qualify, nothing is read back).
+int init_ctx(gnnd_ctx* c, const gnnd_params* prm, const Layout& L, const void* vec_a,
+             const void* vec_b, int64_t split, bool merge_mode, bool may_sync) {
   c->prm = *prm;
   c->stream = (hipStream_t)prm->stream;
   c->sh = Shape{prm->n, prm->d, prm->k, prm->p, prm->metric, split, vec_a, vec_b,
@@ -207,43 +201,65 @@ int create_impl(gnnd_ctx** out, const gnnd_params* prm, const void* vec_a, const
   hipError_t e = launch_zero_u32((uint32_t*)c->ds.pslot, 2 * (size_t)prm->n, c->stream);
   if (e == hipSuccess)
     e = launch_zero_u32((uint32_t*)c->ds.counters, (size_t)kStripes * C_SLOTS * 2, c->stream);
-  if (e != hipSuccess) {
-    int rc = hip_fail(nullptr, e, "clearing workspace counters");
-    delete c;
-    return rc;
-  }
+  if (e != hipSuccess) return hip_fail(nullptr, e, "clearing workspace counters");
   if (prm->metric == GNND_COSINE_F32) {  // the squared norms the cosine distance divides by
     float* norms = reinterpret_cast<float*>(static_cast<char*>(prm->workspace_dev) + L.off_norms);
     c->sh.norms = norms;
     e = launch_row_norms(c->sh, norms, c->stream);
-    if (e != hipSuccess) {
-      int rc = hip_fail(nullptr, e, "row norm kernel");
-      delete c;
-      return rc;
-    }
+    if (e != hipSuccess) return hip_fail(nullptr, e, "row norm kernel");
   }
   // matrix-core path: build the int8 copy; float data qualifies only when every
   // value is an integer in 0..255 (then all distances are exact either way)
   c->use_mfma = false;
-  if (mfma_possible(prm)) {
+  if (mfma_possible(prm) && (may_sync || prm->metric == GNND_L2SQ_U8)) {
     int bad = 0;
     e = launch_zero_u32((uint32_t*)c->flag_dev, 1, c->stream);
     if (e == hipSuccess) e = launch_pack_i8(c->sh, c->ds, c->flag_dev, c->stream);
-    if (e == hipSuccess)
-      e = hipMemcpyAsync(&bad, c->flag_dev, sizeof bad, hipMemcpyDeviceToHost, c->stream);
-    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
-    if (e != hipSuccess) {
-      int rc = hip_fail(nullptr, e, "packing vectors to int8");
-      delete c;
-      return rc;
+    if (prm->metric != GNND_L2SQ_U8) {  // bytes always fit; floats have to be looked at
+      if (e == hipSuccess)
+        e = hipMemcpyAsync(&bad, c->flag_dev, sizeof bad, hipMemcpyDeviceToHost, c->stream);
+      if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
     }
+    if (e != hipSuccess) return hip_fail(nullptr, e, "packing vectors to int8");
     c->use_mfma = (bad == 0);
   }
-  if (prm->join_path == GNND_JOIN_MFMA && !c->use_mfma) {
-    delete c;
+  if (prm->join_path == GNND_JOIN_MFMA && !c->use_mfma)
     return fail(nullptr, GNND_EINVAL,
-                "GNND_JOIN_MFMA needs d <= 128 and uint8 vectors or float32 vectors holding "
-                "integers 0..255 with the squared-L2 metric");
+                may_sync ? "GNND_JOIN_MFMA needs d <= 128 and uint8 vectors or float32 vectors "
+                           "holding integers 0..255 with the squared-L2 metric"
+                         : "GNND_JOIN_MFMA needs d <= 128 and uint8 vectors here (float32 "
+                           "vectors have to be checked, which synchronises: use gnnd_create)");
+  return GNND_OK;
+}
+
+const char* check_pointers(const gnnd_params* prm, const void* vec_a, const void* vec_b) {
+  if (!vec_a) return "vectors pointer is NULL";
+  if (((uintptr_t)vec_a & 15) || ((uintptr_t)vec_b & 15)) return "vectors must be 16-byte aligned";
+  if (!prm->workspace_dev) return "workspace is NULL";
+  if ((uintptr_t)prm->workspace_dev & 255) return "workspace must be 256-byte aligned";
+  return nullptr;
+}
+
+// Shared by gnnd_create and gnnd_merge.
+int create_impl(gnnd_ctx** out, const gnnd_params* prm, const void* vec_a, const void* vec_b,
+                int64_t split, bool merge_mode) {
+  if (!out) return fail(nullptr, GNND_EINVAL, "out is NULL");
+  *out = nullptr;
+  if (const char* m = check_params(prm)) return fail(nullptr, GNND_EINVAL, m);
+  if (const char* m = check_pointers(prm, vec_a, vec_b)) return fail(nullptr, GNND_EINVAL, m);
+  Layout L = make_layout(prm, merge_mode);
+  if (prm->workspace_bytes < L.total) {
+    char buf[128];
+    snprintf(buf, sizeof buf, "workspace too small: %zu bytes given, %zu needed",
+             prm->workspace_bytes, L.total);
+    return fail(nullptr, GNND_ENOSPC, buf);
+  }
+  gnnd_ctx* c = new (std::nothrow) gnnd_ctx();
+  if (!c) return fail(nullptr, GNND_EINVAL, "out of host memory");
+  const int rc = init_ctx(c, prm, L, vec_a, vec_b, split, merge_mode, true);
+  if (rc != GNND_OK) {
+    delete c;
+    return rc;
   }
   *out = c;
   return GNND_OK;
@@ -753,6 +769,30 @@ done:
 }
 #undef GNND_HIP
 
+// Device address of the static scratch array on the current device, looked up
+// once per device (every GPU holds its own copy of the array at its own address).
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {nullptr};
+
+int static_scratch_of(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(nullptr, e, "hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices) return fail(nullptr, GNND_EINVAL, "device number out of range");
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_fail(nullptr, e, "hipGetSymbolAddress(scratch)");
+    if (!ptr || ((uintptr_t)ptr & 255))
+      return fail(nullptr, GNND_EHIP, "the static scratch array has no usable device address");
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return GNND_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -1042,6 +1082,40 @@ int gnnd_build_sharded_files(const gnnd_params* prm, const char* vectors_path, i
   }
   if (hipError_t e = store.open_streams()) return hip_fail(nullptr, e, "creating the file stream");
   return run_sharded(prm, pl, store, build_iters, merge_iters, (hipStream_t)copy_stream, stats);
+}
+
+int gnnd_build_static(const gnnd_params* prm, const void* vectors_dev, int32_t max_iters,
+                      int32_t* ids_out_dev, void* dist_out_dev) {
+  if (const char* m = check_params(prm)) return fail(nullptr, GNND_EINVAL, m);
+  if (max_iters < 0) return fail(nullptr, GNND_EINVAL, "max_iters must be >= 0");
+  if (!ids_out_dev || !dist_out_dev) return fail(nullptr, GNND_EINVAL, "NULL output pointer");
+  gnnd_params q = *prm;
+  q.workspace_dev = nullptr;
+  q.workspace_bytes = 0;
+  const Layout L = make_layout(&q, false);
+  if (L.total > kStaticScratchBytes) {
+    char buf[192];
+    snprintf(buf, sizeof buf,
+             "these parameters need %zu bytes of scratch, the static array holds %zu: use "
+             "gnnd_create / gnnd_build with a workspace of the caller's",
+             L.total, kStaticScratchBytes);
+    return fail(nullptr, GNND_ENOSPC, buf);
+  }
+  void* base = nullptr;
+  if (int rc = static_scratch_of(&base)) return rc;
+  q.workspace_dev = base;
+  q.workspace_bytes = kStaticScratchBytes;
+  if (const char* m = check_pointers(&q, vectors_dev, nullptr)) return fail(nullptr, GNND_EINVAL, m);
+  gnnd_ctx c;  // on the stack: nothing is allocated on the host either
+  int rc = init_ctx(&c, &q, L, vectors_dev, nullptr, q.n, false, /*may_sync=*/false);
+  if (rc == GNND_OK) rc = gnnd_build(&c, max_iters, 0.f, nullptr);
+  if (rc == GNND_OK) {
+    hipError_t e = launch_get_graph(c.sh, c.ds, ids_out_dev, dist_out_dev, nullptr, 0, c.stream);
+    if (e != hipSuccess) rc = hip_fail(nullptr, e, "get_graph kernel");
+  } else if (!c.err.empty()) {
+    g_last_error = c.err;
+  }
+  return rc;
 }
 
 int gnnd_exact_knn(const void* vec, int64_t n, int32_t d, int32_t metric, const int32_t* queries,
