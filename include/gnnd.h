@@ -65,7 +65,12 @@ enum {
 enum {
   GNND_JOIN_AUTO = 0, /* library picks                                               */
   GNND_JOIN_VALU = 1, /* per-pair float32 fused accumulation in dimension order      */
-  GNND_JOIN_MFMA = 2  /* Gram-block form on the matrix cores (exact for uint8 data)  */
+  GNND_JOIN_MFMA = 2, /* Gram-block form on the matrix cores (exact for uint8 data)  */
+  GNND_JOIN_MFMA_DIRECT = 3 /* the same, every nearest-object result handed to its
+                               destination list by itself (one device-wide atomic each);
+                               GNND_JOIN_MFMA / AUTO collect the results per workgroup and
+                               bucket of destinations first where the workspace for that is
+                               affordable (n <= 2^20) and use this form beyond.  Same lists */
 };
 
 /* Which cross-matching results go to the list update. */
@@ -104,7 +109,9 @@ typedef struct gnnd_iter_stats {
   uint64_t dropped;    /* results lost to a full proposal segment: always 0        */
   uint64_t passed;     /* results handed to the list update (after the early drop) */
   float ms_sample, ms_join, ms_update;
-  float reserved2;
+  float ms_handout;    /* between join and update: the pass that moves staged results into
+                          the destination lists' segments (matrix-core join, n <= 2^20);
+                          ~0 where results are handed on inside the join itself        */
 } gnnd_iter_stats;
 
 /* Device scratch needed for these parameters (pure host arithmetic; n, d, k, p,
@@ -133,8 +140,9 @@ int gnnd_join_path(const gnnd_ctx* ctx);
  * at most 65536; 0 switches profiling off); the HIP events of the window are
  * created by this call.  While profiling is on, every iteration that is run
  * without statistics (gnnd_iterate with NULL, gnnd_build) records four events on
- * the stream - before sampling, before the cross-matching, before the update,
- * after it.  An iteration that finds the window full runs as usual, is not
+ * the stream - before sampling, before the cross-matching, behind the
+ * cross-matching kernel (in front of the pass that moves staged results into
+ * the destinations' segments, where there is one), before the update, after it.  An iteration that finds the window full runs as usual, is not
  * recorded and is counted as missed.
  * gnnd_get_stage_ms synchronises the stream, returns the number of recorded
  * iterations, the number of missed ones and the summed milliseconds of each
@@ -142,7 +150,8 @@ int gnnd_join_path(const gnnd_ctx* ctx);
  * window of the same size. */
 int gnnd_set_profiling(gnnd_ctx* ctx, int iterations);
 int gnnd_get_stage_ms(gnnd_ctx* ctx, int32_t* count_host, int32_t* missed_host,
-                      float* ms_sample_host, float* ms_join_host, float* ms_update_host);
+                      float* ms_sample_host, float* ms_join_host, float* ms_handout_host,
+                      float* ms_update_host);
 
 /* Alg. 1, first loop: every list gets k distinct random objects other than the
  * node itself, with their distances, ascending by (distance, id), all flagged
@@ -282,7 +291,7 @@ int gnnd_build_sharded_files(const gnnd_params* prm, const char* vectors_path, i
  * and dist_out_dev (n*k float32 / int32 by metric) are the caller's.  Random
  * initial graph, then exactly max_iters iterations; same result as gnnd_create +
  * gnnd_build + gnnd_get_graph with the same parameters.
- *  - The array holds GNND_STATIC_SCRATCH_BYTES = 64 MiB per GPU (about 23,000
+ *  - The array holds GNND_STATIC_SCRATCH_BYTES = 64 MiB per GPU (about 12,000
  *    nodes at k = p = 32, d = 128); parameters whose gnnd_workspace_bytes() need
  *    exceeds it are refused with GNND_ENOSPC before anything is launched.
  *  - Nothing is allocated or freed, on the device or on the host, and the call

@@ -8,7 +8,7 @@ import numpy as np
 import torch
 
 L2SQ_F32, ANGULAR_F32, L2SQ_U8, CHI2_F32, COSINE_F32 = 0, 1, 2, 3, 4
-JOIN_AUTO, JOIN_VALU, JOIN_MFMA = 0, 1, 2
+JOIN_AUTO, JOIN_VALU, JOIN_MFMA, JOIN_MFMA_DIRECT = 0, 1, 2, 3
 UPDATE_SELECTIVE, UPDATE_ALL_PAIRS = 0, 1
 OK, EINVAL, ENOSPC, ESTATE, EHIP, EIO = 0, -1, -2, -3, -4, -5
 STATIC_SCRATCH_BYTES = 64 << 20  # GNND_STATIC_SCRATCH_BYTES of include/gnnd.h
@@ -45,7 +45,7 @@ class IterStats(C.Structure):
                 ("dist_evals", C.c_uint64), ("sum_new", C.c_uint64), ("sum_old", C.c_uint64),
                 ("proposals", C.c_uint64), ("dropped", C.c_uint64), ("passed", C.c_uint64),
                 ("ms_sample", C.c_float), ("ms_join", C.c_float),
-                ("ms_update", C.c_float), ("reserved2", C.c_float)]
+                ("ms_update", C.c_float), ("ms_handout", C.c_float)]
 
     def as_dict(self):
         return {f: getattr(self, f) for f, _ in self._fields_ if not f.startswith("reserved")}
@@ -114,7 +114,8 @@ def load_library():
     lib.gnnd_set_profiling.argtypes = [vp, C.c_int]
     lib.gnnd_get_stage_ms.restype = C.c_int
     lib.gnnd_get_stage_ms.argtypes = [vp, C.POINTER(i32), C.POINTER(i32), C.POINTER(C.c_float),
-                                      C.POINTER(C.c_float), C.POINTER(C.c_float)]
+                                      C.POINTER(C.c_float), C.POINTER(C.c_float),
+                                      C.POINTER(C.c_float)]
     lib.gnnd_build_static.restype = C.c_int
     lib.gnnd_build_static.argtypes = [PP, vp, i32, vp, vp]
     lib.gnnd_exact_knn.restype = C.c_int
@@ -213,11 +214,12 @@ class Gnnd:
 
     def stage_ms(self):
         """(iterations recorded, iterations missed because the window was full, ms sampling,
-        ms cross-matching, ms update) since the last call."""
-        cnt, miss, a, b, c = C.c_int32(), C.c_int32(), C.c_float(), C.c_float(), C.c_float()
+        ms cross-matching, ms hand-out pass, ms update) since the last call."""
+        cnt, miss = C.c_int32(), C.c_int32()
+        a, b, h, c = C.c_float(), C.c_float(), C.c_float(), C.c_float()
         _check(self._lib.gnnd_get_stage_ms(self._ctx, C.byref(cnt), C.byref(miss), C.byref(a),
-                                           C.byref(b), C.byref(c)), self._ctx)
-        return cnt.value, miss.value, a.value, b.value, c.value
+                                           C.byref(b), C.byref(h), C.byref(c)), self._ctx)
+        return cnt.value, miss.value, a.value, b.value, h.value, c.value
 
     def init_random(self):
         _check(self._lib.gnnd_init_random(self._ctx), self._ctx)

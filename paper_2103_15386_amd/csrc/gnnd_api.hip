@@ -40,7 +40,8 @@ thread_local std::string g_last_error = "";
 struct Layout {
   size_t off_G, off_kth, off_snew, off_sold, off_cnew, off_cold, off_ron,
       off_roo, off_csn, off_cso, off_capn, off_capo, off_pslot, off_poff, off_bins, off_scan,
-      off_cnt, off_snap, off_aside, off_shadow, off_norms, off_flag, off_bkc, off_bko, total;
+      off_cnt, off_snap, off_aside, off_shadow, off_norms, off_flag, off_bkc, off_bko, off_stg_ent,
+      off_stg_cur, total;
 };
 
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -55,10 +56,12 @@ const char* check_params(const gnnd_params* q) {
   if (q->n <= q->k) return "n must exceed k";
   if (q->n > ((int64_t)1 << 27)) return "n must be <= 2^27";
   if (q->n * (int64_t)q->p >= ((int64_t)1 << 32)) return "n * p must be below 2^32";
-  if (q->join_path < GNND_JOIN_AUTO || q->join_path > GNND_JOIN_MFMA) return "unknown join_path";
+  if (q->join_path < GNND_JOIN_AUTO || q->join_path > GNND_JOIN_MFMA_DIRECT)
+    return "unknown join_path";
   if (q->update_mode != GNND_UPDATE_SELECTIVE && q->update_mode != GNND_UPDATE_ALL_PAIRS)
     return "unknown update_mode";
-  if (q->update_mode == GNND_UPDATE_ALL_PAIRS && q->join_path == GNND_JOIN_MFMA)
+  if (q->update_mode == GNND_UPDATE_ALL_PAIRS &&
+      (q->join_path == GNND_JOIN_MFMA || q->join_path == GNND_JOIN_MFMA_DIRECT))
     return "GNND_UPDATE_ALL_PAIRS runs with GNND_JOIN_VALU (or GNND_JOIN_AUTO) only";
   return nullptr;
 }
@@ -68,6 +71,13 @@ const char* check_params(const gnnd_params* q) {
 bool mfma_possible(const gnnd_params* q) {
   return q->join_path != GNND_JOIN_VALU && q->update_mode == GNND_UPDATE_SELECTIVE && q->d <= 128 &&
          (q->metric == GNND_L2SQ_U8 || q->metric == GNND_L2SQ_F32);
+}
+
+// The matrix-core join stages its results per bucket of destinations (instead of handing
+// them on one by one) for up to 2^20 nodes: a staged result then fits one 64-bit word, and
+// the staging array is as large again as the proposal array.
+bool stage_possible(const gnnd_params* q) {
+  return mfma_possible(q) && q->join_path != GNND_JOIN_MFMA_DIRECT && q->n <= kStageMaxNodes;
 }
 
 Layout make_layout(const gnnd_params* q, bool with_aside) {
@@ -106,6 +116,9 @@ Layout make_layout(const gnnd_params* q, bool with_aside) {
   L.off_flag = take(256);
   L.off_bkc = take(2 * 4096 * 4);
   L.off_bko = take(2 * 4097 * 8);
+  const bool staged = stage_possible(q);
+  L.off_stg_ent = take(staged ? n * slots_per_node * 8 : 0);
+  L.off_stg_cur = take(staged ? (size_t)kStageBuckets * 8 : 0);
   L.total = o;
   return L;
 }
@@ -114,6 +127,7 @@ Layout make_layout(const gnnd_params* q, bool with_aside) {
 
 constexpr int kProfItersDefault = 64;    // window of gnnd_set_profiling(ctx, 1)
 constexpr int kProfItersMax = 1 << 16;   // largest window a caller may ask for
+constexpr int kProfEvents = 5;  // before sampling, join, hand-out pass, update; after the update
 
 struct gnnd_ctx {
   gnnd_params prm;
@@ -126,13 +140,13 @@ struct gnnd_ctx {
   bool merge_mode;
   bool use_mfma;
   int* flag_dev;
-  hipEvent_t ev[4];
+  hipEvent_t ev[5];
   bool have_events;
   // profiling mode: four events per iteration, recorded without synchronising
   bool prof_on;
   int prof_count;   // iterations recorded in the current window
   int prof_missed;  // iterations that found the window full (not recorded)
-  std::vector<hipEvent_t> prof;  // 4 events per iteration of the window
+  std::vector<hipEvent_t> prof;  // kProfEvents events per iteration of the window
   uint64_t* snap;  // device copy of the counters taken when the iteration began
   std::string err;
 };
@@ -174,6 +188,9 @@ void bind(gnnd_ctx* c, const Layout& L) {
   c->flag_dev = (int*)(w + L.off_flag);
   d.bk_cnt = (uint32_t*)(w + L.off_bkc);
   d.bk_off = (uint64_t*)(w + L.off_bko);
+  const bool staged = stage_possible(&c->prm);
+  d.stg_ent = staged ? (uint64_t*)(w + L.off_stg_ent) : nullptr;
+  d.stg_cur = staged ? (unsigned long long*)(w + L.off_stg_cur) : nullptr;
 }
 
 // Fill in a default-constructed context (no allocation of any kind): layout,
@@ -223,7 +240,7 @@ int init_ctx(gnnd_ctx* c, const gnnd_params* prm, const Layout& L, const void* v
     if (e != hipSuccess) return hip_fail(nullptr, e, "packing vectors to int8");
     c->use_mfma = (bad == 0);
   }
-  if (prm->join_path == GNND_JOIN_MFMA && !c->use_mfma)
+  if ((prm->join_path == GNND_JOIN_MFMA || prm->join_path == GNND_JOIN_MFMA_DIRECT) && !c->use_mfma)
     return fail(nullptr, GNND_EINVAL,
                 may_sync ? "GNND_JOIN_MFMA needs d <= 128 and uint8 vectors or float32 vectors "
                            "holding integers 0..255 with the squared-L2 metric"
@@ -267,7 +284,7 @@ int create_impl(gnnd_ctx** out, const gnnd_params* prm, const void* vec_a, const
 
 int ensure_events(gnnd_ctx* c) {
   if (c->have_events) return GNND_OK;
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < kProfEvents; ++i) {
     hipError_t e = hipEventCreate(&c->ev[i]);
     if (e != hipSuccess) return hip_fail(c, e, "hipEventCreate");
   }
@@ -310,10 +327,17 @@ int step_sample(gnnd_ctx* c) {
   c->stage = 1;
   return GNND_OK;
 }
-int step_join(gnnd_ctx* c) {
+// `after_join` (may be NULL) is recorded behind the cross-matching kernel itself, in front of
+// the pass that moves staged results into the destinations' segments (where there is one).
+int step_join(gnnd_ctx* c, hipEvent_t after_join = nullptr) {
   if (c->stage != 1) return fail(c, GNND_ESTATE, "stage order is sample, join, update");
-  hipError_t e = c->use_mfma ? launch_join_mfma(c->sh, c->ds, c->merge_mode, c->stream)
-                             : launch_join(c->sh, c->ds, c->prm.join_path, c->merge_mode, c->stream);
+  hipError_t e;
+  if (c->use_mfma) {
+    e = launch_join_mfma(c->sh, c->ds, c->merge_mode, c->stream, after_join);
+  } else {
+    e = launch_join(c->sh, c->ds, c->prm.join_path, c->merge_mode, c->stream);
+    if (after_join) (void)hipEventRecord(after_join, c->stream);
+  }
   if (e != hipSuccess) return hip_fail(c, e, "join kernel");
   c->stage = 2;
   return GNND_OK;
@@ -329,16 +353,17 @@ int step_update(gnnd_ctx* c) {
 
 int iterate_impl(gnnd_ctx* c, gnnd_iter_stats* out) {
   int rc;
-  if (!out && c->prof_on && (size_t)c->prof_count * 4 >= c->prof.size()) c->prof_missed += 1;
-  if (!out && c->prof_on && (size_t)c->prof_count * 4 < c->prof.size()) {
-    hipEvent_t* ev = &c->prof[(size_t)c->prof_count * 4];
+  if (!out && c->prof_on && (size_t)c->prof_count * kProfEvents >= c->prof.size())
+    c->prof_missed += 1;
+  if (!out && c->prof_on && (size_t)c->prof_count * kProfEvents < c->prof.size()) {
+    hipEvent_t* ev = &c->prof[(size_t)c->prof_count * kProfEvents];
     (void)hipEventRecord(ev[0], c->stream);
     if ((rc = step_sample(c)) != GNND_OK) return rc;
     (void)hipEventRecord(ev[1], c->stream);
-    if ((rc = step_join(c)) != GNND_OK) return rc;
-    (void)hipEventRecord(ev[2], c->stream);
-    if ((rc = step_update(c)) != GNND_OK) return rc;
+    if ((rc = step_join(c, ev[2])) != GNND_OK) return rc;
     (void)hipEventRecord(ev[3], c->stream);
+    if ((rc = step_update(c)) != GNND_OK) return rc;
+    (void)hipEventRecord(ev[4], c->stream);
     c->prof_count += 1;
     return GNND_OK;
   }
@@ -348,15 +373,16 @@ int iterate_impl(gnnd_ctx* c, gnnd_iter_stats* out) {
   }
   if ((rc = step_sample(c)) != GNND_OK) return rc;
   if (out) (void)hipEventRecord(c->ev[1], c->stream);
-  if ((rc = step_join(c)) != GNND_OK) return rc;
-  if (out) (void)hipEventRecord(c->ev[2], c->stream);
+  if ((rc = step_join(c, out ? c->ev[2] : nullptr)) != GNND_OK) return rc;
+  if (out) (void)hipEventRecord(c->ev[3], c->stream);
   if ((rc = step_update(c)) != GNND_OK) return rc;
   if (out) {
-    (void)hipEventRecord(c->ev[3], c->stream);
+    (void)hipEventRecord(c->ev[4], c->stream);
     if ((rc = read_stats(c, out)) != GNND_OK) return rc;
     (void)hipEventElapsedTime(&out->ms_sample, c->ev[0], c->ev[1]);
     (void)hipEventElapsedTime(&out->ms_join, c->ev[1], c->ev[2]);
-    (void)hipEventElapsedTime(&out->ms_update, c->ev[2], c->ev[3]);
+    (void)hipEventElapsedTime(&out->ms_handout, c->ev[2], c->ev[3]);
+    (void)hipEventElapsedTime(&out->ms_update, c->ev[3], c->ev[4]);
   }
   return GNND_OK;
 }
@@ -809,7 +835,7 @@ int gnnd_create(gnnd_ctx** out, const gnnd_params* prm, const void* vectors_dev)
 void gnnd_destroy(gnnd_ctx* c) {
   if (!c) return;
   if (c->have_events)
-    for (int i = 0; i < 4; ++i) (void)hipEventDestroy(c->ev[i]);
+    for (int i = 0; i < kProfEvents; ++i) (void)hipEventDestroy(c->ev[i]);
   for (hipEvent_t ev : c->prof) (void)hipEventDestroy(ev);
   delete c;
 }
@@ -828,7 +854,7 @@ int gnnd_set_profiling(gnnd_ctx* c, int iterations) {
   if (iterations > 0) {
     // the events are created here, outside any timed loop; a window never shrinks
     const size_t want =
-        4 * (size_t)(iterations < kProfItersDefault ? kProfItersDefault : iterations);
+        kProfEvents * (size_t)(iterations < kProfItersDefault ? kProfItersDefault : iterations);
     try {
       c->prof.reserve(want);
     } catch (...) {
@@ -848,23 +874,25 @@ int gnnd_set_profiling(gnnd_ctx* c, int iterations) {
 }
 
 int gnnd_get_stage_ms(gnnd_ctx* c, int32_t* count, int32_t* missed, float* ms_sample,
-                      float* ms_join, float* ms_update) {
+                      float* ms_join, float* ms_handout, float* ms_update) {
   if (!c) return fail(nullptr, GNND_EINVAL, "ctx is NULL");
-  if (!count || !missed || !ms_sample || !ms_join || !ms_update)
+  if (!count || !missed || !ms_sample || !ms_join || !ms_handout || !ms_update)
     return fail(c, GNND_EINVAL, "NULL output pointer");
   hipError_t e = hipStreamSynchronize(c->stream);
   if (e != hipSuccess) return hip_fail(c, e, "hipStreamSynchronize");
   *count = c->prof_count;
   *missed = c->prof_missed;
-  *ms_sample = *ms_join = *ms_update = 0.f;
+  *ms_sample = *ms_join = *ms_handout = *ms_update = 0.f;
   for (int t = 0; t < c->prof_count; ++t) {
-    const hipEvent_t* ev = &c->prof[(size_t)t * 4];
-    float a = 0, b = 0, d = 0;
+    const hipEvent_t* ev = &c->prof[(size_t)t * kProfEvents];
+    float a = 0, b = 0, h = 0, d = 0;
     (void)hipEventElapsedTime(&a, ev[0], ev[1]);
     (void)hipEventElapsedTime(&b, ev[1], ev[2]);
-    (void)hipEventElapsedTime(&d, ev[2], ev[3]);
+    (void)hipEventElapsedTime(&h, ev[2], ev[3]);
+    (void)hipEventElapsedTime(&d, ev[3], ev[4]);
     *ms_sample += a;
     *ms_join += b;
+    *ms_handout += h;
     *ms_update += d;
   }
   c->prof_count = 0;

@@ -22,6 +22,9 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int kMB = 256;  // 4 waves = 4 nodes in flight per workgroup
 constexpr int64_t kJoinGrid = 256 * 3 * 2;  // 256 CUs x 3 resident workgroups x 2
+// staged hand-out: one workgroup of 8 waves per CU (2 per SIMD: the staging code needs the registers) shares the staging area
+constexpr int kStagedWaves = 8;
+constexpr int kMBStaged = kStagedWaves * kWave;
 constexpr int32_t kFar = 1 << 24;  // "norm" of an absent row: above every real distance
 
 // Convert float32 rows holding integers 0..255 (or uint8 rows) to int8 rows
@@ -278,27 +281,97 @@ __device__ inline v16i gram(const Operand& rows, const Operand& cols) {
 // node i are evaluated the ids of node i+1 are already in flight, and as soon
 // as the last tile has consumed the operand registers the rows of node i+1 are
 // requested, before the results of node i are handed out.
-template <int KSTEPS, bool FCODE, bool MERGE>
-__global__ __launch_bounds__(kMB) __attribute__((amdgpu_waves_per_eu(3, 3))) void k_join_mfma(
+// STAGED: results are not handed to their destinations one by one (one returning
+// device-wide atomic and one scattered 8-byte store each - the rate of those atomics
+// was what the kernel ran at) but collected per workgroup in LDS, kStageSlots places
+// for each of <= kStageBuckets buckets of consecutive destination ids, and written
+// out bucket by bucket: one atomic and one contiguous piece per bucket and flush.
+// The bucket regions tile an array shaped like `bins` (a bucket's region starts where
+// the segment of its first destination starts, so it can hold whatever its
+// destinations can receive); k_result_csr then moves every result into its
+// destination's segment.  A result that finds its bucket's places taken goes to the
+// bucket's region directly.
+//
+// The waves of a workgroup run at their own pace, so a flush is a rendezvous: every
+// wave looks at the fill count after each node and joins the flush once it has reached
+// the threshold (the count only falls inside a flush, so every wave gets there); a wave
+// that has run out of nodes keeps joining flushes until all waves have run out.
+struct StageArgs {
+  uint64_t* ent;            // bucket regions: staged results
+  unsigned long long* cur;  // per bucket: results written to its region so far
+  const uint64_t* poff;     // segment offsets of the destinations (n + 1)
+  int tb, nb;               // log2(destinations per bucket), number of buckets
+  uint32_t threshold;       // fill count that triggers a flush
+};
+constexpr size_t kStageLdsBytes = (size_t)kStageBuckets * kStageSlots * 8 + kStageBuckets * 20 + 16;
+// a staged result: distance code | destination inside its bucket | object id
+__device__ inline uint64_t stage_record(uint64_t entry, uint32_t dest, int tb) {
+  return (entry & 0xffffffff00000000ull) | ((uint64_t)(dest & ((1u << tb) - 1u)) << kStageIdBits) |
+         (uint64_t)entry_id(entry);
+}
+
+template <int KSTEPS, bool FCODE, bool MERGE, bool STAGED>
+__global__ __launch_bounds__(STAGED ? kMBStaged : kMB)
+__attribute__((amdgpu_waves_per_eu(STAGED ? 2 : 3, STAGED ? 2 : 3))) void k_join_mfma(
     const int8_t* __restrict__ shadow, const NodeMeta* __restrict__ meta, int dpad, int64_t n,
     int p, int64_t split, const int32_t* __restrict__ snew, const int32_t* __restrict__ sold,
-    uint64_t* pslot, uint64_t slots, uint64_t* __restrict__ bins, uint64_t* counters) {
+    uint64_t* pslot, uint64_t slots, uint64_t* __restrict__ bins, uint64_t* counters,
+    StageArgs sa) {
+  constexpr int WAVES = STAGED ? kStagedWaves : kMB / kWave;
   // per wave, for the 128 rows (NEW 0..63, OLD 64..127): -((norm << 6) | position), the ids
   // (absent = INT_MAX so that both halves stay ascending), and a scratch row
-  __shared__ __attribute__((aligned(16))) int32_t s_norm[4][128];
-  __shared__ int32_t s_id[4][128];
-  __shared__ int32_t s_eq[4][64];
+  __shared__ __attribute__((aligned(16))) int32_t s_norm[WAVES][128];
+  __shared__ int32_t s_id[WAVES][128];
+  __shared__ int32_t s_eq[WAVES][64];
+  extern __shared__ __attribute__((aligned(16))) unsigned char stage_raw[];
+  uint64_t* const st_ent = reinterpret_cast<uint64_t*>(stage_raw);
+  uint64_t* const st_region = st_ent + kStageBuckets * kStageSlots;
+  uint64_t* const st_gbase = st_region + kStageBuckets;
+  uint32_t* const st_cnt = reinterpret_cast<uint32_t*>(st_gbase + kStageBuckets);
+  uint32_t* const st_fill = st_cnt + kStageBuckets;  // [0] results staged, [1] waves out of nodes
   const int wave = threadIdx.x >> 6, lane = lane_id(), half = lane >> 5, col = lane & 31;
-  const int64_t W = (int64_t)gridDim.x * 4;
-  int64_t s = (int64_t)blockIdx.x * 4 + wave;
-  if (s >= n) return;
+  const int64_t W = (int64_t)gridDim.x * WAVES;
+  int64_t s = (int64_t)blockIdx.x * WAVES + wave;
+  if (!STAGED && s >= n) return;
+  if (STAGED) {
+    for (int b = threadIdx.x; b < sa.nb; b += kMBStaged) {
+      st_cnt[b] = 0;
+      const int64_t first = (int64_t)b << sa.tb;
+      st_region[b] = sa.poff[first < n ? first : n];
+    }
+    if (threadIdx.x == 0) st_fill[0] = st_fill[1] = 0;
+    __syncthreads();
+  }
+  // One flush (all waves of the workgroup together).  Returns true when every wave has
+  // run out of nodes, i.e. when this was the last one.
+  auto flush = [&]() -> bool {
+    __syncthreads();  // nobody is adding results any more
+    const uint32_t out_of_nodes = *reinterpret_cast<volatile uint32_t*>(st_fill + 1);
+    for (int b = threadIdx.x; b < sa.nb; b += kMBStaged) {
+      const uint32_t c = st_cnt[b] < (uint32_t)kStageSlots ? st_cnt[b] : (uint32_t)kStageSlots;
+      st_gbase[b] = c ? atomicAdd(&sa.cur[b], (unsigned long long)c) : 0ull;
+    }
+    __syncthreads();
+    // a wave per bucket: its results leave as one contiguous piece
+    for (int b = wave; b < sa.nb; b += WAVES) {
+      const uint32_t c = st_cnt[b] < (uint32_t)kStageSlots ? st_cnt[b] : (uint32_t)kStageSlots;
+      const uint64_t at = st_region[b] + st_gbase[b] + (uint32_t)lane;
+      if ((uint32_t)lane < c && at < slots) sa.ent[at] = st_ent[b * kStageSlots + lane];
+    }
+    __syncthreads();
+    for (int b = threadIdx.x; b < sa.nb; b += kMBStaged) st_cnt[b] = 0;
+    if (threadIdx.x == 0) st_fill[0] = 0;
+    __syncthreads();
+    return out_of_nodes == (uint32_t)WAVES;
+  };
+  const bool have_nodes = s < n;
   const int L = 2 * p;
   const bool in_list = lane < L;
   const uint2 m_none = make_uint2(0, (uint32_t)kFar);
 
   // unused list slots hold -1, so the ids alone say how long a list is
-  int32_t id_new = in_list ? snew[s * L + lane] : -1;
-  int32_t id_old = in_list ? sold[s * L + lane] : -1;
+  int32_t id_new = (have_nodes && in_list) ? snew[s * L + lane] : -1;
+  int32_t id_old = (have_nodes && in_list) ? sold[s * L + lane] : -1;
   int32_t nx_new = -1, nx_old = -1;
   if (s + W < n && in_list) {
     nx_new = snew[(s + W) * L + lane];
@@ -319,7 +392,7 @@ __global__ __launch_bounds__(kMB) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
   };
   request_rows(id_new, id_old);
 
-  for (;;) {
+  while (have_nodes) {
     const int nn = __popcll(__ballot(id_new >= 0)), no = __popcll(__ballot(id_old >= 0));
     const bool do_nn = !MERGE && nn > 1;
     const bool active = nn > 0 && (do_nn || no > 0);
@@ -497,19 +570,48 @@ __global__ __launch_bounds__(kMB) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     }
     // slot requests for all three results first ...
     // (the two results of a NEW sample go to the same list: one request for both)
-    // one returning add on the destination's slot word yields the segment start
-    // and the place in it
-    uint64_t word_n = 0, word_o = 0;
     const uint32_t want_n = (pass[0] ? 1u : 0u) + (pass[1] ? 1u : 0u);
-    if (want_n)
-      word_n = atomicAdd(reinterpret_cast<unsigned long long*>(&pslot[id_new]),
-                         (unsigned long long)want_n);
-    if (pass[2])
-      word_o = atomicAdd(reinterpret_cast<unsigned long long*>(&pslot[id_old]), 1ull);
     const uint32_t passed_total =
         (uint32_t)__popcll(__ballot(pass[0])) + (uint32_t)__popcll(__ballot(pass[1])) +
         (uint32_t)__popcll(__ballot(pass[2]));
-    // ... then, with the operand registers free, the next node's rows ...
+    uint64_t word_n = 0, word_o = 0;  // direct hand-out: slot words of the destinations
+    uint32_t place_n = 0, place_o = 0;  // staged hand-out: places in the buckets' LDS areas
+    const int bucket_n = STAGED ? (int)((uint32_t)id_new >> sa.tb) : 0;
+    const int bucket_o = STAGED ? (int)((uint32_t)id_old >> sa.tb) : 0;
+    if (STAGED) {
+      if (want_n) place_n = atomicAdd(&st_cnt[bucket_n], want_n);
+      if (pass[2]) place_o = atomicAdd(&st_cnt[bucket_o], 1u);
+      if (passed_total && lane == 0) atomicAdd(&st_fill[0], passed_total);
+    } else {
+      // one returning add on the destination's slot word yields the segment start
+      // and the place in it
+      if (want_n)
+        word_n = atomicAdd(reinterpret_cast<unsigned long long*>(&pslot[id_new]),
+                           (unsigned long long)want_n);
+      if (pass[2])
+        word_o = atomicAdd(reinterpret_cast<unsigned long long*>(&pslot[id_old]), 1ull);
+    }
+    // staged: places in LDS come back at once, so the results are put away before the
+    // next node's rows take up the operand registers
+    // (segments and bucket regions cannot overflow, see the sampling stage; the tests
+    // against the array size only keep a violated bound from writing outside the array)
+    if (STAGED) {
+      auto put = [&](int bucket, uint32_t place, uint64_t e, int32_t dest) {
+        const uint64_t rec = stage_record(e, (uint32_t)dest, sa.tb);
+        if (place < (uint32_t)kStageSlots) {
+          st_ent[bucket * kStageSlots + (int)place] = rec;
+        } else {  // the bucket's places are taken: straight to its region
+          const uint64_t at = st_region[bucket] + atomicAdd(&sa.cur[bucket], 1ull);
+          if (at < slots) sa.ent[at] = rec;
+          else ++over_total;
+        }
+      };
+      if (pass[0]) put(bucket_n, place_n, entry[0], id_new);
+      if (pass[1]) put(bucket_n, place_n + (pass[0] ? 1u : 0u), entry[1], id_new);
+      if (pass[2]) put(bucket_o, place_o, entry[2], id_old);
+    }
+    // direct: with the operand registers free, the next node's rows are requested while
+    // the slot words are still on their way ...
     const int64_t s_next = s + W;
     const bool more = s_next < n;
     int32_t nn_new = -1, nn_old = -1;
@@ -521,21 +623,21 @@ __global__ __launch_bounds__(kMB) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
       }
     }
     // ... and only now the slots are used
-    // (segments cannot overflow, see the sampling stage; the test against the
-    // array size only keeps a violated bound from writing outside the array)
-    const uint64_t at_n = (word_n >> kSlotCountBits) + (word_n & kSlotCountMask);
-    const uint64_t at_o = (word_o >> kSlotCountBits) + (word_o & kSlotCountMask);
-    if (pass[0] && pass[1]) {  // neighbouring slots: one 16-byte store
-      if (at_n + 1 < slots)
-        __builtin_nontemporal_store(EntryPair{entry[0], entry[1]}, reinterpret_cast<EntryPair*>(bins + at_n));
-      else over_total += 2;
-    } else if (want_n) {
-      if (at_n < slots) __builtin_nontemporal_store(pass[0] ? entry[0] : entry[1], &bins[at_n]);
-      else ++over_total;
-    }
-    if (pass[2]) {
-      if (at_o < slots) __builtin_nontemporal_store(entry[2], &bins[at_o]);
-      else ++over_total;
+    if (!STAGED) {
+      const uint64_t at_n = (word_n >> kSlotCountBits) + (word_n & kSlotCountMask);
+      const uint64_t at_o = (word_o >> kSlotCountBits) + (word_o & kSlotCountMask);
+      if (pass[0] && pass[1]) {  // neighbouring slots: one 16-byte store
+        if (at_n + 1 < slots)
+          __builtin_nontemporal_store(EntryPair{entry[0], entry[1]}, reinterpret_cast<EntryPair*>(bins + at_n));
+        else over_total += 2;
+      } else if (want_n) {
+        if (at_n < slots) __builtin_nontemporal_store(pass[0] ? entry[0] : entry[1], &bins[at_n]);
+        else ++over_total;
+      }
+      if (pass[2]) {
+        if (at_o < slots) __builtin_nontemporal_store(entry[2], &bins[at_o]);
+        else ++over_total;
+      }
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) over_total += __shfl_xor(over_total, off, kWave);
@@ -558,42 +660,169 @@ __global__ __launch_bounds__(kMB) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
                                 (unsigned long long)over_total);
       if (ev) atomicAdd(reinterpret_cast<unsigned long long*>(cs + C_EVALS), (unsigned long long)ev);
     }
+    if (STAGED) {
+      // every wave looks at the fill count after every node (a wave-uniform LDS read)
+      const uint32_t fill = *reinterpret_cast<volatile uint32_t*>(st_fill);
+      if ((uint32_t)__builtin_amdgcn_readfirstlane((int)fill) >= sa.threshold) (void)flush();
+    }
     if (!more) break;
     s = s_next;
     id_new = nx_new; id_old = nx_old;
     nx_new = nn_new; nx_old = nn_old;
   }
+  if (STAGED) {
+    if (lane == 0) atomicAdd(&st_fill[1], 1u);
+    while (!flush()) {
+    }
+  }
 }
 
-template <int KSTEPS>
-static void launch_k(bool fcode, bool merge, unsigned grid, hipStream_t st, const int8_t* shadow,
-                     const NodeMeta* meta, int dpad, const Shape& sh, const DevState& ds) {
-#define GNND_ARGS shadow, meta, dpad, sh.n, sh.p, sh.split, ds.snew, ds.sold, \
-                  ds.pslot, (uint64_t)sh.slots(), ds.bins, ds.counters
-  if (fcode) {
-    if (merge) k_join_mfma<KSTEPS, true, true><<<grid, kMB, 0, st>>>(GNND_ARGS);
-    else k_join_mfma<KSTEPS, true, false><<<grid, kMB, 0, st>>>(GNND_ARGS);
-  } else {
-    if (merge) k_join_mfma<KSTEPS, false, true><<<grid, kMB, 0, st>>>(GNND_ARGS);
-    else k_join_mfma<KSTEPS, false, false><<<grid, kMB, 0, st>>>(GNND_ARGS);
+// Second half of the staged hand-out: one workgroup per bucket moves the bucket's
+// results from its region into the segments of their destinations (LDS counter per
+// destination = place in the segment) and writes the destinations' slot words
+// (segment start, results received) that the list update reads.
+constexpr int kRcBlock = 1024;
+// The destinations' segment starts (relative to the region) are kept in LDS next to the
+// counters: a bucket has at most 2^12 destinations.
+__global__ __launch_bounds__(kRcBlock) void k_result_csr(int64_t n, int tb,
+                                                         const uint64_t* __restrict__ poff,
+                                                         const unsigned long long* __restrict__ cur,
+                                                         const uint64_t* __restrict__ ent,
+                                                         uint64_t* __restrict__ bins,
+                                                         uint64_t* __restrict__ pslot,
+                                                         uint64_t* counters) {
+  extern __shared__ uint32_t received[];  // 2^tb counters, then 2^tb + 1 segment starts
+  uint32_t* const seg_start = received + ((size_t)1 << tb);
+  const int64_t first = (int64_t)blockIdx.x << tb;
+  const int T = (int)(n - first < ((int64_t)1 << tb) ? n - first : ((int64_t)1 << tb));
+  const uint64_t region = poff[first], room = poff[first + T] - region;
+  for (int t = threadIdx.x; t < T; t += kRcBlock) {
+    received[t] = 0;
+    seg_start[t] = (uint32_t)(poff[first + t] - region);
   }
+  if (threadIdx.x == 0) seg_start[T] = (uint32_t)room;
+  __syncthreads();
+  uint64_t count = cur[blockIdx.x];
+  if (count > room) {  // cannot happen: a region holds what its destinations can receive
+    if (threadIdx.x == 0)
+      atomicAdd(reinterpret_cast<unsigned long long*>(counters + C_OVERFLOW),
+                (unsigned long long)(count - room));
+    count = room;
+  }
+  constexpr int kAtOnce = 8;  // results in flight per thread
+  for (uint64_t i0 = threadIdx.x; i0 < count; i0 += (uint64_t)kAtOnce * kRcBlock) {
+    uint64_t e[kAtOnce];
+#pragma unroll
+    for (int r = 0; r < kAtOnce; ++r) {
+      const uint64_t i = i0 + (uint64_t)r * kRcBlock;
+      e[r] = i < count ? ent[region + i] : ~0ull;
+    }
+#pragma unroll
+    for (int r = 0; r < kAtOnce; ++r) {
+      const int t = (int)(((uint32_t)e[r] >> kStageIdBits) & ((1u << tb) - 1u));
+      if (e[r] == ~0ull || t >= T) continue;
+      const uint32_t place = atomicAdd(&received[t], 1u);
+      const uint64_t seg = region + seg_start[t], cap = seg_start[t + 1] - seg_start[t];
+      // back to a list entry: distance code | object id | "admitted now" + NEW
+      if (place < cap)
+        bins[seg + place] = make_entry((uint32_t)(e[r] >> 32),
+                                       (uint32_t)e[r] & ((1u << kStageIdBits) - 1u), 3u);
+    }
+  }
+  __syncthreads();
+  for (int t = threadIdx.x; t < T; t += kRcBlock) {
+    const uint64_t got = received[t] < kSlotCountMask ? received[t] : kSlotCountMask;
+    pslot[first + t] = ((region + seg_start[t]) << kSlotCountBits) | got;
+  }
+}
+
+template <int KSTEPS, bool STAGED>
+static hipError_t launch_k(bool fcode, bool merge, unsigned grid, hipStream_t st,
+                           const int8_t* shadow, const NodeMeta* meta, int dpad, const Shape& sh,
+                           const DevState& ds, const StageArgs& sa) {
+  constexpr int block = STAGED ? kMBStaged : kMB;
+  const size_t lds = STAGED ? kStageLdsBytes : 0;
+#define GNND_ARGS shadow, meta, dpad, sh.n, sh.p, sh.split, ds.snew, ds.sold, \
+                  ds.pslot, (uint64_t)sh.slots(), ds.bins, ds.counters, sa
+#define GNND_LAUNCH(F, M)                                                                      \
+  do {                                                                                         \
+    auto* kern = k_join_mfma<KSTEPS, F, M, STAGED>;                                            \
+    if (STAGED) {                                                                              \
+      static bool attr_set = false; /* per instantiation: a staging area beyond the default */ \
+      if (!attr_set) {                                                                         \
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                \
+                                           hipFuncAttributeMaxDynamicSharedMemorySize,         \
+                                           (int)kStageLdsBytes);                               \
+        if (e != hipSuccess) return e;                                                         \
+        attr_set = true;                                                                       \
+      }                                                                                        \
+    }                                                                                          \
+    kern<<<grid, block, lds, st>>>(GNND_ARGS);                                                 \
+  } while (0)
+  if (fcode) {
+    if (merge) GNND_LAUNCH(true, true);
+    else GNND_LAUNCH(true, false);
+  } else {
+    if (merge) GNND_LAUNCH(false, true);
+    else GNND_LAUNCH(false, false);
+  }
+#undef GNND_LAUNCH
 #undef GNND_ARGS
+  return hipGetLastError();
+}
+
+static int compute_units() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+      cus = v;
+    else
+      cus = 256;
+  }
+  return cus;
 }
 
 hipError_t launch_join_mfma(const Shape& sh, const DevState& ds, bool merge_mode,
-                            hipStream_t st) {
+                            hipStream_t st, hipEvent_t after_join) {
   const int dpad = (sh.d + 31) & ~31;
   const int ksteps = dpad / 32;
-  // persistent wavefronts: about two resident sets of workgroups, each wave strides over nodes
-  const int64_t want = (sh.n + 3) / 4;
-  const unsigned grid = (unsigned)(want < kJoinGrid ? want : kJoinGrid);
   const bool fcode = sh.metric != kL2U8;
-  switch (ksteps) {
-    case 1: launch_k<1>(fcode, merge_mode, grid, st, ds.shadow, ds.meta, dpad, sh, ds); break;
-    case 2: launch_k<2>(fcode, merge_mode, grid, st, ds.shadow, ds.meta, dpad, sh, ds); break;
-    case 3: launch_k<3>(fcode, merge_mode, grid, st, ds.shadow, ds.meta, dpad, sh, ds); break;
-    default: launch_k<4>(fcode, merge_mode, grid, st, ds.shadow, ds.meta, dpad, sh, ds);
+  const bool staged = ds.stg_ent != nullptr;
+  StageArgs sa{ds.stg_ent, ds.stg_cur, ds.poff, 0, 0, 0};
+  unsigned grid;
+  if (staged) {
+    sa.tb = stage_bucket_bits(sh.n);
+    sa.nb = (int)((sh.n + ((int64_t)1 << sa.tb) - 1) >> sa.tb);
+    // flush at half-full on average: few results find their bucket's places taken
+    sa.threshold = (uint32_t)(sa.nb * (kStageSlots / 2));
+    hipError_t e = launch_zero_u32(reinterpret_cast<uint32_t*>(ds.stg_cur), 2 * kStageBuckets, st);
+    if (e != hipSuccess) return e;
+    // persistent workgroups, one per CU (the staging area takes most of a CU's LDS)
+    const int64_t want = (sh.n + kStagedWaves - 1) / kStagedWaves;
+    grid = (unsigned)(want < compute_units() ? want : compute_units());
+  } else {
+    // persistent wavefronts: about two resident sets of workgroups, each wave strides over nodes
+    const int64_t want = (sh.n + 3) / 4;
+    grid = (unsigned)(want < kJoinGrid ? want : kJoinGrid);
   }
+  hipError_t e;
+#define GNND_K(K)                                                                             \
+  e = staged ? launch_k<K, true>(fcode, merge_mode, grid, st, ds.shadow, ds.meta, dpad, sh, ds, sa) \
+             : launch_k<K, false>(fcode, merge_mode, grid, st, ds.shadow, ds.meta, dpad, sh, ds, sa)
+  switch (ksteps) {
+    case 1: GNND_K(1); break;
+    case 2: GNND_K(2); break;
+    case 3: GNND_K(3); break;
+    default: GNND_K(4);
+  }
+#undef GNND_K
+  if (after_join) (void)hipEventRecord(after_join, st);
+  if (e != hipSuccess || !staged) return e;
+  // (a region is shorter than 2^32 slots: n <= 2^20, 6p <= 192 slots per node)
+  k_result_csr<<<(unsigned)sa.nb, kRcBlock, ((size_t)8 << sa.tb) + 4, st>>>(
+      sh.n, sa.tb, ds.poff, ds.stg_cur, ds.stg_ent, ds.bins, ds.pslot, ds.counters);
   return hipGetLastError();
 }
 

@@ -53,8 +53,26 @@ struct DevState {
   int8_t* shadow;      // matrix-core path: n rows of dpad int8 (value - 128), zero padded
   uint32_t* bk_cnt;    // 2 x 4096 bucket sizes of the bucketed reverse-candidate sort
   uint64_t* bk_off;    // 2 x 4097 bucket offsets
-
+  // staged hand-out of the matrix-core join (NULL when results are handed on one by one):
+  // results leave the join grouped by bucket of destinations, then a second pass moves
+  // them into the destinations' segments of `bins`
+  uint64_t* stg_ent;   // slots: staged results (see stage_record), bucket regions laid out like bins
+  unsigned long long* stg_cur;  // kStageBuckets: results that have reached each bucket region
 };
+
+// Staged hand-out: destinations are cut into at most kStageBuckets buckets of 2^tb
+// consecutive ids; a workgroup of the join keeps kStageSlots results per bucket in LDS.
+// A staged result is one 64-bit word: distance code (32) | destination inside its bucket
+// (12) | object id (20), which is what limits the staged form to 2^20 nodes.
+constexpr int kStageBuckets = 256;
+constexpr int kStageSlots = 64;
+constexpr int kStageIdBits = 20;
+constexpr int64_t kStageMaxNodes = (int64_t)1 << kStageIdBits;
+inline int stage_bucket_bits(int64_t n) {
+  int tb = 0;
+  while (((n + ((int64_t)1 << tb) - 1) >> tb) > kStageBuckets) ++tb;
+  return tb;
+}
 
 struct Shape {
   int64_t n;
@@ -90,7 +108,11 @@ hipError_t launch_sample(const Shape& sh, const DevState& ds, uint64_t seed, uin
                          hipStream_t st);
 hipError_t launch_join(const Shape& sh, const DevState& ds, int path, bool merge_mode,
                        hipStream_t st);
-hipError_t launch_join_mfma(const Shape& sh, const DevState& ds, bool merge_mode, hipStream_t st);
+// results are staged per bucket when ds.stg_ent is set, handed on one by one otherwise;
+// `after_join` (may be NULL) is recorded behind the cross-matching kernel, in front of the
+// pass that moves staged results into the destinations' segments
+hipError_t launch_join_mfma(const Shape& sh, const DevState& ds, bool merge_mode, hipStream_t st,
+                            hipEvent_t after_join = nullptr);
 hipError_t launch_pack_i8(const Shape& sh, const DevState& ds, int* bad_flag_dev, hipStream_t st);
 hipError_t launch_init_random_i8(const Shape& sh, const DevState& ds, uint64_t seed,
                                  hipStream_t st);

@@ -19,7 +19,13 @@ def _exact(x, metric, k):
     return og.Graph(ids, dist, np.zeros_like(ids, dtype=np.uint8))
 
 
-@pytest.mark.parametrize("path", ["valu", "auto"])
+def x_is_bytes(gen):
+    """Whether the generator's vectors are byte valued (0..255 integers, d <= 128)."""
+    x = gen(64)
+    return x.shape[1] <= 128 and bool(((x == np.rint(x)) & (x >= 0) & (x <= 255)).all())
+
+
+@pytest.mark.parametrize("path", ["valu", "auto", "direct"])
 @pytest.mark.parametrize("metric,gen,k,p,n1,iters", [
     (og.L2SQ_F32, lambda n: W.uniform_f32(n, 12, seed=201), 10, 10, 900, 4),
     (og.L2SQ_F32, lambda n: W.sift_like_f32(n, 128, seed=202, n_comp=8), 32, 32, 1100, 3),
@@ -33,6 +39,8 @@ def _exact(x, metric, k):
 ])
 def test_merge_matches_oracle(metric, gen, k, p, n1, iters, path):
     import paper_2103_15386_amd as amd
+    if path == "direct" and not (metric in (og.L2SQ_U8, og.L2SQ_F32) and x_is_bytes(gen)):
+        pytest.skip("the matrix-core join takes byte-valued data only")
     n = 2000
     x = gen(n)
     g1 = _exact(x[:n1], metric, k)
@@ -42,7 +50,8 @@ def test_merge_matches_oracle(metric, gen, k, p, n1, iters, path):
     dt = np.int32 if metric == og.L2SQ_U8 else np.float32
     out = amd.gnnd_merge(_dev(x[:n1]), _dev(x[n1:]), _dev(g1.ids), _dev(g1.dist.astype(dt)),
                          _dev(g2.ids), _dev(g2.dist.astype(dt)), k, p, metric, SEED, iters,
-                         join_path=amd.JOIN_VALU if path == "valu" else amd.JOIN_AUTO,
+                         join_path={"valu": amd.JOIN_VALU, "auto": amd.JOIN_AUTO,
+                                    "direct": amd.JOIN_MFMA_DIRECT}[path],
                          want_stats=True)
     ids, dist, stats = out
     assert (ids.cpu().numpy() == want.ids).all()

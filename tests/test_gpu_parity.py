@@ -104,6 +104,7 @@ ALL_PAIRS_CASES = ["uniform_c1", "u8_cut", "deep_cut_angular", "tiny_n", "k100_a
 
 @pytest.mark.parametrize("name,path", [(n, "valu") for n in CASES] +
                          [(n, "mfma") for n in MFMA_CASES] +
+                         [(n, "mfma_direct") for n in MFMA_CASES] +
                          [(n, "all") for n in ALL_PAIRS_CASES])
 def test_every_stage_of_every_iteration_matches_oracle(name, path):
     amd = _amd()
@@ -111,7 +112,9 @@ def test_every_stage_of_every_iteration_matches_oracle(name, path):
     x = gen()
     n = len(x)
     every = path == "all"
-    ctx = amd.Gnnd(_dev(x), k, p, metric, SEED, amd.JOIN_MFMA if path == "mfma" else amd.JOIN_VALU,
+    # "mfma": results leave the join staged per bucket of destinations; "mfma_direct": one by one
+    join = {"mfma": amd.JOIN_MFMA, "mfma_direct": amd.JOIN_MFMA_DIRECT}.get(path, amd.JOIN_VALU)
+    ctx = amd.Gnnd(_dev(x), k, p, metric, SEED, join,
                    amd.UPDATE_ALL_PAIRS if every else amd.UPDATE_SELECTIVE)
     ctx.init_random()
     g = og.init_random(x, k, metric, SEED)
@@ -282,10 +285,10 @@ def test_stage_times_are_recorded_per_iteration():
     ctx.build(5, want_stats=False)
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
-    count, missed, ms_sample, ms_join, ms_update = ctx.stage_ms()
+    count, missed, ms_sample, ms_join, ms_handout, ms_update = ctx.stage_ms()
     assert count == 5 and missed == 0
-    assert ms_sample > 0 and ms_join > 0 and ms_update > 0
-    assert ms_sample + ms_join + ms_update <= wall_ms
+    assert ms_sample > 0 and ms_join > 0 and ms_handout > 0 and ms_update > 0
+    assert ms_sample + ms_join + ms_handout + ms_update <= wall_ms
     count, missed, *_ = ctx.stage_ms()  # reading clears the record
     assert count == 0 and missed == 0
     # a window holds what was asked for (never fewer than 64 iterations); what does not
@@ -298,8 +301,8 @@ def test_stage_times_are_recorded_per_iteration():
     ctx.set_profiling(140)
     for _ in range(20):
         ctx.build(7, want_stats=False)
-    count, missed, ms_sample, ms_join, ms_update = ctx.stage_ms()
-    assert (count, missed) == (140, 0) and min(ms_sample, ms_join, ms_update) > 0
+    count, missed, ms_sample, ms_join, ms_handout, ms_update = ctx.stage_ms()
+    assert (count, missed) == (140, 0) and min(ms_sample, ms_join, ms_handout, ms_update) > 0
     ctx.close()
 
 
