@@ -31,7 +31,12 @@ PEAK_INT8_TOPS = 5000.0
 # same counters misread a 1 GiB device copy.  Keyed by (workload, n, d, k, p, join
 # kernel): any other run reports "traffic": null.  A build of T iterations takes the
 # mean of the first T entries; T beyond the table also gives null.
-JOIN_TRAFFIC = {}
+JOIN_TRAFFIC = {
+    ("sift1m", 1_000_000, 128, 32, 32, "k_join_mfma", "selective"): {
+        "fetch_raw_mib": [6970.4, 4594.0, 5200.9, 5037.6, 5111.4, 4766.8, 4587.8],
+        "write_raw_mib": [607.2, 481.0, 745.0, 593.3, 446.6, 249.4, 140.5],
+        "fetch_scale": 2.0, "write_scale": 1.0},
+}
 
 
 def join_traffic(key, T):
