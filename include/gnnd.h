@@ -87,7 +87,8 @@ typedef struct gnnd_params {
   int64_t n;      /* number of vectors, k < n <= 2^27                               */
   int32_t d;      /* dimension, >= 1 (float metrics: multiple of 4 reads fastest)   */
   int32_t k;      /* list length, 2 <= k <= 128                                     */
-  int32_t p;      /* sample number of Sec. 4.1, 1 <= p <= min(k, 32)                */
+  int32_t p;      /* sample number of Sec. 4.1, 1 <= p <= min(k, 64); the matrix-core
+                     join and GNND_UPDATE_ALL_PAIRS take p <= 32                    */
   int32_t metric; /* one of the distance constants above                            */
   uint64_t seed;  /* seed of all random draws                                       */
   void* stream;   /* hipStream_t; NULL = the default stream                         */

@@ -204,6 +204,29 @@ __device__ inline T wave_merge_smallest(T a_sorted, T b_sorted, int lane) {
   return wave_bitonic_merge(vmin(a_sorted, br), lane);
 }
 
+// 128 values, two per lane (value i in lane i % 64 of register i / 64), ascending over
+// (lo, hi): two 64-lane networks and a 128-wide bitonic merge.
+template <typename T>
+__device__ inline void sort128(T& lo, T& hi, int lane) {
+  lo = wave_sort(lo, lane);
+  hi = wave_sort(hi, lane);
+  const T t = reverse_lanes(hi, lane);  // lo ++ t is bitonic
+  const T a = vmin(lo, t), b = vmax(lo, t);
+  lo = wave_bitonic_merge(a, lane);
+  hi = wave_bitonic_merge(b, lane);
+}
+
+// (lo, hi) ascending, c ascending (64 values): afterwards (lo, hi) holds the 128
+// smallest of the 192, ascending (c is split against lo; the larger half goes on to hi).
+template <typename T>
+__device__ inline void merge128(T& lo, T& hi, T c, int lane) {
+  const T t = reverse_lanes(c, lane);
+  const T a = vmin(lo, t), b = vmax(lo, t);
+  lo = wave_bitonic_merge(a, lane);
+  const T spill = wave_bitonic_merge(b, lane);  // the 64 largest of lo and c, ascending
+  hi = wave_merge_smallest(hi, spill, lane);
+}
+
 // Stable compaction of the lanes with keep == true to the front; the other
 // lanes end up behind them holding `fill`.
 __device__ inline uint64_t wave_compact(uint64_t v, bool keep, uint64_t fill, int lane) {

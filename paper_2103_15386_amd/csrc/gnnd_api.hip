@@ -50,7 +50,7 @@ const char* check_params(const gnnd_params* q) {
   if (!q) return "params is NULL";
   if (q->metric < GNND_L2SQ_F32 || q->metric > GNND_COSINE_F32) return "unknown metric";
   if (q->k < 2 || q->k > 128) return "k must be in [2, 128]";
-  if (q->p < 1 || q->p > 32 || q->p > q->k) return "p must be in [1, min(k, 32)]";
+  if (q->p < 1 || q->p > 64 || q->p > q->k) return "p must be in [1, min(k, 64)]";
   if (q->d < 1) return "d must be >= 1";
   if (q->metric == GNND_L2SQ_U8 && q->d > 32768) return "d must be <= 32768 for uint8 vectors";
   if (q->n <= q->k) return "n must exceed k";
@@ -63,6 +63,8 @@ const char* check_params(const gnnd_params* q) {
   if (q->update_mode == GNND_UPDATE_ALL_PAIRS &&
       (q->join_path == GNND_JOIN_MFMA || q->join_path == GNND_JOIN_MFMA_DIRECT))
     return "GNND_UPDATE_ALL_PAIRS runs with GNND_JOIN_VALU (or GNND_JOIN_AUTO) only";
+  if (q->update_mode == GNND_UPDATE_ALL_PAIRS && q->p > 32)
+    return "GNND_UPDATE_ALL_PAIRS needs p <= 32";
   return nullptr;
 }
 
@@ -70,7 +72,7 @@ const char* check_params(const gnnd_params* q) {
 // vectors, or float32 vectors that turn out to hold only integers 0..255.
 bool mfma_possible(const gnnd_params* q) {
   return q->join_path != GNND_JOIN_VALU && q->update_mode == GNND_UPDATE_SELECTIVE && q->d <= 128 &&
-         (q->metric == GNND_L2SQ_U8 || q->metric == GNND_L2SQ_F32);
+         q->p <= 32 && (q->metric == GNND_L2SQ_U8 || q->metric == GNND_L2SQ_F32);
 }
 
 // The matrix-core join stages its results per bucket of destinations (instead of handing
@@ -242,9 +244,9 @@ int init_ctx(gnnd_ctx* c, const gnnd_params* prm, const Layout& L, const void* v
   }
   if ((prm->join_path == GNND_JOIN_MFMA || prm->join_path == GNND_JOIN_MFMA_DIRECT) && !c->use_mfma)
     return fail(nullptr, GNND_EINVAL,
-                may_sync ? "GNND_JOIN_MFMA needs d <= 128 and uint8 vectors or float32 vectors "
+                may_sync ? "GNND_JOIN_MFMA needs d <= 128, p <= 32 and uint8 vectors or float32 vectors "
                            "holding integers 0..255 with the squared-L2 metric"
-                         : "GNND_JOIN_MFMA needs d <= 128 and uint8 vectors here (float32 "
+                         : "GNND_JOIN_MFMA needs d <= 128, p <= 32 and uint8 vectors here (float32 "
                            "vectors have to be checked, which synchronises: use gnnd_create)");
   return GNND_OK;
 }

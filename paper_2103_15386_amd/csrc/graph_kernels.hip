@@ -579,6 +579,11 @@ hipError_t launch_sample(const Shape& sh, const DevState& ds, uint64_t seed, uin
   // forward sampling, and the reverse candidates grouped by target (two-level counting sort)
   hipError_t e = launch_sample_buckets(sh, ds, st);
   if (e != hipSuccess) return e;
+  if (2 * sh.p > kWave) {  // two list entries per lane
+    e = launch_rev_select_long(sh, ds, seed, iter, st);
+    if (e != hipSuccess) return e;
+    return launch_scan(ds.capn, ds.capo, ds.poff, ds.pslot, ds.counters, ds.scan_tmp, sh.n, st);
+  }
   k_rev_select<<<grid, kBlock, 0, st>>>(
       sh.n, sh.p, hash_base(seed, kTagRevNew), hash_base(seed, kTagRevOld), iter, ds.snew,
       ds.sold, ds.cnew, ds.cold, ds.roff_new, ds.roff_old, ds.csr_new, ds.csr_old, ds.capn,

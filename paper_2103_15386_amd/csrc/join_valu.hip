@@ -373,6 +373,7 @@ static void launch_join_as(const Shape& sh, const DevState& ds, bool merge_mode,
 hipError_t launch_join(const Shape& sh, const DevState& ds, int path, bool merge_mode,
                        hipStream_t st) {
   (void)path;
+  if (2 * sh.p > kWave) return launch_join_long(sh, ds, merge_mode, st);  // sample lists beyond 64
   if (sh.all_pairs) launch_join_as<true>(sh, ds, merge_mode, st);
   else launch_join_as<false>(sh, ds, merge_mode, st);
   return hipGetLastError();

@@ -117,6 +117,10 @@ hipError_t launch_pack_i8(const Shape& sh, const DevState& ds, int* bad_flag_dev
 hipError_t launch_init_random_i8(const Shape& sh, const DevState& ds, uint64_t seed,
                                  hipStream_t st);
 hipError_t launch_sample_buckets(const Shape& sh, const DevState& ds, hipStream_t st);
+// sample lists of 65..128 objects (p > 32): reverse selection and the join for long lists
+hipError_t launch_rev_select_long(const Shape& sh, const DevState& ds, uint64_t seed,
+                                  uint32_t iter, hipStream_t st);
+hipError_t launch_join_long(const Shape& sh, const DevState& ds, bool merge_mode, hipStream_t st);
 hipError_t launch_update(const Shape& sh, const DevState& ds, hipStream_t st);
 // lists of 65..128 entries (two per lane); the launchers above forward to these
 hipError_t launch_init_random_wide(const Shape& sh, const DevState& ds, uint64_t seed,

@@ -231,11 +231,12 @@ __global__ __launch_bounds__(kCsrBlock) void k_bucket_scan(int nb, const uint32_
 // copies them out in that order, so that the part of a batch that goes to one
 // bucket leaves as one contiguous piece instead of one 8-byte store per edge to
 // as many places (0.50 -> 0.24 ms per million nodes).
+// PW threads serve a row (its up to PW forward samples of one kind): 32 for p <= 32, 64 beyond.
 constexpr int kStBlock = 1024;
-constexpr int kStRows = 256;                 // rows per batch
-constexpr int kStEdges = kStRows * 32;       // at most p <= 32 forward samples per row and kind
-constexpr int kStPasses = kStRows / (kStBlock / 32);
+constexpr int kStEdges = 256 * 32;           // edges per batch: 256 rows of 32, or 128 rows of 64
+constexpr int kStPasses = 8;                 // passes of kStBlock / PW rows make a batch
 
+template <int PW>
 __global__ __launch_bounds__(kStBlock) void k_fwd_scatter_staged(
     int64_t n, int p, BucketGeom g, const int32_t* snew, const int32_t* sold,
     const uint32_t* wg_hist, const uint64_t* boff, uint2* edges_new, uint2* edges_old) {
@@ -254,7 +255,9 @@ __global__ __launch_bounds__(kStBlock) void k_fwd_scatter_staged(
   const int64_t row0 = (int64_t)blockIdx.x * g.rows_per_wg;
   const int64_t row1 = row0 + g.rows_per_wg < n ? row0 + g.rows_per_wg : n;
   const int per = (g.nb + kStBlock - 1) / kStBlock;  // buckets per thread in the scan (<= 4)
-  const int sub = tid & 31, rsel = tid >> 5;           // entry of a row, row of a pass
+  constexpr int kRowsPerPass = kStBlock / PW, kStRows = kStPasses * kRowsPerPass;
+  static_assert(kStRows * PW == kStEdges, "a batch fills the staging area");
+  const int sub = tid & (PW - 1), rsel = tid / PW;     // entry of a row, row of a pass
   for (int64_t b0 = row0; b0 < row1; b0 += kStRows) {
     for (int kind = 0; kind < 2; ++kind) {
       const int32_t* list = kind ? sold : snew;
@@ -265,7 +268,7 @@ __global__ __launch_bounds__(kStBlock) void k_fwd_scatter_staged(
       uint32_t rank[kStPasses];
 #pragma unroll
       for (int q = 0; q < kStPasses; ++q) {
-        const int64_t s = b0 + q * (kStBlock / 32) + rsel;
+        const int64_t s = b0 + q * kRowsPerPass + rsel;
         v[q] = (s < row1 && sub < p) ? list[s * L + sub] : -1;
       }
 #pragma unroll
@@ -301,7 +304,7 @@ __global__ __launch_bounds__(kStBlock) void k_fwd_scatter_staged(
 #pragma unroll
       for (int q = 0; q < kStPasses; ++q)
         if (v[q] >= 0) {
-          const int64_t s = b0 + q * (kStBlock / 32) + rsel;
+          const int64_t s = b0 + q * kRowsPerPass + rsel;
           stage[off[(uint32_t)v[q] >> g.tb] + rank[q]] = make_uint2((uint32_t)v[q], (uint32_t)s);
         }
       __syncthreads();
@@ -443,13 +446,20 @@ hipError_t launch_sample_buckets(const Shape& sh, const DevState& ds, hipStream_
   k_bucket_scan<<<1, kCsrBlock, 0, st>>>(g.nb, bcnt, boff);
   static bool staged_attr = false;
   if (!staged_attr) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_fwd_scatter_staged),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_fwd_scatter_staged<32>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, 144 << 10);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_fwd_scatter_staged<64>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, 144 << 10);
     if (e != hipSuccess) return e;
     staged_attr = true;
   }
-  k_fwd_scatter_staged<<<grid, kStBlock, staged_lds_bytes(g), st>>>(
-      sh.n, sh.p, g, ds.snew, ds.sold, wg_hist, boff, edges_new, edges_old);
+  if (sh.p <= 32)
+    k_fwd_scatter_staged<32><<<grid, kStBlock, staged_lds_bytes(g), st>>>(
+        sh.n, sh.p, g, ds.snew, ds.sold, wg_hist, boff, edges_new, edges_old);
+  else
+    k_fwd_scatter_staged<64><<<grid, kStBlock, staged_lds_bytes(g), st>>>(
+        sh.n, sh.p, g, ds.snew, ds.sold, wg_hist, boff, edges_new, edges_old);
   k_bucket_csr<<<dim3((unsigned)g.nb, 2), kCsrBlock, (size_t)4 << g.tb, st>>>(
       sh.n, g, boff, edges_new, edges_old, ds.roff_new, ds.roff_old, ds.csr_new,
       ds.csr_old);

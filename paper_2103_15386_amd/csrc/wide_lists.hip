@@ -3,9 +3,8 @@
 // entries per lane - entry i sits in lane i % 64 of register i / 64.  Sorting is
 // two 64-lane networks plus a 128-wide bitonic merge; a sorted chunk of 64
 // candidates is merged into the list by splitting (smaller half / larger half)
-// against the first register and merging the larger half into the second.
-// Sample lists stay at 2p <= 64 objects, so sampling beyond the forward part and
-// both join kernels are the ones used for short lists.
+// against the first register and merging the larger half into the second
+// (sort128 / merge128).  The length of the sample lists is another matter (2p).
 #include "device_utils.hpp"
 #include "kernels.hpp"
 
@@ -21,26 +20,6 @@ __device__ inline int64_t wide_wave_index() {
 }
 inline dim3 wide_blocks(int64_t waves) {
   return grid_blocks((waves + kWavesPerWB - 1) / kWavesPerWB);
-}
-
-// 128 values ascending over (lo, hi).
-__device__ inline void sort128(uint64_t& lo, uint64_t& hi, int lane) {
-  lo = wave_sort(lo, lane);
-  hi = wave_sort(hi, lane);
-  const uint64_t t = reverse_lanes(hi, lane);  // lo ++ t is bitonic
-  const uint64_t a = vmin(lo, t), b = vmax(lo, t);
-  lo = wave_bitonic_merge(a, lane);
-  hi = wave_bitonic_merge(b, lane);
-}
-
-// (lo, hi) ascending, c ascending (64 values): afterwards (lo, hi) holds the
-// 128 smallest of the 192, ascending.
-__device__ inline void merge128(uint64_t& lo, uint64_t& hi, uint64_t c, int lane) {
-  const uint64_t t = reverse_lanes(c, lane);
-  const uint64_t a = vmin(lo, t), b = vmax(lo, t);
-  lo = wave_bitonic_merge(a, lane);
-  const uint64_t spill = wave_bitonic_merge(b, lane);  // the 64 largest of lo and c, ascending
-  hi = wave_merge_smallest(hi, spill, lane);
 }
 
 // lower bound of key kk among the 64 ascending entries of `row`, compared on (distance, id)

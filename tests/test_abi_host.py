@@ -43,7 +43,8 @@ def test_workspace_size_and_parameter_validation(amd):
     assert amd.workspace_bytes((1 << 27) + 1, 16, 10, 8, amd.L2SQ_F32) == 0  # n <= 2^27
     assert amd.workspace_bytes(1 << 27, 16, 10, 8, amd.L2SQ_F32) > 0
     assert amd.workspace_bytes(4096, 16, 10, 11, amd.L2SQ_F32) == 0   # p > k
-    assert amd.workspace_bytes(4096, 16, 40, 33, amd.L2SQ_F32) == 0   # p > 32
+    assert amd.workspace_bytes(4096, 16, 40, 33, amd.L2SQ_F32) > 0    # sample lists of 66
+    assert amd.workspace_bytes(4096, 16, 128, 65, amd.L2SQ_F32) == 0  # p > 64
     assert amd.workspace_bytes(4096, 0, 10, 8, amd.L2SQ_F32) == 0     # d < 1
     assert amd.workspace_bytes(4096, 16, 10, 8, 7) == 0               # metric
     # gnnd_create validates before touching the GPU: errors come back as codes

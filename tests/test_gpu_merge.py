@@ -36,6 +36,7 @@ def x_is_bytes(gen):
     (og.CHI2_F32, lambda n: W.gist_like_f32(n, 40, seed=207, n_comp=8), 14, 10, 1200, 3),
     (og.COSINE_F32, lambda n: W.scaled_directions_f32(n, 24, seed=208, n_comp=8), 16, 12, 1000, 3),
     (og.COSINE_F32, lambda n: W.scaled_directions_f32(n, 10, seed=209, n_comp=4), 70, 16, 900, 2),
+    (og.L2SQ_F32, lambda n: W.uniform_f32(n, 10, seed=210), 80, 40, 900, 3),  # long sample lists
 ])
 def test_merge_matches_oracle(metric, gen, k, p, n1, iters, path):
     import paper_2103_15386_amd as amd

@@ -72,6 +72,14 @@ CASES = {
     "k100_angular": (lambda: W.deep_like_f32(1500, 48, seed=1022, n_comp=8),
                      og.ANGULAR_F32, 100, 24, 4),
     "k65_tiny": (lambda: W.uniform_f32(140, 6, seed=1023), og.L2SQ_F32, 65, 9, 3),
+    # sample lists longer than one wavefront (p > 32: the paper varies p up to 42, Sec. 6.3)
+    "p42_k64": (lambda: W.uniform_f32(2000, 12, seed=1081), og.L2SQ_F32, 64, 42, 4),
+    "p64_k128_u8": (lambda: W.sift_like_u8(1500, 32, seed=1082, n_comp=6), og.L2SQ_U8, 128, 64, 3),
+    "p33_k40_angular": (lambda: W.deep_like_f32(1200, 24, seed=1083, n_comp=8),
+                        og.ANGULAR_F32, 40, 33, 4),
+    "p40_k48_cosine_d70": (lambda: W.scaled_directions_f32(900, 70, seed=1084, n_comp=6),
+                           og.COSINE_F32, 48, 40, 3),
+    "p50_k50_small_n": (lambda: W.uniform_f32(90, 5, seed=1085), og.L2SQ_F32, 50, 50, 3),
 }
 
 
