@@ -210,13 +210,21 @@ void og_bruteforce(const void* vec, int64_t n, int d, int metric, const int32_t*
  * until the id is neither `forbid` nor one drawn for an earlier slot; after
  * OG_HASH_ATTEMPTS failed attempts it steps to the next id (cyclically) until
  * one is free, which always ends because count <= number of allowed ids. */
+static void draw_distinct_from(uint64_t seed, uint32_t tag, uint32_t s, int slot0, int count,
+                               uint32_t n_range, int32_t base, int32_t forbid, int32_t* out);
 static void draw_distinct(uint64_t seed, uint32_t tag, uint32_t s, int count, uint32_t n_range,
                           int32_t base, int32_t forbid, int32_t* out) {
+  draw_distinct_from(seed, tag, s, 0, count, n_range, base, forbid, out);
+}
+/* The same with the slots numbered slot0, slot0 + 1, ... in the hash (several groups of
+ * slots of one node, each distinct within itself). */
+static void draw_distinct_from(uint64_t seed, uint32_t tag, uint32_t s, int slot0, int count,
+                               uint32_t n_range, int32_t base, int32_t forbid, int32_t* out) {
   for (int j = 0; j < count; ++j) {
     uint32_t cand = 0;
     int ok = 0;
     for (uint32_t attempt = 0; attempt < OG_HASH_ATTEMPTS && !ok; ++attempt) {
-      cand = og_bounded(og_hash(seed, tag, s, (uint32_t)j, attempt), n_range);
+      cand = og_bounded(og_hash(seed, tag, s, (uint32_t)(slot0 + j), attempt), n_range);
       ok = ((int32_t)cand + base != forbid);
       for (int e = 0; e < j && ok; ++e) ok = (out[e] != (int32_t)cand + base);
     }
@@ -265,6 +273,44 @@ void og_init_random(const void* vec, int64_t n, int d, int k, int metric, uint64
     free(row);
     free(draw);
   }
+}
+
+/* Segmented lists (Sec. 4.3, "Multiple Spinlocks"): a list of k = 32 m entries is kept as
+ * m = k / 32 segments of 32 entries, object v can only live in segment v % m, and when an
+ * iteration is over the segments are merged into one ascending list.  Reading for the
+ * first loop of Alg. 1 (the paper does not say how a segmented list starts): every segment
+ * starts with 32 distinct random objects of its own residue class (other than s), drawn
+ * like the plain list - slot 32 r + j of node s takes the class member number
+ * hash(seed, INIT, s, 32 r + j, attempt) mapped onto the class size; the list is handed out
+ * merged, ascending by (distance, id), all NEW.  Every class must have more than 32
+ * members (n >= 33 m + m suffices).  With m = 1 this is og_init_random with k = 32. */
+void og_init_random_segmented(const void* vec, int64_t n, int d, int k, int metric, uint64_t seed,
+                              int32_t* ids, double* dist, uint8_t* isnew) {
+  const int m = k / 32;
+  entry_t* row = (entry_t*)malloc(sizeof(entry_t) * (size_t)k);
+  int32_t* draw = (int32_t*)malloc(sizeof(int32_t) * 32);
+  for (int64_t s = 0; s < n; ++s) {
+    for (int r = 0; r < m; ++r) {
+      const uint32_t members = (uint32_t)((n - r + m - 1) / m);  /* ids r, r + m, r + 2m, ... */
+      const int32_t own = (s % m == r) ? (int32_t)(s / m) : -1;  /* s as a member number */
+      draw_distinct_from(seed, OG_TAG_INIT, (uint32_t)s, 32 * r, 32, members, 0, own, draw);
+      for (int j = 0; j < 32; ++j) {
+        const int32_t id = draw[j] * m + r;
+        row[32 * r + j].id = id;
+        row[32 * r + j].d = og_distance(metric, d, vec, s, id);
+        row[32 * r + j].isnew = 1;
+        row[32 * r + j].fresh = 0;
+      }
+    }
+    qsort(row, (size_t)k, sizeof(entry_t), entry_cmp);
+    for (int j = 0; j < k; ++j) {
+      ids[s * k + j] = row[j].id;
+      dist[s * k + j] = row[j].d;
+      isnew[s * k + j] = 1;
+    }
+  }
+  free(row);
+  free(draw);
 }
 
 /* ------------------------------------------------------------------------- */
@@ -624,6 +670,9 @@ uint64_t og_classic_join_update(const void* vec, int64_t n, int d, int k, int p,
 uint64_t og_update_rows(int64_t n, int k, int P, int32_t* ids, double* dist, uint8_t* isnew,
                         const int32_t* pu, const int32_t* pv, const double* pd,
                         const int32_t* pcnt);
+static uint64_t update_classes(int64_t n, int k, int P, int classes, int32_t* ids, double* dist,
+                               uint8_t* isnew, const int32_t* pu, const int32_t* pv,
+                               const double* pd, const int32_t* pcnt);
 uint64_t og_update(int64_t n, int k, int p, int32_t* ids, double* dist, uint8_t* isnew,
                    const int32_t* pu, const int32_t* pv, const double* pd, const int32_t* pcnt) {
   return og_update_rows(n, k, 6 * p, ids, dist, isnew, pu, pv, pd, pcnt);
@@ -632,6 +681,23 @@ uint64_t og_update(int64_t n, int k, int p, int32_t* ids, double* dist, uint8_t*
 uint64_t og_update_rows(int64_t n, int k, int P, int32_t* ids, double* dist, uint8_t* isnew,
                         const int32_t* pu, const int32_t* pv, const double* pd,
                         const int32_t* pcnt) {
+  return update_classes(n, k, P, 1, ids, dist, isnew, pu, pv, pd, pcnt);
+}
+/* Insertion into segmented lists (Sec. 4.3, "Multiple Spinlocks"): "the object v will be
+ * inserted into the v % (k / 32)-th segment", each segment "keeps 32 neighbors", and "as the
+ * iteration is completed, all the segments of one k-NN list will be merged into one".  As a
+ * set function: per residue class of the ids (m = k / 32 classes) the 32 best, by
+ * (distance, id), of the class's entries before the iteration and the proposals of that
+ * class, one entry per id; the list is their union, ascending.  m = 1 is the plain list. */
+uint64_t og_update_segmented(int64_t n, int k, int P, int32_t* ids, double* dist, uint8_t* isnew,
+                             const int32_t* pu, const int32_t* pv, const double* pd,
+                             const int32_t* pcnt) {
+  return update_classes(n, k, P, k / 32, ids, dist, isnew, pu, pv, pd, pcnt);
+}
+/* `classes` classes of ids (v % classes), each holding at most k / classes entries. */
+static uint64_t update_classes(int64_t n, int k, int P, int classes, int32_t* ids, double* dist,
+                               uint8_t* isnew, const int32_t* pu, const int32_t* pv,
+                               const double* pd, const int32_t* pcnt) {
   int64_t* off = (int64_t*)calloc((size_t)n + 1, sizeof(int64_t));
   for (int64_t s = 0; s < n; ++s)
     for (int j = 0; j < pcnt[s]; ++j) off[pu[s * P + j] + 1]++;
@@ -672,10 +738,13 @@ uint64_t og_update_rows(int64_t n, int k, int P, int32_t* ids, double* dist, uin
     }
     qsort(pool, (size_t)m, sizeof(entry_t), entry_cmp);
     int w = 0;
+    int held[4] = {0, 0, 0, 0};  /* entries taken per class (at most 4 classes: k <= 128) */
     for (int64_t e = 0; e < m && w < k; ++e) {
       int dup = 0;
       for (int j = 0; j < w && !dup; ++j) dup = (ids[u * k + j] == pool[e].id);
       if (dup) continue;
+      if (held[pool[e].id % classes] >= k / classes) continue;  /* its segment is full */
+      held[pool[e].id % classes]++;
       ids[u * k + w] = pool[e].id;
       dist[u * k + w] = pool[e].d;
       isnew[u * k + w] = pool[e].isnew;

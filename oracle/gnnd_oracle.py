@@ -73,6 +73,12 @@ def _load():
     lib.og_classic_join_update.argtypes = [vp, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int,
                                            i32p, i32p, i32p, i32p, i32p, f64p, u8p,
                                            np.ctypeslib.ndpointer(np.uint64, flags="C")]
+    lib.og_update_segmented.restype = C.c_uint64
+    lib.og_update_segmented.argtypes = [C.c_int64, C.c_int, C.c_int, i32p, f64p, u8p, i32p, i32p,
+                                        f64p, i32p]
+    lib.og_init_random_segmented.restype = None
+    lib.og_init_random_segmented.argtypes = [vp, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_uint64,
+                                             i32p, f64p, u8p]
     lib.og_update.restype = C.c_uint64
     lib.og_update.argtypes = [C.c_int64, C.c_int, C.c_int, i32p, f64p, u8p, i32p, i32p, f64p,
                               i32p]
@@ -146,11 +152,19 @@ class Graph:
         return Graph(self.ids.copy(), self.dist.copy(), self.isnew.copy())
 
 
-def init_random(vectors, k, metric, seed):
+def init_random(vectors, k, metric, seed, segmented=False):
+    """Alg. 1, first loop.  segmented: the list of k = 32 m entries starts as m segments of
+    32 random objects of one residue class each (Sec. 4.3, "Multiple Spinlocks")."""
     v = _vec(vectors, metric)
     n, d = v.shape
     g = Graph(np.empty((n, k), np.int32), np.empty((n, k), np.float64), np.empty((n, k), np.uint8))
-    _load().og_init_random(v.ctypes.data, n, d, k, metric, seed, g.ids, g.dist, g.isnew)
+    if segmented:
+        if k % 32 or not 32 <= k <= 128 or n < 34 * (k // 32):
+            raise ValueError("segmented lists need k in {32, 64, 96, 128} and n >= 34 k / 32")
+        _load().og_init_random_segmented(v.ctypes.data, n, d, k, metric, seed, g.ids, g.dist,
+                                         g.isnew)
+    else:
+        _load().og_init_random(v.ctypes.data, n, d, k, metric, seed, g.ids, g.dist, g.isnew)
     return g
 
 
@@ -187,31 +201,34 @@ def insert_one(ids_row, dist_row, isnew_row, v, d):
     return int(_load().og_insert_one(len(ids_row), ids_row, dist_row, isnew_row, v, d))
 
 
-def update(g, p, pu, pv, pd, pcnt):
+def update(g, p, pu, pv, pd, pcnt, segmented=False):
     n, k = g.ids.shape
+    if segmented:  # object v competes inside segment v % (k / 32) only
+        return int(_load().og_update_segmented(n, k, pu.shape[1], g.ids, g.dist, g.isnew, pu, pv,
+                                               pd, pcnt))
     if pu.shape[1] != 6 * p:  # rows of the all-pairs join
         return int(_load().og_update_rows(n, k, pu.shape[1], g.ids, g.dist, g.isnew, pu, pv, pd,
                                           pcnt))
     return int(_load().og_update(n, k, p, g.ids, g.dist, g.isnew, pu, pv, pd, pcnt))
 
 
-def iterate(vectors, metric, g, p, seed, it, split=-1, all_pairs=False):
+def iterate(vectors, metric, g, p, seed, it, split=-1, all_pairs=False, segmented=False):
     """One GNND iteration (Alg. 1 loop body) in place; `it` counts from 1.
     Returns a dict of statistics and the intermediate sample lists/proposals."""
     snew, cnew, sold, cold = sample(g, p, seed, it)
     pu, pv, pd, pcnt, ev = join(vectors, metric, p, snew, cnew, sold, cold, split, all_pairs)
-    ins = update(g, p, pu, pv, pd, pcnt)
+    ins = update(g, p, pu, pv, pd, pcnt, segmented)
     return dict(iter=it, inserts=ins, dist_evals=ev, sum_new=int(cnew.sum()),
                 sum_old=int(cold.sum()), proposals=int(pcnt.sum()),
                 snew=snew, cnew=cnew, sold=sold, cold=cold)
 
 
-def build(vectors, k, p, metric, seed, iters, all_pairs=False):
+def build(vectors, k, p, metric, seed, iters, all_pairs=False, segmented=False):
     """Alg. 1 as a whole: random initial graph, then `iters` iterations."""
-    g = init_random(vectors, k, metric, seed)
+    g = init_random(vectors, k, metric, seed, segmented)
     stats = []
     for it in range(1, iters + 1):
-        st = iterate(vectors, metric, g, p, seed, it, all_pairs=all_pairs)
+        st = iterate(vectors, metric, g, p, seed, it, all_pairs=all_pairs, segmented=segmented)
         stats.append({key: st[key] for key in ("iter", "inserts", "dist_evals", "sum_new",
                                                "sum_old", "proposals")})
     return g, stats

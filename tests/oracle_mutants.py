@@ -46,6 +46,11 @@ muts = [
  ("merge final without the set-aside half", "    for (int j = 0; j < fill; ++j) {\n      pool[m].id = aside_ids[s * fill + j];", "    for (int j = 0; j < 0; ++j) {\n      pool[m].id = aside_ids[s * fill + j];"),
  ("merge sets aside one entry twice", "aside_ids[s * fill + j] = og_to_internal(sid[keep + j], n1, base1, n2, base2);\n      aside_dist[s * fill + j] = sdist[keep + j];", "aside_ids[s * fill + j] = og_to_internal(sid[keep + (j ? j - 1 : 0)], n1, base1, n2, base2);\n      aside_dist[s * fill + j] = sdist[keep + (j ? j - 1 : 0)];"),
  ("merge fill distance to the wrong node", "row[keep + j].d = og_distance(metric, d, vec, s, draw[j]);", "row[keep + j].d = og_distance(metric, d, vec, s > 0 ? s - 1 : s, draw[j]);"),
+ ("segment capacity ignored", "      if (held[pool[e].id % classes] >= k / classes) continue;  /* its segment is full */\n", ""),
+ ("segment chosen by position not id", "      if (held[pool[e].id % classes] >= k / classes) continue;  /* its segment is full */\n      held[pool[e].id % classes]++;", "      if (held[w % classes] >= k / classes) continue;\n      held[w % classes]++;"),
+ ("segmented init ignores the class", "        const int32_t id = draw[j] * m + r;", "        const int32_t id = draw[j] * m;"),
+ ("segmented init may draw the node itself", "      const int32_t own = (s % m == r) ? (int32_t)(s / m) : -1;  /* s as a member number */", "      const int32_t own = -1;"),
+ ("segmented init reuses slot numbers", "draw_distinct_from(seed, OG_TAG_INIT, (uint32_t)s, 32 * r, 32, members, 0, own, draw);", "draw_distinct_from(seed, OG_TAG_INIT, (uint32_t)s, 0, 32, members, 0, own, draw);"),
  ("classic inserts one side only", "        ins += (uint64_t)og_insert_one(k, ids + (int64_t)N[b] * k, dist + (int64_t)N[b] * k,\n                                       isnew + (int64_t)N[b] * k, N[a], dd);\n", ""),
 ]
 root=os.path.dirname(os.path.dirname(os.path.abspath(__file__))); tmp="/tmp/gnnd_oracle_mutants"

@@ -913,3 +913,127 @@ def test_phi_trend_of_gnnd_overlaps_classic_nn_descent():
     exact = og.phi(td)
     assert exact <= trend_classic[-1] <= 1.02 * exact and exact <= trend[-1] <= 1.02 * exact
     _check_lists(g_classic, x, og.L2SQ_F32)
+
+
+# ---- segmented lists (Sec. 4.3, "Multiple Spinlocks") ------------------------------------
+def _class_rows(g, s, m):
+    """Per residue class the (distance, id) pairs of row s, in list order."""
+    return [[(float(dd), int(v)) for v, dd in zip(g.ids[s], g.dist[s]) if v % m == r]
+            for r in range(m)]
+
+
+def test_segmented_init_draws_32_of_every_class_and_reduces_to_the_plain_init():
+    # "k-NN list is divided into k/32 segments. Each segment keeps 32 neighbors.  The object
+    # v will be inserted into the v % (k/32)-th segment": a list that starts segmented holds
+    # 32 objects of every residue class.  With one segment (k = 32) nothing distinguishes the
+    # segmented form from the plain one: same draws, same list.
+    x = W.uniform_f32(500, 7, seed=91)
+    plain = og.init_random(x, 32, og.L2SQ_F32, 5)
+    seg = og.init_random(x, 32, og.L2SQ_F32, 5, segmented=True)
+    assert (plain.ids == seg.ids).all() and (plain.dist == seg.dist).all()
+    for k in (64, 96, 128):
+        m = k // 32
+        g = og.init_random(x, k, og.L2SQ_F32, 5, segmented=True)
+        assert g.isnew.all()
+        for s in range(0, 500, 7):
+            assert s not in g.ids[s] and len(set(g.ids[s].tolist())) == k
+            keys = list(zip(g.dist[s].tolist(), g.ids[s].tolist()))
+            assert keys == sorted(keys)
+            assert np.bincount(g.ids[s] % m, minlength=m).tolist() == [32] * m
+            for v, dd in zip(g.ids[s], g.dist[s]):
+                assert dd == og.distance(x, og.L2SQ_F32, s, int(v))
+        # the draws are the documented ones: slot 32 r + j, first attempt, when nothing clashes
+        s = 11
+        for r in range(m):
+            members = (500 - r + m - 1) // m
+            first = [og.bounded(og.hash5(5, og.TAG_INIT, s, 32 * r + j, 0), members) * m + r
+                     for j in range(32)]
+            if len(set(first)) == 32 and s not in first:
+                assert sorted(first) == sorted(v for v in g.ids[s].tolist() if v % m == r)
+    # tiny classes: with n = 34 m every class has 34 members, one of them possibly s itself
+    tiny = og.init_random(W.uniform_f32(68, 3, seed=92), 64, og.L2SQ_F32, 6, segmented=True)
+    assert all(np.bincount(tiny.ids[s] % 2, minlength=2).tolist() == [32, 32] for s in range(68))
+    with pytest.raises(ValueError):
+        og.init_random(x, 48, og.L2SQ_F32, 5, segmented=True)
+
+
+def test_segmented_update_is_the_per_class_best_32_and_order_independent():
+    # The update as a set function, recomputed from its definition in Python: per class the
+    # 32 best of (class entries before) u (proposals of that class), one entry per id; and
+    # the same lists come out of one-by-one insertions into the 32-entry segments in any
+    # order (each segment behind its own lock, Sec. 4.3).
+    rng = np.random.default_rng(17)
+    x = W.small_integer_f32(400, 4, seed=93, hi=5)  # many equal distances
+    for k in (64, 128):
+        m = k // 32
+        g = og.init_random(x, k, og.L2SQ_F32, 9, segmented=True)
+        p = 16
+        snew, cnew, sold, cold = og.sample(g, p, 9, 1)
+        pu, pv, pd, pcnt, _ = og.join(x, og.L2SQ_F32, p, snew, cnew, sold, cold)
+        before = g.copy()
+        ins = og.update(g, p, pu, pv, pd, pcnt, segmented=True)
+        props = {}
+        for s in range(400):
+            for j in range(pcnt[s]):
+                props.setdefault(int(pu[s, j]), []).append((float(pd[s, j]), int(pv[s, j])))
+        admitted = 0
+        for u in range(400):
+            old = _class_rows(before, u, m)
+            want = []
+            for r in range(m):
+                pool = {v: dd for dd, v in old[r]}
+                for dd, v in props.get(u, []):
+                    if v % m == r:
+                        pool.setdefault(v, dd)
+                best = sorted((dd, v) for v, dd in pool.items())[:32]
+                admitted += len({v for _, v in best} - {v for _, v in old[r]})
+                want += best
+            got = list(zip(g.dist[u].tolist(), g.ids[u].tolist()))
+            assert got == sorted(want), u
+        assert ins == admitted
+        # admitted entries are NEW, the others keep the flag sampling left them with
+        for u in range(0, 400, 9):
+            was = dict(zip(before.ids[u].tolist(), before.isnew[u].tolist()))
+            for v, f in zip(g.ids[u].tolist(), g.isnew[u].tolist()):
+                assert f == (1 if v not in was else was[v])
+        # one by one, random order, into per-class arrays of 32
+        for u in rng.choice(400, 25, replace=False):
+            segs = [[np.array([v for _, v in c], np.int32), np.array([dd for dd, _ in c]),
+                     np.zeros(32, np.uint8)] for c in _class_rows(before, int(u), m)]
+            mine = props.get(int(u), [])
+            for i in rng.permutation(len(mine)):
+                dd, v = mine[i]
+                og.insert_one(segs[v % m][0], segs[v % m][1], segs[v % m][2], v, dd)
+            merged = sorted((float(dd), int(v)) for sg in segs for v, dd in zip(sg[0], sg[1]))
+            assert merged == list(zip(g.dist[u].tolist(), g.ids[u].tolist()))
+
+
+def test_segmented_build_converges_to_the_exact_lists_of_every_class():
+    # On a tiny input the iteration finds, for every node, its exact nearest neighbours
+    # (Recall@10 = 1 against exhaustive search) and the exact 8 nearest members of every
+    # residue class (exhaustive search per class); phi never grows on the way and every
+    # class keeps its 32 entries.  (The far end of a 32-entry segment is not reached by the
+    # nearest-partner proposals of Alg. 2 on so small a set, hence the first 8.)
+    n, k, m = 600, 64, 2
+    x = W.uniform_f32(n, 3, seed=94)
+    g = og.init_random(x, k, og.L2SQ_F32, 3, segmented=True)
+    phi = [og.phi(g.dist)]
+    for it in range(1, 11):
+        prev = g.dist.copy()
+        og.iterate(x, og.L2SQ_F32, g, 32, 3, it, segmented=True)
+        assert ((g.ids % m) == 0).sum(1).tolist() == [32] * n
+        assert (np.sort(g.dist, axis=1) == g.dist).all()
+        phi.append(og.phi(g.dist))
+        assert phi[-1] <= phi[-2] and (g.dist.sum(1) <= prev.sum(1)).all()
+    tids, tdist = og.bruteforce(x, og.L2SQ_F32, np.arange(n), 10)
+    assert og.recall_at(g.ids, g.dist, tids, tdist, 10) == (1.0, 1.0)
+    hit = total = 0
+    for s in range(0, n, 5):
+        for r in range(m):
+            members = np.array([v for v in range(r, n, m) if v != s], np.int32)
+            dd = np.array([og.distance(x, og.L2SQ_F32, s, int(v)) for v in members])
+            exact = sorted(zip(dd.tolist(), members.tolist()))[:8]
+            got = [(float(a), int(v)) for v, a in zip(g.ids[s], g.dist[s]) if v % m == r][:8]
+            hit += len(set(exact) & set(got))
+            total += 8
+    assert hit / total > 0.995, hit / total
