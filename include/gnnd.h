@@ -83,6 +83,18 @@ enum {
                                 runs in the GNND_JOIN_VALU form only                    */
 };
 
+/* How a k-NN list is kept (Sec. 4.3, "Multiple Spinlocks"). */
+enum {
+  GNND_LISTS_PLAIN = 0,    /* one ascending list of k entries: the best k seen so far       */
+  GNND_LISTS_SEGMENTED = 1 /* k = 32 m (k = 32, 64, 96, 128): m segments of 32 entries,
+                              object v can only live in segment v % m; a list starts with
+                              32 random objects of every residue class and always holds,
+                              per class, the best 32 seen so far; it is handed out merged,
+                              ascending by (distance, id).  For gnnd_create / gnnd_build
+                              (not for merges or loaded graphs); selective update only.
+                              With k = 32 the same as GNND_LISTS_PLAIN                    */
+};
+
 typedef struct gnnd_params {
   int64_t n;      /* number of vectors, k < n <= 2^27                               */
   int32_t d;      /* dimension, >= 1 (float metrics: multiple of 4 reads fastest)   */
@@ -96,6 +108,8 @@ typedef struct gnnd_params {
   size_t workspace_bytes; /* its size, >= gnnd_workspace_bytes()                    */
   int32_t join_path;      /* GNND_JOIN_*                                            */
   int32_t update_mode;    /* GNND_UPDATE_*; 0 = the method as published             */
+  int32_t list_mode;      /* GNND_LISTS_*; 0 = plain lists                          */
+  int32_t reserved;       /* 0                                                      */
 } gnnd_params;
 
 /* Counters of one iteration.  ms_* are stream times from HIP events. */

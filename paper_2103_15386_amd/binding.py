@@ -10,6 +10,7 @@ import torch
 L2SQ_F32, ANGULAR_F32, L2SQ_U8, CHI2_F32, COSINE_F32 = 0, 1, 2, 3, 4
 JOIN_AUTO, JOIN_VALU, JOIN_MFMA, JOIN_MFMA_DIRECT = 0, 1, 2, 3
 UPDATE_SELECTIVE, UPDATE_ALL_PAIRS = 0, 1
+LISTS_PLAIN, LISTS_SEGMENTED = 0, 1
 OK, EINVAL, ENOSPC, ESTATE, EHIP, EIO = 0, -1, -2, -3, -4, -5
 STATIC_SCRATCH_BYTES = 64 << 20  # GNND_STATIC_SCRATCH_BYTES of include/gnnd.h
 
@@ -37,7 +38,8 @@ class Params(C.Structure):
     _fields_ = [("n", C.c_int64), ("d", C.c_int32), ("k", C.c_int32), ("p", C.c_int32),
                 ("metric", C.c_int32), ("seed", C.c_uint64), ("stream", C.c_void_p),
                 ("workspace_dev", C.c_void_p), ("workspace_bytes", C.c_size_t),
-                ("join_path", C.c_int32), ("update_mode", C.c_int32)]
+                ("join_path", C.c_int32), ("update_mode", C.c_int32),
+                ("list_mode", C.c_int32), ("reserved", C.c_int32)]
 
 
 class IterStats(C.Structure):
@@ -154,22 +156,23 @@ def _stream_ptr(device):
 
 
 def make_params(n, d, k, p, metric, seed=42, join_path=JOIN_AUTO, stream=0, workspace=None,
-                update_mode=UPDATE_SELECTIVE):
+                update_mode=UPDATE_SELECTIVE, list_mode=LISTS_PLAIN):
     prm = Params()
     prm.n, prm.d, prm.k, prm.p, prm.metric = n, d, k, p, metric
     prm.seed = seed
     prm.stream = stream
     prm.join_path = join_path
     prm.update_mode = update_mode
+    prm.list_mode = list_mode
     if workspace is not None:
         prm.workspace_dev = workspace.data_ptr()
         prm.workspace_bytes = workspace.numel() * workspace.element_size()
     return prm
 
 
-def workspace_bytes(n, d, k, p, metric, update_mode=UPDATE_SELECTIVE):
+def workspace_bytes(n, d, k, p, metric, update_mode=UPDATE_SELECTIVE, list_mode=LISTS_PLAIN):
     """Bytes of device scratch a context with these parameters needs (0 = invalid)."""
-    prm = make_params(n, d, k, p, metric, update_mode=update_mode)
+    prm = make_params(n, d, k, p, metric, update_mode=update_mode, list_mode=list_mode)
     return int(load_library().gnnd_workspace_bytes(C.byref(prm)))
 
 
@@ -177,22 +180,22 @@ class Gnnd:
     """One GNND context over a resident vector tensor (n x d, float32 or uint8)."""
 
     def __init__(self, vectors, k, p, metric=L2SQ_F32, seed=42, join_path=JOIN_AUTO,
-                 update_mode=UPDATE_SELECTIVE):
+                 update_mode=UPDATE_SELECTIVE, list_mode=LISTS_PLAIN):
         lib = load_library()
         self.vectors = _require_device(vectors, _elem_dtype(metric), "vectors")
         self.n, self.d = vectors.shape
         self.k, self.p, self.metric, self.seed = k, p, metric, seed
         self.update_mode = update_mode
-        need = workspace_bytes(self.n, self.d, k, p, metric, update_mode)
+        need = workspace_bytes(self.n, self.d, k, p, metric, update_mode, list_mode)
         if need == 0:
             prm = make_params(self.n, self.d, k, p, metric, seed, join_path,
-                              update_mode=update_mode)
+                              update_mode=update_mode, list_mode=list_mode)
             ctx = C.c_void_p()
             rc = lib.gnnd_create(C.byref(ctx), C.byref(prm), vectors.data_ptr())
             raise GnndError(rc, _err())
         self.workspace = torch.empty(need, dtype=torch.uint8, device=vectors.device)
         self.prm = make_params(self.n, self.d, k, p, metric, seed, join_path,
-                               _stream_ptr(vectors.device), self.workspace, update_mode)
+                               _stream_ptr(vectors.device), self.workspace, update_mode, list_mode)
         self._ctx = C.c_void_p()
         _check(lib.gnnd_create(C.byref(self._ctx), C.byref(self.prm), vectors.data_ptr()))
         self._lib = lib

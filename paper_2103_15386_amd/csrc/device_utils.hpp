@@ -240,6 +240,37 @@ __device__ inline uint64_t wave_compact(uint64_t v, bool keep, uint64_t fill, in
   return ((uint64_t)hi << 32) | lo;
 }
 
+// Drop from `pk` (one candidate per lane, kKeyMax = none) what cannot enter the
+// ascending list `row` of k entries: not closer than its last entry, already
+// in it, or a repeat of another candidate.  Returns the survivors ascending.
+__device__ inline uint64_t filter_candidates(uint64_t pk, uint64_t row, int k, int lane,
+                                             bool& any) {
+  const uint64_t last = readlane64(row, k - 1);
+  if (pk != kKeyMax && entry_key(pk) >= entry_key(last)) pk = kKeyMax;
+  any = __ballot(pk != kKeyMax) != 0ull;
+  if (!any) return pk;
+  // already in the list?  The 64 lanes of `row` ascend (unused lanes hold the
+  // maximum), so each candidate finds its lower bound in six halving steps.
+  const uint64_t kk = entry_key(pk);
+  int pos = 0;
+#pragma unroll
+  for (int step = kWave / 2; step > 0; step >>= 1) {
+    const uint64_t r = __shfl(row, pos + step - 1, kWave);
+    pos += (entry_key(r) < kk) ? step : 0;
+  }
+  if (entry_key(__shfl(row, pos, kWave)) == kk) pk = kKeyMax;
+  const uint64_t left = __ballot(pk != kKeyMax);
+  any = left != 0ull;
+  if (!any) return pk;
+  // survivors to the front, then a sorting network just wide enough for them
+  pk = wave_compact(pk, pk != kKeyMax, kKeyMax, lane);
+  pk = wave_sort_upto(pk, lane, __popcll(left));
+  const uint64_t prev = __shfl_up(pk, 1, kWave);
+  const bool rep = lane > 0 && pk != kKeyMax && entry_key(pk) == entry_key(prev);
+  if (__ballot(rep) != 0ull) pk = wave_compact(pk, !rep, kKeyMax, lane);
+  return pk;
+}
+
 // ---- canonical distances --------------------------------------------------
 // Float metrics accumulate one fused multiply-add per dimension, in dimension
 // order, in float32; bytes accumulate exact int32 squares.  The result is the

@@ -65,6 +65,14 @@ const char* check_params(const gnnd_params* q) {
     return "GNND_UPDATE_ALL_PAIRS runs with GNND_JOIN_VALU (or GNND_JOIN_AUTO) only";
   if (q->update_mode == GNND_UPDATE_ALL_PAIRS && q->p > 32)
     return "GNND_UPDATE_ALL_PAIRS needs p <= 32";
+  if (q->list_mode != GNND_LISTS_PLAIN && q->list_mode != GNND_LISTS_SEGMENTED)
+    return "unknown list_mode";
+  if (q->list_mode == GNND_LISTS_SEGMENTED) {
+    if (q->k % 32 != 0) return "segmented lists need k = 32, 64, 96 or 128";
+    if (q->n < (int64_t)34 * (q->k / 32))
+      return "segmented lists need n >= 34 k / 32 (more than 32 other objects per residue class)";
+    if (q->update_mode != GNND_UPDATE_SELECTIVE) return "segmented lists run the selective update";
+  }
   return nullptr;
 }
 
@@ -206,6 +214,8 @@ int init_ctx(gnnd_ctx* c, const gnnd_params* prm, const Layout& L, const void* v
   c->stream = (hipStream_t)prm->stream;
   c->sh = Shape{prm->n, prm->d, prm->k, prm->p, prm->metric, split, vec_a, vec_b,
                 prm->update_mode == GNND_UPDATE_ALL_PAIRS ? 1 : 0};
+  // one segment of 32 is the plain list
+  c->sh.segments = prm->list_mode == GNND_LISTS_SEGMENTED ? prm->k / 32 : 1;
   c->iter = 0;
   c->stage = 0;
   c->has_graph = false;
@@ -396,6 +406,8 @@ int merge_impl(const gnnd_params* prm, const void* vec1, int64_t n1, int64_t bas
                const int32_t* ids1, const void* dist1, const int32_t* ids2, const void* dist2,
                int32_t iters, int32_t* ids_out, void* dist_out, gnnd_iter_stats* stats) {
   if (const char* m = check_params(prm)) return fail(nullptr, GNND_EINVAL, m);
+  if (prm->list_mode != GNND_LISTS_PLAIN)
+    return fail(nullptr, GNND_EINVAL, "the merge works on plain lists (list_mode 0)");
   if (n1 <= 0 || n2 <= 0 || n1 + n2 != prm->n)
     return fail(nullptr, GNND_EINVAL, "n1 + n2 must equal params.n, both positive");
   if (n1 <= prm->k || n2 <= prm->k)
@@ -448,6 +460,7 @@ struct ShardPlan {
 
 const char* plan_shards(const gnnd_params* prm, int32_t shards, ShardPlan* pl) {
   if (!prm) return "params is NULL";
+  if (prm->list_mode != GNND_LISTS_PLAIN) return "the shard driver works on plain lists (list_mode 0)";
   if (shards < 2 || shards > 1024) return "shards must be in [2, 1024]";
   gnnd_params q = *prm;
   pl->shards = shards;
@@ -965,6 +978,8 @@ int gnnd_set_graph(gnnd_ctx* c, const int32_t* ids, const void* dist, const uint
   if (!ids || !dist) return fail(c, GNND_EINVAL, "ids and dist are required");
   if (iter < 0) return fail(c, GNND_EINVAL, "iter must be >= 0");
   if (c->merge_mode) return fail(c, GNND_ESTATE, "context belongs to a merge");
+  if (c->sh.segments > 1)
+    return fail(c, GNND_ESTATE, "a graph cannot be loaded into segmented lists");
   // ids are checked on the device (they become row numbers); the verdict is fetched here
   int bad = 0;
   hipError_t e = launch_zero_u32((uint32_t*)c->flag_dev, 1, c->stream);

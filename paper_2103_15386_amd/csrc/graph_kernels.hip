@@ -134,37 +134,6 @@ __global__ __launch_bounds__(kBlock) void k_rev_select(int64_t n, int p, uint64_
 }
 
 // ---------------------------------------------------------------------------
-// Drop from `pk` (one candidate per lane, kKeyMax = none) what cannot enter the
-// ascending list `row` of k entries: not closer than its last entry, already
-// in it, or a repeat of another candidate.  Returns the survivors ascending.
-__device__ inline uint64_t filter_candidates(uint64_t pk, uint64_t row, int k, int lane,
-                                             bool& any) {
-  const uint64_t last = readlane64(row, k - 1);
-  if (pk != kKeyMax && entry_key(pk) >= entry_key(last)) pk = kKeyMax;
-  any = __ballot(pk != kKeyMax) != 0ull;
-  if (!any) return pk;
-  // already in the list?  The 64 lanes of `row` ascend (unused lanes hold the
-  // maximum), so each candidate finds its lower bound in six halving steps.
-  const uint64_t kk = entry_key(pk);
-  int pos = 0;
-#pragma unroll
-  for (int step = kWave / 2; step > 0; step >>= 1) {
-    const uint64_t r = __shfl(row, pos + step - 1, kWave);
-    pos += (entry_key(r) < kk) ? step : 0;
-  }
-  if (entry_key(__shfl(row, pos, kWave)) == kk) pk = kKeyMax;
-  const uint64_t left = __ballot(pk != kKeyMax);
-  any = left != 0ull;
-  if (!any) return pk;
-  // survivors to the front, then a sorting network just wide enough for them
-  pk = wave_compact(pk, pk != kKeyMax, kKeyMax, lane);
-  pk = wave_sort_upto(pk, lane, __popcll(left));
-  const uint64_t prev = __shfl_up(pk, 1, kWave);
-  const bool rep = lane > 0 && pk != kKeyMax && entry_key(pk) == entry_key(prev);
-  if (__ballot(rep) != 0ull) pk = wave_compact(pk, !rep, kKeyMax, lane);
-  return pk;
-}
-
 // Sec. 4.3 list insertion for all proposals of one destination at once: the
 // list becomes the best k, by (distance, id), of its entries and the proposed
 // objects, one entry per id - what inserting them one by one under a lock
@@ -548,6 +517,7 @@ hipError_t launch_row_norms(const Shape& sh, float* norms, hipStream_t st) {
 
 hipError_t launch_init_random(const Shape& sh, const DevState& ds, uint64_t seed,
                               hipStream_t st) {
+  if (sh.segments > 1) return launch_init_random_segmented(sh, ds, seed, st);
   if (sh.k > kWave) return launch_init_random_wide(sh, ds, seed, st);
   const dim3 grid = blocks_for_waves(sh.n);
   const uint64_t base = hash_base(seed, kTagInit);
@@ -594,6 +564,7 @@ hipError_t launch_sample(const Shape& sh, const DevState& ds, uint64_t seed, uin
 }
 
 hipError_t launch_update(const Shape& sh, const DevState& ds, hipStream_t st) {
+  if (sh.segments > 1) return launch_update_segmented(sh, ds, st);
   if (sh.k > kWave) return launch_update_wide(sh, ds, st);
   k_update<<<blocks_for_waves(sh.n), kBlock, 0, st>>>(sh.n, sh.k, ds.G, ds.meta, ds.pslot, ds.poff,
                                                       ds.bins, ds.counters);

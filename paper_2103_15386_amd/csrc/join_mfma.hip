@@ -828,7 +828,8 @@ hipError_t launch_join_mfma(const Shape& sh, const DevState& ds, bool merge_mode
 
 hipError_t launch_init_random_i8(const Shape& sh, const DevState& ds, uint64_t seed,
                                  hipStream_t st) {
-  // long lists: the general kernel on the original vectors gives the same integers
+  // long or segmented lists: the general kernels on the original vectors give the same integers
+  if (sh.segments > 1) return launch_init_random_segmented(sh, ds, seed, st);
   if (sh.k > kWave) return launch_init_random_wide(sh, ds, seed, st);
   const int dpad = (sh.d + 31) & ~31;
   const dim3 grid = grid_blocks((sh.n + 3) / 4);

@@ -82,6 +82,7 @@ struct Shape {
   const void* vec_b;
   int32_t all_pairs;  // 1: every evaluated pair is proposed (ablation), 0: nearest partners only
   const float* norms = nullptr;  // squared norm per node, where the metric needs it (cosine)
+  int32_t segments = 1;  // > 1: the list is k / 32 segments, object v lives in segment v % segments
   // slots of the proposal array: per appearance in a NEW list two results (all pairs: one per
   // possible partner, 2 * 2p - 1), in an OLD list one (all pairs: 2p); at most 2np appearances each
   __host__ __device__ int64_t slots_new_per_appearance() const {
@@ -126,6 +127,10 @@ hipError_t launch_update(const Shape& sh, const DevState& ds, hipStream_t st);
 hipError_t launch_init_random_wide(const Shape& sh, const DevState& ds, uint64_t seed,
                                    hipStream_t st);
 hipError_t launch_update_wide(const Shape& sh, const DevState& ds, hipStream_t st);
+// segmented lists (sh.segments > 1); the launchers above forward to these as well
+hipError_t launch_init_random_segmented(const Shape& sh, const DevState& ds, uint64_t seed,
+                                        hipStream_t st);
+hipError_t launch_update_segmented(const Shape& sh, const DevState& ds, hipStream_t st);
 hipError_t launch_get_graph(const Shape& sh, const DevState& ds, int32_t* ids, void* dist,
                             uint8_t* isnew, int32_t id_offset, hipStream_t st);
 hipError_t launch_set_graph(const Shape& sh, const DevState& ds, const int32_t* ids,

@@ -459,3 +459,67 @@ def test_two_contexts_on_two_streams_do_not_disturb_each_other():
     assert torch.equal(gb[0], ref_b[0]) and torch.equal(gb[1], ref_b[1])
     for c in (ca, cb, ref_a[2], ref_b[2]):
         c.close()
+
+
+# ---- segmented lists (Sec. 4.3, "Multiple Spinlocks") ---------------------------------------
+SEGMENTED_CASES = {
+    # name: (generator, metric, k, p, iters, join path)
+    "seg_k64_uniform": (lambda: W.uniform_f32(2000, 12, seed=1091), og.L2SQ_F32, 64, 24, 5, "valu"),
+    "seg_k128_sift_mfma": (lambda: W.sift_like_f32(1800, 128, seed=1092, n_comp=8),
+                           og.L2SQ_F32, 128, 32, 4, "mfma"),
+    "seg_k96_u8": (lambda: W.sift_like_u8(1500, 64, seed=1093, n_comp=6), og.L2SQ_U8, 96, 20, 4,
+                   "mfma_direct"),
+    "seg_k64_angular_p40": (lambda: W.deep_like_f32(1300, 24, seed=1094, n_comp=8),
+                            og.ANGULAR_F32, 64, 40, 4, "valu"),
+    # every residue class has 34 members only: the random init runs out of first attempts
+    "seg_k128_tiny_classes": (lambda: W.uniform_f32(136, 5, seed=1095), og.L2SQ_F32, 128, 16, 3,
+                              "valu"),
+    "seg_k32_is_plain": (lambda: W.uniform_f32(900, 8, seed=1096), og.L2SQ_F32, 32, 16, 3, "valu"),
+}
+
+
+@pytest.mark.parametrize("name", list(SEGMENTED_CASES))
+def test_segmented_lists_match_oracle_after_every_iteration(name):
+    amd = _amd()
+    gen, metric, k, p, iters, path = SEGMENTED_CASES[name]
+    x = gen()
+    join = {"mfma": amd.JOIN_MFMA, "mfma_direct": amd.JOIN_MFMA_DIRECT}.get(path, amd.JOIN_VALU)
+    ctx = amd.Gnnd(_dev(x), k, p, metric, SEED, join, list_mode=amd.LISTS_SEGMENTED)
+    ctx.init_random()
+    g = og.init_random(x, k, metric, SEED, segmented=True)
+    _assert_graph_equal(ctx, g, "segmented init")
+    m = k // 32
+    for it in range(1, iters + 1):
+        st = ctx.iterate()
+        ref = og.iterate(x, metric, g, p, SEED, it, segmented=True)
+        _assert_graph_equal(ctx, g, f"segmented iteration {it}")
+        for key in ("inserts", "dist_evals", "sum_new", "sum_old", "proposals"):
+            assert st[key] == ref[key], (it, key, st[key], ref[key])
+        assert st["dropped"] == 0
+    ids, _, _ = _graph_np(ctx)
+    assert all(np.bincount(row % m, minlength=m).tolist() == [32] * m for row in ids[::37])
+    # a build in one call ends in the same graph
+    ctx.build(iters, want_stats=False)
+    _assert_graph_equal(ctx, g, "segmented build")
+    if k == 32:  # one segment is the plain list
+        plain = amd.Gnnd(_dev(x), k, p, metric, SEED, join)
+        plain.build(iters, want_stats=False)
+        a, b = ctx.graph(), plain.graph()
+        assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+        plain.close()
+    ctx.close()
+
+
+def test_segmented_lists_refuse_what_the_paper_does_not_define():
+    amd = _amd()
+    x = _dev(W.uniform_f32(400, 6, seed=1097))
+    with pytest.raises(amd.GnndError):  # k must be a multiple of 32
+        amd.Gnnd(x, 48, 16, amd.L2SQ_F32, SEED, list_mode=amd.LISTS_SEGMENTED)
+    with pytest.raises(amd.GnndError):  # classes of fewer than 34 members
+        amd.Gnnd(x[:100].contiguous(), 96, 16, amd.L2SQ_F32, SEED, list_mode=amd.LISTS_SEGMENTED)
+    ctx = amd.Gnnd(x, 64, 16, amd.L2SQ_F32, SEED, list_mode=amd.LISTS_SEGMENTED)
+    ctx.build(2, want_stats=False)
+    ids, dist, flags = ctx.graph(with_flags=True)
+    with pytest.raises(amd.GnndError):  # a loaded graph need not be segmented
+        ctx.set_graph(ids, dist, flags, 2)
+    ctx.close()
