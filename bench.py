@@ -64,6 +64,9 @@ def parse():
     ap.add_argument("--update", choices=["selective", "all-pairs"], default="selective",
                     help="all-pairs: the ablation variant that proposes every evaluated pair "
                          "(runs with the valu join; ~100 KB of workspace per node at p = 32)")
+    ap.add_argument("--lists", choices=["plain", "segmented"], default="plain",
+                    help="segmented: the k-NN list as k/32 segments of 32, object v in segment "
+                         "v %% (k/32) (the paper's multiple-spinlock layout; k = 64, 96, 128)")
     ap.add_argument("--cpu-sample-n", type=int, default=None,
                     help="rows of the oracle's timed sample (default 200000; 30000 at d = 960)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -120,10 +123,11 @@ def time_oracle(args, iters, n, threads):
     gen, metric, _, _ = float_workload(args, W, og)
     x = gen(n)
     t0 = time.perf_counter()
-    g = og.init_random(x, args.k, metric, W.ALGO_SEED)
+    seg = args.lists == "segmented"
+    g = og.init_random(x, args.k, metric, W.ALGO_SEED, segmented=seg)
     evals = 0
     for it in range(1, iters + 1):
-        evals += og.iterate(x, metric, g, args.p, W.ALGO_SEED, it)["dist_evals"]
+        evals += og.iterate(x, metric, g, args.p, W.ALGO_SEED, it, segmented=seg)["dist_evals"]
     dt = time.perf_counter() - t0
     return evals, dt
 
@@ -241,7 +245,8 @@ def main():
     ql = q.long()
 
     update_mode = amd.UPDATE_ALL_PAIRS if args.update == "all-pairs" else amd.UPDATE_SELECTIVE
-    ctx = amd.Gnnd(xd, args.k, args.p, metric, seed, join_path, update_mode)
+    list_mode = amd.LISTS_SEGMENTED if args.lists == "segmented" else amd.LISTS_PLAIN
+    ctx = amd.Gnnd(xd, args.k, args.p, metric, seed, join_path, update_mode, list_mode)
 
     # calibration build (untimed): recall and per-stage times after every iteration
     ctx.init_random()
@@ -305,9 +310,10 @@ def main():
     avg_join_s = join_ms / T / 1e3
     hbm = {"bound": "hbm", "achieved": alg_bytes / avg_join_s / 1e9, "peak": PEAK_HBM_GBS,
            "unit": "GB/s", "traffic": None}
-    kernel_name = "k_join_mfma" if mfma else "k_join_valu"
+    kernel_name = "k_join_mfma" if mfma else ("k_join_long" if args.p > 32 else "k_join_valu")
     hbm["traffic"], hbm["traffic_raw"] = join_traffic(
-        (args.workload, args.n, args.d, args.k, args.p, kernel_name, args.update), T)
+        (args.workload, args.n, args.d, args.k, args.p, kernel_name, args.update), T) \
+        if args.lists == "plain" else (None, None)
     hbm["frac"] = hbm["achieved"] / hbm["peak"]
     if mfma:
         ops = total_evals / T * args.d * 2
@@ -338,6 +344,7 @@ def main():
         "config": {"workload": f"{shape_name} n={args.n} d={args.d} f32, k={args.k} "
                                f"p={args.p}, {metric_name}, random init + {T} iterations",
                    "join_path": "mfma_i8" if mfma else "valu", "update": args.update,
+                   "lists": args.lists,
                    "eval_nodes": args.eval_nodes},
         "reached_target": reached, "iterations": T, "recall_at_10": trace[T - 1]["recall_at_10"],
         "best_recall_at_10": best,
@@ -354,7 +361,7 @@ def main():
         # one fused multiply-add per dimension and pair), same T, as an extra figure
         ctx.close()
         del ctx
-        vctx = amd.Gnnd(xd, args.k, args.p, metric, seed, amd.JOIN_VALU, update_mode)
+        vctx = amd.Gnnd(xd, args.k, args.p, metric, seed, amd.JOIN_VALU, update_mode, list_mode)
         v_s, v_stage, v_rec = timed_builds(vctx, min(args.steps, 3), 1)
         v_bytes = vectors * (args.d * 4 + 4)
         v_join_s = v_stage["join"] / T / 1e3

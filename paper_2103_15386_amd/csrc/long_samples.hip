@@ -192,46 +192,89 @@ __global__ __launch_bounds__(kLB) void k_join_long(
       const int row0 = 64 * rb;                                   // index into ids[]
       const int col0 = new_cols ? 64 * cb : kMaxList + 64 * (cb - 2);
       const bool diagonal = new_cols && cb == rb;
+      // sub-blocks of 16 rows / 16 columns beyond the lists' ends are switched off (uniform)
+      const int rows_here = nn - 64 * rb < 64 ? nn - 64 * rb : 64;
+      const int cols_total = new_cols ? nn - 64 * cb : no - 64 * (cb - 2);
+      const int cols_here = cols_total < 64 ? cols_total : 64;
+      const int RB = (rows_here + 15) >> 4, CB = (cols_here + 15) >> 4;
       ACC acc[4][4];
 #pragma unroll
       for (int r = 0; r < 4; ++r)
 #pragma unroll
         for (int c = 0; c < 4; ++c) acc[r][c] = 0;
       for (int d0 = 0; d0 < d; d0 += kLC) {
-        // stage 64 row vectors and 64 column vectors: 16 threads per vector, 16 vectors per pass
+        // stage the row vectors and the column vectors: 16 threads per vector, 16 vectors per pass
         const int part = tid & 15;
 #pragma unroll
         for (int pass = 0; pass < 4; ++pass) {
           const int r = pass * 16 + (tid >> 4);
-          const int32_t idr = ids[row0 + r], idc = ids[col0 + r];
-          stage_long<ACC>(rows_t + r * kLLD, idr >= 0 ? vs.row<T>((uint32_t)idr) : nullptr, d, d0,
-                          part);
-          stage_long<ACC>(cols_t + r * kLLD, idc >= 0 ? vs.row<T>((uint32_t)idc) : nullptr, d, d0,
-                          part);
+          if (pass < RB) {
+            const int32_t idr = ids[row0 + r];
+            stage_long<ACC>(rows_t + r * kLLD, idr >= 0 ? vs.row<T>((uint32_t)idr) : nullptr, d,
+                            d0, part);
+          }
+          if (pass < CB) {
+            const int32_t idc = ids[col0 + r];
+            stage_long<ACC>(cols_t + r * kLLD, idc >= 0 ? vs.row<T>((uint32_t)idc) : nullptr, d,
+                            d0, part);
+          }
         }
         __syncthreads();
         const int width = (d - d0) < kLC ? (d - d0) : kLC;
-        for (int j = 0; j < width; ++j) {
-          ACC a[4], b[4];
+        const int nsub = (width + 15) >> 4;
+        for (int sub = 0; sub < nsub; ++sub) {
+          // 16 dimensions at a time; dimensions past the vectors' end are staged as zeros,
+          // and a pair of zeros leaves every metric's running sum as it is
+          ACC a[4][16];
 #pragma unroll
-          for (int r = 0; r < 4; ++r) a[r] = rows_t[(ty + 16 * r) * kLLD + j];
+          for (int r = 0; r < 4; ++r) {
+            if (r < RB) {
+              const ACC* src = rows_t + (ty + 16 * r) * kLLD + sub * 16;
 #pragma unroll
-          for (int c = 0; c < 4; ++c) b[c] = cols_t[(tx + 16 * c) * kLLD + j];
+              for (int q = 0; q < 4; ++q) {
+                const int4 w = *reinterpret_cast<const int4*>(src + q * 4);
+                a[r][q * 4 + 0] = __builtin_bit_cast(ACC, w.x);
+                a[r][q * 4 + 1] = __builtin_bit_cast(ACC, w.y);
+                a[r][q * 4 + 2] = __builtin_bit_cast(ACC, w.z);
+                a[r][q * 4 + 3] = __builtin_bit_cast(ACC, w.w);
+              }
+            }
+          }
 #pragma unroll
-          for (int r = 0; r < 4; ++r)
+          for (int c = 0; c < 4; ++c) {
+            if (c < CB) {
+              const ACC* src = cols_t + (tx + 16 * c) * kLLD + sub * 16;
+              ACC b[16];
 #pragma unroll
-            for (int c = 0; c < 4; ++c) TR::step(a[r], b[c], acc[r][c]);
+              for (int q = 0; q < 4; ++q) {
+                const int4 w = *reinterpret_cast<const int4*>(src + q * 4);
+                b[q * 4 + 0] = __builtin_bit_cast(ACC, w.x);
+                b[q * 4 + 1] = __builtin_bit_cast(ACC, w.y);
+                b[q * 4 + 2] = __builtin_bit_cast(ACC, w.z);
+                b[q * 4 + 3] = __builtin_bit_cast(ACC, w.w);
+              }
+#pragma unroll
+              for (int r = 0; r < 4; ++r) {
+                if (r < RB) {
+#pragma unroll
+                  for (int j = 0; j < 16; ++j) TR::step(a[r][j], b[j], acc[r][c]);
+                }
+              }
+            }
+          }
         }
         __syncthreads();
       }
       // nearest partners from the register tile
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
+        if (r >= RB) continue;
         const int R = row0 + ty + 16 * r;
         const int32_t idr = ids[R];
         uint64_t along = kKeyMax;  // nearest column object of row R in this block
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
+          if (c >= CB) continue;
           const int C = col0 + tx + 16 * c;
           const int32_t idc = ids[C];
           bool ok = idr >= 0 && idc >= 0;
