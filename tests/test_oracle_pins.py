@@ -942,14 +942,24 @@ def test_segmented_init_draws_32_of_every_class_and_reduces_to_the_plain_init():
             assert np.bincount(g.ids[s] % m, minlength=m).tolist() == [32] * m
             for v, dd in zip(g.ids[s], g.dist[s]):
                 assert dd == og.distance(x, og.L2SQ_F32, s, int(v))
-        # the draws are the documented ones: slot 32 r + j, first attempt, when nothing clashes
-        s = 11
-        for r in range(m):
-            members = (500 - r + m - 1) // m
-            first = [og.bounded(og.hash5(5, og.TAG_INIT, s, 32 * r + j, 0), members) * m + r
-                     for j in range(32)]
-            if len(set(first)) == 32 and s not in first:
-                assert sorted(first) == sorted(v for v in g.ids[s].tolist() if v % m == r)
+        # the draws are the documented ones: slot 32 r + j takes the first member number of
+        # hash(seed, INIT, s, 32 r + j, attempt), attempt = 0, 1, ..., that is neither s nor
+        # taken by an earlier slot of the segment (the rule written out here in Python)
+        for s in (0, 11, 250, 499):
+            for r in range(m):
+                members = (500 - r + m - 1) // m
+                own = s // m if s % m == r else -1
+                taken = []
+                for j in range(32):
+                    for attempt in range(256):
+                        c = og.bounded(og.hash5(5, og.TAG_INIT, s, 32 * r + j, attempt), members)
+                        if c != own and c not in taken:
+                            break
+                    else:
+                        raise AssertionError("256 attempts exhausted on a class of 125+ members")
+                    taken.append(c)
+                want = sorted(c * m + r for c in taken)
+                assert want == sorted(v for v in g.ids[s].tolist() if v % m == r), (k, s, r)
     # tiny classes: with n = 34 m every class has 34 members, one of them possibly s itself
     tiny = og.init_random(W.uniform_f32(68, 3, seed=92), 64, og.L2SQ_F32, 6, segmented=True)
     assert all(np.bincount(tiny.ids[s] % 2, minlength=2).tolist() == [32, 32] for s in range(68))
