@@ -66,6 +66,12 @@ __device__ inline uint64_t entry_key(uint64_t e) { return e >> 2; }  // (distanc
 
 // ---- wavefront helpers (one value per lane, 64 lanes) --------------------
 __device__ inline int lane_id() { return (int)(threadIdx.x & (kWave - 1)); }
+// Number of this wavefront inside its workgroup, as a scalar: every lane holds the same
+// value, and saying so keeps what is derived from it (row numbers, base addresses) in
+// scalar registers.
+__device__ inline int wave_id() {
+  return __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+}
 __device__ inline uint64_t lanes_below(int lane) { return (1ull << lane) - 1ull; }
 
 // A launch may not span 2^32 threads in one grid dimension (16 M workgroups of

@@ -11,7 +11,7 @@ constexpr int kBlock = 256;
 constexpr int kWavesPerBlock = kBlock / kWave;
 
 __device__ inline int64_t wave_global_index() {
-  return block_linear() * kWavesPerBlock + (threadIdx.x >> 6);
+  return block_linear() * kWavesPerBlock + wave_id();
 }
 static inline dim3 blocks_for_waves(int64_t waves) {
   return grid_blocks((waves + kWavesPerBlock - 1) / kWavesPerBlock);
@@ -37,7 +37,7 @@ __global__ __launch_bounds__(kBlock) void k_init_random(VecSrc vs, int64_t n, in
   const int lane = lane_id();
   uint32_t id = draw_distinct(base_hash, (uint32_t)s, k, (uint32_t)n, 0u, (uint32_t)s, lane);
   const uint32_t code =
-      wave_distances<METRIC>(vs, (uint32_t)s, id, lane < k, tile[threadIdx.x >> 6], lane);
+      wave_distances<METRIC>(vs, (uint32_t)s, id, lane < k, tile[wave_id()], lane);
   uint64_t e = lane < k ? make_entry(code, id, 1u) : kKeyMax;
   e = wave_sort(e, lane);
   if (lane < k) G[s * k + lane] = e;
@@ -275,7 +275,7 @@ __global__ __launch_bounds__(kBlock) void k_merge_init(VecSrc vs, int64_t n, Mer
   const int src = lane - keep;
   const uint32_t did = __shfl(draw, src < 0 ? 0 : src, kWave);
   const uint32_t code = wave_distances<METRIC>(vs, (uint32_t)s, did, lane >= keep && lane < k,
-                                               tile[threadIdx.x >> 6], lane);
+                                               tile[wave_id()], lane);
   uint64_t e = kKeyMax;
   if (lane < keep) e = make_entry(code_in, id_in, 0u);
   else if (lane < k) e = make_entry(code, did, 1u);
@@ -326,7 +326,7 @@ __global__ __launch_bounds__(kBlock) void k_exact_knn(const void* vec, int64_t n
   using T = typename D::elem;
   __shared__ uint64_t part[kWavesPerBlock][kWave];
   const int lane = lane_id();
-  const int wave = threadIdx.x >> 6;
+  const int wave = wave_id();
   const int64_t q = blockIdx.x;
   const uint32_t s = (uint32_t)queries[q];
   const T* base = reinterpret_cast<const T*>(vec);
@@ -377,7 +377,7 @@ constexpr int kScanPerBlock = kBlock * kScanPerThread;
 __device__ inline uint64_t block_exclusive_scan(uint64_t v, uint64_t* total) {
   __shared__ uint64_t wsum[kWavesPerBlock];
   const int lane = lane_id();
-  const int wave = threadIdx.x >> 6;
+  const int wave = wave_id();
   uint64_t inc = v;
 #pragma unroll
   for (int off = 1; off < kWave; off <<= 1) {
@@ -474,8 +474,8 @@ hipError_t launch_zero_u32(uint32_t* p, size_t count, hipStream_t st) {
 __global__ __launch_bounds__(kBlock) void k_row_norms(VecSrc vs, int64_t n, float* norms) {
   __shared__ float tile[kWavesPerBlock][64 * kEvalStride];
   const int lane = lane_id();
-  float* my = tile[threadIdx.x >> 6];
-  const int64_t row0 = (block_linear() * kWavesPerBlock + (threadIdx.x >> 6)) * 64;
+  float* my = tile[wave_id()];
+  const int64_t row0 = (block_linear() * kWavesPerBlock + wave_id()) * 64;
   if (row0 >= n) return;
   const int d = vs.d;
   const int part = lane & 7, rsel = lane >> 3;

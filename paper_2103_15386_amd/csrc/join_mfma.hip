@@ -35,7 +35,7 @@ __global__ __launch_bounds__(256) void k_pack_i8(const void* vec_a, const void* 
                                                  int64_t split, int64_t n, int d, int dpad,
                                                  int8_t* shadow, NodeMeta* meta, int* bad) {
   const int lane = lane_id();
-  const int64_t row = block_linear() * 4 + (threadIdx.x >> 6);
+  const int64_t row = block_linear() * 4 + wave_id();
   if (row >= n) return;
   const T* src = row < split ? reinterpret_cast<const T*>(vec_a) + row * d
                              : reinterpret_cast<const T*>(vec_b) + (row - split) * d;
@@ -67,7 +67,7 @@ __global__ __launch_bounds__(256) void k_pack_u8_wide(const uint8_t* vec_a, cons
   const int lane = lane_id();
   const int C = dpad >> 4, per_wave = kWave / C;
   const int grp = lane / C, sub = lane - grp * C;
-  const int64_t row = (block_linear() * 4 + (threadIdx.x >> 6)) * per_wave + grp;
+  const int64_t row = (block_linear() * 4 + wave_id()) * per_wave + grp;
   const bool on = grp < per_wave && row < n;
   int32_t part = 0;
   if (on) {
@@ -143,7 +143,7 @@ __global__ __launch_bounds__(256) void k_init_random_i8(const int8_t* __restrict
                                                         NodeMeta* meta, int dpad, int64_t n, int k,
                                                         uint64_t base_hash, uint64_t* G) {
   const int lane = lane_id();
-  const int64_t s = block_linear() * 4 + (threadIdx.x >> 6);
+  const int64_t s = block_linear() * 4 + wave_id();
   if (s >= n) return;
   // the list for one id per lane, ascending
   auto list_of = [&](uint32_t id) {
@@ -176,7 +176,7 @@ __global__ __launch_bounds__(256) void k_merge_init_i8(const int8_t* __restrict_
                                                        const int32_t* ids2, const void* dist2,
                                                        uint64_t* G, uint64_t* aside) {
   const int lane = lane_id();
-  const int64_t s = block_linear() * 4 + (threadIdx.x >> 6);
+  const int64_t s = block_linear() * 4 + wave_id();
   if (s >= n) return;
   const int64_t n1 = mi.n1;
   const bool first = s < n1;
@@ -329,7 +329,7 @@ __attribute__((amdgpu_waves_per_eu(STAGED ? 2 : 3, STAGED ? 2 : 3))) void k_join
   uint64_t* const st_gbase = st_region + kStageBuckets;
   uint32_t* const st_cnt = reinterpret_cast<uint32_t*>(st_gbase + kStageBuckets);
   uint32_t* const st_fill = st_cnt + kStageBuckets;  // [0] results staged, [1] waves out of nodes
-  const int wave = threadIdx.x >> 6, lane = lane_id(), half = lane >> 5, col = lane & 31;
+  const int wave = wave_id(), lane = lane_id(), half = lane >> 5, col = lane & 31;
   const int64_t W = (int64_t)gridDim.x * WAVES;
   int64_t s = (int64_t)blockIdx.x * WAVES + wave;
   if (!STAGED && s >= n) return;

@@ -87,7 +87,7 @@ __global__ __launch_bounds__(kLB) void k_rev_select_long(
     int32_t* sold, int32_t* cnew, int32_t* cold, const uint64_t* roff_new,
     const uint64_t* roff_old, const int32_t* csr_new, const int32_t* csr_old, uint32_t* capn,
     uint32_t* capo, uint32_t per_new, uint32_t per_old, uint64_t* counters) {
-  const int64_t v = block_linear() * kWavesPerLB + (threadIdx.x >> 6);
+  const int64_t v = block_linear() * kWavesPerLB + wave_id();
   if (v >= n) return;
   const int lane = lane_id();
   const int L = 2 * p;

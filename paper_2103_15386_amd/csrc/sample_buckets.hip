@@ -121,7 +121,7 @@ __global__ __launch_bounds__(kSB) void k_fwd_count(int64_t n, int k, int p, Buck
   __shared__ uint32_t hist[2 * kMaxBuckets];
   for (int i = threadIdx.x; i < 2 * g.nb; i += kSB) hist[i] = 0;
   __syncthreads();
-  const int lane = lane_id(), wave = threadIdx.x >> 6;
+  const int lane = lane_id(), wave = wave_id();
   const int64_t row0 = (int64_t)blockIdx.x * g.rows_per_wg;
   const int64_t row1 = row0 + g.rows_per_wg < n ? row0 + g.rows_per_wg : n;
   constexpr int kRowsAtOnce = 4;  // rows in flight per wavefront
@@ -165,7 +165,7 @@ __global__ __launch_bounds__(kSB) void k_fwd_count(int64_t n, int k, int p, Buck
 // order inside a bucket no longer depends on timing.
 __global__ __launch_bounds__(kSB) void k_wg_scan(int W, int rows, uint32_t* wg_hist,
                                                  uint32_t* bcnt) {
-  const int c = blockIdx.x * (kSB / kWave) + (threadIdx.x >> 6);
+  const int c = blockIdx.x * (kSB / kWave) + wave_id();
   if (c >= rows) return;
   const int lane = lane_id();
   uint32_t* row = wg_hist + (size_t)c * W;

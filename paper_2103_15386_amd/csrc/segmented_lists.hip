@@ -21,7 +21,7 @@ constexpr int kSeg = 32;        // entries per segment
 constexpr int kMaxSegments = 4; // k <= 128
 
 __device__ inline int64_t seg_wave_index() {
-  return block_linear() * kWavesPerSGB + (threadIdx.x >> 6);
+  return block_linear() * kWavesPerSGB + wave_id();
 }
 inline dim3 seg_blocks(int64_t waves) {
   return grid_blocks((waves + kWavesPerSGB - 1) / kWavesPerSGB);
@@ -106,7 +106,7 @@ __global__ __launch_bounds__(kSGB) void k_init_random_segmented(VecSrc vs, int64
     e[reg] = kKeyMax;
     if (reg == 0 || k > kWave) {  // uniform
       const uint32_t code =
-          wave_distances<METRIC>(vs, (uint32_t)s, id, on[reg], tile[threadIdx.x >> 6], lane);
+          wave_distances<METRIC>(vs, (uint32_t)s, id, on[reg], tile[wave_id()], lane);
       if (on[reg]) e[reg] = make_entry(code, id, 1u);
     }
   }

@@ -16,7 +16,7 @@ constexpr int kWB = 256;
 constexpr int kWavesPerWB = kWB / kWave;
 
 __device__ inline int64_t wide_wave_index() {
-  return block_linear() * kWavesPerWB + (threadIdx.x >> 6);
+  return block_linear() * kWavesPerWB + wave_id();
 }
 inline dim3 wide_blocks(int64_t waves) {
   return grid_blocks((waves + kWavesPerWB - 1) / kWavesPerWB);
@@ -112,7 +112,7 @@ __global__ __launch_bounds__(kWB) void k_init_random_wide(VecSrc vs, int64_t n, 
   const int lane = lane_id();
   uint32_t id0, id1;
   draw_distinct_wide(base_hash, (uint32_t)s, k, (uint32_t)n, 0u, (uint32_t)s, lane, id0, id1);
-  uint32_t* my_tile = tile[threadIdx.x >> 6];
+  uint32_t* my_tile = tile[wave_id()];
   const uint32_t c0 = wave_distances<METRIC>(vs, (uint32_t)s, id0, true, my_tile, lane);
   const uint32_t c1 = wave_distances<METRIC>(vs, (uint32_t)s, id1, lane + kWave < k, my_tile, lane);
   uint64_t lo = make_entry(c0, id0, 1u);
@@ -199,7 +199,7 @@ __global__ __launch_bounds__(kWB) void k_merge_init_wide(VecSrc vs, int64_t n, M
                                       0xffffffffu, lane);
   uint64_t lo = lane < keep ? in0 : kKeyMax;
   const uint32_t cd =
-      wave_distances<METRIC>(vs, (uint32_t)s, draw, lane < fill, tile[threadIdx.x >> 6], lane);
+      wave_distances<METRIC>(vs, (uint32_t)s, draw, lane < fill, tile[wave_id()], lane);
   uint64_t hi = lane < fill ? make_entry(cd, draw, 1u) : kKeyMax;
   sort128(lo, hi, lane);
   G[s * k + lane] = lo;
