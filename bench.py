@@ -60,7 +60,7 @@ def parse():
     ap.add_argument("--max-iters", type=int, default=12)
     ap.add_argument("--target", type=float, default=0.95)
     ap.add_argument("--eval-nodes", type=int, default=2000)
-    ap.add_argument("--join", choices=["auto", "valu", "mfma"], default="auto")
+    ap.add_argument("--join", choices=["auto", "valu", "mfma", "gram"], default="auto")
     ap.add_argument("--update", choices=["selective", "all-pairs"], default="selective",
                     help="all-pairs: the ablation variant that proposes every evaluated pair "
                          "(runs with the valu join; ~100 KB of workspace per node at p = 32)")
@@ -236,7 +236,8 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    join_path = {"auto": amd.JOIN_AUTO, "valu": amd.JOIN_VALU, "mfma": amd.JOIN_MFMA}[args.join]
+    join_path = {"auto": amd.JOIN_AUTO, "valu": amd.JOIN_VALU, "mfma": amd.JOIN_MFMA,
+                 "gram": amd.JOIN_GRAM}[args.join]
     seed = W.ALGO_SEED
 
     # ground truth for the recall evaluation: exhaustive search on sampled nodes
@@ -266,6 +267,7 @@ def main():
 
     stream = torch.cuda.current_stream(dev)
     mfma = ctx.join_path() == amd.JOIN_MFMA
+    gram = ctx.join_path() == amd.JOIN_GRAM
 
     def timed_builds(c, steps, warmup):
         """`steps` builds of T iterations on context c after `warmup` untimed ones: seconds
@@ -310,7 +312,8 @@ def main():
     avg_join_s = join_ms / T / 1e3
     hbm = {"bound": "hbm", "achieved": alg_bytes / avg_join_s / 1e9, "peak": PEAK_HBM_GBS,
            "unit": "GB/s", "traffic": None}
-    kernel_name = "k_join_mfma" if mfma else ("k_join_long" if args.p > 32 else "k_join_valu")
+    kernel_name = "k_join_mfma" if mfma else "k_join_gram" if gram else (
+        "k_join_long" if args.p > 32 else "k_join_valu")
     hbm["traffic"], hbm["traffic_raw"] = join_traffic(
         (args.workload, args.n, args.d, args.k, args.p, kernel_name, args.update), T) \
         if args.lists == "plain" else (None, None)
@@ -319,6 +322,10 @@ def main():
         ops = total_evals / T * args.d * 2
         other = {"bound": "mfma", "achieved": ops / avg_join_s / 1e12, "peak": PEAK_INT8_TOPS,
                  "unit": "TOP/s"}
+    elif gram:  # float32 matrix instructions: the same peak as the vector units'
+        ops = total_evals / T * args.d * 2
+        other = {"bound": "mfma", "achieved": ops / avg_join_s / 1e12, "peak": PEAK_FP32_TFLOPS,
+                 "unit": "TFLOP/s"}
     else:
         ops = total_evals / T * args.d * (2 if metric == amd.ANGULAR_F32 else 3)
         other = {"bound": "alu", "achieved": ops / avg_join_s / 1e12, "peak": PEAK_FP32_TFLOPS,
@@ -343,7 +350,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{shape_name} n={args.n} d={args.d} f32, k={args.k} "
                                f"p={args.p}, {metric_name}, random init + {T} iterations",
-                   "join_path": "mfma_i8" if mfma else "valu", "update": args.update,
+                   "join_path": "mfma_i8" if mfma else "gram_f32" if gram else "valu",
+                   "update": args.update,
                    "lists": args.lists,
                    "eval_nodes": args.eval_nodes},
         "reached_target": reached, "iterations": T, "recall_at_10": trace[T - 1]["recall_at_10"],
@@ -357,20 +365,23 @@ def main():
         "roofline": roof,
     }
     if mfma and not args.no_valu_line:
-        # the same workload through the general float32 join (the paper's arithmetic:
-        # one fused multiply-add per dimension and pair), same T, as an extra figure
+        # the same workload through the two float32 joins, same T, as extra figures: the
+        # paper's arithmetic (one fused multiply-add per dimension and pair) for every pair,
+        # and the matrix-core form that spends it on the possible nearest partners only
         ctx.close()
         del ctx
-        vctx = amd.Gnnd(xd, args.k, args.p, metric, seed, amd.JOIN_VALU, update_mode, list_mode)
-        v_s, v_stage, v_rec = timed_builds(vctx, min(args.steps, 3), 1)
-        v_bytes = vectors * (args.d * 4 + 4)
-        v_join_s = v_stage["join"] / T / 1e3
-        out["f32_valu_join"] = {
-            "build_s": v_s, "stage_ms": v_stage, "stage_records": v_rec, "dtype": "f32",
-            "kernel": "k_join_valu", "avg_launch_ms": v_join_s * 1e3,
-            "hbm_frac": v_bytes / v_join_s / 1e9 / PEAK_HBM_GBS,
-            "alu_frac": total_evals / T * args.d * 3 / v_join_s / 1e12 / PEAK_FP32_TFLOPS}
-        vctx.close()
+        for key, path, kernel, per_dim in (("f32_gram_join", amd.JOIN_GRAM, "k_join_gram", 2),
+                                           ("f32_valu_join", amd.JOIN_VALU, "k_join_valu", 3)):
+            vctx = amd.Gnnd(xd, args.k, args.p, metric, seed, path, update_mode, list_mode)
+            v_s, v_stage, v_rec = timed_builds(vctx, min(args.steps, 3), 1)
+            v_bytes = vectors * (args.d * 4 + 4)
+            v_join_s = v_stage["join"] / T / 1e3
+            out[key] = {
+                "build_s": v_s, "stage_ms": v_stage, "stage_records": v_rec, "dtype": "f32",
+                "kernel": kernel, "avg_launch_ms": v_join_s * 1e3,
+                "hbm_frac": v_bytes / v_join_s / 1e9 / PEAK_HBM_GBS,
+                "alu_frac": total_evals / T * args.d * per_dim / v_join_s / 1e12 / PEAK_FP32_TFLOPS}
+            vctx.close()
     if not args.no_cpu_baseline:
         try:
             out["cpu_baseline"] = cpu_baseline(args, T)

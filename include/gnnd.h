@@ -66,11 +66,16 @@ enum {
   GNND_JOIN_AUTO = 0, /* library picks                                               */
   GNND_JOIN_VALU = 1, /* per-pair float32 fused accumulation in dimension order      */
   GNND_JOIN_MFMA = 2, /* Gram-block form on the matrix cores (exact for uint8 data)  */
-  GNND_JOIN_MFMA_DIRECT = 3 /* the same, every nearest-object result handed to its
+  GNND_JOIN_MFMA_DIRECT = 3, /* the same, every nearest-object result handed to its
                                destination list by itself (one device-wide atomic each);
                                GNND_JOIN_MFMA / AUTO collect the results per workgroup and
                                bucket of destinations first where the workspace for that is
                                affordable (n <= 2^20) and use this form beyond.  Same lists */
+  GNND_JOIN_GRAM = 4  /* float32 vectors of any dimension, squared L2 / angular / cosine,
+                         p <= 32: inner products on the matrix cores pick, per sample, the
+                         few partners that can be its nearest one; their distances are then
+                         accumulated as in GNND_JOIN_VALU.  Same results as GNND_JOIN_VALU,
+                         bit for bit                                                      */
 };
 
 /* Which cross-matching results go to the list update. */
@@ -144,10 +149,11 @@ void gnnd_destroy(gnnd_ctx* ctx);
 const char* gnnd_last_error(const gnnd_ctx* ctx);
 
 /* Which evaluation of the cross-matching distances (Sec. 4.2) this context
- * uses: GNND_JOIN_VALU or GNND_JOIN_MFMA (GNND_JOIN_AUTO resolved at creation:
- * the matrix-core form is taken when it is exact - squared L2, d <= 128, uint8
- * vectors or float32 vectors holding only integers 0..255).  Negative on a
- * NULL context. */
+ * uses: GNND_JOIN_VALU, GNND_JOIN_MFMA or GNND_JOIN_GRAM (GNND_JOIN_AUTO resolved
+ * at creation: the int8 matrix-core form is taken when it is exact - squared
+ * L2, d <= 128, p <= 32, uint8 vectors or float32 vectors holding only integers
+ * 0..255; other float32 vectors of up to 128 dimensions take GNND_JOIN_GRAM
+ * where it applies; GNND_JOIN_VALU otherwise).  Negative on a NULL context. */
 int gnnd_join_path(const gnnd_ctx* ctx);
 
 /* Stage timing without synchronising inside the loop.  gnnd_set_profiling(ctx,
@@ -316,10 +322,10 @@ int gnnd_build_sharded_files(const gnnd_params* prm, const char* vectors_path, i
  *    that device at this point, and the device holds it until the process
  *    ends): make one call per device before capturing or entering a loop that
  *    must not touch the allocator.
- *  - GNND_JOIN_AUTO takes the matrix-core join for uint8 vectors (d <= 128) and
- *    the general join for float32 vectors (deciding that float data are byte
- *    valued would need a synchronisation); GNND_JOIN_MFMA with float32 vectors
- *    is refused.
+ *  - GNND_JOIN_AUTO takes the int8 matrix-core join for uint8 vectors (d <= 128)
+ *    and never for float32 vectors (deciding that float data are byte valued
+ *    would need a synchronisation: they take GNND_JOIN_GRAM or GNND_JOIN_VALU);
+ *    GNND_JOIN_MFMA with float32 vectors is refused.
  *  - All calls on one GPU share that GPU's array: two calls that overlap in time
  *    on one GPU (different streams or threads) race.  Each call clears what it
  *    needs cleared; nothing is kept from one call to the next. */

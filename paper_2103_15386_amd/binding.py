@@ -8,7 +8,7 @@ import numpy as np
 import torch
 
 L2SQ_F32, ANGULAR_F32, L2SQ_U8, CHI2_F32, COSINE_F32 = 0, 1, 2, 3, 4
-JOIN_AUTO, JOIN_VALU, JOIN_MFMA, JOIN_MFMA_DIRECT = 0, 1, 2, 3
+JOIN_AUTO, JOIN_VALU, JOIN_MFMA, JOIN_MFMA_DIRECT, JOIN_GRAM = 0, 1, 2, 3, 4
 UPDATE_SELECTIVE, UPDATE_ALL_PAIRS = 0, 1
 LISTS_PLAIN, LISTS_SEGMENTED = 0, 1
 OK, EINVAL, ENOSPC, ESTATE, EHIP, EIO = 0, -1, -2, -3, -4, -5
@@ -170,9 +170,11 @@ def make_params(n, d, k, p, metric, seed=42, join_path=JOIN_AUTO, stream=0, work
     return prm
 
 
-def workspace_bytes(n, d, k, p, metric, update_mode=UPDATE_SELECTIVE, list_mode=LISTS_PLAIN):
+def workspace_bytes(n, d, k, p, metric, update_mode=UPDATE_SELECTIVE, list_mode=LISTS_PLAIN,
+                    join_path=JOIN_AUTO):
     """Bytes of device scratch a context with these parameters needs (0 = invalid)."""
-    prm = make_params(n, d, k, p, metric, update_mode=update_mode, list_mode=list_mode)
+    prm = make_params(n, d, k, p, metric, join_path=join_path, update_mode=update_mode,
+                      list_mode=list_mode)
     return int(load_library().gnnd_workspace_bytes(C.byref(prm)))
 
 
@@ -186,7 +188,7 @@ class Gnnd:
         self.n, self.d = vectors.shape
         self.k, self.p, self.metric, self.seed = k, p, metric, seed
         self.update_mode = update_mode
-        need = workspace_bytes(self.n, self.d, k, p, metric, update_mode, list_mode)
+        need = workspace_bytes(self.n, self.d, k, p, metric, update_mode, list_mode, join_path)
         if need == 0:
             prm = make_params(self.n, self.d, k, p, metric, seed, join_path,
                               update_mode=update_mode, list_mode=list_mode)
@@ -345,7 +347,7 @@ def gnnd_merge(vec1, vec2, ids1, dist1, ids2, dist2, k, p, metric=L2SQ_F32, seed
     n = n1 + n2
     base2 = n1 if base2 is None else base2
     id_space = max(base1 + n1, base2 + n2) if id_space is None else id_space
-    need = workspace_bytes(n, d, k, p, metric)
+    need = workspace_bytes(n, d, k, p, metric, join_path=join_path)
     dev = vec1.device
     ws = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
     prm = make_params(n, d, k, p, metric, seed, join_path, _stream_ptr(dev), ws)
@@ -378,7 +380,8 @@ def gnnd_append(vec1, ids1, dist1, vec2, k, p, metric=L2SQ_F32, seed=42, build_i
     n2 = vec2.shape[0]
     n = n1 + n2
     dev = vec1.device
-    ws = torch.empty(max(workspace_bytes(n, d, k, p, metric), 256), dtype=torch.uint8, device=dev)
+    ws = torch.empty(max(workspace_bytes(n, d, k, p, metric, join_path=join_path), 256),
+                     dtype=torch.uint8, device=dev)
     prm = make_params(n, d, k, p, metric, seed, join_path, _stream_ptr(dev), ws)
     ids = torch.empty((n, k), dtype=torch.int32, device=dev)
     dist = torch.empty((n, k), dtype=dt, device=dev)

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgnnd_hip.so")
 SOURCES = ["graph_kernels.hip", "wide_lists.hip", "long_samples.hip", "segmented_lists.hip", "join_valu.hip",
-           "join_mfma.hip", "sample_buckets.hip", "gnnd_api.hip"]
+           "join_mfma.hip", "join_gram.hip", "sample_buckets.hip", "gnnd_api.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-result",
          # packed FP32 instructions are kept off on purpose

@@ -56,15 +56,20 @@ const char* check_params(const gnnd_params* q) {
   if (q->n <= q->k) return "n must exceed k";
   if (q->n > ((int64_t)1 << 27)) return "n must be <= 2^27";
   if (q->n * (int64_t)q->p >= ((int64_t)1 << 32)) return "n * p must be below 2^32";
-  if (q->join_path < GNND_JOIN_AUTO || q->join_path > GNND_JOIN_MFMA_DIRECT)
-    return "unknown join_path";
+  if (q->join_path < GNND_JOIN_AUTO || q->join_path > GNND_JOIN_GRAM) return "unknown join_path";
   if (q->update_mode != GNND_UPDATE_SELECTIVE && q->update_mode != GNND_UPDATE_ALL_PAIRS)
     return "unknown update_mode";
   if (q->update_mode == GNND_UPDATE_ALL_PAIRS &&
-      (q->join_path == GNND_JOIN_MFMA || q->join_path == GNND_JOIN_MFMA_DIRECT))
+      (q->join_path == GNND_JOIN_MFMA || q->join_path == GNND_JOIN_MFMA_DIRECT ||
+       q->join_path == GNND_JOIN_GRAM))
     return "GNND_UPDATE_ALL_PAIRS runs with GNND_JOIN_VALU (or GNND_JOIN_AUTO) only";
   if (q->update_mode == GNND_UPDATE_ALL_PAIRS && q->p > 32)
     return "GNND_UPDATE_ALL_PAIRS needs p <= 32";
+  if (q->join_path == GNND_JOIN_GRAM &&
+      (q->p > 32 || (q->metric != GNND_L2SQ_F32 && q->metric != GNND_ANGULAR_F32 &&
+                     q->metric != GNND_COSINE_F32)))
+    return "GNND_JOIN_GRAM needs float32 vectors, p <= 32 and the squared-L2, angular or cosine "
+           "metric";
   if (q->list_mode != GNND_LISTS_PLAIN && q->list_mode != GNND_LISTS_SEGMENTED)
     return "unknown list_mode";
   if (q->list_mode == GNND_LISTS_SEGMENTED) {
@@ -79,8 +84,25 @@ const char* check_params(const gnnd_params* q) {
 // The matrix-core join handles byte-valued data of up to 128 dimensions: uint8
 // vectors, or float32 vectors that turn out to hold only integers 0..255.
 bool mfma_possible(const gnnd_params* q) {
-  return q->join_path != GNND_JOIN_VALU && q->update_mode == GNND_UPDATE_SELECTIVE && q->d <= 128 &&
-         q->p <= 32 && (q->metric == GNND_L2SQ_U8 || q->metric == GNND_L2SQ_F32);
+  return q->join_path != GNND_JOIN_VALU && q->join_path != GNND_JOIN_GRAM &&
+         q->update_mode == GNND_UPDATE_SELECTIVE && q->d <= 128 && q->p <= 32 &&
+         (q->metric == GNND_L2SQ_U8 || q->metric == GNND_L2SQ_F32);
+}
+
+// The float32 matrix-core join (inner products by matrix instructions, canonical distances
+// for the results) takes any float32 data under the metrics that are functions of an inner
+// product and the norms.  Left to itself the library takes it up to 128 dimensions, where it
+// was measured about a tenth ahead of the general join (level with it on long vectors).
+constexpr int kGramAutoMaxDim = 128;
+bool gram_possible(const gnnd_params* q) {
+  return (q->join_path == GNND_JOIN_GRAM ||
+          (q->join_path == GNND_JOIN_AUTO && q->d <= kGramAutoMaxDim)) &&
+         q->update_mode == GNND_UPDATE_SELECTIVE && q->p <= 32 &&
+         (q->metric == GNND_L2SQ_F32 || q->metric == GNND_ANGULAR_F32 ||
+          q->metric == GNND_COSINE_F32);
+}
+bool needs_norms(const gnnd_params* q) {
+  return q->metric == GNND_COSINE_F32 || gram_possible(q);
 }
 
 // The matrix-core join stages its results per bucket of destinations (instead of handing
@@ -122,7 +144,7 @@ Layout make_layout(const gnnd_params* q, bool with_aside) {
   L.off_aside = take(with_aside ? n * (k / 2) * 8 : 0);
   const bool shadow = mfma_possible(q);
   L.off_shadow = take(shadow ? n * (size_t)((q->d + 31) & ~31) : 0);
-  L.off_norms = take(q->metric == GNND_COSINE_F32 ? n * 4 : 0);  // squared norms (cosine only)
+  L.off_norms = take(needs_norms(q) ? n * 4 : 0);  // squared norms
   L.off_flag = take(256);
   L.off_bkc = take(2 * 4096 * 4);
   L.off_bko = take(2 * 4097 * 8);
@@ -149,6 +171,7 @@ struct gnnd_ctx {
   bool has_graph;
   bool merge_mode;
   bool use_mfma;
+  bool use_gram;
   int* flag_dev;
   hipEvent_t ev[5];
   bool have_events;
@@ -231,7 +254,8 @@ int init_ctx(gnnd_ctx* c, const gnnd_params* prm, const Layout& L, const void* v
   if (e == hipSuccess)
     e = launch_zero_u32((uint32_t*)c->ds.counters, (size_t)kStripes * C_SLOTS * 2, c->stream);
   if (e != hipSuccess) return hip_fail(nullptr, e, "clearing workspace counters");
-  if (prm->metric == GNND_COSINE_F32) {  // the squared norms the cosine distance divides by
+  if (needs_norms(prm)) {  // the cosine distance divides by them, the float32 matrix-core
+                           // join turns inner products into distances with them
     float* norms = reinterpret_cast<float*>(static_cast<char*>(prm->workspace_dev) + L.off_norms);
     c->sh.norms = norms;
     e = launch_row_norms(c->sh, norms, c->stream);
@@ -252,6 +276,7 @@ int init_ctx(gnnd_ctx* c, const gnnd_params* prm, const Layout& L, const void* v
     if (e != hipSuccess) return hip_fail(nullptr, e, "packing vectors to int8");
     c->use_mfma = (bad == 0);
   }
+  c->use_gram = gram_possible(prm) && !c->use_mfma;
   if ((prm->join_path == GNND_JOIN_MFMA || prm->join_path == GNND_JOIN_MFMA_DIRECT) && !c->use_mfma)
     return fail(nullptr, GNND_EINVAL,
                 may_sync ? "GNND_JOIN_MFMA needs d <= 128, p <= 32 and uint8 vectors or float32 vectors "
@@ -347,7 +372,8 @@ int step_join(gnnd_ctx* c, hipEvent_t after_join = nullptr) {
   if (c->use_mfma) {
     e = launch_join_mfma(c->sh, c->ds, c->merge_mode, c->stream, after_join);
   } else {
-    e = launch_join(c->sh, c->ds, c->prm.join_path, c->merge_mode, c->stream);
+    e = c->use_gram ? launch_join_gram(c->sh, c->ds, c->merge_mode, c->stream)
+                    : launch_join(c->sh, c->ds, c->prm.join_path, c->merge_mode, c->stream);
     if (after_join) (void)hipEventRecord(after_join, c->stream);
   }
   if (e != hipSuccess) return hip_fail(c, e, "join kernel");
@@ -859,7 +885,7 @@ const char* gnnd_last_error(const gnnd_ctx* c) { return c ? c->err.c_str() : g_l
 
 int gnnd_join_path(const gnnd_ctx* c) {
   if (!c) return GNND_EINVAL;
-  return c->use_mfma ? GNND_JOIN_MFMA : GNND_JOIN_VALU;
+  return c->use_mfma ? GNND_JOIN_MFMA : c->use_gram ? GNND_JOIN_GRAM : GNND_JOIN_VALU;
 }
 
 int gnnd_set_profiling(gnnd_ctx* c, int iterations) {

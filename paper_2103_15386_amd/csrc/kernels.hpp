@@ -81,7 +81,7 @@ struct Shape {
   const void* vec_a;
   const void* vec_b;
   int32_t all_pairs;  // 1: every evaluated pair is proposed (ablation), 0: nearest partners only
-  const float* norms = nullptr;  // squared norm per node, where the metric needs it (cosine)
+  const float* norms = nullptr;  // squared norm per node, where metric or join need it
   int32_t segments = 1;  // > 1: the list is k / 32 segments, object v lives in segment v % segments
   // slots of the proposal array: per appearance in a NEW list two results (all pairs: one per
   // possible partner, 2 * 2p - 1), in an OLD list one (all pairs: 2p); at most 2np appearances each
@@ -109,6 +109,9 @@ hipError_t launch_sample(const Shape& sh, const DevState& ds, uint64_t seed, uin
                          hipStream_t st);
 hipError_t launch_join(const Shape& sh, const DevState& ds, int path, bool merge_mode,
                        hipStream_t st);
+// float32 vectors, metrics that are functions of an inner product and the norms (sh.norms
+// must be set): inner products on the matrix cores, canonical distances for the results
+hipError_t launch_join_gram(const Shape& sh, const DevState& ds, bool merge_mode, hipStream_t st);
 // results are staged per bucket when ds.stg_ent is set, handed on one by one otherwise;
 // `after_join` (may be NULL) is recorded behind the cross-matching kernel, in front of the
 // pass that moves staged results into the destinations' segments

@@ -47,6 +47,16 @@ def test_workspace_size_and_parameter_validation(amd):
     assert amd.workspace_bytes(4096, 16, 128, 65, amd.L2SQ_F32) == 0  # p > 64
     assert amd.workspace_bytes(4096, 0, 10, 8, amd.L2SQ_F32) == 0     # d < 1
     assert amd.workspace_bytes(4096, 16, 10, 8, 7) == 0               # metric
+    # the float32 matrix-core join: float vectors, inner-product metrics, p <= 32; it keeps the
+    # squared norms of all vectors in the workspace
+    gram = amd.workspace_bytes(4096, 16, 10, 8, amd.L2SQ_F32, join_path=amd.JOIN_GRAM)
+    assert gram >= amd.workspace_bytes(4096, 16, 10, 8, amd.L2SQ_F32, join_path=amd.JOIN_VALU) + 4096 * 4
+    assert amd.workspace_bytes(4096, 16, 10, 8, amd.L2SQ_U8, join_path=amd.JOIN_GRAM) == 0
+    assert amd.workspace_bytes(4096, 16, 10, 8, amd.CHI2_F32, join_path=amd.JOIN_GRAM) == 0
+    assert amd.workspace_bytes(4096, 16, 40, 33, amd.COSINE_F32, join_path=amd.JOIN_GRAM) == 0
+    assert amd.workspace_bytes(4096, 16, 10, 8, amd.ANGULAR_F32, amd.UPDATE_ALL_PAIRS,
+                               join_path=amd.JOIN_GRAM) == 0
+    assert amd.workspace_bytes(4096, 16, 10, 8, amd.L2SQ_F32, join_path=5) == 0
     # gnnd_create validates before touching the GPU: errors come back as codes
     ctx = C.c_void_p()
     prm = binding.make_params(50, 8, 50, 8, amd.L2SQ_F32)

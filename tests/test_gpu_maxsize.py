@@ -38,7 +38,7 @@ def test_largest_context_builds_a_valid_improving_graph(kind):
         d, metric = 4, og.L2SQ_F32
         x = rng.random((N, d), dtype=np.float32)
     xd = torch.from_numpy(x).cuda()
-    ctx = amd.Gnnd(xd, k, p, metric, SEED)
+    ctx = amd.Gnnd(xd, k, p, metric, SEED, amd.JOIN_AUTO if kind == "u8_mfma" else amd.JOIN_VALU)
     assert ctx.join_path() == (amd.JOIN_MFMA if kind == "u8_mfma" else amd.JOIN_VALU)
     ctx.init_random()
     ids0, dist0 = ctx.graph()

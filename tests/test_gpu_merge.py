@@ -25,7 +25,7 @@ def x_is_bytes(gen):
     return x.shape[1] <= 128 and bool(((x == np.rint(x)) & (x >= 0) & (x <= 255)).all())
 
 
-@pytest.mark.parametrize("path", ["valu", "auto", "direct"])
+@pytest.mark.parametrize("path", ["valu", "auto", "direct", "gram"])
 @pytest.mark.parametrize("metric,gen,k,p,n1,iters", [
     (og.L2SQ_F32, lambda n: W.uniform_f32(n, 12, seed=201), 10, 10, 900, 4),
     (og.L2SQ_F32, lambda n: W.sift_like_f32(n, 128, seed=202, n_comp=8), 32, 32, 1100, 3),
@@ -42,6 +42,8 @@ def test_merge_matches_oracle(metric, gen, k, p, n1, iters, path):
     import paper_2103_15386_amd as amd
     if path == "direct" and not (metric in (og.L2SQ_U8, og.L2SQ_F32) and x_is_bytes(gen)):
         pytest.skip("the matrix-core join takes byte-valued data only")
+    if path == "gram" and (metric in (og.L2SQ_U8, og.CHI2_F32) or p > 32):
+        pytest.skip("the float32 matrix-core join takes float vectors, inner-product metrics, p <= 32")
     n = 2000
     x = gen(n)
     g1 = _exact(x[:n1], metric, k)
@@ -52,7 +54,7 @@ def test_merge_matches_oracle(metric, gen, k, p, n1, iters, path):
     out = amd.gnnd_merge(_dev(x[:n1]), _dev(x[n1:]), _dev(g1.ids), _dev(g1.dist.astype(dt)),
                          _dev(g2.ids), _dev(g2.dist.astype(dt)), k, p, metric, SEED, iters,
                          join_path={"valu": amd.JOIN_VALU, "auto": amd.JOIN_AUTO,
-                                    "direct": amd.JOIN_MFMA_DIRECT}[path],
+                                    "direct": amd.JOIN_MFMA_DIRECT, "gram": amd.JOIN_GRAM}[path],
                          want_stats=True)
     ids, dist, stats = out
     assert (ids.cpu().numpy() == want.ids).all()

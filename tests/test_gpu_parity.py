@@ -105,6 +105,16 @@ CASES["u8_small_lists"] = (lambda: W.sift_like_u8(1500, 64, seed=1013, n_comp=4)
                            og.L2SQ_U8, 8, 5, 5)
 
 
+# float32 matrix-core join: inner products by matrix instructions pick the partners, canonical
+# sums decide - every float case with p <= 32 under squared L2, angular or cosine, and two
+# with groups of (almost) identical vectors, where many partners stay in the race
+CASES["near_copies_d24"] = (lambda: W.near_copies_f32(1600, 24, seed=1091), og.L2SQ_F32, 24, 16, 4)
+CASES["near_copies_cosine_d70"] = (lambda: W.near_copies_f32(1200, 70, seed=1092, copies=12),
+                                   og.COSINE_F32, 20, 20, 4)
+GRAM_CASES = [n for n, c in CASES.items()
+              if c[1] in (og.L2SQ_F32, og.ANGULAR_F32, og.COSINE_F32) and c[3] <= 32]
+
+
 # "all": the variant that proposes every evaluated pair (no selective update)
 ALL_PAIRS_CASES = ["uniform_c1", "u8_cut", "deep_cut_angular", "tiny_n", "k100_angular",
                    "cosine_ragged_d11_zero_rows"]
@@ -113,6 +123,7 @@ ALL_PAIRS_CASES = ["uniform_c1", "u8_cut", "deep_cut_angular", "tiny_n", "k100_a
 @pytest.mark.parametrize("name,path", [(n, "valu") for n in CASES] +
                          [(n, "mfma") for n in MFMA_CASES] +
                          [(n, "mfma_direct") for n in MFMA_CASES] +
+                         [(n, "gram") for n in GRAM_CASES] +
                          [(n, "all") for n in ALL_PAIRS_CASES])
 def test_every_stage_of_every_iteration_matches_oracle(name, path):
     amd = _amd()
@@ -121,9 +132,11 @@ def test_every_stage_of_every_iteration_matches_oracle(name, path):
     n = len(x)
     every = path == "all"
     # "mfma": results leave the join staged per bucket of destinations; "mfma_direct": one by one
-    join = {"mfma": amd.JOIN_MFMA, "mfma_direct": amd.JOIN_MFMA_DIRECT}.get(path, amd.JOIN_VALU)
+    join = {"mfma": amd.JOIN_MFMA, "mfma_direct": amd.JOIN_MFMA_DIRECT,
+            "gram": amd.JOIN_GRAM}.get(path, amd.JOIN_VALU)
     ctx = amd.Gnnd(_dev(x), k, p, metric, SEED, join,
                    amd.UPDATE_ALL_PAIRS if every else amd.UPDATE_SELECTIVE)
+    assert ctx.join_path() == {"mfma_direct": amd.JOIN_MFMA}.get(path, join) or path == "all"
     ctx.init_random()
     g = og.init_random(x, k, metric, SEED)
     for it in range(1, iters + 1):

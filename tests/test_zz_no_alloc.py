@@ -32,7 +32,7 @@ def test_static_scratch_build_equals_the_workspace_build_on_calls_in_a_row():
     cases = [
         # uint8 rows: matrix-core join, several tiles and a ragged tail (n not a multiple of 4)
         (W.sift_like_u8(6001, 64, seed=71, n_comp=8), 16, 16, amd.L2SQ_U8, 4, amd.JOIN_AUTO),
-        # smaller input next, float rows, general join, k < 64 lanes, p < k
+        # smaller input next, float rows, float32 matrix-core join, k < 64 lanes, p < k
         (W.uniform_f32(2500, 24, seed=72), 10, 8, amd.L2SQ_F32, 5, amd.JOIN_AUTO),
         # the first shape again: nothing may be left over from the smaller call
         (W.sift_like_u8(6001, 64, seed=71, n_comp=8), 16, 16, amd.L2SQ_U8, 4, amd.JOIN_AUTO),
@@ -58,6 +58,8 @@ def test_static_scratch_build_equals_the_workspace_build_on_calls_in_a_row():
         assert torch.equal(got_dist, want_dist), f"distances differ (n={len(x)}, k={k})"
         if metric == amd.L2SQ_U8:
             assert path == amd.JOIN_MFMA  # the reference resolved to the same join
+        elif jp == amd.JOIN_AUTO:
+            assert path == amd.JOIN_GRAM
 
 
 @pytest.mark.gpu

@@ -80,6 +80,19 @@ def scaled_directions_f32(n, d, seed, n_comp=16, zero_rows=0):
     return np.ascontiguousarray(x, dtype=np.float32)
 
 
+def near_copies_f32(n, d, seed, copies=8, jitter=1e-6):
+    """Groups of `copies` almost identical vectors: n / copies uniform vectors, each
+    repeated `copies` times, half of the repeats exactly, the others moved by a relative
+    `jitter` per coordinate.  Many partners of a sample are then equally near, or nearer
+    than float32 inner products can tell apart: ties by id and near-ties everywhere."""
+    rng = np.random.default_rng(seed)
+    base = rng.random((-(-n // copies), d), dtype=np.float32)
+    x = np.repeat(base, copies, axis=0)[:n].copy()
+    moved = (np.arange(n) % copies) >= copies // 2
+    x[moved] *= (1.0 + jitter * rng.standard_normal((int(moved.sum()), d))).astype(np.float32)
+    return np.ascontiguousarray(x[rng.permutation(n)], dtype=np.float32)
+
+
 def small_integer_f32(n, d, seed, hi=16):
     """Tiny integer-valued float vectors: every distance is an exact small
     integer in any summation order (handy for exact pins)."""
