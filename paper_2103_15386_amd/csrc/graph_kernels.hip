@@ -172,6 +172,111 @@ __global__ __launch_bounds__(kBlock) void k_update(int64_t n, int k, uint64_t* G
 }
 
 // ---------------------------------------------------------------------------
+// The same for lists of up to 32 entries, two destinations per wavefront: the lower and the
+// upper 32 lanes each own a destination, and every step above runs on 32 lanes - both halves
+// by the same instructions, with shorter sorting and merging networks.
+__device__ inline uint64_t half_lanes(int lane) {
+  return (lane & 32) ? 0xffffffff00000000ull : 0x00000000ffffffffull;
+}
+// stable compaction inside each half (see wave_compact)
+__device__ inline uint64_t half_compact(uint64_t v, bool keep, uint64_t fill, int lane) {
+  const uint64_t mask = __ballot(keep) & half_lanes(lane);
+  const int nkeep = __popcll(mask);
+  const int before = __popcll(mask & lanes_below(lane));
+  const int dst = (lane & 32) | (keep ? before : nkeep + ((lane & 31) - before));
+  const uint64_t x = keep ? v : fill;
+  const uint32_t lo = __builtin_amdgcn_ds_permute(dst << 2, (int)(uint32_t)x);
+  const uint32_t hi = __builtin_amdgcn_ds_permute(dst << 2, (int)(uint32_t)(x >> 32));
+  return ((uint64_t)hi << 32) | lo;
+}
+// the 32 smallest of two ascending 32-lane sequences, ascending, in each half
+__device__ inline uint64_t half_merge_smallest(uint64_t a_sorted, uint64_t b_sorted, int lane) {
+  // value of lane 31 - (lane % 32) of the half: mirror inside the row of 16, then swap the rows
+  const uint32_t mlo = (uint32_t)__builtin_amdgcn_mov_dpp((int)(uint32_t)b_sorted, 0x140, 0xF, 0xF, true);
+  const uint32_t mhi =
+      (uint32_t)__builtin_amdgcn_mov_dpp((int)(uint32_t)(b_sorted >> 32), 0x140, 0xF, 0xF, true);
+  const uint64_t br = xor_lanes(((uint64_t)mhi << 32) | mlo, 16, lane);
+  uint64_t v = vmin(a_sorted, br);
+#pragma unroll
+  for (int j = 16; j > 0; j >>= 1) {
+    const uint64_t o = xor_lanes(v, j, lane);
+    v = exchange(v, o, (lane & j) == 0);
+  }
+  return v;
+}
+// filter_candidates on 32 lanes: `row` holds k <= 32 ascending entries per half
+__device__ inline uint64_t half_filter_candidates(uint64_t pk, uint64_t row, int k, int lane,
+                                                  bool& any) {
+  const int base = lane & 32, l32 = lane & 31;
+  const uint64_t last = __shfl(row, base | (k - 1), kWave);
+  if (pk != kKeyMax && entry_key(pk) >= entry_key(last)) pk = kKeyMax;
+  any = __ballot(pk != kKeyMax) != 0ull;
+  if (!any) return pk;
+  const uint64_t kk = entry_key(pk);
+  int pos = 0;
+#pragma unroll
+  for (int step = 16; step > 0; step >>= 1) {
+    const uint64_t r = __shfl(row, base | (pos + step - 1), kWave);
+    pos += (entry_key(r) < kk) ? step : 0;
+  }
+  if (entry_key(__shfl(row, base | pos, kWave)) == kk) pk = kKeyMax;
+  const uint64_t left = __ballot(pk != kKeyMax);
+  any = left != 0ull;
+  if (!any) return pk;
+  pk = half_compact(pk, pk != kKeyMax, kKeyMax, lane);
+  const int c0 = __popcll(left & 0xffffffffull), c1 = __popcll(left >> 32);
+  const int count = c0 > c1 ? c0 : c1;
+  // the networks over up to 32 lanes never cross the halves; the in-half lane number makes
+  // both halves ascend
+  if (count > 16) pk = wave_sort_first<32>(pk, l32);
+  else if (count > 8) pk = wave_sort_first<16>(pk, l32);
+  else if (count > 4) pk = wave_sort_first<8>(pk, l32);
+  else if (count > 2) pk = wave_sort_first<4>(pk, l32);
+  else if (count > 1) pk = wave_sort_first<2>(pk, l32);
+  const uint64_t prev = __shfl_up(pk, 1, kWave);
+  const bool rep = l32 > 0 && pk != kKeyMax && entry_key(pk) == entry_key(prev);
+  if (__ballot(rep) != 0ull) pk = half_compact(pk, !rep, kKeyMax, lane);
+  return pk;
+}
+
+__global__ __launch_bounds__(kBlock) void k_update_pairs(int64_t n, int k, uint64_t* G,
+                                                         NodeMeta* meta, const uint64_t* pslot,
+                                                         const uint64_t* poff,
+                                                         const uint64_t* bins, uint64_t* counters) {
+  const int lane = lane_id(), l32 = lane & 31;
+  const int64_t u = wave_global_index() * 2 + (lane >> 5);
+  if (u - (lane >> 5) >= n) return;  // the whole wavefront lies beyond the last node
+  const bool live = u < n;
+  uint64_t cnt = live ? pslot[u] & kSlotCountMask : 0;
+  const uint64_t beg = live ? poff[u] : 0, cap = live ? poff[u + 1] - beg : 0;
+  uint64_t row = (live && l32 < k) ? G[u * k + l32] : kKeyMax;
+  if (__ballot(cnt != 0) == 0ull) return;
+  if (cnt > cap) {  // cannot happen: a segment is sized by the bound of what its node can receive
+    if (l32 == 0) counter_add(counters, C_OVERFLOW, u, cnt - cap);
+    cnt = cap;
+  }
+  const uint64_t cnt_other = __shfl(cnt, lane ^ 32, kWave);
+  const uint64_t rounds = cnt > cnt_other ? cnt : cnt_other;
+  bool changed = false;
+  for (uint64_t c = 0; c < rounds; c += 32) {
+    uint64_t pk = (c + l32 < cnt) ? bins[beg + c + l32] : kKeyMax;
+    bool any;
+    pk = half_filter_candidates(pk, row, k, lane, any);
+    if (!any) continue;
+    const bool mine = (__ballot(pk != kKeyMax) & half_lanes(lane)) != 0ull;
+    row = half_merge_smallest(row, pk, lane);  // a half without survivors keeps its row
+    if (l32 >= k) row = kKeyMax;
+    changed = changed || mine;
+  }
+  const uint64_t admitted = __ballot(l32 < k && (row & 2ull)) & half_lanes(lane);
+  if (changed) {
+    if (l32 < k) G[u * k + l32] = row & ~2ull;
+    if (l32 == k - 1) meta[u].kth = entry_code(row);
+    if (l32 == 0) counter_add(counters, C_INSERTS, u, (uint64_t)__popcll(admitted));
+  }
+}
+
+// ---------------------------------------------------------------------------
 template <bool FLOAT>
 __global__ __launch_bounds__(kBlock) void k_get_graph(int64_t total, const uint64_t* G,
                                                       int32_t* ids, void* dist, uint8_t* isnew,
@@ -566,8 +671,12 @@ hipError_t launch_sample(const Shape& sh, const DevState& ds, uint64_t seed, uin
 hipError_t launch_update(const Shape& sh, const DevState& ds, hipStream_t st) {
   if (sh.segments > 1) return launch_update_segmented(sh, ds, st);
   if (sh.k > kWave) return launch_update_wide(sh, ds, st);
-  k_update<<<blocks_for_waves(sh.n), kBlock, 0, st>>>(sh.n, sh.k, ds.G, ds.meta, ds.pslot, ds.poff,
-                                                      ds.bins, ds.counters);
+  if (sh.k <= 32)
+    k_update_pairs<<<blocks_for_waves((sh.n + 1) / 2), kBlock, 0, st>>>(
+        sh.n, sh.k, ds.G, ds.meta, ds.pslot, ds.poff, ds.bins, ds.counters);
+  else
+    k_update<<<blocks_for_waves(sh.n), kBlock, 0, st>>>(sh.n, sh.k, ds.G, ds.meta, ds.pslot,
+                                                        ds.poff, ds.bins, ds.counters);
   return hipGetLastError();
 }
 
