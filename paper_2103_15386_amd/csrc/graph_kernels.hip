@@ -204,14 +204,14 @@ __device__ inline uint64_t half_merge_smallest(uint64_t a_sorted, uint64_t b_sor
   }
   return v;
 }
-// filter_candidates on 32 lanes: `row` holds k <= 32 ascending entries per half
-__device__ inline uint64_t half_filter_candidates(uint64_t pk, uint64_t row, int k, int lane,
-                                                  bool& any) {
-  const int base = lane & 32, l32 = lane & 31;
+// filter_candidates on 32 lanes, in two parts; `row` holds k <= 32 ascending entries per half.
+// First part: what is not closer than the list's last entry or already in the list becomes
+// kKeyMax (where it stands).
+__device__ inline uint64_t half_drop_known(uint64_t pk, uint64_t row, int k, int lane) {
+  const int base = lane & 32;
   const uint64_t last = __shfl(row, base | (k - 1), kWave);
   if (pk != kKeyMax && entry_key(pk) >= entry_key(last)) pk = kKeyMax;
-  any = __ballot(pk != kKeyMax) != 0ull;
-  if (!any) return pk;
+  if (__ballot(pk != kKeyMax) == 0ull) return pk;
   const uint64_t kk = entry_key(pk);
   int pos = 0;
 #pragma unroll
@@ -220,12 +220,12 @@ __device__ inline uint64_t half_filter_candidates(uint64_t pk, uint64_t row, int
     pos += (entry_key(r) < kk) ? step : 0;
   }
   if (entry_key(__shfl(row, base | pos, kWave)) == kk) pk = kKeyMax;
-  const uint64_t left = __ballot(pk != kKeyMax);
-  any = left != 0ull;
-  if (!any) return pk;
-  pk = half_compact(pk, pk != kKeyMax, kKeyMax, lane);
-  const int c0 = __popcll(left & 0xffffffffull), c1 = __popcll(left >> 32);
-  const int count = c0 > c1 ? c0 : c1;
+  return pk;
+}
+// Second part: the survivors, already at the front of their half (`count` = the larger
+// number of them in the two halves), ascending and without repeats.
+__device__ inline uint64_t half_sort_unique(uint64_t pk, int count, int lane) {
+  const int l32 = lane & 31;
   // the networks over up to 32 lanes never cross the halves; the in-half lane number makes
   // both halves ascend
   if (count > 16) pk = wave_sort_first<32>(pk, l32);
@@ -257,18 +257,50 @@ __global__ __launch_bounds__(kBlock) void k_update_pairs(int64_t n, int k, uint6
   }
   const uint64_t cnt_other = __shfl(cnt, lane ^ 32, kWave);
   const uint64_t rounds = cnt > cnt_other ? cnt : cnt_other;
+  const uint64_t mine_mask = half_lanes(lane);
   bool changed = false;
-  for (uint64_t c = 0; c < rounds; c += 32) {
-    uint64_t pk = (c + l32 < cnt) ? bins[beg + c + l32] : kKeyMax;
-    bool any;
-    pk = half_filter_candidates(pk, row, k, lane, any);
-    if (!any) continue;
-    const bool mine = (__ballot(pk != kKeyMax) & half_lanes(lane)) != 0ull;
+  // survivors (at the front of their half, `count` at most in either half) into the row
+  auto admit = [&](uint64_t pk, int count) {
+    pk = half_sort_unique(pk, count, lane);
+    const bool mine = (__ballot(pk != kKeyMax) & mine_mask) != 0ull;
     row = half_merge_smallest(row, pk, lane);  // a half without survivors keeps its row
     if (l32 >= k) row = kKeyMax;
     changed = changed || mine;
+  };
+  // A round takes 64 proposals per destination, two per lane.  Few of them survive the cheap
+  // tests as a rule: when the survivors of both registers fit one half they go through one
+  // sorting and one merging network, otherwise the second register waits for the first.
+  for (uint64_t c = 0; c < rounds; c += 64) {
+    uint64_t pa = (c + l32 < cnt) ? bins[beg + c + l32] : kKeyMax;
+    uint64_t pb = (c + 32 + l32 < cnt) ? bins[beg + c + 32 + l32] : kKeyMax;
+    pa = half_drop_known(pa, row, k, lane);
+    pb = half_drop_known(pb, row, k, lane);
+    const uint64_t left_a = __ballot(pa != kKeyMax), left_b = __ballot(pb != kKeyMax);
+    if ((left_a | left_b) == 0ull) continue;
+    const int na = __popcll(left_a & mine_mask), nb = __popcll(left_b & mine_mask);
+    const int na_max = vmax(__popcll(left_a & 0xffffffffull), __popcll(left_a >> 32));
+    pa = half_compact(pa, pa != kKeyMax, kKeyMax, lane);
+    if (left_b == 0ull) {
+      admit(pa, na_max);
+    } else if (__ballot(na + nb > 32) == 0ull) {
+      pb = half_compact(pb, pb != kKeyMax, kKeyMax, lane);
+      const int src = l32 - na;
+      const uint64_t shifted = __shfl(pb, (lane & 32) | (src < 0 ? 0 : src), kWave);
+      const int n0 = __popcll(left_a & 0xffffffffull) + __popcll(left_b & 0xffffffffull);
+      const int n1 = __popcll(left_a >> 32) + __popcll(left_b >> 32);
+      admit(l32 < na ? pa : shifted, vmax(n0, n1));
+    } else {
+      if (left_a != 0ull) admit(pa, na_max);
+      // the list has changed: the second register takes the cheap tests again
+      pb = half_drop_known(pb, row, k, lane);
+      const uint64_t left = __ballot(pb != kKeyMax);
+      if (left != 0ull) {
+        pb = half_compact(pb, pb != kKeyMax, kKeyMax, lane);
+        admit(pb, vmax(__popcll(left & 0xffffffffull), __popcll(left >> 32)));
+      }
+    }
   }
-  const uint64_t admitted = __ballot(l32 < k && (row & 2ull)) & half_lanes(lane);
+  const uint64_t admitted = __ballot(l32 < k && (row & 2ull)) & mine_mask;
   if (changed) {
     if (l32 < k) G[u * k + l32] = row & ~2ull;
     if (l32 == k - 1) meta[u].kth = entry_code(row);
