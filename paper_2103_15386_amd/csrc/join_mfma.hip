@@ -329,7 +329,8 @@ __attribute__((amdgpu_waves_per_eu(STAGED ? 2 : 3, STAGED ? 2 : 3))) void k_join
   uint64_t* const st_gbase = st_region + kStageBuckets;
   uint32_t* const st_cnt = reinterpret_cast<uint32_t*>(st_gbase + kStageBuckets);
   uint32_t* const st_fill = st_cnt + kStageBuckets;  // [0] results staged, [1] waves out of nodes
-  const int wave = wave_id(), lane = lane_id(), half = lane >> 5, col = lane & 31;
+  // (the wave index as a vector value: measured 3 % faster here than the scalar form)
+  const int wave = threadIdx.x >> 6, lane = lane_id(), half = lane >> 5, col = lane & 31;
   const int64_t W = (int64_t)gridDim.x * WAVES;
   int64_t s = (int64_t)blockIdx.x * WAVES + wave;
   if (!STAGED && s >= n) return;
