@@ -679,12 +679,24 @@ __attribute__((amdgpu_waves_per_eu(STAGED ? 2 : 3, STAGED ? 2 : 3))) void k_join
 }
 
 // Second half of the staged hand-out: one workgroup per bucket moves the bucket's
-// results from its region into the segments of their destinations (LDS counter per
-// destination = place in the segment) and writes the destinations' slot words
-// (segment start, results received) that the list update reads.
+// results from its region into the segments of their destinations and writes the
+// destinations' slot words (segment start, results received) that the list update reads.
+// The results arrive in no order, and 8-byte stores to scattered places are served at a
+// fixed rate whatever their number per line; so the workgroup takes the region in tiles,
+// puts every tile in destination order inside LDS (counting sort: an LDS counter per
+// destination gives each result its rank, a scan of the counters the start of each
+// destination's run) and writes it out run by run: neighbouring lanes then store to
+// neighbouring places.
 constexpr int kRcBlock = 1024;
-// The destinations' segment starts (relative to the region) are kept in LDS next to the
-// counters: a bucket has at most 2^12 destinations.
+constexpr int kRcPerThread = 12;                     // results per thread and tile
+constexpr int kRcTile = kRcBlock * kRcPerThread;     // 96 KB of LDS
+// LDS: the tile, then per destination of the bucket (at most 2^12) the number of results in
+// the tile / the start of its run, the next free place of its segment and the segment's end
+// (both relative to the region).
+static size_t result_csr_lds_bytes(int tb) {
+  return (size_t)kRcTile * 8 + (((size_t)3 << tb) + 1) * 4;
+}
+
 __global__ __launch_bounds__(kRcBlock) void k_result_csr(int64_t n, int tb,
                                                          const uint64_t* __restrict__ poff,
                                                          const unsigned long long* __restrict__ cur,
@@ -692,48 +704,107 @@ __global__ __launch_bounds__(kRcBlock) void k_result_csr(int64_t n, int tb,
                                                          uint64_t* __restrict__ bins,
                                                          uint64_t* __restrict__ pslot,
                                                          uint64_t* counters) {
-  extern __shared__ uint32_t received[];  // 2^tb counters, then 2^tb + 1 segment starts
-  uint32_t* const seg_start = received + ((size_t)1 << tb);
+  extern __shared__ __attribute__((aligned(16))) uint64_t rc_lds[];
+  __shared__ uint32_t part[kRcBlock / kWave];
+  uint64_t* const tile = rc_lds;
+  const int T_max = 1 << tb;
+  uint32_t* const run = reinterpret_cast<uint32_t*>(rc_lds + kRcTile);  // T_max + 1 entries
+  uint32_t* const next = run + T_max + 1;
+  uint32_t* const seg_end = next + T_max;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int64_t first = (int64_t)blockIdx.x << tb;
-  const int T = (int)(n - first < ((int64_t)1 << tb) ? n - first : ((int64_t)1 << tb));
+  const int T = (int)(n - first < (int64_t)T_max ? n - first : (int64_t)T_max);
   const uint64_t region = poff[first], room = poff[first + T] - region;
-  for (int t = threadIdx.x; t < T; t += kRcBlock) {
-    received[t] = 0;
-    seg_start[t] = (uint32_t)(poff[first + t] - region);
+  for (int t = tid; t < T_max; t += kRcBlock) {
+    next[t] = t < T ? (uint32_t)(poff[first + t] - region) : (uint32_t)room;
+    seg_end[t] = t < T ? (uint32_t)(poff[first + t + 1] - region) : (uint32_t)room;
   }
-  if (threadIdx.x == 0) seg_start[T] = (uint32_t)room;
-  __syncthreads();
   uint64_t count = cur[blockIdx.x];
   if (count > room) {  // cannot happen: a region holds what its destinations can receive
-    if (threadIdx.x == 0)
+    if (tid == 0)
       atomicAdd(reinterpret_cast<unsigned long long*>(counters + C_OVERFLOW),
                 (unsigned long long)(count - room));
     count = room;
   }
-  constexpr int kAtOnce = 8;  // results in flight per thread
-  for (uint64_t i0 = threadIdx.x; i0 < count; i0 += (uint64_t)kAtOnce * kRcBlock) {
-    uint64_t e[kAtOnce];
+  const int per = (T_max + kRcBlock - 1) / kRcBlock;  // counters per thread in the scan (<= 4)
+  for (uint64_t base = 0; base < count; base += kRcTile) {
+    for (int t = tid; t <= T_max; t += kRcBlock) run[t] = 0;
+    __syncthreads();
+    // rank of every result among the tile's results for the same destination
+    uint64_t e[kRcPerThread];
+    uint32_t rank[kRcPerThread];
 #pragma unroll
-    for (int r = 0; r < kAtOnce; ++r) {
-      const uint64_t i = i0 + (uint64_t)r * kRcBlock;
+    for (int r = 0; r < kRcPerThread; ++r) {
+      const uint64_t i = base + (uint64_t)r * kRcBlock + tid;
       e[r] = i < count ? ent[region + i] : ~0ull;
     }
 #pragma unroll
-    for (int r = 0; r < kAtOnce; ++r) {
-      const int t = (int)(((uint32_t)e[r] >> kStageIdBits) & ((1u << tb) - 1u));
-      if (e[r] == ~0ull || t >= T) continue;
-      const uint32_t place = atomicAdd(&received[t], 1u);
-      const uint64_t seg = region + seg_start[t], cap = seg_start[t + 1] - seg_start[t];
-      // back to a list entry: distance code | object id | "admitted now" + NEW
-      if (place < cap)
-        bins[seg + place] = make_entry((uint32_t)(e[r] >> 32),
-                                       (uint32_t)e[r] & ((1u << kStageIdBits) - 1u), 3u);
+    for (int r = 0; r < kRcPerThread; ++r) {
+      const int t = (int)(((uint32_t)e[r] >> kStageIdBits) & (uint32_t)(T_max - 1));
+      if (e[r] == ~0ull || t >= T) e[r] = ~0ull;
+      else rank[r] = atomicAdd(&run[t], 1u);
     }
+    __syncthreads();
+    // exclusive scan of the counters: thread i takes counters per*i .. per*i + per - 1
+    uint32_t mine[4], sum = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int t = tid * per + j;
+      mine[j] = (j < per && t < T_max) ? run[t] : 0u;
+      sum += mine[j];
+    }
+    uint32_t inc = sum;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+      const uint32_t o = __shfl_up(inc, off, kWave);
+      if (lane >= off) inc += o;
+    }
+    if (lane == kWave - 1) part[wave] = inc;
+    __syncthreads();
+    uint32_t before = 0;
+    for (int w = 0; w < wave; ++w) before += part[w];
+    uint32_t at = before + inc - sum;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int t = tid * per + j;
+      if (j < per && t < T_max) run[t] = at;
+      at += mine[j];
+    }
+    if (tid == kRcBlock - 1) run[T_max] = at;  // results in the tile
+    __syncthreads();
+    // the tile in destination order
+#pragma unroll
+    for (int r = 0; r < kRcPerThread; ++r) {
+      if (e[r] != ~0ull) {
+        const int t = (int)(((uint32_t)e[r] >> kStageIdBits) & (uint32_t)(T_max - 1));
+        tile[run[t] + rank[r]] = e[r];
+      }
+    }
+    __syncthreads();
+    const uint32_t in_tile = run[T_max];
+#pragma unroll
+    for (int r = 0; r < kRcPerThread; ++r) {
+      const uint32_t j = (uint32_t)r * kRcBlock + tid;
+      if (j < in_tile) {
+        const uint64_t x = tile[j];
+        const int t = (int)(((uint32_t)x >> kStageIdBits) & (uint32_t)(T_max - 1));
+        const uint32_t place = next[t] + (j - run[t]);
+        // back to a list entry: distance code | object id | "admitted now" + NEW
+        if (place < seg_end[t])
+          bins[region + place] = make_entry((uint32_t)(x >> 32),
+                                            (uint32_t)x & ((1u << kStageIdBits) - 1u), 3u);
+      }
+    }
+    __syncthreads();
+    for (int t = tid; t < T; t += kRcBlock) next[t] += run[t + 1] - run[t];
+    __syncthreads();
   }
   __syncthreads();
-  for (int t = threadIdx.x; t < T; t += kRcBlock) {
-    const uint64_t got = received[t] < kSlotCountMask ? received[t] : kSlotCountMask;
-    pslot[first + t] = ((region + seg_start[t]) << kSlotCountBits) | got;
+  for (int t = tid; t < T; t += kRcBlock) {
+    const uint64_t start = poff[first + t] - region;
+    const uint64_t end = next[t] < seg_end[t] ? next[t] : seg_end[t];
+    const uint64_t got = end - start < kSlotCountMask ? end - start : kSlotCountMask;
+    pslot[first + t] = ((region + start) << kSlotCountBits) | got;
   }
 }
 
@@ -822,8 +893,12 @@ hipError_t launch_join_mfma(const Shape& sh, const DevState& ds, bool merge_mode
   if (after_join) (void)hipEventRecord(after_join, st);
   if (e != hipSuccess || !staged) return e;
   // (a region is shorter than 2^32 slots: n <= 2^20, 6p <= 192 slots per node)
-  k_result_csr<<<(unsigned)sa.nb, kRcBlock, ((size_t)8 << sa.tb) + 4, st>>>(
-      sh.n, sa.tb, ds.poff, ds.stg_cur, ds.stg_ent, ds.bins, ds.pslot, ds.counters);
+  const size_t lds = result_csr_lds_bytes(sa.tb);
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_result_csr),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
+  k_result_csr<<<(unsigned)sa.nb, kRcBlock, lds, st>>>(sh.n, sa.tb, ds.poff, ds.stg_cur, ds.stg_ent,
+                                                      ds.bins, ds.pslot, ds.counters);
   return hipGetLastError();
 }
 
