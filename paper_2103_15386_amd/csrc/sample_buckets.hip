@@ -236,7 +236,9 @@ constexpr int kStBlock = 1024;
 constexpr int kStEdges = 256 * 32;           // edges per batch: 256 rows of 32, or 128 rows of 64
 constexpr int kStPasses = 8;                 // passes of kStBlock / PW rows make a batch
 
-template <int PW>
+// PACKED: an edge leaves as one 32-bit word, (target inside its bucket) << (32 - tb) | source,
+// which the sources of up to 2^(32 - tb) nodes fit; otherwise as (target, source).
+template <int PW, bool PACKED>
 __global__ __launch_bounds__(kStBlock) void k_fwd_scatter_staged(
     int64_t n, int p, BucketGeom g, const int32_t* snew, const int32_t* sold,
     const uint32_t* wg_hist, const uint64_t* boff, uint2* edges_new, uint2* edges_old) {
@@ -312,7 +314,12 @@ __global__ __launch_bounds__(kStBlock) void k_fwd_scatter_staged(
       for (uint32_t i = tid; i < total; i += kStBlock) {
         const uint2 rec = stage[i];
         const uint32_t b = rec.x >> g.tb;
-        edges[cursor[kind * g.nb + b] + (i - off[b])] = rec;
+        const uint32_t at = cursor[kind * g.nb + b] + (i - off[b]);
+        if (PACKED)
+          reinterpret_cast<uint32_t*>(edges)[at] =
+              ((rec.x & ((1u << g.tb) - 1u)) << (32 - g.tb)) | rec.y;
+        else
+          edges[at] = rec;
       }
       __syncthreads();
       for (int i = tid; i < g.nb; i += kStBlock) cursor[kind * g.nb + i] += cnt[i];
@@ -327,6 +334,7 @@ static size_t staged_lds_bytes(const BucketGeom& g) {
 
 // One workgroup per (bucket, kind): counting sort of the bucket's edges by
 // target.  LDS holds one counter per target of the bucket (dynamic size).
+template <bool PACKED>
 __global__ __launch_bounds__(kCsrBlock) void k_bucket_csr(int64_t n, BucketGeom g,
                                                           const uint64_t* boff,
                                                           const uint2* edges_new,
@@ -347,16 +355,18 @@ __global__ __launch_bounds__(kCsrBlock) void k_bucket_csr(int64_t n, BucketGeom 
   for (int i = threadIdx.x; i < T; i += kCsrBlock) cnt[i] = 0;
   __syncthreads();
   constexpr int kAtOnce = 8;  // edges in flight per thread
+  const uint32_t* const words = reinterpret_cast<const uint32_t*>(edges);
+  const int sh = 32 - g.tb;  // packed edge: target inside the bucket above, source below
   for (uint64_t e0 = beg + threadIdx.x; e0 < end; e0 += kAtOnce * kCsrBlock) {
     uint32_t t[kAtOnce];
 #pragma unroll
     for (int r = 0; r < kAtOnce; ++r) {
       const uint64_t e = e0 + (uint64_t)r * kCsrBlock;
-      t[r] = e < end ? edges[e].x : 0xffffffffu;
+      t[r] = e < end ? (PACKED ? words[e] >> sh : edges[e].x & mask) : 0xffffffffu;
     }
 #pragma unroll
     for (int r = 0; r < kAtOnce; ++r)
-      if (t[r] != 0xffffffffu) atomicAdd(&cnt[t[r] & mask], 1u);
+      if (t[r] != 0xffffffffu) atomicAdd(&cnt[t[r]], 1u);
   }
   __syncthreads();
   // exclusive scan over the T counters: T / 1024 consecutive counters per thread
@@ -394,16 +404,25 @@ __global__ __launch_bounds__(kCsrBlock) void k_bucket_csr(int64_t n, BucketGeom 
   if (b == g.nb - 1 && threadIdx.x == 0) roff[n] = bo[g.nb];
   __syncthreads();
   for (uint64_t e0 = beg + threadIdx.x; e0 < end; e0 += kAtOnce * kCsrBlock) {
-    uint2 ed[kAtOnce];
+    uint2 ed[kAtOnce];  // (target inside the bucket, source); target 0xffffffff: none
 #pragma unroll
     for (int r = 0; r < kAtOnce; ++r) {
       const uint64_t e = e0 + (uint64_t)r * kCsrBlock;
-      ed[r] = e < end ? edges[e] : make_uint2(0xffffffffu, 0u);
+      ed[r] = make_uint2(0xffffffffu, 0u);
+      if (e < end) {
+        if (PACKED) {
+          const uint32_t w = words[e];
+          ed[r] = make_uint2(w >> sh, w & ((1u << sh) - 1u));
+        } else {
+          const uint2 x = edges[e];
+          ed[r] = make_uint2(x.x & mask, x.y);
+        }
+      }
     }
 #pragma unroll
     for (int r = 0; r < kAtOnce; ++r)
       if (ed[r].x != 0xffffffffu) {
-        const uint32_t pos = atomicAdd(&cnt[ed[r].x & mask], 1u);
+        const uint32_t pos = atomicAdd(&cnt[ed[r].x], 1u);
         csr[beg + pos] = (int32_t)ed[r].y;
       }
   }
@@ -423,8 +442,11 @@ hipError_t launch_sample_buckets(const Shape& sh, const DevState& ds, hipStream_
   const BucketGeom g = bucket_geom(sh.n);
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_bucket_csr),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_bucket_csr<false>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, 4 << 15);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_bucket_csr<true>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, 4 << 15);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
@@ -446,23 +468,35 @@ hipError_t launch_sample_buckets(const Shape& sh, const DevState& ds, hipStream_
   k_bucket_scan<<<1, kCsrBlock, 0, st>>>(g.nb, bcnt, boff);
   static bool staged_attr = false;
   if (!staged_attr) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_fwd_scatter_staged<32>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 144 << 10);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_fwd_scatter_staged<64>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, 144 << 10);
+    hipError_t e = hipSuccess;
+    const void* kernels[4] = {reinterpret_cast<const void*>(k_fwd_scatter_staged<32, false>),
+                              reinterpret_cast<const void*>(k_fwd_scatter_staged<32, true>),
+                              reinterpret_cast<const void*>(k_fwd_scatter_staged<64, false>),
+                              reinterpret_cast<const void*>(k_fwd_scatter_staged<64, true>)};
+    for (int i = 0; i < 4 && e == hipSuccess; ++i)
+      e = hipFuncSetAttribute(kernels[i], hipFuncAttributeMaxDynamicSharedMemorySize, 144 << 10);
     if (e != hipSuccess) return e;
     staged_attr = true;
   }
-  if (sh.p <= 32)
-    k_fwd_scatter_staged<32><<<grid, kStBlock, staged_lds_bytes(g), st>>>(
-        sh.n, sh.p, g, ds.snew, ds.sold, wg_hist, boff, edges_new, edges_old);
+  // one 32-bit word per edge where the source ids fit beside the target's place in its bucket
+  const bool packed = sh.n <= ((int64_t)1 << (32 - g.tb));
+#define GNND_SCATTER(PW, PK)                                                            \
+  k_fwd_scatter_staged<PW, PK><<<grid, kStBlock, staged_lds_bytes(g), st>>>(            \
+      sh.n, sh.p, g, ds.snew, ds.sold, wg_hist, boff, edges_new, edges_old)
+  if (sh.p <= 32) {
+    if (packed) GNND_SCATTER(32, true);
+    else GNND_SCATTER(32, false);
+  } else {
+    if (packed) GNND_SCATTER(64, true);
+    else GNND_SCATTER(64, false);
+  }
+#undef GNND_SCATTER
+  if (packed)
+    k_bucket_csr<true><<<dim3((unsigned)g.nb, 2), kCsrBlock, (size_t)4 << g.tb, st>>>(
+        sh.n, g, boff, edges_new, edges_old, ds.roff_new, ds.roff_old, ds.csr_new, ds.csr_old);
   else
-    k_fwd_scatter_staged<64><<<grid, kStBlock, staged_lds_bytes(g), st>>>(
-        sh.n, sh.p, g, ds.snew, ds.sold, wg_hist, boff, edges_new, edges_old);
-  k_bucket_csr<<<dim3((unsigned)g.nb, 2), kCsrBlock, (size_t)4 << g.tb, st>>>(
-      sh.n, g, boff, edges_new, edges_old, ds.roff_new, ds.roff_old, ds.csr_new,
-      ds.csr_old);
+    k_bucket_csr<false><<<dim3((unsigned)g.nb, 2), kCsrBlock, (size_t)4 << g.tb, st>>>(
+        sh.n, g, boff, edges_new, edges_old, ds.roff_new, ds.roff_old, ds.csr_new, ds.csr_old);
   return hipGetLastError();
 }
 
