@@ -89,9 +89,12 @@ __device__ inline int select_list(int64_t v, int p, uint64_t base, uint32_t iter
   return count;
 }
 
-// One wavefront finishes both sample lists of a node.  Everything that does not
-// depend on another load (sizes, offsets, both list rows) is requested first,
-// then both candidate segments, so a node costs two memory round trips.
+// One wavefront finishes both sample lists of kNodesPerWave nodes.  The kernel is bound by
+// the latency of its two dependent rounds of reads (sizes, offsets and list rows, then the
+// candidate segments), not by its arithmetic, and it needs few registers: so a wavefront
+// requests everything of the first round for all its nodes at once, then everything of the
+// second round, and only then works the lists off one node after the other.
+constexpr int kNodesPerWave = 4;
 __global__ __launch_bounds__(kBlock) void k_rev_select(int64_t n, int p, uint64_t base_new,
                                                        uint64_t base_old, uint32_t iter,
                                                        int32_t* snew, int32_t* sold,
@@ -103,33 +106,57 @@ __global__ __launch_bounds__(kBlock) void k_rev_select(int64_t n, int p, uint64_
                                                        uint32_t* capn, uint32_t* capo,
                                                        uint32_t per_new, uint32_t per_old,
                                                        uint64_t* counters) {
-  const int64_t v = wave_global_index();
-  if (v >= n) return;
+  const int64_t v0 = wave_global_index() * kNodesPerWave;
+  if (v0 >= n) return;
   const int lane = lane_id();
   const int L = 2 * p;
-  int32_t* list_n = snew + v * L;
-  int32_t* list_o = sold + v * L;
-  const int nfn = cnew[v], nfo = cold[v];
-  const uint64_t bn = roff_new[v], en = roff_new[v + 1], bo = roff_old[v], eo = roff_old[v + 1];
-  const uint32_t rown = lane < L ? (uint32_t)list_n[lane] : kIdMax;
-  const uint32_t rowo = lane < L ? (uint32_t)list_o[lane] : kIdMax;
-  const uint64_t dn = en - bn, dO = eo - bo;
-  const uint32_t firstn = lane < dn ? (uint32_t)csr_new[bn + lane] : kIdMax;
-  const uint32_t firsto = lane < dO ? (uint32_t)csr_old[bo + lane] : kIdMax;
-  const int cn = select_list(v, p, base_new, iter, list_n, rown, nfn, csr_new, bn, dn, firstn, lane);
-  const int co = select_list(v, p, base_old, iter, list_o, rowo, nfo, csr_old, bo, dO, firsto, lane);
+  int nfn[kNodesPerWave], nfo[kNodesPerWave];
+  uint64_t bn[kNodesPerWave], dn[kNodesPerWave], bo[kNodesPerWave], dO[kNodesPerWave];
+  uint32_t rown[kNodesPerWave], rowo[kNodesPerWave], firstn[kNodesPerWave], firsto[kNodesPerWave];
+#pragma unroll
+  for (int i = 0; i < kNodesPerWave; ++i) {
+    const int64_t v = v0 + i < n ? v0 + i : n - 1;  // beyond the end: the last node again, unused
+    nfn[i] = cnew[v];
+    nfo[i] = cold[v];
+    bn[i] = roff_new[v];
+    dn[i] = roff_new[v + 1] - bn[i];
+    bo[i] = roff_old[v];
+    dO[i] = roff_old[v + 1] - bo[i];
+    rown[i] = lane < L ? (uint32_t)snew[v * L + lane] : kIdMax;
+    rowo[i] = lane < L ? (uint32_t)sold[v * L + lane] : kIdMax;
+  }
+#pragma unroll
+  for (int i = 0; i < kNodesPerWave; ++i) {
+    firstn[i] = lane < dn[i] ? (uint32_t)csr_new[bn[i] + lane] : kIdMax;
+    firsto[i] = lane < dO[i] ? (uint32_t)csr_old[bo[i] + lane] : kIdMax;
+  }
+  uint64_t sum_new = 0, sum_old = 0;
+#pragma unroll
+  for (int i = 0; i < kNodesPerWave; ++i) {
+    const int64_t v = v0 + i;
+    if (v < n) {  // uniform
+      const int cn = select_list(v, p, base_new, iter, snew + v * L, rown[i], nfn[i], csr_new,
+                                 bn[i], dn[i], firstn[i], lane);
+      const int co = select_list(v, p, base_old, iter, sold + v * L, rowo[i], nfo[i], csr_old,
+                                 bo[i], dO[i], firsto[i], lane);
+      sum_new += (uint64_t)cn;
+      sum_old += (uint64_t)co;
+      if (lane == 0) {
+        cnew[v] = cn;
+        cold[v] = co;
+        // v can only sit in the sample list of a node that holds v as a forward
+        // sample (deg of them) or that v holds as one (nf): that bounds the number
+        // of joins v takes part in, hence the nearest-object results it can
+        // receive - two per join as a NEW sample, one as an OLD sample (per_new, per_old;
+        // when every pair is proposed: one per possible partner).
+        capn[v] = (uint32_t)(per_new * (dn[i] + (uint64_t)nfn[i]));
+        capo[v] = (uint32_t)(per_old * (dO[i] + (uint64_t)nfo[i]));
+      }
+    }
+  }
   if (lane == 0) {
-    cnew[v] = cn;
-    cold[v] = co;
-    counter_add(counters, C_SUMNEW, v, (uint64_t)cn);
-    counter_add(counters, C_SUMOLD, v, (uint64_t)co);
-    // v can only sit in the sample list of a node that holds v as a forward
-    // sample (deg of them) or that v holds as one (nf): that bounds the number
-    // of joins v takes part in, hence the nearest-object results it can
-    // receive - two per join as a NEW sample, one as an OLD sample (per_new, per_old;
-    // when every pair is proposed: one per possible partner).
-    capn[v] = (uint32_t)(per_new * (dn + (uint64_t)nfn));
-    capo[v] = (uint32_t)(per_old * (dO + (uint64_t)nfo));
+    counter_add(counters, C_SUMNEW, v0, sum_new);
+    counter_add(counters, C_SUMOLD, v0, sum_old);
   }
 }
 
@@ -682,7 +709,6 @@ hipError_t launch_init_random(const Shape& sh, const DevState& ds, uint64_t seed
 
 hipError_t launch_sample(const Shape& sh, const DevState& ds, uint64_t seed, uint32_t iter,
                          hipStream_t st) {
-  const dim3 grid = blocks_for_waves(sh.n);
   // forward sampling, and the reverse candidates grouped by target (two-level counting sort)
   hipError_t e = launch_sample_buckets(sh, ds, st);
   if (e != hipSuccess) return e;
@@ -691,7 +717,7 @@ hipError_t launch_sample(const Shape& sh, const DevState& ds, uint64_t seed, uin
     if (e != hipSuccess) return e;
     return launch_scan(ds.capn, ds.capo, ds.poff, ds.pslot, ds.counters, ds.scan_tmp, sh.n, st);
   }
-  k_rev_select<<<grid, kBlock, 0, st>>>(
+  k_rev_select<<<blocks_for_waves((sh.n + kNodesPerWave - 1) / kNodesPerWave), kBlock, 0, st>>>(
       sh.n, sh.p, hash_base(seed, kTagRevNew), hash_base(seed, kTagRevOld), iter, ds.snew,
       ds.sold, ds.cnew, ds.cold, ds.roff_new, ds.roff_old, ds.csr_new, ds.csr_old, ds.capn,
       ds.capo, (uint32_t)sh.slots_new_per_appearance(), (uint32_t)sh.slots_old_per_appearance(),
