@@ -122,8 +122,8 @@ __global__ __launch_bounds__(kBlock) void k_rev_select(int64_t n, int p, uint64_
     dn[i] = roff_new[v + 1] - bn[i];
     bo[i] = roff_old[v];
     dO[i] = roff_old[v + 1] - bo[i];
-    rown[i] = lane < L ? (uint32_t)snew[v * L + lane] : kIdMax;
-    rowo[i] = lane < L ? (uint32_t)sold[v * L + lane] : kIdMax;
+    rown[i] = lane < p ? (uint32_t)snew[v * L + lane] : kIdMax;  // the forward part
+    rowo[i] = lane < p ? (uint32_t)sold[v * L + lane] : kIdMax;
   }
 #pragma unroll
   for (int i = 0; i < kNodesPerWave; ++i) {
@@ -266,22 +266,14 @@ __device__ inline uint64_t half_sort_unique(uint64_t pk, int count, int lane) {
   return pk;
 }
 
-__global__ __launch_bounds__(kBlock) void k_update_pairs(int64_t n, int k, uint64_t* G,
-                                                         NodeMeta* meta, const uint64_t* pslot,
-                                                         const uint64_t* poff,
-                                                         const uint64_t* bins, uint64_t* counters) {
-  const int lane = lane_id(), l32 = lane & 31;
-  const int64_t u = wave_global_index() * 2 + (lane >> 5);
-  if (u - (lane >> 5) >= n) return;  // the whole wavefront lies beyond the last node
-  const bool live = u < n;
-  uint64_t cnt = live ? pslot[u] & kSlotCountMask : 0;
-  const uint64_t beg = live ? poff[u] : 0, cap = live ? poff[u + 1] - beg : 0;
-  uint64_t row = (live && l32 < k) ? G[u * k + l32] : kKeyMax;
+// The work on one pair of destinations (one per half): `row`, `cnt`, `beg` as loaded, `pa` /
+// `pb` the first 64 proposals of each destination (two per lane, kKeyMax beyond cnt).
+__device__ inline void update_pair(int64_t u, bool live, int k, uint64_t cnt, uint64_t beg,
+                                   uint64_t row, uint64_t pa, uint64_t pb, uint64_t* G,
+                                   NodeMeta* meta, const uint64_t* bins, uint64_t* counters,
+                                   int lane) {
+  const int l32 = lane & 31;
   if (__ballot(cnt != 0) == 0ull) return;
-  if (cnt > cap) {  // cannot happen: a segment is sized by the bound of what its node can receive
-    if (l32 == 0) counter_add(counters, C_OVERFLOW, u, cnt - cap);
-    cnt = cap;
-  }
   const uint64_t cnt_other = __shfl(cnt, lane ^ 32, kWave);
   const uint64_t rounds = cnt > cnt_other ? cnt : cnt_other;
   const uint64_t mine_mask = half_lanes(lane);
@@ -298,8 +290,10 @@ __global__ __launch_bounds__(kBlock) void k_update_pairs(int64_t n, int k, uint6
   // tests as a rule: when the survivors of both registers fit one half they go through one
   // sorting and one merging network, otherwise the second register waits for the first.
   for (uint64_t c = 0; c < rounds; c += 64) {
-    uint64_t pa = (c + l32 < cnt) ? bins[beg + c + l32] : kKeyMax;
-    uint64_t pb = (c + 32 + l32 < cnt) ? bins[beg + c + 32 + l32] : kKeyMax;
+    if (c > 0) {
+      pa = (c + l32 < cnt) ? bins[beg + c + l32] : kKeyMax;
+      pb = (c + 32 + l32 < cnt) ? bins[beg + c + 32 + l32] : kKeyMax;
+    }
     pa = half_drop_known(pa, row, k, lane);
     pb = half_drop_known(pb, row, k, lane);
     const uint64_t left_a = __ballot(pa != kKeyMax), left_b = __ballot(pb != kKeyMax);
@@ -328,11 +322,50 @@ __global__ __launch_bounds__(kBlock) void k_update_pairs(int64_t n, int k, uint6
     }
   }
   const uint64_t admitted = __ballot(l32 < k && (row & 2ull)) & mine_mask;
-  if (changed) {
+  if (changed && live) {
     if (l32 < k) G[u * k + l32] = row & ~2ull;
     if (l32 == k - 1) meta[u].kth = entry_code(row);
     if (l32 == 0) counter_add(counters, C_INSERTS, u, (uint64_t)__popcll(admitted));
   }
+}
+
+// One pair of destinations per wavefront.  (Unlike k_rev_select this kernel is bound by
+// vector-instruction issue: with two pairs per wavefront and both rounds of reads requested up
+// front it was slower, 3.4 against 3.1 ms per build on the benchmark workload.)
+constexpr int kPairsPerWave = 1;
+__global__ __launch_bounds__(kBlock) void k_update_pairs(int64_t n, int k, uint64_t* G,
+                                                         NodeMeta* meta, const uint64_t* pslot,
+                                                         const uint64_t* poff,
+                                                         const uint64_t* bins, uint64_t* counters) {
+  const int lane = lane_id(), l32 = lane & 31;
+  const int64_t u0 = wave_global_index() * (2 * kPairsPerWave) + (lane >> 5);
+  if (u0 - (lane >> 5) >= n) return;  // the whole wavefront lies beyond the last node
+  int64_t u[kPairsPerWave];
+  bool live[kPairsPerWave];
+  uint64_t cnt[kPairsPerWave], beg[kPairsPerWave], row[kPairsPerWave];
+  uint64_t pa[kPairsPerWave], pb[kPairsPerWave];
+#pragma unroll
+  for (int j = 0; j < kPairsPerWave; ++j) {
+    u[j] = u0 + 2 * j;
+    live[j] = u[j] < n;
+    cnt[j] = live[j] ? pslot[u[j]] & kSlotCountMask : 0;
+    beg[j] = live[j] ? poff[u[j]] : 0;
+    const uint64_t cap = live[j] ? poff[u[j] + 1] - beg[j] : 0;
+    row[j] = (live[j] && l32 < k) ? G[u[j] * k + l32] : kKeyMax;
+    if (cnt[j] > cap) {  // cannot happen: a segment is sized by the bound of what its node can receive
+      if (l32 == 0) counter_add(counters, C_OVERFLOW, u[j], cnt[j] - cap);
+      cnt[j] = cap;
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < kPairsPerWave; ++j) {
+    pa[j] = (l32 < cnt[j]) ? bins[beg[j] + l32] : kKeyMax;
+    pb[j] = (32 + l32 < cnt[j]) ? bins[beg[j] + 32 + l32] : kKeyMax;
+  }
+#pragma unroll
+  for (int j = 0; j < kPairsPerWave; ++j)
+    update_pair(u[j], live[j], k, cnt[j], beg[j], row[j], pa[j], pb[j], G, meta, bins, counters,
+                lane);
 }
 
 // ---------------------------------------------------------------------------
@@ -730,7 +763,7 @@ hipError_t launch_update(const Shape& sh, const DevState& ds, hipStream_t st) {
   if (sh.segments > 1) return launch_update_segmented(sh, ds, st);
   if (sh.k > kWave) return launch_update_wide(sh, ds, st);
   if (sh.k <= 32)
-    k_update_pairs<<<blocks_for_waves((sh.n + 1) / 2), kBlock, 0, st>>>(
+    k_update_pairs<<<blocks_for_waves((sh.n + 2 * kPairsPerWave - 1) / (2 * kPairsPerWave)), kBlock, 0, st>>>(
         sh.n, sh.k, ds.G, ds.meta, ds.pslot, ds.poff, ds.bins, ds.counters);
   else
     k_update<<<blocks_for_waves(sh.n), kBlock, 0, st>>>(sh.n, sh.k, ds.G, ds.meta, ds.pslot,
