@@ -152,8 +152,9 @@ const char* gnnd_last_error(const gnnd_ctx* ctx);
  * uses: GNND_JOIN_VALU, GNND_JOIN_MFMA or GNND_JOIN_GRAM (GNND_JOIN_AUTO resolved
  * at creation: the int8 matrix-core form is taken when it is exact - squared
  * L2, d <= 128, p <= 32, uint8 vectors or float32 vectors holding only integers
- * 0..255; other float32 vectors of up to 128 dimensions take GNND_JOIN_GRAM
- * where it applies; GNND_JOIN_VALU otherwise).  Negative on a NULL context. */
+ * 0..255; other float32 vectors take GNND_JOIN_GRAM where it applies (squared
+ * L2, angular, cosine; p <= 32; selective update); GNND_JOIN_VALU otherwise).
+ * Negative on a NULL context. */
 int gnnd_join_path(const gnnd_ctx* ctx);
 
 /* Stage timing without synchronising inside the loop.  gnnd_set_profiling(ctx,

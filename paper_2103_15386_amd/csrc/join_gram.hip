@@ -57,9 +57,29 @@ struct GramLds {
   unsigned long long cmask[192];  // the partners left (bit per partner)
 };
 
-// WHOLE: the dimension is a multiple of 16, every step reads 16 present dimensions
-template <int METRIC, bool WHOLE>
-__global__ __launch_bounds__(kWave) void k_join_gram(
+// Which build of the kernel takes a node with rb blocks of NEW and co blocks of OLD samples:
+// 0: no OLD samples (every node of the first iteration), 1: at most three blocks of each,
+// 2: at most two of NEW (and four of OLD: late iterations), 3: the rest.
+__host__ __device__ constexpr int gram_class(int rb, int co) {
+  return co == 0 ? 0 : (rb <= 3 && co <= 3) ? 1 : rb <= 2 ? 2 : 3;
+}
+// wavefronts per SIMD the build of a class is compiled for
+__host__ __device__ constexpr int gram_waves(int cls) { return cls == 3 ? 2 : cls == 1 ? 3 : 4; }
+// first LDS row of operand block q of a build with RBM blocks of NEW samples
+template <int RBM>
+__device__ constexpr int block_row(int q) {
+  return q < RBM ? 16 * q : 64 + 16 * (q - RBM);
+}
+
+// WHOLE: the dimension is a multiple of 16, every step reads 16 present dimensions.
+// RBM, COM: the kernel is built for nodes with at most RBM blocks of 16 NEW and COM blocks of
+// 16 OLD samples and takes the nodes of its class (gram_class) only:
+// the accumulators of all blocks and two sets of operands live in registers, and a build for
+// fewer blocks runs more wavefronts per SIMD.
+template <int METRIC, bool WHOLE, int RBM, int COM>
+__global__ __launch_bounds__(kWave)
+__attribute__((amdgpu_waves_per_eu(gram_waves(gram_class(RBM, COM)),
+                                   gram_waves(gram_class(RBM, COM))))) void k_join_gram(
     VecSrc vs, int64_t n, int p, int merge_mode, const int32_t* __restrict__ snew,
     const int32_t* __restrict__ sold, const int32_t* __restrict__ cnew,
     const int32_t* __restrict__ cold, const NodeMeta* __restrict__ meta, uint64_t* pslot,
@@ -84,6 +104,8 @@ __global__ __launch_bounds__(kWave) void k_join_gram(
   const int nn = cnew[s], no = cold[s];
   const bool do_nn = !merge_mode && nn > 1;
   if (nn == 0 || (!do_nn && no == 0)) return;  // nothing to evaluate
+  if (gram_class((nn + 15) >> 4, (no + 15) >> 4) != gram_class(RBM, COM)) return;  // another build's
+  constexpr int NB = RBM + COM;  // operand blocks: NEW blocks first, then OLD blocks
   // lane l holds NEW sample l and OLD sample l
   const int32_t idn = lane < nn ? snew[s * L + lane] : -1;
   const int32_t ido = lane < no ? sold[s * L + lane] : -1;
@@ -105,21 +127,21 @@ __global__ __launch_bounds__(kWave) void k_join_gram(
   // as long as both operands agree.  rows[q] / rows[4 + q]: this lane's row of NEW / OLD block
   // q.  An empty list place reads the node's first NEW sample instead: whatever stands in its
   // row or column of a block, the NaN weight of the place keeps it out of every result.
-  const float* rows[8];
+  const float* rows[NB];
   {
     const float* any_row = row_of(S.ids[0]) + g4;
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      const int32_t id = S.ids[(q < 4 ? 0 : 64) + 16 * (q & 3) + l16];
+    for (int q = 0; q < NB; ++q) {
+      const int32_t id = S.ids[block_row<RBM>(q) + l16];
       rows[q] = id >= 0 ? row_of(id) + g4 : any_row;
     }
   }
-  // the operands of one step: always all eight loads, so that the number of loads in flight
+  // the operands of one step: always all NB loads, so that the number of loads in flight
   // is known where the products wait for them
   auto fetch = [&](float4* f, int d0) {
     const int j = d0 + g4;
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
+    for (int q = 0; q < NB; ++q) {
       const float* src = rows[q] + d0;
       if (WHOLE) {
         f[q] = *reinterpret_cast<const float4*>(src);
@@ -139,7 +161,7 @@ __global__ __launch_bounds__(kWave) void k_join_gram(
   };
   // two steps are in flight: the first two are requested before anything else
   const int d_last = ((d - 1) / kWC) * kWC;
-  float4 opa[8], opb[8];
+  float4 opa[NB], opb[NB];
   fetch(opa, 0);
   fetch(opb, kWC < d_last ? kWC : d_last);
 
@@ -178,13 +200,13 @@ __global__ __launch_bounds__(kWave) void k_join_gram(
   // ---- 1. inner products --------------------------------------------------------------
   // acc_no[rb][cb]: NEW rows 16 rb.. x OLD rows 16 cb..; acc_nn[rb (rb + 1) / 2 + cb], cb <= rb:
   // NEW rows 16 rb.. x NEW rows 16 cb..
-  f32x4 acc_no[4][4], acc_nn[10];
+  f32x4 acc_no[RBM][COM > 0 ? COM : 1], acc_nn[RBM * (RBM + 1) / 2];
 #pragma unroll
-  for (int rb = 0; rb < 4; ++rb)
+  for (int rb = 0; rb < RBM; ++rb)
 #pragma unroll
-    for (int cb = 0; cb < 4; ++cb) acc_no[rb][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int cb = 0; cb < COM; ++cb) acc_no[rb][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-  for (int t = 0; t < 10; ++t) acc_nn[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int t = 0; t < RBM * (RBM + 1) / 2; ++t) acc_nn[t] = f32x4{0.f, 0.f, 0.f, 0.f};
   auto mfma4 = [](f32x4& acc, const float4& a, const float4& b) {
     acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, b.x, acc, 0, 0, 0);
     acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, b.y, acc, 0, 0, 0);
@@ -193,11 +215,11 @@ __global__ __launch_bounds__(kWave) void k_join_gram(
   };
   auto products = [&](const float4* op) {
 #pragma unroll
-    for (int rb = 0; rb < 4; ++rb) {
+    for (int rb = 0; rb < RBM; ++rb) {
       if (rb < RB) {  // uniform
 #pragma unroll
-        for (int cb = 0; cb < 4; ++cb)
-          if (cb < CO) mfma4(acc_no[rb][cb], op[rb], op[4 + cb]);
+        for (int cb = 0; cb < COM; ++cb)
+          if (cb < CO) mfma4(acc_no[rb][cb], op[rb], op[RBM + cb]);
         if (do_nn) {
 #pragma unroll
           for (int cb = 0; cb <= rb; ++cb) mfma4(acc_nn[rb * (rb + 1) / 2 + cb], op[rb], op[cb]);
@@ -299,10 +321,10 @@ __global__ __launch_bounds__(kWave) void k_join_gram(
   };
   auto over_blocks = [&](auto fold) {
 #pragma unroll
-    for (int rb = 0; rb < 4; ++rb) {
+    for (int rb = 0; rb < RBM; ++rb) {
       if (rb < RB) {  // uniform
 #pragma unroll
-        for (int cb = 0; cb < 4; ++cb)
+        for (int cb = 0; cb < COM; ++cb)
           if (cb < CO) fold(acc_no[rb][cb], 16 * rb, 64 + 16 * cb);
         if (do_nn) {
 #pragma unroll
@@ -366,10 +388,10 @@ __global__ __launch_bounds__(kWave) void k_join_gram(
     {
       const float* any_row = row_of(S.ids[0]) + g4;
 #pragma unroll
-      for (int q = 0; q < 8; ++q) {
-        const int r = 16 * (q & 3) + l16;
-        const int32_t id = S.ids[(q < 4 ? 0 : 64) + r];
-        const bool wanted = (((q < 4 ? m0 : m1) >> r) & 1ull) != 0;  // then id >= 0
+      for (int q = 0; q < NB; ++q) {
+        const int row = block_row<RBM>(q) + l16;
+        const int32_t id = S.ids[row];
+        const bool wanted = (((row < 64 ? m0 : m1) >> (row & 63)) & 1ull) != 0;  // then id >= 0
         rows[q] = wanted ? row_of(id) + g4 : any_row;
       }
     }
@@ -381,8 +403,8 @@ __global__ __launch_bounds__(kWave) void k_join_gram(
     auto sums = [&](const float4* op, int d0) {
       __syncthreads();  // the tile has been read
 #pragma unroll
-      for (int q = 0; q < 8; ++q)
-        *reinterpret_cast<float4*>(S.tile + ((q < 4 ? 0 : 64) + 16 * (q & 3) + l16) * kWLD + g4) = op[q];
+      for (int q = 0; q < NB; ++q)
+        *reinterpret_cast<float4*>(S.tile + (block_row<RBM>(q) + l16) * kWLD + g4) = op[q];
       __syncthreads();
       const int width = (d - d0) < kWC ? (d - d0) : kWC;
 #pragma unroll
@@ -483,9 +505,19 @@ hipError_t launch_join_gram(const Shape& sh, const DevState& ds, bool merge_mode
   const int mm = merge_mode ? 1 : 0;
 #define GNND_GRAM_ARGS vs, sh.n, sh.p, mm, ds.snew, ds.sold, ds.cnew, ds.cold, ds.meta, ds.pslot, \
                        slots, ds.bins, ds.counters
-#define GNND_GRAM_LAUNCH(M)                                                              \
-  if (sh.d % kWC == 0) k_join_gram<M, true><<<grid, kWave, 0, st>>>(GNND_GRAM_ARGS); \
-  else k_join_gram<M, false><<<grid, kWave, 0, st>>>(GNND_GRAM_ARGS);
+  // four builds over all nodes, each for its class of nodes (gram_class); in a merge no node
+  // is without OLD samples and has work to do
+#define GNND_GRAM_CLASSES(M, W)                                                   \
+  if (!merge_mode) k_join_gram<M, W, 4, 0><<<grid, kWave, 0, st>>>(GNND_GRAM_ARGS); \
+  k_join_gram<M, W, 3, 3><<<grid, kWave, 0, st>>>(GNND_GRAM_ARGS);                  \
+  k_join_gram<M, W, 2, 4><<<grid, kWave, 0, st>>>(GNND_GRAM_ARGS);                  \
+  k_join_gram<M, W, 4, 4><<<grid, kWave, 0, st>>>(GNND_GRAM_ARGS);
+#define GNND_GRAM_LAUNCH(M)                      \
+  if (sh.d % kWC == 0) {                         \
+    GNND_GRAM_CLASSES(M, true)                   \
+  } else {                                       \
+    GNND_GRAM_CLASSES(M, false)                  \
+  }
   switch (sh.metric) {
     case kL2F32: GNND_GRAM_LAUNCH(kL2F32) break;
     case kAngularF32: GNND_GRAM_LAUNCH(kAngularF32) break;
@@ -493,6 +525,7 @@ hipError_t launch_join_gram(const Shape& sh, const DevState& ds, bool merge_mode
     default: return hipErrorInvalidValue;  // no inner-product form for the other metrics
   }
 #undef GNND_GRAM_LAUNCH
+#undef GNND_GRAM_CLASSES
 #undef GNND_GRAM_ARGS
   return hipGetLastError();
 }
