@@ -44,7 +44,6 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 // rows 64..127 the OLD samples; slots 0..63 stand for "NEW sample towards NEW", 64..127 for
 // "NEW sample towards OLD", 128..191 for "OLD sample towards NEW".
 struct GramLds {
-  float tile[128 * kWLD];  // step 4: 16 dimensions of every vector
   int32_t ids[128];
   float norms[128];   // squared norms
   // what the approximate distance needs of a sample: its squared norm (cosine: one over its
@@ -85,7 +84,11 @@ __attribute__((amdgpu_waves_per_eu(gram_waves(gram_class(RBM, COM)),
     const int32_t* __restrict__ cold, const NodeMeta* __restrict__ meta, uint64_t* pslot,
     uint64_t slots, uint64_t* __restrict__ bins, uint64_t* counters) {
   using TR = JoinTraits<METRIC>;
+  constexpr int NB = RBM + COM;  // operand blocks: NEW blocks first, then OLD blocks
   __shared__ __attribute__((aligned(16))) GramLds S;
+  // step 4: 16 dimensions of every vector the build can hold, operand block after operand block
+  __shared__ __attribute__((aligned(16))) float tile[NB * 16 * kWLD];
+  auto tile_row = [](int row) { return row < 64 ? row : row - 64 + 16 * RBM; };
   constexpr uint32_t kNone = 0xffffffffu;
   const float kInf = __uint_as_float(0x7f800000u), kNaN = __uint_as_float(0x7fc00000u);
 
@@ -105,7 +108,6 @@ __attribute__((amdgpu_waves_per_eu(gram_waves(gram_class(RBM, COM)),
   const bool do_nn = !merge_mode && nn > 1;
   if (nn == 0 || (!do_nn && no == 0)) return;  // nothing to evaluate
   if (gram_class((nn + 15) >> 4, (no + 15) >> 4) != gram_class(RBM, COM)) return;  // another build's
-  constexpr int NB = RBM + COM;  // operand blocks: NEW blocks first, then OLD blocks
   // lane l holds NEW sample l and OLD sample l
   const int32_t idn = lane < nn ? snew[s * L + lane] : -1;
   const int32_t ido = lane < no ? sold[s * L + lane] : -1;
@@ -404,20 +406,21 @@ __attribute__((amdgpu_waves_per_eu(gram_waves(gram_class(RBM, COM)),
       __syncthreads();  // the tile has been read
 #pragma unroll
       for (int q = 0; q < NB; ++q)
-        *reinterpret_cast<float4*>(S.tile + (block_row<RBM>(q) + l16) * kWLD + g4) = op[q];
+        *reinterpret_cast<float4*>(tile + (16 * q + l16) * kWLD + g4) = op[q];
       __syncthreads();
       const int width = (d - d0) < kWC ? (d - d0) : kWC;
 #pragma unroll
       for (int t = 0; t < 3; ++t) {
         if (lanes_with[t][0]) {  // uniform
-          const float* pa = S.tile + (t == 2 ? 64 + lane : lane) * kWLD;
+          const float* pa = tile + tile_row(t == 2 ? 64 + lane : lane) * kWLD;
           int j = 0;
           for (; j + 3 < width; j += 4) {
             const float4 va = *reinterpret_cast<const float4*>(pa + j);
 #pragma unroll
             for (int i = 0; i < kWCand; ++i) {
               if (lanes_with[t][i]) {
-                const float4 vb = *reinterpret_cast<const float4*>(S.tile + crow[t][i] * kWLD + j);
+                const float4 vb =
+                    *reinterpret_cast<const float4*>(tile + tile_row(crow[t][i]) * kWLD + j);
                 TR::step(va.x, vb.x, sum[t][i]);
                 TR::step(va.y, vb.y, sum[t][i]);
                 TR::step(va.z, vb.z, sum[t][i]);
@@ -428,7 +431,7 @@ __attribute__((amdgpu_waves_per_eu(gram_waves(gram_class(RBM, COM)),
           for (; j < width; ++j) {
 #pragma unroll
             for (int i = 0; i < kWCand; ++i)
-              if (lanes_with[t][i]) TR::step(pa[j], S.tile[crow[t][i] * kWLD + j], sum[t][i]);
+              if (lanes_with[t][i]) TR::step(pa[j], tile[tile_row(crow[t][i]) * kWLD + j], sum[t][i]);
           }
         }
       }
