@@ -339,8 +339,8 @@ def main():
     else:
         roof["other_bound"] = other
     roof["kernel"] = kernel_name
-    if gram:  # one launch per class of nodes; the figures are per iteration, all four together
-        roof["launches_per_iteration"] = 4
+    if gram:  # one launch per class of nodes; the figures are per iteration, all seven together
+        roof["launches_per_iteration"] = 7
     roof["avg_launch_ms"] = avg_join_s * 1e3
     roof["algorithmic_bytes_per_launch"] = alg_bytes
 

@@ -41,7 +41,7 @@ struct Layout {
   size_t off_G, off_kth, off_snew, off_sold, off_cnew, off_cold, off_ron,
       off_roo, off_csn, off_cso, off_capn, off_capo, off_pslot, off_poff, off_bins, off_scan,
       off_cnt, off_snap, off_aside, off_shadow, off_norms, off_flag, off_bkc, off_bko, off_stg_ent,
-      off_stg_cur, total;
+      off_stg_cur, off_gram_nodes, off_gram_count, total;
 };
 
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -149,6 +149,9 @@ Layout make_layout(const gnnd_params* q, bool with_aside) {
   const bool staged = stage_possible(q);
   L.off_stg_ent = take(staged ? n * slots_per_node * 8 : 0);
   L.off_stg_cur = take(staged ? (size_t)kStageBuckets * 8 : 0);
+  const bool gram = gram_possible(q);
+  L.off_gram_nodes = take(gram ? (size_t)kGramClasses * n * 4 : 0);
+  L.off_gram_count = take(gram ? 256 : 0);
   L.total = o;
   return L;
 }
@@ -222,6 +225,9 @@ void bind(gnnd_ctx* c, const Layout& L) {
   const bool staged = stage_possible(&c->prm);
   d.stg_ent = staged ? (uint64_t*)(w + L.off_stg_ent) : nullptr;
   d.stg_cur = staged ? (unsigned long long*)(w + L.off_stg_cur) : nullptr;
+  const bool gram = gram_possible(&c->prm);
+  d.gram_nodes = gram ? (int32_t*)(w + L.off_gram_nodes) : nullptr;
+  d.gram_count = gram ? (uint32_t*)(w + L.off_gram_count) : nullptr;
 }
 
 // Fill in a default-constructed context (no allocation of any kind): layout,
@@ -275,6 +281,10 @@ int init_ctx(gnnd_ctx* c, const gnnd_params* prm, const Layout& L, const void* v
     c->use_mfma = (bad == 0);
   }
   c->use_gram = gram_possible(prm) && !c->use_mfma;
+  if (c->use_gram) {
+    e = launch_gram_norms(c->sh, c->ds, c->stream);
+    if (e != hipSuccess) return hip_fail(nullptr, e, "row norm kernel");
+  }
   if ((prm->join_path == GNND_JOIN_MFMA || prm->join_path == GNND_JOIN_MFMA_DIRECT) && !c->use_mfma)
     return fail(nullptr, GNND_EINVAL,
                 may_sync ? "GNND_JOIN_MFMA needs d <= 128, p <= 32 and uint8 vectors or float32 vectors "

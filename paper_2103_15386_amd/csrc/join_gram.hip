@@ -25,6 +25,8 @@
 //     way, and pass through an LDS tile 16 dimensions at a time, where one lane
 //     per sample accumulates the canonical distances of the partners left; the
 //     smallest (distance, id) is the result.
+#include <stddef.h>
+
 #include "device_utils.hpp"
 #include "kernels.hpp"
 
@@ -56,58 +58,67 @@ struct GramLds {
   unsigned long long cmask[192];  // the partners left (bit per partner)
 };
 
-// Which build of the kernel takes a node with rb blocks of NEW and co blocks of OLD samples:
-// 0: no OLD samples (every node of the first iteration), 1: at most three blocks of each,
-// 2: at most two of NEW (and four of OLD: late iterations), 3: the rest.
-__host__ __device__ constexpr int gram_class(int rb, int co) {
-  return co == 0 ? 0 : (rb <= 3 && co <= 3) ? 1 : rb <= 2 ? 2 : 3;
+// The builds of the kernel: build c holds up to rbm blocks of 16 NEW and com blocks of 16 OLD
+// samples and is compiled for `waves` wavefronts per SIMD.  The shapes follow what a
+// construction meets: every node of the first iteration has NEW samples only; in the next few
+// iterations most have 33 to 48 NEW samples and up to 16 OLD ones; later the NEW samples dwindle
+// and the OLD ones fill up.
+struct GramShape {
+  int rbm, com, waves;
+};
+__host__ __device__ constexpr GramShape gram_shape(int cls) {
+  return cls == 0   ? GramShape{4, 0, 4}
+         : cls == 1 ? GramShape{1, 2, 4}
+         : cls == 2 ? GramShape{3, 1, 4}
+         : cls == 3 ? GramShape{1, 4, 4}
+         : cls == 4 ? GramShape{2, 4, 3}
+         : cls == 5 ? GramShape{4, 2, 3}
+                    : GramShape{4, 4, 2};
 }
-// wavefronts per SIMD the build of a class is compiled for
-__host__ __device__ constexpr int gram_waves(int cls) { return cls == 3 ? 2 : cls == 1 ? 3 : 4; }
+// Which build takes a node with rb blocks of NEW and co blocks of OLD samples: the cheapest
+// one that holds them.
+__host__ __device__ constexpr int gram_class(int rb, int co) {
+  return co == 0 ? 0 : (rb <= 1 && co <= 2) ? 1 : (rb <= 3 && co <= 1) ? 2 : rb <= 1 ? 3
+         : rb <= 2 ? 4 : co <= 2 ? 5 : 6;
+}
+static_assert(kGramClasses == 7, "gram_shape and gram_class list seven builds");
 // first LDS row of operand block q of a build with RBM blocks of NEW samples
 template <int RBM>
 __device__ constexpr int block_row(int q) {
   return q < RBM ? 16 * q : 64 + 16 * (q - RBM);
 }
 
-// WHOLE: the dimension is a multiple of 16, every step reads 16 present dimensions.
-// RBM, COM: the kernel is built for nodes with at most RBM blocks of 16 NEW and COM blocks of
-// 16 OLD samples and takes the nodes of its class (gram_class) only:
-// the accumulators of all blocks and two sets of operands live in registers, and a build for
-// fewer blocks runs more wavefronts per SIMD.
+// What a wavefront has counted over its nodes (the same in every lane).
+struct GramTally {
+  uint64_t found = 0, passed = 0, overflow = 0, evals = 0;
+};
+
 template <int METRIC, bool WHOLE, int RBM, int COM>
-__global__ __launch_bounds__(kWave)
-__attribute__((amdgpu_waves_per_eu(gram_waves(gram_class(RBM, COM)),
-                                   gram_waves(gram_class(RBM, COM))))) void k_join_gram(
-    VecSrc vs, int64_t n, int p, int merge_mode, const int32_t* __restrict__ snew,
-    const int32_t* __restrict__ sold, const int32_t* __restrict__ cnew,
-    const int32_t* __restrict__ cold, const NodeMeta* __restrict__ meta, uint64_t* pslot,
-    uint64_t slots, uint64_t* __restrict__ bins, uint64_t* counters) {
+__device__ __forceinline__ void gram_node(GramLds& S, float* tile, const VecSrc& vs, int64_t s,
+                                          int p, int merge_mode,
+                                          const int32_t* __restrict__ snew,
+                                          const int32_t* __restrict__ sold, int nn, int no,
+                                          const NodeMeta* __restrict__ meta, uint64_t* pslot,
+                                          uint64_t slots, uint64_t* __restrict__ bins,
+                                          GramTally& tally) {
   using TR = JoinTraits<METRIC>;
   constexpr int NB = RBM + COM;  // operand blocks: NEW blocks first, then OLD blocks
-  __shared__ __attribute__((aligned(16))) GramLds S;
-  // step 4: 16 dimensions of every vector the build can hold, operand block after operand block
-  __shared__ __attribute__((aligned(16))) float tile[NB * 16 * kWLD];
   auto tile_row = [](int row) { return row < 64 ? row : row - 64 + 16 * RBM; };
   constexpr uint32_t kNone = 0xffffffffu;
   const float kInf = __uint_as_float(0x7f800000u), kNaN = __uint_as_float(0x7fc00000u);
-
-  const int64_t s = block_linear();
-  if (s >= n) return;  // a folded grid may be longer than the node list
-  const int lane = threadIdx.x;
+  // (taken anew for every node: what depends on the lane is worked out again per node
+  // instead of being held in registers across the loop over nodes)
+  int lane = threadIdx.x;
+  asm volatile("" : "+v"(lane));
   const int L = 2 * p;
   const int64_t split = vs.split;
   const int d = vs.d;
   const float* const set_a = reinterpret_cast<const float*>(vs.a);
   const float* const set_b = reinterpret_cast<const float*>(vs.b);
-  const float* const norms = vs.norms;
   auto row_of = [=](int32_t id) {
     return (int64_t)id < split ? set_a + (int64_t)id * d : set_b + ((int64_t)id - split) * d;
   };
-  const int nn = cnew[s], no = cold[s];
   const bool do_nn = !merge_mode && nn > 1;
-  if (nn == 0 || (!do_nn && no == 0)) return;  // nothing to evaluate
-  if (gram_class((nn + 15) >> 4, (no + 15) >> 4) != gram_class(RBM, COM)) return;  // another build's
   // lane l holds NEW sample l and OLD sample l
   const int32_t idn = lane < nn ? snew[s * L + lane] : -1;
   const int32_t ido = lane < no ? sold[s * L + lane] : -1;
@@ -168,8 +179,12 @@ __attribute__((amdgpu_waves_per_eu(gram_waves(gram_class(RBM, COM)),
   fetch(opb, kWC < d_last ? kWC : d_last);
 
   {
-    const uint32_t kthn = idn >= 0 ? meta[idn].kth : 0u, ktho = ido >= 0 ? meta[ido].kth : 0u;
-    const float nrmn = idn >= 0 ? norms[idn] : 0.f, nrmo = ido >= 0 ? norms[ido] : 0.f;
+    // one 8-byte record per sample: the threshold of its list and its squared norm
+    // (launch_gram_norms put the float's bits where the int8 join keeps its integer norm)
+    const uint2 mn = idn >= 0 ? *reinterpret_cast<const uint2*>(&meta[idn]) : make_uint2(0u, 0u);
+    const uint2 mo = ido >= 0 ? *reinterpret_cast<const uint2*>(&meta[ido]) : make_uint2(0u, 0u);
+    const uint32_t kthn = mn.x, ktho = mo.x;
+    const float nrmn = __uint_as_float(mn.y), nrmo = __uint_as_float(mo.y);
     auto weight_of = [&](int32_t id, float nrm) {
       float w = nrm;
       if (METRIC == kCosineF32) w = nrm > 0.f ? 1.0f / sqrtf(nrm) : 0.f;
@@ -481,40 +496,152 @@ __attribute__((amdgpu_waves_per_eu(gram_waves(gram_class(RBM, COM)),
     n_pass += (uint32_t)__popcll(__ballot(pass));
     n_over += (uint32_t)__popcll(__ballot(over));
   }
-  if (lane == 0) {
-    uint64_t* cs = counters + (s & (kStripes - 1)) * C_SLOTS;
-    if (n_pass) atomicAdd(reinterpret_cast<unsigned long long*>(cs + C_PASSED),
-                          (unsigned long long)n_pass);
-    if (n_over) atomicAdd(reinterpret_cast<unsigned long long*>(cs + C_OVERFLOW),
-                          (unsigned long long)n_over);
-    if (n_found) atomicAdd(reinterpret_cast<unsigned long long*>(cs + C_PROPS),
-                           (unsigned long long)n_found);
-    // pairs that count as evaluated: NEW x OLD without the objects sampled as both (a merge:
-    // pairs across the two sets), and all pairs of NEW samples
-    const uint64_t fa = new_first, fb = old_first;
-    uint64_t ev = merge_mode ? fa * ((uint64_t)no - fb) + ((uint64_t)nn - fa) * fb
-                             : (uint64_t)nn * no - n_dup;
-    if (do_nn) ev += (uint64_t)nn * (nn - 1) / 2;
-    if (ev) atomicAdd(reinterpret_cast<unsigned long long*>(cs + C_EVALS), (unsigned long long)ev);
+  tally.found += n_found;
+  tally.passed += n_pass;
+  tally.overflow += n_over;
+  // pairs that count as evaluated: NEW x OLD without the objects sampled as both (a merge:
+  // pairs across the two sets), and all pairs of NEW samples
+  const uint64_t fa = new_first, fb = old_first;
+  tally.evals += merge_mode ? fa * ((uint64_t)no - fb) + ((uint64_t)nn - fa) * fb
+                            : (uint64_t)nn * no - n_dup;
+  if (do_nn) tally.evals += (uint64_t)nn * (nn - 1) / 2;
+}
+
+// The nodes that have something to evaluate, listed by class (list c at nodes + c n, its
+// length in count[c]; the order inside a list is of no consequence).  A workgroup takes
+// kClassifyNodes consecutive nodes, numbers those of each class in LDS and reserves their
+// places with one addition per class.
+constexpr int kClassifyPerThread = 16;
+constexpr int kClassifyNodes = 256 * kClassifyPerThread;
+__global__ __launch_bounds__(256) void k_gram_classify(int64_t n, int merge_mode,
+                                                       const int32_t* __restrict__ cnew,
+                                                       const int32_t* __restrict__ cold,
+                                                       int32_t* nodes, uint32_t* count) {
+  __shared__ uint32_t here[kGramClasses], base[kGramClasses];
+  const int64_t first = block_linear() * kClassifyNodes;
+  if (threadIdx.x < kGramClasses) here[threadIdx.x] = 0u;
+  __syncthreads();
+  int32_t place[kClassifyPerThread];  // class + kGramClasses x (number within the workgroup)
+#pragma unroll
+  for (int j = 0; j < kClassifyPerThread; ++j) {
+    const int64_t s = first + j * 256 + threadIdx.x;
+    place[j] = -1;
+    if (s < n) {
+      const int nn = cnew[s], no = cold[s];
+      const bool do_nn = !merge_mode && nn > 1;
+      if (nn != 0 && (do_nn || no != 0)) {
+        const int cls = gram_class((nn + 15) >> 4, (no + 15) >> 4);
+        place[j] = cls + kGramClasses * (int32_t)atomicAdd(&here[cls], 1u);
+      }
+    }
   }
+  __syncthreads();
+  if (threadIdx.x < kGramClasses && here[threadIdx.x] != 0u)
+    base[threadIdx.x] = atomicAdd(&count[threadIdx.x], here[threadIdx.x]);
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < kClassifyPerThread; ++j) {
+    if (place[j] >= 0) {
+      const int cls = place[j] % kGramClasses;
+      nodes[(int64_t)cls * n + base[cls] + place[j] / kGramClasses] =
+          (int32_t)(first + j * 256 + threadIdx.x);
+    }
+  }
+}
+
+// WHOLE: the dimension is a multiple of 16, every step reads 16 present dimensions.
+// CLS: the build (gram_shape); it takes the nodes of its class from that class's list.  The
+// accumulators of all blocks and two sets of operands live in registers, and a build for
+// fewer blocks runs more wavefronts per SIMD and reads and multiplies fewer empty blocks.
+// Persistent wavefronts: wavefront w takes the list's places w, w + (number of wavefronts), ...
+template <int METRIC, bool WHOLE, int CLS>
+__global__ __launch_bounds__(kWave)
+__attribute__((amdgpu_waves_per_eu(gram_shape(CLS).waves, gram_shape(CLS).waves))) void k_join_gram(
+    VecSrc vs, int64_t n, int p, int merge_mode, const int32_t* __restrict__ snew,
+    const int32_t* __restrict__ sold, const int32_t* __restrict__ cnew,
+    const int32_t* __restrict__ cold, const NodeMeta* __restrict__ meta, uint64_t* pslot,
+    uint64_t slots, uint64_t* __restrict__ bins, uint64_t* counters,
+    const int32_t* __restrict__ nodes, const uint32_t* __restrict__ count) {
+  constexpr int RBM = gram_shape(CLS).rbm, COM = gram_shape(CLS).com;
+  constexpr int NB = RBM + COM;
+  constexpr int cls = CLS;
+  __shared__ __attribute__((aligned(16))) GramLds S;
+  // step 4: 16 dimensions of every vector the build can hold, operand block after operand block
+  __shared__ __attribute__((aligned(16))) float tile[NB * 16 * kWLD];
+  const uint32_t mine = count[cls];
+  const int32_t* const list = nodes + (int64_t)cls * n;
+  GramTally tally;
+  for (uint32_t i = blockIdx.x; i < mine; i += gridDim.x) {
+    const int64_t s = list[i];
+    gram_node<METRIC, WHOLE, RBM, COM>(S, tile, vs, s, p, merge_mode, snew, sold, cnew[s], cold[s],
+                                       meta, pslot, slots, bins, tally);
+    __syncthreads();  // the LDS arrays are taken over by the next node
+  }
+  if (threadIdx.x == 0) {
+    uint64_t* cs = counters + (blockIdx.x & (kStripes - 1)) * C_SLOTS;
+    if (tally.passed) atomicAdd(reinterpret_cast<unsigned long long*>(cs + C_PASSED),
+                                (unsigned long long)tally.passed);
+    if (tally.overflow) atomicAdd(reinterpret_cast<unsigned long long*>(cs + C_OVERFLOW),
+                                  (unsigned long long)tally.overflow);
+    if (tally.found) atomicAdd(reinterpret_cast<unsigned long long*>(cs + C_PROPS),
+                               (unsigned long long)tally.found);
+    if (tally.evals) atomicAdd(reinterpret_cast<unsigned long long*>(cs + C_EVALS),
+                               (unsigned long long)tally.evals);
+  }
+}
+
+__global__ __launch_bounds__(256) void k_gram_norms(int64_t n, const float* __restrict__ norms,
+                                                    NodeMeta* meta) {
+  const int64_t s = block_linear() * 256 + threadIdx.x;
+  if (s < n) meta[s].norm = (int32_t)__float_as_uint(norms[s]);
+}
+
+int compute_units() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+      cus = v;
+    else
+      cus = 256;
+  }
+  return cus;
 }
 
 }  // namespace
 
+hipError_t launch_gram_norms(const Shape& sh, const DevState& ds, hipStream_t st) {
+  static_assert(sizeof(NodeMeta) == 8 && offsetof(NodeMeta, kth) == 0 && offsetof(NodeMeta, norm) == 4,
+                "k_join_gram reads a NodeMeta as (kth, norm bits)");
+  k_gram_norms<<<grid_blocks((sh.n + 255) / 256), 256, 0, st>>>(sh.n, sh.norms, ds.meta);
+  return hipGetLastError();
+}
+
 hipError_t launch_join_gram(const Shape& sh, const DevState& ds, bool merge_mode, hipStream_t st) {
   VecSrc vs{sh.vec_a, sh.vec_b, sh.split, sh.d, sh.norms};
-  const dim3 grid = grid_blocks(sh.n);
   const uint64_t slots = (uint64_t)sh.slots();
   const int mm = merge_mode ? 1 : 0;
+  // the nodes with work to do, by class
+  hipError_t e = launch_zero_u32(ds.gram_count, kGramClasses, st);
+  if (e != hipSuccess) return e;
+  k_gram_classify<<<grid_blocks((sh.n + kClassifyNodes - 1) / kClassifyNodes), 256, 0, st>>>(
+      sh.n, mm, ds.cnew, ds.cold, ds.gram_nodes, ds.gram_count);
+  // one build per class, each with about four sets of resident wavefronts (the lists' lengths
+  // are known on the device only) and never more wavefronts than nodes
+  const int64_t cap = (int64_t)64 * compute_units();
+  const unsigned grid = (unsigned)(sh.n < cap ? sh.n : cap);
 #define GNND_GRAM_ARGS vs, sh.n, sh.p, mm, ds.snew, ds.sold, ds.cnew, ds.cold, ds.meta, ds.pslot, \
-                       slots, ds.bins, ds.counters
-  // four builds over all nodes, each for its class of nodes (gram_class); in a merge no node
-  // is without OLD samples and has work to do
-#define GNND_GRAM_CLASSES(M, W)                                                   \
-  if (!merge_mode) k_join_gram<M, W, 4, 0><<<grid, kWave, 0, st>>>(GNND_GRAM_ARGS); \
-  k_join_gram<M, W, 3, 3><<<grid, kWave, 0, st>>>(GNND_GRAM_ARGS);                  \
-  k_join_gram<M, W, 2, 4><<<grid, kWave, 0, st>>>(GNND_GRAM_ARGS);                  \
-  k_join_gram<M, W, 4, 4><<<grid, kWave, 0, st>>>(GNND_GRAM_ARGS);
+                       slots, ds.bins, ds.counters, ds.gram_nodes, ds.gram_count
+  // (in a merge no node without OLD samples has work to do)
+#define GNND_GRAM_CLASSES(M, W)                                                \
+  if (!merge_mode) k_join_gram<M, W, 0><<<grid, kWave, 0, st>>>(GNND_GRAM_ARGS); \
+  k_join_gram<M, W, 1><<<grid, kWave, 0, st>>>(GNND_GRAM_ARGS);                  \
+  k_join_gram<M, W, 2><<<grid, kWave, 0, st>>>(GNND_GRAM_ARGS);                  \
+  k_join_gram<M, W, 3><<<grid, kWave, 0, st>>>(GNND_GRAM_ARGS);                  \
+  k_join_gram<M, W, 4><<<grid, kWave, 0, st>>>(GNND_GRAM_ARGS);                  \
+  k_join_gram<M, W, 5><<<grid, kWave, 0, st>>>(GNND_GRAM_ARGS);                  \
+  k_join_gram<M, W, 6><<<grid, kWave, 0, st>>>(GNND_GRAM_ARGS);
 #define GNND_GRAM_LAUNCH(M)                      \
   if (sh.d % kWC == 0) {                         \
     GNND_GRAM_CLASSES(M, true)                   \

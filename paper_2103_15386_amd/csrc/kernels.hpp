@@ -24,7 +24,8 @@ constexpr uint64_t kSlotCountMask = (1ull << kSlotCountBits) - 1;
 // What the join gathers per sampled object besides its vector, kept small (8
 // bytes, 8 MB per million nodes) so that the array stays cache resident: the
 // distance code of its list's last entry (nothing farther can enter) and the
-// squared norm of its int8 row.
+// squared norm of its int8 row (int8 join) or the bits of the float32 squared
+// norm of its row (float32 matrix-core join).
 struct alignas(8) NodeMeta {
   uint32_t kth;
   int32_t norm;
@@ -58,7 +59,12 @@ struct DevState {
   // them into the destinations' segments of `bins`
   uint64_t* stg_ent;   // slots: staged results (see stage_record), bucket regions laid out like bins
   unsigned long long* stg_cur;  // kStageBuckets: results that have reached each bucket region
+  // float32 matrix-core join (NULL when it is not in use): the nodes that have work to do,
+  // listed per class of node - kGramClasses lists of n places - and the lists' lengths
+  int32_t* gram_nodes;
+  uint32_t* gram_count;
 };
+constexpr int kGramClasses = 7;
 
 // Staged hand-out: destinations are cut into at most kStageBuckets buckets of 2^tb
 // consecutive ids; a workgroup of the join keeps kStageSlots results per bucket in LDS.
@@ -109,6 +115,9 @@ hipError_t launch_sample(const Shape& sh, const DevState& ds, uint64_t seed, uin
                          hipStream_t st);
 hipError_t launch_join(const Shape& sh, const DevState& ds, int path, bool merge_mode,
                        hipStream_t st);
+// The float32 matrix-core join reads a sample's squared norm from its NodeMeta record (bits of
+// the float in `norm`): copied there from sh.norms once the join path is chosen.
+hipError_t launch_gram_norms(const Shape& sh, const DevState& ds, hipStream_t st);
 // float32 vectors, metrics that are functions of an inner product and the norms (sh.norms
 // must be set): inner products on the matrix cores, canonical distances for the results
 hipError_t launch_join_gram(const Shape& sh, const DevState& ds, bool merge_mode, hipStream_t st);

@@ -115,6 +115,42 @@ GRAM_CASES = [n for n, c in CASES.items()
               if c[1] in (og.L2SQ_F32, og.ANGULAR_F32, og.COSINE_F32) and c[3] <= 32]
 
 
+
+def _gram_build_of(rb, co):
+    """Which of its seven builds the float matrix-core join uses for a node with rb blocks of
+    16 NEW and co blocks of 16 OLD samples (restated from the kernel's rule, only to check
+    below that the parity cases exercise every build)."""
+    if co == 0:
+        return 0
+    if rb <= 1 and co <= 2:
+        return 1
+    if rb <= 3 and co <= 1:
+        return 2
+    if rb <= 1:
+        return 3
+    if rb <= 2:
+        return 4
+    return 5 if co <= 2 else 6
+
+
+def test_gram_parity_cases_reach_every_build_of_the_kernel():
+    """The case "sift_cut" (checked stage by stage against the oracle below) has nodes for each
+    of the seven builds of the float matrix-core join."""
+    amd = _amd()
+    gen, metric, k, p, iters = CASES["sift_cut"]
+    ctx = amd.Gnnd(_dev(gen()), k, p, metric, SEED, amd.JOIN_GRAM)
+    ctx.init_random()
+    seen = set()
+    for _ in range(iters):
+        ctx.step_sample()
+        _, cnew, _, cold = [t.cpu().numpy() for t in ctx.samples()]
+        work = (cnew > 1) | ((cnew > 0) & (cold > 0))
+        seen |= {_gram_build_of(int(a), int(b))
+                 for a, b in zip((cnew[work] + 15) >> 4, (cold[work] + 15) >> 4)}
+        ctx.step_join()
+        ctx.step_update(False)
+    assert seen == set(range(7)), seen
+
 # "all": the variant that proposes every evaluated pair (no selective update)
 ALL_PAIRS_CASES = ["uniform_c1", "u8_cut", "deep_cut_angular", "tiny_n", "k100_angular",
                    "cosine_ragged_d11_zero_rows"]
