@@ -149,34 +149,37 @@ __device__ __forceinline__ void gram_node(GramLds& S, float* tile, const VecSrc&
       rows[q] = id >= 0 ? row_of(id) + g4 : any_row;
     }
   }
-  // the operands of one step: always all NB loads, so that the number of loads in flight
-  // is known where the products wait for them
-  auto fetch = [&](float4* f, int d0) {
-    const int j = d0 + g4;
+  // The operands of two steps, 32 dimensions of every row, are requested together: the two
+  // 64-byte pieces of a row are the halves of one 128-byte line where rows are aligned to
+  // lines, and memory serves a line requested at once faster than its halves requested one
+  // after the other (measured on random rows: 6.5 against 5.5 TB/s).  Always all 2 NB loads,
+  // so that the number of loads in flight is known where the products wait for them; where
+  // the vector ends after the first of the two steps, the second reads that step once more.
+  const int d_last = ((d - 1) / kWC) * kWC;
+  auto fetch_one = [&](const float* src, int j) {
+    if (WHOLE) return *reinterpret_cast<const float4*>(src);
+    // dimensions beyond the last one count as zeros
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (aligned && j + 3 < d) {
+      v = *reinterpret_cast<const float4*>(src);
+    } else {
+      if (j + 0 < d) v.x = src[0];
+      if (j + 1 < d) v.y = src[1];
+      if (j + 2 < d) v.z = src[2];
+      if (j + 3 < d) v.w = src[3];
+    }
+    return v;
+  };
+  auto fetch2 = [&](float4* fa, float4* fb, int d0) {
+    const int d1 = d0 + kWC < d_last ? d0 + kWC : d_last;
 #pragma unroll
     for (int q = 0; q < NB; ++q) {
-      const float* src = rows[q] + d0;
-      if (WHOLE) {
-        f[q] = *reinterpret_cast<const float4*>(src);
-      } else {  // dimensions beyond the last one count as zeros
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (aligned && j + 3 < d) {
-          v = *reinterpret_cast<const float4*>(src);
-        } else {
-          if (j + 0 < d) v.x = src[0];
-          if (j + 1 < d) v.y = src[1];
-          if (j + 2 < d) v.z = src[2];
-          if (j + 3 < d) v.w = src[3];
-        }
-        f[q] = v;
-      }
+      fa[q] = fetch_one(rows[q] + d0, d0 + g4);
+      fb[q] = fetch_one(rows[q] + d1, d1 + g4);
     }
   };
-  // two steps are in flight: the first two are requested before anything else
-  const int d_last = ((d - 1) / kWC) * kWC;
   float4 opa[NB], opb[NB];
-  fetch(opa, 0);
-  fetch(opb, kWC < d_last ? kWC : d_last);
+  fetch2(opa, opb, 0);
 
   {
     // one 8-byte record per sample: the threshold of its list and its squared norm
@@ -244,17 +247,13 @@ __device__ __forceinline__ void gram_node(GramLds& S, float* tile, const VecSrc&
       }
     }
   };
-  // steps 0, 2, 4, ... use opa, steps 1, 3, ... opb; a set is requested again (two steps
-  // ahead, or the last step once more where the vector ends) as soon as its products are done
+  // steps 0, 2, 4, ... use opa, steps 1, 3, ... opb
   for (int d0 = 0;;) {
     products(opa);
-    d0 += kWC;
+    if (d0 + kWC < d) products(opb);
+    d0 += 2 * kWC;
     if (d0 >= d) break;
-    fetch(opa, d0 + kWC < d_last ? d0 + kWC : d_last);
-    products(opb);
-    d0 += kWC;
-    if (d0 >= d) break;
-    fetch(opb, d0 + kWC < d_last ? d0 + kWC : d_last);
+    fetch2(opa, opb, d0);
   }
 
   // ---- 2. + 3. partners that may be the nearest one --------------------------------------
@@ -451,17 +450,13 @@ __device__ __forceinline__ void gram_node(GramLds& S, float* tile, const VecSrc&
         }
       }
     };
-    fetch(opa, 0);
-    fetch(opb, kWC < d_last ? kWC : d_last);
+    fetch2(opa, opb, 0);
     for (int d0 = 0;;) {
       sums(opa, d0);
-      d0 += kWC;
+      if (d0 + kWC < d) sums(opb, d0 + kWC);
+      d0 += 2 * kWC;
       if (d0 >= d) break;
-      fetch(opa, d0 + kWC < d_last ? d0 + kWC : d_last);
-      sums(opb, d0);
-      d0 += kWC;
-      if (d0 >= d) break;
-      fetch(opb, d0 + kWC < d_last ? d0 + kWC : d_last);
+      fetch2(opa, opb, d0);
     }
 #pragma unroll
     for (int t = 0; t < 3; ++t) {
