@@ -45,6 +45,11 @@ __global__ __launch_bounds__(kBlock) void k_init_random(VecSrc vs, int64_t n, in
 }
 
 // ---------------------------------------------------------------------------
+// What the reverse candidates of v are ranked by: hash(seed, kind, v, s, iter), ties by s.
+__device__ inline uint64_t select_key(uint64_t base, int64_t v, uint32_t s, uint32_t iter) {
+  return ((hash3(base, (uint32_t)v, s, iter) >> 32) << 32) | (uint64_t)s;
+}
+
 // Sec. 4.1, reverse part and duplicate removal for one list.  `fwd_raw` is the
 // list row as loaded (its first nf entries are the forward samples), `first` the
 // first 64 reverse candidates (lane < deg).  Of the candidates the 2p - nf with
@@ -52,27 +57,34 @@ __global__ __launch_bounds__(kBlock) void k_init_random(VecSrc vs, int64_t n, in
 // paper's "append until the list is full" with the winners chosen by a hash
 // instead of by thread timing.  The list is then sorted by id, duplicates are
 // dropped and it is written back with -1 behind its end.  Returns its size.
-__device__ inline int select_list(int64_t v, int p, uint64_t base, uint32_t iter, int32_t* list,
+__device__ __forceinline__ int select_list(int64_t v, int p, uint64_t base, uint32_t iter, int32_t* list,
                                   uint32_t fwd_raw, int nf, const int32_t* csr, uint64_t beg,
-                                  uint64_t deg, uint32_t first, int lane) {
+                                  uint32_t deg, uint32_t first, int lane) {
   const uint32_t fwd = lane < nf ? fwd_raw : kIdMax;
   const int room = 2 * p - nf;
   uint32_t rev = kIdMax;
   int m;
-  if (deg <= (uint64_t)room) {
+  if (deg <= (uint32_t)room) {
     m = (int)deg;
     if (lane < m) rev = first;
   } else {
     m = room;
-    uint64_t best = kKeyMax;
-    for (uint64_t c = 0; c < deg; c += kWave) {
-      uint64_t key = kKeyMax;
-      if (c + lane < deg) {
-        const uint32_t s = c == 0 ? first : (uint32_t)csr[beg + c + lane];
-        key = ((hash3(base, (uint32_t)v, s, iter) >> 32) << 32) | (uint64_t)s;
+    uint64_t best = lane < deg ? select_key(base, v, first, iter) : kKeyMax;
+    if (room == kWave / 2 && deg <= (uint32_t)kWave) {
+      // The usual case (a full forward part, up to 64 candidates).  Which 32 candidates win
+      // is all that matters - the list is sorted by id below - so the network stops where
+      // the lower half of the lanes holds the 32 smallest keys: halves sorted up and down
+      // (15 stages), then one exchange across the halves, instead of 21 stages.
+      best = wave_sort_first<kWave / 2>(best, lane);
+      best = vmin(best, xor_lanes(best, kWave / 2, lane));
+    } else {
+      best = wave_sort(best, lane);
+      for (uint32_t c = kWave; c < deg; c += kWave) {
+        uint64_t key =
+            c + lane < deg ? select_key(base, v, (uint32_t)csr[beg + c + lane], iter) : kKeyMax;
+        key = wave_sort(key, lane);
+        best = wave_merge_smallest(best, key, lane);
       }
-      key = wave_sort(key, lane);
-      best = wave_merge_smallest(best, key, lane);
     }
     if (lane < room) rev = (uint32_t)best;
   }
@@ -111,7 +123,8 @@ __global__ __launch_bounds__(kBlock) void k_rev_select(int64_t n, int p, uint64_
   const int lane = lane_id();
   const int L = 2 * p;
   int nfn[kNodesPerWave], nfo[kNodesPerWave];
-  uint64_t bn[kNodesPerWave], dn[kNodesPerWave], bo[kNodesPerWave], dO[kNodesPerWave];
+  uint64_t bn[kNodesPerWave], bo[kNodesPerWave];
+  uint32_t dn[kNodesPerWave], dO[kNodesPerWave];  // a node's reverse degree is below 2^32
   uint32_t rown[kNodesPerWave], rowo[kNodesPerWave], firstn[kNodesPerWave], firsto[kNodesPerWave];
 #pragma unroll
   for (int i = 0; i < kNodesPerWave; ++i) {
@@ -119,16 +132,16 @@ __global__ __launch_bounds__(kBlock) void k_rev_select(int64_t n, int p, uint64_
     nfn[i] = cnew[v];
     nfo[i] = cold[v];
     bn[i] = roff_new[v];
-    dn[i] = roff_new[v + 1] - bn[i];
+    dn[i] = (uint32_t)(roff_new[v + 1] - bn[i]);
     bo[i] = roff_old[v];
-    dO[i] = roff_old[v + 1] - bo[i];
+    dO[i] = (uint32_t)(roff_old[v + 1] - bo[i]);
     rown[i] = lane < p ? (uint32_t)snew[v * L + lane] : kIdMax;  // the forward part
     rowo[i] = lane < p ? (uint32_t)sold[v * L + lane] : kIdMax;
   }
 #pragma unroll
   for (int i = 0; i < kNodesPerWave; ++i) {
-    firstn[i] = lane < dn[i] ? (uint32_t)csr_new[bn[i] + lane] : kIdMax;
-    firsto[i] = lane < dO[i] ? (uint32_t)csr_old[bo[i] + lane] : kIdMax;
+    firstn[i] = (uint32_t)lane < dn[i] ? (uint32_t)csr_new[bn[i] + lane] : kIdMax;
+    firsto[i] = (uint32_t)lane < dO[i] ? (uint32_t)csr_old[bo[i] + lane] : kIdMax;
   }
   uint64_t sum_new = 0, sum_old = 0;
 #pragma unroll
