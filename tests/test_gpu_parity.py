@@ -111,6 +111,12 @@ CASES["u8_small_lists"] = (lambda: W.sift_like_u8(1500, 64, seed=1013, n_comp=4)
 CASES["near_copies_d24"] = (lambda: W.near_copies_f32(1600, 24, seed=1091), og.L2SQ_F32, 24, 16, 4)
 CASES["near_copies_cosine_d70"] = (lambda: W.near_copies_f32(1200, 70, seed=1092, copies=12),
                                    og.COSINE_F32, 20, 20, 4)
+# full sample lists (p = 32) over enough iterations that nodes of every shape occur - few to 64
+# NEW samples, none to 64 OLD - under the other two metrics as well ("sift_cut" is squared L2)
+CASES["deep_cut_angular_p32"] = (lambda: W.deep_like_f32(2200, 96, seed=1093, n_comp=12),
+                                 og.ANGULAR_F32, 32, 32, 5)
+CASES["cosine_p32_d40"] = (lambda: W.scaled_directions_f32(2000, 40, seed=1094, n_comp=10),
+                           og.COSINE_F32, 32, 32, 5)
 GRAM_CASES = [n for n, c in CASES.items()
               if c[1] in (og.L2SQ_F32, og.ANGULAR_F32, og.COSINE_F32) and c[3] <= 32]
 
@@ -133,11 +139,12 @@ def _gram_build_of(rb, co):
     return 5 if co <= 2 else 6
 
 
-def test_gram_parity_cases_reach_every_build_of_the_kernel():
-    """The case "sift_cut" (checked stage by stage against the oracle below) has nodes for each
-    of the seven builds of the float matrix-core join."""
+@pytest.mark.parametrize("name", ["sift_cut", "deep_cut_angular_p32", "cosine_p32_d40"])
+def test_gram_parity_cases_reach_every_build_of_the_kernel(name):
+    """These cases (checked stage by stage against the oracle below, one per metric) have nodes
+    for each of the seven builds of the float matrix-core join."""
     amd = _amd()
-    gen, metric, k, p, iters = CASES["sift_cut"]
+    gen, metric, k, p, iters = CASES[name]
     ctx = amd.Gnnd(_dev(gen()), k, p, metric, SEED, amd.JOIN_GRAM)
     ctx.init_random()
     seen = set()
