@@ -104,33 +104,51 @@ __device__ inline int32_t wave_distances_i8(const int8_t* __restrict__ shadow,
   const bool pow2 = (C & (C - 1)) == 0;
   const v4i x = *reinterpret_cast<const v4i*>(shadow + s * dpad + 16 * sub);
   const int32_t norm_s = meta[s].norm;
+  // (the objects' norms come from their rows, which are here anyway: a gather of the stored
+  // norm would be a second scattered access per object)
   int32_t dot = 0, norm_id = 0;
-  if (lane < count) norm_id = meta[id].norm;
   for (int r0 = 0; r0 < count; r0 += per_load) {
     const int j = r0 + grp;  // the object this group reads
     const bool act = lane_used && j < count;
     const uint32_t nid = __shfl(id, act ? j : 0, kWave);
-    int32_t part = 0;
+    int32_t part = 0, part_sq = 0;
     if (act) {
       const v4i y = *reinterpret_cast<const v4i*>(shadow + (int64_t)nid * dpad + 16 * sub);
 #pragma unroll
-      for (int t = 0; t < 4; ++t) part = __builtin_amdgcn_sdot4(x[t], y[t], part, false);
+      for (int t = 0; t < 4; ++t) {
+        part = __builtin_amdgcn_sdot4(x[t], y[t], part, false);
+        part_sq = __builtin_amdgcn_sdot4(y[t], y[t], part_sq, false);
+      }
     }
-    int32_t total = part;
+    int32_t total = part, total_sq = part_sq;
     if (pow2) {  // groups are aligned blocks of 2, 4 or 8 lanes: butterfly sum
-      if (C > 1) total += (int32_t)xor_lanes((uint32_t)total, 1, lane);
-      if (C > 2) total += (int32_t)xor_lanes((uint32_t)total, 2, lane);
-      if (C > 4) total += (int32_t)xor_lanes((uint32_t)total, 4, lane);
+      if (C > 1) {
+        total += (int32_t)xor_lanes((uint32_t)total, 1, lane);
+        total_sq += (int32_t)xor_lanes((uint32_t)total_sq, 1, lane);
+      }
+      if (C > 2) {
+        total += (int32_t)xor_lanes((uint32_t)total, 2, lane);
+        total_sq += (int32_t)xor_lanes((uint32_t)total_sq, 2, lane);
+      }
+      if (C > 4) {
+        total += (int32_t)xor_lanes((uint32_t)total, 4, lane);
+        total_sq += (int32_t)xor_lanes((uint32_t)total_sq, 4, lane);
+      }
     } else {
       for (int off = 1; off < C; ++off) {
         int o = sub + off;
         o = o >= C ? o - C : o;
         total += __shfl(part, (grp * C + o) & 63, kWave);
+        total_sq += __shfl(part_sq, (grp * C + o) & 63, kWave);
       }
     }
     // object j = lane sits in group lane - r0
     const int32_t got = __shfl(total, ((lane - r0) * C) & 63, kWave);
-    if (lane >= r0 && lane < r0 + per_load) dot = got;
+    const int32_t got_sq = __shfl(total_sq, ((lane - r0) * C) & 63, kWave);
+    if (lane >= r0 && lane < r0 + per_load) {
+      dot = got;
+      norm_id = got_sq;
+    }
   }
   return lane < count ? norm_s + norm_id - 2 * dot : 0;
 }
