@@ -33,8 +33,8 @@ PEAK_INT8_TOPS = 5000.0
 # mean of the first T entries; T beyond the table also gives null.
 JOIN_TRAFFIC = {
     ("sift1m", 1_000_000, 128, 32, 32, "k_join_mfma", "selective"): {
-        "fetch_raw_mib": [6970.4, 4594.0, 5200.9, 5037.6, 5111.4, 4766.8, 4587.8],
-        "write_raw_mib": [607.2, 481.0, 745.0, 593.3, 446.6, 249.4, 140.5],
+        "fetch_raw_mib": [3904.9, 4594.0, 5201.5, 5036.5, 5111.4, 4766.6, 4588.3],
+        "write_raw_mib": [572.3, 481.1, 743.2, 596.0, 446.9, 250.2, 140.7],
         "fetch_scale": 2.0, "write_scale": 1.0},
 }
 

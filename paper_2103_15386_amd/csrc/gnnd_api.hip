@@ -170,6 +170,7 @@ struct gnnd_ctx {
   int32_t iter;       // iterations completed
   int stage;          // 0 = ready for sample, 1 = sampled, 2 = joined
   bool has_graph;
+  bool fresh_random;  // the graph is what gnnd_init_random left: no update has touched it yet
   bool merge_mode;
   bool use_mfma;
   bool use_gram;
@@ -246,6 +247,7 @@ int init_ctx(gnnd_ctx* c, const gnnd_params* prm, const Layout& L, const void* v
   c->iter = 0;
   c->stage = 0;
   c->has_graph = false;
+  c->fresh_random = false;
   c->merge_mode = merge_mode;
   c->have_events = false;
   c->prof_on = false;
@@ -378,7 +380,7 @@ int step_join(gnnd_ctx* c, hipEvent_t after_join = nullptr) {
   if (c->stage != 1) return fail(c, GNND_ESTATE, "stage order is sample, join, update");
   hipError_t e;
   if (c->use_mfma) {
-    e = launch_join_mfma(c->sh, c->ds, c->merge_mode, c->stream, after_join);
+    e = launch_join_mfma(c->sh, c->ds, c->merge_mode, c->fresh_random, c->stream, after_join);
   } else {
     e = c->use_gram ? launch_join_gram(c->sh, c->ds, c->merge_mode, c->stream)
                     : launch_join(c->sh, c->ds, c->prm.join_path, c->merge_mode, c->stream);
@@ -394,6 +396,7 @@ int step_update(gnnd_ctx* c) {
   if (e != hipSuccess) return hip_fail(c, e, "update kernels");
   c->stage = 0;
   c->iter += 1;
+  c->fresh_random = false;
   return GNND_OK;
 }
 
@@ -956,6 +959,7 @@ int gnnd_init_random(gnnd_ctx* c) {
                              : launch_init_random(c->sh, c->ds, c->prm.seed, c->stream);
   if (e != hipSuccess) return hip_fail(c, e, "init kernel");
   c->has_graph = true;
+  c->fresh_random = true;
   c->iter = 0;
   c->stage = 0;
   return GNND_OK;
@@ -1027,6 +1031,7 @@ int gnnd_set_graph(gnnd_ctx* c, const int32_t* ids, const void* dist, const uint
     return fail(c, GNND_EINVAL, "graph holds ids outside 0..n-1 or a node in its own list");
   }
   c->has_graph = true;
+  c->fresh_random = false;
   c->iter = iter;
   c->stage = 0;
   return GNND_OK;

@@ -328,7 +328,34 @@ __device__ inline uint64_t stage_record(uint64_t entry, uint32_t dest, int tb) {
          (uint64_t)entry_id(entry);
 }
 
-template <int KSTEPS, bool FCODE, bool MERGE, bool STAGED>
+// Squared norm of the row this lane's sample stands for, from the operand registers: sample
+// `lane` of a list is row lane % 32 of block lane / 32, and lanes l and l + 32 hold the two
+// halves of row l of both blocks.
+template <int KSTEPS>
+__device__ inline int32_t half_row_sq(const Operand& o) {
+  int32_t acc = 0;
+#pragma unroll
+  for (int s = 0; s < KSTEPS; ++s)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc = __builtin_amdgcn_sdot4(o.k[s][i], o.k[s][i], acc, false);
+  return acc;
+}
+template <int KSTEPS>
+__device__ inline int32_t sample_norm(const Operand& b0, const Operand& b1, int half, int lane) {
+  const int32_t p0 = half_row_sq<KSTEPS>(b0), p1 = half_row_sq<KSTEPS>(b1);
+  const int32_t mine = half ? p1 : p0, give = half ? p0 : p1;
+  return mine + (int32_t)xor_lanes((uint32_t)give, 32, lane);
+}
+
+// LEAN (staged hand-out only): the form for a launch in which the thresholds of the lists
+// decide little and the nodes have few OLD samples - the first iteration on a random graph,
+// where every result passes and a node's time is the time the memory system needs for its
+// scattered lines.  The 8-byte (threshold, norm) records, one more scattered line per sampled
+// object, are not read: the norms come from the operand registers and every result found is
+// handed on; k_result_csr<true> then applies the thresholds, so the same results reach the
+// lists.  Right for any input; faster only where the saved reads outweigh the extra
+// arithmetic and the larger flow of results.
+template <int KSTEPS, bool FCODE, bool MERGE, bool STAGED, bool LEAN = false>
 __global__ __launch_bounds__(STAGED ? kMBStaged : kMB)
 __attribute__((amdgpu_waves_per_eu(STAGED ? 2 : 3, STAGED ? 2 : 3))) void k_join_mfma(
     const int8_t* __restrict__ shadow, const NodeMeta* __restrict__ meta, int dpad, int64_t n,
@@ -405,9 +432,12 @@ __attribute__((amdgpu_waves_per_eu(STAGED ? 2 : 3, STAGED ? 2 : 3))) void k_join
     N1 = load_block<KSTEPS>(shadow, dpad, __shfl(idn, 32 + col, kWave), half);
     O0 = load_block<KSTEPS>(shadow, dpad, __shfl(ido, col, kWave), half);
     O1 = load_block<KSTEPS>(shadow, dpad, __shfl(ido, 32 + col, kWave), half);
-    // one 8-byte gather per sampled object: list threshold and norm
-    m_new = idn >= 0 ? *reinterpret_cast<const uint2*>(meta + idn) : m_none;
-    m_old = ido >= 0 ? *reinterpret_cast<const uint2*>(meta + ido) : m_none;
+    if (LEAN) {
+      m_new = m_old = m_none;
+    } else {  // one 8-byte gather per sampled object: list threshold and norm
+      m_new = idn >= 0 ? *reinterpret_cast<const uint2*>(meta + idn) : m_none;
+      m_old = ido >= 0 ? *reinterpret_cast<const uint2*>(meta + ido) : m_none;
+    }
   };
   request_rows(id_new, id_old);
 
@@ -415,7 +445,15 @@ __attribute__((amdgpu_waves_per_eu(STAGED ? 2 : 3, STAGED ? 2 : 3))) void k_join
     const int nn = __popcll(__ballot(id_new >= 0)), no = __popcll(__ballot(id_old >= 0));
     const bool do_nn = !MERGE && nn > 1;
     const bool active = nn > 0 && (do_nn || no > 0);
-    const uint2 cm_new = m_new, cm_old = m_old;  // this node's thresholds and norms
+    uint2 cm_new = m_new, cm_old = m_old;  // this node's thresholds and norms
+    if (LEAN && active) {  // (all lanes take part in the exchange between the halves)
+      const uint32_t norm_new = (uint32_t)sample_norm<KSTEPS>(N0, N1, half, lane);
+      if (id_new >= 0) cm_new.y = norm_new;
+      if (no > 0) {  // uniform
+        const uint32_t norm_old = (uint32_t)sample_norm<KSTEPS>(O0, O1, half, lane);
+        if (id_old >= 0) cm_old.y = norm_old;
+      }
+    }
     int32_t a0 = kNone, a1 = kNone;  // NEW column blocks: nearest other NEW
     int32_t b0 = kNone, b1 = kNone;  // NEW column blocks: nearest OLD
     int32_t c0 = kNone, c1 = kNone;  // OLD column blocks: nearest NEW
@@ -580,7 +618,8 @@ __attribute__((amdgpu_waves_per_eu(STAGED ? 2 : 3, STAGED ? 2 : 3))) void k_join
         const int32_t other = found ? s_id[wave][(kind == 1 ? 64 : 0) + (res & 63)] : 0;
         const uint32_t code = FCODE ? ord_f32((float)dist) : ord_i32(dist);
         // a result that cannot beat the last entry of the destination list is dropped
-        pass[kind] = found && code <= cm.x;
+        // (LEAN: every result goes on, k_result_csr applies the threshold)
+        pass[kind] = found && (LEAN || code <= cm.x);
         entry[kind] = make_entry(code, (uint32_t)other, 3u);
         found_total += (uint32_t)__popcll(__ballot(found));
       }
@@ -671,8 +710,10 @@ __attribute__((amdgpu_waves_per_eu(STAGED ? 2 : 3, STAGED ? 2 : 3))) void k_join
         ev = (do_nn ? (uint64_t)nn * (nn - 1) / 2 : 0) + (uint64_t)nn * no - dups;
       }
       uint64_t* cs = counters + (s & (kStripes - 1)) * C_SLOTS;
-      if (passed_total) atomicAdd(reinterpret_cast<unsigned long long*>(cs + C_PASSED),
-                                  (unsigned long long)passed_total);
+      // (LEAN: k_result_csr counts what passes the thresholds)
+      if (!LEAN && passed_total)
+        atomicAdd(reinterpret_cast<unsigned long long*>(cs + C_PASSED),
+                  (unsigned long long)passed_total);
       if (found_total) atomicAdd(reinterpret_cast<unsigned long long*>(cs + C_PROPS),
                                  (unsigned long long)found_total);
       if (over_total) atomicAdd(reinterpret_cast<unsigned long long*>(cs + C_OVERFLOW),
@@ -706,22 +747,28 @@ __attribute__((amdgpu_waves_per_eu(STAGED ? 2 : 3, STAGED ? 2 : 3))) void k_join
 // destination's run) and writes it out run by run: neighbouring lanes then store to
 // neighbouring places.
 constexpr int kRcBlock = 1024;
-constexpr int kRcPerThread = 12;                     // results per thread and tile
-constexpr int kRcTile = kRcBlock * kRcPerThread;     // 96 KB of LDS
+// FILTER (behind the LEAN join, which hands on every result): a result that cannot beat the
+// last entry of its destination's list is dropped here, and what is left is counted as passed.
+// Results per thread and tile: 12 (96 KB of LDS), 11 where the thresholds need room too.
+constexpr int rc_per_thread(bool filter) { return filter ? 11 : 12; }
 // LDS: the tile, then per destination of the bucket (at most 2^12) the number of results in
-// the tile / the start of its run, the next free place of its segment and the segment's end
-// (both relative to the region).
-static size_t result_csr_lds_bytes(int tb) {
-  return (size_t)kRcTile * 8 + (((size_t)3 << tb) + 1) * 4;
+// the tile / the start of its run, the next free place of its segment, the segment's end
+// (both relative to the region) and, with FILTER, the threshold of its list.
+static size_t result_csr_lds_bytes(int tb, bool filter) {
+  return (size_t)kRcBlock * rc_per_thread(filter) * 8 + (((size_t)(filter ? 4 : 3) << tb) + 1) * 4;
 }
 
+template <bool FILTER>
 __global__ __launch_bounds__(kRcBlock) void k_result_csr(int64_t n, int tb,
                                                          const uint64_t* __restrict__ poff,
                                                          const unsigned long long* __restrict__ cur,
                                                          const uint64_t* __restrict__ ent,
                                                          uint64_t* __restrict__ bins,
                                                          uint64_t* __restrict__ pslot,
+                                                         const NodeMeta* __restrict__ meta,
                                                          uint64_t* counters) {
+  constexpr int kRcPerThread = rc_per_thread(FILTER);
+  constexpr int kRcTile = kRcBlock * kRcPerThread;
   extern __shared__ __attribute__((aligned(16))) uint64_t rc_lds[];
   __shared__ uint32_t part[kRcBlock / kWave];
   uint64_t* const tile = rc_lds;
@@ -729,6 +776,7 @@ __global__ __launch_bounds__(kRcBlock) void k_result_csr(int64_t n, int tb,
   uint32_t* const run = reinterpret_cast<uint32_t*>(rc_lds + kRcTile);  // T_max + 1 entries
   uint32_t* const next = run + T_max + 1;
   uint32_t* const seg_end = next + T_max;
+  uint32_t* const kth_s = seg_end + T_max;  // FILTER only
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int64_t first = (int64_t)blockIdx.x << tb;
   const int T = (int)(n - first < (int64_t)T_max ? n - first : (int64_t)T_max);
@@ -736,7 +784,9 @@ __global__ __launch_bounds__(kRcBlock) void k_result_csr(int64_t n, int tb,
   for (int t = tid; t < T_max; t += kRcBlock) {
     next[t] = t < T ? (uint32_t)(poff[first + t] - region) : (uint32_t)room;
     seg_end[t] = t < T ? (uint32_t)(poff[first + t + 1] - region) : (uint32_t)room;
+    if (FILTER) kth_s[t] = t < T ? meta[first + t].kth : 0u;
   }
+  uint32_t kept = 0;  // FILTER: results that pass
   uint64_t count = cur[blockIdx.x];
   if (count > room) {  // cannot happen: a region holds what its destinations can receive
     if (tid == 0)
@@ -759,8 +809,12 @@ __global__ __launch_bounds__(kRcBlock) void k_result_csr(int64_t n, int tb,
 #pragma unroll
     for (int r = 0; r < kRcPerThread; ++r) {
       const int t = (int)(((uint32_t)e[r] >> kStageIdBits) & (uint32_t)(T_max - 1));
-      if (e[r] == ~0ull || t >= T) e[r] = ~0ull;
-      else rank[r] = atomicAdd(&run[t], 1u);
+      if (e[r] == ~0ull || t >= T || (FILTER && (uint32_t)(e[r] >> 32) > kth_s[t])) {
+        e[r] = ~0ull;
+      } else {
+        rank[r] = atomicAdd(&run[t], 1u);
+        ++kept;
+      }
     }
     __syncthreads();
     // exclusive scan of the counters: thread i takes counters per*i .. per*i + per - 1
@@ -818,6 +872,15 @@ __global__ __launch_bounds__(kRcBlock) void k_result_csr(int64_t n, int tb,
     __syncthreads();
   }
   __syncthreads();
+  if (FILTER) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) kept += __shfl_xor(kept, off, kWave);
+    if (lane == 0 && kept)
+      atomicAdd(reinterpret_cast<unsigned long long*>(
+                    counters +
+                    ((blockIdx.x * (kRcBlock / kWave) + wave) & (kStripes - 1)) * C_SLOTS + C_PASSED),
+                (unsigned long long)kept);
+  }
   for (int t = tid; t < T; t += kRcBlock) {
     const uint64_t start = poff[first + t] - region;
     const uint64_t end = next[t] < seg_end[t] ? next[t] : seg_end[t];
@@ -826,7 +889,7 @@ __global__ __launch_bounds__(kRcBlock) void k_result_csr(int64_t n, int tb,
   }
 }
 
-template <int KSTEPS, bool STAGED>
+template <int KSTEPS, bool STAGED, bool LEAN = false>
 static hipError_t launch_k(bool fcode, bool merge, unsigned grid, hipStream_t st,
                            const int8_t* shadow, const NodeMeta* meta, int dpad, const Shape& sh,
                            const DevState& ds, const StageArgs& sa) {
@@ -836,7 +899,7 @@ static hipError_t launch_k(bool fcode, bool merge, unsigned grid, hipStream_t st
                   ds.pslot, (uint64_t)sh.slots(), ds.bins, ds.counters, sa
 #define GNND_LAUNCH(F, M)                                                                      \
   do {                                                                                         \
-    auto* kern = k_join_mfma<KSTEPS, F, M, STAGED>;                                            \
+    auto* kern = k_join_mfma<KSTEPS, F, M, STAGED, LEAN>;                                      \
     if (STAGED) {                                                                              \
       static bool attr_set = false; /* per instantiation: a staging area beyond the default */ \
       if (!attr_set) {                                                                         \
@@ -849,7 +912,10 @@ static hipError_t launch_k(bool fcode, bool merge, unsigned grid, hipStream_t st
     }                                                                                          \
     kern<<<grid, block, lds, st>>>(GNND_ARGS);                                                 \
   } while (0)
-  if (fcode) {
+  if (LEAN) {  // never with a merge
+    if (fcode) GNND_LAUNCH(true, false);
+    else GNND_LAUNCH(false, false);
+  } else if (fcode) {
     if (merge) GNND_LAUNCH(true, true);
     else GNND_LAUNCH(true, false);
   } else {
@@ -874,12 +940,14 @@ static int compute_units() {
   return cus;
 }
 
-hipError_t launch_join_mfma(const Shape& sh, const DevState& ds, bool merge_mode,
+hipError_t launch_join_mfma(const Shape& sh, const DevState& ds, bool merge_mode, bool first_look,
                             hipStream_t st, hipEvent_t after_join) {
   const int dpad = (sh.d + 31) & ~31;
   const int ksteps = dpad / 32;
   const bool fcode = sh.metric != kL2U8;
   const bool staged = ds.stg_ent != nullptr;
+  // the first iteration on a random graph: see LEAN
+  const bool lean = staged && first_look && !merge_mode;
   StageArgs sa{ds.stg_ent, ds.stg_cur, ds.poff, 0, 0, 0};
   unsigned grid;
   if (staged) {
@@ -898,9 +966,10 @@ hipError_t launch_join_mfma(const Shape& sh, const DevState& ds, bool merge_mode
     grid = (unsigned)(want < kJoinGrid ? want : kJoinGrid);
   }
   hipError_t e;
-#define GNND_K(K)                                                                             \
-  e = staged ? launch_k<K, true>(fcode, merge_mode, grid, st, ds.shadow, ds.meta, dpad, sh, ds, sa) \
-             : launch_k<K, false>(fcode, merge_mode, grid, st, ds.shadow, ds.meta, dpad, sh, ds, sa)
+#define GNND_K(K)                                                                               \
+  e = lean     ? launch_k<K, true, true>(fcode, false, grid, st, ds.shadow, ds.meta, dpad, sh, ds, sa) \
+      : staged ? launch_k<K, true>(fcode, merge_mode, grid, st, ds.shadow, ds.meta, dpad, sh, ds, sa) \
+               : launch_k<K, false>(fcode, merge_mode, grid, st, ds.shadow, ds.meta, dpad, sh, ds, sa)
   switch (ksteps) {
     case 1: GNND_K(1); break;
     case 2: GNND_K(2); break;
@@ -911,12 +980,13 @@ hipError_t launch_join_mfma(const Shape& sh, const DevState& ds, bool merge_mode
   if (after_join) (void)hipEventRecord(after_join, st);
   if (e != hipSuccess || !staged) return e;
   // (a region is shorter than 2^32 slots: n <= 2^20, 6p <= 192 slots per node)
-  const size_t lds = result_csr_lds_bytes(sa.tb);
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_result_csr),
+  const size_t lds = result_csr_lds_bytes(sa.tb, lean);
+  auto* csr = lean ? &k_result_csr<true> : &k_result_csr<false>;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(csr),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
-  k_result_csr<<<(unsigned)sa.nb, kRcBlock, lds, st>>>(sh.n, sa.tb, ds.poff, ds.stg_cur, ds.stg_ent,
-                                                      ds.bins, ds.pslot, ds.counters);
+  csr<<<(unsigned)sa.nb, kRcBlock, lds, st>>>(sh.n, sa.tb, ds.poff, ds.stg_cur, ds.stg_ent, ds.bins,
+                                             ds.pslot, ds.meta, ds.counters);
   return hipGetLastError();
 }
 

@@ -123,9 +123,11 @@ hipError_t launch_gram_norms(const Shape& sh, const DevState& ds, hipStream_t st
 hipError_t launch_join_gram(const Shape& sh, const DevState& ds, bool merge_mode, hipStream_t st);
 // results are staged per bucket when ds.stg_ent is set, handed on one by one otherwise;
 // `after_join` (may be NULL) is recorded behind the cross-matching kernel, in front of the
-// pass that moves staged results into the destinations' segments
-hipError_t launch_join_mfma(const Shape& sh, const DevState& ds, bool merge_mode, hipStream_t st,
-                            hipEvent_t after_join = nullptr);
+// pass that moves staged results into the destinations' segments.  `first_look`: the graph is
+// a fresh random one (first iteration) - a hint that selects a form of the staged join that
+// leaves the lists' thresholds to the second pass; same results with or without it
+hipError_t launch_join_mfma(const Shape& sh, const DevState& ds, bool merge_mode, bool first_look,
+                            hipStream_t st, hipEvent_t after_join = nullptr);
 hipError_t launch_pack_i8(const Shape& sh, const DevState& ds, int* bad_flag_dev, hipStream_t st);
 hipError_t launch_init_random_i8(const Shape& sh, const DevState& ds, uint64_t seed,
                                  hipStream_t st);

@@ -211,6 +211,8 @@ def test_every_stage_of_every_iteration_matches_oracle(name, path):
         assert st["dist_evals"] == evals
         assert st["sum_new"] == int(cnew.sum()) and st["sum_old"] == int(cold.sum())
         assert st["proposals"] == int(pcnt.sum()) and st["dropped"] == 0
+        if not every:  # what the join (or the pass behind it) let through = what the update saw
+            assert st["passed"] == int(used.sum()), f"it {it}: passed"
     ctx.close()
 
 
