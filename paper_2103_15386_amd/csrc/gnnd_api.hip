@@ -366,8 +366,7 @@ int step_sample(gnnd_ctx* c) {
   if (!c->has_graph) return fail(c, GNND_ESTATE, "no graph: call gnnd_init_random or gnnd_set_graph first");
   if (c->stage != 0) return fail(c, GNND_ESTATE, "stage order is sample, join, update");
   // the counters only grow: keep their values from before this iteration
-  hipError_t e = hipMemcpyAsync(c->snap, c->ds.counters, (size_t)kStripes * C_SLOTS * 8,
-                                hipMemcpyDeviceToDevice, c->stream);
+  hipError_t e = launch_copy_u64(c->snap, c->ds.counters, (size_t)kStripes * C_SLOTS, c->stream);
   if (e != hipSuccess) return hip_fail(c, e, "counter snapshot");
   e = launch_sample(c->sh, c->ds, c->prm.seed, (uint32_t)(c->iter + 1), c->stream);
   if (e != hipSuccess) return hip_fail(c, e, "sampling kernels");

@@ -451,6 +451,12 @@ __global__ __launch_bounds__(kBlock) void k_zero_u32(uint32_t* p, size_t count) 
   if (i < count) p[i] = 0u;
 }
 
+__global__ __launch_bounds__(kBlock) void k_copy_u64(uint64_t* dst, const uint64_t* src,
+                                                     size_t count) {
+  const size_t i = (size_t)block_linear() * kBlock + threadIdx.x;
+  if (i < count) dst[i] = src[i];
+}
+
 // ---------------------------------------------------------------------------
 // GGM, Alg. 3 "Divide" + "Append": keep the first ceil(k/2) entries (OLD), set
 // the rest aside, refill with floor(k/2) random objects of the other set (NEW)
@@ -674,6 +680,15 @@ static VecSrc vec_src(const Shape& sh) {
 hipError_t launch_zero_u32(uint32_t* p, size_t count, hipStream_t st) {
   if (count == 0) return hipSuccess;
   k_zero_u32<<<grid_blocks((int64_t)((count + kBlock - 1) / kBlock)), kBlock, 0, st>>>(p, count);
+  return hipGetLastError();
+}
+
+// A small copy inside the stream of kernels (the runtime's own copy leaves the GPU idle for
+// some 10 microseconds around it).
+hipError_t launch_copy_u64(uint64_t* dst, const uint64_t* src, size_t count, hipStream_t st) {
+  if (count == 0) return hipSuccess;
+  k_copy_u64<<<grid_blocks((int64_t)((count + kBlock - 1) / kBlock)), kBlock, 0, st>>>(dst, src,
+                                                                                      count);
   return hipGetLastError();
 }
 

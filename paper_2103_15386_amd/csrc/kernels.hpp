@@ -171,6 +171,7 @@ hipError_t launch_exact_knn(const void* vec, int64_t n, int32_t d, int32_t metri
                             const int32_t* queries, int64_t nq, int32_t K, int32_t* ids_out,
                             void* dist_out, hipStream_t st);
 hipError_t launch_zero_u32(uint32_t* p, size_t count, hipStream_t st);
+hipError_t launch_copy_u64(uint64_t* dst, const uint64_t* src, size_t count, hipStream_t st);
 
 // Exclusive scan of `count` uint32 into uint64 offsets out[0..count] (out[count] = total).
 // (in2 may be NULL; otherwise the scanned values are in[i] + in2[i])
