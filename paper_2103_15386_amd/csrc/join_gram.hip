@@ -3,14 +3,14 @@
 // treats NEW x OLD as a tiled matrix product), results exactly those of the
 // per-pair evaluation in dimension order.
 //
-// One wavefront per node, no barriers between wavefronts, four steps:
+// One wavefront per node at a time, no barriers between wavefronts, four steps:
 //  1. The inner products of the block [NEW x (NEW | OLD)] of the node's <= 64 NEW
 //     and <= 64 OLD sample vectors are accumulated by v_mfma_f32_16x16x4_f32 in
 //     16 x 16 blocks, all of them in registers; only blocks that hold list
 //     entries are computed (lower block triangle of NEW x NEW).  The operands
 //     come straight from memory: four lanes read 64 consecutive bytes of a row,
 //     which is the matrix instruction's own operand layout, 16 dimensions per
-//     step, the next step's operands requested before this step's products.
+//     step, two steps (both halves of a 128-byte line) requested together.
 //  2. Inner product and squared norms give every pair an approximate distance
 //     whose difference from the canonical sum (one fused multiply-add per
 //     dimension, in dimension order) is bounded by eps(pair), see pair_bounds.
@@ -21,10 +21,14 @@
 //     beyond the threshold of the sample's list are dropped, for nothing at that
 //     distance is handed on.  One partner is left as a rule, seldom a few, often
 //     none.
-//  4. The vectors concerned are read once more (from the cache now), the same
-//     way, and pass through an LDS tile 16 dimensions at a time, where one lane
-//     per sample accumulates the canonical distances of the partners left; the
-//     smallest (distance, id) is the result.
+//  4. The vectors concerned are read once more, the same way, and pass through
+//     an LDS tile 16 dimensions at a time, where one lane per sample accumulates
+//     the canonical distances of the partners left; the smallest (distance, id)
+//     is the result.
+// The nodes are listed by the number of blocks of 16 samples they fill
+// (k_gram_classify), and each class has its own build of the kernel, with the
+// registers and the LDS tile that its blocks need, run by persistent wavefronts
+// over the class's list.
 #include <stddef.h>
 
 #include "device_utils.hpp"
