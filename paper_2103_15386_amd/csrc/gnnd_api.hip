@@ -41,7 +41,7 @@ struct Layout {
   size_t off_G, off_kth, off_snew, off_sold, off_cnew, off_cold, off_ron,
       off_roo, off_csn, off_cso, off_capn, off_capo, off_pslot, off_poff, off_bins, off_scan,
       off_cnt, off_snap, off_aside, off_shadow, off_norms, off_flag, off_bkc, off_bko, off_stg_ent,
-      off_stg_cur, off_gram_nodes, off_gram_count, total;
+      off_stg_cur, off_cls_nodes, off_cls_count, total;
 };
 
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -150,8 +150,9 @@ Layout make_layout(const gnnd_params* q, bool with_aside) {
   L.off_stg_ent = take(staged ? n * slots_per_node * 8 : 0);
   L.off_stg_cur = take(staged ? (size_t)kStageBuckets * 8 : 0);
   const bool gram = gram_possible(q);
-  L.off_gram_nodes = take(gram ? (size_t)kGramClasses * n * 4 : 0);
-  L.off_gram_count = take(gram ? 256 : 0);
+  // (the float join lists its nodes in kGramClasses classes, the staged int8 join in three)
+  L.off_cls_nodes = take(gram ? (size_t)kGramClasses * n * 4 : staged ? (size_t)3 * n * 4 : 0);
+  L.off_cls_count = take(gram || staged ? 256 : 0);
   L.total = o;
   return L;
 }
@@ -227,8 +228,8 @@ void bind(gnnd_ctx* c, const Layout& L) {
   d.stg_ent = staged ? (uint64_t*)(w + L.off_stg_ent) : nullptr;
   d.stg_cur = staged ? (unsigned long long*)(w + L.off_stg_cur) : nullptr;
   const bool gram = gram_possible(&c->prm);
-  d.gram_nodes = gram ? (int32_t*)(w + L.off_gram_nodes) : nullptr;
-  d.gram_count = gram ? (uint32_t*)(w + L.off_gram_count) : nullptr;
+  d.cls_nodes = gram || staged ? (int32_t*)(w + L.off_cls_nodes) : nullptr;
+  d.cls_count = gram || staged ? (uint32_t*)(w + L.off_cls_count) : nullptr;
 }
 
 // Fill in a default-constructed context (no allocation of any kind): layout,

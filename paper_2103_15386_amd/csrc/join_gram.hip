@@ -622,16 +622,16 @@ hipError_t launch_join_gram(const Shape& sh, const DevState& ds, bool merge_mode
   const uint64_t slots = (uint64_t)sh.slots();
   const int mm = merge_mode ? 1 : 0;
   // the nodes with work to do, by class
-  hipError_t e = launch_zero_u32(ds.gram_count, kGramClasses, st);
+  hipError_t e = launch_zero_u32(ds.cls_count, kGramClasses, st);
   if (e != hipSuccess) return e;
   k_gram_classify<<<grid_blocks((sh.n + kClassifyNodes - 1) / kClassifyNodes), 256, 0, st>>>(
-      sh.n, mm, ds.cnew, ds.cold, ds.gram_nodes, ds.gram_count);
+      sh.n, mm, ds.cnew, ds.cold, ds.cls_nodes, ds.cls_count);
   // one build per class, each with about four sets of resident wavefronts (the lists' lengths
   // are known on the device only) and never more wavefronts than nodes
   const int64_t cap = (int64_t)64 * compute_units();
   const unsigned grid = (unsigned)(sh.n < cap ? sh.n : cap);
 #define GNND_GRAM_ARGS vs, sh.n, sh.p, mm, ds.snew, ds.sold, ds.cnew, ds.cold, ds.meta, ds.pslot, \
-                       slots, ds.bins, ds.counters, ds.gram_nodes, ds.gram_count
+                       slots, ds.bins, ds.counters, ds.cls_nodes, ds.cls_count
   // (in a merge no node without OLD samples has work to do)
 #define GNND_GRAM_CLASSES(M, W)                                                \
   if (!merge_mode) k_join_gram<M, W, 0><<<grid, kWave, 0, st>>>(GNND_GRAM_ARGS); \

@@ -23,7 +23,8 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 constexpr int kMB = 256;  // 4 waves = 4 nodes in flight per workgroup
 constexpr int64_t kJoinGrid = 256 * 3 * 2;  // 256 CUs x 3 resident workgroups x 2
 // staged hand-out: one workgroup of 8 waves per CU (2 per SIMD: the staging code needs the registers) shares the staging area
-constexpr int kStagedWaves = 8;
+constexpr int kStagedWaves = 8;       // four operand blocks: 2 wavefronts per SIMD
+constexpr int kStagedWavesSlim = 12;  // three operand blocks: 3 wavefronts per SIMD
 constexpr int kMBStaged = kStagedWaves * kWave;
 constexpr int32_t kFar = 1 << 24;  // "norm" of an absent row: above every real distance
 
@@ -320,6 +321,9 @@ struct StageArgs {
   const uint64_t* poff;     // segment offsets of the destinations (n + 1)
   int tb, nb;               // log2(destinations per bucket), number of buckets
   uint32_t threshold;       // fill count that triggers a flush
+  const int32_t* nodes;     // kJoinShapes lists of n places: the nodes of each shape
+  const uint32_t* count;    // their lengths
+  bool count_passed;        // false when the pass behind the join counts what passes
 };
 constexpr size_t kStageLdsBytes = (size_t)kStageBuckets * kStageSlots * 8 + kStageBuckets * 20 + 16;
 // a staged result: distance code | destination inside its bucket | object id
@@ -355,14 +359,29 @@ __device__ inline int32_t sample_norm(const Operand& b0, const Operand& b1, int 
 // handed on; k_result_csr<true> then applies the thresholds, so the same results reach the
 // lists.  Right for any input; faster only where the saved reads outweigh the extra
 // arithmetic and the larger flow of results.
-template <int KSTEPS, bool FCODE, bool MERGE, bool STAGED, bool LEAN = false>
-__global__ __launch_bounds__(STAGED ? kMBStaged : kMB)
-__attribute__((amdgpu_waves_per_eu(STAGED ? 2 : 3, STAGED ? 2 : 3))) void k_join_mfma(
+// SHAPE (staged hand-out only): which of the four operand blocks of 32 rows a node fills.
+// 0: any (NEW 0..31, NEW 32..63, OLD 0..31, OLD 32..63); 1: at most 32 OLD samples; 2: at
+// most 32 NEW samples.  Most nodes are of shape 1 (early iterations: many NEW, few OLD) or 2
+// (late ones); without the fourth block's 16 registers the kernel fits 3 wavefronts per SIMD,
+// which hide the per-node chain wait -> evaluate -> hand on much better than 2 do (12 to 16 %
+// less time per launch).  k_join_shapes lists the nodes of each shape (those with nothing to
+// evaluate are in no list) and every build runs over its own list.
+constexpr int kJoinShapes = 3;
+__host__ __device__ constexpr int join_list_of_shape(int shape) { return shape == 0 ? 2 : shape - 1; }
+__host__ __device__ constexpr int join_waves(bool staged, int shape) {
+  return staged ? (shape ? kStagedWavesSlim : kStagedWaves) : kMB / kWave;
+}
+
+template <int KSTEPS, bool FCODE, bool MERGE, bool STAGED, bool LEAN = false, int SHAPE = 0>
+__global__ __launch_bounds__(join_waves(STAGED, SHAPE) * kWave)
+__attribute__((amdgpu_waves_per_eu(STAGED && !SHAPE ? 2 : 3, STAGED && !SHAPE ? 2 : 3))) void k_join_mfma(
     const int8_t* __restrict__ shadow, const NodeMeta* __restrict__ meta, int dpad, int64_t n,
     int p, int64_t split, const int32_t* __restrict__ snew, const int32_t* __restrict__ sold,
     uint64_t* pslot, uint64_t slots, uint64_t* __restrict__ bins, uint64_t* counters,
     StageArgs sa) {
-  constexpr int WAVES = STAGED ? kStagedWaves : kMB / kWave;
+  constexpr int WAVES = join_waves(STAGED, SHAPE);
+  constexpr bool kHasN1 = SHAPE != 2, kHasO1 = SHAPE != 1;
+  static_assert(STAGED || SHAPE == 0, "shapes come with the node lists of the staged form");
   // per wave, for the 128 rows (NEW 0..63, OLD 64..127): -((norm << 6) | position), the ids
   // (absent = INT_MAX so that both halves stay ascending), and a scratch row
   __shared__ __attribute__((aligned(16))) int32_t s_norm[WAVES][128];
@@ -377,10 +396,17 @@ __attribute__((amdgpu_waves_per_eu(STAGED ? 2 : 3, STAGED ? 2 : 3))) void k_join
   // (the wave index as a vector value: measured 3 % faster here than the scalar form)
   const int wave = threadIdx.x >> 6, lane = lane_id(), half = lane >> 5, col = lane & 31;
   const int64_t W = (int64_t)gridDim.x * WAVES;
-  int64_t s = (int64_t)blockIdx.x * WAVES + wave;
-  if (!STAGED && s >= n) return;
+  // place `pos` of this build's list of nodes (staged) / of all nodes (direct)
+  int64_t pos = (int64_t)blockIdx.x * WAVES + wave;
+  const int64_t places = STAGED ? (int64_t)sa.count[join_list_of_shape(SHAPE)] : n;
+  const int32_t* const list = STAGED ? sa.nodes + (int64_t)join_list_of_shape(SHAPE) * n : nullptr;
+  auto node_at = [&](int64_t at) -> int64_t {  // -1 beyond the end
+    if (at >= places) return -1;
+    return STAGED ? (int64_t)list[at] : at;
+  };
+  if (!STAGED && pos >= n) return;
   if (STAGED) {
-    for (int b = threadIdx.x; b < sa.nb; b += kMBStaged) {
+    for (int b = threadIdx.x; b < sa.nb; b += WAVES * kWave) {
       st_cnt[b] = 0;
       const int64_t first = (int64_t)b << sa.tb;
       st_region[b] = sa.poff[first < n ? first : n];
@@ -393,7 +419,7 @@ __attribute__((amdgpu_waves_per_eu(STAGED ? 2 : 3, STAGED ? 2 : 3))) void k_join
   auto flush = [&]() -> bool {
     __syncthreads();  // nobody is adding results any more
     const uint32_t out_of_nodes = *reinterpret_cast<volatile uint32_t*>(st_fill + 1);
-    for (int b = threadIdx.x; b < sa.nb; b += kMBStaged) {
+    for (int b = threadIdx.x; b < sa.nb; b += WAVES * kWave) {
       const uint32_t c = st_cnt[b] < (uint32_t)kStageSlots ? st_cnt[b] : (uint32_t)kStageSlots;
       st_gbase[b] = c ? atomicAdd(&sa.cur[b], (unsigned long long)c) : 0ull;
     }
@@ -405,12 +431,14 @@ __attribute__((amdgpu_waves_per_eu(STAGED ? 2 : 3, STAGED ? 2 : 3))) void k_join
       if ((uint32_t)lane < c && at < slots) sa.ent[at] = st_ent[b * kStageSlots + lane];
     }
     __syncthreads();
-    for (int b = threadIdx.x; b < sa.nb; b += kMBStaged) st_cnt[b] = 0;
+    for (int b = threadIdx.x; b < sa.nb; b += WAVES * kWave) st_cnt[b] = 0;
     if (threadIdx.x == 0) st_fill[0] = 0;
     __syncthreads();
     return out_of_nodes == (uint32_t)WAVES;
   };
-  const bool have_nodes = s < n;
+  // this node, the next one and the one after: sample ids are requested two nodes ahead
+  int64_t s = node_at(pos), s1 = node_at(pos + W), s2 = node_at(pos + 2 * W);
+  const bool have_nodes = s >= 0;
   const int L = 2 * p;
   const bool in_list = lane < L;
   const uint2 m_none = make_uint2(0, (uint32_t)kFar);
@@ -419,9 +447,9 @@ __attribute__((amdgpu_waves_per_eu(STAGED ? 2 : 3, STAGED ? 2 : 3))) void k_join
   int32_t id_new = (have_nodes && in_list) ? snew[s * L + lane] : -1;
   int32_t id_old = (have_nodes && in_list) ? sold[s * L + lane] : -1;
   int32_t nx_new = -1, nx_old = -1;
-  if (s + W < n && in_list) {
-    nx_new = snew[(s + W) * L + lane];
-    nx_old = sold[(s + W) * L + lane];
+  if (s1 >= 0 && in_list) {
+    nx_new = snew[s1 * L + lane];
+    nx_old = sold[s1 * L + lane];
   }
   Operand N0, N1, O0, O1;
   uint2 m_new, m_old;
@@ -429,9 +457,9 @@ __attribute__((amdgpu_waves_per_eu(STAGED ? 2 : 3, STAGED ? 2 : 3))) void k_join
     // block b of a list = its rows 32b..32b+31; lane (col, half) holds bytes
     // [32 step + 16 half, +16) of row `col` of the block for every step
     N0 = load_block<KSTEPS>(shadow, dpad, __shfl(idn, col, kWave), half);
-    N1 = load_block<KSTEPS>(shadow, dpad, __shfl(idn, 32 + col, kWave), half);
+    if (kHasN1) N1 = load_block<KSTEPS>(shadow, dpad, __shfl(idn, 32 + col, kWave), half);
     O0 = load_block<KSTEPS>(shadow, dpad, __shfl(ido, col, kWave), half);
-    O1 = load_block<KSTEPS>(shadow, dpad, __shfl(ido, 32 + col, kWave), half);
+    if (kHasO1) O1 = load_block<KSTEPS>(shadow, dpad, __shfl(ido, 32 + col, kWave), half);
     if (LEAN) {
       m_new = m_old = m_none;
     } else {  // one 8-byte gather per sampled object: list threshold and norm
@@ -447,10 +475,11 @@ __attribute__((amdgpu_waves_per_eu(STAGED ? 2 : 3, STAGED ? 2 : 3))) void k_join
     const bool active = nn > 0 && (do_nn || no > 0);
     uint2 cm_new = m_new, cm_old = m_old;  // this node's thresholds and norms
     if (LEAN && active) {  // (all lanes take part in the exchange between the halves)
-      const uint32_t norm_new = (uint32_t)sample_norm<KSTEPS>(N0, N1, half, lane);
+      // (a block the shape does not have stands for samples that are absent)
+      const uint32_t norm_new = (uint32_t)sample_norm<KSTEPS>(N0, kHasN1 ? N1 : N0, half, lane);
       if (id_new >= 0) cm_new.y = norm_new;
       if (no > 0) {  // uniform
-        const uint32_t norm_old = (uint32_t)sample_norm<KSTEPS>(O0, O1, half, lane);
+        const uint32_t norm_old = (uint32_t)sample_norm<KSTEPS>(O0, kHasO1 ? O1 : O0, half, lane);
         if (id_old >= 0) cm_old.y = norm_old;
       }
     }
@@ -523,7 +552,7 @@ __attribute__((amdgpu_waves_per_eu(STAGED ? 2 : 3, STAGED ? 2 : 3))) void k_join
           v16i g = gram<KSTEPS>(N0, N0);
           a0 = max(a0, tile_col_best<true>(g, normN, half, 1u << col));
         }
-        if (nn > 32) {
+        if (kHasN1 && nn > 32) {
           {
             v16i g = gram<KSTEPS>(N1, N0);
             a0 = max(a0, tile_col_best<false>(g, normN + 32, half, 0u));
@@ -546,20 +575,20 @@ __attribute__((amdgpu_waves_per_eu(STAGED ? 2 : 3, STAGED ? 2 : 3))) void k_join
                                                       excl_rows(eq_old_c0, 0, cls_old0, rid_n0))
                                  : tile_col_best<false>(g, normO, half, 0u));
         }
-        if (no > 32) {
+        if (kHasO1 && no > 32) {
           v16i g = gram<KSTEPS>(O1, N0);
           b0 = max(b0, masked_no ? tile_col_best<true>(g, normO + 32, half,
                                                       excl_rows(eq_old_c0, 1, cls_old1, rid_n0))
                                  : tile_col_best<false>(g, normO + 32, half, 0u));
         }
-        if (nn > 32) {
+        if (kHasN1 && nn > 32) {
           {
             v16i g = gram<KSTEPS>(O0, N1);
             b1 = max(b1, masked_no ? tile_col_best<true>(g, normO, half,
                                                         excl_rows(eq_old_c1, 0, cls_old0, rid_n1))
                                    : tile_col_best<false>(g, normO, half, 0u));
           }
-          if (no > 32) {
+          if (kHasO1 && no > 32) {
             v16i g = gram<KSTEPS>(O1, N1);
             b1 = max(b1, masked_no ? tile_col_best<true>(g, normO + 32, half,
                                                         excl_rows(eq_old_c1, 1, cls_old1, rid_n1))
@@ -573,20 +602,20 @@ __attribute__((amdgpu_waves_per_eu(STAGED ? 2 : 3, STAGED ? 2 : 3))) void k_join
                                                       excl_rows(eq_new_c0, 0, cls_new0, rid_o0))
                                  : tile_col_best<false>(g, normN, half, 0u));
         }
-        if (nn > 32) {
+        if (kHasN1 && nn > 32) {
           v16i g = gram<KSTEPS>(N1, O0);
           c0 = max(c0, masked_no ? tile_col_best<true>(g, normN + 32, half,
                                                       excl_rows(eq_new_c0, 1, cls_new1, rid_o0))
                                  : tile_col_best<false>(g, normN + 32, half, 0u));
         }
-        if (no > 32) {
+        if (kHasO1 && no > 32) {
           {
             v16i g = gram<KSTEPS>(N0, O1);
             c1 = max(c1, masked_no ? tile_col_best<true>(g, normN, half,
                                                         excl_rows(eq_new_c1, 0, cls_new0, rid_o1))
                                    : tile_col_best<false>(g, normN, half, 0u));
           }
-          if (nn > 32) {
+          if (kHasN1 && nn > 32) {
             v16i g = gram<KSTEPS>(N1, O1);
             c1 = max(c1, masked_no ? tile_col_best<true>(g, normN + 32, half,
                                                         excl_rows(eq_new_c1, 1, cls_new1, rid_o1))
@@ -670,15 +699,16 @@ __attribute__((amdgpu_waves_per_eu(STAGED ? 2 : 3, STAGED ? 2 : 3))) void k_join
     }
     // direct: with the operand registers free, the next node's rows are requested while
     // the slot words are still on their way ...
-    const int64_t s_next = s + W;
-    const bool more = s_next < n;
+    const bool more = s1 >= 0;
     int32_t nn_new = -1, nn_old = -1;
+    int64_t s3 = -1;
     if (more) {
       request_rows(nx_new, nx_old);
-      if (s_next + W < n && in_list) {
-        nn_new = snew[(s_next + W) * L + lane];
-        nn_old = sold[(s_next + W) * L + lane];
+      if (s2 >= 0 && in_list) {
+        nn_new = snew[s2 * L + lane];
+        nn_old = sold[s2 * L + lane];
       }
+      s3 = node_at(pos + 3 * W);
     }
     // ... and only now the slots are used
     if (!STAGED) {
@@ -710,8 +740,9 @@ __attribute__((amdgpu_waves_per_eu(STAGED ? 2 : 3, STAGED ? 2 : 3))) void k_join
         ev = (do_nn ? (uint64_t)nn * (nn - 1) / 2 : 0) + (uint64_t)nn * no - dups;
       }
       uint64_t* cs = counters + (s & (kStripes - 1)) * C_SLOTS;
-      // (LEAN: k_result_csr counts what passes the thresholds)
-      if (!LEAN && passed_total)
+      // (k_result_csr<true>, behind a launch with a LEAN build, counts what passes the
+      // thresholds)
+      if (!LEAN && sa.count_passed && passed_total)
         atomicAdd(reinterpret_cast<unsigned long long*>(cs + C_PASSED),
                   (unsigned long long)passed_total);
       if (found_total) atomicAdd(reinterpret_cast<unsigned long long*>(cs + C_PROPS),
@@ -726,7 +757,8 @@ __attribute__((amdgpu_waves_per_eu(STAGED ? 2 : 3, STAGED ? 2 : 3))) void k_join
       if ((uint32_t)__builtin_amdgcn_readfirstlane((int)fill) >= sa.threshold) (void)flush();
     }
     if (!more) break;
-    s = s_next;
+    pos += W;
+    s = s1; s1 = s2; s2 = s3;
     id_new = nx_new; id_old = nx_old;
     nx_new = nn_new; nx_old = nn_old;
   }
@@ -889,17 +921,59 @@ __global__ __launch_bounds__(kRcBlock) void k_result_csr(int64_t n, int tb,
   }
 }
 
-template <int KSTEPS, bool STAGED, bool LEAN = false>
+// The nodes that have something to evaluate, listed by shape (list c at nodes + c n, its
+// length in count[c]; the order inside a list is of no consequence).  A workgroup takes
+// kShapeNodes consecutive nodes, numbers those of each list in LDS and reserves their places
+// with one addition per list.
+constexpr int kShapePerThread = 16;
+constexpr int kShapeNodes = 256 * kShapePerThread;
+__global__ __launch_bounds__(256) void k_join_shapes(int64_t n, int merge_mode,
+                                                     const int32_t* __restrict__ cnew,
+                                                     const int32_t* __restrict__ cold,
+                                                     int32_t* nodes, uint32_t* count) {
+  __shared__ uint32_t here[kJoinShapes], base[kJoinShapes];
+  const int64_t first = block_linear() * kShapeNodes;
+  if (threadIdx.x < kJoinShapes) here[threadIdx.x] = 0u;
+  __syncthreads();
+  int32_t place[kShapePerThread];  // list + kJoinShapes x (number within the workgroup)
+#pragma unroll
+  for (int j = 0; j < kShapePerThread; ++j) {
+    const int64_t s = first + j * 256 + threadIdx.x;
+    place[j] = -1;
+    if (s < n) {
+      const int nn = cnew[s], no = cold[s];
+      const bool do_nn = !merge_mode && nn > 1;
+      if (nn > 0 && (do_nn || no > 0)) {
+        const int c = join_list_of_shape(no <= 32 ? 1 : nn <= 32 ? 2 : 0);
+        place[j] = c + kJoinShapes * (int32_t)atomicAdd(&here[c], 1u);
+      }
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x < kJoinShapes && here[threadIdx.x] != 0u)
+    base[threadIdx.x] = atomicAdd(&count[threadIdx.x], here[threadIdx.x]);
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < kShapePerThread; ++j) {
+    if (place[j] >= 0) {
+      const int c = place[j] % kJoinShapes;
+      nodes[(int64_t)c * n + base[c] + place[j] / kJoinShapes] =
+          (int32_t)(first + j * 256 + threadIdx.x);
+    }
+  }
+}
+
+template <int KSTEPS, bool STAGED, bool LEAN = false, int SHAPE = 0>
 static hipError_t launch_k(bool fcode, bool merge, unsigned grid, hipStream_t st,
                            const int8_t* shadow, const NodeMeta* meta, int dpad, const Shape& sh,
                            const DevState& ds, const StageArgs& sa) {
-  constexpr int block = STAGED ? kMBStaged : kMB;
+  constexpr int block = join_waves(STAGED, SHAPE) * kWave;
   const size_t lds = STAGED ? kStageLdsBytes : 0;
 #define GNND_ARGS shadow, meta, dpad, sh.n, sh.p, sh.split, ds.snew, ds.sold, \
                   ds.pslot, (uint64_t)sh.slots(), ds.bins, ds.counters, sa
 #define GNND_LAUNCH(F, M)                                                                      \
   do {                                                                                         \
-    auto* kern = k_join_mfma<KSTEPS, F, M, STAGED, LEAN>;                                      \
+    auto* kern = k_join_mfma<KSTEPS, F, M, STAGED, LEAN, SHAPE>;                               \
     if (STAGED) {                                                                              \
       static bool attr_set = false; /* per instantiation: a staging area beyond the default */ \
       if (!attr_set) {                                                                         \
@@ -948,28 +1022,51 @@ hipError_t launch_join_mfma(const Shape& sh, const DevState& ds, bool merge_mode
   const bool staged = ds.stg_ent != nullptr;
   // the first iteration on a random graph: see LEAN
   const bool lean = staged && first_look && !merge_mode;
-  StageArgs sa{ds.stg_ent, ds.stg_cur, ds.poff, 0, 0, 0};
-  unsigned grid;
-  if (staged) {
-    sa.tb = stage_bucket_bits(sh.n);
-    sa.nb = (int)((sh.n + ((int64_t)1 << sa.tb) - 1) >> sa.tb);
-    // flush at half-full on average: few results find their bucket's places taken
-    sa.threshold = (uint32_t)(sa.nb * (kStageSlots / 2));
-    hipError_t e = launch_zero_u32(reinterpret_cast<uint32_t*>(ds.stg_cur), 2 * kStageBuckets, st);
-    if (e != hipSuccess) return e;
-    // persistent workgroups, one per CU (the staging area takes most of a CU's LDS)
-    const int64_t want = (sh.n + kStagedWaves - 1) / kStagedWaves;
-    grid = (unsigned)(want < compute_units() ? want : compute_units());
-  } else {
+  StageArgs sa{ds.stg_ent, ds.stg_cur, ds.poff, 0, 0, 0, ds.cls_nodes, ds.cls_count, !lean};
+  hipError_t e;
+  if (!staged) {
     // persistent wavefronts: about two resident sets of workgroups, each wave strides over nodes
     const int64_t want = (sh.n + 3) / 4;
-    grid = (unsigned)(want < kJoinGrid ? want : kJoinGrid);
+    const unsigned grid = (unsigned)(want < kJoinGrid ? want : kJoinGrid);
+#define GNND_K(K) \
+  e = launch_k<K, false>(fcode, merge_mode, grid, st, ds.shadow, ds.meta, dpad, sh, ds, sa)
+    switch (ksteps) {
+      case 1: GNND_K(1); break;
+      case 2: GNND_K(2); break;
+      case 3: GNND_K(3); break;
+      default: GNND_K(4);
+    }
+#undef GNND_K
+    if (after_join) (void)hipEventRecord(after_join, st);
+    return e;
   }
-  hipError_t e;
-#define GNND_K(K)                                                                               \
-  e = lean     ? launch_k<K, true, true>(fcode, false, grid, st, ds.shadow, ds.meta, dpad, sh, ds, sa) \
-      : staged ? launch_k<K, true>(fcode, merge_mode, grid, st, ds.shadow, ds.meta, dpad, sh, ds, sa) \
-               : launch_k<K, false>(fcode, merge_mode, grid, st, ds.shadow, ds.meta, dpad, sh, ds, sa)
+  sa.tb = stage_bucket_bits(sh.n);
+  sa.nb = (int)((sh.n + ((int64_t)1 << sa.tb) - 1) >> sa.tb);
+  // flush at half-full on average: few results find their bucket's places taken
+  sa.threshold = (uint32_t)(sa.nb * (kStageSlots / 2));
+  e = launch_zero_u32(reinterpret_cast<uint32_t*>(ds.stg_cur), 2 * kStageBuckets, st);
+  if (e == hipSuccess) e = launch_zero_u32(ds.cls_count, kJoinShapes, st);
+  if (e != hipSuccess) return e;
+  k_join_shapes<<<grid_blocks((sh.n + kShapeNodes - 1) / kShapeNodes), 256, 0, st>>>(
+      sh.n, merge_mode ? 1 : 0, ds.cnew, ds.cold, ds.cls_nodes, ds.cls_count);
+  // persistent workgroups, one per CU (the staging area takes most of a CU's LDS); one launch
+  // per shape, the common shapes first; all of them add to the same bucket regions
+  auto grid_for = [&](int waves) {
+    const int64_t want = (sh.n + waves - 1) / waves;
+    return (unsigned)(want < compute_units() ? want : compute_units());
+  };
+  const unsigned grid_slim = grid_for(kStagedWavesSlim), grid_full = grid_for(kStagedWaves);
+#define GNND_K(K)                                                                                  \
+  e = lean ? launch_k<K, true, true, 1>(fcode, false, grid_slim, st, ds.shadow, ds.meta, dpad, sh, \
+                                        ds, sa)                                                    \
+           : launch_k<K, true, false, 1>(fcode, merge_mode, grid_slim, st, ds.shadow, ds.meta,     \
+                                         dpad, sh, ds, sa);                                        \
+  if (e == hipSuccess)                                                                             \
+    e = launch_k<K, true, false, 2>(fcode, merge_mode, grid_slim, st, ds.shadow, ds.meta, dpad,    \
+                                    sh, ds, sa);                                                   \
+  if (e == hipSuccess)                                                                             \
+    e = launch_k<K, true, false, 0>(fcode, merge_mode, grid_full, st, ds.shadow, ds.meta, dpad,    \
+                                    sh, ds, sa)
   switch (ksteps) {
     case 1: GNND_K(1); break;
     case 2: GNND_K(2); break;
@@ -978,7 +1075,7 @@ hipError_t launch_join_mfma(const Shape& sh, const DevState& ds, bool merge_mode
   }
 #undef GNND_K
   if (after_join) (void)hipEventRecord(after_join, st);
-  if (e != hipSuccess || !staged) return e;
+  if (e != hipSuccess) return e;
   // (a region is shorter than 2^32 slots: n <= 2^20, 6p <= 192 slots per node)
   const size_t lds = result_csr_lds_bytes(sa.tb, lean);
   auto* csr = lean ? &k_result_csr<true> : &k_result_csr<false>;

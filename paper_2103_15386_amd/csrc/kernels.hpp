@@ -59,12 +59,14 @@ struct DevState {
   // them into the destinations' segments of `bins`
   uint64_t* stg_ent;   // slots: staged results (see stage_record), bucket regions laid out like bins
   unsigned long long* stg_cur;  // kStageBuckets: results that have reached each bucket region
-  // float32 matrix-core join (NULL when it is not in use): the nodes that have work to do,
-  // listed per class of node - kGramClasses lists of n places - and the lists' lengths
-  int32_t* gram_nodes;
-  uint32_t* gram_count;
+  // float32 matrix-core join and staged int8 join (NULL when neither is in use): the nodes
+  // that have work to do, listed per class of node - kNodeClassesMax lists of n places, of
+  // which the float join uses kGramClasses and the int8 join three - and the lists' lengths
+  int32_t* cls_nodes;
+  uint32_t* cls_count;
 };
 constexpr int kGramClasses = 7;
+constexpr int kNodeClassesMax = 7;
 
 // Staged hand-out: destinations are cut into at most kStageBuckets buckets of 2^tb
 // consecutive ids; a workgroup of the join keeps kStageSlots results per bucket in LDS.
