@@ -341,7 +341,7 @@ def main():
     roof["kernel"] = kernel_name
     if gram:  # one launch per class of nodes; the figures are per iteration, all seven together
         roof["launches_per_iteration"] = 7
-    elif kernel_name == "k_join_mfma" and n <= (1 << 20):
+    elif kernel_name == "k_join_mfma" and args.n <= (1 << 20):
         # staged hand-out: one build per shape of node (<= 32 OLD samples, <= 32 NEW samples,
         # the rest); the figures are per iteration, the three launches together
         roof["launches_per_iteration"] = 3
