@@ -12,6 +12,8 @@
 // directions are needed (NEW->OLD and OLD->NEW) instead of reducing across
 // lanes.  Sample lists are sorted by id, so the row position inside a list
 // breaks distance ties exactly like the id does.
+#include <type_traits>
+
 #include "device_utils.hpp"
 #include "kernels.hpp"
 
@@ -395,14 +397,16 @@ __attribute__((amdgpu_waves_per_eu(STAGED && !SHAPE ? 2 : 3, STAGED && !SHAPE ? 
   uint32_t* const st_fill = st_cnt + kStageBuckets;  // [0] results staged, [1] waves out of nodes
   // (the wave index as a vector value: measured 3 % faster here than the scalar form)
   const int wave = threadIdx.x >> 6, lane = lane_id(), half = lane >> 5, col = lane & 31;
-  const int64_t W = (int64_t)gridDim.x * WAVES;
+  // (with lists n <= 2^20: places, node numbers and offsets into the sample lists fit 32 bits)
+  using node_t = typename std::conditional<STAGED, int32_t, int64_t>::type;
+  const node_t W = (node_t)gridDim.x * WAVES;
   // place `pos` of this build's list of nodes (staged) / of all nodes (direct)
-  int64_t pos = (int64_t)blockIdx.x * WAVES + wave;
-  const int64_t places = STAGED ? (int64_t)sa.count[join_list_of_shape(SHAPE)] : n;
+  node_t pos = (node_t)blockIdx.x * WAVES + wave;
+  const node_t places = STAGED ? (node_t)sa.count[join_list_of_shape(SHAPE)] : (node_t)n;
   const int32_t* const list = STAGED ? sa.nodes + (int64_t)join_list_of_shape(SHAPE) * n : nullptr;
-  auto node_at = [&](int64_t at) -> int64_t {  // -1 beyond the end
-    if (at >= places) return -1;
-    return STAGED ? (int64_t)list[at] : at;
+  auto node_at = [&](node_t at) -> node_t {  // -1 beyond the end
+    if (at >= places) return (node_t)-1;
+    return STAGED ? (node_t)list[at] : (node_t)at;
   };
   if (!STAGED && pos >= n) return;
   if (STAGED) {
@@ -437,11 +441,10 @@ __attribute__((amdgpu_waves_per_eu(STAGED && !SHAPE ? 2 : 3, STAGED && !SHAPE ? 
     return out_of_nodes == (uint32_t)WAVES;
   };
   // this node, the next one and the one after: sample ids are requested two nodes ahead
-  int64_t s = node_at(pos), s1 = node_at(pos + W), s2 = node_at(pos + 2 * W);
+  node_t s = node_at(pos), s1 = node_at(pos + W), s2 = node_at(pos + 2 * W);
   const bool have_nodes = s >= 0;
   const int L = 2 * p;
   const bool in_list = lane < L;
-  const uint2 m_none = make_uint2(0, (uint32_t)kFar);
 
   // unused list slots hold -1, so the ids alone say how long a list is
   int32_t id_new = (have_nodes && in_list) ? snew[s * L + lane] : -1;
@@ -460,11 +463,10 @@ __attribute__((amdgpu_waves_per_eu(STAGED && !SHAPE ? 2 : 3, STAGED && !SHAPE ? 
     if (kHasN1) N1 = load_block<KSTEPS>(shadow, dpad, __shfl(idn, 32 + col, kWave), half);
     O0 = load_block<KSTEPS>(shadow, dpad, __shfl(ido, col, kWave), half);
     if (kHasO1) O1 = load_block<KSTEPS>(shadow, dpad, __shfl(ido, 32 + col, kWave), half);
-    if (LEAN) {
-      m_new = m_old = m_none;
-    } else {  // one 8-byte gather per sampled object: list threshold and norm
-      m_new = idn >= 0 ? *reinterpret_cast<const uint2*>(meta + idn) : m_none;
-      m_old = ido >= 0 ? *reinterpret_cast<const uint2*>(meta + ido) : m_none;
+    m_new = m_old = make_uint2(0u, (uint32_t)kFar);  // an absent sample: far from everything
+    if (!LEAN) {  // one 8-byte gather per sampled object: list threshold and norm
+      if (idn >= 0) m_new = *reinterpret_cast<const uint2*>(meta + idn);
+      if (ido >= 0) m_old = *reinterpret_cast<const uint2*>(meta + ido);
     }
   };
   request_rows(id_new, id_old);
@@ -701,7 +703,7 @@ __attribute__((amdgpu_waves_per_eu(STAGED && !SHAPE ? 2 : 3, STAGED && !SHAPE ? 
     // the slot words are still on their way ...
     const bool more = s1 >= 0;
     int32_t nn_new = -1, nn_old = -1;
-    int64_t s3 = -1;
+    node_t s3 = -1;
     if (more) {
       request_rows(nx_new, nx_old);
       if (s2 >= 0 && in_list) {
