@@ -33,8 +33,8 @@ PEAK_INT8_TOPS = 5000.0
 # mean of the first T entries; T beyond the table also gives null.
 JOIN_TRAFFIC = {
     ("sift1m", 1_000_000, 128, 32, 32, "k_join_mfma", "selective"): {
-        "fetch_raw_mib": [3923.7, 4716.0, 5343.9, 5160.1, 5181.3, 4863.4, 4311.3],
-        "write_raw_mib": [574.7, 481.6, 745.2, 595.8, 449.6, 254.9, 144.8],
+        "fetch_raw_mib": [3930.8, 4592.3, 5184.2, 5013.2, 5055.2, 4731.6, 4191.9],
+        "write_raw_mib": [577.5, 478.0, 740.7, 591.7, 446.0, 250.8, 140.9],
         "fetch_scale": 2.0, "write_scale": 1.0},
 }
 
