@@ -353,20 +353,21 @@ __device__ inline int32_t sample_norm(const Operand& b0, const Operand& b1, int 
   return mine + (int32_t)xor_lanes((uint32_t)give, 32, lane);
 }
 
-// LEAN (staged hand-out only): the form for a launch in which the thresholds of the lists
+// LEAN: the form for a launch in which the thresholds of the lists
 // decide little and the nodes have few OLD samples - the first iteration on a random graph,
 // where every result passes and a node's time is the time the memory system needs for its
 // scattered lines.  The 8-byte (threshold, norm) records, one more scattered line per sampled
 // object, are not read: the norms come from the operand registers and every result found is
-// handed on; k_result_csr<true> then applies the thresholds, so the same results reach the
-// lists.  Right for any input; faster only where the saved reads outweigh the extra
-// arithmetic and the larger flow of results.
+// handed on; k_result_csr<true> then applies the thresholds (staged hand-out; with the direct
+// hand-out the list update drops what cannot enter), so the same results reach the lists.
+// Right for any input; faster only where the saved reads outweigh the extra arithmetic and
+// the larger flow of results.
 // SHAPE (staged hand-out only): which of the four operand blocks of 32 rows a node fills.
 // 0: any (NEW 0..31, NEW 32..63, OLD 0..31, OLD 32..63); 1: at most 32 OLD samples; 2: at
 // most 32 NEW samples.  Most nodes are of shape 1 (early iterations: many NEW, few OLD) or 2
 // (late ones); without the fourth block's 16 registers the kernel fits 3 wavefronts per SIMD,
-// which hide the per-node chain wait -> evaluate -> hand on much better than 2 do (12 to 16 %
-// less time per launch).  k_join_shapes lists the nodes of each shape (those with nothing to
+// which hide the per-node chain wait -> evaluate -> hand on better than 2 do (6 to 12 % less
+// time per iteration).  k_join_shapes lists the nodes of each shape (those with nothing to
 // evaluate are in no list) and every build runs over its own list.
 constexpr int kJoinShapes = 3;
 __host__ __device__ constexpr int join_list_of_shape(int shape) { return shape == 0 ? 2 : shape - 1; }
@@ -744,7 +745,8 @@ __attribute__((amdgpu_waves_per_eu(STAGED && !SHAPE ? 2 : 3, STAGED && !SHAPE ? 
       uint64_t* cs = counters + (s & (kStripes - 1)) * C_SLOTS;
       // (k_result_csr<true>, behind a launch with a LEAN build, counts what passes the
       // thresholds)
-      if (!LEAN && sa.count_passed && passed_total)
+      // (direct hand-out with a LEAN build: every result found has been handed on)
+      if ((LEAN ? !STAGED : sa.count_passed) && passed_total)
         atomicAdd(reinterpret_cast<unsigned long long*>(cs + C_PASSED),
                   (unsigned long long)passed_total);
       if (found_total) atomicAdd(reinterpret_cast<unsigned long long*>(cs + C_PROPS),
@@ -1023,15 +1025,16 @@ hipError_t launch_join_mfma(const Shape& sh, const DevState& ds, bool merge_mode
   const bool fcode = sh.metric != kL2U8;
   const bool staged = ds.stg_ent != nullptr;
   // the first iteration on a random graph: see LEAN
-  const bool lean = staged && first_look && !merge_mode;
-  StageArgs sa{ds.stg_ent, ds.stg_cur, ds.poff, 0, 0, 0, ds.cls_nodes, ds.cls_count, !lean};
+  const bool lean = first_look && !merge_mode;
+  StageArgs sa{ds.stg_ent, ds.stg_cur, ds.poff, 0, 0, 0, ds.cls_nodes, ds.cls_count, !(lean && staged)};
   hipError_t e;
   if (!staged) {
     // persistent wavefronts: about two resident sets of workgroups, each wave strides over nodes
     const int64_t want = (sh.n + 3) / 4;
     const unsigned grid = (unsigned)(want < kJoinGrid ? want : kJoinGrid);
-#define GNND_K(K) \
-  e = launch_k<K, false>(fcode, merge_mode, grid, st, ds.shadow, ds.meta, dpad, sh, ds, sa)
+#define GNND_K(K)                                                                               \
+  e = lean ? launch_k<K, false, true>(fcode, false, grid, st, ds.shadow, ds.meta, dpad, sh, ds, sa) \
+           : launch_k<K, false>(fcode, merge_mode, grid, st, ds.shadow, ds.meta, dpad, sh, ds, sa)
     switch (ksteps) {
       case 1: GNND_K(1); break;
       case 2: GNND_K(2); break;
